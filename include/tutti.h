@@ -1,0 +1,174 @@
+/*
+ * tutti.h -- C ABI of libtutti: the per-layer KV-object hot path on one MI355X (gfx950).
+ *
+ * The library moves one layer's KV cache between the paged blocks an inference engine keeps
+ * scattered in HBM and contiguous, aligned per-layer KV objects (pack on save, unpack on
+ * restore), and builds the submission entries that describe those objects' I/O, all on the
+ * GPU, so the host does a constant amount of work per layer whatever the number of blocks
+ * (the paper's O(layer) instead of O(layer x blocks): sec. 1 and sec. 3.1).
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; tutti_pool / tutti_objcfg
+ *     pointers are HOST pointers read during the call.  `stream` is a hipStream_t passed as
+ *     void* (NULL = the null stream).
+ *   - The library allocates no device memory and keeps no per-call state (the pool is fixed
+ *     for the engine's lifetime and nothing on the I/O path may allocate: sec. 3.1 "P2P
+ *     Memory Mapping Table", sec. 3.2 "Zero-Copy Ring Buffers").
+ *   - A call validates its host arguments in O(1), enqueues a constant number of kernels on
+ *     `stream` and returns; it never synchronises and never copies to the host.  Results are
+ *     valid once the caller has synchronised the stream.
+ *   - Return value: 0 (TUTTI_OK) or a negative TUTTI_E* code; on error nothing was enqueued.
+ *   - What only the device can know is reported through the optional status word d_status
+ *     (TUTTI_ST_* bits, ORed in atomically, never cleared by the library) and never causes an
+ *     out-of-bounds access: offending blocks / requests / entries are skipped.
+ *   - Overlapping calls that write the same blocks or the same staging bytes race.
+ */
+#ifndef TUTTI_H
+#define TUTTI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TUTTI_OK 0
+#define TUTTI_EINVAL (-1) /* null pointer, zero dimension, bad alignment / layout / opcode / layer */
+#define TUTTI_ERANGE (-2) /* n_req > TUTTI_MAX_REQ, cu_budget > number of CUs */
+#define TUTTI_EHIP (-3)   /* a HIP call failed; see tutti_last_hip_error() */
+
+#define TUTTI_LAYOUT_NHD 0u /* block stored [T][h][d]: the paper's [Block, h, d] (sec. 2.1) */
+#define TUTTI_LAYOUT_HND 1u /* block stored [h][T][d]: head-major engines; objects stay token-major */
+
+#define TUTTI_OP_READ 1u  /* object -> HBM (restore / retrieve_layer) */
+#define TUTTI_OP_WRITE 2u /* HBM -> object (save / store_layer) */
+
+#define TUTTI_IOCB_SLOTS 2048u /* I/O contexts per IOCB (sec. 3.2 "Zero-Copy Ring Buffers") */
+#define TUTTI_MAX_REQ 2048u    /* requests per call */
+
+#define TUTTI_ST_BAD_BLOCK 1u /* a block-table entry >= num_blocks, or beyond table_len: block skipped */
+#define TUTTI_ST_STAGE_CAP 2u /* a request's objects end beyond stage_cap: request skipped */
+#define TUTTI_ST_SQE_CAP 4u   /* more entries than sqe_cap: the excess was not written */
+
+/* One layer's paged pool (sec. 2.1 "Paged KV Memory Management"): a K plane and a V plane, each
+ * num_blocks blocks of T*h*d*e bytes, block b at base + b*block_stride.  Planes stay owned by the
+ * caller.  Requirements: bases and block_stride multiples of 16; T*h*d*e a multiple of 16. */
+typedef struct tutti_pool {
+  void *k_base;
+  void *v_base;
+  uint64_t block_stride;
+  uint32_t num_blocks;
+  uint32_t block_tokens; /* T */
+  uint32_t num_kv_heads; /* h */
+  uint32_t head_dim;     /* d */
+  uint32_t elt_bytes;    /* e */
+  uint32_t pool_layout;  /* TUTTI_LAYOUT_* */
+} tutti_pool;
+
+/* Object geometry: `align` is the alignment unit of every object and offset (power of two >= 16,
+ * 4096 in every workload here), `chunk_bytes` the largest span one submission entry covers
+ * (multiple of align), `num_layers` the L of the 2*L objects in a GPU file (sec. 3.1). */
+typedef struct tutti_objcfg {
+  uint32_t align;
+  uint32_t chunk_bytes;
+  uint32_t num_layers;
+} tutti_objcfg;
+
+/* Extent of one request's objects; the same for every layer.  32 bytes. */
+typedef struct tutti_extent {
+  uint64_t stage_off; /* offset of the K object in the layer's staging buffer; multiple of align */
+  uint64_t obj_bytes; /* align_up(n_blocks * block_bytes, align); the V object follows the K object */
+  uint32_t n_blocks;
+  uint32_t n_chunks;  /* ceil(obj_bytes / chunk_bytes), per object */
+  uint32_t sqe_base;  /* index of the request's first submission entry of a layer */
+  uint32_t table_off; /* index of the request's first entry in the flattened block table */
+} tutti_extent;
+
+/* Submission entry: 64 bytes, little-endian.  It carries what the paper's I/O context records
+ * (SGL address, GPU-file offset, length: sec. 3.2), the 16-byte SGL triple address / length /
+ * identifier (sec. 3.1 "P2P Memory Mapping Table") and the entry's place in the 2048-slot IOCBs. */
+typedef struct tutti_sqe {
+  uint8_t opcode;      /* TUTTI_OP_* */
+  uint8_t kind;        /* 0 = K object, 1 = V object */
+  uint16_t layer;
+  uint32_t file_id;    /* GPU file of the request (caller-supplied) */
+  uint64_t file_off;   /* (2*layer + kind) * obj_bytes + chunk * chunk_bytes */
+  uint64_t addr;       /* stage_addr + stage_off + kind * obj_bytes + chunk * chunk_bytes */
+  uint32_t len;        /* min(chunk_bytes, rest of the object); multiple of align */
+  uint32_t sgl_id;     /* caller-supplied registration identifier */
+  uint64_t user_data;  /* (request << 32) | entry index within the layer */
+  uint32_t iocb_idx;   /* entry index / 2048 */
+  uint32_t ioctx_slot; /* entry index % 2048 */
+  uint8_t rsvd[16];    /* zero */
+} tutti_sqe;
+
+/* ---- a1: extents.  Sec. 3.1 ("one key object and one value object for each layer"), sec. 3.2
+ * (offset and length of an I/O context).  For request r with n_r = d_n_blocks[r] hit blocks:
+ * obj_bytes = align_up(n_r*block_bytes, align), n_chunks = ceil(obj_bytes/chunk_bytes); stage_off,
+ * sqe_base and table_off are the exclusive prefix sums over r of 2*obj_bytes, 2*n_chunks and n_r.
+ * Writes d_extents[0..n_req) and d_totals[0] = staging bytes of a layer, d_totals[1] = entries of a
+ * layer.  n_req may be 0.  sqe_base / table_off are meaningful only while the totals fit 32 bits. */
+int tutti_obj_layout(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                     tutti_extent *d_extents, uint64_t *d_totals, void *stream);
+
+/* ---- a2: pack (save; store_layer of sec. 3.4).  For every request r, kind in {K, V} and j < n_r,
+ * object bytes [j*block_bytes, (j+1)*block_bytes) <- pool block d_block_table[table_off_r + j], in
+ * token-major order ((t*h + i)*d + k)*e whatever the pool layout; the tail up to obj_bytes <- 0.
+ * The K object of r starts at d_stage + stage_off_r, its V object obj_bytes later.
+ * table_len = number of entries in d_block_table (entries beyond it are never read).
+ * d_stage: 16-byte aligned, stage_cap bytes.  cu_budget: 0 = whole GPU, else the launch is limited
+ * to about that many compute units' worth of workgroups (see tutti_layer_restore). */
+int tutti_obj_pack(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                   const uint32_t *d_block_table, uint32_t table_len, void *d_stage, uint64_t stage_cap,
+                   uint32_t cu_budget, uint32_t *d_status, void *stream);
+
+/* ---- a3: unpack (restore).  The inverse copy: pool block <- object bytes.  Padding is not read;
+ * pool blocks not named in the table are not touched.  A block id must not appear twice in one
+ * call (two writers of one block race). */
+int tutti_obj_unpack(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                     const uint32_t *d_block_table, uint32_t table_len, const void *d_stage, uint64_t stage_cap,
+                     uint32_t cu_budget, uint32_t *d_status, void *stream);
+
+/* ---- a4: submission entries (sec. 3.2: commands are generated on the GPU, one I/O context per
+ * transfer, 2048 per IOCB).  One entry per chunk of every K and V object of `layer`, in the order
+ * request ascending, K then V, chunk ascending; entry index = sqe_base_r + kind*n_chunks_r + chunk.
+ * stage_addr is the address the entries should name for byte 0 of the staging buffer (multiple of
+ * align); it is only arithmetic, never dereferenced.  Entries with index >= sqe_cap are dropped. */
+int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                    const uint32_t *d_file_id, uint32_t layer, uint32_t opcode, uint64_t stage_addr, uint32_t sgl_id,
+                    tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t *d_status, void *stream);
+
+/* ---- a5 + a6: one layer's restore in ONE launch (retrieve_layer of sec. 3.4; "the CPU only loads
+ * I/O kernels once per layer", sec. 1): extents from d_n_blocks, READ entries for `layer`, then the
+ * unpack of every hit block, as tutti_obj_layout + tutti_sqe_build(READ) + tutti_obj_unpack would.
+ * Also writes d_extents[0..n_req) and d_totals[0..2).  d_stage must be device-accessible.
+ * cu_budget stands in for the SM count of the paper's issue_io(IOCB_ids, SMs) (sec. 3.2): 0 = whole
+ * GPU; B > 0 limits the grid to B compute units' worth of persistent workgroups so a concurrent
+ * compute kernel keeps the rest; B > CU count is TUTTI_ERANGE. */
+int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                        const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                        uint32_t layer, const void *d_stage, uint64_t stage_cap, uint64_t stage_addr,
+                        uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe,
+                        uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status, void *stream);
+
+/* ---- measurement aid: a plain contiguous device-to-device copy of `bytes` (multiple of 16, both
+ * pointers 16-byte aligned) with the same load/store width and launch shape as unpack: the
+ * achievable ceiling the pack/unpack rates are compared with. */
+int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream);
+
+/* ---- housekeeping */
+const char *tutti_strerror(int code);
+int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */
+int tutti_cu_count(void);           /* compute units of the current device, or a negative TUTTI_E* */
+uint32_t tutti_version(void);       /* 0x00MMmmpp */
+/* sizeof / offsetof table of the records above (33 values: extent size + 6 offsets, sqe size + 11,
+ * pool size + 9, objcfg size + 3); returns the count or TUTTI_EINVAL if cap is too small. */
+int tutti_abi_describe(uint32_t *out, uint32_t cap);
+/* Launch tuning, for experiments: wgs_per_cu persistent workgroups per budgeted CU (0 = default),
+ * unroll = 16-byte accesses in flight per lane (0 = default; 1, 2, 4 or 8). */
+int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TUTTI_H */

@@ -1,0 +1,364 @@
+/*
+ * tutti_oracle.c -- CPU oracle for the per-layer KV object path. TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain C, one thread, one loop per index of the definition (the d contiguous elements of a
+ * (token, head) row move as one memcpy); no blocking, no tiling, no vector code.
+ * See tutti_oracle.h for what the paper fixes and what is a repository reading.
+ * The only callers allowed are the tests, the smoke check and the benchmark's cpu_baseline leg.
+ */
+#include "tutti_oracle.h"
+
+#include <pthread.h>
+#include <stddef.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ helpers */
+
+static int is_pow2(uint32_t x) { return x != 0 && (x & (x - 1)) == 0; }
+
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+/* Bytes of one block of one plane: T*h*d*e for a [Block, h, d] block (sec. 2.1). */
+uint32_t orc_block_bytes(const orc_pool *pool) {
+  if (!pool) return 0;
+  uint64_t b = (uint64_t)pool->block_tokens;
+  b *= pool->num_kv_heads;
+  if (b > 0xffffffffull) return 0;
+  b *= pool->head_dim;
+  if (b > 0xffffffffull) return 0;
+  b *= pool->elt_bytes;
+  if (b > 0xffffffffull) return 0;
+  return (uint32_t)b;
+}
+
+static int check_geometry(const orc_pool *pool, const orc_objcfg *cfg) {
+  if (!pool || !cfg) return ORC_EINVAL;
+  uint32_t bb = orc_block_bytes(pool);
+  if (bb == 0 || bb % 16 != 0) return ORC_EINVAL;
+  if (pool->num_blocks == 0) return ORC_EINVAL;
+  if (pool->block_stride < bb || pool->block_stride % 16 != 0) return ORC_EINVAL;
+  if (pool->pool_layout != ORC_LAYOUT_NHD && pool->pool_layout != ORC_LAYOUT_HND) return ORC_EINVAL;
+  if (!is_pow2(cfg->align) || cfg->align < 16) return ORC_EINVAL;
+  if (cfg->chunk_bytes == 0 || cfg->chunk_bytes % cfg->align != 0) return ORC_EINVAL;
+  if (cfg->num_layers == 0 || cfg->num_layers > 65536u) return ORC_EINVAL;
+  return ORC_OK;
+}
+
+int orc_abi_describe(uint32_t *out, uint32_t cap) {
+  if (!out || cap < 33) return ORC_EINVAL;
+  uint32_t i = 0;
+  out[i++] = sizeof(orc_extent);
+  out[i++] = offsetof(orc_extent, stage_off);
+  out[i++] = offsetof(orc_extent, obj_bytes);
+  out[i++] = offsetof(orc_extent, n_blocks);
+  out[i++] = offsetof(orc_extent, n_chunks);
+  out[i++] = offsetof(orc_extent, sqe_base);
+  out[i++] = offsetof(orc_extent, table_off);
+  out[i++] = sizeof(orc_sqe);
+  out[i++] = offsetof(orc_sqe, opcode);
+  out[i++] = offsetof(orc_sqe, kind);
+  out[i++] = offsetof(orc_sqe, layer);
+  out[i++] = offsetof(orc_sqe, file_id);
+  out[i++] = offsetof(orc_sqe, file_off);
+  out[i++] = offsetof(orc_sqe, addr);
+  out[i++] = offsetof(orc_sqe, len);
+  out[i++] = offsetof(orc_sqe, sgl_id);
+  out[i++] = offsetof(orc_sqe, user_data);
+  out[i++] = offsetof(orc_sqe, iocb_idx);
+  out[i++] = offsetof(orc_sqe, ioctx_slot);
+  out[i++] = sizeof(orc_pool);
+  out[i++] = offsetof(orc_pool, k_base);
+  out[i++] = offsetof(orc_pool, v_base);
+  out[i++] = offsetof(orc_pool, block_stride);
+  out[i++] = offsetof(orc_pool, num_blocks);
+  out[i++] = offsetof(orc_pool, block_tokens);
+  out[i++] = offsetof(orc_pool, num_kv_heads);
+  out[i++] = offsetof(orc_pool, head_dim);
+  out[i++] = offsetof(orc_pool, elt_bytes);
+  out[i++] = offsetof(orc_pool, pool_layout);
+  out[i++] = sizeof(orc_objcfg);
+  out[i++] = offsetof(orc_objcfg, align);
+  out[i++] = offsetof(orc_objcfg, chunk_bytes);
+  out[i++] = offsetof(orc_objcfg, num_layers);
+  return (int)i;
+}
+
+/* Pool of pool_bytes, one descriptor per gran bytes (sec. 3.1, "P2P Memory Mapping Table"). */
+uint64_t orc_desc_count(uint64_t pool_bytes, uint64_t gran) {
+  if (gran == 0) return 0;
+  return (pool_bytes + gran - 1) / gran;
+}
+
+/* ------------------------------------------------------------------ extents */
+
+/*
+ * Extents.  One K object and one V object per (request, layer) (sec. 3.1, "Scalable GPU File
+ * Pool"); each holds the request's n hit blocks back to back and is padded to the alignment
+ * unit; an I/O context has an offset and a length (sec. 3.2), so an object is cut into
+ * chunks of at most C bytes.  Offsets are running sums over the requests in order.
+ */
+int orc_obj_layout(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                   orc_extent *extents, uint64_t *totals) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (n_req > 0 && (!n_blocks || !extents)) return ORC_EINVAL;
+  if (!totals) return ORC_EINVAL;
+  const uint64_t bb = orc_block_bytes(pool);
+  const uint64_t A = cfg->align;
+  const uint64_t C = cfg->chunk_bytes;
+
+  uint64_t stage = 0; /* bytes used so far in the staging buffer */
+  uint64_t n_sqe = 0; /* entries so far */
+  uint64_t n_tab = 0; /* block-table entries so far */
+  for (uint32_t r = 0; r < n_req; ++r) {
+    uint64_t obj = align_up((uint64_t)n_blocks[r] * bb, A);
+    uint64_t chunks = (obj + C - 1) / C;
+    extents[r].stage_off = stage;
+    extents[r].obj_bytes = obj;
+    extents[r].n_blocks = n_blocks[r];
+    extents[r].n_chunks = (uint32_t)chunks;
+    extents[r].sqe_base = (uint32_t)n_sqe;
+    extents[r].table_off = (uint32_t)n_tab;
+    stage += 2 * obj;    /* K object, then V object */
+    n_sqe += 2 * chunks; /* K chunks, then V chunks */
+    n_tab += n_blocks[r];
+  }
+  totals[0] = stage;
+  totals[1] = n_sqe;
+  return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ pack / unpack */
+
+/*
+ * Copy one block between its place in the pool and its place in the object.
+ * The object is token-major: token t, head i, dim k of the block at ((t*h + i)*d + k)*e.
+ * An NHD block [T][h][d] (the paper's [Block, h, d], sec. 2.1) is already in that order.
+ * An HND block [h][T][d] holds the same element at ((i*T + t)*d + k)*e.
+ * to_object != 0: pool -> object; else object -> pool.
+ */
+static void move_block(const orc_pool *pool, uint8_t *blk, uint8_t *obj, int to_object) {
+  const uint64_t T = pool->block_tokens, h = pool->num_kv_heads, d = pool->head_dim, e = pool->elt_bytes;
+  for (uint64_t t = 0; t < T; ++t) {
+    for (uint64_t i = 0; i < h; ++i) {
+      /* the d elements of (t, i) are contiguous in both orders: move them as one row */
+      uint64_t in_obj = ((t * h + i) * d) * e;
+      uint64_t in_blk = (pool->pool_layout == ORC_LAYOUT_NHD) ? in_obj : ((i * T + t) * d) * e;
+      if (to_object)
+        memcpy(obj + in_obj, blk + in_blk, d * e);
+      else
+        memcpy(blk + in_blk, obj + in_obj, d * e);
+    }
+  }
+}
+
+/*
+ * Shared body of pack and unpack over the flattened block range [g_lo, g_hi), where block j of
+ * request r has flattened index table_off_r + j.  The single-threaded oracle passes the whole range.
+ */
+static void move_range(const orc_pool *pool, const orc_extent *extents, uint32_t n_req, const uint32_t *block_table,
+                       uint8_t *stage, uint64_t stage_cap, int to_object, uint64_t g_lo, uint64_t g_hi,
+                       uint32_t *status) {
+  const uint64_t bb = orc_block_bytes(pool);
+  uint32_t st = 0;
+  for (uint32_t r = 0; r < n_req; ++r) {
+    const orc_extent *x = &extents[r];
+    if (x->stage_off + 2 * x->obj_bytes > stage_cap) continue; /* does not fit: skip the request */
+    for (uint32_t kind = 0; kind < 2; ++kind) {
+      uint8_t *plane = (uint8_t *)(kind == 0 ? pool->k_base : pool->v_base);
+      uint8_t *obj = stage + x->stage_off + kind * x->obj_bytes; /* V object follows K object */
+      for (uint32_t j = 0; j < x->n_blocks; ++j) {
+        uint64_t g = (uint64_t)x->table_off + j;
+        if (g < g_lo || g >= g_hi) continue;
+        uint32_t id = block_table[g];
+        if (id >= pool->num_blocks) {
+          st |= ORC_ST_BAD_BLOCK;
+        } else {
+          move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + (uint64_t)j * bb, to_object);
+        }
+        if (to_object && j + 1 == x->n_blocks) /* pad the tail of the object with zeros */
+          memset(obj + (uint64_t)x->n_blocks * bb, 0, x->obj_bytes - (uint64_t)x->n_blocks * bb);
+      }
+    }
+  }
+  if (status && st) __atomic_fetch_or(status, st, __ATOMIC_RELAXED);
+}
+
+static int check_move_args(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                           const uint32_t *block_table, const void *stage) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (!pool->k_base || !pool->v_base) return ORC_EINVAL;
+  if (n_req > 0 && (!extents || !stage)) return ORC_EINVAL;
+  uint64_t n_tab = 0;
+  for (uint32_t r = 0; r < n_req; ++r) n_tab += extents[r].n_blocks;
+  if (n_tab > 0 && !block_table) return ORC_EINVAL;
+  return ORC_OK;
+}
+
+/* ORC_ST_STAGE_CAP if any request's objects end beyond stage_cap. */
+static uint32_t cap_status(const orc_extent *extents, uint32_t n_req, uint64_t stage_cap) {
+  for (uint32_t r = 0; r < n_req; ++r)
+    if (extents[r].stage_off + 2 * extents[r].obj_bytes > stage_cap) return ORC_ST_STAGE_CAP;
+  return 0;
+}
+
+static uint64_t total_blocks(const orc_extent *extents, uint32_t n_req) {
+  uint64_t hi = 0;
+  for (uint32_t r = 0; r < n_req; ++r) {
+    uint64_t end = (uint64_t)extents[r].table_off + extents[r].n_blocks;
+    if (end > hi) hi = end;
+  }
+  return hi;
+}
+
+/* Save direction: every hit block of every request into its object (sec. 3.1; store_layer of sec. 3.4). */
+int orc_obj_pack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                 const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t *status) {
+  int rc = check_move_args(pool, cfg, extents, n_req, block_table, stage);
+  if (rc) return rc;
+  if (status) *status |= cap_status(extents, n_req, stage_cap);
+  move_range(pool, extents, n_req, block_table, (uint8_t *)stage, stage_cap, 1, 0, total_blocks(extents, n_req), status);
+  return ORC_OK;
+}
+
+/* Restore direction: every object back into the request's blocks (retrieve_layer of sec. 3.4). */
+int orc_obj_unpack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                   const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t *status) {
+  int rc = check_move_args(pool, cfg, extents, n_req, block_table, stage);
+  if (rc) return rc;
+  if (status) *status |= cap_status(extents, n_req, stage_cap);
+  move_range(pool, extents, n_req, block_table, (uint8_t *)(uintptr_t)stage, stage_cap, 0, 0,
+             total_blocks(extents, n_req), status);
+  return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ submission entries */
+
+/*
+ * Entries of one layer in the order: request ascending; K object then V object; chunk ascending.
+ * Each carries the I/O-context fields (address, GPU-file offset, length: sec. 3.2), the SGL
+ * identifier (sec. 3.1) and its place in the 2048-slot IOCBs (sec. 3.2).  A request's GPU file
+ * holds its 2*L objects layer-major, K before V (sec. 3.1: 2*L objects per file; the order is
+ * this repository's reading).
+ */
+int orc_sqe_build(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                  const uint32_t *file_id, uint32_t layer, uint32_t opcode, uint64_t stage_addr, uint32_t sgl_id,
+                  orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (n_req > 0 && (!extents || !file_id)) return ORC_EINVAL;
+  if (sqe_cap > 0 && !sqe) return ORC_EINVAL;
+  if (opcode != ORC_OP_READ && opcode != ORC_OP_WRITE) return ORC_EINVAL;
+  if (layer >= cfg->num_layers) return ORC_EINVAL;
+  if (stage_addr % cfg->align != 0) return ORC_EINVAL;
+  const uint64_t C = cfg->chunk_bytes;
+  uint32_t st = 0;
+
+  for (uint32_t r = 0; r < n_req; ++r) {
+    const orc_extent *x = &extents[r];
+    for (uint32_t kind = 0; kind < 2; ++kind) {
+      for (uint32_t c = 0; c < x->n_chunks; ++c) {
+        uint64_t i = (uint64_t)x->sqe_base + (uint64_t)kind * x->n_chunks + c;
+        if (i >= sqe_cap) {
+          st |= ORC_ST_SQE_CAP;
+          continue;
+        }
+        uint64_t left = x->obj_bytes - (uint64_t)c * C;
+        orc_sqe s;
+        memset(&s, 0, sizeof s);
+        s.opcode = (uint8_t)opcode;
+        s.kind = (uint8_t)kind;
+        s.layer = (uint16_t)layer;
+        s.file_id = file_id[r];
+        s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)c * C;
+        s.addr = stage_addr + x->stage_off + (uint64_t)kind * x->obj_bytes + (uint64_t)c * C;
+        s.len = (uint32_t)(left < C ? left : C);
+        s.sgl_id = sgl_id;
+        s.user_data = ((uint64_t)r << 32) | (uint32_t)i;
+        s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);
+        s.ioctx_slot = (uint32_t)(i % ORC_IOCB_SLOTS);
+        sqe[i] = s;
+      }
+    }
+  }
+  if (status && st) *status |= st;
+  return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ fused restore */
+
+/* One layer's restore as the library's single call does it: extents, READ entries, unpack. */
+int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                      const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, const void *stage,
+                      uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents,
+                      uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (layer >= cfg->num_layers || stage_addr % cfg->align != 0) return ORC_EINVAL;
+  if (n_req > 0 && (!file_id || !stage)) return ORC_EINVAL;
+  if (!pool->k_base || !pool->v_base) return ORC_EINVAL;
+  if (sqe_cap > 0 && !sqe) return ORC_EINVAL;
+  rc = orc_obj_layout(pool, cfg, n_blocks, n_req, extents, totals);
+  if (rc) return rc;
+  rc = orc_sqe_build(pool, cfg, extents, n_req, file_id, layer, ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);
+  if (rc) return rc;
+  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);
+}
+
+/* ------------------------------------------------------------------ threaded timing helpers */
+
+typedef struct {
+  const orc_pool *pool;
+  const orc_extent *extents;
+  uint32_t n_req;
+  const uint32_t *block_table;
+  uint8_t *stage;
+  uint64_t stage_cap;
+  int to_object;
+  uint64_t g_lo, g_hi;
+} mt_job;
+
+static void *mt_run(void *p) {
+  mt_job *j = (mt_job *)p;
+  move_range(j->pool, j->extents, j->n_req, j->block_table, j->stage, j->stage_cap, j->to_object, j->g_lo, j->g_hi,
+             NULL);
+  return NULL;
+}
+
+static int move_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                   const uint32_t *block_table, uint8_t *stage, uint64_t stage_cap, int to_object,
+                   uint32_t n_threads) {
+  int rc = check_move_args(pool, cfg, extents, n_req, block_table, stage);
+  if (rc) return rc;
+  if (n_threads == 0 || n_threads > 1024) return ORC_ERANGE;
+  uint64_t n = total_blocks(extents, n_req);
+  pthread_t tid[1024];
+  mt_job job[1024];
+  uint32_t started = 0;
+  for (uint32_t t = 0; t < n_threads; ++t) {
+    job[t].pool = pool;
+    job[t].extents = extents;
+    job[t].n_req = n_req;
+    job[t].block_table = block_table;
+    job[t].stage = stage;
+    job[t].stage_cap = stage_cap;
+    job[t].to_object = to_object;
+    job[t].g_lo = n * t / n_threads;
+    job[t].g_hi = n * (t + 1) / n_threads;
+    if (pthread_create(&tid[t], NULL, mt_run, &job[t]) != 0) break;
+    ++started;
+  }
+  for (uint32_t t = 0; t < started; ++t) pthread_join(tid[t], NULL);
+  return started == n_threads ? ORC_OK : ORC_ERANGE;
+}
+
+int orc_obj_pack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                    const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t n_threads) {
+  return move_mt(pool, cfg, extents, n_req, block_table, (uint8_t *)stage, stage_cap, 1, n_threads);
+}
+
+int orc_obj_unpack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                      const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t n_threads) {
+  return move_mt(pool, cfg, extents, n_req, block_table, (uint8_t *)(uintptr_t)stage, stage_cap, 0, n_threads);
+}

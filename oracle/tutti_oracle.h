@@ -1,0 +1,151 @@
+/*
+ * tutti_oracle.h -- CPU oracle for the per-layer KV object path. TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, single-threaded, obviously-correct host implementation of what the GPU
+ * library computes: object extents, pack (paged blocks -> contiguous per-layer objects),
+ * unpack (objects -> paged blocks) and submission-entry construction.  It exists so that
+ * the tests, the smoke check and the benchmark's cpu_baseline leg can compare the HIP path
+ * against an independent definition.  Nothing on the product path may include, link or
+ * call it, and it shares no source, header, table or helper with the HIP library: every
+ * record below is re-declared here on purpose (a test checks that both sides agree on
+ * sizeof/offsetof).
+ *
+ * What the paper fixes and what is this repository's reading of it:
+ *   - a paged KV block has shape [Block, h, d] (sec. 2.1, "Paged KV Memory Management");
+ *   - there is one key object and one value object per layer, and a GPU file holds 2*L
+ *     objects (sec. 3.1, "Scalable GPU File Pool");
+ *   - an I/O context carries an SGL address, a GPU-file offset and a length, and 2048 of
+ *     them form one IOCB = one submission-queue entry (sec. 3.2, "Zero-Copy Ring Buffers");
+ *   - an SGL descriptor is 16 bytes: address 8, length 4, identifier 4 (sec. 3.1, "P2P
+ *     Memory Mapping Table").
+ *   The paper gives no byte layout for any record, no alignment unit, no chunk size, no
+ *   order of the 2*L objects in a file and no padding content.  Those are repository
+ *   readings: 4 KiB alignment, caller-chosen chunk size, layer-major K-then-V object
+ *   order, zero padding.  The record layouts, user_data packing and these readings are
+ *   "parity unpinned" by the paper: they are pinned only by closed forms, invariants and
+ *   brute force in the CPU tests.
+ *
+ * All pointers are HOST pointers.  Every function returns 0 on success and a negative
+ * ORC_E* code on bad arguments; nothing is written on error.
+ */
+#ifndef TUTTI_ORACLE_H
+#define TUTTI_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ORC_OK 0
+#define ORC_EINVAL (-1)
+#define ORC_ERANGE (-2)
+
+#define ORC_LAYOUT_NHD 0u /* block stored [T][h][d]  (the paper's [Block, h, d]) */
+#define ORC_LAYOUT_HND 1u /* block stored [h][T][d]  (head-major engines)        */
+
+#define ORC_OP_READ 1u  /* object -> HBM, restore */
+#define ORC_OP_WRITE 2u /* HBM -> object, save    */
+
+#define ORC_IOCB_SLOTS 2048u /* I/O contexts per IOCB, sec. 3.2 */
+
+/* Bits of the optional status word (ORed in, never cleared, by pack / unpack / restore). */
+#define ORC_ST_BAD_BLOCK 1u  /* a block-table entry >= num_blocks: that block was skipped */
+#define ORC_ST_STAGE_CAP 2u  /* a request's objects end beyond stage_cap: the request was skipped */
+#define ORC_ST_SQE_CAP 4u    /* more entries than sqe_cap: the excess was not written */
+
+/* One layer's paged pool: a K plane and a V plane of num_blocks blocks each. */
+typedef struct {
+  void *k_base;
+  void *v_base;
+  uint64_t block_stride; /* bytes between consecutive blocks of a plane, >= block_bytes */
+  uint32_t num_blocks;
+  uint32_t block_tokens; /* T */
+  uint32_t num_kv_heads; /* h */
+  uint32_t head_dim;     /* d */
+  uint32_t elt_bytes;    /* e */
+  uint32_t pool_layout;  /* ORC_LAYOUT_* */
+} orc_pool;
+
+typedef struct {
+  uint32_t align;       /* object alignment unit A, power of two >= 16 */
+  uint32_t chunk_bytes; /* C, multiple of A: one submission entry covers at most C bytes */
+  uint32_t num_layers;  /* L */
+} orc_objcfg;
+
+/* Per-request extent, identical for every layer. */
+typedef struct {
+  uint64_t stage_off; /* byte offset of the request's K object in the layer's staging buffer */
+  uint64_t obj_bytes; /* align_up(n_blocks*block_bytes, A); the V object follows the K object */
+  uint32_t n_blocks;
+  uint32_t n_chunks;  /* ceil(obj_bytes / C), per object */
+  uint32_t sqe_base;  /* index of the request's first entry in the layer's entry array */
+  uint32_t table_off; /* index of the request's first entry in the flattened block table */
+} orc_extent;
+
+/* Submission entry, 64 bytes, little-endian, naturally aligned. */
+typedef struct {
+  uint8_t opcode;
+  uint8_t kind; /* 0 = K object, 1 = V object */
+  uint16_t layer;
+  uint32_t file_id;
+  uint64_t file_off;
+  uint64_t addr;
+  uint32_t len;
+  uint32_t sgl_id;
+  uint64_t user_data; /* (request << 32) | entry index within the layer */
+  uint32_t iocb_idx;
+  uint32_t ioctx_slot;
+  uint8_t rsvd[16];
+} orc_sqe;
+
+/* Size/offset table of the records above, for the cross-check against the library's header:
+ * out[0..]: sizeof(extent), offsets of its 6 fields, sizeof(sqe), offsets of its 11 fields,
+ * sizeof(pool), offsets of its 9 fields, sizeof(objcfg), offsets of its 3 fields (33 values). */
+int orc_abi_describe(uint32_t *out, uint32_t cap);
+
+/* T*h*d*e, or 0 if any factor is 0 or the product does not fit 32 bits. */
+uint32_t orc_block_bytes(const orc_pool *pool);
+
+/* Extents of n_req requests; totals[0] = staging bytes of one layer, totals[1] = entries of one layer. */
+int orc_obj_layout(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                   orc_extent *extents, uint64_t *totals);
+
+/* Paged blocks -> objects.  stage receives, per request, the K object then the V object,
+ * each zero-padded to obj_bytes.  Requests whose objects do not fit in stage_cap are skipped,
+ * and so is any block whose table entry is >= num_blocks (its object bytes stay as they were);
+ * both are reported in *status (may be NULL). */
+int orc_obj_pack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                 const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t *status);
+
+/* Objects -> paged blocks; padding is not read; blocks not named in the table are not touched. */
+int orc_obj_unpack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                   const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t *status);
+
+/* One entry per chunk of every K and V object of one layer.  Entries with index >= sqe_cap are not written. */
+int orc_sqe_build(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                  const uint32_t *file_id, uint32_t layer, uint32_t opcode, uint64_t stage_addr, uint32_t sgl_id,
+                  orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
+
+/* layout, then READ entries, then unpack, for one layer. */
+int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                      const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, const void *stage,
+                      uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents,
+                      uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
+
+/* Descriptor count for a pool of pool_bytes described at gran bytes per descriptor
+ * (the arithmetic of sec. 3.1, "P2P Memory Mapping Table"). */
+uint64_t orc_desc_count(uint64_t pool_bytes, uint64_t gran);
+
+/* Timing helpers for the benchmark's cpu_baseline leg only: the same per-block copies as
+ * orc_obj_pack / orc_obj_unpack, with the flattened block range split evenly over n_threads
+ * POSIX threads.  Parity never uses these. */
+int orc_obj_pack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                    const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t n_threads);
+int orc_obj_unpack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                      const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t n_threads);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,183 @@
+"""ctypes wrapper of the CPU oracle (oracle/tutti_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, `__graft_entry__.smoke()` and `bench.py`'s cpu_baseline leg may import this.
+It shares nothing with the HIP library or its binding: the records are declared here a
+third time as numpy dtypes / ctypes structures, and a test checks all declarations agree.
+
+Every array is a host numpy array.  K and V planes are uint8 arrays of
+`num_blocks * block_stride` bytes (any dtype is viewed as bytes).
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+LAYOUT_NHD, LAYOUT_HND = 0, 1
+OP_READ, OP_WRITE = 1, 2
+ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP = 1, 2, 4
+IOCB_SLOTS = 2048
+
+EXTENT_DTYPE = np.dtype([("stage_off", "<u8"), ("obj_bytes", "<u8"), ("n_blocks", "<u4"), ("n_chunks", "<u4"),
+                         ("sqe_base", "<u4"), ("table_off", "<u4")], align=True)
+SQE_DTYPE = np.dtype([("opcode", "u1"), ("kind", "u1"), ("layer", "<u2"), ("file_id", "<u4"), ("file_off", "<u8"),
+                      ("addr", "<u8"), ("len", "<u4"), ("sgl_id", "<u4"), ("user_data", "<u8"), ("iocb_idx", "<u4"),
+                      ("ioctx_slot", "<u4"), ("rsvd", "u1", (16,))], align=True)
+
+
+class OrcPool(C.Structure):
+    _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("block_stride", C.c_uint64),
+                ("num_blocks", C.c_uint32), ("block_tokens", C.c_uint32), ("num_kv_heads", C.c_uint32),
+                ("head_dim", C.c_uint32), ("elt_bytes", C.c_uint32), ("pool_layout", C.c_uint32)]
+
+
+class OrcObjCfg(C.Structure):
+    _fields_ = [("align", C.c_uint32), ("chunk_bytes", C.c_uint32), ("num_layers", C.c_uint32)]
+
+
+class OracleError(RuntimeError):
+    def __init__(self, fn, rc):
+        super().__init__(f"{fn} returned {rc}")
+        self.rc = rc
+
+
+def lib():
+    """Load the oracle library, building it with gcc first if it is not there."""
+    global _LIB
+    if _LIB is None:
+        path = os.path.join(_HERE, "libtutti_oracle.so")
+        if not os.path.exists(path):
+            import importlib.util
+            spec = importlib.util.spec_from_file_location("_oracle_build", os.path.join(_HERE, "build.py"))
+            mod = importlib.util.module_from_spec(spec)
+            spec.loader.exec_module(mod)
+            mod.build_oracle()
+        L = C.CDLL(path)
+        L.orc_block_bytes.restype = C.c_uint32
+        L.orc_desc_count.restype = C.c_uint64
+        L.orc_desc_count.argtypes = [C.c_uint64, C.c_uint64]
+        _LIB = L
+    return _LIB
+
+
+def _ptr(a):
+    return C.c_void_p(a.ctypes.data if a is not None else 0)
+
+
+def _bytes_view(a):
+    a = np.ascontiguousarray(a)
+    return a.view(np.uint8).reshape(-1)
+
+
+def make_pool(k_plane, v_plane, *, num_blocks, block_tokens, num_kv_heads, head_dim, elt_bytes, block_stride=None,
+              pool_layout=LAYOUT_NHD):
+    """Describe one layer's pool.  k_plane / v_plane: writable contiguous host arrays (or None)."""
+    bb = block_tokens * num_kv_heads * head_dim * elt_bytes
+    p = OrcPool()
+    p.k_base = k_plane.ctypes.data if k_plane is not None else 0
+    p.v_base = v_plane.ctypes.data if v_plane is not None else 0
+    p.block_stride = bb if block_stride is None else block_stride
+    p.num_blocks, p.block_tokens, p.num_kv_heads = num_blocks, block_tokens, num_kv_heads
+    p.head_dim, p.elt_bytes, p.pool_layout = head_dim, elt_bytes, pool_layout
+    p._keep = (k_plane, v_plane)
+    return p
+
+
+def make_cfg(align=4096, chunk_bytes=2 << 20, num_layers=1):
+    return OrcObjCfg(align, chunk_bytes, num_layers)
+
+
+def abi_describe():
+    out = np.zeros(64, np.uint32)
+    n = lib().orc_abi_describe(_ptr(out), C.c_uint32(out.size))
+    if n < 0:
+        raise OracleError("orc_abi_describe", n)
+    return out[:n].tolist()
+
+
+def block_bytes(pool):
+    return int(lib().orc_block_bytes(C.byref(pool)))
+
+
+def desc_count(pool_bytes, gran):
+    return int(lib().orc_desc_count(pool_bytes, gran))
+
+
+def obj_layout(pool, cfg, n_blocks):
+    n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)
+    ext = np.zeros(n_blocks.size, EXTENT_DTYPE)
+    totals = np.zeros(2, np.uint64)
+    rc = lib().orc_obj_layout(C.byref(pool), C.byref(cfg), _ptr(n_blocks), C.c_uint32(n_blocks.size), _ptr(ext),
+                              _ptr(totals))
+    if rc:
+        raise OracleError("orc_obj_layout", rc)
+    return ext, totals
+
+
+def obj_pack(pool, cfg, extents, block_table, stage, stage_cap=None, n_threads=0):
+    """Pack into `stage` (uint8 host array, modified in place).  Returns the status word."""
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    cap = stage.nbytes if stage_cap is None else stage_cap
+    status = C.c_uint32(0)
+    if n_threads:
+        rc = lib().orc_obj_pack_mt(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
+                                   _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.c_uint32(n_threads))
+    else:
+        rc = lib().orc_obj_pack(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
+                                _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.byref(status))
+    if rc:
+        raise OracleError("orc_obj_pack", rc)
+    return status.value
+
+
+def obj_unpack(pool, cfg, extents, block_table, stage, stage_cap=None, n_threads=0):
+    """Unpack `stage` into the planes the pool points at.  Returns the status word."""
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    cap = stage.nbytes if stage_cap is None else stage_cap
+    status = C.c_uint32(0)
+    if n_threads:
+        rc = lib().orc_obj_unpack_mt(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
+                                     _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.c_uint32(n_threads))
+    else:
+        rc = lib().orc_obj_unpack(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
+                                  _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.byref(status))
+    if rc:
+        raise OracleError("orc_obj_unpack", rc)
+    return status.value
+
+
+def sqe_build(pool, cfg, extents, file_id, layer, opcode, stage_addr, sgl_id, sqe_cap=None):
+    """Returns (sqe array of sqe_cap entries, status).  Default capacity: exactly what the extents need."""
+    file_id = np.ascontiguousarray(file_id, dtype=np.uint32)
+    need = int(2 * extents["n_chunks"].astype(np.uint64).sum())
+    cap = need if sqe_cap is None else sqe_cap
+    sqe = np.zeros(cap, SQE_DTYPE)
+    status = C.c_uint32(0)
+    rc = lib().orc_sqe_build(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size), _ptr(file_id),
+                             C.c_uint32(layer), C.c_uint32(opcode), C.c_uint64(stage_addr), C.c_uint32(sgl_id),
+                             _ptr(sqe), C.c_uint32(cap), C.byref(status))
+    if rc:
+        raise OracleError("orc_sqe_build", rc)
+    return sqe, status.value
+
+
+def layer_restore(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap,
+                  stage_cap=None):
+    """Returns (extents, totals, sqe, status); the planes the pool points at are modified in place."""
+    n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    file_id = np.ascontiguousarray(file_id, dtype=np.uint32)
+    ext = np.zeros(n_blocks.size, EXTENT_DTYPE)
+    totals = np.zeros(2, np.uint64)
+    sqe = np.zeros(sqe_cap, SQE_DTYPE)
+    cap = stage.nbytes if stage_cap is None else stage_cap
+    status = C.c_uint32(0)
+    rc = lib().orc_layer_restore(C.byref(pool), C.byref(cfg), _ptr(n_blocks), C.c_uint32(n_blocks.size),
+                                 _ptr(block_table), _ptr(file_id), C.c_uint32(layer), _ptr(stage), C.c_uint64(cap),
+                                 C.c_uint64(stage_addr), C.c_uint32(sgl_id), _ptr(ext), _ptr(totals), _ptr(sqe),
+                                 C.c_uint32(sqe_cap), C.byref(status))
+    if rc:
+        raise OracleError("orc_layer_restore", rc)
+    return ext, totals, sqe, status.value

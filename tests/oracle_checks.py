@@ -1,0 +1,489 @@
+"""Pins for the CPU oracle: what the paper prints, closed forms, library routines, brute force.
+
+Every check takes the oracle wrapper module `orc` and raises AssertionError on a mismatch, so
+the same checks run against the real oracle (tests must pass) and against deliberately broken
+copies of its source (tests/test_oracle_mutants.py: every check list must catch its mutants).
+Nothing here retypes the oracle's own code path: expected values come from the paper's printed
+numbers (tests/golden/paper_counts.txt), numpy library routines (cumsum, fancy indexing,
+transpose), or a six-deep pure-Python loop written from the element-wise definition.
+"""
+import itertools
+import os
+
+import numpy as np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_counts.txt")
+
+
+def golden():
+    out = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, value, _ = [x.strip() for x in line.split("|", 2)]
+            out[name] = int(value)
+    return out
+
+
+def _pool(orc, T, h, d, e, N, k=None, v=None, stride=None, layout=0):
+    return orc.make_pool(k, v, num_blocks=N, block_tokens=T, num_kv_heads=h, head_dim=d, elt_bytes=e,
+                         block_stride=stride, pool_layout=layout)
+
+
+def _planes(rng, N, stride):
+    k = rng.integers(0, 256, size=N * stride, dtype=np.uint8)
+    v = rng.integers(0, 256, size=N * stride, dtype=np.uint8)
+    return k, v
+
+
+# ---------------------------------------------------------------------------- paper counts
+
+def check_paper_counts(orc):
+    g = golden()
+    # 64 layers, 64-token blocks, 128K tokens, one entry per block (chunk = block): sec. 2.2
+    T, h, d, e = 64, 8, 128, 2
+    bb = T * h * d * e
+    p = _pool(orc, T, h, d, e, 4096)
+    cfg = orc.make_cfg(4096, bb, 64)
+    n = 128 * 1024 // T
+    ext, tot = orc.obj_layout(p, cfg, [n])
+    assert int(tot[1]) * 64 == g["io_count_64layer_block64_128k"]
+    assert int(tot[1]) == g["objects_per_file_factor"] * n
+    # 256-token chunks, 128K tokens, K and V counted separately: sec. 2.2
+    p = _pool(orc, 256, 8, 128, 2, 1024)
+    cfg = orc.make_cfg(4096, 256 * 8 * 128 * 2, 32)
+    ext, tot = orc.obj_layout(p, cfg, [128 * 1024 // 256])
+    assert int(tot[1]) == g["chunk_accesses_256tok_128k"]
+    # descriptor arithmetic: sec. 3.1
+    assert orc.desc_count(60 * 1024 ** 3, 4096) == g["pool_pages_60GiB_4KiB"]
+    nd = orc.desc_count(60 * 1024 ** 3, 64 * 1024)
+    assert nd == g["descriptors_60GiB_64KiB"]
+    assert nd * 4096 == g["prp_bytes"] and nd * g["sgl_descriptor_bytes"] == g["sgl_bytes"]
+    assert orc.desc_count(65537, 65536) == 2 and orc.desc_count(65536, 65536) == 1
+    assert orc.IOCB_SLOTS == g["iocb_slots"]
+
+
+def check_closed_forms_8b(orc):
+    """The 8B shape: 2048 blocks of 32 KiB, 2 MiB chunks -> 64 entries and 128 MiB per layer."""
+    p = _pool(orc, 16, 8, 128, 2, 65536)
+    assert orc.block_bytes(p) == 32768
+    cfg = orc.make_cfg(4096, 2 << 20, 32)
+    ext, tot = orc.obj_layout(p, cfg, [2048])
+    assert int(tot[0]) == 134217728 and int(tot[1]) == 64
+    assert int(ext["obj_bytes"][0]) == 67108864 and int(ext["n_chunks"][0]) == 32
+    # Tiny: 32 blocks of 4 KiB -> one 128 KiB object per plane; 4 KiB chunks -> 32 entries per object
+    p = _pool(orc, 16, 2, 64, 2, 256)
+    assert orc.block_bytes(p) == 4096
+    ext, tot = orc.obj_layout(p, orc.make_cfg(4096, 4096, 1), [32])
+    assert int(tot[0]) == 262144 and int(tot[1]) == 64
+    ext, tot = orc.obj_layout(p, orc.make_cfg(4096, 2 << 20, 1), [32])
+    assert int(tot[1]) == 2
+
+
+def check_abi(orc):
+    g = golden()
+    d = orc.abi_describe()
+    assert len(d) == 33
+    ext, sqe, pool, cfg = d[0:7], d[7:19], d[19:29], d[29:33]
+    assert ext == [32, 0, 8, 16, 20, 24, 28]
+    assert sqe == [64, 0, 1, 2, 4, 8, 16, 24, 28, 32, 40, 44]
+    assert pool == [48, 0, 8, 16, 24, 28, 32, 36, 40, 44]
+    assert cfg == [12, 0, 4, 8]
+    # the wrapper's numpy / ctypes declarations agree with the C ones
+    E, S = orc.EXTENT_DTYPE, orc.SQE_DTYPE
+    assert E.itemsize == 32 and [E.fields[n][1] for n in E.names] == ext[1:]
+    assert S.itemsize == 64 and [S.fields[n][1] for n in S.names[:-1]] == sqe[1:]
+    assert S.fields["rsvd"][1] == 48
+    import ctypes
+    assert ctypes.sizeof(orc.OrcPool) == 48 and ctypes.sizeof(orc.OrcObjCfg) == 12
+    # the SGL triple (address 8, length 4, identifier 4) sits in 16 consecutive bytes: sec. 3.1
+    assert S.fields["addr"][1] + 8 == S.fields["len"][1] and S.fields["len"][1] + 4 == S.fields["sgl_id"][1]
+    assert S.fields["sgl_id"][1] + 4 - S.fields["addr"][1] == g["sgl_descriptor_bytes"]
+
+
+# ---------------------------------------------------------------------------- extents
+
+def check_layout_scan(orc, seed=11):
+    """Offsets are exclusive prefix sums (numpy cumsum) and obey the alignment / packing invariants."""
+    rng = np.random.default_rng(seed)
+    for T, h, d, e, A, C in [(16, 8, 128, 2, 4096, 2 << 20), (16, 2, 64, 2, 4096, 4096), (16, 5, 40, 2, 4096, 8192),
+                             (3, 1, 8, 2, 512, 512), (16, 8, 128, 2, 4096, 32768), (7, 3, 16, 1, 64, 192)]:
+        bb = T * h * d * e
+        for R in (1, 2, 7, 64, 65, 300):
+            n = rng.integers(0, 50, size=R).astype(np.uint32)
+            n[rng.integers(0, R)] = 0
+            p = _pool(orc, T, h, d, e, 1 << 16)
+            ext, tot = orc.obj_layout(p, orc.make_cfg(A, C, 4), n)
+            obj = (n.astype(np.uint64) * bb + A - 1) // A * A
+            chunks = (obj + C - 1) // C
+            assert np.array_equal(ext["n_blocks"], n)
+            assert np.array_equal(ext["obj_bytes"], obj)
+            assert np.array_equal(ext["n_chunks"], chunks.astype(np.uint32))
+            assert np.array_equal(ext["stage_off"], np.cumsum(2 * obj) - 2 * obj)
+            assert np.array_equal(ext["sqe_base"], (np.cumsum(2 * chunks) - 2 * chunks).astype(np.uint32))
+            assert np.array_equal(ext["table_off"], (np.cumsum(n.astype(np.uint64)) - n).astype(np.uint32))
+            assert int(tot[0]) == int((2 * obj).sum()) and int(tot[1]) == int((2 * chunks).sum())
+            assert np.all(ext["stage_off"] % A == 0) and np.all(ext["obj_bytes"] % A == 0)
+            assert np.all(ext["obj_bytes"] >= n.astype(np.uint64) * bb)
+            assert np.all(ext["obj_bytes"] < n.astype(np.uint64) * bb + A)
+            # naive O(R^2) sums
+            for r in range(0, R, max(1, R // 5)):
+                assert int(ext["stage_off"][r]) == sum(2 * int(o) for o in obj[:r])
+    # no requests at all
+    ext, tot = orc.obj_layout(_pool(orc, 16, 8, 128, 2, 64), orc.make_cfg(), np.zeros(0, np.uint32))
+    assert ext.size == 0 and int(tot[0]) == 0 and int(tot[1]) == 0
+
+
+# ---------------------------------------------------------------------------- pack / unpack
+
+def _ref_extents(n_blocks, bb, A):
+    """Plain-Python extents for the reference formulations below: (stage_off, obj_bytes) per request."""
+    out, off = [], 0
+    for n in n_blocks:
+        obj = -(-int(n) * bb // A) * A
+        out.append((off, obj))
+        off += 2 * obj
+    return out, off
+
+
+def ref_pack_elementwise(k, v, layout, T, h, d, e, stride, n_blocks, table, A):
+    """The definition, element by element: six nested loops (request, kind, block, token, head, dim)."""
+    bb = T * h * d * e
+    ext, total = _ref_extents(n_blocks, bb, A)
+    stage = np.zeros(total, np.uint8)
+    pos = 0
+    for r, n in enumerate(n_blocks):
+        off, obj = ext[r]
+        for kind in range(2):
+            plane = (k, v)[kind]
+            for j in range(int(n)):
+                blk = int(table[pos + j]) * stride
+                for t in range(T):
+                    for i in range(h):
+                        for x in range(d):
+                            src = ((t * h + i) * d + x) * e if layout == 0 else ((i * T + t) * d + x) * e
+                            dst = off + kind * obj + j * bb + ((t * h + i) * d + x) * e
+                            stage[dst:dst + e] = plane[blk + src: blk + src + e]
+        pos += int(n)
+    return stage
+
+
+def check_pack_bruteforce(orc):
+    """Pools of <= 6 blocks: every ordered selection of blocks as the table, both layouts."""
+    rng = np.random.default_rng(5)
+    T, h, d, e, A = 3, 2, 4, 2, 64  # block_bytes 48: not a multiple of A, so every object has padding
+    bb = T * h * d * e
+    for N in (1, 3, 4):
+        k, v = _planes(rng, N, bb)
+        for layout in (0, 1):
+            p = _pool(orc, T, h, d, e, N, k, v, layout=layout)
+            cfg = orc.make_cfg(A, A, 2)
+            for m in range(0, N + 1):
+                for table in itertools.permutations(range(N), m):
+                    ext, tot = orc.obj_layout(p, cfg, [m])
+                    stage = np.full(int(tot[0]), 0xAB, np.uint8)
+                    assert orc.obj_pack(p, cfg, ext, np.array(table, np.uint32), stage) == 0
+                    want = ref_pack_elementwise(k, v, layout, T, h, d, e, bb, [m], table, A)
+                    assert np.array_equal(stage, want), (N, layout, table)
+    # two requests sharing one pool of 6 blocks, every split of a permutation
+    N = 6
+    k, v = _planes(rng, N, bb)
+    for layout in (0, 1):
+        p = _pool(orc, T, h, d, e, N, k, v, layout=layout)
+        cfg = orc.make_cfg(A, 2 * A, 2)
+        for perm in itertools.islice(itertools.permutations(range(N)), 0, 720, 7):
+            for cut in range(0, N + 1):
+                nb = [cut, N - cut]
+                ext, tot = orc.obj_layout(p, cfg, nb)
+                stage = np.full(int(tot[0]), 0xCD, np.uint8)
+                orc.obj_pack(p, cfg, ext, np.array(perm, np.uint32), stage)
+                want = ref_pack_elementwise(k, v, layout, T, h, d, e, bb, nb, perm, A)
+                assert np.array_equal(stage, want), (layout, perm, cut)
+
+
+def check_pack_vs_numpy(orc, seed=3):
+    """NHD pack is a fancy-index gather; identity table is a memcpy; HND is a transpose; strided pools."""
+    rng = np.random.default_rng(seed)
+    for T, h, d, e, A, pad in [(16, 2, 64, 2, 4096, 0), (16, 8, 128, 2, 4096, 0), (16, 5, 40, 2, 4096, 0),
+                               (16, 2, 64, 2, 4096, 256), (4, 3, 8, 2, 128, 16)]:
+        bb = T * h * d * e
+        stride = bb + pad
+        N = 64
+        k, v = _planes(rng, N, stride)
+        k2, v2 = k.reshape(N, stride), v.reshape(N, stride)
+        n = np.array([5, 0, 17, 1, 9], np.uint32)
+        table = rng.permutation(N)[: int(n.sum())].astype(np.uint32)
+        cfg = orc.make_cfg(A, 4 * A, 3)
+        for layout in (0, 1):
+            p = _pool(orc, T, h, d, e, N, k, v, stride=stride, layout=layout)
+            ext, tot = orc.obj_layout(p, cfg, n)
+            stage = np.full(int(tot[0]), 0xEE, np.uint8)
+            assert orc.obj_pack(p, cfg, ext, table, stage) == 0
+            pos = 0
+            for r in range(n.size):
+                ids = table[pos:pos + n[r]]
+                for kind, plane in enumerate((k2, v2)):
+                    blocks = plane[ids, :bb]                     # library gather
+                    if layout == 1:                              # [h][T][d*e] -> [T][h][d*e]
+                        blocks = blocks.reshape(-1, h, T, d * e).transpose(0, 2, 1, 3)
+                    want = np.ascontiguousarray(blocks).reshape(-1)
+                    o = int(ext["stage_off"][r]) + kind * int(ext["obj_bytes"][r])
+                    got = stage[o:o + int(ext["obj_bytes"][r])]
+                    assert np.array_equal(got[:want.size], want), (layout, r, kind)
+                    assert not got[want.size:].any(), "padding must be zero"
+                pos += int(n[r])
+        # identity table on a dense NHD pool: the K object is the first n*bb bytes of the plane
+        if pad == 0:
+            p = _pool(orc, T, h, d, e, N, k, v)
+            ext, tot = orc.obj_layout(p, cfg, [N])
+            stage = np.zeros(int(tot[0]), np.uint8)
+            orc.obj_pack(p, cfg, ext, np.arange(N, dtype=np.uint32), stage)
+            assert stage[:N * bb].tobytes() == k.tobytes()
+            o = int(ext["obj_bytes"][0])
+            assert stage[o:o + N * bb].tobytes() == v.tobytes()
+
+
+def check_address_tags(orc):
+    """Each 32-bit word of the pool holds its own index: every misplaced word is visible."""
+    T, h, d, e, A, N = 16, 2, 64, 2, 4096, 32
+    bb = T * h * d * e
+    words = bb // 4
+    k = np.arange(N * words, dtype=np.uint32)
+    v = np.arange(N * words, dtype=np.uint32) + (1 << 30)
+    table = np.array([9, 3, 31, 0, 17], np.uint32)
+    p = _pool(orc, T, h, d, e, N, k.view(np.uint8), v.view(np.uint8))
+    cfg = orc.make_cfg(A, A, 1)
+    ext, tot = orc.obj_layout(p, cfg, [table.size])
+    stage = np.zeros(int(tot[0]), np.uint8)
+    orc.obj_pack(p, cfg, ext, table, stage)
+    sw = stage.view(np.uint32)
+    for j, b in enumerate(table):
+        assert np.array_equal(sw[j * words:(j + 1) * words], np.arange(b * words, (b + 1) * words, dtype=np.uint32))
+        vo = int(ext["obj_bytes"][0]) // 4
+        assert np.array_equal(sw[vo + j * words: vo + (j + 1) * words],
+                              np.arange(b * words, (b + 1) * words, dtype=np.uint32) + (1 << 30))
+
+
+def check_roundtrip_and_untouched(orc, seed=8):
+    """unpack(pack(P)) = P on the named blocks; unpack writes nothing else; pack(unpack(S)) = S."""
+    rng = np.random.default_rng(seed)
+    for T, h, d, e, A, pad, layout in [(16, 2, 64, 2, 4096, 0, 0), (16, 2, 64, 2, 4096, 0, 1),
+                                       (16, 5, 40, 2, 4096, 64, 0), (4, 3, 8, 2, 128, 16, 1)]:
+        bb = T * h * d * e
+        stride = bb + pad
+        N = 48
+        k, v = _planes(rng, N, stride)
+        n = np.array([7, 0, 12, 3], np.uint32)
+        table = rng.permutation(N)[: int(n.sum())].astype(np.uint32)
+        cfg = orc.make_cfg(A, 2 * A, 2)
+        p = _pool(orc, T, h, d, e, N, k, v, stride=stride, layout=layout)
+        ext, tot = orc.obj_layout(p, cfg, n)
+        stage = np.zeros(int(tot[0]), np.uint8)
+        orc.obj_pack(p, cfg, ext, table, stage)
+        # restore into a different, pre-filled pool
+        k2, v2 = _planes(rng, N, stride)
+        k2_before, v2_before = k2.copy(), v2.copy()
+        p2 = _pool(orc, T, h, d, e, N, k2, v2, stride=stride, layout=layout)
+        assert orc.obj_unpack(p2, cfg, ext, table, stage) == 0
+        named = np.zeros(N, bool)
+        named[table] = True
+        for b in range(N):
+            sl = slice(b * stride, b * stride + bb)
+            gap = slice(b * stride + bb, (b + 1) * stride)
+            if named[b]:
+                assert np.array_equal(k2[sl], k[sl]) and np.array_equal(v2[sl], v[sl])
+            else:
+                assert np.array_equal(k2[sl], k2_before[sl]) and np.array_equal(v2[sl], v2_before[sl])
+            assert np.array_equal(k2[gap], k2_before[gap]) and np.array_equal(v2[gap], v2_before[gap])
+        # and back: pack of the restored pool reproduces the staging buffer, padding zero
+        stage2 = np.full(int(tot[0]), 0x77, np.uint8)
+        orc.obj_pack(p2, cfg, ext, table, stage2)
+        assert np.array_equal(stage2, stage)
+        # K and V are not swapped: the first object of request 0 holds K bytes
+        if layout == 0:
+            b0 = int(table[0])
+            assert np.array_equal(stage[:bb], k[b0 * stride: b0 * stride + bb])
+
+
+def check_skips_and_status(orc):
+    rng = np.random.default_rng(21)
+    T, h, d, e, A, N = 4, 2, 8, 2, 128, 16
+    bb = T * h * d * e
+    k, v = _planes(rng, N, bb)
+    p = _pool(orc, T, h, d, e, N, k, v)
+    cfg = orc.make_cfg(A, A, 1)
+    n = np.array([3, 2], np.uint32)
+    ext, tot = orc.obj_layout(p, cfg, n)
+    table = np.array([1, 99, 4, 7, 8], np.uint32)  # 99 is out of range
+    stage = np.full(int(tot[0]), 0x55, np.uint8)
+    st = orc.obj_pack(p, cfg, ext, table, stage)
+    assert st == orc.ST_BAD_BLOCK
+    assert np.all(stage[bb:2 * bb] == 0x55), "a skipped block leaves its object bytes alone"
+    assert np.array_equal(stage[:bb], k[bb:2 * bb]) and np.array_equal(stage[2 * bb:3 * bb], k[4 * bb:5 * bb])
+    # the first id that is out of range is num_blocks itself (planes hold one spare block here)
+    kx, vx = _planes(rng, N + 1, bb)
+    px = _pool(orc, T, h, d, e, N, kx, vx)
+    stage = np.full(int(tot[0]), 0x55, np.uint8)
+    st = orc.obj_pack(px, cfg, ext, np.array([N - 1, N, 0, 1, 2], np.uint32), stage)
+    assert st == orc.ST_BAD_BLOCK and np.all(stage[bb:2 * bb] == 0x55)
+    assert np.array_equal(stage[:bb], kx[(N - 1) * bb:N * bb])
+    # staging buffer too small for the second request: only the first is packed
+    table = np.array([1, 2, 4, 7, 8], np.uint32)
+    cap = int(ext["stage_off"][1]) + 8
+    stage = np.full(int(tot[0]), 0x55, np.uint8)
+    st = orc.obj_pack(p, cfg, ext, table, stage, stage_cap=cap)
+    assert st == orc.ST_STAGE_CAP
+    assert np.all(stage[int(ext["stage_off"][1]):] == 0x55)
+    assert np.array_equal(stage[:bb], k[bb:2 * bb])
+    k2, v2 = k.copy(), v.copy()
+    p2 = _pool(orc, T, h, d, e, N, k2, v2)
+    stage[:] = 0
+    st = orc.obj_unpack(p2, cfg, ext, table, stage, stage_cap=cap)
+    assert st == orc.ST_STAGE_CAP
+    assert not k2[bb:3 * bb].any() and np.array_equal(k2[7 * bb:9 * bb], k[7 * bb:9 * bb])
+    # entry capacity
+    sqe, st = orc.sqe_build(p, cfg, ext, [5, 6], 0, orc.OP_READ, 0, 0, sqe_cap=3)
+    assert st == orc.ST_SQE_CAP and sqe.size == 3 and np.all(sqe["opcode"] == orc.OP_READ)
+
+
+def check_errors(orc):
+    import pytest
+    p = _pool(orc, 16, 2, 64, 2, 8)
+    for bad in [dict(align=4095), dict(align=8), dict(chunk_bytes=4097), dict(chunk_bytes=0), dict(num_layers=0)]:
+        kw = dict(align=4096, chunk_bytes=8192, num_layers=1)
+        kw.update(bad)
+        with pytest.raises(orc.OracleError):
+            orc.obj_layout(p, orc.make_cfg(**kw), [1])
+    for bad in [dict(T=0), dict(d=3, e=1, T=1, h=1), dict(N=0), dict(stride=4095), dict(layout=2)]:
+        kw = dict(T=16, h=2, d=64, e=2, N=8, stride=None, layout=0)
+        kw.update(bad)
+        with pytest.raises(orc.OracleError):
+            orc.obj_layout(_pool(orc, kw["T"], kw["h"], kw["d"], kw["e"], kw["N"], stride=kw["stride"],
+                                 layout=kw["layout"]), orc.make_cfg(), [1])
+    ext, _ = orc.obj_layout(p, orc.make_cfg(num_layers=2), [2])
+    with pytest.raises(orc.OracleError):
+        orc.sqe_build(p, orc.make_cfg(num_layers=2), ext, [1], 2, orc.OP_READ, 0, 0)      # layer >= L
+    with pytest.raises(orc.OracleError):
+        orc.sqe_build(p, orc.make_cfg(num_layers=2), ext, [1], 0, 3, 0, 0)               # bad opcode
+    with pytest.raises(orc.OracleError):
+        orc.sqe_build(p, orc.make_cfg(num_layers=2), ext, [1], 0, orc.OP_READ, 100, 0)   # misaligned address
+
+
+# ---------------------------------------------------------------------------- submission entries
+
+def check_sqe_fields(orc, seed=13):
+    """Entry order, every field, and the tiling invariants, from a separate Python enumeration."""
+    rng = np.random.default_rng(seed)
+    for T, h, d, e, A, C, L in [(16, 8, 128, 2, 4096, 2 << 20, 32), (16, 2, 64, 2, 4096, 4096, 1),
+                                (16, 5, 40, 2, 4096, 12288, 5), (16, 8, 128, 2, 4096, 32768, 80)]:
+        bb = T * h * d * e
+        p = _pool(orc, T, h, d, e, 1 << 16)
+        cfg = orc.make_cfg(A, C, L)
+        n = rng.integers(0, 300, size=9).astype(np.uint32)
+        n[4] = 0
+        fid = rng.integers(0, 1 << 32, size=n.size, dtype=np.uint64).astype(np.uint32)
+        ext, tot = orc.obj_layout(p, cfg, n)
+        base = 0x7F0000000000
+        for layer, op in [(0, orc.OP_READ), (L - 1, orc.OP_WRITE)]:
+            sqe, st = orc.sqe_build(p, cfg, ext, fid, layer, op, base, 77)
+            assert st == 0 and sqe.size == int(tot[1])
+            i = 0
+            stage_off = 0
+            for r in range(n.size):
+                obj = -(-int(n[r]) * bb // A) * A
+                for kind in range(2):
+                    c = 0
+                    covered = 0
+                    while covered < obj:
+                        s = sqe[i]
+                        ln = min(C, obj - covered)
+                        assert (s["opcode"], s["kind"], s["layer"], s["file_id"]) == (op, kind, layer, fid[r])
+                        assert int(s["len"]) == ln and ln % A == 0
+                        assert int(s["addr"]) == base + stage_off + kind * obj + covered
+                        assert int(s["file_off"]) == (2 * layer + kind) * obj + covered
+                        assert int(s["sgl_id"]) == 77
+                        assert int(s["user_data"]) == (r << 32) | i
+                        assert (int(s["iocb_idx"]), int(s["ioctx_slot"])) == divmod(i, 2048)
+                        assert not s["rsvd"].any()
+                        covered += ln
+                        c += 1
+                        i += 1
+                    assert c == int(ext["n_chunks"][r])
+                stage_off += 2 * obj
+            assert i == sqe.size
+            # the entries tile the staging range exactly, in order
+            ends = sqe["addr"] + sqe["len"]
+            assert sqe.size == 0 or (int(sqe["addr"][0]) == base and int(ends[-1]) == base + int(tot[0]))
+            assert np.array_equal(sqe["addr"][1:], ends[:-1])
+        # the last chunk of (layer L-1, V) ends the request's GPU file of 2*L objects: sec. 3.1
+        sqe, _ = orc.sqe_build(p, cfg, ext, fid, L - 1, orc.OP_READ, base, 0)
+        for r in range(n.size):
+            if n[r] == 0:
+                continue
+            last = sqe[int(ext["sqe_base"][r]) + 2 * int(ext["n_chunks"][r]) - 1]
+            assert int(last["kind"]) == 1
+            assert int(last["file_off"]) + int(last["len"]) == 2 * L * int(ext["obj_bytes"][r])
+    # more than one IOCB: 2048 slots each (sec. 3.2)
+    p = _pool(orc, 16, 2, 64, 2, 1 << 16)
+    cfg = orc.make_cfg(4096, 4096, 1)
+    ext, tot = orc.obj_layout(p, cfg, [1500, 1000])
+    sqe, _ = orc.sqe_build(p, cfg, ext, [1, 2], 0, orc.OP_READ, 0, 0)
+    assert sqe.size == 5000 and int(sqe["iocb_idx"][-1]) == 2 and int(sqe["ioctx_slot"][2048]) == 0
+    assert np.array_equal(sqe["iocb_idx"].astype(np.int64) * 2048 + sqe["ioctx_slot"], np.arange(5000))
+
+
+def check_layer_restore(orc, seed=17):
+    """The fused call equals layout + READ entries + unpack done one by one."""
+    rng = np.random.default_rng(seed)
+    T, h, d, e, A, N = 16, 2, 64, 2, 4096, 64
+    bb = T * h * d * e
+    for layout in (0, 1):
+        n = np.array([4, 0, 9, 2], np.uint32)
+        table = rng.permutation(N)[: int(n.sum())].astype(np.uint32)
+        fid = np.array([10, 11, 12, 13], np.uint32)
+        cfg = orc.make_cfg(A, 2 * A, 3)
+        k, v = _planes(rng, N, bb)
+        ka, va = k.copy(), v.copy()
+        pa = _pool(orc, T, h, d, e, N, ka, va, layout=layout)
+        ext, tot = orc.obj_layout(pa, cfg, n)
+        stage = rng.integers(0, 256, size=int(tot[0]), dtype=np.uint8)
+        sqe, _ = orc.sqe_build(pa, cfg, ext, fid, 1, orc.OP_READ, 8192, 5)
+        orc.obj_unpack(pa, cfg, ext, table, stage)
+        kb, vb = k.copy(), v.copy()
+        pb = _pool(orc, T, h, d, e, N, kb, vb, layout=layout)
+        ext2, tot2, sqe2, st = orc.layer_restore(pb, cfg, n, table, fid, 1, stage, 8192, 5, sqe.size)
+        assert st == 0 and np.array_equal(tot, tot2)
+        assert ext.tobytes() == ext2.tobytes() and sqe.tobytes() == sqe2.tobytes()
+        assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+        assert not np.array_equal(ka, k)
+
+
+def check_threaded(orc, seed=19):
+    """The threaded timing helpers produce the single-threaded result."""
+    rng = np.random.default_rng(seed)
+    T, h, d, e, A, N = 16, 2, 64, 2, 4096, 128
+    bb = T * h * d * e
+    for layout in (0, 1):
+        k, v = _planes(rng, N, bb)
+        n = np.array([30, 0, 41, 5], np.uint32)
+        table = rng.permutation(N)[: int(n.sum())].astype(np.uint32)
+        cfg = orc.make_cfg(A, A, 1)
+        p = _pool(orc, T, h, d, e, N, k, v, layout=layout)
+        ext, tot = orc.obj_layout(p, cfg, n)
+        s1 = np.zeros(int(tot[0]), np.uint8)
+        orc.obj_pack(p, cfg, ext, table, s1)
+        for nt in (1, 3, 8):
+            s2 = np.full(int(tot[0]), 0x11, np.uint8)
+            orc.obj_pack(p, cfg, ext, table, s2, n_threads=nt)
+            assert np.array_equal(s1, s2)
+            k2, v2 = np.zeros_like(k), np.zeros_like(v)
+            k3, v3 = np.zeros_like(k), np.zeros_like(v)
+            orc.obj_unpack(_pool(orc, T, h, d, e, N, k2, v2, layout=layout), cfg, ext, table, s1)
+            orc.obj_unpack(_pool(orc, T, h, d, e, N, k3, v3, layout=layout), cfg, ext, table, s1, n_threads=nt)
+            assert np.array_equal(k2, k3) and np.array_equal(v2, v3)
+
+
+ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
+              check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
+              check_sqe_fields, check_layer_restore, check_threaded]

@@ -1,0 +1,86 @@
+"""CPU test of the pins themselves: each plausible mistake, planted in a copy of the oracle's
+source and compiled with gcc, must be caught by at least one check of tests/oracle_checks.py.
+The mistakes are planted in the oracle only, on the CPU; nothing here touches the HIP path."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+import oracle_checks as oc
+
+SRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "tutti_oracle.c")
+
+MUTANTS = {
+    "v_object_overlaps_k": ("stage += 2 * obj;", "stage += obj;"),
+    "entries_counted_once": ("n_sqe += 2 * chunks;", "n_sqe += chunks;"),
+    "align_down": ("return (x + a - 1) / a * a;", "return x / a * a;"),
+    "chunks_floor": ("uint64_t chunks = (obj + C - 1) / C;", "uint64_t chunks = obj / C;"),
+    "table_off_is_request": ("extents[r].table_off = (uint32_t)n_tab;", "extents[r].table_off = r;"),
+    "k_v_planes_swapped": ("kind == 0 ? pool->k_base : pool->v_base", "kind == 1 ? pool->k_base : pool->v_base"),
+    "v_object_at_k": ("uint8_t *obj = stage + x->stage_off + kind * x->obj_bytes;",
+                      "uint8_t *obj = stage + x->stage_off;"),
+    "hnd_ignored": ("? in_obj : ((i * T + t) * d) * e;", "? in_obj : ((t * h + i) * d) * e;"),
+    "hnd_transposed_wrong": ("((i * T + t) * d) * e;", "((i * h + t) * d) * e;"),
+    "stride_ignored": ("plane + (uint64_t)id * pool->block_stride", "plane + (uint64_t)id * bb"),
+    "object_uses_stride": ("obj + (uint64_t)j * bb, to_object", "obj + (uint64_t)j * pool->block_stride, to_object"),
+    "padding_not_zeroed": ("memset(obj + (uint64_t)x->n_blocks * bb, 0,", "if (0) memset(obj + (uint64_t)x->n_blocks * bb, 0,"),
+    "table_offset_dropped": ("uint32_t id = block_table[g];", "uint32_t id = block_table[j];"),
+    "block_bound_off_by_one": ("if (id >= pool->num_blocks) {", "if (id > pool->num_blocks) {"),
+    "unpack_direction": ("(uint8_t *)(uintptr_t)stage, stage_cap, 0, 0,\n             total_blocks",
+                         "(uint8_t *)(uintptr_t)stage, stage_cap, 1, 0,\n             total_blocks"),
+    "file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)"),
+    "file_off_all_k_then_v": ("s.file_off = (2ull * layer + kind) * x->obj_bytes",
+                              "s.file_off = ((uint64_t)kind * cfg->num_layers + layer) * x->obj_bytes"),
+    "addr_without_kind": ("s.addr = stage_addr + x->stage_off + (uint64_t)kind * x->obj_bytes",
+                          "s.addr = stage_addr + x->stage_off"),
+    "len_always_chunk": ("s.len = (uint32_t)(left < C ? left : C);", "s.len = (uint32_t)C;"),
+    "iocb_div_mod_swapped": ("s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);", "s.iocb_idx = (uint32_t)(i % ORC_IOCB_SLOTS);"),
+    "iocb_2000": ("s.ioctx_slot = (uint32_t)(i % ORC_IOCB_SLOTS);", "s.ioctx_slot = (uint32_t)(i % 2000);"),
+    "user_data_swapped": ("s.user_data = ((uint64_t)r << 32) | (uint32_t)i;", "s.user_data = ((uint64_t)i << 32) | r;"),
+    "entries_interleaved": ("(uint64_t)x->sqe_base + (uint64_t)kind * x->n_chunks + c;",
+                            "(uint64_t)x->sqe_base + 2ull * c + kind;"),
+    "file_id_of_first": ("s.file_id = file_id[r];", "s.file_id = file_id[0];"),
+    "rsvd_dirty": ("memset(&s, 0, sizeof s);", "memset(&s, 0xff, sizeof s);"),
+    "cap_check_inclusive": ("if (x->stage_off + 2 * x->obj_bytes > stage_cap) continue;",
+                            "if (x->stage_off + 2 * x->obj_bytes >= stage_cap) continue;"),
+    "restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
+                             "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);"),
+}
+
+
+RUNNER = """
+import ctypes, sys
+sys.path.insert(0, {root!r}); sys.path.insert(0, {tests!r})
+from oracle import tutti_oracle as orc
+import oracle_checks as oc
+lib = ctypes.CDLL({so!r})
+lib.orc_block_bytes.restype = ctypes.c_uint32
+lib.orc_desc_count.restype = ctypes.c_uint64
+lib.orc_desc_count.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+orc._LIB = lib
+for check in oc.ALL_CHECKS:
+    try:
+        check(orc)
+    except (AssertionError, orc.OracleError, IndexError, ValueError):
+        print("caught by", check.__name__)
+        sys.exit(3)
+sys.exit(0)
+"""
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_mutant_is_caught(orc, tmp_path, name):
+    old, new = MUTANTS[name]
+    text = open(SRC).read()
+    assert text.count(old) == 1, f"mutation site for {name} must be unique in the oracle source"
+    src = tmp_path / "mutant.c"
+    src.write_text(text.replace(old, new))
+    so = tmp_path / "libmutant.so"
+    subprocess.run(["gcc", "-std=c11", "-O1", "-w", "-fPIC", "-shared", "-pthread", f"-I{os.path.dirname(SRC)}",
+                    str(src), "-o", str(so)], check=True)
+    # a separate process: a broken oracle may run out of bounds and take the interpreter with it
+    tests = os.path.dirname(os.path.abspath(__file__))
+    code = RUNNER.format(root=os.path.dirname(tests), tests=tests, so=str(so))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0, f"no pin notices the mistake '{name}'"
