@@ -1,0 +1,362 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-layer KV object hot path on ONE MI355X.
+
+A step is one pass of the whole path over the Llama-3-8B-shaped 32K-token workload (config 2):
+for every layer, save (tutti_obj_layout + tutti_obj_pack + tutti_sqe_build(WRITE)), then for every
+layer, restore (tutti_layer_restore: extents + READ entries + unpack in one launch).  Every layer
+has its own K/V planes and its own staging buffer, so each launch touches memory no earlier launch
+left in the 256 MB Infinity Cache.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+  value            payload GB/s of the whole step (bytes packed + bytes restored, 1 GB = 1e9 B)
+  roofline         the dominant kernel (k_restore: the unpack) against the 8 TB/s HBM peak,
+                   timed with events on the launch stream inside the timed region
+  cpu_baseline     the CPU oracle, as it stands, on one layer of the same workload
+Extra legs (same JSON line): restore / pack alone, a plain-copy ceiling, entries built per second,
+and with --corun the CU-budget sweep beside a bf16 4096^3 GEMM (config 5).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def median(xs):
+    return float(np.median(np.asarray(xs, dtype=np.float64)))
+
+
+def read_traffic_note():
+    """HBM bytes per k_restore launch measured with rocprofv3 --pmc (profiles/), if recorded."""
+    path = os.path.join(ROOT, "profiles", "k_restore_llama8b_32k_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=0, help="layers resident (0 = all 32 if memory allows)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the copy-ceiling / entry-rate legs")
+    ap.add_argument("--corun", action="store_true", help="also run the CU-budget sweep beside a GEMM (config 5)")
+    ap.add_argument("--wgs-per-cu", type=int, default=0)
+    ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--plain-loads", action="store_true", help="disable non-temporal loads/stores")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this path has no collective and no cross-GPU step; "
+              "run it with --gpus 1 (each GPU of a larger job would run exactly this on its own shard)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2605_03375_amd import binding as B
+    from paper_2605_03375_amd import workloads as W
+
+    B.lib()  # no fallback: raises if libtutti.so is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    B.tutti_set_tuning(args.wgs_per_cu, args.unroll)
+    B.tutti_set_nontemporal(0 if args.plain_loads else 1)
+
+    w = W.llama8b_32k()
+    s = w.shape
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    plane_bytes = s.num_blocks * bb
+    n_tab = int(w.block_table.size)
+    payload_layer = 2 * n_tab * bb                       # K + V bytes of one layer's hit blocks
+    n_sqe_layer = 2 * ((n_tab * bb + w.chunk_bytes - 1) // w.chunk_bytes)
+    free, total = torch.cuda.mem_get_info()
+    per_layer = 2 * plane_bytes + payload_layer
+    fit = int((free - (6 << 30)) // per_layer)
+    L = min(s.num_layers, fit) if args.layers == 0 else min(args.layers, s.num_layers, fit)
+    if L < 1:
+        raise SystemExit("not enough free HBM for even one layer of the pool")
+    log(f"[bench] {w.name}: {L}/{s.num_layers} layers resident, {plane_bytes >> 20} MiB per plane, "
+        f"{payload_layer >> 20} MiB payload per layer, free HBM {free >> 30} GiB")
+
+    geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
+                head_dim=s.head_dim, elt_bytes=s.elt_bytes)
+    cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
+    t0 = time.time()
+    planes = []
+    for l in range(L):
+        k = W.device_values(W.seed_for(2, l), plane_bytes // 2, s.dtype, dev).view(torch.uint8)
+        v = W.device_values(W.seed_for(2, l) + 500, plane_bytes // 2, s.dtype, dev).view(torch.uint8)
+        planes.append((k, v))
+        if l % 8 == 7 or l == L - 1:
+            torch.cuda.synchronize()
+            log(f"[bench] filled {l + 1}/{L} layers ({time.time() - t0:.1f} s)")
+    pools = [B.make_pool(k, v, **geom) for k, v in planes]
+    stages = [torch.zeros(payload_layer, dtype=torch.uint8, device=dev) for _ in range(L)]
+    d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
+    d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
+    d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
+    ext_w = torch.zeros(L, 32, dtype=torch.uint8, device=dev)
+    ext_r = torch.zeros(L, 32, dtype=torch.uint8, device=dev)
+    tot_w = torch.zeros(L, 2, dtype=torch.int64, device=dev)
+    tot_r = torch.zeros(L, 2, dtype=torch.int64, device=dev)
+    wsqe = torch.zeros(L, n_sqe_layer * 64, dtype=torch.uint8, device=dev)
+    rsqe = torch.zeros(L, n_sqe_layer * 64, dtype=torch.uint8, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    sgl_id = 1
+    stream = torch.cuda.current_stream()
+
+    def save_layers():
+        for l in range(L):
+            B.tutti_obj_layout(pools[l], cfg, d_n, 1, ext_w[l], tot_w[l], stream)
+            B.tutti_obj_pack(pools[l], cfg, ext_w[l], 1, d_tab, n_tab, stages[l], payload_layer, 0, status, stream)
+            B.tutti_sqe_build(pools[l], cfg, ext_w[l], 1, d_fid, l, B.OP_WRITE, stages[l].data_ptr(), sgl_id,
+                              wsqe[l], n_sqe_layer, status, stream)
+
+    def restore_layers(budget=0):
+        for l in range(L):
+            B.tutti_layer_restore(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload_layer,
+                                  stages[l].data_ptr(), sgl_id, ext_r[l], tot_r[l], rsqe[l], n_sqe_layer, budget,
+                                  status, stream)
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731  (events of torch's current stream = launch stream)
+
+    for _ in range(args.warmup):
+        save_layers()
+        restore_layers()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps
+    marks = []
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record(stream)
+        save_layers()
+        e1.record(stream)
+        restore_layers()
+        e2.record(stream)
+        marks.append((e0, e1, e2))
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ms_per_step = (t_end - t_begin) * 1e3 / args.steps
+    save_ms = [a.elapsed_time(b) for a, b, _ in marks]
+    rest_ms = [b.elapsed_time(c) for _, b, c in marks]
+    assert int(status.item()) == 0, f"device status word {int(status.item())}: a block or capacity check tripped"
+
+    step_payload = 2 * L * payload_layer                 # packed + restored
+    value = step_payload / (ms_per_step * 1e-3) / 1e9
+    restore_us = float(np.mean(rest_ms)) * 1e3 / L       # average k_restore launch, launch gaps included
+    save_us = float(np.mean(save_ms)) * 1e3 / L
+    # algorithmic bytes of one k_restore launch: payload read + payload written, the block table,
+    # the request counts and file ids, the entries and extents it writes
+    restore_alg_bytes = 2 * payload_layer + 4 * n_tab + 4 * w.n_req * 2 + 64 * n_sqe_layer + 32 * w.n_req + 16
+    achieved = restore_alg_bytes / (restore_us * 1e-6) / 1e9
+
+    out = {
+        "metric": "per-layer KV save+restore payload GB/s, Llama-3-8B shape, 32K-token prefix (pack + one-launch restore)",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "config 2: llama8b_32k (bf16 KV, block 16, 8 KV heads x 128, 65536-block pool per "
+                               "layer, one 32K-token prefix = 2048 shuffled blocks, 2 MiB chunks)",
+                   "layers_resident": L, "layers_model": s.num_layers, "payload_bytes_per_layer": payload_layer,
+                   "step": "per layer: layout + pack + WRITE entries; then per layer: layer_restore",
+                   "wgs_per_cu": args.wgs_per_cu, "unroll": args.unroll, "nontemporal": not args.plain_loads},
+        "roofline": {"bound": "hbm", "kernel": "k_restore", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
+                     "algorithmic_bytes_per_launch": restore_alg_bytes, "avg_launch_us": round(restore_us, 2)},
+        "restore": {"us_per_layer": round(restore_us, 2),
+                    "payload_GBps": round(payload_layer / (restore_us * 1e-6) / 1e9, 1),
+                    "traffic_GBps": round(2 * payload_layer / (restore_us * 1e-6) / 1e9, 1),
+                    "pct_hbm_peak": round(100 * 2 * payload_layer / (restore_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+                    "median_train_ms": round(median(rest_ms), 4), "min_train_ms": round(min(rest_ms), 4)},
+        "save": {"us_per_layer": round(save_us, 2),
+                 "payload_GBps": round(payload_layer / (save_us * 1e-6) / 1e9, 1),
+                 "traffic_GBps": round(2 * payload_layer / (save_us * 1e-6) / 1e9, 1),
+                 "launches_per_layer": 3},
+    }
+    log(f"[bench] step {ms_per_step:.3f} ms, restore {restore_us:.1f} us/layer "
+        f"({out['restore']['traffic_GBps']} GB/s traffic, {out['restore']['pct_hbm_peak']} % of peak), "
+        f"save {save_us:.1f} us/layer")
+
+    if not args.no_extra:
+        out["copy_ceiling"] = copy_ceiling(torch, B, stages, payload_layer, dev)
+        out["copy_ceiling"]["restore_vs_copy"] = round(out["restore"]["traffic_GBps"] /
+                                                       out["copy_ceiling"]["traffic_GBps"], 4)
+        out["sqe"] = sqe_rate(torch, B, W, dev)
+        log(f"[bench] copy ceiling {out['copy_ceiling']}; entries {out['sqe']}")
+    if args.corun:
+        out["corun"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], stages[0], geom, payload_layer)
+    print(json.dumps(out), flush=True)
+
+
+def copy_ceiling(torch, B, stages, nbytes, dev, reps=5):
+    """Same-size contiguous copy with the same access shape, rotating over cold sources."""
+    dsts = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(4)]
+    for i, s in enumerate(stages):
+        B.tutti_copy_baseline(dsts[i % 4], s, nbytes)
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i, s in enumerate(stages):
+            B.tutti_copy_baseline(dsts[i % 4], s, nbytes)
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) * 1e3 / len(stages))
+    us = median(times)
+    return {"bytes": nbytes, "us_per_copy": round(us, 2), "traffic_GBps": round(2 * nbytes / (us * 1e-6) / 1e9, 1),
+            "pct_hbm_peak": round(100 * 2 * nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
+
+
+def sqe_rate(torch, B, W, dev, reps=50):
+    """Entries built per second on config 3's batch of 64 requests, per-chunk and per-block."""
+    res = {}
+    for label, chunk in (("chunk_2MiB", 2 << 20), ("per_block_32KiB", 32768)):
+        w = W.batch64_zipf(chunk_bytes=chunk)
+        s = w.shape
+        geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
+                    head_dim=s.head_dim, elt_bytes=s.elt_bytes)
+        pool = B.make_pool(4096, 4096, **geom)  # entries are arithmetic only: the planes are never touched
+        cfg = B.make_cfg(w.align, chunk, s.num_layers)
+        d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
+        d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
+        ext = torch.zeros(w.n_req * 32, dtype=torch.uint8, device=dev)
+        tot = torch.zeros(2, dtype=torch.int64, device=dev)
+        B.tutti_obj_layout(pool, cfg, d_n, w.n_req, ext, tot)
+        torch.cuda.synchronize()
+        n_sqe = int(tot[1].item())
+        sqe = torch.zeros(n_sqe * 64, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            B.tutti_sqe_build(pool, cfg, ext, w.n_req, d_fid, 3, B.OP_READ, 1 << 40, 1, sqe, n_sqe)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            B.tutti_sqe_build(pool, cfg, ext, w.n_req, d_fid, i % s.num_layers, B.OP_READ, 1 << 40, 1, sqe, n_sqe)
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / reps
+        res[label] = {"entries_per_layer": n_sqe, "us_per_launch": round(us, 2),
+                      "sqes_per_s": round(n_sqe / (us * 1e-6), 0),
+                      "regime": "launch-latency bound" if us < 20 else "HBM-write bound"}
+    return res
+
+
+def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=100):
+    """Config 5: restore under a CU budget on one stream while a bf16 4096^3 GEMM loops on another."""
+    a = torch.randn(4096, 4096, dtype=torch.bfloat16, device=dev)
+    b = torch.randn(4096, 4096, dtype=torch.bfloat16, device=dev)
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+
+    def time_gemm(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            e0.record(side)
+            for _ in range(n):
+                torch.matmul(a, b)
+            e1.record(side)
+        return e0, e1
+
+    def time_restore(budget, trains):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(main)
+        for _ in range(trains):
+            restore_layers(budget)
+        e1.record(main)
+        return e0, e1
+
+    for _ in range(3):
+        g0, g1 = time_gemm(10)
+    torch.cuda.synchronize()
+    out = {}
+    for budget in (8, 16, 32, 64, 0):
+        rows = []
+        for _ in range(3):  # interleave solo / co-run
+            g0, g1 = time_gemm(gemm_iters)
+            torch.cuda.synchronize()
+            gemm_solo = g0.elapsed_time(g1) / gemm_iters
+            r0, r1 = time_restore(budget, 1)
+            torch.cuda.synchronize()
+            rest_solo = r0.elapsed_time(r1) / L
+            trains = max(1, int(round(gemm_solo * gemm_iters / (rest_solo * L))))
+            side.wait_stream(main)
+            g0, g1 = time_gemm(gemm_iters)
+            r0, r1 = time_restore(budget, trains)
+            torch.cuda.synchronize()
+            rows.append((gemm_solo, g0.elapsed_time(g1) / gemm_iters, rest_solo, r0.elapsed_time(r1) / (L * trains)))
+        gs, gc, rs, rc = (median([r[i] for r in rows]) for i in range(4))
+        out[str(budget)] = {"gemm_ms_solo": round(gs, 4), "gemm_ms_corun": round(gc, 4),
+                            "gemm_slowdown": round(gc / gs, 3),
+                            "restore_payload_GBps_solo": round(payload_layer / (rs * 1e-3) / 1e9, 1),
+                            "restore_payload_GBps_corun": round(payload_layer / (rc * 1e-3) / 1e9, 1)}
+        log(f"[bench] corun budget {budget}: {out[str(budget)]}")
+    return out
+
+
+def cpu_baseline(torch, W, w, plane0, stage0, geom, payload_layer, budget_s=8.0):
+    """The CPU oracle on layer 0 of the same workload: pack + restore of its 2048 blocks, on host
+    copies of exactly the bytes the GPU used; single thread, then all cores of the affinity mask.
+    Also a free full-size parity check: the GPU's staging buffer of layer 0 must equal the oracle's."""
+    from oracle import tutti_oracle as orc
+    k_host, v_host = plane0[0].cpu().numpy(), plane0[1].cpu().numpy()
+    gpu_stage = stage0.cpu().numpy()
+    pool = orc.make_pool(k_host, v_host, **geom)
+    cfg = orc.make_cfg(w.align, w.chunk_bytes, w.shape.num_layers)
+    ext, tot = orc.obj_layout(pool, cfg, w.n_blocks)
+    stage = np.zeros(int(tot[0]), np.uint8)
+    cores = min(len(os.sched_getaffinity(0)), 16)
+
+    def one_pass(nt):
+        t = time.perf_counter()
+        orc.obj_pack(pool, cfg, ext, w.block_table, stage, n_threads=nt)
+        if nt:
+            orc.obj_unpack(pool, cfg, ext, w.block_table, stage, n_threads=nt)
+        else:
+            orc.layer_restore(pool, cfg, w.n_blocks, w.block_table, w.file_id, 0, stage, 0, 1, int(tot[1]))
+        return time.perf_counter() - t
+
+    res = {}
+    for label, nt in (("1thread", 0), ("allcores", cores)):
+        one_pass(nt)
+        times, t_start = [], time.perf_counter()
+        while len(times) < 5 or (time.perf_counter() - t_start < budget_s and len(times) < 200):
+            times.append(one_pass(nt))
+        res[label] = (2 * payload_layer / median(times) / 1e9, len(times))
+    parity = bool(np.array_equal(stage, gpu_stage))
+    log(f"[bench] oracle: 1 thread {res['1thread'][0]:.2f} GB/s, {cores} threads {res['allcores'][0]:.2f} GB/s; "
+        f"GPU staging buffer of layer 0 equals the oracle's: {parity}")
+    assert parity, "GPU-packed layer 0 differs from the CPU oracle"
+    return {"value": round(res["allcores"][0], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "value_1thread": round(res["1thread"][0], 3),
+            "sample": f"layer 0 of config 2 (2048 blocks, {payload_layer >> 20} MiB packed + {payload_layer >> 20} MiB "
+                      f"restored per pass), median of {res['allcores'][1]} passes with {cores} threads "
+                      f"({res['1thread'][1]} passes single-threaded)"}
+
+
+if __name__ == "__main__":
+    main()

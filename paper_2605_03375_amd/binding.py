@@ -1,0 +1,206 @@
+"""ctypes binding of libtutti (include/tutti.h): argument marshalling only.
+
+Every function has the name and argument order of its C entry point; device pointers may be
+given as torch tensors (their data_ptr() is taken) or as integers.  `stream=None` means
+torch's current stream.  A non-zero return code raises TuttiError.  There is no fallback:
+if the HIP library has not been built, `lib()` raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtutti.so")
+_LIB = None
+
+OK, EINVAL, ERANGE, EHIP = 0, -1, -2, -3
+LAYOUT_NHD, LAYOUT_HND = 0, 1
+OP_READ, OP_WRITE = 1, 2
+IOCB_SLOTS = 2048
+MAX_REQ = 2048
+ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP = 1, 2, 4
+
+# Declarations of the C records for decoding results on the host.
+EXTENT_DTYPE = np.dtype({"names": ["stage_off", "obj_bytes", "n_blocks", "n_chunks", "sqe_base", "table_off"],
+                         "formats": ["<u8", "<u8", "<u4", "<u4", "<u4", "<u4"],
+                         "offsets": [0, 8, 16, 20, 24, 28], "itemsize": 32})
+SQE_DTYPE = np.dtype({"names": ["opcode", "kind", "layer", "file_id", "file_off", "addr", "len", "sgl_id",
+                                "user_data", "iocb_idx", "ioctx_slot", "rsvd"],
+                      "formats": ["u1", "u1", "<u2", "<u4", "<u8", "<u8", "<u4", "<u4", "<u8", "<u4", "<u4",
+                                  ("u1", (16,))],
+                      "offsets": [0, 1, 2, 4, 8, 16, 24, 28, 32, 40, 44, 48], "itemsize": 64})
+
+EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
+           "tutti_copy_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
+           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal"]
+
+
+class tutti_pool(C.Structure):
+    _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("block_stride", C.c_uint64),
+                ("num_blocks", C.c_uint32), ("block_tokens", C.c_uint32), ("num_kv_heads", C.c_uint32),
+                ("head_dim", C.c_uint32), ("elt_bytes", C.c_uint32), ("pool_layout", C.c_uint32)]
+
+
+class tutti_objcfg(C.Structure):
+    _fields_ = [("align", C.c_uint32), ("chunk_bytes", C.c_uint32), ("num_layers", C.c_uint32)]
+
+
+class TuttiError(RuntimeError):
+    def __init__(self, fn, code):
+        self.fn, self.code = fn, code
+        msg = lib().tutti_strerror(code).decode()
+        hip = lib().tutti_last_hip_error() if code == EHIP else 0
+        super().__init__(f"{fn}: {msg} (code {code}" + (f", hipError {hip})" if hip else ")"))
+
+
+def lib():
+    """The loaded HIP library.  Raises if it has not been built: there is no other path."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_03375_amd.build` "
+                               "(or __graft_entry__.build()); libtutti has no CPU fallback")
+        # PyTorch ships its own HIP runtime (same soname as the system one).  Import it first so
+        # that libtutti binds to the runtime that owns the process's device context and streams;
+        # two HIP runtimes in one process do not share a device.
+        import torch  # noqa: F401
+        L = C.CDLL(LIB_PATH)
+        vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
+        pp, pc = C.POINTER(tutti_pool), C.POINTER(tutti_objcfg)
+        L.tutti_obj_layout.argtypes = [pp, pc, vp, u32, vp, vp, vp]
+        L.tutti_obj_pack.argtypes = [pp, pc, vp, u32, vp, u32, vp, u64, u32, vp, vp]
+        L.tutti_obj_unpack.argtypes = [pp, pc, vp, u32, vp, u32, vp, u64, u32, vp, vp]
+        L.tutti_sqe_build.argtypes = [pp, pc, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
+        L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
+                                          vp, vp]
+        L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
+        L.tutti_strerror.argtypes = [C.c_int]
+        L.tutti_strerror.restype = C.c_char_p
+        L.tutti_version.restype = u32
+        L.tutti_abi_describe.argtypes = [vp, u32]
+        L.tutti_set_tuning.argtypes = [u32, u32]
+        L.tutti_set_nontemporal.argtypes = [u32]
+        for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
+                     "tutti_layer_restore", "tutti_copy_baseline", "tutti_last_hip_error", "tutti_cu_count",
+                     "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal"):
+            getattr(L, name).restype = C.c_int
+        _LIB = L
+    return _LIB
+
+
+def _p(x):
+    """Device (or host) pointer of a tensor / array / int / None, as c_void_p."""
+    if x is None:
+        return C.c_void_p(0)
+    if hasattr(x, "data_ptr"):
+        return C.c_void_p(x.data_ptr())
+    if isinstance(x, np.ndarray):
+        return C.c_void_p(x.ctypes.data)
+    return C.c_void_p(int(x))
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if hasattr(stream, "cuda_stream"):
+        return C.c_void_p(stream.cuda_stream)
+    return C.c_void_p(int(stream))
+
+
+def _check(fn, rc):
+    if rc != OK:
+        raise TuttiError(fn, rc)
+    return rc
+
+
+def make_pool(k_base, v_base, *, num_blocks, block_tokens, num_kv_heads, head_dim, elt_bytes, block_stride=None,
+              pool_layout=LAYOUT_NHD):
+    p = tutti_pool()
+    p.k_base, p.v_base = _p(k_base), _p(v_base)
+    p.block_stride = (block_tokens * num_kv_heads * head_dim * elt_bytes) if block_stride is None else block_stride
+    p.num_blocks, p.block_tokens, p.num_kv_heads = num_blocks, block_tokens, num_kv_heads
+    p.head_dim, p.elt_bytes, p.pool_layout = head_dim, elt_bytes, pool_layout
+    p._keep = (k_base, v_base)
+    return p
+
+
+def make_cfg(align=4096, chunk_bytes=2 << 20, num_layers=1):
+    return tutti_objcfg(align, chunk_bytes, num_layers)
+
+
+def tutti_obj_layout(pool, cfg, d_n_blocks, n_req, d_extents, d_totals, stream=None):
+    return _check("tutti_obj_layout", lib().tutti_obj_layout(C.byref(pool), C.byref(cfg), _p(d_n_blocks), n_req,
+                                                             _p(d_extents), _p(d_totals), _stream(stream)))
+
+
+def tutti_obj_pack(pool, cfg, d_extents, n_req, d_block_table, table_len, d_stage, stage_cap, cu_budget=0,
+                   d_status=None, stream=None):
+    return _check("tutti_obj_pack", lib().tutti_obj_pack(C.byref(pool), C.byref(cfg), _p(d_extents), n_req,
+                                                         _p(d_block_table), table_len, _p(d_stage), stage_cap,
+                                                         cu_budget, _p(d_status), _stream(stream)))
+
+
+def tutti_obj_unpack(pool, cfg, d_extents, n_req, d_block_table, table_len, d_stage, stage_cap, cu_budget=0,
+                     d_status=None, stream=None):
+    return _check("tutti_obj_unpack", lib().tutti_obj_unpack(C.byref(pool), C.byref(cfg), _p(d_extents), n_req,
+                                                             _p(d_block_table), table_len, _p(d_stage), stage_cap,
+                                                             cu_budget, _p(d_status), _stream(stream)))
+
+
+def tutti_sqe_build(pool, cfg, d_extents, n_req, d_file_id, layer, opcode, stage_addr, sgl_id, d_sqe, sqe_cap,
+                    d_status=None, stream=None):
+    return _check("tutti_sqe_build", lib().tutti_sqe_build(C.byref(pool), C.byref(cfg), _p(d_extents), n_req,
+                                                           _p(d_file_id), layer, opcode, stage_addr, sgl_id,
+                                                           _p(d_sqe), sqe_cap, _p(d_status), _stream(stream)))
+
+
+def tutti_layer_restore(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage,
+                        stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, cu_budget=0,
+                        d_status=None, stream=None):
+    return _check("tutti_layer_restore",
+                  lib().tutti_layer_restore(C.byref(pool), C.byref(cfg), _p(d_n_blocks), n_req, _p(d_block_table),
+                                            table_len, _p(d_file_id), layer, _p(d_stage), stage_cap, stage_addr,
+                                            sgl_id, _p(d_extents), _p(d_totals), _p(d_sqe), sqe_cap, cu_budget,
+                                            _p(d_status), _stream(stream)))
+
+
+def tutti_copy_baseline(d_dst, d_src, nbytes, cu_budget=0, stream=None):
+    return _check("tutti_copy_baseline", lib().tutti_copy_baseline(_p(d_dst), _p(d_src), nbytes, cu_budget,
+                                                                   _stream(stream)))
+
+
+def tutti_strerror(code):
+    return lib().tutti_strerror(code).decode()
+
+
+def tutti_last_hip_error():
+    return lib().tutti_last_hip_error()
+
+
+def tutti_cu_count():
+    n = lib().tutti_cu_count()
+    if n < 0:
+        raise TuttiError("tutti_cu_count", n)
+    return n
+
+
+def tutti_version():
+    return lib().tutti_version()
+
+
+def tutti_abi_describe():
+    out = np.zeros(64, np.uint32)
+    n = lib().tutti_abi_describe(_p(out), out.size)
+    if n < 0:
+        raise TuttiError("tutti_abi_describe", n)
+    return out[:n].tolist()
+
+
+def tutti_set_tuning(wgs_per_cu=0, unroll=0):
+    return _check("tutti_set_tuning", lib().tutti_set_tuning(wgs_per_cu, unroll))
+
+
+def tutti_set_nontemporal(on=1):
+    return _check("tutti_set_nontemporal", lib().tutti_set_nontemporal(1 if on else 0))

@@ -1,0 +1,35 @@
+"""Compile libtutti (HIP, gfx950) in-tree: paper_2605_03375_amd/libtutti.so.
+
+hipcc cross-compiles without a GPU.  `python -m paper_2605_03375_amd.build` or `build_lib()`.
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libtutti.so")
+SOURCES = [os.path.join(CSRC, "tutti_api.hip")]
+DEPS = SOURCES + [os.path.join(CSRC, "tutti_kernels.hip.h"), os.path.join(ROOT, "include", "tutti.h")]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
+    # no packed-fp32 instructions in any HIP code of this repository
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+]
+
+
+def build_lib(force: bool = True, verbose: bool = False) -> str:
+    if not force and os.path.exists(LIB):
+        if os.path.getmtime(LIB) >= max(os.path.getmtime(p) for p in DEPS):
+            return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, f"-I{os.path.join(ROOT, 'include')}", f"-I{CSRC}", *SOURCES, "-o", LIB]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True, cwd=ROOT)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_lib(force=True, verbose=True))

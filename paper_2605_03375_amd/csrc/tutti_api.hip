@@ -1,0 +1,438 @@
+// Host side of libtutti: the C ABI declared in include/tutti.h.
+//
+// Each entry point checks its host arguments in O(1), fills a small argument struct and
+// enqueues a constant number of kernels on the caller's stream.  No allocation, no
+// synchronisation, no device-to-host copy.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+
+#include "tutti.h"
+#include "tutti_kernels.hip.h"
+
+namespace {
+
+using namespace tutti;
+
+thread_local int t_last_hip = 0;
+
+std::atomic<uint32_t> g_wgs_per_cu{0};
+std::atomic<uint32_t> g_unroll{0};
+std::atomic<uint32_t> g_nontemporal{1};
+
+constexpr uint32_t kDefaultWgsPerCu = 8;  // 32 wavefronts per CU
+constexpr uint32_t kDefaultUnroll = 4;    // 4 x 16 B in flight per lane: 4 KiB slices
+constexpr int kMaxDevices = 64;
+
+std::atomic<int> g_cu_count[kMaxDevices];
+
+int hip_fail(hipError_t e) {
+  t_last_hip = static_cast<int>(e);
+  return TUTTI_EHIP;
+}
+
+// Compute units of the current device (queried once per device).
+int cu_count() {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return TUTTI_ERANGE;
+  int n = g_cu_count[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (n <= 0) return TUTTI_ERANGE;
+  g_cu_count[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
+bool is_pow2(uint32_t x) { return x != 0 && (x & (x - 1)) == 0; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Geometry checks shared by every entry point; *block_bytes = T*h*d*e.
+int check_geometry(const tutti_pool *pool, const tutti_objcfg *cfg, uint32_t *block_bytes) {
+  if (!pool || !cfg) return TUTTI_EINVAL;
+  uint64_t b = pool->block_tokens;
+  b *= pool->num_kv_heads;
+  if (b > 0xffffffffull) return TUTTI_EINVAL;
+  b *= pool->head_dim;
+  if (b > 0xffffffffull) return TUTTI_EINVAL;
+  b *= pool->elt_bytes;
+  if (b == 0 || b > 0xffffffffull || b % 16 != 0) return TUTTI_EINVAL;
+  if (pool->num_blocks == 0) return TUTTI_EINVAL;
+  if (pool->block_stride < b || pool->block_stride % 16 != 0) return TUTTI_EINVAL;
+  if (pool->pool_layout != TUTTI_LAYOUT_NHD && pool->pool_layout != TUTTI_LAYOUT_HND) return TUTTI_EINVAL;
+  if (!is_pow2(cfg->align) || cfg->align < 16) return TUTTI_EINVAL;
+  if (cfg->chunk_bytes == 0 || cfg->chunk_bytes % cfg->align != 0) return TUTTI_EINVAL;
+  if (cfg->num_layers == 0 || cfg->num_layers > 65536u) return TUTTI_EINVAL;
+  *block_bytes = static_cast<uint32_t>(b);
+  return TUTTI_OK;
+}
+
+int check_planes(const tutti_pool *pool) {
+  if (!pool->k_base || !pool->v_base || !aligned16(pool->k_base) || !aligned16(pool->v_base)) return TUTTI_EINVAL;
+  if (pool->pool_layout == TUTTI_LAYOUT_HND) {
+    // a head-major row (d*e bytes) must hold whole 16-byte units
+    const uint64_t row = static_cast<uint64_t>(pool->head_dim) * pool->elt_bytes;
+    if (row % 16 != 0) return TUTTI_EINVAL;
+  }
+  return TUTTI_OK;
+}
+
+struct Launch {
+  uint32_t grid;
+  uint32_t unroll;
+  bool nontemporal;
+};
+
+// Grid of persistent workgroups: enough for every item to have its own wavefront, capped by
+// the CU budget (0 = all CUs) times the workgroups kept resident per CU.
+int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  if (cu_budget > static_cast<uint32_t>(cus)) return TUTTI_ERANGE;
+  const uint32_t budget = cu_budget ? cu_budget : static_cast<uint32_t>(cus);
+  uint32_t per_cu = g_wgs_per_cu.load(std::memory_order_relaxed);
+  if (per_cu == 0) per_cu = kDefaultWgsPerCu;
+  uint64_t cap = static_cast<uint64_t>(budget) * per_cu;
+  uint64_t need = (n_wave_items + kWgWaves - 1) / kWgWaves;
+  if (need == 0) need = 1;
+  out->grid = static_cast<uint32_t>(need < cap ? need : cap);
+  uint32_t u = g_unroll.load(std::memory_order_relaxed);
+  out->unroll = u ? u : kDefaultUnroll;
+  out->nontemporal = g_nontemporal.load(std::memory_order_relaxed) != 0;
+  return TUTTI_OK;
+}
+
+int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t *d_block_table, uint32_t table_len,
+                   const void *d_stage, uint64_t stage_cap, uint32_t *d_status, uint32_t unroll, MoveArgs *m) {
+  const uint32_t slice = kWave * 16u * unroll;
+  m->k_base = static_cast<unsigned char *>(pool->k_base);
+  m->v_base = static_cast<unsigned char *>(pool->v_base);
+  m->stage = static_cast<unsigned char *>(const_cast<void *>(d_stage));
+  m->table = d_block_table;
+  m->status = d_status;
+  m->block_stride = pool->block_stride;
+  m->stage_cap = stage_cap;
+  m->num_blocks = pool->num_blocks;
+  m->block_bytes = block_bytes;
+  m->table_len = table_len;
+  m->slices_per_block = static_cast<uint32_t>((static_cast<uint64_t>(block_bytes) + slice - 1) / slice);
+  m->row_bytes = pool->head_dim * pool->elt_bytes;
+  m->block_tokens = pool->block_tokens;
+  m->num_kv_heads = pool->num_kv_heads;
+  // the kernels number work items in 32 bits
+  if (2ull * table_len * m->slices_per_block > 0xffffffffull) return TUTTI_ERANGE;
+  return TUTTI_OK;
+}
+
+template <int DIR, bool HND>
+hipError_t launch_move(const Launch &L, uint32_t lds, hipStream_t s, const MoveArgs &m, const tutti_extent *ext,
+                       uint32_t n_req) {
+#define TUTTI_MOVE_CASE(U)                                                                             \
+  case U:                                                                                              \
+    if (L.nontemporal)                                                                                 \
+      hipLaunchKernelGGL((k_move<DIR, HND, U, true>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext, n_req);  \
+    else                                                                                               \
+      hipLaunchKernelGGL((k_move<DIR, HND, U, false>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext, n_req); \
+    break;
+  switch (L.unroll) {
+    TUTTI_MOVE_CASE(1)
+    TUTTI_MOVE_CASE(2)
+    TUTTI_MOVE_CASE(4)
+    TUTTI_MOVE_CASE(8)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef TUTTI_MOVE_CASE
+  return hipGetLastError();
+}
+
+template <bool HND>
+hipError_t launch_restore(const Launch &L, uint32_t lds, hipStream_t s, const MoveArgs &m, const SqeArgs &q,
+                          const LayoutArgs &a) {
+#define TUTTI_RESTORE_CASE(U)                                                                       \
+  case U:                                                                                           \
+    if (L.nontemporal)                                                                              \
+      hipLaunchKernelGGL((k_restore<HND, U, true>), dim3(L.grid), dim3(kWgThreads), lds, s, m, q, a);  \
+    else                                                                                            \
+      hipLaunchKernelGGL((k_restore<HND, U, false>), dim3(L.grid), dim3(kWgThreads), lds, s, m, q, a); \
+    break;
+  switch (L.unroll) {
+    TUTTI_RESTORE_CASE(1)
+    TUTTI_RESTORE_CASE(2)
+    TUTTI_RESTORE_CASE(4)
+    TUTTI_RESTORE_CASE(8)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef TUTTI_RESTORE_CASE
+  return hipGetLastError();
+}
+
+template <int DIR>
+int move_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+               const uint32_t *d_block_table, uint32_t table_len, const void *d_stage, uint64_t stage_cap,
+               uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  uint32_t bb = 0;
+  int rc = check_geometry(pool, cfg, &bb);
+  if (rc) return rc;
+  rc = check_planes(pool);
+  if (rc) return rc;
+  if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
+  if (n_req > 0 && !d_extents) return TUTTI_EINVAL;
+  if (table_len > 0 && !d_block_table) return TUTTI_EINVAL;
+  if (!d_stage && (stage_cap > 0 || table_len > 0)) return TUTTI_EINVAL;
+  if (!aligned16(d_stage)) return TUTTI_EINVAL;
+  if (n_req == 0 || table_len == 0) return TUTTI_OK;  // nothing to move
+  Launch L;
+  // the unroll decides the slice size, so read the tuning before sizing the grid
+  rc = plan_launch(cu_budget, 0, &L);
+  if (rc) return rc;
+  MoveArgs m;
+  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, L.unroll, &m);
+  if (rc) return rc;
+  rc = plan_launch(cu_budget, 2ull * table_len * m.slices_per_block, &L);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint32_t lds = req_lds_bytes(n_req);
+  hipError_t e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_move<DIR, true>(L, lds, s, m, d_extents, n_req)
+                                                          : launch_move<DIR, false>(L, lds, s, m, d_extents, n_req);
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int tutti_obj_layout(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                     tutti_extent *d_extents, uint64_t *d_totals, void *stream) {
+  uint32_t bb = 0;
+  int rc = check_geometry(pool, cfg, &bb);
+  if (rc) return rc;
+  if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
+  if (!d_totals || (n_req > 0 && (!d_n_blocks || !d_extents))) return TUTTI_EINVAL;
+  LayoutArgs a;
+  a.n_blocks = d_n_blocks;
+  a.extents = d_extents;
+  a.totals = d_totals;
+  a.geom = ScanGeom{bb, cfg->align, cfg->chunk_bytes};
+  a.n_req = n_req;
+  hipLaunchKernelGGL(k_layout, dim3(1), dim3(kWave), req_lds_bytes(n_req), static_cast<hipStream_t>(stream), a);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_obj_pack(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                   const uint32_t *d_block_table, uint32_t table_len, void *d_stage, uint64_t stage_cap,
+                   uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  return move_entry<kPack>(pool, cfg, d_extents, n_req, d_block_table, table_len, d_stage, stage_cap, cu_budget,
+                           d_status, stream);
+}
+
+int tutti_obj_unpack(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                     const uint32_t *d_block_table, uint32_t table_len, const void *d_stage, uint64_t stage_cap,
+                     uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  return move_entry<kUnpack>(pool, cfg, d_extents, n_req, d_block_table, table_len, d_stage, stage_cap, cu_budget,
+                             d_status, stream);
+}
+
+int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                    const uint32_t *d_file_id, uint32_t layer, uint32_t opcode, uint64_t stage_addr, uint32_t sgl_id,
+                    tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t *d_status, void *stream) {
+  uint32_t bb = 0;
+  int rc = check_geometry(pool, cfg, &bb);
+  if (rc) return rc;
+  if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
+  if (n_req > 0 && (!d_extents || !d_file_id)) return TUTTI_EINVAL;
+  if (sqe_cap > 0 && (!d_sqe || !aligned16(d_sqe))) return TUTTI_EINVAL;
+  if (opcode != TUTTI_OP_READ && opcode != TUTTI_OP_WRITE) return TUTTI_EINVAL;
+  if (layer >= cfg->num_layers) return TUTTI_EINVAL;
+  if (stage_addr % cfg->align != 0) return TUTTI_EINVAL;
+  if (n_req == 0) return TUTTI_OK;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  SqeArgs q;
+  q.file_id = d_file_id;
+  q.sqe = d_sqe;
+  q.status = d_status;
+  q.stage_addr = stage_addr;
+  q.sqe_cap = sqe_cap;
+  q.chunk_bytes = cfg->chunk_bytes;
+  q.layer = layer;
+  q.opcode = opcode;
+  q.sgl_id = sgl_id;
+  // one lane per 16-byte quarter of an entry; at most a few workgroups per CU
+  uint64_t need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
+  if (need == 0) need = 1;
+  const uint64_t cap = static_cast<uint64_t>(cus) * 4;
+  const uint32_t grid = static_cast<uint32_t>(need < cap ? need : cap);
+  hipLaunchKernelGGL(k_sqe, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req), static_cast<hipStream_t>(stream), q,
+                     d_extents, n_req);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                        const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                        uint32_t layer, const void *d_stage, uint64_t stage_cap, uint64_t stage_addr,
+                        uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe,
+                        uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  uint32_t bb = 0;
+  int rc = check_geometry(pool, cfg, &bb);
+  if (rc) return rc;
+  rc = check_planes(pool);
+  if (rc) return rc;
+  if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
+  if (!d_totals || (n_req > 0 && (!d_n_blocks || !d_extents || !d_file_id))) return TUTTI_EINVAL;
+  if (table_len > 0 && !d_block_table) return TUTTI_EINVAL;
+  if (!d_stage && (stage_cap > 0 || table_len > 0)) return TUTTI_EINVAL;
+  if (!aligned16(d_stage)) return TUTTI_EINVAL;
+  if (sqe_cap > 0 && (!d_sqe || !aligned16(d_sqe))) return TUTTI_EINVAL;
+  if (layer >= cfg->num_layers) return TUTTI_EINVAL;
+  if (stage_addr % cfg->align != 0) return TUTTI_EINVAL;
+
+  Launch L;
+  rc = plan_launch(cu_budget, 0, &L);
+  if (rc) return rc;
+  MoveArgs m;
+  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, L.unroll, &m);
+  if (rc) return rc;
+  uint64_t items = 2ull * table_len * m.slices_per_block;
+  const uint64_t sqe_items = (4ull * sqe_cap + kWave - 1) / kWave;  // wavefronts the entry writes can use
+  if (sqe_items > items) items = sqe_items;
+  rc = plan_launch(cu_budget, items, &L);
+  if (rc) return rc;
+
+  SqeArgs q;
+  q.file_id = d_file_id;
+  q.sqe = d_sqe;
+  q.status = d_status;
+  q.stage_addr = stage_addr;
+  q.sqe_cap = sqe_cap;
+  q.chunk_bytes = cfg->chunk_bytes;
+  q.layer = layer;
+  q.opcode = TUTTI_OP_READ;
+  q.sgl_id = sgl_id;
+
+  LayoutArgs a;
+  a.n_blocks = d_n_blocks;
+  a.extents = d_extents;
+  a.totals = d_totals;
+  a.geom = ScanGeom{bb, cfg->align, cfg->chunk_bytes};
+  a.n_req = n_req;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint32_t lds = req_lds_bytes(n_req);
+  hipError_t e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_restore<true>(L, lds, s, m, q, a)
+                                                          : launch_restore<false>(L, lds, s, m, q, a);
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream) {
+  if (!d_dst || !d_src || !aligned16(d_dst) || !aligned16(d_src) || bytes % 16 != 0) return TUTTI_EINVAL;
+  if (bytes == 0) return TUTTI_OK;
+  Launch L;
+  int rc = plan_launch(cu_budget, 0, &L);
+  if (rc) return rc;
+  const uint64_t slice = kWave * 16ull * L.unroll;
+  rc = plan_launch(cu_budget, (bytes + slice - 1) / slice, &L);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char *dst = static_cast<unsigned char *>(d_dst);
+  const unsigned char *src = static_cast<const unsigned char *>(d_src);
+#define TUTTI_COPY_CASE(U)                                                                         \
+  case U:                                                                                          \
+    if (L.nontemporal)                                                                             \
+      hipLaunchKernelGGL((k_copy<U, true>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes);  \
+    else                                                                                           \
+      hipLaunchKernelGGL((k_copy<U, false>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes); \
+    break;
+  switch (L.unroll) {
+    TUTTI_COPY_CASE(1)
+    TUTTI_COPY_CASE(2)
+    TUTTI_COPY_CASE(4)
+    TUTTI_COPY_CASE(8)
+    default:
+      return TUTTI_EINVAL;
+  }
+#undef TUTTI_COPY_CASE
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+const char *tutti_strerror(int code) {
+  switch (code) {
+    case TUTTI_OK:
+      return "ok";
+    case TUTTI_EINVAL:
+      return "invalid argument (null pointer, zero dimension, bad alignment, layout, opcode or layer)";
+    case TUTTI_ERANGE:
+      return "out of range (too many requests, CU budget above the CU count, or table too long)";
+    case TUTTI_EHIP:
+      return "a HIP call failed (see tutti_last_hip_error)";
+    default:
+      return "unknown tutti error code";
+  }
+}
+
+int tutti_last_hip_error(void) { return t_last_hip; }
+
+int tutti_cu_count(void) { return cu_count(); }
+
+uint32_t tutti_version(void) { return 0x00000100u; }
+
+int tutti_abi_describe(uint32_t *out, uint32_t cap) {
+  if (!out || cap < 33) return TUTTI_EINVAL;
+  uint32_t i = 0;
+  out[i++] = sizeof(tutti_extent);
+  out[i++] = offsetof(tutti_extent, stage_off);
+  out[i++] = offsetof(tutti_extent, obj_bytes);
+  out[i++] = offsetof(tutti_extent, n_blocks);
+  out[i++] = offsetof(tutti_extent, n_chunks);
+  out[i++] = offsetof(tutti_extent, sqe_base);
+  out[i++] = offsetof(tutti_extent, table_off);
+  out[i++] = sizeof(tutti_sqe);
+  out[i++] = offsetof(tutti_sqe, opcode);
+  out[i++] = offsetof(tutti_sqe, kind);
+  out[i++] = offsetof(tutti_sqe, layer);
+  out[i++] = offsetof(tutti_sqe, file_id);
+  out[i++] = offsetof(tutti_sqe, file_off);
+  out[i++] = offsetof(tutti_sqe, addr);
+  out[i++] = offsetof(tutti_sqe, len);
+  out[i++] = offsetof(tutti_sqe, sgl_id);
+  out[i++] = offsetof(tutti_sqe, user_data);
+  out[i++] = offsetof(tutti_sqe, iocb_idx);
+  out[i++] = offsetof(tutti_sqe, ioctx_slot);
+  out[i++] = sizeof(tutti_pool);
+  out[i++] = offsetof(tutti_pool, k_base);
+  out[i++] = offsetof(tutti_pool, v_base);
+  out[i++] = offsetof(tutti_pool, block_stride);
+  out[i++] = offsetof(tutti_pool, num_blocks);
+  out[i++] = offsetof(tutti_pool, block_tokens);
+  out[i++] = offsetof(tutti_pool, num_kv_heads);
+  out[i++] = offsetof(tutti_pool, head_dim);
+  out[i++] = offsetof(tutti_pool, elt_bytes);
+  out[i++] = offsetof(tutti_pool, pool_layout);
+  out[i++] = sizeof(tutti_objcfg);
+  out[i++] = offsetof(tutti_objcfg, align);
+  out[i++] = offsetof(tutti_objcfg, chunk_bytes);
+  out[i++] = offsetof(tutti_objcfg, num_layers);
+  return static_cast<int>(i);
+}
+
+int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll) {
+  if (unroll != 0 && unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return TUTTI_EINVAL;
+  if (wgs_per_cu > 1024) return TUTTI_ERANGE;
+  g_wgs_per_cu.store(wgs_per_cu, std::memory_order_relaxed);
+  g_unroll.store(unroll, std::memory_order_relaxed);
+  return TUTTI_OK;
+}
+
+// Experiment switch: 1 = non-temporal loads and stores in the copy loops (default), 0 = plain.
+int tutti_set_nontemporal(uint32_t on) {
+  g_nontemporal.store(on ? 1u : 0u, std::memory_order_relaxed);
+  return TUTTI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,425 @@
+// Device code of libtutti for gfx950 (wave64).  Included once, by tutti_api.hip.
+//
+// Kernels
+//   k_layout        one wavefront: extents of all requests by a wave-level prefix scan
+//   k_sqe           submission entries from extents, four lanes per 64-byte entry
+//   k_move          pack / unpack between paged blocks and objects, extents given
+//   k_restore       one layer's restore in one launch: scan + entries + unpack
+//   k_copy          plain contiguous copy with the same access shape (measurement ceiling)
+//
+// Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
+// the scan), then walks work items with a persistent grid-stride loop, so the grid can be any
+// size: the whole GPU, or a few compute units' worth when the caller sets a CU budget.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tutti.h"
+
+namespace tutti {
+
+constexpr uint32_t kWave = 64;
+constexpr uint32_t kWgThreads = 256;
+constexpr uint32_t kWgWaves = kWgThreads / kWave;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------
+// Per-request offsets in LDS.  Laid out in the dynamic LDS block as
+//   u64 stage_off[R] | u64 obj_bytes[R] | u32 table_off[R+1] | u32 sqe_base[R+1]
+// with the totals in the two sentinel slots.  24*R + 8 bytes.
+// ------------------------------------------------------------------------------------------
+struct ReqLds {
+  uint64_t *stage_off;
+  uint64_t *obj_bytes;
+  uint32_t *table_off;
+  uint32_t *sqe_base;
+};
+
+__device__ __forceinline__ ReqLds carve_lds(unsigned char *smem, uint32_t n_req) {
+  ReqLds l;
+  l.stage_off = reinterpret_cast<uint64_t *>(smem);
+  l.obj_bytes = l.stage_off + n_req;
+  l.table_off = reinterpret_cast<uint32_t *>(l.obj_bytes + n_req);
+  l.sqe_base = l.table_off + n_req + 1;
+  return l;
+}
+
+__host__ __device__ constexpr uint32_t req_lds_bytes(uint32_t n_req) { return 24u * n_req + 8u; }
+
+__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, uint32_t delta) {
+  uint32_t lo = __shfl_up(static_cast<uint32_t>(v), delta, kWave);
+  uint32_t hi = __shfl_up(static_cast<uint32_t>(v >> 32), delta, kWave);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t shfl_u64(uint64_t v, uint32_t src) {
+  uint32_t lo = __shfl(static_cast<uint32_t>(v), src, kWave);
+  uint32_t hi = __shfl(static_cast<uint32_t>(v >> 32), src, kWave);
+  return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v, uint32_t lane) {
+#pragma unroll
+  for (uint32_t d = 1; d < kWave; d <<= 1) {
+    uint64_t t = shfl_up_u64(v, d);
+    if (lane >= d) v += t;
+  }
+  return v;
+}
+
+struct ScanGeom {
+  uint32_t block_bytes;
+  uint32_t align;       // power of two
+  uint32_t chunk_bytes; // multiple of align
+};
+
+// Extents of all requests, computed by ONE wavefront (the caller passes lane = its lane id and
+// makes sure only one wave of the workgroup runs this).  64 requests per pass, running totals
+// carried between passes.  Results go to LDS and, when ext_out != nullptr, to global memory.
+__device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32_t *__restrict__ n_blocks, uint32_t n_req,
+                                                  uint32_t lane, ReqLds l, tutti_extent *__restrict__ ext_out,
+                                                  uint64_t *__restrict__ totals_out) {
+  uint64_t carry_stage = 0, carry_sqe = 0, carry_tab = 0;
+  for (uint32_t base = 0; base < n_req; base += kWave) {
+    const uint32_t r = base + lane;
+    const uint32_t n = (r < n_req) ? n_blocks[r] : 0u;
+    const uint64_t raw = static_cast<uint64_t>(n) * g.block_bytes;
+    const uint64_t obj = (raw + (g.align - 1)) & ~static_cast<uint64_t>(g.align - 1);
+    const uint64_t chunks = (obj + g.chunk_bytes - 1) / g.chunk_bytes;
+    const uint64_t inc_stage = wave_inclusive_scan(2 * obj, lane);
+    const uint64_t inc_sqe = wave_inclusive_scan(2 * chunks, lane);
+    const uint64_t inc_tab = wave_inclusive_scan(n, lane);
+    if (r < n_req) {
+      const uint64_t stage_off = carry_stage + inc_stage - 2 * obj;
+      const uint32_t sqe_base = static_cast<uint32_t>(carry_sqe + inc_sqe - 2 * chunks);
+      const uint32_t table_off = static_cast<uint32_t>(carry_tab + inc_tab - n);
+      l.stage_off[r] = stage_off;
+      l.obj_bytes[r] = obj;
+      l.table_off[r] = table_off;
+      l.sqe_base[r] = sqe_base;
+      if (ext_out) {
+        tutti_extent e;
+        e.stage_off = stage_off;
+        e.obj_bytes = obj;
+        e.n_blocks = n;
+        e.n_chunks = static_cast<uint32_t>(chunks);
+        e.sqe_base = sqe_base;
+        e.table_off = table_off;
+        ext_out[r] = e;
+      }
+    }
+    carry_stage += shfl_u64(inc_stage, kWave - 1);
+    carry_sqe += shfl_u64(inc_sqe, kWave - 1);
+    carry_tab += shfl_u64(inc_tab, kWave - 1);
+  }
+  if (lane == 0) {
+    l.table_off[n_req] = static_cast<uint32_t>(carry_tab);
+    l.sqe_base[n_req] = static_cast<uint32_t>(carry_sqe);
+    if (totals_out) {
+      totals_out[0] = carry_stage;
+      totals_out[1] = carry_sqe;
+    }
+  }
+}
+
+// Per-request offsets from extents the caller already has (workgroup-wide, then a barrier).
+__device__ __forceinline__ void lds_from_extents(const tutti_extent *__restrict__ ext, uint32_t n_req, ReqLds l) {
+  for (uint32_t r = threadIdx.x; r < n_req; r += blockDim.x) {
+    const tutti_extent e = ext[r];
+    l.stage_off[r] = e.stage_off;
+    l.obj_bytes[r] = e.obj_bytes;
+    l.table_off[r] = e.table_off;
+    l.sqe_base[r] = e.sqe_base;
+    if (r + 1 == n_req) {
+      l.table_off[n_req] = e.table_off + e.n_blocks;
+      l.sqe_base[n_req] = e.sqe_base + 2u * e.n_chunks;
+    }
+  }
+  if (n_req == 0 && threadIdx.x == 0) {
+    l.table_off[0] = 0;
+    l.sqe_base[0] = 0;
+  }
+  __syncthreads();
+}
+
+// Largest r in [0, n) with a[r] <= key, for a non-decreasing a with a[0] <= key.  Empty
+// requests share their offset with the next one, so the answer is never an empty request
+// when key is below the total.
+__device__ __forceinline__ uint32_t find_owner(const uint32_t *a, uint32_t n, uint32_t key) {
+  uint32_t lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (a[mid] <= key)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  return lo;
+}
+
+// ------------------------------------------------------------------------------------------
+// Submission entries.  Four consecutive lanes write the four 16-byte quarters of one 64-byte
+// entry, so a wavefront's store covers 16 whole entries = 1 KiB of consecutive bytes.
+// ------------------------------------------------------------------------------------------
+struct SqeArgs {
+  const uint32_t *file_id;
+  tutti_sqe *sqe;
+  uint32_t *status;
+  uint64_t stage_addr;
+  uint32_t sqe_cap;
+  uint32_t chunk_bytes;
+  uint32_t layer;
+  uint32_t opcode;
+  uint32_t sgl_id;
+};
+
+__device__ __forceinline__ void emit_sqes(const SqeArgs a, const ReqLds l, uint32_t n_req) {
+  const uint32_t n_sqe = l.sqe_base[n_req];
+  const uint32_t n_write = n_sqe < a.sqe_cap ? n_sqe : a.sqe_cap;
+  if (n_sqe > a.sqe_cap && blockIdx.x == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
+  const uint64_t n_quarters = 4ull * n_write;
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  u32x4 *out = reinterpret_cast<u32x4 *>(a.sqe);
+  for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; q < n_quarters; q += stride) {
+    const uint32_t i = static_cast<uint32_t>(q >> 2);
+    const uint32_t part = static_cast<uint32_t>(q & 3);
+    const uint32_t r = find_owner(l.sqe_base, n_req, i);
+    const uint32_t base = l.sqe_base[r];
+    const uint32_t n_chunks = (l.sqe_base[r + 1] - base) >> 1;
+    const uint32_t v = i - base;
+    const uint32_t kind = v >= n_chunks ? 1u : 0u;
+    const uint32_t c = v - kind * n_chunks;
+    const uint64_t obj = l.obj_bytes[r];
+    const uint64_t in_obj = static_cast<uint64_t>(c) * a.chunk_bytes;
+    u32x4 w = {0u, 0u, 0u, 0u};
+    if (part == 0) {
+      const uint64_t file_off = (2ull * a.layer + kind) * obj + in_obj;
+      w.x = (a.opcode & 0xffu) | (kind << 8) | (a.layer << 16);
+      w.y = a.file_id[r];
+      w.z = static_cast<uint32_t>(file_off);
+      w.w = static_cast<uint32_t>(file_off >> 32);
+    } else if (part == 1) {
+      const uint64_t addr = a.stage_addr + l.stage_off[r] + kind * obj + in_obj;
+      const uint64_t left = obj - in_obj;
+      w.x = static_cast<uint32_t>(addr);
+      w.y = static_cast<uint32_t>(addr >> 32);
+      w.z = left < a.chunk_bytes ? static_cast<uint32_t>(left) : a.chunk_bytes;
+      w.w = a.sgl_id;
+    } else if (part == 2) {
+      w.x = i;
+      w.y = r;
+      w.z = i / TUTTI_IOCB_SLOTS;
+      w.w = i % TUTTI_IOCB_SLOTS;
+    }
+    out[q] = w;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Pack / unpack.  A work item is one slice of one (block, K|V): kSliceUnits*1 KiB, moved by one
+// wavefront with 16-byte accesses per lane (1 KiB per wavefront instruction, whole cache lines
+// on both sides).  Items are numbered in staging-buffer order (request, K then V, block, slice),
+// so neighbouring wavefronts stream neighbouring object bytes while the pool side jumps from
+// block to block as the table says.
+// ------------------------------------------------------------------------------------------
+struct MoveArgs {
+  unsigned char *k_base;
+  unsigned char *v_base;
+  unsigned char *stage;
+  const uint32_t *table;
+  uint32_t *status;
+  uint64_t block_stride;
+  uint64_t stage_cap;
+  uint32_t num_blocks;
+  uint32_t block_bytes;
+  uint32_t table_len;
+  uint32_t slices_per_block;
+  // head-major pools only: a row is the d*e bytes of one (token, head)
+  uint32_t row_bytes;
+  uint32_t block_tokens;
+  uint32_t num_kv_heads;
+};
+
+constexpr int kPack = 0;   // pool -> object
+constexpr int kUnpack = 1; // object -> pool
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const unsigned char *p) {
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+  return *reinterpret_cast<const u32x4 *>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void st16(unsigned char *p, u32x4 v) {
+  if (NT)
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+  else
+    *reinterpret_cast<u32x4 *>(p) = v;
+}
+
+// Offset inside a head-major block [h][T][row] of the 16 bytes that sit at canonical
+// (token-major, [T][h][row]) offset o.
+__device__ __forceinline__ uint32_t hnd_offset(uint32_t o, uint32_t row_bytes, uint32_t T, uint32_t h) {
+  const uint32_t row = o / row_bytes;
+  const uint32_t w = o - row * row_bytes;
+  const uint32_t t = row / h;
+  const uint32_t i = row - t * h;
+  return (i * T + t) * row_bytes + w;
+}
+
+template <int DIR, bool HND, int U, bool NT>
+__device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req) {
+  constexpr uint32_t kSlice = kWave * 16u * U;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t n_waves = gridDim.x * (blockDim.x / kWave);
+  // never more blocks than the table holds, whatever the extents claim
+  const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
+  const uint32_t S = a.slices_per_block;
+  const uint32_t n_items = 2u * total_blocks * S;  // the host checked that 2 * table_len * S fits 32 bits
+
+  for (uint32_t it = blockIdx.x * (blockDim.x / kWave) + wave_in_wg; it < n_items; it += n_waves) {
+    const uint32_t u = it / S;  // (block, kind) unit in staging order
+    const uint32_t s = it - u * S;
+    const uint32_t r = find_owner(l.table_off, n_req, u >> 1);
+    const uint32_t toff = l.table_off[r];
+    const uint32_t n = l.table_off[r + 1] - toff;
+    const uint32_t v = u - 2u * toff;
+    const uint32_t kind = v >= n ? 1u : 0u;
+    const uint32_t j = v - kind * n;
+    const uint64_t obj = l.obj_bytes[r];
+    const uint64_t stage_off = l.stage_off[r];
+    if (stage_off + 2 * obj > a.stage_cap || stage_off + 2 * obj < stage_off) {
+      if (lane == 0 && j == 0 && s == 0 && kind == 0 && a.status) atomicOr(a.status, TUTTI_ST_STAGE_CAP);
+      continue;
+    }
+    if ((static_cast<uint64_t>(j) + 1) * a.block_bytes > obj) continue;  // inconsistent extents: stay inside the object
+    unsigned char *obj_ptr = a.stage + stage_off + kind * obj;
+    const uint32_t in_blk = s * kSlice;  // first byte of the slice inside the block
+    const uint32_t tab_idx = toff + j;
+    uint32_t id = a.num_blocks;
+    if (tab_idx < a.table_len) id = __builtin_amdgcn_readfirstlane(a.table[tab_idx]);
+    if (id < a.num_blocks) {
+      unsigned char *blk_ptr = (kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
+      unsigned char *obj_blk = obj_ptr + static_cast<uint64_t>(j) * a.block_bytes;
+      const uint32_t o0 = in_blk + lane * 16u;  // this lane's first 16 bytes, canonical offset in the block
+      if (in_blk + kSlice <= a.block_bytes) {
+        // whole slice inside the block: U independent loads in flight, then U stores
+        u32x4 buf[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+          const uint32_t o = o0 + k * (kWave * 16u);
+          if (DIR == kPack)
+            buf[k] = ld16<NT>(blk_ptr + (HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o));
+          else
+            buf[k] = ld16<NT>(obj_blk + o);
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+          const uint32_t o = o0 + k * (kWave * 16u);
+          if (DIR == kPack)
+            st16<NT>(obj_blk + o, buf[k]);
+          else
+            st16<NT>(blk_ptr + (HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o), buf[k]);
+        }
+      } else {
+        // ragged last slice of a block: one guarded 16-byte move at a time
+        for (int k = 0; k < U; ++k) {
+          const uint32_t o = o0 + k * (kWave * 16u);
+          if (o < a.block_bytes) {
+            const uint32_t po = HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o;
+            if (DIR == kPack)
+              st16<NT>(obj_blk + o, ld16<NT>(blk_ptr + po));
+            else
+              st16<NT>(blk_ptr + po, ld16<NT>(obj_blk + o));
+          }
+        }
+      }
+    } else if (lane == 0 && s == 0 && a.status) {
+      atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
+    }
+    if (DIR == kPack && j + 1 == n && s + 1 == S) {
+      // zero the tail of the object up to its aligned size (fewer than `align` bytes)
+      const uint64_t used = static_cast<uint64_t>(n) * a.block_bytes;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      for (uint64_t o = used + lane * 16ull; o < obj; o += kWave * 16ull) st16<false>(obj_ptr + o, zero);
+    }
+  }
+}
+
+struct LayoutArgs {
+  const uint32_t *n_blocks;
+  tutti_extent *extents;
+  uint64_t *totals;
+  ScanGeom geom;
+  uint32_t n_req;
+};
+
+__global__ __launch_bounds__(kWave) void k_layout(const LayoutArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, a.n_req);
+  wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, a.extents, a.totals);
+}
+
+__global__ __launch_bounds__(kWgThreads) void k_sqe(const SqeArgs a, const tutti_extent *__restrict__ ext,
+                                                     uint32_t n_req) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, n_req);
+  lds_from_extents(ext, n_req, l);
+  emit_sqes(a, l, n_req);
+}
+
+template <int DIR, bool HND, int U, bool NT>
+__global__ __launch_bounds__(kWgThreads) void k_move(const MoveArgs a, const tutti_extent *__restrict__ ext,
+                                                      uint32_t n_req) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, n_req);
+  lds_from_extents(ext, n_req, l);
+  move_items<DIR, HND, U, NT>(a, l, n_req);
+}
+
+// One layer's restore: every workgroup redoes the (tiny) scan into its own LDS with its first
+// wavefront, workgroup 0 also publishes extents and totals, then all workgroups share the
+// entry writes and the unpack.
+template <bool HND, int U, bool NT>
+__global__ __launch_bounds__(kWgThreads) void k_restore(const MoveArgs m, const SqeArgs q, const LayoutArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, a.n_req);
+  if (threadIdx.x < kWave) {
+    const bool publish = blockIdx.x == 0;
+    wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
+                      publish ? a.totals : nullptr);
+  }
+  __syncthreads();
+  emit_sqes(q, l, a.n_req);
+  move_items<kUnpack, HND, U, NT>(m, l, a.n_req);
+}
+
+// Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.
+template <int U, bool NT>
+__global__ __launch_bounds__(kWgThreads) void k_copy(unsigned char *__restrict__ dst,
+                                                      const unsigned char *__restrict__ src, uint64_t bytes) {
+  constexpr uint64_t kSlice = kWave * 16ull * U;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * (blockDim.x / kWave);
+  const uint64_t n_items = (bytes + kSlice - 1) / kSlice;
+  for (uint64_t it = static_cast<uint64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave; it < n_items;
+       it += n_waves) {
+    const uint64_t o0 = it * kSlice + lane * 16ull;
+    if ((it + 1) * kSlice <= bytes) {
+      u32x4 buf[U];
+#pragma unroll
+      for (int k = 0; k < U; ++k) buf[k] = ld16<NT>(src + o0 + k * (kWave * 16ull));
+#pragma unroll
+      for (int k = 0; k < U; ++k) st16<NT>(dst + o0 + k * (kWave * 16ull), buf[k]);
+    } else {
+      for (int k = 0; k < U; ++k) {
+        const uint64_t o = o0 + k * (kWave * 16ull);
+        if (o < bytes) st16<NT>(dst + o, ld16<NT>(src + o));
+      }
+    }
+  }
+}
+
+}  // namespace tutti

@@ -1,0 +1,207 @@
+"""Helpers for the GPU parity tests: one layer's inputs on host and device, both sides run on them.
+
+The HIP path is always called through the C ABI (paper_2605_03375_amd.binding); the oracle through
+oracle.tutti_oracle.  Nothing computed by one side is ever fed to the other: both start from the
+same seeded inputs and only their outputs are compared, byte for byte.
+"""
+import numpy as np
+import torch
+
+from paper_2605_03375_amd import binding as B
+from paper_2605_03375_amd import workloads as W
+
+DEV = "cuda:0"
+
+
+def to_dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).to(DEV)
+
+
+def as_u8(t):
+    return t.contiguous().view(torch.uint8).reshape(-1)
+
+
+class LayerCase:
+    """One layer's pool, table and object geometry, resident on host (numpy) and device (torch)."""
+
+    def __init__(self, *, T, h, d, e, N, n_blocks, table, file_id=None, align=4096, chunk=2 << 20, L=1, layout=0,
+                 pad=0, fill="values", seed=1, dtype="bf16", name="case"):
+        self.T, self.h, self.d, self.e, self.N = T, h, d, e, N
+        self.bb = T * h * d * e
+        self.stride = self.bb + pad
+        self.align, self.chunk, self.L, self.layout, self.name = align, chunk, L, layout, name
+        self.n_blocks = np.ascontiguousarray(n_blocks, np.uint32)
+        self.table = np.ascontiguousarray(table, np.uint32)
+        self.file_id = (np.arange(self.n_blocks.size, dtype=np.uint32) + 1000) if file_id is None else \
+            np.ascontiguousarray(file_id, np.uint32)
+        nbytes = N * self.stride
+        if fill == "tags":
+            self.k_dev = W.device_address_tags(nbytes, 0, DEV)
+            self.v_dev = W.device_address_tags(nbytes, 1 << 30, DEV)
+        else:
+            self.k_dev = as_u8(W.device_values(seed, nbytes // 2, dtype, DEV))
+            self.v_dev = as_u8(W.device_values(seed + 7, nbytes // 2, dtype, DEV))
+        self.k_host = self.k_dev.cpu().numpy()
+        self.v_host = self.v_dev.cpu().numpy()
+        self.d_n_blocks = to_dev(self.n_blocks) if self.n_blocks.size else torch.zeros(1, dtype=torch.int32, device=DEV)
+        self.d_table = to_dev(self.table) if self.table.size else torch.zeros(1, dtype=torch.int32, device=DEV)
+        self.d_file_id = to_dev(self.file_id) if self.file_id.size else torch.zeros(1, dtype=torch.int32, device=DEV)
+
+    @classmethod
+    def from_workload(cls, w, **kw):
+        s = w.shape
+        return cls(T=s.block_tokens, h=s.num_kv_heads, d=s.head_dim, e=s.elt_bytes, N=s.num_blocks,
+                   n_blocks=w.n_blocks, table=w.block_table, file_id=w.file_id, align=w.align, chunk=w.chunk_bytes,
+                   L=s.num_layers, dtype=s.dtype, seed=w.seed, name=w.name, **kw)
+
+    # ---- descriptors for each side
+    def geom(self):
+        return dict(num_blocks=self.N, block_tokens=self.T, num_kv_heads=self.h, head_dim=self.d, elt_bytes=self.e,
+                    block_stride=self.stride, pool_layout=self.layout)
+
+    def gpu_pool(self, k=None, v=None):
+        return B.make_pool(self.k_dev if k is None else k, self.v_dev if v is None else v, **self.geom())
+
+    def orc_pool(self, orc, k=None, v=None):
+        return orc.make_pool(self.k_host if k is None else k, self.v_host if v is None else v, **self.geom())
+
+    def gpu_cfg(self):
+        return B.make_cfg(self.align, self.chunk, self.L)
+
+    def orc_cfg(self, orc):
+        return orc.make_cfg(self.align, self.chunk, self.L)
+
+    @property
+    def n_req(self):
+        return int(self.n_blocks.size)
+
+
+def new_status():
+    return torch.zeros(1, dtype=torch.int32, device=DEV)
+
+
+def gpu_layout(c):
+    ext = torch.zeros(max(1, c.n_req) * 32, dtype=torch.uint8, device=DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=DEV)
+    B.tutti_obj_layout(c.gpu_pool(), c.gpu_cfg(), c.d_n_blocks, c.n_req, ext, tot)
+    torch.cuda.synchronize()
+    return ext, tot
+
+
+def ext_np(ext, n_req):
+    return ext.cpu().numpy()[: 32 * n_req].view(B.EXTENT_DTYPE)
+
+
+def check_layout(orc, c):
+    ext, tot = gpu_layout(c)
+    o_ext, o_tot = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes(), f"{c.name}: extents differ"
+    assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot), f"{c.name}: totals differ"
+    return ext, tot, o_ext, o_tot
+
+
+def check_pack(orc, c, ext, o_ext, o_tot, cu_budget=0, stage_cap=None, table_len=None):
+    nbytes = max(int(o_tot[0]), 16)
+    fill = 0xA5
+    stage = torch.full((nbytes,), fill, dtype=torch.uint8, device=DEV)
+    st = new_status()
+    B.tutti_obj_pack(c.gpu_pool(), c.gpu_cfg(), ext, c.n_req, c.d_table,
+                     c.table.size if table_len is None else table_len, stage,
+                     int(o_tot[0]) if stage_cap is None else stage_cap, cu_budget, st)
+    torch.cuda.synchronize()
+    o_stage = np.full(nbytes, fill, np.uint8)
+    o_st = orc.obj_pack(c.orc_pool(orc), c.orc_cfg(orc), o_ext, c.table, o_stage,
+                        stage_cap=int(o_tot[0]) if stage_cap is None else stage_cap)
+    got = stage.cpu().numpy()
+    assert np.array_equal(got, o_stage), f"{c.name}: packed objects differ at byte {first_diff(got, o_stage)}"
+    assert int(st.item()) == o_st, f"{c.name}: pack status {int(st.item())} vs oracle {o_st}"
+    return stage
+
+
+def first_diff(a, b):
+    idx = np.flatnonzero(a != b)
+    return int(idx[0]) if idx.size else -1
+
+
+def check_unpack(orc, c, ext, o_ext, o_tot, cu_budget=0, seed=99, stage_cap=None):
+    nbytes = max(int(o_tot[0]), 16)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    stage = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=DEV, generator=g)
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    st = new_status()
+    B.tutti_obj_unpack(c.gpu_pool(k2, v2), c.gpu_cfg(), ext, c.n_req, c.d_table, c.table.size, stage,
+                       int(o_tot[0]) if stage_cap is None else stage_cap, cu_budget, st)
+    torch.cuda.synchronize()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    o_st = orc.obj_unpack(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), o_ext, c.table, stage.cpu().numpy(),
+                          stage_cap=int(o_tot[0]) if stage_cap is None else stage_cap)
+    gk, gv = k2.cpu().numpy(), v2.cpu().numpy()
+    assert np.array_equal(gk, ok), f"{c.name}: K plane differs at byte {first_diff(gk, ok)}"
+    assert np.array_equal(gv, ov), f"{c.name}: V plane differs at byte {first_diff(gv, ov)}"
+    assert int(st.item()) == o_st
+    return stage
+
+
+def check_sqe(orc, c, ext, o_ext, o_tot, layer=0, stage_addr=0x7F1200000000, sgl_id=42, sqe_cap=None):
+    n = int(o_tot[1])
+    cap = n if sqe_cap is None else sqe_cap
+    for op in (B.OP_READ, B.OP_WRITE):
+        sqe = torch.full((max(cap, 1) * 64,), 0x3C, dtype=torch.uint8, device=DEV)
+        st = new_status()
+        B.tutti_sqe_build(c.gpu_pool(), c.gpu_cfg(), ext, c.n_req, c.d_file_id, layer, op, stage_addr, sgl_id, sqe,
+                          cap, st)
+        torch.cuda.synchronize()
+        o_sqe, o_st = orc.sqe_build(c.orc_pool(orc), c.orc_cfg(orc), o_ext, c.file_id, layer, op, stage_addr, sgl_id,
+                                    sqe_cap=cap)
+        n_written = min(n, cap)
+        got = sqe.cpu().numpy()
+        assert got[: 64 * n_written].tobytes() == o_sqe[:n_written].tobytes(), f"{c.name}: entries differ (op {op})"
+        assert np.all(got[64 * n_written:] == 0x3C), "entries beyond the count must stay untouched"
+        assert int(st.item()) == o_st
+
+
+def check_layer_restore(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000, sgl_id=7, seed=5, sqe_cap=None,
+                        stage_cap=None):
+    o_ext0, o_tot0 = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    nbytes = max(int(o_tot0[0]), 16)
+    n_sqe = int(o_tot0[1])
+    cap = n_sqe if sqe_cap is None else sqe_cap
+    scap = int(o_tot0[0]) if stage_cap is None else stage_cap
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    stage = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=DEV, generator=g)
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ext = torch.zeros(max(1, c.n_req) * 32, dtype=torch.uint8, device=DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=DEV)
+    sqe = torch.full((max(cap, 1) * 64,), 0x3C, dtype=torch.uint8, device=DEV)
+    st = new_status()
+    B.tutti_layer_restore(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id,
+                          layer, stage, scap, stage_addr, sgl_id, ext, tot, sqe, cap, cu_budget, st)
+    torch.cuda.synchronize()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    o_ext, o_tot, o_sqe, o_st = orc.layer_restore(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks, c.table,
+                                                  c.file_id, layer, stage.cpu().numpy(), stage_addr, sgl_id, cap,
+                                                  stage_cap=scap)
+    assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes()
+    assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot)
+    n_written = min(n_sqe, cap)
+    got = sqe.cpu().numpy()
+    assert got[: 64 * n_written].tobytes() == o_sqe[:n_written].tobytes(), f"{c.name}: restore entries differ"
+    assert np.all(got[64 * n_written:] == 0x3C)
+    gk, gv = k2.cpu().numpy(), v2.cpu().numpy()
+    assert np.array_equal(gk, ok), f"{c.name}: restore K plane differs at byte {first_diff(gk, ok)}"
+    assert np.array_equal(gv, ov), f"{c.name}: restore V plane differs at byte {first_diff(gv, ov)}"
+    assert int(st.item()) == o_st
+
+
+def check_everything(orc, c, cu_budget=0):
+    """All five entry points on one case, each against the oracle."""
+    ext, tot, o_ext, o_tot = check_layout(orc, c)
+    check_pack(orc, c, ext, o_ext, o_tot, cu_budget)
+    check_unpack(orc, c, ext, o_ext, o_tot, cu_budget)
+    check_sqe(orc, c, ext, o_ext, o_tot, layer=c.L - 1)
+    check_layer_restore(orc, c, layer=c.L - 1, cu_budget=cu_budget)

@@ -1,0 +1,146 @@
+"""CPU tests of the boundary: the library loads, exports what include/tutti.h declares, agrees
+with the oracle on every record layout, and rejects bad host arguments before touching HIP."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_03375_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "tutti.h")).read()
+    declared = sorted(set(re.findall(r"\b(tutti_[a-z_0-9]+)\s*\(", header)))
+    assert set(declared) == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore"):
+        assert name in declared and callable(getattr(B, name))
+    assert B.tutti_version() >= 0x100
+
+
+def test_record_layouts_agree_with_oracle(orc):
+    lib_abi = B.tutti_abi_describe()
+    assert lib_abi == orc.abi_describe()
+    E, S = B.EXTENT_DTYPE, B.SQE_DTYPE
+    assert [E.itemsize] + [E.fields[n][1] for n in E.names] == lib_abi[0:7]
+    assert [S.itemsize] + [S.fields[n][1] for n in S.names[:-1]] == lib_abi[7:19]
+    import ctypes
+    assert ctypes.sizeof(B.tutti_pool) == lib_abi[19] and ctypes.sizeof(B.tutti_objcfg) == lib_abi[29]
+    assert [getattr(B.tutti_pool, f).offset for f, _ in B.tutti_pool._fields_] == lib_abi[20:29]
+    assert [getattr(B.tutti_objcfg, f).offset for f, _ in B.tutti_objcfg._fields_] == lib_abi[30:33]
+    for a, b in [(B.OP_READ, orc.OP_READ), (B.OP_WRITE, orc.OP_WRITE), (B.LAYOUT_HND, orc.LAYOUT_HND),
+                 (B.IOCB_SLOTS, orc.IOCB_SLOTS), (B.ST_BAD_BLOCK, orc.ST_BAD_BLOCK),
+                 (B.ST_STAGE_CAP, orc.ST_STAGE_CAP), (B.ST_SQE_CAP, orc.ST_SQE_CAP)]:
+        assert a == b
+
+
+def test_strerror():
+    for code in (B.OK, B.EINVAL, B.ERANGE, B.EHIP, -99):
+        assert isinstance(B.tutti_strerror(code), str) and B.tutti_strerror(code)
+
+
+GOOD = dict(num_blocks=8, block_tokens=16, num_kv_heads=2, head_dim=64, elt_bytes=2)
+FAKE = 0x10000  # a non-null, 16-byte aligned stand-in for device pointers: never dereferenced on these paths
+
+
+def _expect(code, fn, *a, **kw):
+    with pytest.raises(B.TuttiError) as ei:
+        fn(*a, **kw, stream=0)
+    assert ei.value.code == code, ei.value
+
+
+@pytest.mark.parametrize("bad", [dict(block_tokens=0), dict(num_blocks=0), dict(head_dim=3, elt_bytes=1,
+                                 block_tokens=1, num_kv_heads=1), dict(block_stride=4000), dict(block_stride=4104),
+                                 dict(pool_layout=2)])
+def test_bad_pool_is_einval(bad):
+    kw = dict(GOOD)
+    kw.update(bad)
+    p = B.make_pool(FAKE, FAKE, **kw)
+    _expect(B.EINVAL, B.tutti_obj_layout, p, B.make_cfg(), FAKE, 1, FAKE, FAKE)
+    _expect(B.EINVAL, B.tutti_obj_pack, p, B.make_cfg(), FAKE, 1, FAKE, 1, FAKE, 1 << 20)
+    _expect(B.EINVAL, B.tutti_obj_unpack, p, B.make_cfg(), FAKE, 1, FAKE, 1, FAKE, 1 << 20)
+    _expect(B.EINVAL, B.tutti_sqe_build, p, B.make_cfg(), FAKE, 1, FAKE, 0, B.OP_READ, 0, 0, FAKE, 4)
+    _expect(B.EINVAL, B.tutti_layer_restore, p, B.make_cfg(), FAKE, 1, FAKE, 1, FAKE, 0, FAKE, 1 << 20, 0, 0, FAKE,
+            FAKE, FAKE, 4)
+
+
+@pytest.mark.parametrize("bad", [dict(align=4095), dict(align=8), dict(align=0), dict(chunk_bytes=0),
+                                 dict(chunk_bytes=6144), dict(num_layers=0)])
+def test_bad_cfg_is_einval(bad):
+    kw = dict(align=4096, chunk_bytes=8192, num_layers=2)
+    kw.update(bad)
+    p = B.make_pool(FAKE, FAKE, **GOOD)
+    _expect(B.EINVAL, B.tutti_obj_layout, p, B.make_cfg(**kw), FAKE, 1, FAKE, FAKE)
+    _expect(B.EINVAL, B.tutti_sqe_build, p, B.make_cfg(**kw), FAKE, 1, FAKE, 0, B.OP_READ, 0, 0, FAKE, 4)
+
+
+def test_null_and_misaligned_pointers_are_einval():
+    cfg = B.make_cfg(num_layers=2)
+    p = B.make_pool(FAKE, FAKE, **GOOD)
+    _expect(B.EINVAL, B.tutti_obj_layout, p, cfg, 0, 1, FAKE, FAKE)
+    _expect(B.EINVAL, B.tutti_obj_layout, p, cfg, FAKE, 1, 0, FAKE)
+    _expect(B.EINVAL, B.tutti_obj_layout, p, cfg, FAKE, 1, FAKE, 0)
+    _expect(B.EINVAL, B.tutti_obj_pack, p, cfg, 0, 1, FAKE, 1, FAKE, 4096)
+    _expect(B.EINVAL, B.tutti_obj_pack, p, cfg, FAKE, 1, 0, 1, FAKE, 4096)
+    _expect(B.EINVAL, B.tutti_obj_pack, p, cfg, FAKE, 1, FAKE, 1, 0, 4096)
+    _expect(B.EINVAL, B.tutti_obj_unpack, p, cfg, FAKE, 1, FAKE, 1, FAKE + 8, 4096)      # staging not 16-aligned
+    _expect(B.EINVAL, B.tutti_obj_pack, B.make_pool(0, FAKE, **GOOD), cfg, FAKE, 1, FAKE, 1, FAKE, 4096)
+    _expect(B.EINVAL, B.tutti_obj_pack, B.make_pool(FAKE, FAKE + 4, **GOOD), cfg, FAKE, 1, FAKE, 1, FAKE, 4096)
+    _expect(B.EINVAL, B.tutti_sqe_build, p, cfg, FAKE, 1, 0, 0, B.OP_READ, 0, 0, FAKE, 4)
+    _expect(B.EINVAL, B.tutti_sqe_build, p, cfg, FAKE, 1, FAKE, 0, B.OP_READ, 0, 0, 0, 4)
+    _expect(B.EINVAL, B.tutti_sqe_build, p, cfg, FAKE, 1, FAKE, 2, B.OP_READ, 0, 0, FAKE, 4)        # layer >= L
+    _expect(B.EINVAL, B.tutti_sqe_build, p, cfg, FAKE, 1, FAKE, 0, 3, 0, 0, FAKE, 4)                # opcode
+    _expect(B.EINVAL, B.tutti_sqe_build, p, cfg, FAKE, 1, FAKE, 0, B.OP_READ, 100, 0, FAKE, 4)      # stage_addr
+    _expect(B.EINVAL, B.tutti_layer_restore, p, cfg, FAKE, 1, FAKE, 1, FAKE, 2, FAKE, 4096, 0, 0, FAKE, FAKE, FAKE, 4)
+    _expect(B.EINVAL, B.tutti_layer_restore, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, FAKE, 4096, 0, 0, FAKE, 0, FAKE, 4)
+    _expect(B.EINVAL, B.tutti_copy_baseline, FAKE, FAKE, 24)
+    _expect(B.EINVAL, B.tutti_copy_baseline, 0, FAKE, 32)
+    # head-major pools need rows of whole 16-byte units
+    hp = B.make_pool(FAKE, FAKE, num_blocks=8, block_tokens=16, num_kv_heads=2, head_dim=4, elt_bytes=2,
+                     pool_layout=B.LAYOUT_HND)
+    _expect(B.EINVAL, B.tutti_obj_pack, hp, cfg, FAKE, 1, FAKE, 1, FAKE, 4096)
+
+
+def test_too_many_requests_is_erange():
+    p = B.make_pool(FAKE, FAKE, **GOOD)
+    cfg = B.make_cfg()
+    _expect(B.ERANGE, B.tutti_obj_layout, p, cfg, FAKE, B.MAX_REQ + 1, FAKE, FAKE)
+    _expect(B.ERANGE, B.tutti_obj_pack, p, cfg, FAKE, B.MAX_REQ + 1, FAKE, 1, FAKE, 4096)
+    _expect(B.ERANGE, B.tutti_sqe_build, p, cfg, FAKE, B.MAX_REQ + 1, FAKE, 0, B.OP_READ, 0, 0, FAKE, 4)
+
+
+def test_tuning_arguments():
+    with pytest.raises(B.TuttiError):
+        B.tutti_set_tuning(0, 3)
+    B.tutti_set_tuning(0, 0)
+
+
+def test_empty_calls_do_not_need_a_gpu():
+    """n_req = 0 (or an empty table) is a no-op for pack / unpack / entries: nothing is enqueued."""
+    p = B.make_pool(FAKE, FAKE, **GOOD)
+    cfg = B.make_cfg()
+    assert B.tutti_obj_pack(p, cfg, 0, 0, 0, 0, FAKE, 0, stream=0) == B.OK
+    assert B.tutti_obj_unpack(p, cfg, FAKE, 1, 0, 0, FAKE, 0, stream=0) == B.OK
+    assert B.tutti_sqe_build(p, cfg, 0, 0, 0, 0, B.OP_READ, 0, 0, 0, 0, stream=0) == B.OK
+    assert B.tutti_copy_baseline(FAKE, FAKE, 0, stream=0) == B.OK
+
+
+def test_workloads_are_seeded_and_shaped():
+    from paper_2605_03375_amd import workloads as W
+    a, b = W.batch64_zipf(), W.batch64_zipf()
+    assert np.array_equal(a.block_table, b.block_table) and np.array_equal(a.n_blocks, b.n_blocks)
+    assert a.n_req == 64 and len(set(a.block_table.tolist())) == a.block_table.size
+    t = W.tiny()
+    assert t.block_table.size == 32 and t.shape.num_blocks == 256
+    w2 = W.llama8b_32k()
+    assert w2.block_table.size == 2048 and w2.shape.num_blocks == 65536 and w2.shape.num_layers == 32
+    w4 = W.llama70b_128k()
+    assert w4.block_table.size == 8192 and w4.shape.num_blocks == 38146 and w4.shape.num_layers == 80
+    assert len(set(w4.block_table.tolist())) == 8192 and int(w4.block_table.max()) < 38146
+    v = W.host_values(1, 1000, "bf16")
+    assert v.dtype == np.uint16 and np.array_equal(v, W.host_values(1, 1000, "bf16"))

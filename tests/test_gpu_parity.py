@@ -1,0 +1,240 @@
+"""GPU parity tests: every entry point of libtutti, called through the C ABI, byte-for-byte against
+the CPU oracle on the same seeded inputs.  Integer / byte work, so the bar is exact equality."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2605_03375_amd import binding as B      # noqa: E402
+from paper_2605_03375_amd import workloads as W    # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: run with -m 'not gpu' on a CPU-only machine")
+    B.lib()  # fails loudly if the HIP library is not built: there is no fallback
+    import gpu_harness
+    return gpu_harness
+
+
+@pytest.fixture(autouse=True)
+def _default_tuning():
+    B.tutti_set_tuning(0, 0)
+    B.tutti_set_nontemporal(1)
+    yield
+    B.tutti_set_tuning(0, 0)
+    B.tutti_set_nontemporal(1)
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ config 1: Tiny
+
+@pytest.mark.parametrize("layout", [0, 1], ids=["nhd", "hnd"])
+@pytest.mark.parametrize("fill", ["values", "tags"])
+@pytest.mark.parametrize("chunk", [2 << 20, 4096])
+def test_cfg1_tiny(orc, H, layout, fill, chunk):
+    w = W.tiny(chunk_bytes=chunk)
+    say("cfg1", layout, fill, chunk)
+    c = H.LayerCase.from_workload(w, layout=layout, fill=fill)
+    H.check_everything(orc, c)
+
+
+# ------------------------------------------------------------------ shapes that span tiles and leave ragged tails
+
+RAGGED = [
+    # T, h, d, e, N, n_blocks, align, chunk, pad
+    (16, 5, 40, 2, 300, [7, 0, 33, 1, 64, 2], 4096, 12288, 0),      # block 6400 B: ragged slice, padded objects
+    (16, 8, 128, 2, 512, [100, 3, 0, 0, 129], 4096, 2 << 20, 0),    # the 8B block shape
+    (16, 8, 128, 2, 128, [17, 40], 4096, 32768, 4096),              # strided pool, one entry per block
+    (3, 1, 8, 2, 64, [1, 2, 3, 4, 5, 6, 7, 8], 64, 192, 16),        # 48-byte blocks
+    (32, 4, 64, 1, 256, [0, 0, 5, 0, 200], 512, 8192, 0),           # fp8-sized elements, empty requests first
+    (16, 1, 128, 2, 1024, [1000], 4096, 4096, 0),                   # TP-sharded shape: 4 KiB blocks at scale
+    (64, 8, 128, 2, 96, [31, 33], 4096, 131072, 0),                 # 64-token blocks (128 KiB)
+]
+
+
+@pytest.mark.parametrize("layout", [0, 1], ids=["nhd", "hnd"])
+@pytest.mark.parametrize("shape", RAGGED, ids=[f"bb{t*h*d*e}_r{len(n)}" for t, h, d, e, _, n, *_ in RAGGED])
+def test_ragged_shapes(orc, H, shape, layout):
+    T, h, d, e, N, n_blocks, A, C, pad = shape
+    say("ragged", shape, layout)
+    rng = np.random.default_rng(1234 + T * h)
+    table = rng.permutation(N)[: sum(n_blocks)]
+    c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=n_blocks, table=table, align=A, chunk=C, L=3, layout=layout,
+                    pad=pad, seed=T + h, name=f"ragged{shape}")
+    H.check_everything(orc, c)
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+@pytest.mark.parametrize("nt", [0, 1])
+def test_launch_tuning_does_not_change_results(orc, H, unroll, nt):
+    say("tuning", unroll, nt)
+    B.tutti_set_tuning(3, unroll)
+    B.tutti_set_nontemporal(nt)
+    rng = np.random.default_rng(77)
+    for layout in (0, 1):
+        c = H.LayerCase(T=16, h=5, d=40, e=2, N=200, n_blocks=[9, 0, 70, 31], table=rng.permutation(200)[:110],
+                        align=4096, chunk=8192, L=2, layout=layout, name=f"tuning{unroll}")
+        H.check_everything(orc, c)
+
+
+# ------------------------------------------------------------------ edge cases
+
+def test_no_requests_and_empty_requests(orc, H):
+    say("edge: no requests")
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[], table=[], name="no_requests")
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    assert int(o_tot[0]) == 0 and int(o_tot[1]) == 0
+    H.check_layer_restore(orc, c)
+    say("edge: only empty requests")
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[0, 0, 0], table=[], name="empty_requests")
+    H.check_everything(orc, c)
+
+
+def test_max_requests(orc, H):
+    say("edge: 2048 requests")
+    rng = np.random.default_rng(4)
+    n = rng.integers(0, 4, size=B.MAX_REQ).astype(np.uint32)
+    N = int(n.sum()) + 50
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=n, table=rng.permutation(N)[: int(n.sum())], chunk=4096,
+                    L=4, name="max_req")
+    H.check_everything(orc, c)
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=n[:65], table=rng.permutation(N)[: int(n[:65].sum())],
+                    chunk=4096, L=4, layout=1, name="req65")
+    H.check_everything(orc, c)
+
+
+def test_bad_block_ids_are_skipped_and_reported(orc, H):
+    say("edge: bad block ids")
+    table = np.array([3, 999, 5, 16, 7, 1], np.uint32)   # 999 and 16 are out of range for 16 blocks
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[4, 2], table=table, name="bad_ids")
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    H.check_pack(orc, c, ext, o_ext, o_tot)
+    H.check_unpack(orc, c, ext, o_ext, o_tot)
+    H.check_layer_restore(orc, c)
+
+
+def test_small_capacities_are_clamped_and_reported(orc, H):
+    say("edge: capacities")
+    rng = np.random.default_rng(9)
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=64, n_blocks=[5, 9, 3], table=rng.permutation(64)[:17], chunk=4096,
+                    name="caps")
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    cap = int(o_ext["stage_off"][2]) + 4096          # third request does not fit
+    H.check_pack(orc, c, ext, o_ext, o_tot, stage_cap=cap)
+    H.check_unpack(orc, c, ext, o_ext, o_tot, stage_cap=cap)
+    H.check_sqe(orc, c, ext, o_ext, o_tot, sqe_cap=11)
+    H.check_sqe(orc, c, ext, o_ext, o_tot, sqe_cap=0)
+    H.check_layer_restore(orc, c, sqe_cap=5, stage_cap=cap)
+
+
+def test_short_table_is_never_overrun(orc, H):
+    """table_len smaller than the extents claim: the missing blocks are skipped and reported."""
+    say("edge: short table")
+    rng = np.random.default_rng(10)
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=64, n_blocks=[6, 6], table=rng.permutation(64)[:12], name="short")
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    stage = torch.full((int(o_tot[0]),), 0xA5, dtype=torch.uint8, device=H.DEV)
+    st = H.new_status()
+    B.tutti_obj_pack(c.gpu_pool(), c.gpu_cfg(), ext, 2, c.d_table, 8, stage, int(o_tot[0]), 0, st)
+    torch.cuda.synchronize()
+    # the oracle sees the same situation as a table whose tail ids are out of range
+    t2 = c.table.copy()
+    t2[8:] = 0xFFFFFFFF
+    o_stage = np.full(int(o_tot[0]), 0xA5, np.uint8)
+    orc.obj_pack(c.orc_pool(orc), c.orc_cfg(orc), o_ext, t2, o_stage)
+    got = stage.cpu().numpy()
+    bb = c.bb
+    # blocks 0..7 of the flattened table are packed; blocks 8..11 (request 1, j = 2..5) are not
+    assert np.array_equal(got[: 6 * bb], o_stage[: 6 * bb])
+    k1 = int(o_ext["stage_off"][1])
+    assert np.array_equal(got[k1: k1 + 2 * bb], o_stage[k1: k1 + 2 * bb])
+    assert np.all(got[k1 + 2 * bb: k1 + 6 * bb] == 0xA5)
+
+
+def test_cu_budget_out_of_range(H):
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[2], table=[1, 2], name="budget")
+    ext, tot = H.gpu_layout(c)
+    with pytest.raises(B.TuttiError) as ei:
+        B.tutti_obj_unpack(c.gpu_pool(), c.gpu_cfg(), ext, 1, c.d_table, 2, torch.zeros(1 << 16, dtype=torch.uint8,
+                           device=H.DEV), 1 << 16, B.tutti_cu_count() + 1)
+    assert ei.value.code == B.ERANGE
+    assert B.tutti_cu_count() >= 64
+
+
+def test_copy_baseline(H):
+    say("copy baseline")
+    g = torch.Generator(device=H.DEV)
+    g.manual_seed(1)
+    for n in (16, 4096, 1 << 20, (1 << 20) + 48, 5 * 4096 + 16):
+        src = torch.randint(0, 256, (n,), dtype=torch.uint8, device=H.DEV, generator=g)
+        dst = torch.zeros(n + 64, dtype=torch.uint8, device=H.DEV)
+        B.tutti_copy_baseline(dst, src, n)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and not dst[n:].any()
+
+
+# ------------------------------------------------------------------ configs 2-5 at their real shapes
+
+def test_cfg2_llama8b_32k_full_layer(orc, H):
+    """Config 2 at full size for one layer: 65536-block planes (2 GiB each), 2048-block shuffled table."""
+    w = W.llama8b_32k()
+    say("cfg2 full layer", w.shape)
+    c = H.LayerCase.from_workload(w)
+    H.check_everything(orc, c)
+
+
+def test_cfg2_head_major(orc, H):
+    w = W.llama8b_32k(num_blocks=4096)
+    say("cfg2 head-major, 4096-block pool")
+    c = H.LayerCase.from_workload(w, layout=1)
+    H.check_everything(orc, c)
+
+
+@pytest.mark.parametrize("chunk", [2 << 20, 32768], ids=["chunk2MiB", "per_block"])
+def test_cfg3_batch64(orc, H, chunk):
+    """Config 3 at full size: 64 requests, Zipf lengths, partial hits, disjoint tables."""
+    w = W.batch64_zipf(chunk_bytes=chunk)
+    say("cfg3", chunk, int(w.n_blocks.sum()), "blocks")
+    c = H.LayerCase.from_workload(w)
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    H.check_sqe(orc, c, ext, o_ext, o_tot, layer=w.shape.num_layers - 1)
+    if chunk == 2 << 20:
+        H.check_unpack(orc, c, ext, o_ext, o_tot)
+        H.check_pack(orc, c, ext, o_ext, o_tot)
+    H.check_layer_restore(orc, c, layer=5)
+
+
+def test_cfg4_llama70b_128k_layer(orc, H):
+    """Config 4's layer shape: 38146-block planes, 8192-block fragmented table (512 MiB payload)."""
+    w = W.llama70b_128k()
+    say("cfg4 layer", w.shape)
+    c = H.LayerCase.from_workload(w)
+    H.check_everything(orc, c)
+
+
+@pytest.mark.parametrize("budget", [8, 16, 32, 64])
+def test_cfg5_cu_budget_with_concurrent_gemm(orc, H, budget):
+    """Config 5: the restore under a CU budget while a bf16 4096^3 GEMM runs on another stream."""
+    w = W.llama8b_32k(num_blocks=8192)
+    say("cfg5 budget", budget)
+    c = H.LayerCase.from_workload(w)
+    a = torch.randn(4096, 4096, dtype=torch.bfloat16, device=H.DEV)
+    b = torch.randn(4096, 4096, dtype=torch.bfloat16, device=H.DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(20):
+            cmat = a @ b
+    H.check_layer_restore(orc, c, cu_budget=budget)
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    H.check_unpack(orc, c, ext, o_ext, o_tot, cu_budget=budget)
+    H.check_pack(orc, c, ext, o_ext, o_tot, cu_budget=budget)
+    side.synchronize()
+    assert torch.isfinite(cmat.float()).all()
