@@ -79,7 +79,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     B.tutti_set_tuning(args.wgs_per_cu, args.unroll)
-    B.tutti_set_nontemporal(0 if args.plain_loads else 1)
+    B.tutti_set_nontemporal(0 if args.plain_loads else 3)
 
     w = W.llama8b_32k()
     s = w.shape

@@ -167,8 +167,9 @@ int tutti_abi_describe(uint32_t *out, uint32_t cap);
 /* Launch tuning, for experiments: wgs_per_cu persistent workgroups per budgeted CU (0 = default),
  * unroll = 16-byte accesses in flight per lane (0 = default; 1, 2, 4 or 8). */
 int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll);
-/* Experiment switch: 1 = non-temporal 16-byte loads and stores in the copy loops (default), 0 = plain. */
-int tutti_set_nontemporal(uint32_t on);
+/* Experiment switch for the copy loops: bit 0 = non-temporal 16-byte loads, bit 1 = non-temporal
+ * 16-byte stores (default 3 = both). */
+int tutti_set_nontemporal(uint32_t mask);
 
 #ifdef __cplusplus
 }

@@ -202,5 +202,5 @@ def tutti_set_tuning(wgs_per_cu=0, unroll=0):
     return _check("tutti_set_tuning", lib().tutti_set_tuning(wgs_per_cu, unroll))
 
 
-def tutti_set_nontemporal(on=1):
-    return _check("tutti_set_nontemporal", lib().tutti_set_nontemporal(1 if on else 0))
+def tutti_set_nontemporal(mask=3):
+    return _check("tutti_set_nontemporal", lib().tutti_set_nontemporal(int(mask)))

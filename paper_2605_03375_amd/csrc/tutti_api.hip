@@ -18,7 +18,7 @@ thread_local int t_last_hip = 0;
 
 std::atomic<uint32_t> g_wgs_per_cu{0};
 std::atomic<uint32_t> g_unroll{0};
-std::atomic<uint32_t> g_nontemporal{1};
+std::atomic<uint32_t> g_nontemporal{3};  // bit 0: loads, bit 1: stores
 
 constexpr uint32_t kDefaultWgsPerCu = 8;  // 32 wavefronts per CU
 constexpr uint32_t kDefaultUnroll = 4;    // 4 x 16 B in flight per lane: 4 KiB slices
@@ -82,7 +82,7 @@ int check_planes(const tutti_pool *pool) {
 struct Launch {
   uint32_t grid;
   uint32_t unroll;
-  bool nontemporal;
+  uint32_t nontemporal;  // bit 0: loads, bit 1: stores
 };
 
 // Grid of persistent workgroups: enough for every item to have its own wavefront, capped by
@@ -100,7 +100,7 @@ int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
   out->grid = static_cast<uint32_t>(need < cap ? need : cap);
   uint32_t u = g_unroll.load(std::memory_order_relaxed);
   out->unroll = u ? u : kDefaultUnroll;
-  out->nontemporal = g_nontemporal.load(std::memory_order_relaxed) != 0;
+  out->nontemporal = g_nontemporal.load(std::memory_order_relaxed) & 3u;
   return TUTTI_OK;
 }
 
@@ -129,12 +129,18 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
 template <int DIR, bool HND>
 hipError_t launch_move(const Launch &L, uint32_t lds, hipStream_t s, const MoveArgs &m, const tutti_extent *ext,
                        uint32_t n_req) {
-#define TUTTI_MOVE_CASE(U)                                                                             \
-  case U:                                                                                              \
-    if (L.nontemporal)                                                                                 \
-      hipLaunchKernelGGL((k_move<DIR, HND, U, true>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext, n_req);  \
-    else                                                                                               \
-      hipLaunchKernelGGL((k_move<DIR, HND, U, false>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext, n_req); \
+#define TUTTI_MOVE_NT(U, NT)                                                                            \
+  case NT:                                                                                              \
+    hipLaunchKernelGGL((k_move<DIR, HND, U, NT>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext, n_req); \
+    break;
+#define TUTTI_MOVE_CASE(U)       \
+  case U:                        \
+    switch (L.nontemporal) {     \
+      TUTTI_MOVE_NT(U, 0)        \
+      TUTTI_MOVE_NT(U, 1)        \
+      TUTTI_MOVE_NT(U, 2)        \
+      TUTTI_MOVE_NT(U, 3)        \
+    }                            \
     break;
   switch (L.unroll) {
     TUTTI_MOVE_CASE(1)
@@ -144,19 +150,28 @@ hipError_t launch_move(const Launch &L, uint32_t lds, hipStream_t s, const MoveA
     default:
       return hipErrorInvalidValue;
   }
+#undef TUTTI_MOVE_NT
 #undef TUTTI_MOVE_CASE
   return hipGetLastError();
 }
 
 template <bool HND>
-hipError_t launch_restore(const Launch &L, uint32_t lds, hipStream_t s, const MoveArgs &m, const SqeArgs &q,
-                          const LayoutArgs &a) {
-#define TUTTI_RESTORE_CASE(U)                                                                       \
-  case U:                                                                                           \
-    if (L.nontemporal)                                                                              \
-      hipLaunchKernelGGL((k_restore<HND, U, true>), dim3(L.grid), dim3(kWgThreads), lds, s, m, q, a);  \
-    else                                                                                            \
-      hipLaunchKernelGGL((k_restore<HND, U, false>), dim3(L.grid), dim3(kWgThreads), lds, s, m, q, a); \
+hipError_t launch_restore(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
+                          const SqeArgs &q, const LayoutArgs &a) {
+  const uint32_t copy_wgs = L.grid;
+  const dim3 grid(L.grid + sqe_wgs);
+#define TUTTI_RESTORE_NT(U, NT)                                                                      \
+  case NT:                                                                                           \
+    hipLaunchKernelGGL((k_restore<HND, U, NT>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs);     \
+    break;
+#define TUTTI_RESTORE_CASE(U)    \
+  case U:                        \
+    switch (L.nontemporal) {     \
+      TUTTI_RESTORE_NT(U, 0)     \
+      TUTTI_RESTORE_NT(U, 1)     \
+      TUTTI_RESTORE_NT(U, 2)     \
+      TUTTI_RESTORE_NT(U, 3)     \
+    }                            \
     break;
   switch (L.unroll) {
     TUTTI_RESTORE_CASE(1)
@@ -166,6 +181,7 @@ hipError_t launch_restore(const Launch &L, uint32_t lds, hipStream_t s, const Mo
     default:
       return hipErrorInvalidValue;
   }
+#undef TUTTI_RESTORE_NT
 #undef TUTTI_RESTORE_CASE
   return hipGetLastError();
 }
@@ -298,11 +314,12 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   MoveArgs m;
   rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, L.unroll, &m);
   if (rc) return rc;
-  uint64_t items = 2ull * table_len * m.slices_per_block;
-  const uint64_t sqe_items = (4ull * sqe_cap + kWave - 1) / kWave;  // wavefronts the entry writes can use
-  if (sqe_items > items) items = sqe_items;
-  rc = plan_launch(cu_budget, items, &L);
+  rc = plan_launch(cu_budget, 2ull * table_len * m.slices_per_block, &L);
   if (rc) return rc;
+  // extra workgroups behind the copy ones write the entries (one lane per 16-byte quarter)
+  uint64_t sqe_need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
+  if (sqe_need < 1) sqe_need = 1;
+  const uint32_t sqe_wgs = static_cast<uint32_t>(sqe_need < 16 ? sqe_need : 16);
 
   SqeArgs q;
   q.file_id = d_file_id;
@@ -324,8 +341,8 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   const uint32_t lds = req_lds_bytes(n_req);
-  hipError_t e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_restore<true>(L, lds, s, m, q, a)
-                                                          : launch_restore<false>(L, lds, s, m, q, a);
+  hipError_t e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_restore<true>(L, sqe_wgs, lds, s, m, q, a)
+                                                          : launch_restore<false>(L, sqe_wgs, lds, s, m, q, a);
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
@@ -341,12 +358,18 @@ int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char *dst = static_cast<unsigned char *>(d_dst);
   const unsigned char *src = static_cast<const unsigned char *>(d_src);
-#define TUTTI_COPY_CASE(U)                                                                         \
-  case U:                                                                                          \
-    if (L.nontemporal)                                                                             \
-      hipLaunchKernelGGL((k_copy<U, true>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes);  \
-    else                                                                                           \
-      hipLaunchKernelGGL((k_copy<U, false>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes); \
+#define TUTTI_COPY_NT(U, NT)                                                                       \
+  case NT:                                                                                         \
+    hipLaunchKernelGGL((k_copy<U, NT>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes);      \
+    break;
+#define TUTTI_COPY_CASE(U)       \
+  case U:                        \
+    switch (L.nontemporal) {     \
+      TUTTI_COPY_NT(U, 0)        \
+      TUTTI_COPY_NT(U, 1)        \
+      TUTTI_COPY_NT(U, 2)        \
+      TUTTI_COPY_NT(U, 3)        \
+    }                            \
     break;
   switch (L.unroll) {
     TUTTI_COPY_CASE(1)
@@ -356,6 +379,7 @@ int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t
     default:
       return TUTTI_EINVAL;
   }
+#undef TUTTI_COPY_NT
 #undef TUTTI_COPY_CASE
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
@@ -429,9 +453,10 @@ int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll) {
   return TUTTI_OK;
 }
 
-// Experiment switch: 1 = non-temporal loads and stores in the copy loops (default), 0 = plain.
-int tutti_set_nontemporal(uint32_t on) {
-  g_nontemporal.store(on ? 1u : 0u, std::memory_order_relaxed);
+// Experiment switch: bit 0 = non-temporal loads, bit 1 = non-temporal stores in the copy loops.
+int tutti_set_nontemporal(uint32_t mask) {
+  if (mask > 3u) return TUTTI_EINVAL;
+  g_nontemporal.store(mask, std::memory_order_relaxed);
   return TUTTI_OK;
 }
 

@@ -175,14 +175,17 @@ struct SqeArgs {
   uint32_t sgl_id;
 };
 
-__device__ __forceinline__ void emit_sqes(const SqeArgs a, const ReqLds l, uint32_t n_req) {
+// Written by the `n_wgs` workgroups starting at workgroup `first_wg`.
+__device__ __forceinline__ void emit_sqes(const SqeArgs a, const ReqLds l, uint32_t n_req, uint32_t first_wg,
+                                          uint32_t n_wgs) {
   const uint32_t n_sqe = l.sqe_base[n_req];
   const uint32_t n_write = n_sqe < a.sqe_cap ? n_sqe : a.sqe_cap;
-  if (n_sqe > a.sqe_cap && blockIdx.x == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
+  const uint32_t wg = blockIdx.x - first_wg;
+  if (n_sqe > a.sqe_cap && wg == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
   const uint64_t n_quarters = 4ull * n_write;
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  const uint64_t stride = static_cast<uint64_t>(n_wgs) * blockDim.x;
   u32x4 *out = reinterpret_cast<u32x4 *>(a.sqe);
-  for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; q < n_quarters; q += stride) {
+  for (uint64_t q = static_cast<uint64_t>(wg) * blockDim.x + threadIdx.x; q < n_quarters; q += stride) {
     const uint32_t i = static_cast<uint32_t>(q >> 2);
     const uint32_t part = static_cast<uint32_t>(q & 3);
     const uint32_t r = find_owner(l.sqe_base, n_req, i);
@@ -245,14 +248,15 @@ struct MoveArgs {
 constexpr int kPack = 0;   // pool -> object
 constexpr int kUnpack = 1; // object -> pool
 
-template <bool NT>
+// NT is a bit mask: bit 0 = non-temporal loads, bit 1 = non-temporal stores.
+template <int NT>
 __device__ __forceinline__ u32x4 ld16(const unsigned char *p) {
-  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+  if (NT & 1) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
   return *reinterpret_cast<const u32x4 *>(p);
 }
-template <bool NT>
+template <int NT>
 __device__ __forceinline__ void st16(unsigned char *p, u32x4 v) {
-  if (NT)
+  if (NT & 2)
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
   else
     *reinterpret_cast<u32x4 *>(p) = v;
@@ -268,83 +272,140 @@ __device__ __forceinline__ uint32_t hnd_offset(uint32_t o, uint32_t row_bytes, u
   return (i * T + t) * row_bytes + w;
 }
 
-template <int DIR, bool HND, int U, bool NT>
-__device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req) {
-  constexpr uint32_t kSlice = kWave * 16u * U;
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  const uint32_t n_waves = gridDim.x * (blockDim.x / kWave);
-  // never more blocks than the table holds, whatever the extents claim
-  const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
-  const uint32_t S = a.slices_per_block;
-  const uint32_t n_items = 2u * total_blocks * S;  // the host checked that 2 * table_len * S fits 32 bits
+// Wave-uniform description of one work item: where its slice sits on the object side and which
+// block-table entry names the pool side.
+struct Item {
+  unsigned char *obj_ptr;  // start of the (request, kind) object; nullptr = skip the item
+  uint64_t obj_bytes;
+  uint32_t tab_idx;        // index into the block table
+  uint32_t n;              // blocks of the request
+  uint32_t j;              // block within the request
+  uint32_t s;              // slice within the block
+  uint32_t kind;
+};
 
-  for (uint32_t it = blockIdx.x * (blockDim.x / kWave) + wave_in_wg; it < n_items; it += n_waves) {
-    const uint32_t u = it / S;  // (block, kind) unit in staging order
-    const uint32_t s = it - u * S;
-    const uint32_t r = find_owner(l.table_off, n_req, u >> 1);
-    const uint32_t toff = l.table_off[r];
-    const uint32_t n = l.table_off[r + 1] - toff;
-    const uint32_t v = u - 2u * toff;
-    const uint32_t kind = v >= n ? 1u : 0u;
-    const uint32_t j = v - kind * n;
-    const uint64_t obj = l.obj_bytes[r];
-    const uint64_t stage_off = l.stage_off[r];
-    if (stage_off + 2 * obj > a.stage_cap || stage_off + 2 * obj < stage_off) {
-      if (lane == 0 && j == 0 && s == 0 && kind == 0 && a.status) atomicOr(a.status, TUTTI_ST_STAGE_CAP);
-      continue;
-    }
-    if ((static_cast<uint64_t>(j) + 1) * a.block_bytes > obj) continue;  // inconsistent extents: stay inside the object
-    unsigned char *obj_ptr = a.stage + stage_off + kind * obj;
-    const uint32_t in_blk = s * kSlice;  // first byte of the slice inside the block
-    const uint32_t tab_idx = toff + j;
-    uint32_t id = a.num_blocks;
-    if (tab_idx < a.table_len) id = __builtin_amdgcn_readfirstlane(a.table[tab_idx]);
-    if (id < a.num_blocks) {
-      unsigned char *blk_ptr = (kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
-      unsigned char *obj_blk = obj_ptr + static_cast<uint64_t>(j) * a.block_bytes;
-      const uint32_t o0 = in_blk + lane * 16u;  // this lane's first 16 bytes, canonical offset in the block
-      if (in_blk + kSlice <= a.block_bytes) {
-        // whole slice inside the block: U independent loads in flight, then U stores
-        u32x4 buf[U];
+__device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, uint32_t n_req, uint32_t it,
+                                            uint32_t lane) {
+  Item d;
+  const uint32_t S = a.slices_per_block;
+  const uint32_t u = it / S;  // (block, kind) unit in staging order
+  d.s = it - u * S;
+  const uint32_t r = find_owner(l.table_off, n_req, u >> 1);
+  const uint32_t toff = l.table_off[r];
+  d.n = l.table_off[r + 1] - toff;
+  const uint32_t v = u - 2u * toff;
+  d.kind = v >= d.n ? 1u : 0u;
+  d.j = v - d.kind * d.n;
+  d.obj_bytes = l.obj_bytes[r];
+  d.tab_idx = toff + d.j;
+  const uint64_t stage_off = l.stage_off[r];
+  d.obj_ptr = a.stage + stage_off + d.kind * d.obj_bytes;
+  const uint64_t end = stage_off + 2 * d.obj_bytes;
+  if (end > a.stage_cap || end < stage_off) {  // the request's objects do not fit: skip it, report once
+    if (lane == 0 && d.j == 0 && d.s == 0 && d.kind == 0 && a.status) atomicOr(a.status, TUTTI_ST_STAGE_CAP);
+    d.obj_ptr = nullptr;
+  } else if ((static_cast<uint64_t>(d.j) + 1) * a.block_bytes > d.obj_bytes) {
+    d.obj_ptr = nullptr;  // inconsistent extents: stay inside the object
+  }
+  return d;
+}
+
+// Block id of an item through the scalar (constant) path: the index is wave-uniform, so this is
+// one s_load that overlaps the vector loads and stores of the item before it.
+typedef const __attribute__((address_space(4))) uint32_t *const_u32_ptr;
+
+__device__ __forceinline__ uint32_t load_block_id(const MoveArgs &a, const Item &d) {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+  const_u32_ptr tab = (const_u32_ptr)a.table;
+#pragma clang diagnostic pop
+  const uint32_t idx = __builtin_amdgcn_readfirstlane(d.tab_idx);  // uniform by construction
+  const bool ok = __builtin_amdgcn_readfirstlane(d.obj_ptr != nullptr && idx < a.table_len ? 1 : 0) != 0;
+  return ok ? tab[idx] : a.num_blocks;
+}
+
+template <int DIR, bool HND, int U, int NT>
+__device__ __forceinline__ void move_one(const MoveArgs &a, const Item &d, uint32_t id, uint32_t lane) {
+  constexpr uint32_t kSlice = kWave * 16u * U;
+  if (d.obj_ptr == nullptr) return;
+  const uint32_t in_blk = d.s * kSlice;  // first byte of the slice inside the block
+  if (id < a.num_blocks) {
+    unsigned char *blk_ptr = (d.kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
+    unsigned char *obj_blk = d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes;
+    const uint32_t o0 = in_blk + lane * 16u;  // this lane's first 16 bytes, canonical offset in the block
+    if (in_blk + kSlice <= a.block_bytes) {
+      // whole slice inside the block: U independent loads in flight, then U stores
+      u32x4 buf[U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) {
-          const uint32_t o = o0 + k * (kWave * 16u);
-          if (DIR == kPack)
-            buf[k] = ld16<NT>(blk_ptr + (HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o));
-          else
-            buf[k] = ld16<NT>(obj_blk + o);
-        }
+      for (int k = 0; k < U; ++k) {
+        const uint32_t o = o0 + k * (kWave * 16u);
+        if (DIR == kPack)
+          buf[k] = ld16<NT>(blk_ptr + (HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o));
+        else
+          buf[k] = ld16<NT>(obj_blk + o);
+      }
 #pragma unroll
-        for (int k = 0; k < U; ++k) {
-          const uint32_t o = o0 + k * (kWave * 16u);
+      for (int k = 0; k < U; ++k) {
+        const uint32_t o = o0 + k * (kWave * 16u);
+        if (DIR == kPack)
+          st16<NT>(obj_blk + o, buf[k]);
+        else
+          st16<NT>(blk_ptr + (HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o), buf[k]);
+      }
+    } else {
+      // ragged last slice of a block: one guarded 16-byte move at a time
+      for (int k = 0; k < U; ++k) {
+        const uint32_t o = o0 + k * (kWave * 16u);
+        if (o < a.block_bytes) {
+          const uint32_t po = HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o;
           if (DIR == kPack)
-            st16<NT>(obj_blk + o, buf[k]);
+            st16<NT>(obj_blk + o, ld16<NT>(blk_ptr + po));
           else
-            st16<NT>(blk_ptr + (HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o), buf[k]);
-        }
-      } else {
-        // ragged last slice of a block: one guarded 16-byte move at a time
-        for (int k = 0; k < U; ++k) {
-          const uint32_t o = o0 + k * (kWave * 16u);
-          if (o < a.block_bytes) {
-            const uint32_t po = HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o;
-            if (DIR == kPack)
-              st16<NT>(obj_blk + o, ld16<NT>(blk_ptr + po));
-            else
-              st16<NT>(blk_ptr + po, ld16<NT>(obj_blk + o));
-          }
+            st16<NT>(blk_ptr + po, ld16<NT>(obj_blk + o));
         }
       }
-    } else if (lane == 0 && s == 0 && a.status) {
-      atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
     }
-    if (DIR == kPack && j + 1 == n && s + 1 == S) {
-      // zero the tail of the object up to its aligned size (fewer than `align` bytes)
-      const uint64_t used = static_cast<uint64_t>(n) * a.block_bytes;
-      const u32x4 zero = {0u, 0u, 0u, 0u};
-      for (uint64_t o = used + lane * 16ull; o < obj; o += kWave * 16ull) st16<false>(obj_ptr + o, zero);
+  } else if (lane == 0 && d.s == 0 && a.status) {
+    atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
+  }
+  if (DIR == kPack && d.j + 1 == d.n && d.s + 1 == a.slices_per_block) {
+    // zero the tail of the object up to its aligned size (fewer than `align` bytes)
+    const uint64_t used = static_cast<uint64_t>(d.n) * a.block_bytes;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (uint64_t o = used + lane * 16ull; o < d.obj_bytes; o += kWave * 16ull) st16<0>(d.obj_ptr + o, zero);
+  }
+}
+
+// The copy loop of the first `copy_wgs` workgroups of the grid (the rest, if any, have other work).
+// Software-pipelined by one item: the next item is decoded and its block id requested before the
+// current item's loads and stores are issued.
+template <int DIR, bool HND, int U, int NT>
+__device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t copy_wgs) {
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t n_waves = copy_wgs * (blockDim.x / kWave);
+  // never more blocks than the table holds, whatever the extents claim
+  const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
+  const uint32_t n_items = 2u * total_blocks * a.slices_per_block;  // the host checked this fits 32 bits
+
+  uint32_t it = blockIdx.x * (blockDim.x / kWave) + wave_in_wg;
+  if (it >= n_items) return;
+  Item cur = decode_item(a, l, n_req, it, lane);
+  uint32_t id = load_block_id(a, cur);
+  for (;;) {
+    const uint32_t nit = it + n_waves;
+    const bool more = nit < n_items;
+    Item nxt = cur;
+    uint32_t nid = a.num_blocks;
+    if (more) {
+      nxt = decode_item(a, l, n_req, nit, lane);
+      nid = load_block_id(a, nxt);
     }
+    move_one<DIR, HND, U, NT>(a, cur, id, lane);
+    if (!more) break;
+    cur = nxt;
+    id = nid;
+    it = nit;
   }
 }
 
@@ -367,37 +428,41 @@ __global__ __launch_bounds__(kWgThreads) void k_sqe(const SqeArgs a, const tutti
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
   lds_from_extents(ext, n_req, l);
-  emit_sqes(a, l, n_req);
+  emit_sqes(a, l, n_req, 0, gridDim.x);
 }
 
-template <int DIR, bool HND, int U, bool NT>
+template <int DIR, bool HND, int U, int NT>
 __global__ __launch_bounds__(kWgThreads) void k_move(const MoveArgs a, const tutti_extent *__restrict__ ext,
                                                       uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
   lds_from_extents(ext, n_req, l);
-  move_items<DIR, HND, U, NT>(a, l, n_req);
+  move_items<DIR, HND, U, NT>(a, l, n_req, gridDim.x);
 }
 
 // One layer's restore: every workgroup redoes the (tiny) scan into its own LDS with its first
-// wavefront, workgroup 0 also publishes extents and totals, then all workgroups share the
-// entry writes and the unpack.
-template <bool HND, int U, bool NT>
-__global__ __launch_bounds__(kWgThreads) void k_restore(const MoveArgs m, const SqeArgs q, const LayoutArgs a) {
+// wavefront.  The first `copy_wgs` workgroups then unpack; the workgroups after them (at least
+// one) write the entries, and the last of those also publishes extents and totals, so none of the
+// bookkeeping sits in front of the copy.
+template <bool HND, int U, int NT>
+__global__ __launch_bounds__(kWgThreads) void k_restore(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
+                                                         uint32_t copy_wgs) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
   if (threadIdx.x < kWave) {
-    const bool publish = blockIdx.x == 0;
+    const bool publish = blockIdx.x + 1 == gridDim.x;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
                       publish ? a.totals : nullptr);
   }
   __syncthreads();
-  emit_sqes(q, l, a.n_req);
-  move_items<kUnpack, HND, U, NT>(m, l, a.n_req);
+  if (blockIdx.x < copy_wgs)
+    move_items<kUnpack, HND, U, NT>(m, l, a.n_req, copy_wgs);
+  else
+    emit_sqes(q, l, a.n_req, copy_wgs, gridDim.x - copy_wgs);
 }
 
 // Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.
-template <int U, bool NT>
+template <int U, int NT>
 __global__ __launch_bounds__(kWgThreads) void k_copy(unsigned char *__restrict__ dst,
                                                       const unsigned char *__restrict__ src, uint64_t bytes) {
   constexpr uint64_t kSlice = kWave * 16ull * U;

@@ -23,10 +23,10 @@ def H():
 @pytest.fixture(autouse=True)
 def _default_tuning():
     B.tutti_set_tuning(0, 0)
-    B.tutti_set_nontemporal(1)
+    B.tutti_set_nontemporal(3)
     yield
     B.tutti_set_tuning(0, 0)
-    B.tutti_set_nontemporal(1)
+    B.tutti_set_nontemporal(3)
 
 
 def say(*a):
@@ -72,7 +72,7 @@ def test_ragged_shapes(orc, H, shape, layout):
 
 
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8])
-@pytest.mark.parametrize("nt", [0, 1])
+@pytest.mark.parametrize("nt", [0, 1, 2, 3])
 def test_launch_tuning_does_not_change_results(orc, H, unroll, nt):
     say("tuning", unroll, nt)
     B.tutti_set_tuning(3, unroll)
