@@ -20,8 +20,9 @@ std::atomic<uint32_t> g_wgs_per_cu{0};
 std::atomic<uint32_t> g_unroll{0};
 std::atomic<uint32_t> g_nontemporal{3};  // bit 0: loads, bit 1: stores
 
-constexpr uint32_t kDefaultWgsPerCu = 8;  // 32 wavefronts per CU
-constexpr uint32_t kDefaultUnroll = 4;    // 4 x 16 B in flight per lane: 4 KiB slices
+constexpr uint32_t kDefaultWgsPerCu = 8;     // whole-GPU launches: 8 x 256 threads = 32 wavefronts per CU
+constexpr uint32_t kDefaultUnroll = 4;       // 4 x 16 B in flight per lane: 4 KiB slices
+constexpr uint32_t kBudgetUnroll = 8;        // CU-budgeted launches keep more bytes in flight per wavefront
 constexpr int kMaxDevices = 64;
 
 std::atomic<int> g_cu_count[kMaxDevices];
@@ -81,26 +82,39 @@ int check_planes(const tutti_pool *pool) {
 
 struct Launch {
   uint32_t grid;
+  uint32_t wg_threads;   // kWgThreads, or kBudgetWgThreads under a CU budget
   uint32_t unroll;
   uint32_t nontemporal;  // bit 0: loads, bit 1: stores
 };
 
-// Grid of persistent workgroups: enough for every item to have its own wavefront, capped by
-// the CU budget (0 = all CUs) times the workgroups kept resident per CU.
+// Launch shape.  Whole GPU (cu_budget = 0): persistent 256-thread workgroups, enough for every
+// item to have its own wavefront, at most wgs_per_cu per CU.  Under a CU budget B: B workgroups of
+// 1024 threads, i.e. one full-size workgroup per budgeted CU, so the launch occupies at most B
+// compute units and a concurrent compute kernel keeps the others to itself.
 int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
   const int cus = cu_count();
   if (cus < 0) return cus;
   if (cu_budget > static_cast<uint32_t>(cus)) return TUTTI_ERANGE;
-  const uint32_t budget = cu_budget ? cu_budget : static_cast<uint32_t>(cus);
+  uint32_t u = g_unroll.load(std::memory_order_relaxed);
+  out->nontemporal = g_nontemporal.load(std::memory_order_relaxed) & 3u;
+  if (cu_budget) {
+    out->wg_threads = kBudgetWgThreads;
+    out->unroll = u ? u : kBudgetUnroll;
+    const uint64_t waves = kBudgetWgThreads / kWave;
+    uint64_t need = (n_wave_items + waves - 1) / waves;
+    if (need == 0) need = 1;
+    out->grid = static_cast<uint32_t>(need < cu_budget ? need : cu_budget);
+    return TUTTI_OK;
+  }
   uint32_t per_cu = g_wgs_per_cu.load(std::memory_order_relaxed);
   if (per_cu == 0) per_cu = kDefaultWgsPerCu;
-  uint64_t cap = static_cast<uint64_t>(budget) * per_cu;
-  uint64_t need = (n_wave_items + kWgWaves - 1) / kWgWaves;
+  const uint64_t cap = static_cast<uint64_t>(cus) * per_cu;
+  const uint64_t waves = kWgThreads / kWave;
+  uint64_t need = (n_wave_items + waves - 1) / waves;
   if (need == 0) need = 1;
-  out->grid = static_cast<uint32_t>(need < cap ? need : cap);
-  uint32_t u = g_unroll.load(std::memory_order_relaxed);
+  out->wg_threads = kWgThreads;
   out->unroll = u ? u : kDefaultUnroll;
-  out->nontemporal = g_nontemporal.load(std::memory_order_relaxed) & 3u;
+  out->grid = static_cast<uint32_t>(need < cap ? need : cap);
   return TUTTI_OK;
 }
 
@@ -129,9 +143,14 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
 template <int DIR, bool HND>
 hipError_t launch_move(const Launch &L, uint32_t lds, hipStream_t s, const MoveArgs &m, const tutti_extent *ext,
                        uint32_t n_req) {
-#define TUTTI_MOVE_NT(U, NT)                                                                            \
-  case NT:                                                                                              \
-    hipLaunchKernelGGL((k_move<DIR, HND, U, NT>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext, n_req); \
+#define TUTTI_MOVE_NT(U, NT)                                                                                      \
+  case NT:                                                                                                        \
+    if (L.wg_threads == kWgThreads)                                                                               \
+      hipLaunchKernelGGL((k_move<DIR, HND, U, NT, kWgThreads>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext,   \
+                         n_req);                                                                                  \
+    else                                                                                                          \
+      hipLaunchKernelGGL((k_move<DIR, HND, U, NT, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), lds,  \
+                         s, m, ext, n_req);                                                                       \
     break;
 #define TUTTI_MOVE_CASE(U)       \
   case U:                        \
@@ -159,10 +178,16 @@ template <bool HND>
 hipError_t launch_restore(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
                           const SqeArgs &q, const LayoutArgs &a) {
   const uint32_t copy_wgs = L.grid;
-  const dim3 grid(L.grid + sqe_wgs);
-#define TUTTI_RESTORE_NT(U, NT)                                                                      \
-  case NT:                                                                                           \
-    hipLaunchKernelGGL((k_restore<HND, U, NT>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs);     \
+  // whole GPU: entry writers are extra workgroups; CU budget: the last copy workgroup writes them
+  const dim3 grid(L.wg_threads == kWgThreads ? L.grid + sqe_wgs : L.grid);
+#define TUTTI_RESTORE_NT(U, NT)                                                                                   \
+  case NT:                                                                                                        \
+    if (L.wg_threads == kWgThreads)                                                                               \
+      hipLaunchKernelGGL((k_restore<HND, U, NT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,  \
+                         sqe_wgs);                                                                                \
+    else                                                                                                          \
+      hipLaunchKernelGGL((k_restore<HND, U, NT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q,   \
+                         a, copy_wgs, sqe_wgs);                                                                   \
     break;
 #define TUTTI_RESTORE_CASE(U)    \
   case U:                        \
@@ -317,9 +342,10 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   rc = plan_launch(cu_budget, 2ull * table_len * m.slices_per_block, &L);
   if (rc) return rc;
   // extra workgroups behind the copy ones write the entries (one lane per 16-byte quarter)
-  uint64_t sqe_need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
+  uint64_t sqe_need = (4ull * sqe_cap + L.wg_threads - 1) / L.wg_threads;
   if (sqe_need < 1) sqe_need = 1;
-  const uint32_t sqe_wgs = static_cast<uint32_t>(sqe_need < 16 ? sqe_need : 16);
+  const uint64_t sqe_max = cu_budget ? 1 : 16;
+  const uint32_t sqe_wgs = static_cast<uint32_t>(sqe_need < sqe_max ? sqe_need : sqe_max);
 
   SqeArgs q;
   q.file_id = d_file_id;
@@ -358,9 +384,13 @@ int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char *dst = static_cast<unsigned char *>(d_dst);
   const unsigned char *src = static_cast<const unsigned char *>(d_src);
-#define TUTTI_COPY_NT(U, NT)                                                                       \
-  case NT:                                                                                         \
-    hipLaunchKernelGGL((k_copy<U, NT>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes);      \
+#define TUTTI_COPY_NT(U, NT)                                                                                    \
+  case NT:                                                                                                      \
+    if (L.wg_threads == kWgThreads)                                                                             \
+      hipLaunchKernelGGL((k_copy<U, NT, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes);   \
+    else                                                                                                        \
+      hipLaunchKernelGGL((k_copy<U, NT, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, dst,    \
+                         src, bytes);                                                                           \
     break;
 #define TUTTI_COPY_CASE(U)       \
   case U:                        \

@@ -20,8 +20,8 @@
 namespace tutti {
 
 constexpr uint32_t kWave = 64;
-constexpr uint32_t kWgThreads = 256;
-constexpr uint32_t kWgWaves = kWgThreads / kWave;
+constexpr uint32_t kWgThreads = 256;         // whole-GPU launches: 8 such workgroups per CU
+constexpr uint32_t kBudgetWgThreads = 1024;  // CU-budgeted launches: one 16-wave workgroup per budgeted CU
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -431,8 +431,8 @@ __global__ __launch_bounds__(kWgThreads) void k_sqe(const SqeArgs a, const tutti
   emit_sqes(a, l, n_req, 0, gridDim.x);
 }
 
-template <int DIR, bool HND, int U, int NT>
-__global__ __launch_bounds__(kWgThreads) void k_move(const MoveArgs a, const tutti_extent *__restrict__ ext,
+template <int DIR, bool HND, int U, int NT, int WG>
+__global__ __launch_bounds__(WG) void k_move(const MoveArgs a, const tutti_extent *__restrict__ ext,
                                                       uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
@@ -441,12 +441,13 @@ __global__ __launch_bounds__(kWgThreads) void k_move(const MoveArgs a, const tut
 }
 
 // One layer's restore: every workgroup redoes the (tiny) scan into its own LDS with its first
-// wavefront.  The first `copy_wgs` workgroups then unpack; the workgroups after them (at least
-// one) write the entries, and the last of those also publishes extents and totals, so none of the
-// bookkeeping sits in front of the copy.
-template <bool HND, int U, int NT>
-__global__ __launch_bounds__(kWgThreads) void k_restore(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
-                                                         uint32_t copy_wgs) {
+// wavefront.  The first `copy_wgs` workgroups unpack; the last `sqe_wgs` workgroups of the grid
+// write the entries, and the very last one also publishes extents and totals.  A whole-GPU launch
+// adds the entry writers behind the copy workgroups so no bookkeeping sits in front of the copy;
+// a CU-budgeted launch has no workgroup to spare and its last workgroup does both jobs.
+template <bool HND, int U, int NT, int WG>
+__global__ __launch_bounds__(WG) void k_restore(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
+                                                 uint32_t copy_wgs, uint32_t sqe_wgs) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
   if (threadIdx.x < kWave) {
@@ -455,15 +456,14 @@ __global__ __launch_bounds__(kWgThreads) void k_restore(const MoveArgs m, const 
                       publish ? a.totals : nullptr);
   }
   __syncthreads();
-  if (blockIdx.x < copy_wgs)
-    move_items<kUnpack, HND, U, NT>(m, l, a.n_req, copy_wgs);
-  else
-    emit_sqes(q, l, a.n_req, copy_wgs, gridDim.x - copy_wgs);
+  const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
+  if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
+  if (blockIdx.x < copy_wgs) move_items<kUnpack, HND, U, NT>(m, l, a.n_req, copy_wgs);
 }
 
 // Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.
-template <int U, int NT>
-__global__ __launch_bounds__(kWgThreads) void k_copy(unsigned char *__restrict__ dst,
+template <int U, int NT, int WG>
+__global__ __launch_bounds__(WG) void k_copy(unsigned char *__restrict__ dst,
                                                       const unsigned char *__restrict__ src, uint64_t bytes) {
   constexpr uint64_t kSlice = kWave * 16ull * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
