@@ -167,6 +167,10 @@ int tutti_abi_describe(uint32_t *out, uint32_t cap);
 /* Launch tuning, for experiments: wgs_per_cu persistent workgroups per budgeted CU (0 = default),
  * unroll = 16-byte accesses in flight per lane (0 = default; 1, 2, 4 or 8). */
 int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll);
+/* Head-major pools: 0 = the library chooses (token tiles transposed in LDS when a (token, head) row is
+ * shorter than 128 bytes and T, h and the row size are powers of two; else 16 bytes per lane straight
+ * between the two orders), 1 = always the direct copy, 2 = through LDS whenever the shape allows. */
+int tutti_set_hnd_mode(uint32_t mode);
 /* Experiment switch for the copy loops: bit 0 = non-temporal 16-byte loads, bit 1 = non-temporal
  * 16-byte stores (default 3 = both). */
 int tutti_set_nontemporal(uint32_t mask);

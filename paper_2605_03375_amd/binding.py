@@ -33,7 +33,7 @@ SQE_DTYPE = np.dtype({"names": ["opcode", "kind", "layer", "file_id", "file_off"
 
 EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
            "tutti_copy_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
-           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal"]
+           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"]
 
 
 class tutti_pool(C.Structure):
@@ -81,9 +81,10 @@ def lib():
         L.tutti_abi_describe.argtypes = [vp, u32]
         L.tutti_set_tuning.argtypes = [u32, u32]
         L.tutti_set_nontemporal.argtypes = [u32]
+        L.tutti_set_hnd_mode.argtypes = [u32]
         for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
                      "tutti_layer_restore", "tutti_copy_baseline", "tutti_last_hip_error", "tutti_cu_count",
-                     "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal"):
+                     "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"):
             getattr(L, name).restype = C.c_int
         _LIB = L
     return _LIB
@@ -204,3 +205,7 @@ def tutti_set_tuning(wgs_per_cu=0, unroll=0):
 
 def tutti_set_nontemporal(mask=3):
     return _check("tutti_set_nontemporal", lib().tutti_set_nontemporal(int(mask)))
+
+
+def tutti_set_hnd_mode(mode=0):
+    return _check("tutti_set_hnd_mode", lib().tutti_set_hnd_mode(int(mode)))

@@ -19,6 +19,7 @@ thread_local int t_last_hip = 0;
 std::atomic<uint32_t> g_wgs_per_cu{0};
 std::atomic<uint32_t> g_unroll{0};
 std::atomic<uint32_t> g_nontemporal{3};  // bit 0: loads, bit 1: stores
+std::atomic<uint32_t> g_hnd_mode{0};     // head-major pools: 0 = choose, 1 = direct, 2 = through LDS when possible
 
 constexpr uint32_t kDefaultWgsPerCu = 8;     // whole-GPU launches: 8 x 256 threads = 32 wavefronts per CU
 constexpr uint32_t kDefaultUnroll = 4;       // 4 x 16 B in flight per lane: 4 KiB slices
@@ -85,7 +86,17 @@ struct Launch {
   uint32_t wg_threads;   // kWgThreads, or kBudgetWgThreads under a CU budget
   uint32_t unroll;
   uint32_t nontemporal;  // bit 0: loads, bit 1: stores
+  bool hnd_lds;          // head-major pool moved through LDS; unroll then holds 16-byte units per thread per tile
+  uint32_t tile_lds;     // bytes of LDS for the tile
 };
+
+constexpr uint32_t kHndTileCap = 32768;      // largest tile staged in LDS
+constexpr uint32_t kDynLdsCap = 65536;       // dynamic LDS a launch may ask for without opting in to more
+uint32_t log2u(uint32_t x) {
+  uint32_t n = 0;
+  while ((1u << n) < x) ++n;
+  return n;
+}
 
 // Launch shape.  Whole GPU (cu_budget = 0): persistent 256-thread workgroups, enough for every
 // item to have its own wavefront, at most wgs_per_cu per CU.  Under a CU budget B: B workgroups of
@@ -98,6 +109,8 @@ int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
   uint32_t u = g_unroll.load(std::memory_order_relaxed);
   out->nontemporal = g_nontemporal.load(std::memory_order_relaxed) & 3u;
   if (cu_budget) {
+    out->hnd_lds = false;
+    out->tile_lds = 0;
     out->wg_threads = kBudgetWgThreads;
     out->unroll = u ? u : kBudgetUnroll;
     const uint64_t waves = kBudgetWgThreads / kWave;
@@ -112,15 +125,19 @@ int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
   const uint64_t waves = kWgThreads / kWave;
   uint64_t need = (n_wave_items + waves - 1) / waves;
   if (need == 0) need = 1;
+  out->hnd_lds = false;
+  out->tile_lds = 0;
   out->wg_threads = kWgThreads;
   out->unroll = u ? u : kDefaultUnroll;
   out->grid = static_cast<uint32_t>(need < cap ? need : cap);
   return TUTTI_OK;
 }
 
+// Fills the kernel arguments and settles how a head-major pool is moved (L->hnd_lds, L->unroll,
+// L->tile_lds).  L must already hold the workgroup size and default unroll from plan_launch.
 int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t *d_block_table, uint32_t table_len,
-                   const void *d_stage, uint64_t stage_cap, uint32_t *d_status, uint32_t unroll, MoveArgs *m) {
-  const uint32_t slice = kWave * 16u * unroll;
+                   const void *d_stage, uint64_t stage_cap, uint32_t *d_status, uint32_t n_req, Launch *L,
+                   MoveArgs *m) {
   m->k_base = static_cast<unsigned char *>(pool->k_base);
   m->v_base = static_cast<unsigned char *>(pool->v_base);
   m->stage = static_cast<unsigned char *>(const_cast<void *>(d_stage));
@@ -131,13 +148,104 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
   m->num_blocks = pool->num_blocks;
   m->block_bytes = block_bytes;
   m->table_len = table_len;
-  m->slices_per_block = static_cast<uint32_t>((static_cast<uint64_t>(block_bytes) + slice - 1) / slice);
   m->row_bytes = pool->head_dim * pool->elt_bytes;
   m->block_tokens = pool->block_tokens;
   m->num_kv_heads = pool->num_kv_heads;
+  m->row_shift = m->head_shift = m->token_shift = m->tile_shift = m->lds_pitch = 0;
+
+  L->hnd_lds = false;
+  L->tile_lds = 0;
+  const uint32_t mode = g_hnd_mode.load(std::memory_order_relaxed);
+  if (pool->pool_layout == TUTTI_LAYOUT_HND && mode != 1) {
+    // through LDS: T, h and the row size powers of two, one token of all heads within the tile cap,
+    // the tile a whole number (1, 2, 4 or 8) of 16-byte units per thread, and LDS to hold it
+    const uint32_t row = m->row_bytes, T = pool->block_tokens, h = pool->num_kv_heads;
+    const uint64_t group = static_cast<uint64_t>(h) * row;
+    if (is_pow2(row) && is_pow2(T) && is_pow2(h) && row >= 16 && group <= kHndTileCap) {
+      uint32_t tile_tokens = static_cast<uint32_t>(kHndTileCap / group);
+      if (tile_tokens > T) tile_tokens = T;
+      const uint32_t tile_bytes = tile_tokens * static_cast<uint32_t>(group);
+      const uint32_t per_thread = tile_bytes / (L->wg_threads * 16u);
+      const uint32_t pitch = static_cast<uint32_t>(group) + row;
+      const uint64_t lds = static_cast<uint64_t>(align16(req_lds_bytes(n_req))) + static_cast<uint64_t>(tile_tokens) * pitch;
+      const bool fits = tile_bytes % (L->wg_threads * 16u) == 0 && per_thread >= 1 && per_thread <= 8 &&
+                        is_pow2(per_thread) && lds <= kDynLdsCap;
+      // worth it when a row is shorter than a 128-byte line (or when asked for)
+      if (fits && (mode == 2 || row < 128)) {
+        L->hnd_lds = true;
+        L->unroll = per_thread;
+        L->tile_lds = tile_tokens * pitch;
+        m->row_shift = log2u(row);
+        m->head_shift = log2u(h);
+        m->token_shift = log2u(T);
+        m->tile_shift = log2u(tile_tokens);
+        m->lds_pitch = pitch;
+        m->slices_per_block = T / tile_tokens;
+      }
+    }
+  }
+  if (!L->hnd_lds) {
+    const uint32_t slice = kWave * 16u * L->unroll;
+    m->slices_per_block = static_cast<uint32_t>((static_cast<uint64_t>(block_bytes) + slice - 1) / slice);
+  }
   // the kernels number work items in 32 bits
   if (2ull * table_len * m->slices_per_block > 0xffffffffull) return TUTTI_ERANGE;
   return TUTTI_OK;
+}
+
+// Work items of a move, counted in wavefronts' worth for plan_launch (an LDS tile occupies a whole workgroup).
+uint64_t move_wave_items(const Launch &L, const MoveArgs &m) {
+  const uint64_t items = 2ull * m.table_len * m.slices_per_block;
+  return L.hnd_lds ? items * (L.wg_threads / kWave) : items;
+}
+
+template <int DIR>
+hipError_t launch_move_lds(const Launch &L, uint32_t lds, hipStream_t s, const MoveArgs &m, const tutti_extent *ext,
+                           uint32_t n_req) {
+#define TUTTI_LDS_CASE(PT)                                                                                        \
+  case PT:                                                                                                        \
+    if (L.wg_threads == kWgThreads)                                                                               \
+      hipLaunchKernelGGL((k_move_lds<DIR, PT, kWgThreads>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext,        \
+                         n_req);                                                                                  \
+    else                                                                                                          \
+      hipLaunchKernelGGL((k_move_lds<DIR, PT, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), lds, s,    \
+                         m, ext, n_req);                                                                          \
+    break;
+  switch (L.unroll) {
+    TUTTI_LDS_CASE(1)
+    TUTTI_LDS_CASE(2)
+    TUTTI_LDS_CASE(4)
+    TUTTI_LDS_CASE(8)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef TUTTI_LDS_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_restore_lds(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
+                              const SqeArgs &q, const LayoutArgs &a) {
+  const uint32_t copy_wgs = L.grid;
+  const dim3 grid(L.wg_threads == kWgThreads ? L.grid + sqe_wgs : L.grid);
+#define TUTTI_LDS_CASE(PT)                                                                                        \
+  case PT:                                                                                                        \
+    if (L.wg_threads == kWgThreads)                                                                               \
+      hipLaunchKernelGGL((k_restore_lds<PT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,       \
+                         sqe_wgs);                                                                                \
+    else                                                                                                          \
+      hipLaunchKernelGGL((k_restore_lds<PT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q, a,     \
+                         copy_wgs, sqe_wgs);                                                                      \
+    break;
+  switch (L.unroll) {
+    TUTTI_LDS_CASE(1)
+    TUTTI_LDS_CASE(2)
+    TUTTI_LDS_CASE(4)
+    TUTTI_LDS_CASE(8)
+    default:
+      return hipErrorInvalidValue;
+  }
+#undef TUTTI_LDS_CASE
+  return hipGetLastError();
 }
 
 template <int DIR, bool HND>
@@ -227,18 +335,25 @@ int move_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_exte
   if (!aligned16(d_stage)) return TUTTI_EINVAL;
   if (n_req == 0 || table_len == 0) return TUTTI_OK;  // nothing to move
   Launch L;
-  // the unroll decides the slice size, so read the tuning before sizing the grid
+  // the workgroup size and unroll decide the item size, so settle them before sizing the grid
   rc = plan_launch(cu_budget, 0, &L);
   if (rc) return rc;
   MoveArgs m;
-  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, L.unroll, &m);
+  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, n_req, &L, &m);
   if (rc) return rc;
-  rc = plan_launch(cu_budget, 2ull * table_len * m.slices_per_block, &L);
+  Launch G;
+  rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;
+  L.grid = G.grid;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const uint32_t lds = req_lds_bytes(n_req);
-  hipError_t e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_move<DIR, true>(L, lds, s, m, d_extents, n_req)
-                                                          : launch_move<DIR, false>(L, lds, s, m, d_extents, n_req);
+  hipError_t e;
+  if (L.hnd_lds) {
+    e = launch_move_lds<DIR>(L, align16(req_lds_bytes(n_req)) + L.tile_lds, s, m, d_extents, n_req);
+  } else {
+    const uint32_t lds = req_lds_bytes(n_req);
+    e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_move<DIR, true>(L, lds, s, m, d_extents, n_req)
+                                                 : launch_move<DIR, false>(L, lds, s, m, d_extents, n_req);
+  }
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
@@ -337,10 +452,12 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   rc = plan_launch(cu_budget, 0, &L);
   if (rc) return rc;
   MoveArgs m;
-  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, L.unroll, &m);
+  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, n_req, &L, &m);
   if (rc) return rc;
-  rc = plan_launch(cu_budget, 2ull * table_len * m.slices_per_block, &L);
+  Launch G;
+  rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;
+  L.grid = G.grid;
   // extra workgroups behind the copy ones write the entries (one lane per 16-byte quarter)
   uint64_t sqe_need = (4ull * sqe_cap + L.wg_threads - 1) / L.wg_threads;
   if (sqe_need < 1) sqe_need = 1;
@@ -366,9 +483,14 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   a.n_req = n_req;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const uint32_t lds = req_lds_bytes(n_req);
-  hipError_t e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_restore<true>(L, sqe_wgs, lds, s, m, q, a)
-                                                          : launch_restore<false>(L, sqe_wgs, lds, s, m, q, a);
+  hipError_t e;
+  if (L.hnd_lds) {
+    e = launch_restore_lds(L, sqe_wgs, align16(req_lds_bytes(n_req)) + L.tile_lds, s, m, q, a);
+  } else {
+    const uint32_t lds = req_lds_bytes(n_req);
+    e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_restore<true>(L, sqe_wgs, lds, s, m, q, a)
+                                                 : launch_restore<false>(L, sqe_wgs, lds, s, m, q, a);
+  }
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
@@ -480,6 +602,14 @@ int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll) {
   if (wgs_per_cu > 1024) return TUTTI_ERANGE;
   g_wgs_per_cu.store(wgs_per_cu, std::memory_order_relaxed);
   g_unroll.store(unroll, std::memory_order_relaxed);
+  return TUTTI_OK;
+}
+
+// Head-major pools: 0 = library chooses (through LDS when a row is shorter than 128 bytes and the
+// shape allows it), 1 = always the direct 16-byte permuted copy, 2 = through LDS whenever the shape allows.
+int tutti_set_hnd_mode(uint32_t mode) {
+  if (mode > 2u) return TUTTI_EINVAL;
+  g_hnd_mode.store(mode, std::memory_order_relaxed);
   return TUTTI_OK;
 }
 

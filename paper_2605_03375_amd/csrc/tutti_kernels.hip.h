@@ -4,7 +4,9 @@
 //   k_layout        one wavefront: extents of all requests by a wave-level prefix scan
 //   k_sqe           submission entries from extents, four lanes per 64-byte entry
 //   k_move          pack / unpack between paged blocks and objects, extents given
+//   k_move_lds      the same for head-major pools with short rows: token-tile transposed in LDS
 //   k_restore       one layer's restore in one launch: scan + entries + unpack
+//   k_restore_lds   the same with the LDS-staged transpose
 //   k_copy          plain contiguous copy with the same access shape (measurement ceiling)
 //
 // Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
@@ -243,6 +245,13 @@ struct MoveArgs {
   uint32_t row_bytes;
   uint32_t block_tokens;
   uint32_t num_kv_heads;
+  // head-major pools moved through LDS (T, h and the row size are powers of two there):
+  // a tile is 2^tile_shift tokens x all heads; slices_per_block then counts tiles
+  uint32_t row_shift;    // log2(row_bytes)
+  uint32_t head_shift;   // log2(num_kv_heads)
+  uint32_t token_shift;  // log2(block_tokens)
+  uint32_t tile_shift;   // log2(tokens per tile)
+  uint32_t lds_pitch;    // bytes between consecutive tokens of the tile in LDS: h*row_bytes + row_bytes
 };
 
 constexpr int kPack = 0;   // pool -> object
@@ -409,6 +418,92 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Head-major pools with short rows.  A block is stored [h][T][row]; the object wants [T][h][row].
+// Moving 16 bytes per lane straight between the two orders touches the pool in row-sized pieces,
+// which is fine while a row fills whole 128-byte lines and poor below that (partial-line writes).
+// Here a workgroup stages one tile (2^tile_shift tokens x all heads) in LDS instead: the object
+// side is read or written as one contiguous run, the pool side as h runs of tile_tokens*row bytes,
+// and the transpose happens in LDS.  Tokens are padded by one row in LDS so that the lanes of a
+// wavefront, which walk the rows of one head, fall on different banks.
+// PT = 16-byte units per thread per tile (tile bytes = PT * 16 * workgroup size).
+// ------------------------------------------------------------------------------------------
+template <int DIR, int PT, int WG>
+__device__ __forceinline__ void move_items_hnd_lds(const MoveArgs a, const ReqLds l, uint32_t n_req,
+                                                   uint32_t copy_wgs, unsigned char *tile) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
+  const uint32_t n_items = 2u * total_blocks * a.slices_per_block;
+  const uint32_t rs = a.row_shift;
+  const uint32_t gs = a.row_shift + a.head_shift;  // log2 bytes of one token across all heads
+  const uint32_t hr = a.tile_shift + a.row_shift;  // log2 bytes of one head's run inside the tile
+  const uint32_t g_mask = (1u << gs) - 1u, hr_mask = (1u << hr) - 1u, r_mask = (1u << rs) - 1u;
+
+  for (uint32_t it = blockIdx.x; it < n_items; it += copy_wgs) {
+    const Item d = decode_item(a, l, n_req, it, tid);  // workgroup-uniform; thread 0 reports
+    const uint32_t id = load_block_id(a, d);
+    if (d.obj_ptr != nullptr && id < a.num_blocks) {
+      const uint32_t t0 = d.s << a.tile_shift;
+      unsigned char *blk = (d.kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
+      unsigned char *obj_tile = d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes + (static_cast<uint64_t>(t0) << gs);
+      u32x4 v[PT];
+      if (DIR == kUnpack) {
+#pragma unroll
+        for (int k = 0; k < PT; ++k) v[k] = ld16<1>(obj_tile + (k * WG + tid) * 16u);
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+          const uint32_t o = (k * WG + tid) * 16u;
+          *reinterpret_cast<u32x4 *>(tile + (o >> gs) * a.lds_pitch + (o & g_mask)) = v[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+          const uint32_t p = (k * WG + tid) * 16u;  // position in pool order inside the tile
+          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
+          v[k] = *reinterpret_cast<const u32x4 *>(tile + t * a.lds_pitch + (i << rs) + w);
+        }
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+          const uint32_t p = (k * WG + tid) * 16u;
+          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
+          st16<2>(blk + ((((i << a.token_shift) + t0 + t)) << rs) + w, v[k]);
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+          const uint32_t p = (k * WG + tid) * 16u;
+          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
+          v[k] = ld16<1>(blk + ((((i << a.token_shift) + t0 + t)) << rs) + w);
+        }
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+          const uint32_t p = (k * WG + tid) * 16u;
+          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
+          *reinterpret_cast<u32x4 *>(tile + t * a.lds_pitch + (i << rs) + w) = v[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < PT; ++k) {
+          const uint32_t o = (k * WG + tid) * 16u;
+          v[k] = *reinterpret_cast<const u32x4 *>(tile + (o >> gs) * a.lds_pitch + (o & g_mask));
+        }
+#pragma unroll
+        for (int k = 0; k < PT; ++k) st16<2>(obj_tile + (k * WG + tid) * 16u, v[k]);
+      }
+      __syncthreads();  // the tile is free again
+    } else if (d.obj_ptr != nullptr && tid == 0 && d.s == 0 && a.status) {
+      atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
+    }
+    if (DIR == kPack && d.obj_ptr != nullptr && d.j + 1 == d.n && d.s + 1 == a.slices_per_block) {
+      const uint64_t used = static_cast<uint64_t>(d.n) * a.block_bytes;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      for (uint64_t o = used + tid * 16ull; o < d.obj_bytes; o += WG * 16ull) st16<0>(d.obj_ptr + o, zero);
+    }
+  }
+}
+
+__host__ __device__ constexpr uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
+
 struct LayoutArgs {
   const uint32_t *n_blocks;
   tutti_extent *extents;
@@ -440,6 +535,15 @@ __global__ __launch_bounds__(WG) void k_move(const MoveArgs a, const tutti_exten
   move_items<DIR, HND, U, NT>(a, l, n_req, gridDim.x);
 }
 
+template <int DIR, int PT, int WG>
+__global__ __launch_bounds__(WG) void k_move_lds(const MoveArgs a, const tutti_extent *__restrict__ ext,
+                                                  uint32_t n_req) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, n_req);
+  lds_from_extents(ext, n_req, l);
+  move_items_hnd_lds<DIR, PT, WG>(a, l, n_req, gridDim.x, smem + align16(req_lds_bytes(n_req)));
+}
+
 // One layer's restore: every workgroup redoes the (tiny) scan into its own LDS with its first
 // wavefront.  The first `copy_wgs` workgroups unpack; the last `sqe_wgs` workgroups of the grid
 // write the entries, and the very last one also publishes extents and totals.  A whole-GPU launch
@@ -459,6 +563,23 @@ __global__ __launch_bounds__(WG) void k_restore(const MoveArgs m, const SqeArgs 
   const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
   if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
   if (blockIdx.x < copy_wgs) move_items<kUnpack, HND, U, NT>(m, l, a.n_req, copy_wgs);
+}
+
+template <int PT, int WG>
+__global__ __launch_bounds__(WG) void k_restore_lds(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
+                                                     uint32_t copy_wgs, uint32_t sqe_wgs) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, a.n_req);
+  if (threadIdx.x < kWave) {
+    const bool publish = blockIdx.x + 1 == gridDim.x;
+    wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
+                      publish ? a.totals : nullptr);
+  }
+  __syncthreads();
+  const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
+  if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
+  if (blockIdx.x < copy_wgs)
+    move_items_hnd_lds<kUnpack, PT, WG>(m, l, a.n_req, copy_wgs, smem + align16(req_lds_bytes(a.n_req)));
 }
 
 // Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.

@@ -24,9 +24,11 @@ def H():
 def _default_tuning():
     B.tutti_set_tuning(0, 0)
     B.tutti_set_nontemporal(3)
+    B.tutti_set_hnd_mode(0)
     yield
     B.tutti_set_tuning(0, 0)
     B.tutti_set_nontemporal(3)
+    B.tutti_set_hnd_mode(0)
 
 
 def say(*a):
@@ -82,6 +84,58 @@ def test_launch_tuning_does_not_change_results(orc, H, unroll, nt):
         c = H.LayerCase(T=16, h=5, d=40, e=2, N=200, n_blocks=[9, 0, 70, 31], table=rng.permutation(200)[:110],
                         align=4096, chunk=8192, L=2, layout=layout, name=f"tuning{unroll}")
         H.check_everything(orc, c)
+
+
+# ------------------------------------------------------------------ head-major pools: direct copy and LDS-staged transpose
+
+HND_SHAPES = [
+    # T, h, d, e, N, n_blocks, chunk
+    (16, 64, 16, 2, 300, [40, 0, 7, 129], 2 << 20),   # 32-byte rows: one 32 KiB tile per block
+    (16, 32, 32, 2, 300, [3, 90, 1], 32768),          # 64-byte rows
+    (16, 8, 128, 2, 300, [64, 65], 2 << 20),          # 256-byte rows (the 8B shape)
+    (64, 8, 128, 2, 64, [9, 20], 131072),             # 128 KiB blocks: four tiles per block
+    (16, 2, 64, 2, 256, [32, 5], 4096),               # Tiny's block: a 4 KiB tile
+    (4, 4, 8, 2, 64, [10, 3], 4096),                  # 16-byte rows, tile too small for LDS: direct copy
+    (16, 6, 32, 2, 128, [11, 12], 8192),              # head count not a power of two: direct copy
+    (32, 16, 64, 1, 200, [17, 0, 60], 16384),         # one-byte elements, 64-byte rows
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2], ids=["auto", "direct", "lds"])
+@pytest.mark.parametrize("shape", HND_SHAPES, ids=[f"T{t}h{h}d{d}e{e}" for t, h, d, e, *_ in HND_SHAPES])
+def test_head_major_paths(orc, H, shape, mode):
+    T, h, d, e, N, n_blocks, C = shape
+    say("hnd", shape, "mode", mode)
+    B.tutti_set_hnd_mode(mode)
+    rng = np.random.default_rng(500 + T + h)
+    c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=n_blocks, table=rng.permutation(N)[: sum(n_blocks)], chunk=C, L=2,
+                    layout=1, seed=h, name=f"hnd{shape}m{mode}")
+    H.check_everything(orc, c)
+    H.check_everything(orc, c, cu_budget=3)
+
+
+def test_head_major_lds_edge_cases(orc, H):
+    """Bad ids, a small staging buffer and the 2048-request limit through the LDS-staged path."""
+    say("hnd lds edges")
+    B.tutti_set_hnd_mode(2)
+    table = np.array([3, 999, 5, 16, 7, 1], np.uint32)
+    c = H.LayerCase(T=16, h=32, d=32, e=2, N=16, n_blocks=[4, 2], table=table, layout=1, name="hnd_bad_ids")
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    H.check_pack(orc, c, ext, o_ext, o_tot)
+    H.check_unpack(orc, c, ext, o_ext, o_tot)
+    H.check_layer_restore(orc, c)
+    cap = int(o_ext["stage_off"][1]) + 4096
+    H.check_pack(orc, c, ext, o_ext, o_tot, stage_cap=cap)
+    H.check_layer_restore(orc, c, stage_cap=cap, sqe_cap=1)
+    rng = np.random.default_rng(6)
+    n = rng.integers(0, 3, size=B.MAX_REQ).astype(np.uint32)
+    N = int(n.sum()) + 9
+    c = H.LayerCase(T=16, h=16, d=16, e=2, N=N, n_blocks=n, table=rng.permutation(N)[: int(n.sum())], chunk=8192,
+                    layout=1, name="hnd_max_req")   # 2048 requests: no LDS left for a tile, falls back to direct
+    H.check_everything(orc, c)
+    c = H.LayerCase(T=16, h=16, d=16, e=2, N=N, n_blocks=n[:700], table=rng.permutation(N)[: int(n[:700].sum())],
+                    chunk=8192, layout=1, name="hnd_700_req")
+    H.check_everything(orc, c)
 
 
 # ------------------------------------------------------------------ edge cases
