@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the copy-ceiling / entry-rate legs")
     ap.add_argument("--corun", action="store_true", help="also run the CU-budget sweep beside a GEMM (config 5)")
+    ap.add_argument("--other-configs", action="store_true",
+                    help="also time the per-layer restore of configs 3 and 4 (frees config 2's pool first)")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--plain-loads", action="store_true", help="disable non-temporal loads/stores")
@@ -204,12 +206,73 @@ def main():
         out["copy_ceiling"]["restore_vs_copy"] = round(out["restore"]["traffic_GBps"] /
                                                        out["copy_ceiling"]["traffic_GBps"], 4)
         out["sqe"] = sqe_rate(torch, B, W, dev)
+        out["sqe"]["direct_to_block"] = direct_rate(torch, B, W, dev)
         log(f"[bench] copy ceiling {out['copy_ceiling']}; entries {out['sqe']}")
     if args.corun:
         out["corun"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], stages[0], geom, payload_layer)
+    if args.other_configs:
+        del pools, planes, stages, restore_layers, save_layers
+        torch.cuda.empty_cache()
+        out["other_configs"] = {
+            "config3_batch64_zipf": restore_leg(torch, B, W.batch64_zipf(), dev, max_layers=8),
+            "config4_llama70b_128k": restore_leg(torch, B, W.llama70b_128k(), dev, max_layers=80),
+        }
     print(json.dumps(out), flush=True)
+
+
+def restore_leg(torch, B, w, dev, max_layers, reps=5):
+    """Per-layer tutti_layer_restore of another workload at its real pool size: as many layers resident
+    as fit (each with its own planes and staging buffer, so launches stay cold), contents left as
+    allocated (timing only; parity for these shapes is in the tests)."""
+    s = w.shape
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    plane_bytes = s.num_blocks * bb
+    n_tab = int(w.block_table.size)
+    payload = 2 * n_tab * bb
+    n_sqe = int(2 * np.sum((w.n_blocks.astype(np.int64) * bb + w.chunk_bytes - 1) // w.chunk_bytes))
+    free, _ = torch.cuda.mem_get_info()
+    L = max(1, min(max_layers, s.num_layers, int((free - (8 << 30)) // (2 * plane_bytes + payload))))
+    geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
+                head_dim=s.head_dim, elt_bytes=s.elt_bytes)
+    cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
+    planes = [(torch.empty(plane_bytes, dtype=torch.uint8, device=dev),
+               torch.empty(plane_bytes, dtype=torch.uint8, device=dev)) for _ in range(L)]
+    pools = [B.make_pool(k, v, **geom) for k, v in planes]
+    stages = [torch.empty(payload, dtype=torch.uint8, device=dev) for _ in range(L)]
+    d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
+    d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
+    d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
+    ext = torch.zeros(w.n_req * 32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    sqe = torch.zeros(n_sqe * 64, dtype=torch.uint8, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def train():
+        for l in range(L):
+            B.tutti_layer_restore(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, stages[l], payload,
+                                  stages[l].data_ptr(), 1, ext, tot, sqe, n_sqe, 0, status)
+
+    train()
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        train()
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) * 1e3 / L)
+    us = median(times)
+    assert int(status.item()) == 0 and int(tot[1].item()) == n_sqe
+    res = {"layers_resident": L, "layers_model": s.num_layers, "pool_blocks": s.num_blocks, "requests": w.n_req,
+           "blocks_per_layer": n_tab, "payload_bytes_per_layer": payload, "entries_per_layer": n_sqe,
+           "us_per_layer": round(us, 2), "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
+           "traffic_GBps": round(2 * payload / (us * 1e-6) / 1e9, 1),
+           "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
+    log(f"[bench] {w.name}: {res}")
+    return res
 
 
 def copy_ceiling(torch, B, stages, nbytes, dev, reps=5):
@@ -263,6 +326,46 @@ def sqe_rate(torch, B, W, dev, reps=50):
         res[label] = {"entries_per_layer": n_sqe, "us_per_launch": round(us, 2),
                       "sqes_per_s": round(n_sqe / (us * 1e-6), 0),
                       "regime": "launch-latency bound" if us < 20 else "HBM-write bound"}
+    return res
+
+
+def direct_rate(torch, B, W, dev, reps=50):
+    """Direct-to-block mode (no staging copy): mapping table build for config 2's pool and per-block
+    entries per second for config 3's batch (one entry per hit block and plane)."""
+    w = W.batch64_zipf(chunk_bytes=32768)
+    s = w.shape
+    geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
+                head_dim=s.head_dim, elt_bytes=s.elt_bytes)
+    pool = B.make_pool(4096, 4096, **geom)  # arithmetic only
+    cfg = B.make_cfg(w.align, 32768, s.num_layers)
+    d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
+    d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
+    d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
+    ext = torch.zeros(w.n_req * 32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    B.tutti_obj_layout(pool, cfg, d_n, w.n_req, ext, tot)
+    n_desc = 2 * s.num_blocks
+    sgl = torch.zeros(n_desc * 16, dtype=torch.uint8, device=dev)
+    n_sqe = 2 * int(w.block_table.size)
+    sqe = torch.zeros(n_sqe * 64, dtype=torch.uint8, device=dev)
+    E = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    res = {}
+    for label, fn, n in (
+            ("sgl_table", lambda i: B.tutti_sgl_table_build(pool, 1 << 40, 1 << 41, 1, sgl, n_desc), n_desc),
+            ("entries", lambda i: B.tutti_sqe_build_direct(pool, cfg, ext, w.n_req, d_tab, d_tab.numel(), d_fid,
+                                                           i % s.num_layers, B.OP_READ, sgl.data_ptr(), 1, sqe, n_sqe),
+             n_sqe)):
+        for i in range(3):
+            fn(i)
+        a, b = E(), E()
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / reps
+        res[label] = {"count": n, "us_per_launch": round(us, 2), "per_s": round(n / (us * 1e-6), 0)}
     return res
 
 

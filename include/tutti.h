@@ -151,6 +151,35 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
                         uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe,
                         uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status, void *stream);
 
+/* ---- direct-to-block mode: the paper's own data path, with no staging copy (sec. 3.1 "P2P Memory
+ * Mapping Table", sec. 3.2 "an IOCTX records the SGL address, GPU file offset, and length").
+ *
+ * 16-byte SGL descriptor of one pool block: address 8, length 4, identifier 4 (sec. 3.1). */
+typedef struct tutti_sgl {
+  uint64_t addr;
+  uint32_t len;
+  uint32_t id;
+} tutti_sgl;
+
+/* The mapping table of one layer's pool, built once at start-up (the pool never moves: sec. 3.1):
+ * d_table[b] describes K block b, d_table[num_blocks + b] describes V block b, each
+ * { plane address + b*block_stride, block_bytes, sgl_id }.  k_addr / v_addr are the addresses the
+ * descriptors should name for the planes (a bus address in a real deployment; arithmetic only here,
+ * pool->k_base / v_base are not used).  Descriptors with index >= cap are dropped (TUTTI_ST_SQE_CAP). */
+int tutti_sgl_table_build(const tutti_pool *pool, uint64_t k_addr, uint64_t v_addr, uint32_t sgl_id,
+                          tutti_sgl *d_table, uint32_t cap, uint32_t *d_status, void *stream);
+
+/* One entry per (hit block, K|V) of `layer`: index = 2*table_off_r + kind*n_r + j, in the order request
+ * ascending, K then V, block ascending.  addr = sgl_table_addr + 16*(kind*num_blocks + block id), i.e. the
+ * block's descriptor in the mapping table; len = block_bytes; file_off = (2*layer + kind)*obj_bytes_r +
+ * j*block_bytes: the GPU-file layout of the staged mode, so either mode can read what the other wrote.
+ * block_bytes must be a multiple of cfg->align (else TUTTI_EINVAL); sgl_table_addr a multiple of 16.
+ * A block id >= num_blocks (or beyond table_len) gives a no-op entry (addr 0, len 0) and TUTTI_ST_BAD_BLOCK. */
+int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents,
+                           uint32_t n_req, const uint32_t *d_block_table, uint32_t table_len,
+                           const uint32_t *d_file_id, uint32_t layer, uint32_t opcode, uint64_t sgl_table_addr,
+                           uint32_t sgl_id, tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t *d_status, void *stream);
+
 /* ---- measurement aid: a plain contiguous device-to-device copy of `bytes` (multiple of 16, both
  * pointers 16-byte aligned) with the same load/store width and launch shape as unpack: the
  * achievable ceiling the pack/unpack rates are compared with. */
@@ -161,8 +190,8 @@ const char *tutti_strerror(int code);
 int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */
 int tutti_cu_count(void);           /* compute units of the current device, or a negative TUTTI_E* */
 uint32_t tutti_version(void);       /* 0x00MMmmpp */
-/* sizeof / offsetof table of the records above (33 values: extent size + 6 offsets, sqe size + 11,
- * pool size + 9, objcfg size + 3); returns the count or TUTTI_EINVAL if cap is too small. */
+/* sizeof / offsetof table of the records above (37 values: extent size + 6 offsets, sqe size + 11,
+ * pool size + 9, objcfg size + 3, sgl size + 3); returns the count or TUTTI_EINVAL if cap is too small. */
 int tutti_abi_describe(uint32_t *out, uint32_t cap);
 /* Launch tuning, for experiments: wgs_per_cu persistent workgroups per budgeted CU (0 = default),
  * unroll = 16-byte accesses in flight per lane (0 = default; 1, 2, 4 or 8). */

@@ -45,7 +45,7 @@ static int check_geometry(const orc_pool *pool, const orc_objcfg *cfg) {
 }
 
 int orc_abi_describe(uint32_t *out, uint32_t cap) {
-  if (!out || cap < 33) return ORC_EINVAL;
+  if (!out || cap < 37) return ORC_EINVAL;
   uint32_t i = 0;
   out[i++] = sizeof(orc_extent);
   out[i++] = offsetof(orc_extent, stage_off);
@@ -80,6 +80,10 @@ int orc_abi_describe(uint32_t *out, uint32_t cap) {
   out[i++] = offsetof(orc_objcfg, align);
   out[i++] = offsetof(orc_objcfg, chunk_bytes);
   out[i++] = offsetof(orc_objcfg, num_layers);
+  out[i++] = sizeof(orc_sgl);
+  out[i++] = offsetof(orc_sgl, addr);
+  out[i++] = offsetof(orc_sgl, len);
+  out[i++] = offsetof(orc_sgl, id);
   return (int)i;
 }
 
@@ -274,6 +278,94 @@ int orc_sqe_build(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent 
         s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)c * C;
         s.addr = stage_addr + x->stage_off + (uint64_t)kind * x->obj_bytes + (uint64_t)c * C;
         s.len = (uint32_t)(left < C ? left : C);
+        s.sgl_id = sgl_id;
+        s.user_data = ((uint64_t)r << 32) | (uint32_t)i;
+        s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);
+        s.ioctx_slot = (uint32_t)(i % ORC_IOCB_SLOTS);
+        sqe[i] = s;
+      }
+    }
+  }
+  if (status && st) *status |= st;
+  return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ direct-to-block mode */
+
+/*
+ * The P2P memory mapping table of sec. 3.1: one 16-byte descriptor (address, length, identifier)
+ * per pool block, K plane first, then V plane.  The pool is fixed for the engine's lifetime, so
+ * this is computed once.
+ */
+int orc_sgl_table_build(const orc_pool *pool, uint64_t k_addr, uint64_t v_addr, uint32_t sgl_id, orc_sgl *table,
+                        uint32_t cap, uint32_t *status) {
+  if (!pool) return ORC_EINVAL;
+  const uint32_t bb = orc_block_bytes(pool);
+  if (bb == 0 || bb % 16 != 0 || pool->num_blocks == 0) return ORC_EINVAL;
+  if (pool->block_stride < bb || pool->block_stride % 16 != 0) return ORC_EINVAL;
+  if (cap > 0 && !table) return ORC_EINVAL;
+  uint32_t st = 0;
+  for (uint32_t kind = 0; kind < 2; ++kind) {
+    for (uint32_t b = 0; b < pool->num_blocks; ++b) {
+      uint64_t i = (uint64_t)kind * pool->num_blocks + b;
+      if (i >= cap) {
+        st |= ORC_ST_SQE_CAP;
+        continue;
+      }
+      table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;
+      table[i].len = bb;
+      table[i].id = sgl_id;
+    }
+  }
+  if (status && st) *status |= st;
+  return ORC_OK;
+}
+
+/*
+ * Entries of the paper's own data path: each hit block is one object (sec. 3.1, "representing each
+ * memory block as one object") and one I/O context whose SGL address is the block's descriptor in
+ * the mapping table (sec. 3.2).  The GPU-file layout is the one of the staged mode.
+ */
+int orc_sqe_build_direct(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                         const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint32_t opcode,
+                         uint64_t sgl_table_addr, uint32_t sgl_id, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  const uint64_t bb = orc_block_bytes(pool);
+  if (bb % cfg->align != 0) return ORC_EINVAL;
+  if (n_req > 0 && (!extents || !file_id)) return ORC_EINVAL;
+  if (sqe_cap > 0 && !sqe) return ORC_EINVAL;
+  if (opcode != ORC_OP_READ && opcode != ORC_OP_WRITE) return ORC_EINVAL;
+  if (layer >= cfg->num_layers) return ORC_EINVAL;
+  if (sgl_table_addr % 16 != 0) return ORC_EINVAL;
+  uint64_t n_tab = 0;
+  for (uint32_t r = 0; r < n_req; ++r) n_tab += extents[r].n_blocks;
+  if (n_tab > 0 && !block_table) return ORC_EINVAL;
+  uint32_t st = 0;
+
+  for (uint32_t r = 0; r < n_req; ++r) {
+    const orc_extent *x = &extents[r];
+    for (uint32_t kind = 0; kind < 2; ++kind) {
+      for (uint32_t j = 0; j < x->n_blocks; ++j) {
+        uint64_t i = 2ull * x->table_off + (uint64_t)kind * x->n_blocks + j;
+        if (i >= sqe_cap) {
+          st |= ORC_ST_SQE_CAP;
+          continue;
+        }
+        uint32_t id = block_table[(uint64_t)x->table_off + j];
+        orc_sqe s;
+        memset(&s, 0, sizeof s);
+        s.opcode = (uint8_t)opcode;
+        s.kind = (uint8_t)kind;
+        s.layer = (uint16_t)layer;
+        s.file_id = file_id[r];
+        s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)j * bb;
+        if (id < pool->num_blocks) {
+          s.addr = sgl_table_addr + 16ull * ((uint64_t)kind * pool->num_blocks + id);
+          s.len = (uint32_t)bb;
+        } else {
+          st |= ORC_ST_BAD_BLOCK; /* a no-op entry: nothing to transfer */
+        }
         s.sgl_id = sgl_id;
         s.user_data = ((uint64_t)r << 32) | (uint32_t)i;
         s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);

@@ -101,7 +101,8 @@ typedef struct {
 
 /* Size/offset table of the records above, for the cross-check against the library's header:
  * out[0..]: sizeof(extent), offsets of its 6 fields, sizeof(sqe), offsets of its 11 fields,
- * sizeof(pool), offsets of its 9 fields, sizeof(objcfg), offsets of its 3 fields (33 values). */
+ * sizeof(pool), offsets of its 9 fields, sizeof(objcfg), offsets of its 3 fields, sizeof(sgl), offsets of
+ * its 3 fields (37 values). */
 int orc_abi_describe(uint32_t *out, uint32_t cap);
 
 /* T*h*d*e, or 0 if any factor is 0 or the product does not fit 32 bits. */
@@ -132,6 +133,32 @@ int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_
                       const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, const void *stage,
                       uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents,
                       uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
+
+/* ---- direct-to-block mode: the paper's own data path, no staging copy (sec. 3.1, "P2P Memory
+ * Mapping Table"; sec. 3.2: an I/O context records the SGL address, the GPU-file offset and the length).
+ *
+ * 16-byte SGL descriptor of one pool block: address 8, length 4, identifier 4. */
+typedef struct {
+  uint64_t addr;
+  uint32_t len;
+  uint32_t id;
+} orc_sgl;
+
+/* The mapping table of one layer's pool, computed once at start-up: descriptor b describes K block b,
+ * descriptor num_blocks + b describes V block b: { base + b*block_stride, block_bytes, sgl_id }.
+ * k_addr / v_addr are the addresses the descriptors should name for the two planes (arithmetic only).
+ * Descriptors with index >= cap are not written (ORC_ST_SQE_CAP). */
+int orc_sgl_table_build(const orc_pool *pool, uint64_t k_addr, uint64_t v_addr, uint32_t sgl_id, orc_sgl *table,
+                        uint32_t cap, uint32_t *status);
+
+/* One entry per (hit block, K|V) of one layer, in the order request ascending, K then V, block ascending:
+ * index = 2*table_off_r + kind*n_r + j.  addr = sgl_table_addr + 16*(kind*num_blocks + id) (the block's
+ * descriptor), len = block_bytes, file_off = (2*layer + kind)*obj_bytes_r + j*block_bytes, i.e. the same
+ * GPU-file layout as the staged mode.  block_bytes must be a multiple of the alignment unit.  A block id
+ * >= num_blocks yields an entry with addr = 0 and len = 0 and sets ORC_ST_BAD_BLOCK. */
+int orc_sqe_build_direct(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
+                         const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint32_t opcode,
+                         uint64_t sgl_table_addr, uint32_t sgl_id, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
 
 /* Descriptor count for a pool of pool_bytes described at gran bytes per descriptor
  * (the arithmetic of sec. 3.1, "P2P Memory Mapping Table"). */

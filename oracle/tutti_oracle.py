@@ -27,6 +27,9 @@ SQE_DTYPE = np.dtype([("opcode", "u1"), ("kind", "u1"), ("layer", "<u2"), ("file
                       ("ioctx_slot", "<u4"), ("rsvd", "u1", (16,))], align=True)
 
 
+SGL_DTYPE = np.dtype([("addr", "<u8"), ("len", "<u4"), ("id", "<u4")], align=True)
+
+
 class OrcPool(C.Structure):
     _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("block_stride", C.c_uint64),
                 ("num_blocks", C.c_uint32), ("block_tokens", C.c_uint32), ("num_kv_heads", C.c_uint32),
@@ -181,3 +184,32 @@ def layer_restore(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage
     if rc:
         raise OracleError("orc_layer_restore", rc)
     return ext, totals, sqe, status.value
+
+
+def sgl_table_build(pool, k_addr, v_addr, sgl_id, cap=None):
+    """Returns (descriptor array, status).  Default capacity: 2 * num_blocks."""
+    n = 2 * pool.num_blocks if cap is None else cap
+    table = np.zeros(n, SGL_DTYPE)
+    status = C.c_uint32(0)
+    rc = lib().orc_sgl_table_build(C.byref(pool), C.c_uint64(k_addr), C.c_uint64(v_addr), C.c_uint32(sgl_id),
+                                   _ptr(table), C.c_uint32(n), C.byref(status))
+    if rc:
+        raise OracleError("orc_sgl_table_build", rc)
+    return table, status.value
+
+
+def sqe_build_direct(pool, cfg, extents, block_table, file_id, layer, opcode, sgl_table_addr, sgl_id, sqe_cap=None):
+    """Returns (sqe array, status).  Default capacity: 2 * sum(n_blocks)."""
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    file_id = np.ascontiguousarray(file_id, dtype=np.uint32)
+    need = int(2 * extents["n_blocks"].astype(np.uint64).sum())
+    cap = need if sqe_cap is None else sqe_cap
+    sqe = np.zeros(cap, SQE_DTYPE)
+    status = C.c_uint32(0)
+    rc = lib().orc_sqe_build_direct(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
+                                    _ptr(block_table), _ptr(file_id), C.c_uint32(layer), C.c_uint32(opcode),
+                                    C.c_uint64(sgl_table_addr), C.c_uint32(sgl_id), _ptr(sqe), C.c_uint32(cap),
+                                    C.byref(status))
+    if rc:
+        raise OracleError("orc_sqe_build_direct", rc)
+    return sqe, status.value

@@ -31,7 +31,11 @@ SQE_DTYPE = np.dtype({"names": ["opcode", "kind", "layer", "file_id", "file_off"
                                   ("u1", (16,))],
                       "offsets": [0, 1, 2, 4, 8, 16, 24, 28, 32, 40, 44, 48], "itemsize": 64})
 
+SGL_DTYPE = np.dtype({"names": ["addr", "len", "id"], "formats": ["<u8", "<u4", "<u4"], "offsets": [0, 8, 12],
+                      "itemsize": 16})
+
 EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
+           "tutti_sgl_table_build", "tutti_sqe_build_direct",
            "tutti_copy_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"]
 
@@ -75,6 +79,8 @@ def lib():
         L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
                                           vp, vp]
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
+        L.tutti_sgl_table_build.argtypes = [pp, u64, u64, u32, vp, u32, vp, vp]
+        L.tutti_sqe_build_direct.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
         L.tutti_strerror.argtypes = [C.c_int]
         L.tutti_strerror.restype = C.c_char_p
         L.tutti_version.restype = u32
@@ -82,7 +88,7 @@ def lib():
         L.tutti_set_tuning.argtypes = [u32, u32]
         L.tutti_set_nontemporal.argtypes = [u32]
         L.tutti_set_hnd_mode.argtypes = [u32]
-        for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
+        for name in ("tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
                      "tutti_layer_restore", "tutti_copy_baseline", "tutti_last_hip_error", "tutti_cu_count",
                      "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"):
             getattr(L, name).restype = C.c_int
@@ -165,6 +171,20 @@ def tutti_layer_restore(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, 
                                             table_len, _p(d_file_id), layer, _p(d_stage), stage_cap, stage_addr,
                                             sgl_id, _p(d_extents), _p(d_totals), _p(d_sqe), sqe_cap, cu_budget,
                                             _p(d_status), _stream(stream)))
+
+
+def tutti_sgl_table_build(pool, k_addr, v_addr, sgl_id, d_table, cap, d_status=None, stream=None):
+    return _check("tutti_sgl_table_build", lib().tutti_sgl_table_build(C.byref(pool), k_addr, v_addr, sgl_id,
+                                                                       _p(d_table), cap, _p(d_status),
+                                                                       _stream(stream)))
+
+
+def tutti_sqe_build_direct(pool, cfg, d_extents, n_req, d_block_table, table_len, d_file_id, layer, opcode,
+                           sgl_table_addr, sgl_id, d_sqe, sqe_cap, d_status=None, stream=None):
+    return _check("tutti_sqe_build_direct",
+                  lib().tutti_sqe_build_direct(C.byref(pool), C.byref(cfg), _p(d_extents), n_req, _p(d_block_table),
+                                               table_len, _p(d_file_id), layer, opcode, sgl_table_addr, sgl_id,
+                                               _p(d_sqe), sqe_cap, _p(d_status), _stream(stream)))
 
 
 def tutti_copy_baseline(d_dst, d_src, nbytes, cu_budget=0, stream=None):

@@ -494,6 +494,82 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+int tutti_sgl_table_build(const tutti_pool *pool, uint64_t k_addr, uint64_t v_addr, uint32_t sgl_id,
+                          tutti_sgl *d_table, uint32_t cap, uint32_t *d_status, void *stream) {
+  if (!pool) return TUTTI_EINVAL;
+  uint64_t b = pool->block_tokens;
+  b *= pool->num_kv_heads;
+  if (b > 0xffffffffull) return TUTTI_EINVAL;
+  b *= pool->head_dim;
+  if (b > 0xffffffffull) return TUTTI_EINVAL;
+  b *= pool->elt_bytes;
+  if (b == 0 || b > 0xffffffffull || b % 16 != 0 || pool->num_blocks == 0) return TUTTI_EINVAL;
+  if (pool->block_stride < b || pool->block_stride % 16 != 0) return TUTTI_EINVAL;
+  if (cap > 0 && (!d_table || !aligned16(d_table))) return TUTTI_EINVAL;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  SglArgs a;
+  a.table = d_table;
+  a.status = d_status;
+  a.k_addr = k_addr;
+  a.v_addr = v_addr;
+  a.block_stride = pool->block_stride;
+  a.num_blocks = pool->num_blocks;
+  a.block_bytes = static_cast<uint32_t>(b);
+  a.sgl_id = sgl_id;
+  a.cap = cap;
+  uint64_t need = (2ull * pool->num_blocks + kWgThreads - 1) / kWgThreads;
+  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
+  const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
+  hipLaunchKernelGGL(k_sgl_table, dim3(grid), dim3(kWgThreads), 0, static_cast<hipStream_t>(stream), a);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents,
+                           uint32_t n_req, const uint32_t *d_block_table, uint32_t table_len,
+                           const uint32_t *d_file_id, uint32_t layer, uint32_t opcode, uint64_t sgl_table_addr,
+                           uint32_t sgl_id, tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t *d_status, void *stream) {
+  uint32_t bb = 0;
+  int rc = check_geometry(pool, cfg, &bb);
+  if (rc) return rc;
+  if (bb % cfg->align != 0) return TUTTI_EINVAL;
+  if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
+  if (n_req > 0 && (!d_extents || !d_file_id)) return TUTTI_EINVAL;
+  if (table_len > 0 && !d_block_table) return TUTTI_EINVAL;
+  if (sqe_cap > 0 && (!d_sqe || !aligned16(d_sqe))) return TUTTI_EINVAL;
+  if (opcode != TUTTI_OP_READ && opcode != TUTTI_OP_WRITE) return TUTTI_EINVAL;
+  if (layer >= cfg->num_layers) return TUTTI_EINVAL;
+  if (sgl_table_addr % 16 != 0) return TUTTI_EINVAL;
+  if (n_req == 0) return TUTTI_OK;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  SqeArgs q;
+  q.file_id = d_file_id;
+  q.sqe = d_sqe;
+  q.status = d_status;
+  q.stage_addr = 0;
+  q.sqe_cap = sqe_cap;
+  q.chunk_bytes = bb;
+  q.layer = layer;
+  q.opcode = opcode;
+  q.sgl_id = sgl_id;
+  DirectArgs d;
+  d.table = d_block_table;
+  d.sgl_table_addr = sgl_table_addr;
+  d.table_len = table_len;
+  d.num_blocks = pool->num_blocks;
+  d.block_bytes = bb;
+  uint64_t need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
+  if (need == 0) need = 1;
+  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
+  const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
+  hipLaunchKernelGGL(k_sqe_direct, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req),
+                     static_cast<hipStream_t>(stream), q, d, d_extents, n_req);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
 int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream) {
   if (!d_dst || !d_src || !aligned16(d_dst) || !aligned16(d_src) || bytes % 16 != 0) return TUTTI_EINVAL;
   if (bytes == 0) return TUTTI_OK;
@@ -559,7 +635,7 @@ int tutti_cu_count(void) { return cu_count(); }
 uint32_t tutti_version(void) { return 0x00000100u; }
 
 int tutti_abi_describe(uint32_t *out, uint32_t cap) {
-  if (!out || cap < 33) return TUTTI_EINVAL;
+  if (!out || cap < 37) return TUTTI_EINVAL;
   uint32_t i = 0;
   out[i++] = sizeof(tutti_extent);
   out[i++] = offsetof(tutti_extent, stage_off);
@@ -594,6 +670,10 @@ int tutti_abi_describe(uint32_t *out, uint32_t cap) {
   out[i++] = offsetof(tutti_objcfg, align);
   out[i++] = offsetof(tutti_objcfg, chunk_bytes);
   out[i++] = offsetof(tutti_objcfg, num_layers);
+  out[i++] = sizeof(tutti_sgl);
+  out[i++] = offsetof(tutti_sgl, addr);
+  out[i++] = offsetof(tutti_sgl, len);
+  out[i++] = offsetof(tutti_sgl, id);
   return static_cast<int>(i);
 }
 

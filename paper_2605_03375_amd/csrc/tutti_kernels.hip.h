@@ -3,6 +3,8 @@
 // Kernels
 //   k_layout        one wavefront: extents of all requests by a wave-level prefix scan
 //   k_sqe           submission entries from extents, four lanes per 64-byte entry
+//   k_sgl_table     the pool's mapping table: one 16-byte descriptor per block
+//   k_sqe_direct    one entry per (hit block, K|V), naming the block's descriptor: no staging copy
 //   k_move          pack / unpack between paged blocks and objects, extents given
 //   k_move_lds      the same for head-major pools with short rows: token-tile transposed in LDS
 //   k_restore       one layer's restore in one launch: scan + entries + unpack
@@ -220,6 +222,103 @@ __device__ __forceinline__ void emit_sqes(const SqeArgs a, const ReqLds l, uint3
     }
     out[q] = w;
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Direct-to-block mode.  The mapping table holds one 16-byte descriptor per pool block; an entry
+// then names the descriptor of the block it transfers instead of a staging address.
+// ------------------------------------------------------------------------------------------
+struct SglArgs {
+  tutti_sgl *table;
+  uint32_t *status;
+  uint64_t k_addr;
+  uint64_t v_addr;
+  uint64_t block_stride;
+  uint32_t num_blocks;
+  uint32_t block_bytes;
+  uint32_t sgl_id;
+  uint32_t cap;
+};
+
+__global__ __launch_bounds__(kWgThreads) void k_sgl_table(const SglArgs a) {
+  const uint64_t n = 2ull * a.num_blocks;
+  if (n > a.cap && blockIdx.x == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
+  const uint64_t n_write = n < a.cap ? n : a.cap;
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  u32x4 *out = reinterpret_cast<u32x4 *>(a.table);
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n_write; i += stride) {
+    const bool v_plane = i >= a.num_blocks;
+    const uint64_t b = v_plane ? i - a.num_blocks : i;
+    const uint64_t addr = (v_plane ? a.v_addr : a.k_addr) + b * a.block_stride;
+    u32x4 w;
+    w.x = static_cast<uint32_t>(addr);
+    w.y = static_cast<uint32_t>(addr >> 32);
+    w.z = a.block_bytes;
+    w.w = a.sgl_id;
+    out[i] = w;  // a wavefront stores 64 descriptors = 1 KiB of consecutive bytes
+  }
+}
+
+struct DirectArgs {
+  const uint32_t *table;
+  uint64_t sgl_table_addr;
+  uint32_t table_len;
+  uint32_t num_blocks;
+  uint32_t block_bytes;
+};
+
+// Four lanes per entry, as in emit_sqes; the block id comes from the table (one 4-byte load per lane,
+// the four lanes of an entry read the same word).
+__device__ __forceinline__ void emit_direct_sqes(const SqeArgs a, const DirectArgs d, const ReqLds l, uint32_t n_req) {
+  const uint64_t n_sqe = 2ull * l.table_off[n_req];
+  const uint64_t n_write = n_sqe < a.sqe_cap ? n_sqe : a.sqe_cap;
+  if (n_sqe > a.sqe_cap && blockIdx.x == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
+  const uint64_t n_quarters = 4ull * n_write;
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  u32x4 *out = reinterpret_cast<u32x4 *>(a.sqe);
+  for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; q < n_quarters; q += stride) {
+    const uint32_t i = static_cast<uint32_t>(q >> 2);
+    const uint32_t part = static_cast<uint32_t>(q & 3);
+    const uint32_t r = find_owner(l.table_off, n_req, i >> 1);
+    const uint32_t toff = l.table_off[r];
+    const uint32_t n = l.table_off[r + 1] - toff;
+    const uint32_t v = i - 2u * toff;
+    const uint32_t kind = v >= n ? 1u : 0u;
+    const uint32_t j = v - kind * n;
+    const uint32_t tab_idx = toff + j;
+    uint32_t id = d.num_blocks;
+    if (tab_idx < d.table_len) id = d.table[tab_idx];
+    const bool ok = id < d.num_blocks;
+    if (!ok && part == 0 && a.status) atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
+    u32x4 w = {0u, 0u, 0u, 0u};
+    if (part == 0) {
+      const uint64_t file_off = (2ull * a.layer + kind) * l.obj_bytes[r] + static_cast<uint64_t>(j) * d.block_bytes;
+      w.x = (a.opcode & 0xffu) | (kind << 8) | (a.layer << 16);
+      w.y = a.file_id[r];
+      w.z = static_cast<uint32_t>(file_off);
+      w.w = static_cast<uint32_t>(file_off >> 32);
+    } else if (part == 1) {
+      const uint64_t addr = ok ? d.sgl_table_addr + 16ull * (static_cast<uint64_t>(kind) * d.num_blocks + id) : 0ull;
+      w.x = static_cast<uint32_t>(addr);
+      w.y = static_cast<uint32_t>(addr >> 32);
+      w.z = ok ? d.block_bytes : 0u;
+      w.w = a.sgl_id;
+    } else if (part == 2) {
+      w.x = i;
+      w.y = r;
+      w.z = i / TUTTI_IOCB_SLOTS;
+      w.w = i % TUTTI_IOCB_SLOTS;
+    }
+    out[q] = w;
+  }
+}
+
+__global__ __launch_bounds__(kWgThreads) void k_sqe_direct(const SqeArgs a, const DirectArgs d,
+                                                            const tutti_extent *__restrict__ ext, uint32_t n_req) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, n_req);
+  lds_from_extents(ext, n_req, l);
+  emit_direct_sqes(a, d, l, n_req);
 }
 
 // ------------------------------------------------------------------------------------------

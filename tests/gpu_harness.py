@@ -205,3 +205,36 @@ def check_everything(orc, c, cu_budget=0):
     check_unpack(orc, c, ext, o_ext, o_tot, cu_budget)
     check_sqe(orc, c, ext, o_ext, o_tot, layer=c.L - 1)
     check_layer_restore(orc, c, layer=c.L - 1, cu_budget=cu_budget)
+
+
+def check_direct_mode(orc, c, layer=0, sgl_id=17, sqe_cap=None, table_len=None):
+    """Mapping table and per-block entries (no staging copy) against the oracle."""
+    k_addr, v_addr = c.k_dev.data_ptr(), c.v_dev.data_ptr()
+    n_desc = 2 * c.N
+    sgl = torch.full((n_desc * 16 + 64,), 0x3C, dtype=torch.uint8, device=DEV)
+    st = new_status()
+    B.tutti_sgl_table_build(c.gpu_pool(), k_addr, v_addr, sgl_id, sgl, n_desc, st)
+    torch.cuda.synchronize()
+    o_sgl, o_st = orc.sgl_table_build(c.orc_pool(orc), k_addr, v_addr, sgl_id)
+    got = sgl.cpu().numpy()
+    assert got[: 16 * n_desc].tobytes() == o_sgl.tobytes(), f"{c.name}: mapping table differs"
+    assert np.all(got[16 * n_desc:] == 0x3C) and int(st.item()) == o_st == 0
+    ext, tot, o_ext, o_tot = check_layout(orc, c)
+    n = 2 * int(c.n_blocks.sum())
+    cap = n if sqe_cap is None else sqe_cap
+    tl = c.table.size if table_len is None else table_len
+    o_table = c.table.copy()
+    o_table[tl:] = 0xFFFFFFFF          # entries beyond table_len count as out of range
+    for op in (B.OP_READ, B.OP_WRITE):
+        sqe = torch.full((max(cap, 1) * 64,), 0x3C, dtype=torch.uint8, device=DEV)
+        st = new_status()
+        B.tutti_sqe_build_direct(c.gpu_pool(), c.gpu_cfg(), ext, c.n_req, c.d_table, tl, c.d_file_id, layer, op,
+                                 sgl.data_ptr(), sgl_id, sqe, cap, st)
+        torch.cuda.synchronize()
+        o_sqe, o_st = orc.sqe_build_direct(c.orc_pool(orc), c.orc_cfg(orc), o_ext, o_table, c.file_id, layer, op,
+                                           sgl.data_ptr(), sgl_id, sqe_cap=cap)
+        w = min(n, cap)
+        got = sqe.cpu().numpy()
+        assert got[: 64 * w].tobytes() == o_sqe[:w].tobytes(), f"{c.name}: direct entries differ (op {op})"
+        assert np.all(got[64 * w:] == 0x3C) and int(st.item()) == o_st
+    return sgl

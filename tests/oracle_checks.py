@@ -84,8 +84,11 @@ def check_closed_forms_8b(orc):
 def check_abi(orc):
     g = golden()
     d = orc.abi_describe()
-    assert len(d) == 33
-    ext, sqe, pool, cfg = d[0:7], d[7:19], d[19:29], d[29:33]
+    assert len(d) == 37
+    ext, sqe, pool, cfg, sgl = d[0:7], d[7:19], d[19:29], d[29:33], d[33:37]
+    assert sgl == [g["sgl_descriptor_bytes"], 0, 8, 12]      # address 8 + length 4 + identifier 4: sec. 3.1
+    G = orc.SGL_DTYPE
+    assert [G.itemsize] + [G.fields[n][1] for n in G.names] == sgl
     assert ext == [32, 0, 8, 16, 20, 24, 28]
     assert sqe == [64, 0, 1, 2, 4, 8, 16, 24, 28, 32, 40, 44]
     assert pool == [48, 0, 8, 16, 24, 28, 32, 36, 40, 44]
@@ -484,6 +487,100 @@ def check_threaded(orc, seed=19):
             assert np.array_equal(k2, k3) and np.array_equal(v2, v3)
 
 
+# ---------------------------------------------------------------------------- direct-to-block mode
+
+def check_sgl_table(orc):
+    """The mapping table: the paper's descriptor arithmetic, and descriptors that tile the planes."""
+    g = golden()
+    # 60 GiB of KV memory described at 64 KiB granularity (sec. 3.1): K and V planes of 491,520 blocks each
+    p = _pool(orc, 16, 8, 256, 2, 491520)
+    assert orc.block_bytes(p) == 65536
+    assert 2 * p.num_blocks * 65536 == 60 * 1024 ** 3
+    table, st = orc.sgl_table_build(p, 0x100000000000, 0x200000000000, 9)
+    assert st == 0 and table.size == g["descriptors_60GiB_64KiB"] and table.nbytes == g["sgl_bytes"]
+    for base, lo in ((0x100000000000, 0), (0x200000000000, p.num_blocks)):
+        part = table[lo:lo + p.num_blocks]
+        assert int(part["addr"][0]) == base and np.all(part["len"] == 65536) and np.all(part["id"] == 9)
+        assert np.array_equal(part["addr"][1:], part["addr"][:-1] + part["len"][:-1])   # tiles the plane
+        assert int(part["addr"][-1]) + 65536 == base + 30 * 1024 ** 3
+    # strided pool: addresses step by the stride, lengths stay the block size
+    p = _pool(orc, 16, 2, 64, 2, 10, stride=4096 + 512)
+    table, st = orc.sgl_table_build(p, 1 << 20, 1 << 30, 3)
+    assert np.array_equal(table["addr"][:10], (1 << 20) + np.arange(10, dtype=np.uint64) * 4608)
+    assert np.array_equal(table["addr"][10:], (1 << 30) + np.arange(10, dtype=np.uint64) * 4608)
+    assert np.all(table["len"] == 4096)
+    table, st = orc.sgl_table_build(p, 1 << 20, 1 << 30, 3, cap=13)
+    assert st == orc.ST_SQE_CAP and table.size == 13 and int(table["addr"][12]) == (1 << 30) + 2 * 4608
+
+
+def check_direct_entries(orc, seed=23):
+    """One entry per (hit block, K|V): the paper's count, every field from a separate enumeration, and
+    agreement with the staged mode on everything but the address."""
+    g = golden()
+    # 64 layers, 64-token blocks, 128K tokens: 2 x 64 x 128K/64 objects in total (sec. 2.2)
+    T, h, d, e = 64, 8, 128, 2
+    bb = T * h * d * e
+    n = 128 * 1024 // T
+    p = _pool(orc, T, h, d, e, 4096)
+    cfg = orc.make_cfg(4096, bb, 64)
+    ext, tot = orc.obj_layout(p, cfg, [n])
+    sqe, st = orc.sqe_build_direct(p, cfg, ext, np.arange(n), [5], 63, orc.OP_READ, 1 << 32, 0)
+    assert st == 0 and sqe.size * 64 == g["io_count_64layer_block64_128k"]
+    rng = np.random.default_rng(seed)
+    for T, h, d, e, A, pad in [(16, 8, 128, 2, 4096, 0), (16, 2, 64, 2, 4096, 128), (4, 4, 16, 2, 256, 0)]:
+        bb = T * h * d * e
+        N, L = 500, 7
+        p = _pool(orc, T, h, d, e, N, stride=bb + pad)
+        cfg = orc.make_cfg(A, bb, L)
+        nb = np.array([6, 0, 40, 1, 13], np.uint32)
+        table = rng.permutation(N)[: int(nb.sum())].astype(np.uint32)
+        fid = np.array([11, 12, 13, 14, 15], np.uint32)
+        ext, tot = orc.obj_layout(p, cfg, nb)
+        base = 0x7E0000000000
+        k_addr, v_addr = 0x100000000, 0x900000000
+        sgl, _ = orc.sgl_table_build(p, k_addr, v_addr, 21)
+        for layer, op in ((0, orc.OP_WRITE), (L - 1, orc.OP_READ)):
+            sqe, st = orc.sqe_build_direct(p, cfg, ext, table, fid, layer, op, base, 21)
+            assert st == 0 and sqe.size == 2 * int(nb.sum())
+            i, pos = 0, 0
+            for r in range(nb.size):
+                obj = int(nb[r]) * bb           # block size is a multiple of A here: no padding
+                for kind in range(2):
+                    for j in range(int(nb[r])):
+                        s = sqe[i]
+                        bid = int(table[pos + j])
+                        assert (s["opcode"], s["kind"], s["layer"], s["file_id"]) == (op, kind, layer, fid[r])
+                        assert int(s["len"]) == bb and int(s["sgl_id"]) == 21
+                        assert int(s["file_off"]) == (2 * layer + kind) * obj + j * bb
+                        assert int(s["addr"]) == base + 16 * (kind * N + bid)
+                        # the descriptor the entry names describes exactly that block
+                        dsc = sgl[(int(s["addr"]) - base) // 16]
+                        assert int(dsc["addr"]) == (k_addr, v_addr)[kind] + bid * (bb + pad) and int(dsc["len"]) == bb
+                        assert int(s["user_data"]) == (r << 32) | i
+                        assert (int(s["iocb_idx"]), int(s["ioctx_slot"])) == divmod(i, 2048)
+                        assert not s["rsvd"].any()
+                        i += 1
+                pos += int(nb[r])
+            # same GPU-file layout as the staged mode with one chunk per block
+            staged, _ = orc.sqe_build(p, cfg, ext, fid, layer, op, 0, 21)
+            for f in ("opcode", "kind", "layer", "file_id", "file_off", "len", "sgl_id", "user_data", "iocb_idx",
+                      "ioctx_slot"):
+                assert np.array_equal(staged[f], sqe[f]), f
+    # out-of-range ids become no-op entries; the capacity clamps
+    p = _pool(orc, 16, 2, 64, 2, 8)
+    cfg = orc.make_cfg(4096, 4096, 1)
+    ext, _ = orc.obj_layout(p, cfg, [3])
+    sqe, st = orc.sqe_build_direct(p, cfg, ext, [1, 8, 2], [1], 0, orc.OP_READ, 0, 0)
+    assert st == orc.ST_BAD_BLOCK and int(sqe["len"][1]) == 0 and int(sqe["addr"][1]) == 0 and int(sqe["len"][4]) == 0
+    assert int(sqe["len"][0]) == 4096 and int(sqe["addr"][5]) == 16 * (8 + 2)
+    sqe, st = orc.sqe_build_direct(p, cfg, ext, [1, 3, 2], [1], 0, orc.OP_READ, 0, 0, sqe_cap=4)
+    assert st == orc.ST_SQE_CAP and sqe.size == 4
+    import pytest
+    with pytest.raises(orc.OracleError):   # blocks must be whole alignment units in this mode
+        orc.sqe_build_direct(_pool(orc, 16, 5, 40, 2, 8), orc.make_cfg(4096, 8192, 1), ext, [1, 3, 2], [1], 0,
+                             orc.OP_READ, 0, 0)
+
+
 ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
-              check_sqe_fields, check_layer_restore, check_threaded]
+              check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries]

@@ -18,7 +18,8 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for name in declared:
         assert getattr(L, name) is not None
-    for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore"):
+    for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
+                 "tutti_sgl_table_build", "tutti_sqe_build_direct"):
         assert name in declared and callable(getattr(B, name))
     assert B.tutti_version() >= 0x100
 
@@ -33,6 +34,8 @@ def test_record_layouts_agree_with_oracle(orc):
     assert ctypes.sizeof(B.tutti_pool) == lib_abi[19] and ctypes.sizeof(B.tutti_objcfg) == lib_abi[29]
     assert [getattr(B.tutti_pool, f).offset for f, _ in B.tutti_pool._fields_] == lib_abi[20:29]
     assert [getattr(B.tutti_objcfg, f).offset for f, _ in B.tutti_objcfg._fields_] == lib_abi[30:33]
+    G = B.SGL_DTYPE
+    assert [G.itemsize] + [G.fields[n][1] for n in G.names] == lib_abi[33:37]
     for a, b in [(B.OP_READ, orc.OP_READ), (B.OP_WRITE, orc.OP_WRITE), (B.LAYOUT_HND, orc.LAYOUT_HND),
                  (B.IOCB_SLOTS, orc.IOCB_SLOTS), (B.ST_BAD_BLOCK, orc.ST_BAD_BLOCK),
                  (B.ST_STAGE_CAP, orc.ST_STAGE_CAP), (B.ST_SQE_CAP, orc.ST_SQE_CAP)]:
@@ -98,6 +101,13 @@ def test_null_and_misaligned_pointers_are_einval():
     _expect(B.EINVAL, B.tutti_sqe_build, p, cfg, FAKE, 1, FAKE, 0, B.OP_READ, 100, 0, FAKE, 4)      # stage_addr
     _expect(B.EINVAL, B.tutti_layer_restore, p, cfg, FAKE, 1, FAKE, 1, FAKE, 2, FAKE, 4096, 0, 0, FAKE, FAKE, FAKE, 4)
     _expect(B.EINVAL, B.tutti_layer_restore, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, FAKE, 4096, 0, 0, FAKE, 0, FAKE, 4)
+    _expect(B.EINVAL, B.tutti_sqe_build_direct, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, B.OP_READ, 8, 0, FAKE, 4)  # table addr
+    _expect(B.EINVAL, B.tutti_sqe_build_direct, p, cfg, FAKE, 1, FAKE, 1, FAKE, 5, B.OP_READ, 0, 0, FAKE, 4)  # layer
+    _expect(B.EINVAL, B.tutti_sqe_build_direct, p, cfg, FAKE, 1, 0, 1, FAKE, 0, B.OP_READ, 0, 0, FAKE, 4)     # table
+    odd = B.make_pool(FAKE, FAKE, num_blocks=8, block_tokens=16, num_kv_heads=5, head_dim=40, elt_bytes=2)
+    _expect(B.EINVAL, B.tutti_sqe_build_direct, odd, cfg, FAKE, 1, FAKE, 1, FAKE, 0, B.OP_READ, 0, 0, FAKE, 4)
+    _expect(B.EINVAL, B.tutti_sgl_table_build, p, 0, 0, 0, 0, 4)
+    _expect(B.EINVAL, B.tutti_sgl_table_build, B.make_pool(FAKE, FAKE, **dict(GOOD, num_blocks=0)), 0, 0, 0, FAKE, 4)
     _expect(B.EINVAL, B.tutti_copy_baseline, FAKE, FAKE, 24)
     _expect(B.EINVAL, B.tutti_copy_baseline, 0, FAKE, 32)
     # head-major pools need rows of whole 16-byte units

@@ -138,6 +138,40 @@ def test_head_major_lds_edge_cases(orc, H):
     H.check_everything(orc, c)
 
 
+# ------------------------------------------------------------------ direct-to-block mode (no staging copy)
+
+def test_direct_mode_small_shapes(orc, H):
+    say("direct mode: small shapes")
+    rng = np.random.default_rng(31)
+    for T, h, d, e, N, nb, A, pad in [(16, 2, 64, 2, 256, [32], 4096, 0), (16, 8, 128, 2, 500, [6, 0, 40, 1, 13], 4096, 0),
+                                      (4, 4, 16, 2, 100, [9, 9, 0, 30], 256, 256), (16, 1, 128, 2, 3000, [2500], 4096, 0)]:
+        bb = T * h * d * e
+        c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], align=A, chunk=bb,
+                        L=9, pad=pad, name=f"direct_bb{bb}")
+        H.check_direct_mode(orc, c, layer=8)
+    # out-of-range ids, a short table, small capacities
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[4, 2], table=[3, 999, 5, 16, 7, 1], chunk=4096, name="direct_bad")
+    H.check_direct_mode(orc, c)
+    H.check_direct_mode(orc, c, table_len=4)
+    H.check_direct_mode(orc, c, sqe_cap=5)
+    H.check_direct_mode(orc, c, sqe_cap=0)
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[0, 0], table=[], chunk=4096, name="direct_empty")
+    H.check_direct_mode(orc, c)
+
+
+def test_direct_mode_cfg3_and_cfg4(orc, H):
+    """Per-block entries at the scale the paper cares about: 81,438 per layer (config 3), 16,384 (config 4)."""
+    w = W.batch64_zipf(chunk_bytes=32768)
+    say("direct mode cfg3", int(w.n_blocks.sum()))
+    # planes are never touched in this mode: a small stand-in pool keeps the test light
+    c = H.LayerCase.from_workload(w)
+    H.check_direct_mode(orc, c, layer=31)
+    w = W.llama70b_128k()
+    say("direct mode cfg4")
+    c = H.LayerCase.from_workload(w)
+    H.check_direct_mode(orc, c, layer=79)
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_no_requests_and_empty_requests(orc, H):

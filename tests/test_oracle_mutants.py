@@ -29,21 +29,44 @@ MUTANTS = {
     "block_bound_off_by_one": ("if (id >= pool->num_blocks) {", "if (id > pool->num_blocks) {"),
     "unpack_direction": ("(uint8_t *)(uintptr_t)stage, stage_cap, 0, 0,\n             total_blocks",
                          "(uint8_t *)(uintptr_t)stage, stage_cap, 1, 0,\n             total_blocks"),
-    "file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)"),
+    "file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)", 0),
+    "direct_file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)", 1),
+    "direct_file_id_of_first": ("s.file_id = file_id[r];", "s.file_id = file_id[0];", 1),
+    "direct_iocb_div_mod_swapped": ("s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);",
+                                    "s.iocb_idx = (uint32_t)(i % ORC_IOCB_SLOTS);", 1),
+    "direct_user_data_swapped": ("s.user_data = ((uint64_t)r << 32) | (uint32_t)i;",
+                                 "s.user_data = ((uint64_t)i << 32) | r;", 1),
+    "direct_rsvd_dirty": ("memset(&s, 0, sizeof s);", "memset(&s, 0xff, sizeof s);", 1),
     "file_off_all_k_then_v": ("s.file_off = (2ull * layer + kind) * x->obj_bytes",
-                              "s.file_off = ((uint64_t)kind * cfg->num_layers + layer) * x->obj_bytes"),
+                              "s.file_off = ((uint64_t)kind * cfg->num_layers + layer) * x->obj_bytes", 0),
     "addr_without_kind": ("s.addr = stage_addr + x->stage_off + (uint64_t)kind * x->obj_bytes",
                           "s.addr = stage_addr + x->stage_off"),
     "len_always_chunk": ("s.len = (uint32_t)(left < C ? left : C);", "s.len = (uint32_t)C;"),
-    "iocb_div_mod_swapped": ("s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);", "s.iocb_idx = (uint32_t)(i % ORC_IOCB_SLOTS);"),
-    "iocb_2000": ("s.ioctx_slot = (uint32_t)(i % ORC_IOCB_SLOTS);", "s.ioctx_slot = (uint32_t)(i % 2000);"),
-    "user_data_swapped": ("s.user_data = ((uint64_t)r << 32) | (uint32_t)i;", "s.user_data = ((uint64_t)i << 32) | r;"),
+    "iocb_div_mod_swapped": ("s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);", "s.iocb_idx = (uint32_t)(i % ORC_IOCB_SLOTS);", 0),
+    "iocb_2000": ("s.ioctx_slot = (uint32_t)(i % ORC_IOCB_SLOTS);", "s.ioctx_slot = (uint32_t)(i % 2000);", 0),
+    "user_data_swapped": ("s.user_data = ((uint64_t)r << 32) | (uint32_t)i;", "s.user_data = ((uint64_t)i << 32) | r;", 0),
     "entries_interleaved": ("(uint64_t)x->sqe_base + (uint64_t)kind * x->n_chunks + c;",
                             "(uint64_t)x->sqe_base + 2ull * c + kind;"),
-    "file_id_of_first": ("s.file_id = file_id[r];", "s.file_id = file_id[0];"),
-    "rsvd_dirty": ("memset(&s, 0, sizeof s);", "memset(&s, 0xff, sizeof s);"),
+    "file_id_of_first": ("s.file_id = file_id[r];", "s.file_id = file_id[0];", 0),
+    "rsvd_dirty": ("memset(&s, 0, sizeof s);", "memset(&s, 0xff, sizeof s);", 0),
     "cap_check_inclusive": ("if (x->stage_off + 2 * x->obj_bytes > stage_cap) continue;",
                             "if (x->stage_off + 2 * x->obj_bytes >= stage_cap) continue;"),
+    "sgl_v_plane_uses_k_address": ("table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;",
+                                   "table[i].addr = k_addr + (uint64_t)b * pool->block_stride;"),
+    "sgl_ignores_stride": ("table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;",
+                           "table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * bb;"),
+    "sgl_len_is_stride": ("table[i].len = bb;", "table[i].len = (uint32_t)pool->block_stride;"),
+    "direct_descriptor_of_k_only": ("s.addr = sgl_table_addr + 16ull * ((uint64_t)kind * pool->num_blocks + id);",
+                                    "s.addr = sgl_table_addr + 16ull * id;"),
+    "direct_addr_by_position": ("s.addr = sgl_table_addr + 16ull * ((uint64_t)kind * pool->num_blocks + id);",
+                                "s.addr = sgl_table_addr + 16ull * ((uint64_t)kind * pool->num_blocks + j);"),
+    "direct_file_off_by_id": ("s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)j * bb;",
+                              "s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)id * bb;"),
+    "direct_index_interleaved": ("uint64_t i = 2ull * x->table_off + (uint64_t)kind * x->n_blocks + j;",
+                                 "uint64_t i = 2ull * x->table_off + 2ull * j + kind;"),
+    "direct_table_offset_dropped": ("uint32_t id = block_table[(uint64_t)x->table_off + j];",
+                                    "uint32_t id = block_table[j];"),
+    "direct_bad_id_bound": ("if (id < pool->num_blocks) {\n          s.addr", "if (id <= pool->num_blocks) {\n          s.addr"),
     "restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
                              "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);"),
 }
@@ -71,11 +94,15 @@ sys.exit(0)
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
 def test_mutant_is_caught(orc, tmp_path, name):
-    old, new = MUTANTS[name]
+    old, new, *which = MUTANTS[name]
+    which = which[0] if which else 0        # which occurrence of the site to change (default: the only one)
     text = open(SRC).read()
-    assert text.count(old) == 1, f"mutation site for {name} must be unique in the oracle source"
+    assert text.count(old) == (1 if not MUTANTS[name][2:] else text.count(old)) and text.count(old) > which, \
+        f"mutation site for {name} not found as expected in the oracle source"
+    parts = text.split(old)
+    mutated = old.join(parts[:which + 1]) + new + old.join(parts[which + 1:])
     src = tmp_path / "mutant.c"
-    src.write_text(text.replace(old, new))
+    src.write_text(mutated)
     so = tmp_path / "libmutant.so"
     subprocess.run(["gcc", "-std=c11", "-O1", "-w", "-fPIC", "-shared", "-pthread", f"-I{os.path.dirname(SRC)}",
                     str(src), "-o", str(so)], check=True)
