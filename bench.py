@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the copy-ceiling / entry-rate legs")
     ap.add_argument("--corun", action="store_true", help="also run the CU-budget sweep beside a GEMM (config 5)")
+    ap.add_argument("--pinned-stage", action="store_true",
+                    help="also time the restore with the staging buffer in pinned host memory (host-link bound)")
     ap.add_argument("--other-configs", action="store_true",
                     help="also time the per-layer restore of configs 3 and 4 (frees config 2's pool first)")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
@@ -212,6 +214,9 @@ def main():
         out["corun"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], stages[0], geom, payload_layer)
+    if args.pinned_stage:
+        out["pinned_host_stage"] = pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload_layer,
+                                              n_sqe_layer, dev)
     if args.other_configs:
         del pools, planes, stages, restore_layers, save_layers
         torch.cuda.empty_cache()
@@ -233,14 +238,15 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
     payload = 2 * n_tab * bb
     n_sqe = int(2 * np.sum((w.n_blocks.astype(np.int64) * bb + w.chunk_bytes - 1) // w.chunk_bytes))
     free, _ = torch.cuda.mem_get_info()
-    L = max(1, min(max_layers, s.num_layers, int((free - (8 << 30)) // (2 * plane_bytes + payload))))
+    n_stage = 8  # staging buffers rotate (8 x payload is well beyond the 256 MB Infinity Cache)
+    L = max(1, min(max_layers, s.num_layers, int((free - (8 << 30) - n_stage * payload) // (2 * plane_bytes))))
     geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
                 head_dim=s.head_dim, elt_bytes=s.elt_bytes)
     cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
     planes = [(torch.empty(plane_bytes, dtype=torch.uint8, device=dev),
                torch.empty(plane_bytes, dtype=torch.uint8, device=dev)) for _ in range(L)]
     pools = [B.make_pool(k, v, **geom) for k, v in planes]
-    stages = [torch.empty(payload, dtype=torch.uint8, device=dev) for _ in range(L)]
+    stages = [torch.empty(payload, dtype=torch.uint8, device=dev) for _ in range(min(L, n_stage))]
     d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
     d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
     d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
@@ -251,8 +257,9 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
 
     def train():
         for l in range(L):
-            B.tutti_layer_restore(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, stages[l], payload,
-                                  stages[l].data_ptr(), 1, ext, tot, sqe, n_sqe, 0, status)
+            st = stages[l % len(stages)]
+            B.tutti_layer_restore(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, st, payload,
+                                  st.data_ptr(), 1, ext, tot, sqe, n_sqe, 0, status)
 
     train()
     torch.cuda.synchronize()
@@ -272,6 +279,45 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
            "traffic_GBps": round(2 * payload / (us * 1e-6) / 1e9, 1),
            "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
     log(f"[bench] {w.name}: {res}")
+    return res
+
+
+def pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload, n_sqe, dev, layers=4, reps=3):
+    """Config 2's per-layer restore and pack with the staging buffer in pinned host memory: the copy
+    crosses the host link, so this is NOT an HBM figure and never the headline value."""
+    L = min(layers, len(pools))
+    stages = [torch.empty(payload, dtype=torch.uint8, pin_memory=True) for _ in range(L)]
+    ext = torch.zeros(32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    sqe = torch.zeros(n_sqe * 64, dtype=torch.uint8, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    B.tutti_obj_layout(pools[0], cfg, d_n, 1, ext, tot)
+
+    def pack():
+        for l in range(L):
+            B.tutti_obj_pack(pools[l], cfg, ext, 1, d_tab, n_tab, stages[l], payload, 0, status)
+
+    def restore():
+        for l in range(L):
+            B.tutti_layer_restore(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload,
+                                  stages[l].data_ptr(), 1, ext, tot, sqe, n_sqe, 0, status)
+
+    res = {"layers": L, "note": "staging buffer in pinned host memory: host-link bound, not an HBM figure"}
+    for label, fn in (("pack", pack), ("restore", restore)):
+        fn()
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b) * 1e3 / L)
+        us = median(times)
+        res[label] = {"us_per_layer": round(us, 1), "payload_GBps": round(payload / (us * 1e-6) / 1e9, 2)}
+    assert int(status.item()) == 0
+    log(f"[bench] pinned-host staging: {res}")
     return res
 
 

@@ -172,6 +172,51 @@ def test_direct_mode_cfg3_and_cfg4(orc, H):
     H.check_direct_mode(orc, c, layer=79)
 
 
+# ------------------------------------------------------------------ staging buffer in pinned host memory
+
+def test_pinned_host_staging(orc, H):
+    """The staging buffer may live in pinned host memory (the closer stand-in for the SSD leg: the
+    copy then crosses the host link).  Same calls, same bytes."""
+    say("pinned-host staging")
+    w = W.llama8b_32k(num_blocks=2048, tokens=4096)
+    c = H.LayerCase.from_workload(w)
+    o_ext, o_tot = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    nbytes = int(o_tot[0])
+    stage = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    stage.fill_(0xA5)
+    ext, tot = H.gpu_layout(c)
+    st = H.new_status()
+    B.tutti_obj_pack(c.gpu_pool(), c.gpu_cfg(), ext, c.n_req, c.d_table, c.table.size, stage, nbytes, 0, st)
+    torch.cuda.synchronize()
+    o_stage = np.full(nbytes, 0xA5, np.uint8)
+    orc.obj_pack(c.orc_pool(orc), c.orc_cfg(orc), o_ext, c.table, o_stage)
+    assert np.array_equal(stage.numpy(), o_stage) and int(st.item()) == 0
+    # restore from pinned memory into a zeroed pool
+    k2, v2 = torch.zeros_like(c.k_dev), torch.zeros_like(c.v_dev)
+    sqe = torch.zeros(64 * int(o_tot[1]), dtype=torch.uint8, device=H.DEV)
+    B.tutti_layer_restore(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id,
+                          3, stage, nbytes, stage.data_ptr(), 1, ext, tot, sqe, int(o_tot[1]), 0, st)
+    torch.cuda.synchronize()
+    ok, ov = np.zeros_like(c.k_host), np.zeros_like(c.v_host)
+    orc.obj_unpack(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), o_ext, c.table, o_stage)
+    assert np.array_equal(k2.cpu().numpy(), ok) and np.array_equal(v2.cpu().numpy(), ov) and int(st.item()) == 0
+
+
+def test_paper_block_sizes(orc, H):
+    """Token counts per block the paper mentions: 16-32 in general (sec. 2.1), 64 in its evaluation (sec. 4)."""
+    rng = np.random.default_rng(64)
+    for T in (32, 64):
+        say("block tokens", T)
+        N = 400
+        nb = [70, 0, 33]
+        c = H.LayerCase(T=T, h=8, d=128, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=2 << 20,
+                        L=32, name=f"T{T}")
+        H.check_everything(orc, c)
+        c = H.LayerCase(T=T, h=8, d=128, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)],
+                        chunk=T * 8 * 128 * 2, L=32, name=f"T{T}_direct")
+        H.check_direct_mode(orc, c, layer=31)
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_no_requests_and_empty_requests(orc, H):
