@@ -212,6 +212,9 @@ def main():
         log(f"[bench] copy ceiling {out['copy_ceiling']}; entries {out['sqe']}")
     if args.corun:
         out["corun"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev)
+        # a GEMM with many more tiles than CUs, for contrast with the 4096^3 one (256 tiles on 256 CUs)
+        out["corun_gemm8192"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=12, reps=2,
+                                            gemm_n=8192, budgets=(8, 32, 0))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], stages[0], geom, payload_layer)
     if args.pinned_stage:
@@ -415,15 +418,16 @@ def direct_rate(torch, B, W, dev, reps=50):
     return res
 
 
-def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, reps=3):
+def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, reps=3, gemm_n=4096,
+                budgets=(8, 16, 32, 64, 0)):
     """Config 5: restore under a CU budget on one stream while a bf16 4096^3 GEMM loops on another.
 
     Each figure is taken under FULL overlap: to time the GEMM, a restore loop long enough to outlast it
     is queued first on the other stream (and the other way round), and the events are checked afterwards
     to confirm the background work was still running when the measured loop ended.
     """
-    a = torch.randn(4096, 4096, dtype=torch.bfloat16, device=dev)
-    b = torch.randn(4096, 4096, dtype=torch.bfloat16, device=dev)
+    a = torch.randn(gemm_n, gemm_n, dtype=torch.bfloat16, device=dev)
+    b = torch.randn(gemm_n, gemm_n, dtype=torch.bfloat16, device=dev)
     side = torch.cuda.Stream()
     main = torch.cuda.current_stream()
     E = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
@@ -448,7 +452,7 @@ def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, 
     gemm_loop(10)
     torch.cuda.synchronize()
     out = {}
-    for budget in (8, 16, 32, 64, 0):
+    for budget in budgets:
         rows = []
         for _ in range(reps):
             g0, g1 = gemm_loop(gemm_iters)
@@ -484,7 +488,7 @@ def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, 
                             "restore_payload_GBps_corun": round(payload_layer / (rc * 1e-3) / 1e9, 1),
                             "restore_slowdown": round(rc / rs, 3),
                             "full_overlap": all(r[4] for r in rows)}
-        log(f"[bench] corun budget {budget}: {out[str(budget)]}")
+        log(f"[bench] corun gemm {gemm_n}^3 budget {budget}: {out[str(budget)]}")
     return out
 
 

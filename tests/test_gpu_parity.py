@@ -217,6 +217,39 @@ def test_paper_block_sizes(orc, H):
         H.check_direct_mode(orc, c, layer=31)
 
 
+# ------------------------------------------------------------------ seeded random shapes
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes(orc, H, seed):
+    """Seeded random geometry, request mix, layout, stride, alignment, chunking and launch shape."""
+    rng = np.random.default_rng(9000 + seed)
+    e = int(rng.choice([1, 2, 4]))
+    d = int(rng.choice([16, 32, 40, 64, 80, 128])) if e > 1 else int(rng.choice([16, 32, 48, 64, 128]))
+    h = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
+    T = int(rng.choice([1, 4, 8, 16, 32]))
+    bb = T * h * d * e
+    A = int(rng.choice([64, 512, 4096]))
+    C = A * int(rng.integers(1, 40))
+    pad = int(rng.choice([0, 0, 16, 4096]))
+    layout = int(rng.integers(0, 2))
+    R = int(rng.choice([1, 2, 5, 17, 64, 100]))
+    nb = rng.integers(0, max(2, 600 // R), size=R)
+    nb[rng.integers(0, R)] = 0
+    N = int(nb.sum()) + int(rng.integers(1, 50))
+    unroll = int(rng.choice([1, 2, 4, 8]))
+    wgs = int(rng.choice([1, 2, 8]))
+    budget = int(rng.choice([0, 0, 1, 5]))
+    say("random", dict(seed=seed, T=T, h=h, d=d, e=e, bb=bb, A=A, C=C, pad=pad, layout=layout, R=R, blocks=int(nb.sum()),
+                       N=N, unroll=unroll, wgs=wgs, budget=budget))
+    B.tutti_set_tuning(wgs, unroll)
+    B.tutti_set_hnd_mode(int(rng.integers(0, 3)))
+    c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=nb, table=rng.permutation(N)[: int(nb.sum())], align=A, chunk=C,
+                    L=int(rng.integers(1, 90)), layout=layout, pad=pad, seed=seed, name=f"random{seed}")
+    H.check_everything(orc, c, cu_budget=budget)
+    if bb % A == 0:
+        H.check_direct_mode(orc, c, layer=c.L - 1)
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_no_requests_and_empty_requests(orc, H):
