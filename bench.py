@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the copy-ceiling / entry-rate legs")
     ap.add_argument("--corun", action="store_true", help="also run the CU-budget sweep beside a GEMM (config 5)")
+    ap.add_argument("--rings", action="store_true",
+                    help="also time the entry-driven path: fill IOCBs on the GPU, then tutti_issue_io (no staging copy)")
     ap.add_argument("--pinned-stage", action="store_true",
                     help="also time the restore with the staging buffer in pinned host memory (host-link bound)")
     ap.add_argument("--other-configs", action="store_true",
@@ -217,6 +219,9 @@ def main():
                                             gemm_n=8192, budgets=(8, 32, 0))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], stages[0], geom, payload_layer)
+    if args.rings:
+        out["rings_direct_to_block"] = ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid,
+                                                payload_layer, dev)
     if args.pinned_stage:
         out["pinned_host_stage"] = pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload_layer,
                                               n_sqe_layer, dev)
@@ -282,6 +287,74 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
            "traffic_GBps": round(2 * payload / (us * 1e-6) / 1e9, 1),
            "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
     log(f"[bench] {w.name}: {res}")
+    return res
+
+
+def ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid, payload, dev, reps=5):
+    """The paper's data path on config 2: per layer, the GPU fills two IOCBs (4096 contexts, one per hit block
+    and plane) and tutti_issue_io moves each block between the request's GPU file (an HBM buffer standing in
+    for the SSD) and the pool block its SGL descriptor names.  No staging copy."""
+    s = w.shape
+    L = len(pools)
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    obj = n_tab * bb
+    file_stride = 2 * s.num_layers * obj                      # one request, all layers: 4 GiB
+    store = torch.empty(file_stride, dtype=torch.uint8, device=dev)
+    fs = B.make_filestore(store, file_stride, int(w.file_id[0]), 1)
+    nd = 2 * s.num_blocks
+    sgls = []
+    for l in range(L):
+        t = torch.empty(nd * 16, dtype=torch.uint8, device=dev)
+        B.tutti_sgl_table_build(pools[l], planes[l][0].data_ptr(), planes[l][1].data_ptr(), 1, t, nd)
+        sgls.append(t)
+    n_slots = (2 * n_tab + B.IOCB_SLOTS - 1) // B.IOCB_SLOTS
+    depth = n_slots * L
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.empty(sq_bytes, dtype=torch.uint8, device=dev)
+    cq = torch.empty(cq_bytes, dtype=torch.uint8, device=dev)
+    ring = B.make_ring(sq, cq, depth)
+    ext = torch.zeros(32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    B.tutti_obj_layout(pools[0], cfg, d_n, 1, ext, tot)
+
+    def train(op, fill=True, issue=True):
+        if fill:
+            B.tutti_ring_init(ring)
+        for l in range(L):
+            if fill:
+                B.tutti_iocb_fill_direct(ring, l * n_slots, n_slots, pools[l], cfg, ext, 1, d_tab, n_tab, d_fid, l, op,
+                                         sgls[l].data_ptr(), 1, status)
+            if issue:
+                B.tutti_issue_io(ring, l * n_slots, n_slots, sgls[l], nd, sgls[l].data_ptr(), fs, bb, 0, status)
+
+    res = {"contexts_per_layer": 2 * n_tab, "iocbs_per_layer": n_slots, "file_store_bytes": file_stride}
+    for label, op in (("save_WRITE", B.OP_WRITE), ("restore_READ", B.OP_READ)):
+        train(op)
+        torch.cuda.synchronize()
+        both, only_io = [], []
+        for _ in range(reps):
+            a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            a.record()
+            train(op)
+            b.record()
+            torch.cuda.synchronize()
+            both.append(a.elapsed_time(b) * 1e3 / L)
+            train(op, issue=False)                 # IOCBs are FILLED again
+            torch.cuda.synchronize()
+            a.record()
+            train(op, fill=False)
+            c.record()
+            torch.cuda.synchronize()
+            only_io.append(a.elapsed_time(c) * 1e3 / L)
+        us, us_io = median(both), median(only_io)
+        res[label] = {"us_per_layer_fill_plus_io": round(us, 2), "us_per_layer_issue_io": round(us_io, 2),
+                      "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
+                      "traffic_GBps_issue_io": round(2 * payload / (us_io * 1e-6) / 1e9, 1),
+                      "pct_hbm_peak_issue_io": round(100 * 2 * payload / (us_io * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
+    done = int(cq[:4].view(torch.int32)[0].item())
+    assert int(status.item()) == 0 and done == depth, (int(status.item()), done, depth)
+    log(f"[bench] rings: {res}")
     return res
 
 

@@ -180,6 +180,87 @@ int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, cons
                            const uint32_t *d_file_id, uint32_t layer, uint32_t opcode, uint64_t sgl_table_addr,
                            uint32_t sgl_id, tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t *d_status, void *stream);
 
+/* ---- submission / completion rings (sec. 3.2 "Zero-Copy Ring Buffers" and "Async I/O Processing").
+ * An SQ entry is an IOCB: a 64-byte header followed by 2048 I/O contexts (tutti_sqe records); the CQ
+ * collects the indices of completed IOCBs.  Rings live in caller-allocated DEVICE memory (the paper maps
+ * them to the CPU so that it can fill them; here the GPU fills them itself, so no mapping is needed).
+ * The header layout, the CQ layout and the file store that stands in for the SSD are this repository's. */
+#define TUTTI_IOCB_FREE 0u
+#define TUTTI_IOCB_FILLED 1u
+#define TUTTI_IOCB_DONE 2u
+
+typedef struct tutti_iocb_hdr {
+  uint32_t iocb_idx;  /* unique index = slot in the SQ (tutti_ring_init) */
+  uint32_t num_ioctx; /* valid contexts (tutti_iocb_fill_direct) */
+  uint32_t state;     /* TUTTI_IOCB_* */
+  uint32_t done;      /* contexts completed: 0 while FILLED, num_ioctx once DONE */
+  uint32_t layer;
+  uint32_t opcode;
+  uint32_t rsvd[10];
+} tutti_iocb_hdr;
+
+typedef struct tutti_iocb {
+  tutti_iocb_hdr hdr;
+  tutti_sqe ioctx[TUTTI_IOCB_SLOTS];
+} tutti_iocb; /* 64 + 2048*64 = 131136 bytes */
+
+typedef struct tutti_cq_hdr {
+  uint32_t tail;  /* completions so far */
+  uint32_t depth;
+  uint32_t rsvd[14];
+  /* followed by uint32_t entry[depth]: entry[t % depth] = index of the t-th completed IOCB */
+} tutti_cq_hdr;
+
+/* Host-side handle of a ring: d_sq = depth IOCBs, d_cq = tutti_cq_hdr + depth entries (64 + 4*depth bytes),
+ * both 16-byte aligned device memory owned by the caller. */
+typedef struct tutti_ring {
+  tutti_iocb *d_sq;
+  void *d_cq;
+  uint32_t depth;
+} tutti_ring;
+
+/* The stand-in for the SSD: n_files GPU files of file_stride bytes in device(-accessible) memory,
+ * file f at base + (f - first_file_id)*file_stride; base and file_stride multiples of 16. */
+typedef struct tutti_filestore {
+  void *base;
+  uint64_t file_stride;
+  uint32_t first_file_id;
+  uint32_t n_files;
+} tutti_filestore;
+
+/* init_queue(depth): every IOCB FREE with its unique index, CQ empty (entries 0xffffffff). */
+int tutti_ring_init(const tutti_ring *ring, void *stream);
+
+/* get_iocb + fill, done by the GPU for one layer in direct-to-block mode: context i of
+ * tutti_sqe_build_direct goes to IOCB slot (first_slot + i/2048) % depth, position i % 2048.  All n_slots
+ * IOCBs become FILLED with num_ioctx (0 if unused), layer, opcode and done = 0.  The host picks first_slot
+ * and n_slots (ceil(2*table_len/2048) always suffices); contexts beyond n_slots*2048 are dropped and
+ * reported (TUTTI_ST_SQE_CAP).  Other arguments as in tutti_sqe_build_direct. */
+int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                           const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                           const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                           uint32_t layer, uint32_t opcode, uint64_t sgl_table_addr, uint32_t sgl_id,
+                           uint32_t *d_status, void *stream);
+
+/* issue_io(IOCB_ids, SMs): the I/O kernel.  Executes every context of the n_slots FILLED IOCBs starting
+ * at first_slot: resolves the SGL descriptor the context names (index (addr - sgl_table_addr)/16 into
+ * d_sgl_table of n_desc descriptors, whose addr fields must be device addresses here), then moves len
+ * bytes between that block and the request's GPU file at file_off (READ: file -> block, WRITE: block ->
+ * file), one wavefront per 4 or 8 KiB slice.  A one-wavefront completion kernel enqueued right behind the
+ * I/O kernel then marks every executed IOCB DONE (done = num_ioctx) and appends its index to the CQ, in slot
+ * order: the kernel boundary is the "all contexts finished" event (counting finished contexts with atomics on
+ * the IOCB header was measured 28x slower).  max_len bounds the length of any context (the pool's block size).
+ * Contexts naming a descriptor or file out of range, longer than their descriptor or max_len, or not 16-byte
+ * aligned are skipped (TUTTI_ST_BAD_BLOCK).  cu_budget as in tutti_layer_restore.  Two tutti_issue_io calls on
+ * the same ring must be ordered by the stream (they share the CQ tail). */
+int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_sgl *d_sgl_table,
+                   uint32_t n_desc, uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len,
+                   uint32_t cu_budget, uint32_t *d_status, void *stream);
+
+/* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
+ * it on any stream and read the flag after synchronising that stream. */
+int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);
+
 /* ---- measurement aid: a plain contiguous device-to-device copy of `bytes` (multiple of 16, both
  * pointers 16-byte aligned) with the same load/store width and launch shape as unpack: the
  * achievable ceiling the pack/unpack rates are compared with. */
@@ -190,8 +271,9 @@ const char *tutti_strerror(int code);
 int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */
 int tutti_cu_count(void);           /* compute units of the current device, or a negative TUTTI_E* */
 uint32_t tutti_version(void);       /* 0x00MMmmpp */
-/* sizeof / offsetof table of the records above (37 values: extent size + 6 offsets, sqe size + 11,
- * pool size + 9, objcfg size + 3, sgl size + 3); returns the count or TUTTI_EINVAL if cap is too small. */
+/* sizeof / offsetof table of the records above (52 values: extent size + 6 offsets, sqe size + 11,
+ * pool size + 9, objcfg size + 3, sgl size + 3, iocb_hdr size + 6, iocb size + offset of its contexts,
+ * cq_hdr size, filestore size + 4); returns the count or TUTTI_EINVAL if cap is too small. */
 int tutti_abi_describe(uint32_t *out, uint32_t cap);
 /* Launch tuning, for experiments: wgs_per_cu persistent workgroups per budgeted CU (0 = default),
  * unroll = 16-byte accesses in flight per lane (0 = default; 1, 2, 4 or 8). */

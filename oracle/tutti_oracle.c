@@ -45,7 +45,7 @@ static int check_geometry(const orc_pool *pool, const orc_objcfg *cfg) {
 }
 
 int orc_abi_describe(uint32_t *out, uint32_t cap) {
-  if (!out || cap < 37) return ORC_EINVAL;
+  if (!out || cap < 52) return ORC_EINVAL;
   uint32_t i = 0;
   out[i++] = sizeof(orc_extent);
   out[i++] = offsetof(orc_extent, stage_off);
@@ -84,6 +84,21 @@ int orc_abi_describe(uint32_t *out, uint32_t cap) {
   out[i++] = offsetof(orc_sgl, addr);
   out[i++] = offsetof(orc_sgl, len);
   out[i++] = offsetof(orc_sgl, id);
+  out[i++] = sizeof(orc_iocb_hdr);
+  out[i++] = offsetof(orc_iocb_hdr, iocb_idx);
+  out[i++] = offsetof(orc_iocb_hdr, num_ioctx);
+  out[i++] = offsetof(orc_iocb_hdr, state);
+  out[i++] = offsetof(orc_iocb_hdr, done);
+  out[i++] = offsetof(orc_iocb_hdr, layer);
+  out[i++] = offsetof(orc_iocb_hdr, opcode);
+  out[i++] = sizeof(orc_iocb);
+  out[i++] = offsetof(orc_iocb, ioctx);
+  out[i++] = sizeof(orc_cq_hdr);
+  out[i++] = sizeof(orc_filestore);
+  out[i++] = offsetof(orc_filestore, base);
+  out[i++] = offsetof(orc_filestore, file_stride);
+  out[i++] = offsetof(orc_filestore, first_file_id);
+  out[i++] = offsetof(orc_filestore, n_files);
   return (int)i;
 }
 
@@ -321,6 +336,33 @@ int orc_sgl_table_build(const orc_pool *pool, uint64_t k_addr, uint64_t v_addr, 
   return ORC_OK;
 }
 
+/* One direct-mode context: block j of request r (extent x), plane `kind`, entry index i of the layer. */
+static uint32_t make_direct_entry(const orc_pool *pool, const orc_extent *x, uint32_t r, uint32_t kind, uint32_t j,
+                                  uint32_t id, uint32_t file_id, uint32_t layer, uint32_t opcode,
+                                  uint64_t sgl_table_addr, uint32_t sgl_id, uint64_t i, orc_sqe *out) {
+  const uint64_t bb = orc_block_bytes(pool);
+  uint32_t st = 0;
+  orc_sqe s;
+  memset(&s, 0, sizeof s);
+  s.opcode = (uint8_t)opcode;
+  s.kind = (uint8_t)kind;
+  s.layer = (uint16_t)layer;
+  s.file_id = file_id;
+  s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)j * bb;
+  if (id < pool->num_blocks) {
+    s.addr = sgl_table_addr + 16ull * ((uint64_t)kind * pool->num_blocks + id);
+    s.len = (uint32_t)bb;
+  } else {
+    st = ORC_ST_BAD_BLOCK; /* a no-op entry: nothing to transfer */
+  }
+  s.sgl_id = sgl_id;
+  s.user_data = ((uint64_t)r << 32) | (uint32_t)i;
+  s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);
+  s.ioctx_slot = (uint32_t)(i % ORC_IOCB_SLOTS);
+  *out = s;
+  return st;
+}
+
 /*
  * Entries of the paper's own data path: each hit block is one object (sec. 3.1, "representing each
  * memory block as one object") and one I/O context whose SGL address is the block's descriptor in
@@ -354,25 +396,129 @@ int orc_sqe_build_direct(const orc_pool *pool, const orc_objcfg *cfg, const orc_
         }
         uint32_t id = block_table[(uint64_t)x->table_off + j];
         orc_sqe s;
-        memset(&s, 0, sizeof s);
-        s.opcode = (uint8_t)opcode;
-        s.kind = (uint8_t)kind;
-        s.layer = (uint16_t)layer;
-        s.file_id = file_id[r];
-        s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)j * bb;
-        if (id < pool->num_blocks) {
-          s.addr = sgl_table_addr + 16ull * ((uint64_t)kind * pool->num_blocks + id);
-          s.len = (uint32_t)bb;
-        } else {
-          st |= ORC_ST_BAD_BLOCK; /* a no-op entry: nothing to transfer */
-        }
-        s.sgl_id = sgl_id;
-        s.user_data = ((uint64_t)r << 32) | (uint32_t)i;
-        s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);
-        s.ioctx_slot = (uint32_t)(i % ORC_IOCB_SLOTS);
+        st |= make_direct_entry(pool, x, r, kind, j, id, file_id[r], layer, opcode, sgl_table_addr, sgl_id, i, &s);
         sqe[i] = s;
       }
     }
+  }
+  if (status && st) *status |= st;
+  return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ rings */
+
+/* init_queue(depth) of sec. 3.2: depth IOCBs, each with a unique index, and an empty CQ. */
+int orc_ring_init(orc_iocb *sq, void *cq, uint32_t depth) {
+  if (!sq || !cq || depth == 0) return ORC_EINVAL;
+  for (uint32_t b = 0; b < depth; ++b) {
+    memset(&sq[b].hdr, 0, sizeof sq[b].hdr);
+    sq[b].hdr.iocb_idx = b;
+    sq[b].hdr.state = ORC_IOCB_FREE;
+  }
+  orc_cq_hdr *c = (orc_cq_hdr *)cq;
+  memset(c, 0, sizeof *c);
+  c->depth = depth;
+  uint32_t *entry = (uint32_t *)(c + 1);
+  for (uint32_t b = 0; b < depth; ++b) entry[b] = 0xffffffffu;
+  return ORC_OK;
+}
+
+/*
+ * get_iocb + fill (sec. 3.2): the contexts of one layer, as orc_sqe_build_direct numbers them, laid into
+ * consecutive IOCBs of 2048 contexts each; num_ioctx records how many of an IOCB's slots are valid.
+ */
+int orc_iocb_fill_direct(orc_iocb *sq, uint32_t depth, uint32_t first_slot, uint32_t n_slots, const orc_pool *pool,
+                         const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req, const uint32_t *block_table,
+                         const uint32_t *file_id, uint32_t layer, uint32_t opcode, uint64_t sgl_table_addr,
+                         uint32_t sgl_id, uint32_t *status) {
+  if (!sq || depth == 0 || n_slots > depth || first_slot >= depth) return ORC_EINVAL;
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (orc_block_bytes(pool) % cfg->align != 0) return ORC_EINVAL;
+  if (opcode != ORC_OP_READ && opcode != ORC_OP_WRITE) return ORC_EINVAL;
+  if (layer >= cfg->num_layers || sgl_table_addr % 16 != 0) return ORC_EINVAL;
+  if (n_req > 0 && (!extents || !file_id)) return ORC_EINVAL;
+  uint64_t n = 0;
+  for (uint32_t r = 0; r < n_req; ++r) n += 2ull * extents[r].n_blocks;
+  if (n > 0 && !block_table) return ORC_EINVAL;
+  const uint64_t cap = (uint64_t)n_slots * ORC_IOCB_SLOTS;
+  const uint64_t n_fill = n < cap ? n : cap;
+
+  for (uint32_t b = 0; b < n_slots; ++b) {
+    orc_iocb *io = &sq[(first_slot + b) % depth];
+    uint64_t lo = (uint64_t)b * ORC_IOCB_SLOTS;
+    uint64_t cnt = n_fill > lo ? n_fill - lo : 0;
+    if (cnt > ORC_IOCB_SLOTS) cnt = ORC_IOCB_SLOTS;
+    io->hdr.num_ioctx = (uint32_t)cnt;
+    io->hdr.state = ORC_IOCB_FILLED;
+    io->hdr.done = 0;
+    io->hdr.layer = layer;
+    io->hdr.opcode = opcode;
+  }
+  uint32_t st = 0;
+  for (uint32_t r = 0; r < n_req; ++r) {
+    const orc_extent *x = &extents[r];
+    for (uint32_t kind = 0; kind < 2; ++kind) {
+      for (uint32_t j = 0; j < x->n_blocks; ++j) {
+        uint64_t i = 2ull * x->table_off + (uint64_t)kind * x->n_blocks + j;
+        if (i >= cap) {
+          st |= ORC_ST_SQE_CAP;
+          continue;
+        }
+        orc_iocb *io = &sq[(first_slot + (uint32_t)(i / ORC_IOCB_SLOTS)) % depth];
+        orc_sqe *s = &io->ioctx[i % ORC_IOCB_SLOTS];
+        st |= make_direct_entry(pool, x, r, kind, j, block_table[(uint64_t)x->table_off + j], file_id[r], layer, opcode,
+                                sgl_table_addr, sgl_id, i, s);
+      }
+    }
+  }
+  if (status && st) *status |= st;
+  return ORC_OK;
+}
+
+/*
+ * issue_io (sec. 3.2): every context becomes one transfer between the block its SGL descriptor describes and
+ * the GPU file at its offset; when an IOCB's contexts are done its index goes to the CQ.
+ */
+int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
+                 const orc_sgl *sgl_table, uint32_t n_desc, uint64_t sgl_table_addr, const orc_filestore *store,
+                 uint32_t *status) {
+  if (!sq || !cq || depth == 0 || n_slots > depth || first_slot >= depth) return ORC_EINVAL;
+  if (!store || !store->base || (n_desc > 0 && !sgl_table)) return ORC_EINVAL;
+  orc_cq_hdr *c = (orc_cq_hdr *)cq;
+  uint32_t *entry = (uint32_t *)(c + 1);
+  uint32_t st = 0;
+  for (uint32_t b = 0; b < n_slots; ++b) {
+    orc_iocb *io = &sq[(first_slot + b) % depth];
+    if (io->hdr.state != ORC_IOCB_FILLED) continue; /* nothing was submitted in this slot */
+    for (uint32_t k = 0; k < io->hdr.num_ioctx && k < ORC_IOCB_SLOTS; ++k) {
+      const orc_sqe *s = &io->ioctx[k];
+      if (s->len == 0) continue; /* a no-op context */
+      if (s->addr < sgl_table_addr || (s->addr - sgl_table_addr) % 16 != 0) {
+        st |= ORC_ST_BAD_BLOCK;
+        continue;
+      }
+      uint64_t di = (s->addr - sgl_table_addr) / 16;
+      if (di >= n_desc || s->len > sgl_table[di].len) {
+        st |= ORC_ST_BAD_BLOCK;
+        continue;
+      }
+      if (s->file_id < store->first_file_id || s->file_id - store->first_file_id >= store->n_files ||
+          s->file_off + s->len > store->file_stride) {
+        st |= ORC_ST_BAD_BLOCK;
+        continue;
+      }
+      uint8_t *blk = (uint8_t *)(uintptr_t)sgl_table[di].addr;
+      uint8_t *fil = (uint8_t *)store->base + (uint64_t)(s->file_id - store->first_file_id) * store->file_stride + s->file_off;
+      if (s->opcode == ORC_OP_READ)
+        memcpy(blk, fil, s->len);
+      else
+        memcpy(fil, blk, s->len);
+    }
+    io->hdr.state = ORC_IOCB_DONE;
+    io->hdr.done = io->hdr.num_ioctx;
+    entry[c->tail % depth] = io->hdr.iocb_idx;
+    c->tail += 1;
   }
   if (status && st) *status |= st;
   return ORC_OK;

@@ -102,7 +102,8 @@ typedef struct {
 /* Size/offset table of the records above, for the cross-check against the library's header:
  * out[0..]: sizeof(extent), offsets of its 6 fields, sizeof(sqe), offsets of its 11 fields,
  * sizeof(pool), offsets of its 9 fields, sizeof(objcfg), offsets of its 3 fields, sizeof(sgl), offsets of
- * its 3 fields (37 values). */
+ * its 3 fields, sizeof(iocb_hdr), offsets of its 6 named fields, sizeof(iocb), offset of its contexts,
+ * sizeof(cq_hdr), sizeof(filestore), offsets of its 4 fields (52 values). */
 int orc_abi_describe(uint32_t *out, uint32_t cap);
 
 /* T*h*d*e, or 0 if any factor is 0 or the product does not fit 32 bits. */
@@ -159,6 +160,65 @@ int orc_sgl_table_build(const orc_pool *pool, uint64_t k_addr, uint64_t v_addr, 
 int orc_sqe_build_direct(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
                          const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint32_t opcode,
                          uint64_t sgl_table_addr, uint32_t sgl_id, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
+
+/* ---- submission / completion rings (sec. 3.2 "Zero-Copy Ring Buffers", "Async I/O Processing").
+ * An SQ entry is an IOCB: a 64-byte header and 2048 I/O contexts (submission entries).  The CQ holds
+ * the indices of completed IOCBs.  Repository readings: the header layout, the CQ layout (tail counter
+ * + index array) and the file store that stands in for the SSD are not fixed by the paper. */
+#define ORC_IOCB_FREE 0u
+#define ORC_IOCB_FILLED 1u
+#define ORC_IOCB_DONE 2u
+
+typedef struct {
+  uint32_t iocb_idx;  /* unique index = slot in the SQ */
+  uint32_t num_ioctx; /* valid contexts */
+  uint32_t state;     /* ORC_IOCB_* */
+  uint32_t done;      /* contexts completed: 0 while FILLED, num_ioctx once DONE */
+  uint32_t layer;
+  uint32_t opcode;
+  uint32_t rsvd[10];
+} orc_iocb_hdr;
+
+typedef struct {
+  orc_iocb_hdr hdr;
+  orc_sqe ioctx[ORC_IOCB_SLOTS];
+} orc_iocb;
+
+typedef struct {
+  uint32_t tail; /* completions so far */
+  uint32_t depth;
+  uint32_t rsvd[14];
+  /* followed by uint32_t entry[depth]: entry[t % depth] = index of the t-th completed IOCB */
+} orc_cq_hdr;
+
+/* The stand-in for the SSD: n_files GPU files of file_stride bytes, file f at base + (f - first_file_id)*file_stride. */
+typedef struct {
+  void *base;
+  uint64_t file_stride;
+  uint32_t first_file_id;
+  uint32_t n_files;
+} orc_filestore;
+
+/* init_queue(depth): every IOCB free with its unique index, CQ empty. */
+int orc_ring_init(orc_iocb *sq, void *cq, uint32_t depth);
+
+/* get_iocb + fill for one layer in direct-to-block mode: context i of orc_sqe_build_direct goes to IOCB slot
+ * (first_slot + i / 2048) % depth, position i % 2048.  All n_slots IOCBs become FILLED with their num_ioctx
+ * (0 if unused), layer and opcode.  Contexts beyond n_slots*2048 are dropped (ORC_ST_SQE_CAP). */
+int orc_iocb_fill_direct(orc_iocb *sq, uint32_t depth, uint32_t first_slot, uint32_t n_slots, const orc_pool *pool,
+                         const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req, const uint32_t *block_table,
+                         const uint32_t *file_id, uint32_t layer, uint32_t opcode, uint64_t sgl_table_addr,
+                         uint32_t sgl_id, uint32_t *status);
+
+/* issue_io: execute every context of the n_slots IOCBs starting at first_slot, in order: resolve the SGL
+ * descriptor the context names (index (addr - sgl_table_addr)/16 into sgl_table, n_desc entries), then move
+ * len bytes between that block and the request's GPU file at file_off (READ: file -> block, WRITE: block ->
+ * file).  The descriptor's address is used as a host pointer here.  Each IOCB is then marked DONE and its
+ * index appended to the CQ.  Contexts naming a descriptor or file outside the given ranges, or longer than
+ * the descriptor, are skipped (ORC_ST_BAD_BLOCK). */
+int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
+                 const orc_sgl *sgl_table, uint32_t n_desc, uint64_t sgl_table_addr, const orc_filestore *store,
+                 uint32_t *status);
 
 /* Descriptor count for a pool of pool_bytes described at gran bytes per descriptor
  * (the arithmetic of sec. 3.1, "P2P Memory Mapping Table"). */

@@ -30,6 +30,18 @@ SQE_DTYPE = np.dtype([("opcode", "u1"), ("kind", "u1"), ("layer", "<u2"), ("file
 SGL_DTYPE = np.dtype([("addr", "<u8"), ("len", "<u4"), ("id", "<u4")], align=True)
 
 
+IOCB_FREE, IOCB_FILLED, IOCB_DONE = 0, 1, 2
+IOCB_HDR_DTYPE = np.dtype([("iocb_idx", "<u4"), ("num_ioctx", "<u4"), ("state", "<u4"), ("done", "<u4"),
+                           ("layer", "<u4"), ("opcode", "<u4"), ("rsvd", "<u4", (10,))], align=True)
+IOCB_DTYPE = np.dtype([("hdr", IOCB_HDR_DTYPE), ("ioctx", SQE_DTYPE, (IOCB_SLOTS,))], align=True)
+CQ_HDR_WORDS = 16  # tail, depth, 14 reserved; then depth entries
+
+
+class OrcFileStore(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("file_stride", C.c_uint64), ("first_file_id", C.c_uint32),
+                ("n_files", C.c_uint32)]
+
+
 class OrcPool(C.Structure):
     _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p), ("block_stride", C.c_uint64),
                 ("num_blocks", C.c_uint32), ("block_tokens", C.c_uint32), ("num_kv_heads", C.c_uint32),
@@ -213,3 +225,40 @@ def sqe_build_direct(pool, cfg, extents, block_table, file_id, layer, opcode, sg
     if rc:
         raise OracleError("orc_sqe_build_direct", rc)
     return sqe, status.value
+
+
+def ring_alloc(depth):
+    """Host memory for an SQ of `depth` IOCBs and its CQ (uint32 words: 16 header words + depth entries)."""
+    return np.zeros(depth, IOCB_DTYPE), np.zeros(CQ_HDR_WORDS + depth, np.uint32)
+
+
+def ring_init(sq, cq):
+    rc = lib().orc_ring_init(_ptr(sq), _ptr(cq), C.c_uint32(sq.size))
+    if rc:
+        raise OracleError("orc_ring_init", rc)
+
+
+def iocb_fill_direct(sq, first_slot, n_slots, pool, cfg, extents, block_table, file_id, layer, opcode,
+                     sgl_table_addr, sgl_id):
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    file_id = np.ascontiguousarray(file_id, dtype=np.uint32)
+    status = C.c_uint32(0)
+    rc = lib().orc_iocb_fill_direct(_ptr(sq), C.c_uint32(sq.size), C.c_uint32(first_slot), C.c_uint32(n_slots),
+                                    C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
+                                    _ptr(block_table), _ptr(file_id), C.c_uint32(layer), C.c_uint32(opcode),
+                                    C.c_uint64(sgl_table_addr), C.c_uint32(sgl_id), C.byref(status))
+    if rc:
+        raise OracleError("orc_iocb_fill_direct", rc)
+    return status.value
+
+
+def issue_io(sq, cq, first_slot, n_slots, sgl_table, sgl_table_addr, store, file_stride, first_file_id, n_files):
+    """`store`: uint8 host array of n_files * file_stride bytes.  Returns the status word."""
+    fs = OrcFileStore(store.ctypes.data, file_stride, first_file_id, n_files)
+    status = C.c_uint32(0)
+    rc = lib().orc_issue_io(_ptr(sq), _ptr(cq), C.c_uint32(sq.size), C.c_uint32(first_slot), C.c_uint32(n_slots),
+                            _ptr(sgl_table), C.c_uint32(sgl_table.size), C.c_uint64(sgl_table_addr), C.byref(fs),
+                            C.byref(status))
+    if rc:
+        raise OracleError("orc_issue_io", rc)
+    return status.value

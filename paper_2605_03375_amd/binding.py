@@ -35,7 +35,8 @@ SGL_DTYPE = np.dtype({"names": ["addr", "len", "id"], "formats": ["<u8", "<u4", 
                       "itemsize": 16})
 
 EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
-           "tutti_sgl_table_build", "tutti_sqe_build_direct",
+           "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
+           "tutti_issue_io", "tutti_wait_cqe",
            "tutti_copy_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"]
 
@@ -48,6 +49,41 @@ class tutti_pool(C.Structure):
 
 class tutti_objcfg(C.Structure):
     _fields_ = [("align", C.c_uint32), ("chunk_bytes", C.c_uint32), ("num_layers", C.c_uint32)]
+
+
+class tutti_ring(C.Structure):
+    _fields_ = [("d_sq", C.c_void_p), ("d_cq", C.c_void_p), ("depth", C.c_uint32)]
+
+
+class tutti_filestore(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("file_stride", C.c_uint64), ("first_file_id", C.c_uint32),
+                ("n_files", C.c_uint32)]
+
+
+IOCB_FREE, IOCB_FILLED, IOCB_DONE = 0, 1, 2
+IOCB_HDR_DTYPE = np.dtype({"names": ["iocb_idx", "num_ioctx", "state", "done", "layer", "opcode"],
+                           "formats": ["<u4"] * 6, "offsets": [0, 4, 8, 12, 16, 20], "itemsize": 64})
+IOCB_DTYPE = np.dtype({"names": ["hdr", "ioctx"], "formats": [IOCB_HDR_DTYPE, (SQE_DTYPE, (IOCB_SLOTS,))],
+                       "offsets": [0, 64], "itemsize": 64 + 64 * IOCB_SLOTS})
+IOCB_BYTES = IOCB_DTYPE.itemsize
+CQ_HDR_BYTES = 64
+
+
+def ring_bytes(depth):
+    """Bytes of device memory for an SQ and a CQ of `depth` IOCBs."""
+    return depth * IOCB_BYTES, CQ_HDR_BYTES + 4 * depth
+
+
+def make_ring(d_sq, d_cq, depth):
+    r = tutti_ring(_p(d_sq), _p(d_cq), depth)
+    r._keep = (d_sq, d_cq)
+    return r
+
+
+def make_filestore(base, file_stride, first_file_id, n_files):
+    f = tutti_filestore(_p(base), file_stride, first_file_id, n_files)
+    f._keep = base
+    return f
 
 
 class TuttiError(RuntimeError):
@@ -79,6 +115,11 @@ def lib():
         L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
                                           vp, vp]
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
+        pr, pf = C.POINTER(tutti_ring), C.POINTER(tutti_filestore)
+        L.tutti_ring_init.argtypes = [pr, vp]
+        L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
+        L.tutti_issue_io.argtypes = [pr, u32, u32, vp, u32, u64, pf, u32, u32, vp, vp]
+        L.tutti_wait_cqe.argtypes = [pr, u32, vp, vp]
         L.tutti_sgl_table_build.argtypes = [pp, u64, u64, u32, vp, u32, vp, vp]
         L.tutti_sqe_build_direct.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
         L.tutti_strerror.argtypes = [C.c_int]
@@ -88,7 +129,8 @@ def lib():
         L.tutti_set_tuning.argtypes = [u32, u32]
         L.tutti_set_nontemporal.argtypes = [u32]
         L.tutti_set_hnd_mode.argtypes = [u32]
-        for name in ("tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
+        for name in ("tutti_ring_init", "tutti_iocb_fill_direct", "tutti_issue_io", "tutti_wait_cqe",
+                     "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
                      "tutti_layer_restore", "tutti_copy_baseline", "tutti_last_hip_error", "tutti_cu_count",
                      "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"):
             getattr(L, name).restype = C.c_int
@@ -185,6 +227,29 @@ def tutti_sqe_build_direct(pool, cfg, d_extents, n_req, d_block_table, table_len
                   lib().tutti_sqe_build_direct(C.byref(pool), C.byref(cfg), _p(d_extents), n_req, _p(d_block_table),
                                                table_len, _p(d_file_id), layer, opcode, sgl_table_addr, sgl_id,
                                                _p(d_sqe), sqe_cap, _p(d_status), _stream(stream)))
+
+
+def tutti_ring_init(ring, stream=None):
+    return _check("tutti_ring_init", lib().tutti_ring_init(C.byref(ring), _stream(stream)))
+
+
+def tutti_iocb_fill_direct(ring, first_slot, n_slots, pool, cfg, d_extents, n_req, d_block_table, table_len,
+                           d_file_id, layer, opcode, sgl_table_addr, sgl_id, d_status=None, stream=None):
+    return _check("tutti_iocb_fill_direct",
+                  lib().tutti_iocb_fill_direct(C.byref(ring), first_slot, n_slots, C.byref(pool), C.byref(cfg),
+                                               _p(d_extents), n_req, _p(d_block_table), table_len, _p(d_file_id),
+                                               layer, opcode, sgl_table_addr, sgl_id, _p(d_status), _stream(stream)))
+
+
+def tutti_issue_io(ring, first_slot, n_slots, d_sgl_table, n_desc, sgl_table_addr, store, max_len, cu_budget=0,
+                   d_status=None, stream=None):
+    return _check("tutti_issue_io",
+                  lib().tutti_issue_io(C.byref(ring), first_slot, n_slots, _p(d_sgl_table), n_desc, sgl_table_addr,
+                                       C.byref(store), max_len, cu_budget, _p(d_status), _stream(stream)))
+
+
+def tutti_wait_cqe(ring, slot, d_flag, stream=None):
+    return _check("tutti_wait_cqe", lib().tutti_wait_cqe(C.byref(ring), slot, _p(d_flag), _stream(stream)))
 
 
 def tutti_copy_baseline(d_dst, d_src, nbytes, cu_budget=0, stream=None):

@@ -570,6 +570,129 @@ int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, cons
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+namespace {
+int check_ring(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots) {
+  if (!ring || !ring->d_sq || !ring->d_cq || ring->depth == 0) return TUTTI_EINVAL;
+  if (!aligned16(ring->d_sq) || !aligned16(ring->d_cq)) return TUTTI_EINVAL;
+  if (first_slot >= ring->depth || n_slots > ring->depth) return TUTTI_EINVAL;
+  return TUTTI_OK;
+}
+}  // namespace
+
+int tutti_ring_init(const tutti_ring *ring, void *stream) {
+  int rc = check_ring(ring, 0, 0);
+  if (rc) return rc;
+  const uint32_t n = ring->depth > 16 ? ring->depth : 16;
+  hipLaunchKernelGGL(k_ring_init, dim3((n + kWgThreads - 1) / kWgThreads), dim3(kWgThreads), 0,
+                     static_cast<hipStream_t>(stream), ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                           const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
+                           const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                           uint32_t layer, uint32_t opcode, uint64_t sgl_table_addr, uint32_t sgl_id,
+                           uint32_t *d_status, void *stream) {
+  int rc = check_ring(ring, first_slot, n_slots);
+  if (rc) return rc;
+  uint32_t bb = 0;
+  rc = check_geometry(pool, cfg, &bb);
+  if (rc) return rc;
+  if (bb % cfg->align != 0) return TUTTI_EINVAL;
+  if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
+  if (n_req > 0 && (!d_extents || !d_file_id)) return TUTTI_EINVAL;
+  if (table_len > 0 && !d_block_table) return TUTTI_EINVAL;
+  if (opcode != TUTTI_OP_READ && opcode != TUTTI_OP_WRITE) return TUTTI_EINVAL;
+  if (layer >= cfg->num_layers) return TUTTI_EINVAL;
+  if (sgl_table_addr % 16 != 0) return TUTTI_EINVAL;
+  if (n_slots == 0) return TUTTI_OK;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
+  SqeArgs q;
+  q.file_id = d_file_id;
+  q.sqe = nullptr;
+  q.status = d_status;
+  q.stage_addr = 0;
+  q.sqe_cap = 0;
+  q.chunk_bytes = bb;
+  q.layer = layer;
+  q.opcode = opcode;
+  q.sgl_id = sgl_id;
+  DirectArgs d;
+  d.table = d_block_table;
+  d.sgl_table_addr = sgl_table_addr;
+  d.table_len = table_len;
+  d.num_blocks = pool->num_blocks;
+  d.block_bytes = bb;
+  uint64_t need = (4ull * n_slots * TUTTI_IOCB_SLOTS + kWgThreads - 1) / kWgThreads;
+  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
+  const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
+  hipLaunchKernelGGL(k_iocb_fill, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req), static_cast<hipStream_t>(stream),
+                     g, q, d, d_extents, n_req);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_sgl *d_sgl_table,
+                   uint32_t n_desc, uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len,
+                   uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  int rc = check_ring(ring, first_slot, n_slots);
+  if (rc) return rc;
+  if (!store || !store->base || !aligned16(store->base) || store->file_stride % 16 != 0) return TUTTI_EINVAL;
+  if (n_desc > 0 && (!d_sgl_table || !aligned16(d_sgl_table))) return TUTTI_EINVAL;
+  if (max_len == 0 || max_len % 16 != 0 || sgl_table_addr % 16 != 0) return TUTTI_EINVAL;
+  if (n_slots == 0) return TUTTI_OK;
+  Launch L;
+  rc = plan_launch(cu_budget, 0, &L);
+  if (rc) return rc;
+  const uint32_t unroll = (L.unroll == 8) ? 8u : 4u;  // 8 KiB slices under a CU budget, 4 KiB otherwise
+  const uint32_t slice = kWave * 16u * unroll;
+  IoArgs a;
+  a.sgl = d_sgl_table;
+  a.store_base = static_cast<unsigned char *>(store->base);
+  a.status = d_status;
+  a.sgl_table_addr = sgl_table_addr;
+  a.file_stride = store->file_stride;
+  a.n_desc = n_desc;
+  a.first_file_id = store->first_file_id;
+  a.n_files = store->n_files;
+  a.max_len = max_len;
+  a.slices = static_cast<uint32_t>((static_cast<uint64_t>(max_len) + slice - 1) / slice);
+  const uint64_t items = static_cast<uint64_t>(n_slots) * TUTTI_IOCB_SLOTS * a.slices;
+  if (items > 0xffffffffull) return TUTTI_ERANGE;
+  rc = plan_launch(cu_budget, items, &L);
+  if (rc) return rc;
+  RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (L.wg_threads == kWgThreads) {
+    if (unroll == 8)
+      hipLaunchKernelGGL((k_issue_io<8, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, g, a);
+    else
+      hipLaunchKernelGGL((k_issue_io<4, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, g, a);
+  } else {
+    if (unroll == 8)
+      hipLaunchKernelGGL((k_issue_io<8, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, g, a);
+    else
+      hipLaunchKernelGGL((k_issue_io<4, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, g, a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, s, g);
+  e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream) {
+  int rc = check_ring(ring, slot, 0);
+  if (rc) return rc;
+  if (!d_flag) return TUTTI_EINVAL;
+  hipLaunchKernelGGL(k_cq_check, dim3(1), dim3(kWave), 0, static_cast<hipStream_t>(stream), ring->d_sq, slot, d_flag);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
 int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream) {
   if (!d_dst || !d_src || !aligned16(d_dst) || !aligned16(d_src) || bytes % 16 != 0) return TUTTI_EINVAL;
   if (bytes == 0) return TUTTI_OK;
@@ -635,7 +758,7 @@ int tutti_cu_count(void) { return cu_count(); }
 uint32_t tutti_version(void) { return 0x00000100u; }
 
 int tutti_abi_describe(uint32_t *out, uint32_t cap) {
-  if (!out || cap < 37) return TUTTI_EINVAL;
+  if (!out || cap < 52) return TUTTI_EINVAL;
   uint32_t i = 0;
   out[i++] = sizeof(tutti_extent);
   out[i++] = offsetof(tutti_extent, stage_off);
@@ -674,6 +797,21 @@ int tutti_abi_describe(uint32_t *out, uint32_t cap) {
   out[i++] = offsetof(tutti_sgl, addr);
   out[i++] = offsetof(tutti_sgl, len);
   out[i++] = offsetof(tutti_sgl, id);
+  out[i++] = sizeof(tutti_iocb_hdr);
+  out[i++] = offsetof(tutti_iocb_hdr, iocb_idx);
+  out[i++] = offsetof(tutti_iocb_hdr, num_ioctx);
+  out[i++] = offsetof(tutti_iocb_hdr, state);
+  out[i++] = offsetof(tutti_iocb_hdr, done);
+  out[i++] = offsetof(tutti_iocb_hdr, layer);
+  out[i++] = offsetof(tutti_iocb_hdr, opcode);
+  out[i++] = sizeof(tutti_iocb);
+  out[i++] = offsetof(tutti_iocb, ioctx);
+  out[i++] = sizeof(tutti_cq_hdr);
+  out[i++] = sizeof(tutti_filestore);
+  out[i++] = offsetof(tutti_filestore, base);
+  out[i++] = offsetof(tutti_filestore, file_stride);
+  out[i++] = offsetof(tutti_filestore, first_file_id);
+  out[i++] = offsetof(tutti_filestore, n_files);
   return static_cast<int>(i);
 }
 

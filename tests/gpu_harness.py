@@ -238,3 +238,65 @@ def check_direct_mode(orc, c, layer=0, sgl_id=17, sqe_cap=None, table_len=None):
         assert got[: 64 * w].tobytes() == o_sqe[:w].tobytes(), f"{c.name}: direct entries differ (op {op})"
         assert np.all(got[64 * w:] == 0x3C) and int(st.item()) == o_st
     return sgl
+
+
+def check_rings(orc, c, layer, opcode, depth, first_slot, n_slots, cu_budget=0, n_desc=None, first_file_id=1000,
+                stride_cut=0, seed=3):
+    """init_queue -> fill -> issue_io -> wait_cqe on device and in the oracle; same inputs, compare outputs."""
+    assert c.bb % c.align == 0
+    o_ext, o_tot = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    ext, tot = gpu_layout(c)
+    file_stride = max(16, int(2 * c.L * (int(o_ext["obj_bytes"].max()) if c.n_req else 0)) - stride_cut)
+    n_files = max(1, c.n_req)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    store = torch.randint(0, 256, (n_files * file_stride,), dtype=torch.uint8, device=DEV, generator=g)
+    o_store = store.cpu().numpy().copy()
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    # mapping tables: device addresses on the device, host addresses for the oracle (it dereferences them)
+    nd = 2 * c.N
+    sgl = torch.zeros(nd * 16, dtype=torch.uint8, device=DEV)
+    B.tutti_sgl_table_build(c.gpu_pool(k2, v2), k2.data_ptr(), v2.data_ptr(), 5, sgl, nd)
+    o_sgl, _ = orc.sgl_table_build(c.orc_pool(orc, ok, ov), ok.ctypes.data, ov.ctypes.data, 5)
+    table_addr = sgl.data_ptr()                       # the same arithmetic base on both sides
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=DEV)
+    ring = B.make_ring(sq, cq, depth)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    st = new_status()
+    B.tutti_ring_init(ring)
+    orc.ring_init(o_sq, o_cq)
+    torch.cuda.synchronize()
+    assert sq.cpu().numpy().tobytes() == o_sq.tobytes() and cq.cpu().numpy().tobytes() == o_cq.tobytes()
+    B.tutti_iocb_fill_direct(ring, first_slot, n_slots, c.gpu_pool(k2, v2), c.gpu_cfg(), ext, c.n_req, c.d_table,
+                             c.table.size, c.d_file_id, layer, opcode, table_addr, 5, st)
+    o_st = orc.iocb_fill_direct(o_sq, first_slot, n_slots, c.orc_pool(orc, ok, ov), c.orc_cfg(orc), o_ext, c.table,
+                                c.file_id, layer, opcode, table_addr, 5)
+    torch.cuda.synchronize()
+    assert sq.cpu().numpy().tobytes() == o_sq.tobytes(), f"{c.name}: filled IOCBs differ"
+    assert int(st.item()) == o_st
+    fs = B.make_filestore(store, file_stride, first_file_id, n_files)
+    ndv = nd if n_desc is None else n_desc
+    st2 = new_status()
+    B.tutti_issue_io(ring, first_slot, n_slots, sgl, ndv, table_addr, fs, c.bb, cu_budget, st2)
+    o_st2 = orc.issue_io(o_sq, o_cq, first_slot, n_slots, o_sgl[:ndv], table_addr, o_store, file_stride, first_file_id,
+                         n_files)
+    flags = torch.full((depth,), 9, dtype=torch.int32, device=DEV)
+    for slot in range(depth):
+        B.tutti_wait_cqe(ring, slot, flags[slot:])
+    torch.cuda.synchronize()
+    assert int(st2.item()) == o_st2, f"{c.name}: issue_io status {int(st2.item())} vs oracle {o_st2}"
+    gk, gv = k2.cpu().numpy(), v2.cpu().numpy()
+    assert np.array_equal(gk, ok), f"{c.name}: K plane differs at byte {first_diff(gk, ok)}"
+    assert np.array_equal(gv, ov), f"{c.name}: V plane differs at byte {first_diff(gv, ov)}"
+    gs = store.cpu().numpy()
+    assert np.array_equal(gs, o_store), f"{c.name}: file store differs at byte {first_diff(gs, o_store)}"
+    assert sq.cpu().numpy().tobytes() == o_sq.tobytes(), f"{c.name}: IOCBs differ after issue_io"
+    g_cq = cq.cpu().numpy().view(np.uint32)
+    assert g_cq.tobytes() == o_cq.tobytes(), f"{c.name}: completion queue differs"
+    n_done = int(o_cq[0])
+    done_slots = {int(x) for x in o_cq[16:16 + min(n_done, depth)]}
+    assert flags.cpu().tolist() == [1 if s in done_slots else 0 for s in range(depth)]
+    return n_done

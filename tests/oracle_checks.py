@@ -84,8 +84,16 @@ def check_closed_forms_8b(orc):
 def check_abi(orc):
     g = golden()
     d = orc.abi_describe()
-    assert len(d) == 37
+    assert len(d) == 52
     ext, sqe, pool, cfg, sgl = d[0:7], d[7:19], d[19:29], d[29:33], d[33:37]
+    hdr, iocb, cqh, fst = d[37:44], d[44:46], d[46], d[47:52]
+    assert hdr == [64, 0, 4, 8, 12, 16, 20] and iocb == [64 + g["iocb_slots"] * 64, 64] and cqh == 64
+    assert fst == [24, 0, 8, 16, 20]
+    Hd, Io = orc.IOCB_HDR_DTYPE, orc.IOCB_DTYPE
+    assert Hd.itemsize == 64 and [Hd.fields[n][1] for n in Hd.names[:6]] == hdr[1:]
+    assert Io.itemsize == iocb[0] and Io.fields["ioctx"][1] == 64 and orc.CQ_HDR_WORDS * 4 == cqh
+    import ctypes as _c
+    assert _c.sizeof(orc.OrcFileStore) == 24
     assert sgl == [g["sgl_descriptor_bytes"], 0, 8, 12]      # address 8 + length 4 + identifier 4: sec. 3.1
     G = orc.SGL_DTYPE
     assert [G.itemsize] + [G.fields[n][1] for n in G.names] == sgl
@@ -581,6 +589,131 @@ def check_direct_entries(orc, seed=23):
                              orc.OP_READ, 0, 0)
 
 
+# ---------------------------------------------------------------------------- rings
+
+def check_ring_fill(orc, seed=29):
+    """init_queue / get_iocb + fill: unique indices, 2048 contexts per IOCB, wrap-around, capacities."""
+    g = golden()
+    rng = np.random.default_rng(seed)
+    depth = 8
+    sq, cq = orc.ring_alloc(depth)
+    sq["hdr"]["state"] = 7
+    cq[:] = 5
+    orc.ring_init(sq, cq)
+    assert np.array_equal(sq["hdr"]["iocb_idx"], np.arange(depth)) and np.all(sq["hdr"]["state"] == orc.IOCB_FREE)
+    assert np.all(sq["hdr"]["num_ioctx"] == 0) and int(cq[0]) == 0 and int(cq[1]) == depth
+    T, h, d, e, N, L = 16, 2, 64, 2, 4000, 5
+    p = _pool(orc, T, h, d, e, N)
+    cfg = orc.make_cfg(4096, 4096, L)
+    nb = np.array([1500, 0, 1000], np.uint32)           # 5000 contexts: 2048 + 2048 + 904
+    table = rng.permutation(N)[: int(nb.sum())].astype(np.uint32)
+    fid = np.array([40, 41, 42], np.uint32)
+    ext, _ = orc.obj_layout(p, cfg, nb)
+    want, _ = orc.sqe_build_direct(p, cfg, ext, table, fid, 3, orc.OP_READ, 1 << 36, 9)
+    st = orc.iocb_fill_direct(sq, 6, 4, p, cfg, ext, table, fid, 3, orc.OP_READ, 1 << 36, 9)   # slots 6, 7, 0, 1
+    assert st == 0
+    slots = [6, 7, 0, 1]
+    counts = [g["iocb_slots"], g["iocb_slots"], 5000 - 2 * g["iocb_slots"], 0]
+    got = []
+    for slot, cnt in zip(slots, counts):
+        hd = sq["hdr"][slot]
+        assert (int(hd["num_ioctx"]), int(hd["state"]), int(hd["layer"]), int(hd["opcode"]), int(hd["iocb_idx"])) == \
+            (cnt, orc.IOCB_FILLED, 3, orc.OP_READ, slot)
+        got.append(sq["ioctx"][slot][:cnt])
+    assert np.concatenate(got).tobytes() == want.tobytes()   # the layer's contexts, dealt 2048 per IOCB
+    for slot in (2, 3, 4, 5):
+        assert int(sq["hdr"]["state"][slot]) == orc.IOCB_FREE
+    # every context knows its own place: i = 2048 * iocb_idx + ioctx_slot (relative to the first IOCB)
+    allc = np.concatenate(got)
+    assert np.array_equal(allc["iocb_idx"].astype(np.int64) * 2048 + allc["ioctx_slot"], np.arange(5000))
+    # too few IOCBs: exactly n_slots * 2048 contexts, reported
+    orc.ring_init(sq, cq)
+    st = orc.iocb_fill_direct(sq, 0, 2, p, cfg, ext, table, fid, 3, orc.OP_WRITE, 1 << 36, 9)
+    assert st == orc.ST_SQE_CAP and int(sq["hdr"]["num_ioctx"][1]) == 2048 and int(sq["hdr"]["state"][2]) == orc.IOCB_FREE
+    assert np.concatenate([sq["ioctx"][0], sq["ioctx"][1]])["file_off"].tobytes() == want["file_off"][:4096].tobytes()
+    import pytest
+    with pytest.raises(orc.OracleError):
+        orc.iocb_fill_direct(sq, 0, depth + 1, p, cfg, ext, table, fid, 3, orc.OP_READ, 1 << 36, 9)
+    with pytest.raises(orc.OracleError):
+        orc.iocb_fill_direct(sq, depth, 1, p, cfg, ext, table, fid, 3, orc.OP_READ, 1 << 36, 9)
+
+
+def check_issue_io(orc, seed=37):
+    """issue_io: READ lands each file chunk in the block its descriptor names, WRITE the reverse; the CQ lists
+    the completed IOCBs.  Expected bytes come from numpy fancy indexing on independently built files."""
+    rng = np.random.default_rng(seed)
+    T, h, d, e, N, L, A = 16, 2, 64, 2, 3000, 3, 4096
+    bb = T * h * d * e
+    for pad in (0, 512):
+        stride = bb + pad
+        k, v = _planes(rng, N, stride)
+        k0, v0 = k.copy(), v.copy()
+        p = _pool(orc, T, h, d, e, N, k, v, stride=stride)
+        cfg = orc.make_cfg(A, bb, L)
+        nb = np.array([1100, 3, 0, 200], np.uint32)       # 2606 contexts: two IOCBs
+        table = rng.permutation(N)[: int(nb.sum())].astype(np.uint32)
+        fid = np.array([70, 71, 72, 73], np.uint32)
+        ext, _ = orc.obj_layout(p, cfg, nb)
+        file_stride = int(2 * L * ext["obj_bytes"].max())
+        store = rng.integers(0, 256, size=4 * file_stride, dtype=np.uint8)
+        store0 = store.copy()
+        sgl, _ = orc.sgl_table_build(p, k.ctypes.data, v.ctypes.data, 4)
+        base = 0x5000_0000_0000
+        depth = 4
+        sq, cq = orc.ring_alloc(depth)
+        orc.ring_init(sq, cq)
+        layer = 1
+        assert orc.iocb_fill_direct(sq, 3, 2, p, cfg, ext, table, fid, layer, orc.OP_READ, base, 4) == 0
+        assert orc.issue_io(sq, cq, 3, 2, sgl, base, store, file_stride, 70, 4) == 0
+        assert int(cq[0]) == 2 and list(cq[16:18]) == [3, 0] and np.all(sq["hdr"]["state"][[3, 0]] == orc.IOCB_DONE)
+        assert np.array_equal(sq["hdr"]["done"][[3, 0]], sq["hdr"]["num_ioctx"][[3, 0]]) and int(sq["hdr"]["done"][1]) == 0
+        k2, v2 = k.reshape(N, stride), v.reshape(N, stride)
+        pos = 0
+        named = np.zeros(N, bool)
+        for r in range(nb.size):
+            ids = table[pos:pos + nb[r]]
+            named[ids] = True
+            obj = int(ext["obj_bytes"][r])
+            for kind, plane in enumerate((k2, v2)):
+                lo = r * file_stride + (2 * layer + kind) * obj
+                want = store0[lo:lo + int(nb[r]) * bb].reshape(-1, bb)
+                assert np.array_equal(plane[ids, :bb], want), (pad, r, kind)        # library gather
+            pos += int(nb[r])
+        assert np.array_equal(k2[~named], k0.reshape(N, stride)[~named]) and np.array_equal(store, store0)
+        assert np.array_equal(k2[:, bb:], k0.reshape(N, stride)[:, bb:])            # stride gaps untouched
+        # WRITE: a fresh layer region of every file receives the blocks
+        k[:] = k0
+        v[:] = v0
+        orc.ring_init(sq, cq)
+        assert orc.iocb_fill_direct(sq, 0, 2, p, cfg, ext, table, fid, 2, orc.OP_WRITE, base, 4) == 0
+        assert orc.issue_io(sq, cq, 0, 2, sgl, base, store, file_stride, 70, 4) == 0
+        pos = 0
+        touched = np.zeros(store.size, bool)
+        for r in range(nb.size):
+            ids = table[pos:pos + nb[r]]
+            obj = int(ext["obj_bytes"][r])
+            for kind, plane in enumerate((k2, v2)):
+                lo = r * file_stride + (4 + kind) * obj
+                assert np.array_equal(store[lo:lo + int(nb[r]) * bb], plane[ids, :bb].reshape(-1))
+                touched[lo:lo + int(nb[r]) * bb] = True
+            pos += int(nb[r])
+        assert np.array_equal(store[~touched], store0[~touched])
+    # contexts that point outside the table, the store or the file are skipped and reported
+    orc.ring_init(sq, cq)
+    orc.iocb_fill_direct(sq, 0, 2, p, cfg, ext, table, fid, 0, orc.OP_READ, base, 4)
+    kb = k.copy()
+    assert orc.issue_io(sq, cq, 0, 2, sgl[:N], base, store, file_stride, 70, 4) == orc.ST_BAD_BLOCK   # V descriptors cut off
+    assert orc.issue_io(sq, cq, 0, 2, sgl, base, store, file_stride, 71, 4) == 0       # already DONE: nothing re-runs
+    orc.ring_init(sq, cq)
+    orc.iocb_fill_direct(sq, 0, 2, p, cfg, ext, table, fid, 0, orc.OP_READ, base, 4)
+    k[:] = kb
+    assert orc.issue_io(sq, cq, 0, 2, sgl, base, store, file_stride, 71, 4) == orc.ST_BAD_BLOCK       # file 70 unknown
+    orc.ring_init(sq, cq)
+    orc.iocb_fill_direct(sq, 0, 2, p, cfg, ext, table, fid, L - 1, orc.OP_READ, base, 4)   # last layer: ends at the file's end
+    assert orc.issue_io(sq, cq, 0, 2, sgl, base, store, file_stride - 16, 70, 4) == orc.ST_BAD_BLOCK  # file too short
+    assert orc.issue_io(sq, cq, 2, 2, sgl, base, store, file_stride, 70, 4) == 0 and int(cq[0]) == 2  # FREE slots: no-op
+
+
 ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
-              check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries]
+              check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io]

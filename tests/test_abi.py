@@ -19,7 +19,8 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert getattr(L, name) is not None
     for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
-                 "tutti_sgl_table_build", "tutti_sqe_build_direct"):
+                 "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
+                 "tutti_issue_io", "tutti_wait_cqe"):
         assert name in declared and callable(getattr(B, name))
     assert B.tutti_version() >= 0x100
 
@@ -36,6 +37,12 @@ def test_record_layouts_agree_with_oracle(orc):
     assert [getattr(B.tutti_objcfg, f).offset for f, _ in B.tutti_objcfg._fields_] == lib_abi[30:33]
     G = B.SGL_DTYPE
     assert [G.itemsize] + [G.fields[n][1] for n in G.names] == lib_abi[33:37]
+    Hd, Io = B.IOCB_HDR_DTYPE, B.IOCB_DTYPE
+    assert [Hd.itemsize] + [Hd.fields[n][1] for n in Hd.names] == lib_abi[37:44]
+    assert [Io.itemsize, Io.fields["ioctx"][1]] == lib_abi[44:46] and B.CQ_HDR_BYTES == lib_abi[46]
+    assert [ctypes.sizeof(B.tutti_filestore)] + [getattr(B.tutti_filestore, f).offset
+                                                 for f, _ in B.tutti_filestore._fields_] == lib_abi[47:52]
+    assert ctypes.sizeof(B.tutti_ring) == 24 and B.ring_bytes(3) == (3 * 131136, 64 + 12)
     for a, b in [(B.OP_READ, orc.OP_READ), (B.OP_WRITE, orc.OP_WRITE), (B.LAYOUT_HND, orc.LAYOUT_HND),
                  (B.IOCB_SLOTS, orc.IOCB_SLOTS), (B.ST_BAD_BLOCK, orc.ST_BAD_BLOCK),
                  (B.ST_STAGE_CAP, orc.ST_STAGE_CAP), (B.ST_SQE_CAP, orc.ST_SQE_CAP)]:
@@ -108,6 +115,19 @@ def test_null_and_misaligned_pointers_are_einval():
     _expect(B.EINVAL, B.tutti_sqe_build_direct, odd, cfg, FAKE, 1, FAKE, 1, FAKE, 0, B.OP_READ, 0, 0, FAKE, 4)
     _expect(B.EINVAL, B.tutti_sgl_table_build, p, 0, 0, 0, 0, 4)
     _expect(B.EINVAL, B.tutti_sgl_table_build, B.make_pool(FAKE, FAKE, **dict(GOOD, num_blocks=0)), 0, 0, 0, FAKE, 4)
+    ring = B.make_ring(FAKE, FAKE, 4)
+    fs = B.make_filestore(FAKE, 4096, 0, 1)
+    _expect(B.EINVAL, B.tutti_ring_init, B.make_ring(0, FAKE, 4))
+    _expect(B.EINVAL, B.tutti_ring_init, B.make_ring(FAKE, FAKE, 0))
+    _expect(B.EINVAL, B.tutti_iocb_fill_direct, ring, 4, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, B.OP_READ, 0, 0)  # slot
+    _expect(B.EINVAL, B.tutti_iocb_fill_direct, ring, 0, 5, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, B.OP_READ, 0, 0)  # n_slots
+    _expect(B.EINVAL, B.tutti_iocb_fill_direct, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 9, 0, 0)          # opcode
+    _expect(B.EINVAL, B.tutti_issue_io, ring, 0, 1, FAKE, 4, 0, B.make_filestore(0, 4096, 0, 1), 4096)
+    _expect(B.EINVAL, B.tutti_issue_io, ring, 0, 1, FAKE, 4, 0, B.make_filestore(FAKE, 4100, 0, 1), 4096)
+    _expect(B.EINVAL, B.tutti_issue_io, ring, 0, 1, FAKE, 4, 0, fs, 0)
+    _expect(B.EINVAL, B.tutti_issue_io, ring, 0, 1, 0, 4, 0, fs, 4096)
+    _expect(B.EINVAL, B.tutti_wait_cqe, ring, 4, FAKE)
+    _expect(B.EINVAL, B.tutti_wait_cqe, ring, 0, 0)
     _expect(B.EINVAL, B.tutti_copy_baseline, FAKE, FAKE, 24)
     _expect(B.EINVAL, B.tutti_copy_baseline, 0, FAKE, 32)
     # head-major pools need rows of whole 16-byte units

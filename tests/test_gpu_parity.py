@@ -250,6 +250,48 @@ def test_random_shapes(orc, H, seed):
         H.check_direct_mode(orc, c, layer=c.L - 1)
 
 
+# ------------------------------------------------------------------ rings: fill IOCBs, execute them, completions
+
+def test_rings_small(orc, H):
+    say("rings: small")
+    rng = np.random.default_rng(41)
+    # 5000 contexts over three IOCBs, wrapping around the end of a ring of 8
+    nb = [1500, 0, 1000]
+    N = 2600
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=4096, L=3,
+                    name="rings5000")
+    for op in (B.OP_READ, B.OP_WRITE):
+        assert H.check_rings(orc, c, layer=1, opcode=op, depth=8, first_slot=6, n_slots=4) == 4
+    H.check_rings(orc, c, layer=2, opcode=B.OP_READ, depth=8, first_slot=0, n_slots=2)          # too few IOCBs
+    H.check_rings(orc, c, layer=0, opcode=B.OP_READ, depth=4, first_slot=3, n_slots=3, cu_budget=2)
+    H.check_rings(orc, c, layer=0, opcode=B.OP_WRITE, depth=4, first_slot=1, n_slots=3, cu_budget=1)
+    # descriptors cut off (V plane unknown), unknown file ids, files too short: skipped and reported
+    H.check_rings(orc, c, layer=0, opcode=B.OP_READ, depth=4, first_slot=0, n_slots=3, n_desc=N)
+    H.check_rings(orc, c, layer=0, opcode=B.OP_READ, depth=4, first_slot=0, n_slots=3, first_file_id=1001)
+    H.check_rings(orc, c, layer=2, opcode=B.OP_WRITE, depth=4, first_slot=0, n_slots=3, stride_cut=4096)
+    # out-of-range block ids give no-op contexts; an empty layer completes its IOCBs at once
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[4, 2], table=[3, 999, 5, 16, 7, 1], chunk=4096, name="rings_bad")
+    H.check_rings(orc, c, layer=0, opcode=B.OP_READ, depth=2, first_slot=1, n_slots=1)
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[0], table=[], chunk=4096, name="rings_empty")
+    assert H.check_rings(orc, c, layer=0, opcode=B.OP_READ, depth=2, first_slot=0, n_slots=2) == 2
+    # strided pool and 128 KiB blocks (several slices per context)
+    c = H.LayerCase(T=64, h=8, d=128, e=2, N=64, n_blocks=[9, 20], table=rng.permutation(64)[:29], chunk=131072, L=2,
+                    pad=4096, name="rings_128K")
+    H.check_rings(orc, c, layer=1, opcode=B.OP_READ, depth=3, first_slot=2, n_slots=1)
+    H.check_rings(orc, c, layer=1, opcode=B.OP_WRITE, depth=3, first_slot=2, n_slots=1, cu_budget=4)
+
+
+def test_rings_cfg2_layer(orc, H):
+    """The paper's data path on config 2's layer: 4096 contexts = two full IOCBs, restore straight from the
+    file store into the scattered blocks (no staging copy)."""
+    w = W.llama8b_32k(num_blocks=8192)
+    say("rings: config 2 layer")
+    c = H.LayerCase.from_workload(w)
+    c.chunk = c.bb
+    for op in (B.OP_READ, B.OP_WRITE):
+        assert H.check_rings(orc, c, layer=31, opcode=op, depth=4, first_slot=3, n_slots=2) == 2
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_no_requests_and_empty_requests(orc, H):

@@ -31,7 +31,8 @@ MUTANTS = {
                          "(uint8_t *)(uintptr_t)stage, stage_cap, 1, 0,\n             total_blocks"),
     "file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)", 0),
     "direct_file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)", 1),
-    "direct_file_id_of_first": ("s.file_id = file_id[r];", "s.file_id = file_id[0];", 1),
+    "direct_file_id_of_first": ("make_direct_entry(pool, x, r, kind, j, id, file_id[r],",
+                                "make_direct_entry(pool, x, r, kind, j, id, file_id[0],"),
     "direct_iocb_div_mod_swapped": ("s.iocb_idx = (uint32_t)(i / ORC_IOCB_SLOTS);",
                                     "s.iocb_idx = (uint32_t)(i % ORC_IOCB_SLOTS);", 1),
     "direct_user_data_swapped": ("s.user_data = ((uint64_t)r << 32) | (uint32_t)i;",
@@ -62,11 +63,28 @@ MUTANTS = {
                                 "s.addr = sgl_table_addr + 16ull * ((uint64_t)kind * pool->num_blocks + j);"),
     "direct_file_off_by_id": ("s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)j * bb;",
                               "s.file_off = (2ull * layer + kind) * x->obj_bytes + (uint64_t)id * bb;"),
+    "fill_table_offset_dropped": ("block_table[(uint64_t)x->table_off + j], file_id[r], layer, opcode,",
+                                  "block_table[j], file_id[r], layer, opcode,"),
     "direct_index_interleaved": ("uint64_t i = 2ull * x->table_off + (uint64_t)kind * x->n_blocks + j;",
-                                 "uint64_t i = 2ull * x->table_off + 2ull * j + kind;"),
+                                 "uint64_t i = 2ull * x->table_off + 2ull * j + kind;", 0),
+    "fill_index_interleaved": ("uint64_t i = 2ull * x->table_off + (uint64_t)kind * x->n_blocks + j;",
+                               "uint64_t i = 2ull * x->table_off + 2ull * j + kind;", 1),
     "direct_table_offset_dropped": ("uint32_t id = block_table[(uint64_t)x->table_off + j];",
                                     "uint32_t id = block_table[j];"),
-    "direct_bad_id_bound": ("if (id < pool->num_blocks) {\n          s.addr", "if (id <= pool->num_blocks) {\n          s.addr"),
+    "direct_bad_id_bound": ("if (id < pool->num_blocks) {\n    s.addr", "if (id <= pool->num_blocks) {\n    s.addr"),
+    "ring_index_not_unique": ("sq[b].hdr.iocb_idx = b;", "sq[b].hdr.iocb_idx = 0;"),
+    "ring_no_wraparound": ("orc_iocb *io = &sq[(first_slot + (uint32_t)(i / ORC_IOCB_SLOTS)) % depth];",
+                           "orc_iocb *io = &sq[(first_slot + (uint32_t)(i / ORC_IOCB_SLOTS)) % (depth + 1)];"),
+    "ring_num_ioctx_full": ("io->hdr.num_ioctx = (uint32_t)cnt;", "io->hdr.num_ioctx = ORC_IOCB_SLOTS;"),
+    "ring_slot_position": ("orc_sqe *s = &io->ioctx[i % ORC_IOCB_SLOTS];", "orc_sqe *s = &io->ioctx[i % 2047];"),
+    "io_direction_swapped": ("if (s->opcode == ORC_OP_READ)\n        memcpy(blk, fil, s->len);",
+                             "if (s->opcode == ORC_OP_WRITE)\n        memcpy(blk, fil, s->len);"),
+    "io_file_stride_ignored": ("(uint64_t)(s->file_id - store->first_file_id) * store->file_stride + s->file_off;",
+                               "s->file_off;"),
+    "io_descriptor_index": ("uint64_t di = (s->addr - sgl_table_addr) / 16;", "uint64_t di = (s->addr - sgl_table_addr) / 32;"),
+    "io_cq_index": ("entry[c->tail % depth] = io->hdr.iocb_idx;", "entry[c->tail % depth] = b;"),
+    "io_not_marked_done": ("io->hdr.state = ORC_IOCB_DONE;", "io->hdr.state = ORC_IOCB_FILLED;"),
+    "io_file_bound": ("s->file_off + s->len > store->file_stride) {", "s->file_off > store->file_stride) {"),
     "restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
                              "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);"),
 }
