@@ -209,6 +209,11 @@ def main():
         out["copy_ceiling"] = copy_ceiling(torch, B, stages, payload_layer, dev)
         out["copy_ceiling"]["restore_vs_copy"] = round(out["restore"]["traffic_GBps"] /
                                                        out["copy_ceiling"]["traffic_GBps"], 4)
+        out["scatter_floor"] = scatter_floor(torch, B, w, stages, payload_layer, dev)
+        out["scatter_floor"]["restore_vs_floor"] = round(out["scatter_floor"]["scattered_writes"]["us"] /
+                                                         out["restore"]["us_per_layer"], 4)
+        out["scatter_floor"]["pack_vs_floor"] = round(out["scatter_floor"]["scattered_reads"]["us"] /
+                                                      out["save"]["us_per_layer"], 4)
         out["sqe"] = sqe_rate(torch, B, W, dev)
         out["sqe"]["direct_to_block"] = direct_rate(torch, B, W, dev)
         log(f"[bench] copy ceiling {out['copy_ceiling']}; entries {out['sqe']}")
@@ -394,6 +399,43 @@ def pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload, n_sqe, d
         res[label] = {"us_per_layer": round(us, 1), "payload_GBps": round(payload / (us * 1e-6) / 1e9, 2)}
     assert int(status.item()) == 0
     log(f"[bench] pinned-host staging: {res}")
+    return res
+
+
+def scatter_floor(torch, B, w, stages, nbytes, dev, n_buf=6, reps=5):
+    """What the memory system gives for config 2's access pattern with nothing else in the kernel: a
+    128 MiB contiguous buffer against 4096 pieces of 32 KiB placed by the same block table inside a 4 GiB
+    span (K plane then V plane), written (the unpack's pattern) or read (the pack's)."""
+    s = w.shape
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    span = 2 * s.num_blocks * bb
+    perm = np.concatenate([w.block_table, w.block_table + s.num_blocks]).astype(np.uint32)
+    d_perm = torch.from_numpy(perm.view(np.int32)).to(dev)
+    bufs = [torch.empty(span, dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    res = {"pieces": int(perm.size), "piece_bytes": bb, "span_bytes": span}
+    for label, wr in (("scattered_writes", 1), ("scattered_reads", 0)):
+        def run():
+            for i in range(len(stages)):
+                B.tutti_scatter_baseline(bufs[i % n_buf], span, stages[i], nbytes, d_perm, bb, wr)
+        if not wr:   # do not clobber the staging buffers the parity check reads later: reads go to a scratch copy
+            scratch = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(4)]
+
+            def run():  # noqa: F811
+                for i in range(len(stages)):
+                    B.tutti_scatter_baseline(bufs[i % n_buf], span, scratch[i % 4], nbytes, d_perm, bb, wr)
+        run()
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            run()
+            b.record()
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b) * 1e3 / len(stages))
+        us = median(times)
+        res[label] = {"us": round(us, 2), "traffic_GBps": round(2 * nbytes / (us * 1e-6) / 1e9, 1),
+                      "pct_hbm_peak": round(100 * 2 * nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
     return res
 
 

@@ -266,6 +266,17 @@ int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void
  * achievable ceiling the pack/unpack rates are compared with. */
 int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream);
 
+/* ---- measurement aid: the same copy with one side scattered at `gran`-byte granularity and nothing else
+ * (no extents, no requests, no K/V planes): piece i of the contiguous side, i < bytes/gran, pairs with the
+ * piece at d_scattered + d_perm[i]*gran.  scatter_writes != 0: contiguous -> scattered (the shape of an
+ * unpack); 0: scattered -> contiguous (a pack).  What the memory system itself gives for that access
+ * pattern: the floor pack / unpack are compared with.  gran a multiple of 4096; bytes a multiple of gran;
+ * every d_perm[i]*gran + gran must lie inside the scattered buffer (span_bytes is checked on the device,
+ * offending pieces are skipped). */
+int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_contig, uint64_t bytes,
+                           const uint32_t *d_perm, uint32_t gran, uint32_t scatter_writes, uint32_t cu_budget,
+                           void *stream);
+
 /* ---- housekeeping */
 const char *tutti_strerror(int code);
 int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */

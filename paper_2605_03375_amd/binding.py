@@ -37,7 +37,7 @@ SGL_DTYPE = np.dtype({"names": ["addr", "len", "id"], "formats": ["<u8", "<u4", 
 EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
            "tutti_issue_io", "tutti_wait_cqe",
-           "tutti_copy_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
+           "tutti_copy_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"]
 
 
@@ -115,6 +115,8 @@ def lib():
         L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
                                           vp, vp]
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
+        L.tutti_scatter_baseline.argtypes = [vp, u64, vp, u64, vp, u32, u32, u32, vp]
+        L.tutti_scatter_baseline.restype = C.c_int
         pr, pf = C.POINTER(tutti_ring), C.POINTER(tutti_filestore)
         L.tutti_ring_init.argtypes = [pr, vp]
         L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
@@ -255,6 +257,13 @@ def tutti_wait_cqe(ring, slot, d_flag, stream=None):
 def tutti_copy_baseline(d_dst, d_src, nbytes, cu_budget=0, stream=None):
     return _check("tutti_copy_baseline", lib().tutti_copy_baseline(_p(d_dst), _p(d_src), nbytes, cu_budget,
                                                                    _stream(stream)))
+
+
+def tutti_scatter_baseline(d_scattered, span_bytes, d_contig, nbytes, d_perm, gran, scatter_writes, cu_budget=0,
+                           stream=None):
+    return _check("tutti_scatter_baseline",
+                  lib().tutti_scatter_baseline(_p(d_scattered), span_bytes, _p(d_contig), nbytes, _p(d_perm), gran,
+                                               1 if scatter_writes else 0, cu_budget, _stream(stream)))
 
 
 def tutti_strerror(code):

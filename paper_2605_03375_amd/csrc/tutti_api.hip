@@ -736,6 +736,28 @@ int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_contig, uint64_t bytes,
+                           const uint32_t *d_perm, uint32_t gran, uint32_t scatter_writes, uint32_t cu_budget,
+                           void *stream) {
+  if (!d_scattered || !d_contig || !d_perm || !aligned16(d_scattered) || !aligned16(d_contig)) return TUTTI_EINVAL;
+  if (gran == 0 || gran % 4096 != 0 || bytes % gran != 0) return TUTTI_EINVAL;
+  if (bytes == 0) return TUTTI_OK;
+  Launch L;
+  int rc = plan_launch(cu_budget, bytes / 4096, &L);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char *sc = static_cast<unsigned char *>(d_scattered);
+  unsigned char *ct = static_cast<unsigned char *>(d_contig);
+  if (L.wg_threads == kWgThreads)
+    hipLaunchKernelGGL((k_scatter<4, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes,
+                       d_perm, gran, scatter_writes);
+  else
+    hipLaunchKernelGGL((k_scatter<4, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, sc, span_bytes, ct,
+                       bytes, d_perm, gran, scatter_writes);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
 const char *tutti_strerror(int code) {
   switch (code) {
     case TUTTI_OK:

@@ -888,4 +888,32 @@ __global__ __launch_bounds__(WG) void k_copy(unsigned char *__restrict__ dst,
   }
 }
 
+// The copy with one side permuted at `gran` bytes: the memory system's own cost of the scatter.
+template <int U, int WG>
+__global__ __launch_bounds__(WG) void k_scatter(unsigned char *__restrict__ scattered, uint64_t span_bytes,
+                                                 unsigned char *__restrict__ contig, uint64_t bytes,
+                                                 const uint32_t *__restrict__ perm, uint32_t gran, uint32_t to_scattered) {
+  constexpr uint32_t kSlice = kWave * 16u * U;  // gran is a multiple of 4096 and of kSlice (host-checked)
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave_in_wg = rfl(threadIdx.x / kWave);
+  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * (blockDim.x / kWave);
+  const uint32_t per = gran / kSlice;
+  const uint64_t n_items = bytes / kSlice;
+  for (uint64_t it = static_cast<uint64_t>(blockIdx.x) * (blockDim.x / kWave) + wave_in_wg; it < n_items; it += n_waves) {
+    const uint64_t piece = it / per;
+    const uint32_t s = static_cast<uint32_t>(it - piece * per);
+    const uint64_t so = static_cast<uint64_t>(rfl(perm[piece])) * gran;
+    if (so + gran > span_bytes) continue;
+    unsigned char *sp = scattered + so + s * kSlice + lane * 16u;
+    unsigned char *cp = contig + it * kSlice + lane * 16u;
+    const unsigned char *src = to_scattered ? cp : sp;
+    unsigned char *dst = to_scattered ? sp : cp;
+    u32x4 buf[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) buf[u] = ld16<3>(src + u * (kWave * 16u));
+#pragma unroll
+    for (int u = 0; u < U; ++u) st16<3>(dst + u * (kWave * 16u), buf[u]);
+  }
+}
+
 }  // namespace tutti

@@ -388,6 +388,35 @@ def test_copy_baseline(H):
         assert torch.equal(dst[:n], src) and not dst[n:].any()
 
 
+def test_scatter_baseline(H):
+    say("scatter baseline")
+    rng = np.random.default_rng(2)
+    gran, n_slots, n = 8192, 64, 24
+    perm = rng.permutation(n_slots)[:n].astype(np.uint32)
+    perm[5] = 200                                     # out of the span: skipped
+    d_perm = H.to_dev(perm)
+    g = torch.Generator(device=H.DEV)
+    g.manual_seed(3)
+    contig = torch.randint(0, 256, (n * gran,), dtype=torch.uint8, device=H.DEV, generator=g)
+    scat = torch.zeros(n_slots * gran, dtype=torch.uint8, device=H.DEV)
+    for budget in (0, 2):
+        scat.zero_()
+        B.tutti_scatter_baseline(scat, scat.numel(), contig, contig.numel(), d_perm, gran, 1, budget)
+        torch.cuda.synchronize()
+        want = np.zeros((n_slots, gran), np.uint8)
+        src = contig.cpu().numpy().reshape(n, gran)
+        for i, p in enumerate(perm):
+            if p < n_slots:
+                want[p] = src[i]
+        assert np.array_equal(scat.cpu().numpy().reshape(n_slots, gran), want)
+        back = torch.full_like(contig, 7)
+        B.tutti_scatter_baseline(scat, scat.numel(), back, back.numel(), d_perm, gran, 0, budget)
+        torch.cuda.synchronize()
+        exp = src.copy()
+        exp[5] = 7
+        assert np.array_equal(back.cpu().numpy().reshape(n, gran), exp)
+
+
 # ------------------------------------------------------------------ configs 2-5 at their real shapes
 
 def test_cfg2_llama8b_32k_full_layer(orc, H):
