@@ -151,6 +151,15 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
                         uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe,
                         uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status, void *stream);
 
+/* ---- one layer's save in ONE launch (store_layer of sec. 3.4): extents from d_n_blocks, WRITE entries for
+ * `layer`, then the pack of every hit block with zero padding, as tutti_obj_layout + tutti_sqe_build(WRITE) +
+ * tutti_obj_pack would.  Arguments as in tutti_layer_restore; d_stage is written. */
+int tutti_layer_save(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                     const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                     void *d_stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, tutti_extent *d_extents,
+                     uint64_t *d_totals, tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status,
+                     void *stream);
+
 /* ---- direct-to-block mode: the paper's own data path, with no staging copy (sec. 3.1 "P2P Memory
  * Mapping Table", sec. 3.2 "an IOCTX records the SGL address, GPU file offset, and length").
  *

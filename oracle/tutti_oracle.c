@@ -544,6 +544,24 @@ int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_
   return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);
 }
 
+/* One layer's save as the library's single call does it: extents, WRITE entries, pack (store_layer of sec. 3.4). */
+int orc_layer_save(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                   const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, void *stage,
+                   uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents, uint64_t *totals,
+                   orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (layer >= cfg->num_layers || stage_addr % cfg->align != 0) return ORC_EINVAL;
+  if (n_req > 0 && (!file_id || !stage)) return ORC_EINVAL;
+  if (!pool->k_base || !pool->v_base) return ORC_EINVAL;
+  if (sqe_cap > 0 && !sqe) return ORC_EINVAL;
+  rc = orc_obj_layout(pool, cfg, n_blocks, n_req, extents, totals);
+  if (rc) return rc;
+  rc = orc_sqe_build(pool, cfg, extents, n_req, file_id, layer, ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);
+  if (rc) return rc;
+  return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);
+}
+
 /* ------------------------------------------------------------------ threaded timing helpers */
 
 typedef struct {

@@ -135,6 +135,12 @@ int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_
                       uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents,
                       uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
 
+/* layout, then WRITE entries, then pack, for one layer (the save direction of the fused call). */
+int orc_layer_save(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                   const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, void *stage,
+                   uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents, uint64_t *totals,
+                   orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
+
 /* ---- direct-to-block mode: the paper's own data path, no staging copy (sec. 3.1, "P2P Memory
  * Mapping Table"; sec. 3.2: an I/O context records the SGL address, the GPU-file offset and the length).
  *

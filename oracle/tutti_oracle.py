@@ -262,3 +262,22 @@ def issue_io(sq, cq, first_slot, n_slots, sgl_table, sgl_table_addr, store, file
     if rc:
         raise OracleError("orc_issue_io", rc)
     return status.value
+
+
+def layer_save(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap, stage_cap=None):
+    """Returns (extents, totals, sqe, status); `stage` is written in place."""
+    n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    file_id = np.ascontiguousarray(file_id, dtype=np.uint32)
+    ext = np.zeros(n_blocks.size, EXTENT_DTYPE)
+    totals = np.zeros(2, np.uint64)
+    sqe = np.zeros(sqe_cap, SQE_DTYPE)
+    cap = stage.nbytes if stage_cap is None else stage_cap
+    status = C.c_uint32(0)
+    rc = lib().orc_layer_save(C.byref(pool), C.byref(cfg), _ptr(n_blocks), C.c_uint32(n_blocks.size),
+                              _ptr(block_table), _ptr(file_id), C.c_uint32(layer), _ptr(stage), C.c_uint64(cap),
+                              C.c_uint64(stage_addr), C.c_uint32(sgl_id), _ptr(ext), _ptr(totals), _ptr(sqe),
+                              C.c_uint32(sqe_cap), C.byref(status))
+    if rc:
+        raise OracleError("orc_layer_save", rc)
+    return ext, totals, sqe, status.value

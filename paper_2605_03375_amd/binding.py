@@ -35,6 +35,7 @@ SGL_DTYPE = np.dtype({"names": ["addr", "len", "id"], "formats": ["<u8", "<u4", 
                       "itemsize": 16})
 
 EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
+           "tutti_layer_save",
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
            "tutti_issue_io", "tutti_wait_cqe",
            "tutti_copy_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
@@ -114,6 +115,8 @@ def lib():
         L.tutti_sqe_build.argtypes = [pp, pc, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
         L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
                                           vp, vp]
+        L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
+        L.tutti_layer_save.restype = C.c_int
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
         L.tutti_scatter_baseline.argtypes = [vp, u64, vp, u64, vp, u32, u32, u32, vp]
         L.tutti_scatter_baseline.restype = C.c_int
@@ -252,6 +255,15 @@ def tutti_issue_io(ring, first_slot, n_slots, d_sgl_table, n_desc, sgl_table_add
 
 def tutti_wait_cqe(ring, slot, d_flag, stream=None):
     return _check("tutti_wait_cqe", lib().tutti_wait_cqe(C.byref(ring), slot, _p(d_flag), _stream(stream)))
+
+
+def tutti_layer_save(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage, stage_cap,
+                     stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, cu_budget=0, d_status=None, stream=None):
+    return _check("tutti_layer_save",
+                  lib().tutti_layer_save(C.byref(pool), C.byref(cfg), _p(d_n_blocks), n_req, _p(d_block_table),
+                                         table_len, _p(d_file_id), layer, _p(d_stage), stage_cap, stage_addr, sgl_id,
+                                         _p(d_extents), _p(d_totals), _p(d_sqe), sqe_cap, cu_budget, _p(d_status),
+                                         _stream(stream)))
 
 
 def tutti_copy_baseline(d_dst, d_src, nbytes, cu_budget=0, stream=None):

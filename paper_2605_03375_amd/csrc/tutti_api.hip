@@ -223,17 +223,18 @@ hipError_t launch_move_lds(const Launch &L, uint32_t lds, hipStream_t s, const M
   return hipGetLastError();
 }
 
-hipError_t launch_restore_lds(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
-                              const SqeArgs &q, const LayoutArgs &a) {
+template <int DIR>
+hipError_t launch_layer_lds(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
+                            const SqeArgs &q, const LayoutArgs &a) {
   const uint32_t copy_wgs = L.grid;
   const dim3 grid(L.wg_threads == kWgThreads ? L.grid + sqe_wgs : L.grid);
 #define TUTTI_LDS_CASE(PT)                                                                                        \
   case PT:                                                                                                        \
     if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_restore_lds<PT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,       \
+      hipLaunchKernelGGL((k_layer_lds<DIR, PT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,       \
                          sqe_wgs);                                                                                \
     else                                                                                                          \
-      hipLaunchKernelGGL((k_restore_lds<PT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q, a,     \
+      hipLaunchKernelGGL((k_layer_lds<DIR, PT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q, a,     \
                          copy_wgs, sqe_wgs);                                                                      \
     break;
   switch (L.unroll) {
@@ -282,8 +283,8 @@ hipError_t launch_move(const Launch &L, uint32_t lds, hipStream_t s, const MoveA
   return hipGetLastError();
 }
 
-template <bool HND>
-hipError_t launch_restore(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
+template <int DIR, bool HND>
+hipError_t launch_layer(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
                           const SqeArgs &q, const LayoutArgs &a) {
   const uint32_t copy_wgs = L.grid;
   // whole GPU: entry writers are extra workgroups; CU budget: the last copy workgroup writes them
@@ -291,10 +292,10 @@ hipError_t launch_restore(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipSt
 #define TUTTI_RESTORE_NT(U, NT)                                                                                   \
   case NT:                                                                                                        \
     if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_restore<HND, U, NT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,  \
+      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,  \
                          sqe_wgs);                                                                                \
     else                                                                                                          \
-      hipLaunchKernelGGL((k_restore<HND, U, NT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q,   \
+      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q,   \
                          a, copy_wgs, sqe_wgs);                                                                   \
     break;
 #define TUTTI_RESTORE_CASE(U)    \
@@ -429,11 +430,15 @@ int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
-int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
-                        const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
-                        uint32_t layer, const void *d_stage, uint64_t stage_cap, uint64_t stage_addr,
-                        uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe,
-                        uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+extern "C++" {
+namespace {
+// One layer in one launch: extents, entries (READ for a restore, WRITE for a save), then the copy.
+template <int DIR>
+int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                const void *d_stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id,
+                tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget,
+                uint32_t *d_status, void *stream) {
   uint32_t bb = 0;
   int rc = check_geometry(pool, cfg, &bb);
   if (rc) return rc;
@@ -472,7 +477,7 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   q.sqe_cap = sqe_cap;
   q.chunk_bytes = cfg->chunk_bytes;
   q.layer = layer;
-  q.opcode = TUTTI_OP_READ;
+  q.opcode = (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE;
   q.sgl_id = sgl_id;
 
   LayoutArgs a;
@@ -485,13 +490,35 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (L.hnd_lds) {
-    e = launch_restore_lds(L, sqe_wgs, align16(req_lds_bytes(n_req)) + L.tile_lds, s, m, q, a);
+    e = launch_layer_lds<DIR>(L, sqe_wgs, align16(req_lds_bytes(n_req)) + L.tile_lds, s, m, q, a);
   } else {
     const uint32_t lds = req_lds_bytes(n_req);
-    e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_restore<true>(L, sqe_wgs, lds, s, m, q, a)
-                                                 : launch_restore<false>(L, sqe_wgs, lds, s, m, q, a);
+    e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_layer<DIR, true>(L, sqe_wgs, lds, s, m, q, a)
+                                                 : launch_layer<DIR, false>(L, sqe_wgs, lds, s, m, q, a);
   }
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+}  // namespace
+}  // extern "C++"
+
+int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                        const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                        uint32_t layer, const void *d_stage, uint64_t stage_cap, uint64_t stage_addr,
+                        uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe,
+                        uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  return layer_entry<kUnpack>(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage,
+                              stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, cu_budget, d_status,
+                              stream);
+}
+
+int tutti_layer_save(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                     const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                     void *d_stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, tutti_extent *d_extents,
+                     uint64_t *d_totals, tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status,
+                     void *stream) {
+  return layer_entry<kPack>(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage,
+                            stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, cu_budget, d_status,
+                            stream);
 }
 
 int tutti_sgl_table_build(const tutti_pool *pool, uint64_t k_addr, uint64_t v_addr, uint32_t sgl_id,

@@ -8,8 +8,8 @@
 //   k_ring_init / k_iocb_fill / k_issue_io / k_cq_check   SQ/CQ rings: fill IOCBs, execute them, report
 //   k_move          pack / unpack between paged blocks and objects, extents given
 //   k_move_lds      the same for head-major pools with short rows: token-tile transposed in LDS
-//   k_restore       one layer's restore in one launch: scan + entries + unpack
-//   k_restore_lds   the same with the LDS-staged transpose
+//   k_layer         one layer's restore (or save) in one launch: scan + entries + unpack (or pack)
+//   k_layer_lds     the same with the LDS-staged transpose
 //   k_copy          plain contiguous copy with the same access shape (measurement ceiling)
 //
 // Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
@@ -824,14 +824,15 @@ __global__ __launch_bounds__(WG) void k_move_lds(const MoveArgs a, const tutti_e
   move_items_hnd_lds<DIR, PT, WG>(a, l, n_req, gridDim.x, smem + align16(req_lds_bytes(n_req)));
 }
 
-// One layer's restore: every workgroup redoes the (tiny) scan into its own LDS with its first
-// wavefront.  The first `copy_wgs` workgroups unpack; the last `sqe_wgs` workgroups of the grid
-// write the entries, and the very last one also publishes extents and totals.  A whole-GPU launch
-// adds the entry writers behind the copy workgroups so no bookkeeping sits in front of the copy;
-// a CU-budgeted launch has no workgroup to spare and its last workgroup does both jobs.
-template <bool HND, int U, int NT, int WG>
-__global__ __launch_bounds__(WG) void k_restore(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
-                                                 uint32_t copy_wgs, uint32_t sqe_wgs) {
+// One layer's restore (DIR = kUnpack) or save (DIR = kPack) in one launch: every workgroup redoes the
+// (tiny) scan into its own LDS with its first wavefront.  The first `copy_wgs` workgroups move the
+// blocks; the last `sqe_wgs` workgroups of the grid write the entries, and the very last one also
+// publishes extents and totals.  A whole-GPU launch adds the entry writers behind the copy workgroups
+// so no bookkeeping sits in front of the copy; a CU-budgeted launch has no workgroup to spare and
+// its last workgroup does both jobs.
+template <int DIR, bool HND, int U, int NT, int WG>
+__global__ __launch_bounds__(WG) void k_layer(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
+                                               uint32_t copy_wgs, uint32_t sqe_wgs) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
   if (threadIdx.x < kWave) {
@@ -842,12 +843,12 @@ __global__ __launch_bounds__(WG) void k_restore(const MoveArgs m, const SqeArgs 
   __syncthreads();
   const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
   if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
-  if (blockIdx.x < copy_wgs) move_items<kUnpack, HND, U, NT>(m, l, a.n_req, copy_wgs);
+  if (blockIdx.x < copy_wgs) move_items<DIR, HND, U, NT>(m, l, a.n_req, copy_wgs);
 }
 
-template <int PT, int WG>
-__global__ __launch_bounds__(WG) void k_restore_lds(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
-                                                     uint32_t copy_wgs, uint32_t sqe_wgs) {
+template <int DIR, int PT, int WG>
+__global__ __launch_bounds__(WG) void k_layer_lds(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
+                                                   uint32_t copy_wgs, uint32_t sqe_wgs) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
   if (threadIdx.x < kWave) {
@@ -859,7 +860,7 @@ __global__ __launch_bounds__(WG) void k_restore_lds(const MoveArgs m, const SqeA
   const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
   if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
   if (blockIdx.x < copy_wgs)
-    move_items_hnd_lds<kUnpack, PT, WG>(m, l, a.n_req, copy_wgs, smem + align16(req_lds_bytes(a.n_req)));
+    move_items_hnd_lds<DIR, PT, WG>(m, l, a.n_req, copy_wgs, smem + align16(req_lds_bytes(a.n_req)));
 }
 
 // Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.

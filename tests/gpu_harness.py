@@ -198,6 +198,33 @@ def check_layer_restore(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000,
     assert int(st.item()) == o_st
 
 
+def check_layer_save(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000, sgl_id=8, sqe_cap=None, stage_cap=None):
+    o_ext0, o_tot0 = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    nbytes = max(int(o_tot0[0]), 16)
+    n_sqe = int(o_tot0[1])
+    cap = n_sqe if sqe_cap is None else sqe_cap
+    scap = int(o_tot0[0]) if stage_cap is None else stage_cap
+    stage = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=DEV)
+    ext = torch.zeros(max(1, c.n_req) * 32, dtype=torch.uint8, device=DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=DEV)
+    sqe = torch.full((max(cap, 1) * 64,), 0x3C, dtype=torch.uint8, device=DEV)
+    st = new_status()
+    B.tutti_layer_save(c.gpu_pool(), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id, layer,
+                       stage, scap, stage_addr, sgl_id, ext, tot, sqe, cap, cu_budget, st)
+    torch.cuda.synchronize()
+    o_stage = np.full(nbytes, 0x5A, np.uint8)
+    o_ext, o_tot, o_sqe, o_st = orc.layer_save(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks, c.table, c.file_id, layer,
+                                               o_stage, stage_addr, sgl_id, cap, stage_cap=scap)
+    assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes()
+    assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot)
+    w = min(n_sqe, cap)
+    got = sqe.cpu().numpy()
+    assert got[: 64 * w].tobytes() == o_sqe[:w].tobytes() and np.all(got[64 * w:] == 0x3C)
+    gs = stage.cpu().numpy()
+    assert np.array_equal(gs, o_stage), f"{c.name}: saved objects differ at byte {first_diff(gs, o_stage)}"
+    assert int(st.item()) == o_st
+
+
 def check_everything(orc, c, cu_budget=0):
     """All five entry points on one case, each against the oracle."""
     ext, tot, o_ext, o_tot = check_layout(orc, c)
@@ -205,6 +232,7 @@ def check_everything(orc, c, cu_budget=0):
     check_unpack(orc, c, ext, o_ext, o_tot, cu_budget)
     check_sqe(orc, c, ext, o_ext, o_tot, layer=c.L - 1)
     check_layer_restore(orc, c, layer=c.L - 1, cu_budget=cu_budget)
+    check_layer_save(orc, c, layer=c.L - 1, cu_budget=cu_budget)
 
 
 def check_direct_mode(orc, c, layer=0, sgl_id=17, sqe_cap=None, table_len=None):

@@ -468,6 +468,15 @@ def check_layer_restore(orc, seed=17):
         assert ext.tobytes() == ext2.tobytes() and sqe.tobytes() == sqe2.tobytes()
         assert np.array_equal(ka, kb) and np.array_equal(va, vb)
         assert not np.array_equal(ka, k)
+        # the save direction: extents, WRITE entries and packed objects as the separate calls give them
+        wsqe, _ = orc.sqe_build(pa, cfg, ext, fid, 2, orc.OP_WRITE, 4096, 6)
+        s1 = np.full(int(tot[0]), 0x42, np.uint8)
+        orc.obj_pack(pa, cfg, ext, table, s1)
+        s2 = np.full(int(tot[0]), 0x42, np.uint8)
+        ext3, tot3, wsqe3, st = orc.layer_save(pa, cfg, n, table, fid, 2, s2, 4096, 6, wsqe.size)
+        assert st == 0 and np.array_equal(tot, tot3) and ext.tobytes() == ext3.tobytes()
+        assert wsqe.tobytes() == wsqe3.tobytes() and np.all(wsqe3["opcode"] == orc.OP_WRITE)
+        assert np.array_equal(s1, s2) and not np.all(s2 == 0x42)
 
 
 def check_threaded(orc, seed=19):

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert getattr(L, name) is not None
     for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
-                 "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
+                 "tutti_layer_save", "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
                  "tutti_issue_io", "tutti_wait_cqe"):
         assert name in declared and callable(getattr(B, name))
     assert B.tutti_version() >= 0x100
@@ -76,6 +76,8 @@ def test_bad_pool_is_einval(bad):
     _expect(B.EINVAL, B.tutti_obj_unpack, p, B.make_cfg(), FAKE, 1, FAKE, 1, FAKE, 1 << 20)
     _expect(B.EINVAL, B.tutti_sqe_build, p, B.make_cfg(), FAKE, 1, FAKE, 0, B.OP_READ, 0, 0, FAKE, 4)
     _expect(B.EINVAL, B.tutti_layer_restore, p, B.make_cfg(), FAKE, 1, FAKE, 1, FAKE, 0, FAKE, 1 << 20, 0, 0, FAKE,
+            FAKE, FAKE, 4)
+    _expect(B.EINVAL, B.tutti_layer_save, p, B.make_cfg(), FAKE, 1, FAKE, 1, FAKE, 0, FAKE, 1 << 20, 0, 0, FAKE,
             FAKE, FAKE, 4)
 
 

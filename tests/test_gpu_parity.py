@@ -326,6 +326,7 @@ def test_bad_block_ids_are_skipped_and_reported(orc, H):
     H.check_pack(orc, c, ext, o_ext, o_tot)
     H.check_unpack(orc, c, ext, o_ext, o_tot)
     H.check_layer_restore(orc, c)
+    H.check_layer_save(orc, c)
 
 
 def test_small_capacities_are_clamped_and_reported(orc, H):
@@ -340,6 +341,7 @@ def test_small_capacities_are_clamped_and_reported(orc, H):
     H.check_sqe(orc, c, ext, o_ext, o_tot, sqe_cap=11)
     H.check_sqe(orc, c, ext, o_ext, o_tot, sqe_cap=0)
     H.check_layer_restore(orc, c, sqe_cap=5, stage_cap=cap)
+    H.check_layer_save(orc, c, sqe_cap=5, stage_cap=cap)
 
 
 def test_short_table_is_never_overrun(orc, H):
@@ -454,6 +456,90 @@ def test_cfg4_llama70b_128k_layer(orc, H):
     say("cfg4 layer", w.shape)
     c = H.LayerCase.from_workload(w)
     H.check_everything(orc, c)
+
+
+def _full_pool_sampled(orc, H, w, sample_layers, n_stage=4):
+    """Every layer of the workload resident, each restored by its own launch as bench.py does it; the layers
+    in `sample_layers` hold seeded values and are compared with the oracle plane by plane, and the save of
+    those layers is compared object by object."""
+    s = w.shape
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    plane_bytes = s.num_blocks * bb
+    payload = 2 * int(w.block_table.size) * bb
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()          # earlier tests' blocks are cached by the allocator, not free
+    free, _ = torch.cuda.mem_get_info()
+    need = s.num_layers * 2 * plane_bytes + n_stage * payload + (6 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free HBM for the whole pool, {free >> 30} GiB free")
+    geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads, head_dim=s.head_dim,
+                elt_bytes=s.elt_bytes)
+    cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
+    planes = []
+    for l in range(s.num_layers):
+        if l in sample_layers:
+            k = W.device_values(W.seed_for(w.cfg_id, l), plane_bytes // 2, s.dtype, H.DEV).view(torch.uint8)
+            v = W.device_values(W.seed_for(w.cfg_id, l) + 500, plane_bytes // 2, s.dtype, H.DEV).view(torch.uint8)
+        else:
+            k = torch.empty(plane_bytes, dtype=torch.uint8, device=H.DEV)
+            v = torch.empty(plane_bytes, dtype=torch.uint8, device=H.DEV)
+        planes.append((k, v))
+    before = {l: (planes[l][0].cpu().numpy(), planes[l][1].cpu().numpy()) for l in sample_layers}
+    g = torch.Generator(device=H.DEV)
+    g.manual_seed(77)
+    stages = [torch.randint(0, 256, (payload,), dtype=torch.uint8, device=H.DEV, generator=g) for _ in range(n_stage)]
+    d_n, d_tab, d_fid = H.to_dev(w.n_blocks), H.to_dev(w.block_table), H.to_dev(w.file_id)
+    ext = torch.zeros(32 * w.n_req, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    n_sqe = int(2 * np.sum((w.n_blocks.astype(np.int64) * bb + w.chunk_bytes - 1) // w.chunk_bytes))
+    sqe = torch.zeros(s.num_layers, n_sqe * 64, dtype=torch.uint8, device=H.DEV)
+    st = H.new_status()
+    n_tab = int(w.block_table.size)
+    for l in range(s.num_layers):          # the restore train
+        stg = stages[l % n_stage]
+        B.tutti_layer_restore(B.make_pool(*planes[l], **geom), cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, stg, payload,
+                              stg.data_ptr(), 1, ext, tot, sqe[l], n_sqe, 0, st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    ocfg = orc.make_cfg(w.align, w.chunk_bytes, s.num_layers)
+    for l in sample_layers:
+        say("  sampled layer", l)
+        ok, ov = before[l]
+        stg = stages[l % n_stage]
+        o_ext, o_tot, o_sqe, o_st = orc.layer_restore(orc.make_pool(ok, ov, **geom), ocfg, w.n_blocks, w.block_table,
+                                                      w.file_id, l, stg.cpu().numpy(), stg.data_ptr(), 1, n_sqe)
+        assert np.array_equal(planes[l][0].cpu().numpy(), ok), f"layer {l}: K plane differs"
+        assert np.array_equal(planes[l][1].cpu().numpy(), ov), f"layer {l}: V plane differs"
+        assert sqe[l].cpu().numpy().tobytes() == o_sqe.tobytes() and o_st == 0
+        # and the save of that layer back into a fresh staging buffer
+        out = torch.zeros(payload, dtype=torch.uint8, device=H.DEV)
+        B.tutti_layer_save(B.make_pool(*planes[l], **geom), cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, out, payload,
+                           out.data_ptr(), 1, ext, tot, sqe[l], n_sqe, 0, st)
+        torch.cuda.synchronize()
+        o_out = np.zeros(payload, np.uint8)
+        orc.obj_pack(orc.make_pool(ok, ov, **geom), ocfg, o_ext, w.block_table, o_out)
+        assert np.array_equal(out.cpu().numpy(), o_out), f"layer {l}: saved objects differ"
+        assert np.array_equal(out.cpu().numpy(), stg.cpu().numpy()), "save after restore returns the staged bytes"
+        del out
+    assert int(st.item()) == 0
+    del planes, stages, before
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def test_cfg2_whole_pool_sampled_layers(orc, H):
+    """Config 2 as bench.py runs it: all 32 layers resident (128 GiB of planes), one launch per layer."""
+    w = W.llama8b_32k()
+    say("cfg2 whole pool")
+    _full_pool_sampled(orc, H, w, sample_layers=(0, 13, 31))
+
+
+def test_cfg4_whole_pool_sampled_layers(orc, H):
+    """Config 4 at its full size: 80 layers x 38146 blocks = 200 GB of planes, fragmented 8192-block table."""
+    w = W.llama70b_128k()
+    say("cfg4 whole pool")
+    _full_pool_sampled(orc, H, w, sample_layers=(0, 41, 79))
 
 
 @pytest.mark.parametrize("budget", [8, 16, 32, 64])

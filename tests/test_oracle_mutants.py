@@ -85,6 +85,10 @@ MUTANTS = {
     "io_cq_index": ("entry[c->tail % depth] = io->hdr.iocb_idx;", "entry[c->tail % depth] = b;"),
     "io_not_marked_done": ("io->hdr.state = ORC_IOCB_DONE;", "io->hdr.state = ORC_IOCB_FILLED;"),
     "io_file_bound": ("s->file_off + s->len > store->file_stride) {", "s->file_off > store->file_stride) {"),
+    "save_builds_read": ("ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);",
+                         "ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);"),
+    "save_unpacks": ("  return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* ---",
+                     "  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* ---"),
     "restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
                              "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);"),
 }
