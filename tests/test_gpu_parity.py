@@ -217,6 +217,73 @@ def test_paper_block_sizes(orc, H):
         H.check_direct_mode(orc, c, layer=31)
 
 
+# ------------------------------------------------------------------ HIP graph capture
+
+def test_layer_calls_can_be_captured_in_a_graph(orc, H):
+    """The per-layer calls allocate nothing and never synchronise, so a train of them can be captured in a
+    HIP graph (no memset nodes are recorded).  Every replay must reproduce the eager result, with eager
+    work and synchronisation between the replays."""
+    say("graph capture")
+    rng = np.random.default_rng(55)
+    nb = [40, 0, 25]
+    N = 256
+    cases = [H.LayerCase(T=16, h=8, d=128, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=65536, L=4,
+                         seed=10 + l, name=f"graph{l}") for l in range(4)]
+    c0 = cases[0]
+    o_ext, o_tot = orc.obj_layout(c0.orc_pool(orc), c0.orc_cfg(orc), c0.n_blocks)
+    nbytes, n_sqe = int(o_tot[0]), int(o_tot[1])
+    stages = [torch.zeros(nbytes, dtype=torch.uint8, device=H.DEV) for _ in cases]
+    k2 = [torch.zeros_like(c.k_dev) for c in cases]
+    v2 = [torch.zeros_like(c.v_dev) for c in cases]
+    ext = torch.zeros(len(cases), 32 * c0.n_req, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(len(cases), 2, dtype=torch.int64, device=H.DEV)
+    wsqe = torch.zeros(len(cases), n_sqe * 64, dtype=torch.uint8, device=H.DEV)
+    rsqe = torch.zeros(len(cases), n_sqe * 64, dtype=torch.uint8, device=H.DEV)
+    st = H.new_status()
+
+    def train():   # save every layer from its pool, then restore it into a second pool
+        for l, c in enumerate(cases):
+            B.tutti_layer_save(c.gpu_pool(), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id, l,
+                               stages[l], nbytes, stages[l].data_ptr(), 2, ext[l], tot[l], wsqe[l], n_sqe, 0, st)
+        for l, c in enumerate(cases):
+            B.tutti_layer_restore(c.gpu_pool(k2[l], v2[l]), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size,
+                                  c.d_file_id, l, stages[l], nbytes, stages[l].data_ptr(), 2, ext[l], tot[l], rsqe[l],
+                                  n_sqe, 0, st)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in stages + k2 + v2] + [ext.clone(), tot.clone(), wsqe.clone(), rsqe.clone()]
+
+    def clear():
+        for t in stages + k2 + v2 + [ext, tot, wsqe, rsqe]:
+            t.zero_()
+
+    train()                                   # eager (also warms up the one-time device query)
+    eager = snapshot()
+    # the eager result is the oracle's
+    for l, c in enumerate(cases):
+        o_stage = np.zeros(nbytes, np.uint8)
+        orc.obj_pack(c.orc_pool(orc), c.orc_cfg(orc), o_ext, c.table, o_stage)
+        assert np.array_equal(stages[l].cpu().numpy(), o_stage)
+    clear()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            train()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        clear()
+        junk = torch.randn(512, 512, device=H.DEV) @ torch.randn(512, 512, device=H.DEV)   # eager work in between
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(eager, got):
+            assert torch.equal(a, b), f"graph replay {rep} differs from the eager result"
+        assert torch.isfinite(junk).all() and int(st.item()) == 0
+
+
 # ------------------------------------------------------------------ seeded random shapes
 
 @pytest.mark.parametrize("seed", range(12))
