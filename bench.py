@@ -10,7 +10,7 @@ left in the 256 MB Infinity Cache.  Inputs are resident in HBM before the timed 
 
 Prints ONE JSON line on stdout; progress goes to stderr.
   value            payload GB/s of the whole step (bytes packed + bytes restored, 1 GB = 1e9 B)
-  roofline         the dominant kernel (k_restore: the unpack) against the 8 TB/s HBM peak,
+  roofline         the dominant kernel (k_layer<unpack>: the fused restore) against the 8 TB/s HBM peak,
                    timed with events on the launch stream inside the timed region
   cpu_baseline     the CPU oracle, as it stands, on one layer of the same workload
 Extra legs (same JSON line): restore / pack alone, a plain-copy ceiling, entries built per second,
@@ -40,7 +40,7 @@ def median(xs):
 
 
 def read_traffic_note():
-    """HBM bytes per k_restore launch measured with rocprofv3 --pmc (profiles/), if recorded."""
+    """HBM bytes per restore launch measured with rocprofv3 --pmc (profiles/), if recorded."""
     path = os.path.join(ROOT, "profiles", "k_restore_llama8b_32k_pmc.txt")
     try:
         for line in open(path):
@@ -178,9 +178,9 @@ def main():
 
     step_payload = 2 * L * payload_layer                 # packed + restored
     value = step_payload / (ms_per_step * 1e-3) / 1e9
-    restore_us = float(np.mean(rest_ms)) * 1e3 / L       # average k_restore launch, launch gaps included
+    restore_us = float(np.mean(rest_ms)) * 1e3 / L       # average restore launch, launch gaps included
     save_us = float(np.mean(save_ms)) * 1e3 / L
-    # algorithmic bytes of one k_restore launch: payload read + payload written, the block table,
+    # algorithmic bytes of one restore launch: payload read + payload written, the block table,
     # the request counts and file ids, the entries and extents it writes
     restore_alg_bytes = 2 * payload_layer + 4 * n_tab + 4 * w.n_req * 2 + 64 * n_sqe_layer + 32 * w.n_req + 16
     achieved = restore_alg_bytes / (restore_us * 1e-6) / 1e9
@@ -196,7 +196,7 @@ def main():
                    "step": "per layer: layer_save (extents + WRITE entries + pack); then per layer: layer_restore "
                            "(extents + READ entries + unpack); one launch each",
                    "wgs_per_cu": args.wgs_per_cu, "unroll": args.unroll, "nontemporal": not args.plain_loads},
-        "roofline": {"bound": "hbm", "kernel": "k_restore", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "k_layer<unpack> (tutti_layer_restore)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
                      "algorithmic_bytes_per_launch": restore_alg_bytes, "avg_launch_us": round(restore_us, 2)},
         "restore": {"us_per_layer": round(restore_us, 2),
