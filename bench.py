@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the copy-ceiling / entry-rate legs")
     ap.add_argument("--corun", action="store_true", help="also run the CU-budget sweep beside a GEMM (config 5)")
+    ap.add_argument("--scatter-sweep", action="store_true",
+                    help="also sweep the granularity of tutti_scatter_baseline (4 KiB .. 4 MiB, random and sorted)")
     ap.add_argument("--rings", action="store_true",
                     help="also time the entry-driven path: fill IOCBs on the GPU, then tutti_issue_io (no staging copy)")
     ap.add_argument("--pinned-stage", action="store_true",
@@ -242,6 +244,8 @@ def main():
                                             gemm_n=8192, budgets=(8, 32, 0))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], stages[0], geom, payload_layer)
+    if args.scatter_sweep:
+        out["scatter_sweep"] = scatter_sweep(torch, B, stages, payload_layer, dev)
     if args.rings:
         out["rings_direct_to_block"] = ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid,
                                                 payload_layer, dev)
@@ -454,6 +458,44 @@ def scatter_floor(torch, B, w, stages, nbytes, dev, n_buf=6, reps=5):
         us = median(times)
         res[label] = {"us": round(us, 2), "traffic_GBps": round(2 * nbytes / (us * 1e-6) / 1e9, 1),
                       "pct_hbm_peak": round(100 * 2 * nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
+    return res
+
+
+def scatter_sweep(torch, B, stages, nbytes, dev, span=2 << 30, n_buf=6, reps=3):
+    """tutti_scatter_baseline at every granularity from 4 KiB to 4 MiB: 128 MiB contiguous against pieces
+    placed inside a 2 GiB span at random, in sorted order, or contiguously; microseconds per 128 MiB."""
+    rng = np.random.default_rng(1)
+    bufs = [torch.empty(span, dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    scratch = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(4)]
+    res = {}
+    gran = 4096
+    while gran <= (4 << 20):
+        n = nbytes // gran
+        perms = {"random": rng.permutation(span // gran)[:n]}
+        perms["sorted"] = np.sort(perms["random"])
+        perms["contiguous"] = np.arange(n)
+        row = {}
+        for order, p in perms.items():
+            d_perm = torch.from_numpy(p.astype(np.uint32).view(np.int32)).to(dev)
+            for label, wr in (("writes", 1), ("reads", 0)):
+                def run():
+                    for i in range(len(stages)):
+                        B.tutti_scatter_baseline(bufs[i % n_buf], span, scratch[i % 4] if not wr else stages[i], nbytes,
+                                                 d_perm, gran, wr)
+                run()
+                torch.cuda.synchronize()
+                ts = []
+                for _ in range(reps):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    run()
+                    b.record()
+                    torch.cuda.synchronize()
+                    ts.append(a.elapsed_time(b) * 1e3 / len(stages))
+                row[f"{order}_{label}_us"] = round(median(ts), 2)
+        res[str(gran)] = row
+        log(f"[bench] scatter sweep gran {gran}: {row}")
+        gran *= 2
     return res
 
 
