@@ -49,6 +49,33 @@ def test_record_layouts_agree_with_oracle(orc):
         assert a == b
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/tutti.h compiles as strict C11 and as C++17 on its own, with the record sizes the ABI promises."""
+    import subprocess
+    src = """
+#include "tutti.h"
+_Static_assert(sizeof(tutti_extent) == 32, "extent");
+_Static_assert(sizeof(tutti_sqe) == 64, "sqe");
+_Static_assert(sizeof(tutti_sgl) == 16, "sgl");
+_Static_assert(sizeof(tutti_iocb_hdr) == 64, "iocb header");
+_Static_assert(sizeof(tutti_iocb) == 64 + 64 * TUTTI_IOCB_SLOTS, "iocb");
+_Static_assert(sizeof(tutti_cq_hdr) == 64, "cq header");
+int (*const p_restore)(const tutti_pool *, const tutti_objcfg *, const uint32_t *, uint32_t, const uint32_t *, uint32_t,
+                       const uint32_t *, uint32_t, const void *, uint64_t, uint64_t, uint32_t, tutti_extent *,
+                       uint64_t *, tutti_sqe *, uint32_t, uint32_t, uint32_t *, void *) = tutti_layer_restore;
+int main(void) { (void)p_restore; return 0; }
+"""
+    inc = os.path.join(ROOT, "include")
+    c = tmp_path / "abi.c"
+    c.write_text(src)
+    subprocess.run(["gcc", "-std=c11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", f"-I{inc}", str(c)],
+                   check=True)
+    cpp = tmp_path / "abi.cc"
+    cpp.write_text(src.replace("_Static_assert", "static_assert"))
+    subprocess.run(["g++", "-std=c++17", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", f"-I{inc}",
+                    str(cpp)], check=True)
+
+
 def test_strerror():
     for code in (B.OK, B.EINVAL, B.ERANGE, B.EHIP, -99):
         assert isinstance(B.tutti_strerror(code), str) and B.tutti_strerror(code)
