@@ -136,8 +136,8 @@ int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
 // Fills the kernel arguments and settles how a head-major pool is moved (L->hnd_lds, L->unroll,
 // L->tile_lds).  L must already hold the workgroup size and default unroll from plan_launch.
 int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t *d_block_table, uint32_t table_len,
-                   const void *d_stage, uint64_t stage_cap, uint32_t *d_status, uint32_t n_req, Launch *L,
-                   MoveArgs *m) {
+                   const void *d_stage, uint64_t stage_cap, uint32_t *d_status, uint32_t n_req, uint32_t align,
+                   Launch *L, MoveArgs *m) {
   m->k_base = static_cast<unsigned char *>(pool->k_base);
   m->v_base = static_cast<unsigned char *>(pool->v_base);
   m->stage = static_cast<unsigned char *>(const_cast<void *>(d_stage));
@@ -190,6 +190,10 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
   }
   // the kernels number work items in 32 bits
   if (2ull * table_len * m->slices_per_block > 0xffffffffull) return TUTTI_ERANGE;
+  m->items_bound = 2u * table_len * m->slices_per_block;
+  // dense staging: no padding anywhere and no ragged slice, so the staging offset of an item is item * slice
+  const uint32_t slice_bytes = kWave * 16u * L->unroll;
+  m->dense = (!L->hnd_lds && block_bytes % align == 0 && block_bytes % slice_bytes == 0) ? 1u : 0u;
   return TUTTI_OK;
 }
 
@@ -340,7 +344,7 @@ int move_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_exte
   rc = plan_launch(cu_budget, 0, &L);
   if (rc) return rc;
   MoveArgs m;
-  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, n_req, &L, &m);
+  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, n_req, cfg->align, &L, &m);
   if (rc) return rc;
   Launch G;
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
@@ -457,7 +461,7 @@ int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t 
   rc = plan_launch(cu_budget, 0, &L);
   if (rc) return rc;
   MoveArgs m;
-  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, n_req, &L, &m);
+  rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, n_req, cfg->align, &L, &m);
   if (rc) return rc;
   Launch G;
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);

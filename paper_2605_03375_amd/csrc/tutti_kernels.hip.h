@@ -546,6 +546,10 @@ struct MoveArgs {
   uint32_t token_shift;  // log2(block_tokens)
   uint32_t tile_shift;   // log2(tokens per tile)
   uint32_t lds_pitch;    // bytes between consecutive tokens of the tile in LDS: h*row_bytes + row_bytes
+  // dense staging: blocks are whole alignment units and whole slices, so item `it` of an unpack reads the
+  // staging bytes [it*slice, (it+1)*slice) whatever the extents are; items_bound = 2 * table_len * slices
+  uint32_t dense;
+  uint32_t items_bound;
 };
 
 constexpr int kPack = 0;   // pool -> object
@@ -665,11 +669,54 @@ __device__ __forceinline__ void move_one(const MoveArgs &a, const Item &d, uint3
   }
 }
 
+// First item of a wavefront in an unpack from dense staging: its source bytes do not depend on the extents,
+// so their loads can be in flight while the workgroup is still fetching or scanning the extents.
+template <int U>
+struct Preload {
+  u32x4 buf[U];
+  bool valid;
+};
+
+template <int U, int NT>
+__device__ __forceinline__ Preload<U> preload_first(const MoveArgs &a) {
+  constexpr uint32_t kSlice = kWave * 16u * U;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t it = blockIdx.x * (blockDim.x / kWave) + rfl(threadIdx.x / kWave);
+  Preload<U> p;
+  p.valid = a.dense != 0 && it < a.items_bound && (static_cast<uint64_t>(it) + 1) * kSlice <= a.stage_cap;
+  if (p.valid) {
+    const unsigned char *src = a.stage + static_cast<uint64_t>(it) * kSlice + lane * 16u;
+#pragma unroll
+    for (int k = 0; k < U; ++k) p.buf[k] = ld16<NT>(src + k * (kWave * 16u));
+  }
+  return p;
+}
+
+// Stores of an unpack item whose slice was preloaded (whole slices only: dense staging).
+template <bool HND, int U, int NT>
+__device__ __forceinline__ void store_preloaded(const MoveArgs &a, const Item &d, uint32_t id, uint32_t lane,
+                                                const Preload<U> &p) {
+  constexpr uint32_t kSlice = kWave * 16u * U;
+  if (d.obj_ptr == nullptr) return;
+  if (id < a.num_blocks) {
+    unsigned char *blk_ptr = (d.kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
+    const uint32_t o0 = d.s * kSlice + lane * 16u;
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const uint32_t o = o0 + k * (kWave * 16u);
+      st16<NT>(blk_ptr + (HND ? hnd_offset(o, a.row_bytes, a.block_tokens, a.num_kv_heads) : o), p.buf[k]);
+    }
+  } else if (lane == 0 && d.s == 0 && a.status) {
+    atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
+  }
+}
+
 // The copy loop of the first `copy_wgs` workgroups of the grid (the rest, if any, have other work).
 // Software-pipelined by one item: the next item is decoded and its block id requested before the
 // current item's loads and stores are issued.
 template <int DIR, bool HND, int U, int NT>
-__device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t copy_wgs) {
+__device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t copy_wgs,
+                                           const Preload<U> &pre) {
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const uint32_t n_waves = copy_wgs * (blockDim.x / kWave);
@@ -681,6 +728,7 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
   if (it >= n_items) return;
   Item cur = decode_item(a, l, n_req, it, lane);
   uint32_t id = load_block_id(a, cur);
+  bool first = true;
   for (;;) {
     const uint32_t nit = it + n_waves;
     const bool more = nit < n_items;
@@ -690,7 +738,11 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
       nxt = decode_item(a, l, n_req, nit, lane);
       nid = load_block_id(a, nxt);
     }
-    move_one<DIR, HND, U, NT>(a, cur, id, lane);
+    if (DIR == kUnpack && first && pre.valid)
+      store_preloaded<HND, U, NT>(a, cur, id, lane, pre);
+    else
+      move_one<DIR, HND, U, NT>(a, cur, id, lane);
+    first = false;
     if (!more) break;
     cur = nxt;
     id = nid;
@@ -811,8 +863,11 @@ __global__ __launch_bounds__(WG) void k_move(const MoveArgs a, const tutti_exten
                                                       uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
+  Preload<U> pre;
+  pre.valid = false;
+  if (DIR == kUnpack) pre = preload_first<U, NT>(a);
   lds_from_extents(ext, n_req, l);
-  move_items<DIR, HND, U, NT>(a, l, n_req, gridDim.x);
+  move_items<DIR, HND, U, NT>(a, l, n_req, gridDim.x, pre);
 }
 
 template <int DIR, int PT, int WG>
@@ -835,6 +890,9 @@ __global__ __launch_bounds__(WG) void k_layer(const MoveArgs m, const SqeArgs q,
                                                uint32_t copy_wgs, uint32_t sqe_wgs) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
+  Preload<U> pre;
+  pre.valid = false;
+  if (DIR == kUnpack && blockIdx.x < copy_wgs) pre = preload_first<U, NT>(m);  // in flight during the scan
   if (threadIdx.x < kWave) {
     const bool publish = blockIdx.x + 1 == gridDim.x;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
@@ -843,7 +901,7 @@ __global__ __launch_bounds__(WG) void k_layer(const MoveArgs m, const SqeArgs q,
   __syncthreads();
   const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
   if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
-  if (blockIdx.x < copy_wgs) move_items<DIR, HND, U, NT>(m, l, a.n_req, copy_wgs);
+  if (blockIdx.x < copy_wgs) move_items<DIR, HND, U, NT>(m, l, a.n_req, copy_wgs, pre);
 }
 
 template <int DIR, int PT, int WG>
