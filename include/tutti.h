@@ -302,6 +302,10 @@ int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll);
  * shorter than 128 bytes and T, h and the row size are powers of two; else 16 bytes per lane straight
  * between the two orders), 1 = always the direct copy, 2 = through LDS whenever the shape allows. */
 int tutti_set_hnd_mode(uint32_t mode);
+/* Experiment switch: how pack / unpack work items are dealt to workgroups.  0 (default): workgroup b starts
+ * at item 4b, so the workgroups the dispatcher deals round-robin to the 8 XCDs take neighbouring 16 KiB;
+ * 1: each XCD takes one contiguous eighth of the items. */
+int tutti_set_xcd_mapping(uint32_t contiguous);
 /* Experiment switch for the copy loops: bit 0 = non-temporal 16-byte loads, bit 1 = non-temporal
  * 16-byte stores (default 3 = both). */
 int tutti_set_nontemporal(uint32_t mask);

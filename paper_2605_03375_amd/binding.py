@@ -39,7 +39,7 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
            "tutti_issue_io", "tutti_wait_cqe",
            "tutti_copy_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
-           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"]
+           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]
 
 
 class tutti_pool(C.Structure):
@@ -134,6 +134,8 @@ def lib():
         L.tutti_set_tuning.argtypes = [u32, u32]
         L.tutti_set_nontemporal.argtypes = [u32]
         L.tutti_set_hnd_mode.argtypes = [u32]
+        L.tutti_set_xcd_mapping.argtypes = [u32]
+        L.tutti_set_xcd_mapping.restype = C.c_int
         for name in ("tutti_ring_init", "tutti_iocb_fill_direct", "tutti_issue_io", "tutti_wait_cqe",
                      "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
                      "tutti_layer_restore", "tutti_copy_baseline", "tutti_last_hip_error", "tutti_cu_count",
@@ -315,3 +317,7 @@ def tutti_set_nontemporal(mask=3):
 
 def tutti_set_hnd_mode(mode=0):
     return _check("tutti_set_hnd_mode", lib().tutti_set_hnd_mode(int(mode)))
+
+
+def tutti_set_xcd_mapping(contiguous=0):
+    return _check("tutti_set_xcd_mapping", lib().tutti_set_xcd_mapping(1 if contiguous else 0))

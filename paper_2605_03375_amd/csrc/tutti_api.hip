@@ -19,6 +19,7 @@ thread_local int t_last_hip = 0;
 std::atomic<uint32_t> g_wgs_per_cu{0};
 std::atomic<uint32_t> g_unroll{0};
 std::atomic<uint32_t> g_nontemporal{3};  // bit 0: loads, bit 1: stores
+std::atomic<uint32_t> g_xcd_contiguous{0};  // experiment: item numbering per XCD (see MoveArgs::xcd_contiguous)
 std::atomic<uint32_t> g_hnd_mode{0};     // head-major pools: 0 = choose, 1 = direct, 2 = through LDS when possible
 
 constexpr uint32_t kDefaultWgsPerCu = 8;     // whole-GPU launches: 8 x 256 threads = 32 wavefronts per CU
@@ -191,6 +192,7 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
   // the kernels number work items in 32 bits
   if (2ull * table_len * m->slices_per_block > 0xffffffffull) return TUTTI_ERANGE;
   m->items_bound = 2u * table_len * m->slices_per_block;
+  m->xcd_contiguous = g_xcd_contiguous.load(std::memory_order_relaxed);
   // dense staging: no padding anywhere and no ragged slice, so the staging offset of an item is item * slice
   const uint32_t slice_bytes = kWave * 16u * L->unroll;
   m->dense = (!L->hnd_lds && block_bytes % align == 0 && block_bytes % slice_bytes == 0) ? 1u : 0u;
@@ -881,6 +883,12 @@ int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll) {
 int tutti_set_hnd_mode(uint32_t mode) {
   if (mode > 2u) return TUTTI_EINVAL;
   g_hnd_mode.store(mode, std::memory_order_relaxed);
+  return TUTTI_OK;
+}
+
+// Experiment switch: 1 = every XCD takes one contiguous eighth of the items instead of every eighth 16 KiB.
+int tutti_set_xcd_mapping(uint32_t contiguous) {
+  g_xcd_contiguous.store(contiguous ? 1u : 0u, std::memory_order_relaxed);
   return TUTTI_OK;
 }
 

@@ -550,7 +550,20 @@ struct MoveArgs {
   // staging bytes [it*slice, (it+1)*slice) whatever the extents are; items_bound = 2 * table_len * slices
   uint32_t dense;
   uint32_t items_bound;
+  // workgroup -> item mapping: 0 = workgroup b starts at item 4b (neighbouring workgroups, which the
+  // dispatcher deals round-robin to the 8 XCDs, take neighbouring 16 KiB); 1 = each XCD takes one
+  // contiguous eighth of the copy workgroups' items
+  uint32_t xcd_contiguous;
 };
+
+// The workgroup index used for item numbering (see MoveArgs::xcd_contiguous).
+__device__ __forceinline__ uint32_t item_wg(const MoveArgs &a, uint32_t copy_wgs) {
+  const uint32_t b = blockIdx.x;
+  if (!a.xcd_contiguous || copy_wgs < 16u) return b;
+  const uint32_t per = copy_wgs / 8u;            // workgroups per XCD (the remainder keeps its own index)
+  if (b >= per * 8u) return b;
+  return (b % 8u) * per + b / 8u;
+}
 
 constexpr int kPack = 0;   // pool -> object
 constexpr int kUnpack = 1; // object -> pool
@@ -678,10 +691,10 @@ struct Preload {
 };
 
 template <int U, int NT>
-__device__ __forceinline__ Preload<U> preload_first(const MoveArgs &a) {
+__device__ __forceinline__ Preload<U> preload_first(const MoveArgs &a, uint32_t copy_wgs) {
   constexpr uint32_t kSlice = kWave * 16u * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t it = blockIdx.x * (blockDim.x / kWave) + rfl(threadIdx.x / kWave);
+  const uint32_t it = item_wg(a, copy_wgs) * (blockDim.x / kWave) + rfl(threadIdx.x / kWave);
   Preload<U> p;
   p.valid = a.dense != 0 && it < a.items_bound && (static_cast<uint64_t>(it) + 1) * kSlice <= a.stage_cap;
   if (p.valid) {
@@ -724,7 +737,7 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
   const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
   const uint32_t n_items = 2u * total_blocks * a.slices_per_block;  // the host checked this fits 32 bits
 
-  uint32_t it = blockIdx.x * (blockDim.x / kWave) + wave_in_wg;
+  uint32_t it = item_wg(a, copy_wgs) * (blockDim.x / kWave) + wave_in_wg;
   if (it >= n_items) return;
   Item cur = decode_item(a, l, n_req, it, lane);
   uint32_t id = load_block_id(a, cur);
@@ -865,7 +878,7 @@ __global__ __launch_bounds__(WG) void k_move(const MoveArgs a, const tutti_exten
   const ReqLds l = carve_lds(smem, n_req);
   Preload<U> pre;
   pre.valid = false;
-  if (DIR == kUnpack) pre = preload_first<U, NT>(a);
+  if (DIR == kUnpack) pre = preload_first<U, NT>(a, gridDim.x);
   lds_from_extents(ext, n_req, l);
   move_items<DIR, HND, U, NT>(a, l, n_req, gridDim.x, pre);
 }
@@ -892,7 +905,7 @@ __global__ __launch_bounds__(WG) void k_layer(const MoveArgs m, const SqeArgs q,
   const ReqLds l = carve_lds(smem, a.n_req);
   Preload<U> pre;
   pre.valid = false;
-  if (DIR == kUnpack && blockIdx.x < copy_wgs) pre = preload_first<U, NT>(m);  // in flight during the scan
+  if (DIR == kUnpack && blockIdx.x < copy_wgs) pre = preload_first<U, NT>(m, copy_wgs);  // in flight during the scan
   if (threadIdx.x < kWave) {
     const bool publish = blockIdx.x + 1 == gridDim.x;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
