@@ -236,6 +236,7 @@ def main():
                                                       out["save"]["us_per_layer"], 4)
         out["sqe"] = sqe_rate(torch, B, W, dev)
         out["sqe"]["direct_to_block"] = direct_rate(torch, B, W, dev)
+        out["sqe"]["direct_to_block_2M_entries"] = big_entry_rate(torch, B, dev)
         log(f"[bench] copy ceiling {out['copy_ceiling']}; entries {out['sqe']}")
     if args.corun:
         out["corun"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev)
@@ -591,6 +592,39 @@ def direct_rate(torch, B, W, dev, reps=50):
         us = a.elapsed_time(b) * 1e3 / reps
         res[label] = {"count": n, "us_per_launch": round(us, 2), "per_s": round(n / (us * 1e-6), 0)}
     return res
+
+
+def big_entry_rate(torch, B, dev, n_req=2048, blocks_per_req=512, reps=20):
+    """Entries per second once the count is large enough to leave the launch-latency regime: 2048 requests
+    x 512 blocks = 2,097,152 per-block entries (128 MiB of entries) in one tutti_sqe_build_direct launch."""
+    rng = np.random.default_rng(7)
+    n_tab = n_req * blocks_per_req
+    num_blocks = 2 * n_tab
+    geom = dict(num_blocks=num_blocks, block_tokens=16, num_kv_heads=8, head_dim=128, elt_bytes=2)
+    pool = B.make_pool(4096, 4096, **geom)  # arithmetic only
+    cfg = B.make_cfg(4096, 32768, 32)
+    d_n = torch.full((n_req,), blocks_per_req, dtype=torch.int32, device=dev)
+    d_tab = torch.from_numpy(rng.permutation(num_blocks)[:n_tab].astype(np.uint32).view(np.int32)).to(dev)
+    d_fid = torch.arange(n_req, dtype=torch.int32, device=dev)
+    ext = torch.zeros(n_req * 32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    B.tutti_obj_layout(pool, cfg, d_n, n_req, ext, tot)
+    n_sqe = 2 * n_tab
+    sqes = [torch.empty(n_sqe * 64, dtype=torch.uint8, device=dev) for _ in range(3)]  # 3 x 128 MiB: cold writes
+    for i in range(3):
+        B.tutti_sqe_build_direct(pool, cfg, ext, n_req, d_tab, n_tab, d_fid, i, B.OP_READ, 1 << 40, 1, sqes[i], n_sqe)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for i in range(reps):
+        B.tutti_sqe_build_direct(pool, cfg, ext, n_req, d_tab, n_tab, d_fid, i % 32, B.OP_READ, 1 << 40, 1, sqes[i % 3],
+                                 n_sqe)
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / reps
+    return {"requests": n_req, "entries": n_sqe, "us_per_launch": round(us, 2),
+            "sqes_per_s": round(n_sqe / (us * 1e-6), 0), "entry_write_GBps": round(64 * n_sqe / (us * 1e-6) / 1e9, 1),
+            "regime": "HBM-write bound (64 B written per entry, 4 B of table read)"}
 
 
 def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, reps=3, gemm_n=4096,
