@@ -154,6 +154,10 @@ def main():
 
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731  (events of torch's current stream = launch stream)
 
+    # host copy of layer 0 as generated, before any kernel of the library has touched it: what the oracle
+    # works from in the cpu_baseline leg, and what the pool must still hold after save + restore
+    pristine = None if args.no_cpu_baseline else (planes[0][0].cpu().numpy(), planes[0][1].cpu().numpy())
+
     for _ in range(args.warmup):
         save_layers()
         restore_layers()
@@ -244,7 +248,7 @@ def main():
         out["corun_gemm8192"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=12, reps=2,
                                             gemm_n=8192, budgets=(8, 32, 0))
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], stages[0], geom, payload_layer)
+        out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], pristine, stages[0], geom, payload_layer)
     if args.scatter_sweep:
         out["scatter_sweep"] = scatter_sweep(torch, B, stages, payload_layer, dev)
     if args.rings:
@@ -701,12 +705,15 @@ def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, 
     return out
 
 
-def cpu_baseline(torch, W, w, plane0, stage0, geom, payload_layer, budget_s=8.0):
-    """The CPU oracle on layer 0 of the same workload: pack + restore of its 2048 blocks, on host
-    copies of exactly the bytes the GPU used; single thread, then all cores of the affinity mask.
-    Also a free full-size parity check: the GPU's staging buffer of layer 0 must equal the oracle's."""
+def cpu_baseline(torch, W, w, plane0, pristine, stage0, geom, payload_layer, budget_s=8.0):
+    """The CPU oracle on layer 0 of the same workload: pack + restore of its 2048 blocks, on the host copy
+    of the planes taken before any kernel ran; single thread, then all cores of the affinity mask.
+    Also a free full-size parity check: after all the timed save + restore steps the pool must still hold
+    those bytes, and the GPU's staging buffer of layer 0 must equal what the oracle packs from them."""
     from oracle import tutti_oracle as orc
-    k_host, v_host = plane0[0].cpu().numpy(), plane0[1].cpu().numpy()
+    k_host, v_host = pristine
+    unchanged = bool(np.array_equal(plane0[0].cpu().numpy(), k_host) and np.array_equal(plane0[1].cpu().numpy(), v_host))
+    assert unchanged, "layer 0 of the pool changed under save + restore"
     gpu_stage = stage0.cpu().numpy()
     pool = orc.make_pool(k_host, v_host, **geom)
     cfg = orc.make_cfg(w.align, w.chunk_bytes, w.shape.num_layers)
