@@ -202,6 +202,49 @@ def test_pinned_host_staging(orc, H):
     assert np.array_equal(k2.cpu().numpy(), ok) and np.array_equal(v2.cpu().numpy(), ov) and int(st.item()) == 0
 
 
+def test_interleaved_kv_pool(orc, H):
+    """One buffer holding [num_blocks][K|V][T][h][d] (the layout of engines that keep a block's K and V side by
+    side): k_base = buffer, v_base = buffer + block_bytes, block_stride = 2 * block_bytes."""
+    say("interleaved K/V pool")
+    rng = np.random.default_rng(12)
+    T, h, d, e, N = 16, 8, 128, 2, 300
+    bb = T * h * d * e
+    nb = np.array([50, 0, 71], np.uint32)
+    table = rng.permutation(N)[: int(nb.sum())].astype(np.uint32)
+    fid = np.array([1, 2, 3], np.uint32)
+    buf = H.as_u8(W.device_values(99, N * 2 * bb // 2, "bf16", H.DEV))
+    host = buf.cpu().numpy()
+    geom = dict(num_blocks=N, block_tokens=T, num_kv_heads=h, head_dim=d, elt_bytes=e, block_stride=2 * bb)
+    pool = B.make_pool(buf, buf.data_ptr() + bb, **geom)
+    cfg = B.make_cfg(4096, 1 << 20, 2)
+    o_pool = orc.make_pool(host, None, **geom)
+    o_pool.v_base = host.ctypes.data + bb
+    ocfg = orc.make_cfg(4096, 1 << 20, 2)
+    o_ext, o_tot = orc.obj_layout(o_pool, ocfg, nb)
+    n_sqe = int(o_tot[1])
+    d_n, d_tab, d_fid = H.to_dev(nb), H.to_dev(table), H.to_dev(fid)
+    ext = torch.zeros(32 * 3, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    sqe = torch.zeros(64 * n_sqe, dtype=torch.uint8, device=H.DEV)
+    stage = torch.zeros(int(o_tot[0]), dtype=torch.uint8, device=H.DEV)
+    st = H.new_status()
+    B.tutti_layer_save(pool, cfg, d_n, 3, d_tab, table.size, d_fid, 1, stage, stage.numel(), stage.data_ptr(), 0, ext, tot,
+                       sqe, n_sqe, 0, st)
+    torch.cuda.synchronize()
+    o_stage = np.zeros(int(o_tot[0]), np.uint8)
+    orc.obj_pack(o_pool, ocfg, o_ext, table, o_stage)
+    assert np.array_equal(stage.cpu().numpy(), o_stage)
+    # restore different bytes into the same interleaved buffer
+    g = torch.Generator(device=H.DEV)
+    g.manual_seed(4)
+    stage2 = torch.randint(0, 256, (int(o_tot[0]),), dtype=torch.uint8, device=H.DEV, generator=g)
+    B.tutti_layer_restore(pool, cfg, d_n, 3, d_tab, table.size, d_fid, 1, stage2, stage2.numel(), stage2.data_ptr(), 0,
+                          ext, tot, sqe, n_sqe, 0, st)
+    torch.cuda.synchronize()
+    orc.obj_unpack(o_pool, ocfg, o_ext, table, stage2.cpu().numpy())
+    assert np.array_equal(buf.cpu().numpy(), host) and int(st.item()) == 0
+
+
 def test_paper_block_sizes(orc, H):
     """Token counts per block the paper mentions: 16-32 in general (sec. 2.1), 64 in its evaluation (sec. 4)."""
     rng = np.random.default_rng(64)
