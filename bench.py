@@ -737,12 +737,26 @@ def cpu_baseline(torch, W, w, plane0, pristine, stage0, geom, payload_layer, bud
         while len(times) < 5 or (time.perf_counter() - t_start < budget_s and len(times) < 200):
             times.append(one_pass(nt))
         res[label] = (2 * payload_layer / median(times) / 1e9, len(times))
+    # entries per second of the oracle on config 3's batch, one entry per block (81,438 entries per layer)
+    w3 = W.batch64_zipf(chunk_bytes=32768)
+    s3 = w3.shape
+    p3 = orc.make_pool(None, None, num_blocks=s3.num_blocks, block_tokens=s3.block_tokens, num_kv_heads=s3.num_kv_heads,
+                       head_dim=s3.head_dim, elt_bytes=s3.elt_bytes)
+    c3 = orc.make_cfg(w3.align, 32768, s3.num_layers)
+    e3, t3 = orc.obj_layout(p3, c3, w3.n_blocks)
+    ts = []
+    for i in range(7):
+        t = time.perf_counter()
+        orc.sqe_build(p3, c3, e3, w3.file_id, i, orc.OP_READ, 1 << 40, 1)
+        ts.append(time.perf_counter() - t)
+    oracle_sqes = int(t3[1]) / median(ts[1:])
     parity = bool(np.array_equal(stage, gpu_stage))
     log(f"[bench] oracle: 1 thread {res['1thread'][0]:.2f} GB/s, {cores} threads {res['allcores'][0]:.2f} GB/s; "
         f"GPU staging buffer of layer 0 equals the oracle's: {parity}")
     assert parity, "GPU-packed layer 0 differs from the CPU oracle"
     return {"value": round(res["allcores"][0], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
             "value_1thread": round(res["1thread"][0], 3),
+            "sqes_per_s_1thread": round(oracle_sqes, 0),
             "sample": f"layer 0 of config 2 (2048 blocks, {payload_layer >> 20} MiB packed + {payload_layer >> 20} MiB "
                       f"restored per pass), median of {res['allcores'][1]} passes with {cores} threads "
                       f"({res['1thread'][1]} passes single-threaded)"}
