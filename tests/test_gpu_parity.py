@@ -329,7 +329,10 @@ def test_layer_calls_can_be_captured_in_a_graph(orc, H):
 
 # ------------------------------------------------------------------ seeded random shapes
 
-@pytest.mark.parametrize("seed", range(12))
+import os as _os
+
+
+@pytest.mark.parametrize("seed", range(int(_os.environ.get("TUTTI_FUZZ_SEEDS", "12"))))
 def test_random_shapes(orc, H, seed):
     """Seeded random geometry, request mix, layout, stride, alignment, chunking and launch shape."""
     rng = np.random.default_rng(9000 + seed)
