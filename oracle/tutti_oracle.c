@@ -10,6 +10,7 @@
 
 #include <pthread.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <string.h>
 
 /* ------------------------------------------------------------------ helpers */
@@ -560,6 +561,50 @@ int orc_layer_save(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *
   rc = orc_sqe_build(pool, cfg, extents, n_req, file_id, layer, ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);
   if (rc) return rc;
   return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);
+}
+
+/* retrieve_layer(layer) / store_layer(layer) of sec. 3.4 through the rings, in direct-to-block mode, written as
+ * the sequence of the steps above: extents, the mapping table of this very pool (descriptors name the planes'
+ * own addresses), the layer's contexts into IOCBs, then the I/O itself with its completions. */
+static int ring_layer(uint32_t opcode, orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
+                      const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                      const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint64_t sgl_table_addr,
+                      uint32_t sgl_id, const orc_filestore *store, orc_extent *extents, uint64_t *totals,
+                      uint32_t *status) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (!pool->k_base || !pool->v_base || !cq) return ORC_EINVAL;
+  rc = orc_obj_layout(pool, cfg, n_blocks, n_req, extents, totals);
+  if (rc) return rc;
+  const uint32_t n_desc = 2u * pool->num_blocks;
+  orc_sgl *table = (orc_sgl *)malloc((size_t)n_desc * sizeof(orc_sgl));
+  if (!table) return ORC_EINVAL;
+  rc = orc_sgl_table_build(pool, (uint64_t)(uintptr_t)pool->k_base, (uint64_t)(uintptr_t)pool->v_base, sgl_id, table,
+                           n_desc, NULL);
+  if (!rc)
+    rc = orc_iocb_fill_direct(sq, depth, first_slot, n_slots, pool, cfg, extents, n_req, block_table, file_id, layer,
+                              opcode, sgl_table_addr, sgl_id, status);
+  if (!rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc, sgl_table_addr, store, status);
+  free(table);
+  return rc;
+}
+
+int orc_retrieve_layer(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
+                       const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                       const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint64_t sgl_table_addr,
+                       uint32_t sgl_id, const orc_filestore *store, orc_extent *extents, uint64_t *totals,
+                       uint32_t *status) {
+  return ring_layer(ORC_OP_READ, sq, cq, depth, first_slot, n_slots, pool, cfg, n_blocks, n_req, block_table, file_id,
+                    layer, sgl_table_addr, sgl_id, store, extents, totals, status);
+}
+
+int orc_store_layer(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
+                    const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                    const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint64_t sgl_table_addr,
+                    uint32_t sgl_id, const orc_filestore *store, orc_extent *extents, uint64_t *totals,
+                    uint32_t *status) {
+  return ring_layer(ORC_OP_WRITE, sq, cq, depth, first_slot, n_slots, pool, cfg, n_blocks, n_req, block_table, file_id,
+                    layer, sgl_table_addr, sgl_id, store, extents, totals, status);
 }
 
 /* ------------------------------------------------------------------ threaded timing helpers */

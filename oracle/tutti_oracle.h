@@ -226,6 +226,22 @@ int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, ui
                  const orc_sgl *sgl_table, uint32_t n_desc, uint64_t sgl_table_addr, const orc_filestore *store,
                  uint32_t *status);
 
+/* retrieve_layer(layer) / store_layer(layer) (sec. 3.4) through the rings in direct-to-block mode: extents of
+ * the requests, the layer's contexts into n_slots IOCBs from first_slot, their execution against the file
+ * store and the completions: orc_obj_layout, orc_iocb_fill_direct and orc_issue_io in that order, with the
+ * mapping table of this very pool (orc_sgl_table_build at the planes' own addresses).  extents (n_req records)
+ * and totals (2 values) are outputs. */
+int orc_retrieve_layer(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
+                       const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                       const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint64_t sgl_table_addr,
+                       uint32_t sgl_id, const orc_filestore *store, orc_extent *extents, uint64_t *totals,
+                       uint32_t *status);
+int orc_store_layer(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
+                    const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                    const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint64_t sgl_table_addr,
+                    uint32_t sgl_id, const orc_filestore *store, orc_extent *extents, uint64_t *totals,
+                    uint32_t *status);
+
 /* Descriptor count for a pool of pool_bytes described at gran bytes per descriptor
  * (the arithmetic of sec. 3.1, "P2P Memory Mapping Table"). */
 uint64_t orc_desc_count(uint64_t pool_bytes, uint64_t gran);

@@ -264,6 +264,38 @@ def issue_io(sq, cq, first_slot, n_slots, sgl_table, sgl_table_addr, store, file
     return status.value
 
 
+def _ring_layer(fn, sq, cq, first_slot, n_slots, pool, cfg, n_blocks, block_table, file_id, layer, sgl_table_addr,
+                sgl_id, store, file_stride, first_file_id, n_files):
+    n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    file_id = np.ascontiguousarray(file_id, dtype=np.uint32)
+    ext = np.zeros(n_blocks.size, EXTENT_DTYPE)
+    totals = np.zeros(2, np.uint64)
+    fs = OrcFileStore(store.ctypes.data, file_stride, first_file_id, n_files)
+    status = C.c_uint32(0)
+    rc = getattr(lib(), fn)(_ptr(sq), _ptr(cq), C.c_uint32(sq.size), C.c_uint32(first_slot), C.c_uint32(n_slots),
+                            C.byref(pool), C.byref(cfg), _ptr(n_blocks), C.c_uint32(n_blocks.size), _ptr(block_table),
+                            _ptr(file_id), C.c_uint32(layer), C.c_uint64(sgl_table_addr), C.c_uint32(sgl_id),
+                            C.byref(fs), _ptr(ext), _ptr(totals), C.byref(status))
+    if rc:
+        raise OracleError(fn, rc)
+    return ext, totals, status.value
+
+
+def retrieve_layer(sq, cq, first_slot, n_slots, pool, cfg, n_blocks, block_table, file_id, layer, sgl_table_addr,
+                   sgl_id, store, file_stride, first_file_id, n_files):
+    """File store -> pool blocks through the rings.  Returns (extents, totals, status); pool, sq, cq change in place."""
+    return _ring_layer("orc_retrieve_layer", sq, cq, first_slot, n_slots, pool, cfg, n_blocks, block_table, file_id,
+                       layer, sgl_table_addr, sgl_id, store, file_stride, first_file_id, n_files)
+
+
+def store_layer(sq, cq, first_slot, n_slots, pool, cfg, n_blocks, block_table, file_id, layer, sgl_table_addr,
+                sgl_id, store, file_stride, first_file_id, n_files):
+    """Pool blocks -> file store through the rings.  Returns (extents, totals, status); store, sq, cq change in place."""
+    return _ring_layer("orc_store_layer", sq, cq, first_slot, n_slots, pool, cfg, n_blocks, block_table, file_id,
+                       layer, sgl_table_addr, sgl_id, store, file_stride, first_file_id, n_files)
+
+
 def layer_save(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap, stage_cap=None):
     """Returns (extents, totals, sqe, status); `stage` is written in place."""
     n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)

@@ -723,6 +723,94 @@ def check_issue_io(orc, seed=37):
     assert orc.issue_io(sq, cq, 2, 2, sgl, base, store, file_stride, 70, 4) == 0 and int(cq[0]) == 2  # FREE slots: no-op
 
 
+def check_ring_layer(orc, seed=41):
+    """store_layer / retrieve_layer through the rings: the file regions hold what obj_pack stages for the same
+    requests (either mode reads what the other wrote), a retrieve into a wiped pool brings the named blocks
+    back (numpy fancy indexing as the reference), extents are those of obj_layout, completions are in slot order."""
+    rng = np.random.default_rng(seed)
+    T, h, d, e, N, L, A = 16, 2, 64, 2, 2600, 3, 4096
+    bb = T * h * d * e
+    stride = bb + 256
+    k, v = _planes(rng, N, stride)
+    k0, v0 = k.copy(), v.copy()
+    p = _pool(orc, T, h, d, e, N, k, v, stride=stride)
+    cfg = orc.make_cfg(A, bb, L)
+    nb = np.array([7, 0, 1200, 31], np.uint32)             # 2476 contexts: two IOCBs
+    table = rng.permutation(N)[: int(nb.sum())].astype(np.uint32)
+    fid = np.array([9, 6, 7, 8], np.uint32)                # files are not in request order
+    ext0, tot0 = orc.obj_layout(p, cfg, nb)
+    file_stride = int(2 * L * ext0["obj_bytes"].max())
+    store = rng.integers(0, 256, size=4 * file_stride, dtype=np.uint8)
+    store0 = store.copy()
+    base = 0x7000_0000_0000
+    depth, layer = 3, 2
+    sq, cq = orc.ring_alloc(depth)
+    orc.ring_init(sq, cq)
+    ext, tot, st = orc.store_layer(sq, cq, 2, 2, p, cfg, nb, table, fid, layer, base, 11, store, file_stride, 6, 4)
+    assert st == 0 and ext.tobytes() == ext0.tobytes() and np.array_equal(tot, tot0)
+    assert np.array_equal(k, k0) and np.array_equal(v, v0)                       # a store does not touch the pool
+    assert int(cq[0]) == 2 and list(cq[16:18]) == [2, 0]
+    assert list(sq["hdr"]["state"]) == [orc.IOCB_DONE, orc.IOCB_FREE, orc.IOCB_DONE]
+    assert list(sq["hdr"]["num_ioctx"][[2, 0]]) == [2048, 2 * int(nb.sum()) - 2048]
+    assert np.all(sq["hdr"]["opcode"][[2, 0]] == orc.OP_WRITE) and np.all(sq["hdr"]["layer"][[2, 0]] == layer)
+    # the staged mode's objects for the same requests: K object then V object per request
+    stage = np.zeros(int(tot0[0]), np.uint8)
+    assert orc.obj_pack(p, cfg, ext0, table, stage) == 0
+    touched = np.zeros(store.size, bool)
+    k2, v2 = k.reshape(N, stride), v.reshape(N, stride)
+    pos = 0
+    for r in range(nb.size):
+        obj = int(ext0["obj_bytes"][r])
+        so = int(ext0["stage_off"][r])
+        ids = table[pos:pos + nb[r]]
+        for kind, plane in enumerate((k2, v2)):
+            lo = (int(fid[r]) - 6) * file_stride + (2 * layer + kind) * obj
+            assert np.array_equal(store[lo:lo + obj], stage[so + kind * obj: so + (kind + 1) * obj]), (r, kind)
+            assert np.array_equal(store[lo:lo + obj], plane[ids, :bb].reshape(-1)), (r, kind)
+            touched[lo:lo + obj] = True
+        pos += int(nb[r])
+    assert np.array_equal(store[~touched], store0[~touched])
+    # retrieve into a wiped pool: named blocks come back, nothing else is written
+    k[:] = 0
+    v[:] = 0
+    ext, tot, st = orc.retrieve_layer(sq, cq, 1, 2, p, cfg, nb, table, fid, layer, base, 11, store, file_stride, 6, 4)
+    assert st == 0 and ext.tobytes() == ext0.tobytes() and np.array_equal(tot, tot0)
+    named = np.zeros(N, bool)
+    named[table] = True
+    k0r, v0r = k0.reshape(N, stride), v0.reshape(N, stride)
+    assert np.array_equal(k2[named, :bb], k0r[named, :bb]) and np.array_equal(v2[named, :bb], v0r[named, :bb])
+    assert not k2[~named].any() and not v2[~named].any() and not k2[:, bb:].any() and not v2[:, bb:].any()
+    assert int(cq[0]) == 4 and list(cq[16:19]) == [2, 0, 1]    # completions 2, 3 (slots 1, 2) land in entries 2, 0
+    assert np.all(sq["hdr"]["opcode"][[1, 2]] == orc.OP_READ)
+    # too few IOCBs: contexts beyond n_slots*2048 are neither recorded nor executed
+    k[:] = 0
+    v[:] = 0
+    orc.ring_init(sq, cq)
+    _, _, st = orc.retrieve_layer(sq, cq, 0, 1, p, cfg, nb, table, fid, layer, base, 11, store, file_stride, 6, 4)
+    assert st == orc.ST_SQE_CAP and int(cq[0]) == 1
+    first = np.zeros(N, bool)          # contexts 0..2047: request 0 whole, request 2's K and the head of its V
+    n0, n2 = int(nb[0]), int(nb[2])
+    k_ids = np.concatenate([table[:n0], table[n0:n0 + n2]])
+    v_ids = np.concatenate([table[:n0], table[n0:n0 + (2048 - 2 * n0 - n2)]])
+    first[k_ids] = True
+    assert np.array_equal(k2[first, :bb], k0r[first, :bb]) and not k2[~first].any()
+    vm = np.zeros(N, bool)
+    vm[v_ids] = True
+    assert np.array_equal(v2[vm, :bb], v0r[vm, :bb]) and not v2[~vm].any()
+    # a block id out of range is a no-op context, reported; the others still move
+    bad = table.copy()
+    bad[5] = N
+    k[:] = 0
+    v[:] = 0
+    orc.ring_init(sq, cq)
+    _, _, st = orc.retrieve_layer(sq, cq, 0, 2, p, cfg, nb, bad, fid, layer, base, 11, store, file_stride, 6, 4)
+    assert st == orc.ST_BAD_BLOCK
+    good = np.zeros(N, bool)
+    good[np.delete(table, 5)] = True
+    assert np.array_equal(k2[good, :bb], k0r[good, :bb]) and not k2[~good].any()
+
+
 ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
-              check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io]
+              check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io,
+              check_ring_layer]

@@ -89,6 +89,13 @@ MUTANTS = {
                          "ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);"),
     "save_unpacks": ("  return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* ---",
                      "  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* ---"),
+    "ring_layer_planes_swapped": ("(uint64_t)(uintptr_t)pool->k_base, (uint64_t)(uintptr_t)pool->v_base, sgl_id, table,",
+                                  "(uint64_t)(uintptr_t)pool->v_base, (uint64_t)(uintptr_t)pool->k_base, sgl_id, table,"),
+    "retrieve_layer_writes": ("return ring_layer(ORC_OP_READ, sq,", "return ring_layer(ORC_OP_WRITE, sq,"),
+    "store_layer_reads": ("return ring_layer(ORC_OP_WRITE, sq,", "return ring_layer(ORC_OP_READ, sq,"),
+    "ring_layer_half_table": ("const uint32_t n_desc = 2u * pool->num_blocks;", "const uint32_t n_desc = 1u * pool->num_blocks;"),
+    "ring_layer_skips_issue": ("if (!rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,",
+                               "if (rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,"),
     "restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
                              "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);"),
 }
