@@ -379,8 +379,23 @@ def ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid, payload,
             c.record()
             torch.cuda.synchronize()
             only_io.append(a.elapsed_time(c) * 1e3 / L)
-        us, us_io = median(both), median(only_io)
+        one_call = B.tutti_store_layer if op == B.OP_WRITE else B.tutti_retrieve_layer
+        fused = []
+        for _ in range(reps):
+            B.tutti_ring_init(ring)
+            torch.cuda.synchronize()
+            a, b = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+            a.record()
+            for l in range(L):
+                one_call(ring, l * n_slots, n_slots, pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l,
+                         sgls[l].data_ptr(), 1, fs, ext, tot, 0, status)
+            b.record()
+            torch.cuda.synchronize()
+            fused.append(a.elapsed_time(b) * 1e3 / L)
+        us, us_io, us_one = median(both), median(only_io), median(fused)
         res[label] = {"us_per_layer_fill_plus_io": round(us, 2), "us_per_layer_issue_io": round(us_io, 2),
+                      "us_per_layer_one_call": round(us_one, 2),
+                      "pct_hbm_peak_one_call": round(100 * 2 * payload / (us_one * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
                       "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
                       "traffic_GBps_issue_io": round(2 * payload / (us_io * 1e-6) / 1e9, 1),
                       "pct_hbm_peak_issue_io": round(100 * 2 * payload / (us_io * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}

@@ -266,6 +266,27 @@ int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots
                    uint32_t n_desc, uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len,
                    uint32_t cu_budget, uint32_t *d_status, void *stream);
 
+/* retrieve_layer(layer) / store_layer(layer) (sec. 3.4 "Layer-wise Overlapping") through the rings, in
+ * direct-to-block mode, as ONE data-moving launch plus the completion kernel: the result (extents, totals,
+ * IOCBs, CQ, pool blocks or file store, status word) is that of tutti_obj_layout, tutti_iocb_fill_direct with
+ * READ (retrieve) or WRITE (store) and tutti_issue_io run one after the other, with a mapping table that
+ * tutti_sgl_table_build made for this pool at its own plane addresses and max_len = the block size.  The
+ * kernel takes block addresses from `pool` itself, so no table is passed; sgl_table_addr and sgl_id only go
+ * into the recorded contexts.  Blocks travel as raw bytes whatever pool->pool_layout says (as in
+ * tutti_issue_io).  Arguments as in those three calls; d_extents (n_req records) and d_totals (2 values) are
+ * outputs.  Same errors as tutti_iocb_fill_direct and tutti_issue_io. */
+int tutti_retrieve_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                         const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                         const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                         uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store,
+                         tutti_extent *d_extents, uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status,
+                         void *stream);
+int tutti_store_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                      const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                      const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                      uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
+                      uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream);
+
 /* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);

@@ -37,7 +37,7 @@ SGL_DTYPE = np.dtype({"names": ["addr", "len", "id"], "formats": ["<u8", "<u4", 
 EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
            "tutti_layer_save",
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
-           "tutti_issue_io", "tutti_wait_cqe",
+           "tutti_issue_io", "tutti_wait_cqe", "tutti_retrieve_layer", "tutti_store_layer",
            "tutti_copy_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]
 
@@ -125,6 +125,9 @@ def lib():
         L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
         L.tutti_issue_io.argtypes = [pr, u32, u32, vp, u32, u64, pf, u32, u32, vp, vp]
         L.tutti_wait_cqe.argtypes = [pr, u32, vp, vp]
+        L.tutti_retrieve_layer.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u64, u32, pf, vp, vp, u32,
+                                           vp, vp]
+        L.tutti_store_layer.argtypes = L.tutti_retrieve_layer.argtypes
         L.tutti_sgl_table_build.argtypes = [pp, u64, u64, u32, vp, u32, vp, vp]
         L.tutti_sqe_build_direct.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
         L.tutti_strerror.argtypes = [C.c_int]
@@ -253,6 +256,26 @@ def tutti_issue_io(ring, first_slot, n_slots, d_sgl_table, n_desc, sgl_table_add
     return _check("tutti_issue_io",
                   lib().tutti_issue_io(C.byref(ring), first_slot, n_slots, _p(d_sgl_table), n_desc, sgl_table_addr,
                                        C.byref(store), max_len, cu_budget, _p(d_status), _stream(stream)))
+
+
+def tutti_retrieve_layer(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id,
+                         layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget=0, d_status=None,
+                         stream=None):
+    return _check("tutti_retrieve_layer",
+                  lib().tutti_retrieve_layer(C.byref(ring), first_slot, n_slots, C.byref(pool), C.byref(cfg),
+                                             _p(d_n_blocks), n_req, _p(d_block_table), table_len, _p(d_file_id), layer,
+                                             sgl_table_addr, sgl_id, C.byref(store), _p(d_extents), _p(d_totals),
+                                             cu_budget, _p(d_status), _stream(stream)))
+
+
+def tutti_store_layer(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id,
+                      layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget=0, d_status=None,
+                      stream=None):
+    return _check("tutti_store_layer",
+                  lib().tutti_store_layer(C.byref(ring), first_slot, n_slots, C.byref(pool), C.byref(cfg),
+                                          _p(d_n_blocks), n_req, _p(d_block_table), table_len, _p(d_file_id), layer,
+                                          sgl_table_addr, sgl_id, C.byref(store), _p(d_extents), _p(d_totals),
+                                          cu_budget, _p(d_status), _stream(stream)))
 
 
 def tutti_wait_cqe(ring, slot, d_flag, stream=None):

@@ -153,6 +153,10 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
   m->block_tokens = pool->block_tokens;
   m->num_kv_heads = pool->num_kv_heads;
   m->row_shift = m->head_shift = m->token_shift = m->tile_shift = m->lds_pitch = 0;
+  m->direct = 0;
+  m->layer = 0;
+  m->file_stride = 0;
+  m->ctx_cap = 0;
 
   L->hnd_lds = false;
   L->tile_lds = 0;
@@ -639,7 +643,6 @@ int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t
   if (opcode != TUTTI_OP_READ && opcode != TUTTI_OP_WRITE) return TUTTI_EINVAL;
   if (layer >= cfg->num_layers) return TUTTI_EINVAL;
   if (sgl_table_addr % 16 != 0) return TUTTI_EINVAL;
-  if (n_slots == 0) return TUTTI_OK;
   const int cus = cu_count();
   if (cus < 0) return cus;
   RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
@@ -660,6 +663,7 @@ int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t
   d.num_blocks = pool->num_blocks;
   d.block_bytes = bb;
   uint64_t need = (4ull * n_slots * TUTTI_IOCB_SLOTS + kWgThreads - 1) / kWgThreads;
+  if (need == 0) need = 1;  // no IOCBs given: one workgroup still reports the dropped contexts
   const uint64_t lim = static_cast<uint64_t>(cus) * 8;
   const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
   hipLaunchKernelGGL(k_iocb_fill, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req), static_cast<hipStream_t>(stream),
@@ -715,6 +719,128 @@ int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots
   hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, s, g);
   e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+extern "C++" {
+namespace {
+// retrieve_layer (DIR = kUnpack) / store_layer (DIR = kPack) through the rings: one launch that scans, records
+// the contexts and moves the blocks, then the completion kernel.
+template <int DIR>
+int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                     const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                     const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                     uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
+                     uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  int rc = check_ring(ring, first_slot, n_slots);
+  if (rc) return rc;
+  uint32_t bb = 0;
+  rc = check_geometry(pool, cfg, &bb);
+  if (rc) return rc;
+  rc = check_planes(pool);
+  if (rc) return rc;
+  if (bb % cfg->align != 0) return TUTTI_EINVAL;
+  if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
+  if (!d_totals || (n_req > 0 && (!d_n_blocks || !d_extents || !d_file_id))) return TUTTI_EINVAL;
+  if (table_len > 0 && !d_block_table) return TUTTI_EINVAL;
+  if (layer >= cfg->num_layers || sgl_table_addr % 16 != 0) return TUTTI_EINVAL;
+  if (!store || !store->base || !aligned16(store->base) || store->file_stride % 16 != 0) return TUTTI_EINVAL;
+
+  Launch L;
+  rc = plan_launch(cu_budget, 0, &L);
+  if (rc) return rc;
+  tutti_pool raw = *pool;  // blocks travel as raw bytes: no head-major handling
+  raw.pool_layout = TUTTI_LAYOUT_NHD;
+  MoveArgs m;
+  rc = fill_move_args(&raw, bb, d_block_table, table_len, store->base, 0, d_status, n_req, cfg->align, &L, &m);
+  if (rc) return rc;
+  m.dense = 0;
+  m.direct = 1;
+  m.layer = layer;
+  m.file_stride = store->file_stride;
+  m.ctx_cap = static_cast<uint64_t>(n_slots) * TUTTI_IOCB_SLOTS;
+  Launch G;
+  rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
+  if (rc) return rc;
+  L.grid = G.grid;
+  uint64_t fill_need = (4ull * n_slots * TUTTI_IOCB_SLOTS + L.wg_threads - 1) / L.wg_threads;
+  if (fill_need < 1) fill_need = 1;
+  const uint64_t fill_max = cu_budget ? 1 : 16;
+  const uint32_t fill_wgs = static_cast<uint32_t>(fill_need < fill_max ? fill_need : fill_max);
+
+  SqeArgs q;
+  q.file_id = d_file_id;
+  q.sqe = nullptr;
+  q.status = d_status;
+  q.stage_addr = 0;
+  q.sqe_cap = 0;
+  q.chunk_bytes = bb;
+  q.layer = layer;
+  q.opcode = (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE;
+  q.sgl_id = sgl_id;
+  DirectArgs d;
+  d.table = d_block_table;
+  d.sgl_table_addr = sgl_table_addr;
+  d.table_len = table_len;
+  d.num_blocks = pool->num_blocks;
+  d.block_bytes = bb;
+  RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
+  FileArgs f{store->file_stride, store->first_file_id, store->n_files};
+  LayoutArgs a;
+  a.n_blocks = d_n_blocks;
+  a.extents = d_extents;
+  a.totals = d_totals;
+  a.geom = ScanGeom{bb, cfg->align, cfg->chunk_bytes};
+  a.n_req = n_req;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint32_t copy_wgs = L.grid;
+  const uint32_t lds = req_lds_bytes(n_req);
+#define TUTTI_RING_CASE(U)                                                                                        \
+  case U:                                                                                                         \
+    if (L.wg_threads == kWgThreads)                                                                               \
+      hipLaunchKernelGGL((k_layer_ring<DIR, U, kWgThreads>), dim3(L.grid + fill_wgs), dim3(kWgThreads), lds, s, m, q, \
+                         d, g, f, a, copy_wgs, fill_wgs);                                                         \
+    else                                                                                                          \
+      hipLaunchKernelGGL((k_layer_ring<DIR, U, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), lds, s, m, \
+                         q, d, g, f, a, copy_wgs, fill_wgs);                                                      \
+    break;
+  switch (L.unroll) {
+    TUTTI_RING_CASE(1)
+    TUTTI_RING_CASE(2)
+    TUTTI_RING_CASE(4)
+    TUTTI_RING_CASE(8)
+    default:
+      return TUTTI_EINVAL;
+  }
+#undef TUTTI_RING_CASE
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, s, g);
+  e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+}  // namespace
+}  // extern "C++"
+
+int tutti_retrieve_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                         const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                         const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                         uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store,
+                         tutti_extent *d_extents, uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status,
+                         void *stream) {
+  return ring_layer_entry<kUnpack>(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len,
+                                   d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget,
+                                   d_status, stream);
+}
+
+int tutti_store_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                      const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                      const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
+                      uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
+                      uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  return ring_layer_entry<kPack>(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len,
+                                 d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget,
+                                 d_status, stream);
 }
 
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream) {

@@ -367,22 +367,21 @@ struct RingArgs {
   uint32_t n_slots;
 };
 
-// Contexts of one layer dealt into IOCBs (see emit_direct_sqes for the entry itself), plus the headers.
-__global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, const SqeArgs a, const DirectArgs d,
-                                                           const tutti_extent *__restrict__ ext, uint32_t n_req) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const ReqLds l = carve_lds(smem, n_req);
-  lds_from_extents(ext, n_req, l);
+// Contexts of one layer dealt into IOCBs (see emit_direct_sqes for the entry itself), plus the headers, by the
+// `n_wgs` workgroups starting at workgroup `first_wg`.
+__device__ __forceinline__ void emit_iocbs(const RingArgs g, const SqeArgs a, const DirectArgs d, const ReqLds l,
+                                           uint32_t n_req, uint32_t first_wg, uint32_t n_wgs) {
   const uint64_t n_ctx = 2ull * l.table_off[n_req];
   const uint64_t cap = static_cast<uint64_t>(g.n_slots) * TUTTI_IOCB_SLOTS;
   const uint64_t n_fill = n_ctx < cap ? n_ctx : cap;
-  const uint64_t tid = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const uint64_t tid = static_cast<uint64_t>(blockIdx.x - first_wg) * blockDim.x + threadIdx.x;
   if (n_ctx > cap && tid == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
-  if (tid < g.n_slots) {  // one thread per IOCB header
-    const uint64_t lo = tid * TUTTI_IOCB_SLOTS;
+  const uint64_t stride = static_cast<uint64_t>(n_wgs) * blockDim.x;
+  for (uint64_t b = tid; b < g.n_slots; b += stride) {  // one thread per IOCB header
+    const uint64_t lo = b * TUTTI_IOCB_SLOTS;
     uint64_t cnt = n_fill > lo ? n_fill - lo : 0;
     if (cnt > TUTTI_IOCB_SLOTS) cnt = TUTTI_IOCB_SLOTS;
-    tutti_iocb_hdr *h = &g.sq[(g.first_slot + tid) % g.depth].hdr;
+    tutti_iocb_hdr *h = &g.sq[(g.first_slot + b) % g.depth].hdr;
     h->num_ioctx = static_cast<uint32_t>(cnt);
     h->state = TUTTI_IOCB_FILLED;
     h->done = 0;
@@ -390,7 +389,6 @@ __global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, cons
     h->opcode = a.opcode;
   }
   const uint64_t n_quarters = 4ull * n_fill;
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
   for (uint64_t q = tid; q < n_quarters; q += stride) {
     const uint32_t i = static_cast<uint32_t>(q >> 2);
     const uint32_t part = static_cast<uint32_t>(q & 3);
@@ -400,6 +398,14 @@ __global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, cons
     tutti_iocb *io = &g.sq[(g.first_slot + i / TUTTI_IOCB_SLOTS) % g.depth];
     reinterpret_cast<u32x4 *>(&io->ioctx[i % TUTTI_IOCB_SLOTS])[part] = w;
   }
+}
+
+__global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, const SqeArgs a, const DirectArgs d,
+                                                           const tutti_extent *__restrict__ ext, uint32_t n_req) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, n_req);
+  lds_from_extents(ext, n_req, l);
+  emit_iocbs(g, a, d, l, n_req, 0, gridDim.x);
 }
 
 struct IoArgs {
@@ -554,7 +560,17 @@ struct MoveArgs {
   // dispatcher deals round-robin to the 8 XCDs, take neighbouring 16 KiB); 1 = each XCD takes one
   // contiguous eighth of the copy workgroups' items
   uint32_t xcd_contiguous;
+  // direct-to-block mode (the rings' one-launch layer path): `stage` is the base of the file store, the
+  // per-request staging offsets in LDS hold the start of each request's file in it (kNoFile if the store has no
+  // such file), and the object side of (request, kind, block j) is the file offset of the context that
+  // emit_iocbs records for it; only the first ctx_cap contexts were recorded and are executed
+  uint32_t direct;
+  uint32_t layer;
+  uint64_t file_stride;
+  uint64_t ctx_cap;
 };
+
+constexpr uint64_t kNoFile = ~0ull;
 
 // The workgroup index used for item numbering (see MoveArgs::xcd_contiguous).
 __device__ __forceinline__ uint32_t item_wg(const MoveArgs &a, uint32_t copy_wgs) {
@@ -582,6 +598,7 @@ __device__ __forceinline__ uint32_t hnd_offset(uint32_t o, uint32_t row_bytes, u
 // block-table entry names the pool side.
 struct Item {
   unsigned char *obj_ptr;  // start of the (request, kind) object; nullptr = skip the item
+  unsigned char *obj_blk;  // where block j of it sits on the object side
   uint64_t obj_bytes;
   uint32_t tab_idx;        // index into the block table
   uint32_t n;              // blocks of the request
@@ -605,7 +622,22 @@ __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, 
   d.obj_bytes = l.obj_bytes[r];
   d.tab_idx = toff + d.j;
   const uint64_t stage_off = l.stage_off[r];
+  if (a.direct) {
+    // same arithmetic as the context's file offset (direct_entry_quarter), then the I/O kernel's checks
+    const uint64_t file_off = (2ull * a.layer + d.kind) * d.obj_bytes + static_cast<uint64_t>(d.j) * a.block_bytes;
+    const uint64_t end = file_off + a.block_bytes;
+    d.obj_ptr = a.stage;
+    d.obj_blk = a.stage + stage_off + file_off;
+    if (u >= a.ctx_cap) {
+      d.obj_ptr = nullptr;  // beyond the IOCBs the caller gave: not recorded, not executed
+    } else if (stage_off == kNoFile || end > a.file_stride || end < file_off) {
+      if (lane == 0 && d.s == 0 && a.status) atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
+      d.obj_ptr = nullptr;
+    }
+    return d;
+  }
   d.obj_ptr = a.stage + stage_off + d.kind * d.obj_bytes;
+  d.obj_blk = d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes;
   const uint64_t end = stage_off + 2 * d.obj_bytes;
   if (end > a.stage_cap || end < stage_off) {  // the request's objects do not fit: skip it, report once
     if (lane == 0 && d.j == 0 && d.s == 0 && d.kind == 0 && a.status) atomicOr(a.status, TUTTI_ST_STAGE_CAP);
@@ -637,7 +669,7 @@ __device__ __forceinline__ void move_one(const MoveArgs &a, const Item &d, uint3
   const uint32_t in_blk = d.s * kSlice;  // first byte of the slice inside the block
   if (id < a.num_blocks) {
     unsigned char *blk_ptr = (d.kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
-    unsigned char *obj_blk = d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes;
+    unsigned char *obj_blk = d.obj_blk;
     const uint32_t o0 = in_blk + lane * 16u;  // this lane's first 16 bytes, canonical offset in the block
     if (in_blk + kSlice <= a.block_bytes) {
       // whole slice inside the block: U independent loads in flight, then U stores
@@ -674,7 +706,7 @@ __device__ __forceinline__ void move_one(const MoveArgs &a, const Item &d, uint3
   } else if (lane == 0 && d.s == 0 && a.status) {
     atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
   }
-  if (DIR == kPack && d.j + 1 == d.n && d.s + 1 == a.slices_per_block) {
+  if (DIR == kPack && !a.direct && d.j + 1 == d.n && d.s + 1 == a.slices_per_block) {
     // zero the tail of the object up to its aligned size (fewer than `align` bytes)
     const uint64_t used = static_cast<uint64_t>(d.n) * a.block_bytes;
     const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -915,6 +947,42 @@ __global__ __launch_bounds__(WG) void k_layer(const MoveArgs m, const SqeArgs q,
   const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
   if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
   if (blockIdx.x < copy_wgs) move_items<DIR, HND, U, NT>(m, l, a.n_req, copy_wgs, pre);
+}
+
+// retrieve_layer / store_layer through the rings in one launch (direct-to-block mode): scan, then the start
+// of every request's file in the store goes where the staging offsets were, then the last `fill_wgs`
+// workgroups record the layer's contexts in the IOCBs while the first `copy_wgs` move the very same blocks,
+// each item deriving its file offset and block from the extents and the table exactly as its context does.
+// Blocks go to the file as they sit in the pool (a descriptor names raw bytes), so there is no head-major case.
+struct FileArgs {
+  uint64_t file_stride;
+  uint32_t first_file_id;
+  uint32_t n_files;
+};
+
+template <int DIR, int U, int WG>
+__global__ __launch_bounds__(WG) void k_layer_ring(const MoveArgs m, const SqeArgs q, const DirectArgs d,
+                                                    const RingArgs g, const FileArgs f, const LayoutArgs a,
+                                                    uint32_t copy_wgs, uint32_t fill_wgs) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const ReqLds l = carve_lds(smem, a.n_req);
+  if (threadIdx.x < kWave) {
+    const bool publish = blockIdx.x + 1 == gridDim.x;
+    wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
+                      publish ? a.totals : nullptr);
+  }
+  __syncthreads();
+  for (uint32_t r = threadIdx.x; r < a.n_req; r += blockDim.x) {
+    const uint32_t fid = q.file_id[r];
+    const uint32_t rel = fid - f.first_file_id;
+    l.stage_off[r] = (fid >= f.first_file_id && rel < f.n_files) ? static_cast<uint64_t>(rel) * f.file_stride : kNoFile;
+  }
+  __syncthreads();
+  const uint32_t first_fill_wg = gridDim.x - fill_wgs;
+  if (blockIdx.x >= first_fill_wg) emit_iocbs(g, q, d, l, a.n_req, first_fill_wg, fill_wgs);
+  Preload<U> pre;
+  pre.valid = false;
+  if (blockIdx.x < copy_wgs) move_items<DIR, false, U, 3>(m, l, a.n_req, copy_wgs, pre);
 }
 
 template <int DIR, int PT, int WG>

@@ -328,3 +328,61 @@ def check_rings(orc, c, layer, opcode, depth, first_slot, n_slots, cu_budget=0, 
     done_slots = {int(x) for x in o_cq[16:16 + min(n_done, depth)]}
     assert flags.cpu().tolist() == [1 if s in done_slots else 0 for s in range(depth)]
     return n_done
+
+
+def check_ring_layer(orc, c, layer, write, depth, first_slot, n_slots, cu_budget=0, first_file_id=1000, n_files=None,
+                     stride_cut=0, seed=5, prefill=False):
+    """retrieve_layer / store_layer through the rings in one call, device against oracle: same inputs, every
+    output compared (extents, totals, status, planes, file store, IOCBs, completion queue, wait_cqe flags).
+    prefill: the ring already holds completions of an earlier call (the CQ tail is not 0)."""
+    assert c.bb % c.align == 0
+    o_ext0, _ = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    file_stride = max(16, int(2 * c.L * (int(o_ext0["obj_bytes"].max()) if c.n_req else 0)) - stride_cut)
+    n_files = max(1, c.n_req) if n_files is None else n_files
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    store = torch.randint(0, 256, (n_files * file_stride,), dtype=torch.uint8, device=DEV, generator=g)
+    o_store = store.cpu().numpy().copy()
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    table_addr = 0x7f00_0000_1000                    # only recorded in the contexts: the same value on both sides
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=DEV)
+    ring = B.make_ring(sq, cq, depth)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    B.tutti_ring_init(ring)
+    orc.ring_init(o_sq, o_cq)
+    fs = B.make_filestore(store, file_stride, first_file_id, n_files)
+    ext = torch.zeros(max(1, c.n_req) * 32, dtype=torch.uint8, device=DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=DEV)
+    fn = B.tutti_store_layer if write else B.tutti_retrieve_layer
+    o_fn = orc.store_layer if write else orc.retrieve_layer
+    calls = [(0, min(1, depth), (layer + 1) % c.L)] if prefill else []
+    calls.append((first_slot, n_slots, layer))
+    for (fslot, ns, lay) in calls:
+        st = new_status()
+        fn(ring, fslot, ns, c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size,
+           c.d_file_id, lay, table_addr, 5, fs, ext, tot, cu_budget, st)
+        o_ext, o_tot, o_st = o_fn(o_sq, o_cq, fslot, ns, c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks, c.table,
+                                  c.file_id, lay, table_addr, 5, o_store, file_stride, first_file_id, n_files)
+        torch.cuda.synchronize()
+        assert int(st.item()) == o_st, f"{c.name}: status {int(st.item())} vs oracle {o_st}"
+    flags = torch.full((depth,), 9, dtype=torch.int32, device=DEV)
+    for slot in range(depth):
+        B.tutti_wait_cqe(ring, slot, flags[slot:])
+    torch.cuda.synchronize()
+    assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes(), f"{c.name}: extents differ"
+    assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot), f"{c.name}: totals differ"
+    gk, gv = k2.cpu().numpy(), v2.cpu().numpy()
+    assert np.array_equal(gk, ok), f"{c.name}: K plane differs at byte {first_diff(gk, ok)}"
+    assert np.array_equal(gv, ov), f"{c.name}: V plane differs at byte {first_diff(gv, ov)}"
+    gs = store.cpu().numpy()
+    assert np.array_equal(gs, o_store), f"{c.name}: file store differs at byte {first_diff(gs, o_store)}"
+    assert sq.cpu().numpy().tobytes() == o_sq.tobytes(), f"{c.name}: IOCBs differ"
+    assert cq.cpu().numpy().tobytes() == o_cq.tobytes(), f"{c.name}: completion queue differs"
+    done = o_sq["hdr"]["state"] == orc.IOCB_DONE
+    assert flags.cpu().tolist() == [1 if x else 0 for x in done]
+    if write:
+        assert np.array_equal(gk, c.k_host) and np.array_equal(gv, c.v_host)
+    return o_st

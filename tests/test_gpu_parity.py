@@ -405,6 +405,64 @@ def test_rings_cfg2_layer(orc, H):
         assert H.check_rings(orc, c, layer=31, opcode=op, depth=4, first_slot=3, n_slots=2) == 2
 
 
+def test_ring_layer_small(orc, H):
+    """retrieve_layer / store_layer in one call against the oracle's layout + fill + issue sequence."""
+    say("ring layer: small")
+    rng = np.random.default_rng(43)
+    nb = [1500, 0, 1000]
+    N = 2600
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=4096, L=3,
+                    name="ringlayer5000")
+    for write in (False, True):
+        assert H.check_ring_layer(orc, c, layer=1, write=write, depth=8, first_slot=6, n_slots=4) == 0
+        assert H.check_ring_layer(orc, c, layer=2, write=write, depth=8, first_slot=0, n_slots=2) == B.ST_SQE_CAP
+        assert H.check_ring_layer(orc, c, layer=0, write=write, depth=4, first_slot=3, n_slots=3, cu_budget=2) == 0
+        assert H.check_ring_layer(orc, c, layer=0, write=write, depth=4, first_slot=1, n_slots=3, cu_budget=1) == 0
+        H.check_ring_layer(orc, c, layer=0, write=write, depth=4, first_slot=1, n_slots=3, prefill=True)
+        # unknown file ids, files too short, no IOCBs at all: skipped and reported
+        assert H.check_ring_layer(orc, c, layer=0, write=write, depth=4, first_slot=0, n_slots=3,
+                                  first_file_id=1001) == B.ST_BAD_BLOCK
+        assert H.check_ring_layer(orc, c, layer=0, write=write, depth=4, first_slot=0, n_slots=3, n_files=2) == B.ST_BAD_BLOCK
+        assert H.check_ring_layer(orc, c, layer=2, write=write, depth=4, first_slot=0, n_slots=3,
+                                  stride_cut=4096) == B.ST_BAD_BLOCK
+        assert H.check_ring_layer(orc, c, layer=1, write=write, depth=4, first_slot=2, n_slots=0) == B.ST_SQE_CAP
+    H.check_rings(orc, c, layer=0, opcode=B.OP_READ, depth=4, first_slot=0, n_slots=0)
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[4, 2], table=[3, 999, 5, 16, 7, 1], chunk=4096,
+                    name="ringlayer_bad")
+    for write in (False, True):
+        assert H.check_ring_layer(orc, c, layer=0, write=write, depth=2, first_slot=1, n_slots=1) == B.ST_BAD_BLOCK
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[0], table=[], chunk=4096, name="ringlayer_empty")
+    assert H.check_ring_layer(orc, c, layer=0, write=False, depth=2, first_slot=0, n_slots=2) == 0
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[], table=[], chunk=4096, name="ringlayer_noreq")
+    assert H.check_ring_layer(orc, c, layer=0, write=True, depth=2, first_slot=1, n_slots=1) == 0
+    # strided pool, 128 KiB blocks, head-major pool (blocks travel as raw bytes), unroll 1 and 2 (ragged slices)
+    for layout in (0, 1):
+        c = H.LayerCase(T=64, h=8, d=128, e=2, N=64, n_blocks=[9, 20], table=rng.permutation(64)[:29], chunk=131072,
+                        L=2, pad=4096, layout=layout, name=f"ringlayer_128K_{layout}")
+        for write in (False, True):
+            H.check_ring_layer(orc, c, layer=1, write=write, depth=3, first_slot=2, n_slots=1)
+            H.check_ring_layer(orc, c, layer=1, write=write, depth=3, first_slot=2, n_slots=1, cu_budget=4)
+    c = H.LayerCase(T=3, h=2, d=256, e=2, N=40, n_blocks=[11, 5], table=rng.permutation(40)[:16], align=1024,
+                    chunk=3072, L=2, name="ringlayer_3K")
+    try:
+        for u in (1, 2, 8):
+            B.tutti_set_tuning(0, u)
+            for write in (False, True):
+                H.check_ring_layer(orc, c, layer=1, write=write, depth=2, first_slot=0, n_slots=1)
+    finally:
+        B.tutti_set_tuning(0, 0)
+
+
+def test_ring_layer_cfg2(orc, H):
+    """Config 2's layer through the rings in one call: 4096 contexts = two full IOCBs."""
+    w = W.llama8b_32k(num_blocks=8192)
+    say("ring layer: config 2 layer")
+    c = H.LayerCase.from_workload(w)
+    c.chunk = c.bb
+    for write in (False, True):
+        assert H.check_ring_layer(orc, c, layer=31, write=write, depth=4, first_slot=3, n_slots=2) == 0
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_no_requests_and_empty_requests(orc, H):

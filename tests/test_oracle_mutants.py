@@ -87,8 +87,8 @@ MUTANTS = {
     "io_file_bound": ("s->file_off + s->len > store->file_stride) {", "s->file_off > store->file_stride) {"),
     "save_builds_read": ("ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);",
                          "ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);"),
-    "save_unpacks": ("  return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* ---",
-                     "  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* ---"),
+    "save_unpacks": ("  return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* retrieve_layer",
+                     "  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* retrieve_layer"),
     "ring_layer_planes_swapped": ("(uint64_t)(uintptr_t)pool->k_base, (uint64_t)(uintptr_t)pool->v_base, sgl_id, table,",
                                   "(uint64_t)(uintptr_t)pool->v_base, (uint64_t)(uintptr_t)pool->k_base, sgl_id, table,"),
     "retrieve_layer_writes": ("return ring_layer(ORC_OP_READ, sq,", "return ring_layer(ORC_OP_WRITE, sq,"),
