@@ -191,8 +191,10 @@ int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, cons
 
 /* ---- submission / completion rings (sec. 3.2 "Zero-Copy Ring Buffers" and "Async I/O Processing").
  * An SQ entry is an IOCB: a 64-byte header followed by 2048 I/O contexts (tutti_sqe records); the CQ
- * collects the indices of completed IOCBs.  Rings live in caller-allocated DEVICE memory (the paper maps
- * them to the CPU so that it can fill them; here the GPU fills them itself, so no mapping is needed).
+ * collects the indices of completed IOCBs.  Rings live in caller-allocated device-accessible memory (the paper maps
+ * them to the CPU so that it can fill them; here the GPU fills them itself, so no mapping is needed).  Device
+ * memory is the normal choice; a CQ (or a whole ring) in pinned host memory also works, and the CPU can then poll
+ * the CQ tail without synchronising the stream: completions are published with system-scope release stores.
  * The header layout, the CQ layout and the file store that stands in for the SSD are this repository's. */
 #define TUTTI_IOCB_FREE 0u
 #define TUTTI_IOCB_FILLED 1u

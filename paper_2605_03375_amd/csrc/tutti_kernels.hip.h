@@ -491,20 +491,38 @@ __global__ __launch_bounds__(WG) void k_issue_io(const RingArgs g, const IoArgs 
 
 // Completion of the IOCBs an I/O kernel has just executed (stream order puts this after all its stores):
 // FILLED -> DONE, done = num_ioctx, index appended to the CQ in slot order.  One wavefront; the CQ tail is
-// only ever advanced here, so no atomics are needed within a stream.
+// only ever advanced here, so no read-modify-write atomics are needed within a stream.  The state and the tail are published
+// with system-scope release stores, so a ring (or just its CQ) placed in pinned host memory can be polled by
+// the CPU while the stream runs on: whoever sees the new tail also sees the entries before it.
 __global__ __launch_bounds__(kWave) void k_complete(const RingArgs g) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  if (blockIdx.x != 0) return;
+  const uint32_t lane = threadIdx.x;
   uint32_t *cq_entry = reinterpret_cast<uint32_t *>(g.cq + 1);
-  uint32_t tail = g.cq->tail;
-  for (uint32_t b = 0; b < g.n_slots; ++b) {
-    tutti_iocb_hdr *h = &g.sq[(g.first_slot + b) % g.depth].hdr;
-    if (h->state != TUTTI_IOCB_FILLED) continue;
-    h->done = h->num_ioctx;
-    cq_entry[tail % g.depth] = h->iocb_idx;
-    tail += 1;
-    __hip_atomic_store(&h->state, TUTTI_IOCB_DONE, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  uint32_t tail = g.cq->tail;  // every lane reads the same word
+  // one lane per IOCB, 64 per pass (the host checked n_slots <= depth, so the slots are distinct): the header
+  // loads of a pass are in flight together, and a ballot gives each executed IOCB its place in the queue
+  for (uint32_t base = 0; base < g.n_slots; base += kWave) {
+    const uint32_t b = base + lane;
+    tutti_iocb_hdr *h = nullptr;
+    uint32_t num = 0, idx = 0;
+    bool live = false;
+    if (b < g.n_slots) {
+      h = &g.sq[(g.first_slot + b) % g.depth].hdr;
+      live = h->state == TUTTI_IOCB_FILLED;
+      num = h->num_ioctx;
+      idx = h->iocb_idx;
+    }
+    const uint64_t mask = __ballot(live);
+    const uint32_t before = static_cast<uint32_t>(__popcll(mask & ((1ull << lane) - 1ull)));
+    if (live) {
+      h->done = num;
+      cq_entry[(tail + before) % g.depth] = idx;
+      __hip_atomic_store(&h->state, TUTTI_IOCB_DONE, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    tail += static_cast<uint32_t>(__popcll(mask));
   }
-  __hip_atomic_store(&g.cq->tail, tail, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();  // the other lanes' queue entries happen before lane 0's release of the tail
+  if (lane == 0) __hip_atomic_store(&g.cq->tail, tail, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 __global__ void k_cq_check(const tutti_iocb *sq, uint32_t slot, uint32_t *flag) {

@@ -453,6 +453,56 @@ def test_ring_layer_small(orc, H):
         B.tutti_set_tuning(0, 0)
 
 
+def test_ring_cq_in_pinned_host_memory_polled_by_cpu(orc, H):
+    """wait_cqe from the host: the completion queue sits in pinned host memory and the CPU polls its tail while
+    the stream runs on (no synchronisation before the poll); what it then reads must be the oracle's queue."""
+    import time
+    say("rings: CQ in pinned host memory")
+    rng = np.random.default_rng(47)
+    nb = [700, 900]
+    N = 2000
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=4096, L=4,
+                    name="ring_hostcq")
+    depth, n_slots = 8, 2
+    o_ext0, _ = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    file_stride = int(2 * c.L * int(o_ext0["obj_bytes"].max()))
+    store = torch.randint(0, 256, (2 * file_stride,), dtype=torch.uint8, device=H.DEV)
+    o_store = store.cpu().numpy().copy()
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=H.DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8).pin_memory()
+    cq_words = cq.numpy().view(np.uint32)                      # the CPU's view of the same bytes
+    ring = B.make_ring(sq, cq, depth)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    B.tutti_ring_init(ring)
+    orc.ring_init(o_sq, o_cq)
+    torch.cuda.synchronize()
+    assert cq_words.tobytes() == o_cq.tobytes()
+    fs = B.make_filestore(store, file_stride, 1000, 2)
+    ext = torch.zeros(c.n_req * 32, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    st = H.new_status()
+    addr = 0x7f00_0000_2000
+    for layer in range(c.L):                                   # four layers, two IOCBs each: the ring of 8 fills up
+        B.tutti_retrieve_layer(ring, layer * n_slots, n_slots, c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req,
+                               c.d_table, c.table.size, c.d_file_id, layer, addr, 5, fs, ext, tot, 0, st)
+    deadline = time.monotonic() + 20.0
+    while int(cq_words[0]) < c.L * n_slots and time.monotonic() < deadline:
+        pass
+    seen = int(cq_words[0])
+    entries = [int(x) for x in cq_words[16:16 + depth]]       # read BEFORE any synchronisation
+    torch.cuda.synchronize()
+    assert seen == c.L * n_slots, f"the CPU saw {seen} completions before the deadline"
+    for layer in range(c.L):
+        orc.retrieve_layer(o_sq, o_cq, layer * n_slots, n_slots, c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks,
+                           c.table, c.file_id, layer, addr, 5, o_store, file_stride, 1000, 2)
+    assert entries == [int(x) for x in o_cq[16:16 + depth]] == list(range(depth))
+    assert cq_words.tobytes() == o_cq.tobytes() and sq.cpu().numpy().tobytes() == o_sq.tobytes()
+    assert np.array_equal(k2.cpu().numpy(), ok) and np.array_equal(v2.cpu().numpy(), ov) and int(st.item()) == 0
+
+
 def test_ring_layer_cfg2(orc, H):
     """Config 2's layer through the rings in one call: 4096 contexts = two full IOCBs."""
     w = W.llama8b_32k(num_blocks=8192)
