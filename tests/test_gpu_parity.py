@@ -503,6 +503,74 @@ def test_ring_cq_in_pinned_host_memory_polled_by_cpu(orc, H):
     assert np.array_equal(k2.cpu().numpy(), ok) and np.array_equal(v2.cpu().numpy(), ov) and int(st.item()) == 0
 
 
+def test_rings_deferred_writes_flushed_in_pieces(orc, H):
+    """Sec. 3.3: pending writes stay recorded in the SQ while the critical-path reads go first, then are issued a
+    few IOCBs at a time under a CU budget.  Same call sequence on both sides; every output compared."""
+    say("rings: deferred writes")
+    rng = np.random.default_rng(53)
+    nb = [1300, 500]
+    N = 2400
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=4096, L=4,
+                    name="ring_deferred")
+    depth = 8
+    o_ext, _ = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    ext, _ = H.gpu_layout(c)
+    file_stride = int(2 * c.L * int(o_ext["obj_bytes"].max()))
+    store = torch.randint(0, 256, (2 * file_stride,), dtype=torch.uint8, device=H.DEV)
+    o_store = store.cpu().numpy().copy()
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    nd = 2 * N
+    sgl = torch.zeros(nd * 16, dtype=torch.uint8, device=H.DEV)
+    B.tutti_sgl_table_build(c.gpu_pool(k2, v2), k2.data_ptr(), v2.data_ptr(), 5, sgl, nd)
+    o_sgl, _ = orc.sgl_table_build(c.orc_pool(orc, ok, ov), ok.ctypes.data, ov.ctypes.data, 5)
+    addr = sgl.data_ptr()
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=H.DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=H.DEV)
+    ring = B.make_ring(sq, cq, depth)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    B.tutti_ring_init(ring)
+    orc.ring_init(o_sq, o_cq)
+    fs = B.make_filestore(store, file_stride, 1000, 2)
+    st = H.new_status()
+    o_st = 0
+    gp, op_, gc, oc_ = c.gpu_pool(k2, v2), c.orc_pool(orc, ok, ov), c.gpu_cfg(), c.orc_cfg(orc)
+
+    def same(what):
+        torch.cuda.synchronize()
+        assert sq.cpu().numpy().tobytes() == o_sq.tobytes(), f"IOCBs differ after {what}"
+        assert cq.cpu().numpy().tobytes() == o_cq.tobytes(), f"completion queue differs after {what}"
+        assert np.array_equal(store.cpu().numpy(), o_store), f"file store differs after {what}"
+        assert np.array_equal(k2.cpu().numpy(), ok) and np.array_equal(v2.cpu().numpy(), ov), f"pool differs after {what}"
+        assert int(st.item()) == o_st
+
+    # writes of layers 0..2 recorded, not issued: slots 0..5 stay FILLED
+    for layer in range(3):
+        B.tutti_iocb_fill_direct(ring, 2 * layer, 2, gp, gc, ext, c.n_req, c.d_table, c.table.size, c.d_file_id, layer,
+                                 B.OP_WRITE, addr, 5, st)
+        o_st |= orc.iocb_fill_direct(o_sq, 2 * layer, 2, op_, oc_, o_ext, c.table, c.file_id, layer, orc.OP_WRITE, addr, 5)
+    same("recording the writes")
+    assert list(o_sq["hdr"]["state"][:6]) == [orc.IOCB_FILLED] * 6 and int(o_cq[0]) == 0
+    # the read of layer 3 goes first, through the two free slots; it overwrites the blocks the writes will save
+    e2 = torch.zeros(c.n_req * 32, dtype=torch.uint8, device=H.DEV)
+    t2 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    B.tutti_retrieve_layer(ring, 6, 2, gp, gc, c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id, 3, addr, 5,
+                           fs, e2, t2, 0, st)
+    _, _, s_ = orc.retrieve_layer(o_sq, o_cq, 6, 2, op_, oc_, c.n_blocks, c.table, c.file_id, 3, addr, 5, o_store,
+                                  file_stride, 1000, 2)
+    o_st |= s_
+    same("the read")
+    assert int(o_cq[0]) == 2 and list(o_cq[16:18]) == [6, 7]
+    # the pending writes, flushed in pieces of 1, 3 and 2 IOCBs under different budgets
+    for first, n, budget in ((0, 1, 2), (1, 3, 4), (4, 2, 0)):
+        B.tutti_issue_io(ring, first, n, sgl, nd, addr, fs, c.bb, budget, st)
+        o_st |= orc.issue_io(o_sq, o_cq, first, n, o_sgl, addr, o_store, file_stride, 1000, 2)
+        same(f"flushing {n} IOCBs from slot {first}")
+    assert int(o_cq[0]) == 8 and list(o_cq[16:24]) == [6, 7, 0, 1, 2, 3, 4, 5]
+    assert np.all(o_sq["hdr"]["state"] == orc.IOCB_DONE) and o_st == 0
+
+
 def test_ring_layer_cfg2(orc, H):
     """Config 2's layer through the rings in one call: 4096 contexts = two full IOCBs."""
     w = W.llama8b_32k(num_blocks=8192)
