@@ -251,6 +251,7 @@ def main():
         out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], pristine, stages[0], geom, payload_layer)
     if args.scatter_sweep:
         out["scatter_sweep"] = scatter_sweep(torch, B, stages, payload_layer, dev)
+        out["scatter_orders_32KiB"] = scatter_orders(torch, B, stages, payload_layer, dev)
     if args.rings:
         out["rings_direct_to_block"] = ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid,
                                                 payload_layer, dev)
@@ -516,6 +517,57 @@ def scatter_sweep(torch, B, stages, nbytes, dev, span=2 << 30, n_buf=6, reps=3):
         res[str(gran)] = row
         log(f"[bench] scatter sweep gran {gran}: {row}")
         gran *= 2
+    return res
+
+
+def scatter_orders(torch, B, stages, nbytes, dev, gran=32768, span=4 << 30, n_buf=4, reps=5):
+    """Does the ORDER in which scattered 32 KiB pieces are visited matter?  The same random set of pieces visited
+    at random, ascending, or dealt round-robin over the residues of the piece index mod M (so that pieces in flight
+    together differ in the address bits just above the piece size), and regular strides for comparison."""
+    rng = np.random.default_rng(1)
+    n = nbytes // gran
+    slots = span // gran
+    ids = rng.permutation(slots)[:n]
+
+    def dealt(M):
+        buckets = [list(ids[ids % M == r]) for r in range(M)]
+        out = []
+        while any(buckets):
+            for b in buckets:
+                if b:
+                    out.append(b.pop())
+        return np.array(out)
+
+    orders = {"random": ids, "ascending": np.sort(ids), "contiguous": np.arange(n)}
+    for S in (2, 32, 1024):
+        orders[f"stride_{S}_pieces"] = (np.arange(n) * S) % slots + (np.arange(n) * S) // slots
+    for M in (8, 32, 256):
+        orders[f"dealt_mod_{M}"] = dealt(M)
+    bufs = [torch.empty(span, dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    scratch = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(4)]
+    res = {}
+    for name, p in orders.items():
+        assert len(set(p.tolist())) == n and int(p.max()) < slots
+        d_perm = torch.from_numpy(p.astype(np.uint32).view(np.int32)).to(dev)
+        row = {}
+        for label, wr in (("writes_us", 1), ("reads_us", 0)):
+            def run():
+                for i in range(len(stages)):
+                    B.tutti_scatter_baseline(bufs[i % n_buf], span, scratch[i % 4] if not wr else stages[i], nbytes,
+                                             d_perm, gran, wr)
+            run()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                run()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) * 1e3 / len(stages))
+            row[label] = round(median(ts), 2)
+        res[name] = row
+        log(f"[bench] scatter order {name}: {row}")
     return res
 
 
