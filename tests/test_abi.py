@@ -155,6 +155,25 @@ def test_null_and_misaligned_pointers_are_einval():
     _expect(B.EINVAL, B.tutti_issue_io, ring, 0, 1, FAKE, 4, 0, B.make_filestore(FAKE, 4100, 0, 1), 4096)
     _expect(B.EINVAL, B.tutti_issue_io, ring, 0, 1, FAKE, 4, 0, fs, 0)
     _expect(B.EINVAL, B.tutti_issue_io, ring, 0, 1, 0, 4, 0, fs, 4096)
+    for one_call in (B.tutti_retrieve_layer, B.tutti_store_layer):
+        ok = (p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, FAKE)
+        _expect(B.EINVAL, one_call, B.make_ring(0, FAKE, 4), 0, 1, *ok)                                   # no SQ
+        _expect(B.EINVAL, one_call, ring, 4, 1, *ok)                                                      # slot
+        _expect(B.EINVAL, one_call, ring, 0, 5, *ok)                                                      # n_slots
+        _expect(B.EINVAL, one_call, ring, 0, 1, odd, *ok[1:])                                             # block % align
+        _expect(B.EINVAL, one_call, ring, 0, 1, B.make_pool(0, FAKE, **GOOD), *ok[1:])                    # no K plane
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, 0, 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, FAKE)     # n_blocks
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, 0, 1, FAKE, 0, 0, 0, fs, FAKE, FAKE)     # table
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, 0, 0, 0, 0, fs, FAKE, FAKE)     # file ids
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 2, 0, 0, fs, FAKE, FAKE)  # layer
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 8, 0, fs, FAKE, FAKE)  # table addr
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0,
+                B.make_filestore(0, 4096, 0, 1), FAKE, FAKE)
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0,
+                B.make_filestore(FAKE, 4100, 0, 1), FAKE, FAKE)
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0, fs, 0, FAKE)     # extents
+        _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, 0)     # totals
+        _expect(B.ERANGE, one_call, ring, 0, 1, p, cfg, FAKE, B.MAX_REQ + 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, FAKE)
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 4, FAKE)
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 0, 0)
     _expect(B.EINVAL, B.tutti_copy_baseline, FAKE, FAKE, 24)
