@@ -243,6 +243,7 @@ def main():
         out["sqe"]["direct_to_block_2M_entries"] = big_entry_rate(torch, B, dev)
         log(f"[bench] copy ceiling {out['copy_ceiling']}; entries {out['sqe']}")
     if args.corun:
+        out["per_cu_limits"] = per_cu_limits(torch, B, dev)
         out["corun"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev)
         # a GEMM with many more tiles than CUs, for contrast with the 4096^3 one (256 tiles on 256 CUs)
         out["corun_gemm8192"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=12, reps=2,
@@ -696,6 +697,38 @@ def big_entry_rate(torch, B, dev, n_req=2048, blocks_per_req=512, reps=20):
     return {"requests": n_req, "entries": n_sqe, "us_per_launch": round(us, 2),
             "sqes_per_s": round(n_sqe / (us * 1e-6), 0), "entry_write_GBps": round(64 * n_sqe / (us * 1e-6) / 1e9, 1),
             "regime": "HBM-write bound (64 B written per entry, 4 B of table read)"}
+
+
+def per_cu_limits(torch, B, dev, nbytes=256 << 20, budgets=(8, 32, 128, 0), reps=3, n_buf=4):
+    """What B compute units (0 = the chip) move when they only read, only write, or copy: GB/s of memory traffic,
+    in total and per budgeted CU.  The budgeted restore is compared with the copy line."""
+    src = [torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 256) for _ in range(n_buf)]
+    dst = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    acc = torch.zeros(4 * B.STREAM_SLOTS, dtype=torch.int32, device=dev)
+    cus = B.tutti_cu_count()
+    res = {}
+    for budget in budgets:
+        row = {}
+        for label, traffic, fn in (("read", nbytes, lambda i: B.tutti_stream_baseline(src[i], nbytes, False, acc, budget)),
+                                   ("write", nbytes, lambda i: B.tutti_stream_baseline(dst[i], nbytes, True, None, budget)),
+                                   ("copy", 2 * nbytes, lambda i: B.tutti_copy_baseline(dst[i], src[i], nbytes, budget))):
+            for i in range(n_buf):
+                fn(i)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for i in range(n_buf):
+                    fn(i)
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) * 1e-3 / n_buf)
+            gbps = traffic / median(ts) / 1e9
+            row[label] = {"traffic_GBps": round(gbps, 1), "per_cu_GBps": round(gbps / (budget or cus), 1)}
+        res[str(budget)] = row
+        log(f"[bench] per-CU limits, budget {budget}: {row}")
+    return res
 
 
 def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, reps=3, gemm_n=4096,

@@ -298,6 +298,17 @@ int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void
  * achievable ceiling the pack/unpack rates are compared with. */
 int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream);
 
+/* ---- measurement aid: one direction only, with the copy's access and launch shape.  write = 0: read `bytes`
+ * from d_buf and xor every 16-byte unit, as four 32-bit words, into d_xor: TUTTI_STREAM_SLOTS slots of four
+ * words, which the caller zeroes first; each wavefront adds its part to one slot with atomics, so the xor over
+ * all slots is the xor of the buffer's units, and calls on one d_xor accumulate.  write != 0: fill d_buf,
+ * 16-byte unit i becoming the words { low 32 bits of i, high 32 bits of i, ~low, 0x54555454 }; d_xor is not
+ * used.  bytes a multiple of 16, d_buf 16-byte aligned.  What one compute unit (under a CU budget) or the chip
+ * reads or writes when it does nothing else: the limits the budgeted copy is compared with. */
+#define TUTTI_STREAM_SLOTS 4096u
+int tutti_stream_baseline(void *d_buf, uint64_t bytes, uint32_t write, uint32_t *d_xor, uint32_t cu_budget,
+                          void *stream);
+
 /* ---- measurement aid: the same copy with one side scattered at `gran`-byte granularity and nothing else
  * (no extents, no requests, no K/V planes): piece i of the contiguous side, i < bytes/gran, pairs with the
  * piece at d_scattered + d_perm[i]*gran.  scatter_writes != 0: contiguous -> scattered (the shape of an

@@ -17,6 +17,7 @@ _LIB = None
 OK, EINVAL, ERANGE, EHIP = 0, -1, -2, -3
 LAYOUT_NHD, LAYOUT_HND = 0, 1
 OP_READ, OP_WRITE = 1, 2
+STREAM_SLOTS = 4096
 IOCB_SLOTS = 2048
 MAX_REQ = 2048
 ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP = 1, 2, 4
@@ -38,7 +39,7 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_layer_save",
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
            "tutti_issue_io", "tutti_wait_cqe", "tutti_retrieve_layer", "tutti_store_layer",
-           "tutti_copy_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
+           "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]
 
 
@@ -118,6 +119,7 @@ def lib():
         L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
         L.tutti_layer_save.restype = C.c_int
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
+        L.tutti_stream_baseline.argtypes = [vp, u64, u32, vp, u32, vp]
         L.tutti_scatter_baseline.argtypes = [vp, u64, vp, u64, vp, u32, u32, u32, vp]
         L.tutti_scatter_baseline.restype = C.c_int
         pr, pf = C.POINTER(tutti_ring), C.POINTER(tutti_filestore)
@@ -289,6 +291,11 @@ def tutti_layer_save(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_f
                                          table_len, _p(d_file_id), layer, _p(d_stage), stage_cap, stage_addr, sgl_id,
                                          _p(d_extents), _p(d_totals), _p(d_sqe), sqe_cap, cu_budget, _p(d_status),
                                          _stream(stream)))
+
+
+def tutti_stream_baseline(d_buf, nbytes, write, d_xor=None, cu_budget=0, stream=None):
+    return _check("tutti_stream_baseline", lib().tutti_stream_baseline(_p(d_buf), nbytes, 1 if write else 0, _p(d_xor),
+                                                                       cu_budget, _stream(stream)))
 
 
 def tutti_copy_baseline(d_dst, d_src, nbytes, cu_budget=0, stream=None):

@@ -895,6 +895,38 @@ int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+int tutti_stream_baseline(void *d_buf, uint64_t bytes, uint32_t write, uint32_t *d_xor, uint32_t cu_budget,
+                          void *stream) {
+  if (!d_buf || !aligned16(d_buf) || bytes % 16 != 0) return TUTTI_EINVAL;
+  if (!write && !d_xor) return TUTTI_EINVAL;
+  if (bytes == 0) return TUTTI_OK;
+  Launch L;
+  int rc = plan_launch(cu_budget, 0, &L);
+  if (rc) return rc;
+  const uint32_t unroll = (L.unroll == 8) ? 8u : 4u;
+  const uint64_t slice = kWave * 16ull * unroll;
+  rc = plan_launch(cu_budget, (bytes + slice - 1) / slice, &L);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char *buf = static_cast<unsigned char *>(d_buf);
+#define TUTTI_STREAM(W, U)                                                                                          \
+  do {                                                                                                              \
+    if (L.wg_threads == kWgThreads)                                                                                 \
+      hipLaunchKernelGGL((k_stream<W, U, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, buf, bytes, d_xor);   \
+    else                                                                                                            \
+      hipLaunchKernelGGL((k_stream<W, U, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, buf, bytes, \
+                         d_xor);                                                                                   \
+  } while (0)
+  if (write) {
+    if (unroll == 8) TUTTI_STREAM(1, 8); else TUTTI_STREAM(1, 4);
+  } else {
+    if (unroll == 8) TUTTI_STREAM(0, 8); else TUTTI_STREAM(0, 4);
+  }
+#undef TUTTI_STREAM
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
 int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_contig, uint64_t bytes,
                            const uint32_t *d_perm, uint32_t gran, uint32_t scatter_writes, uint32_t cu_budget,
                            void *stream) {

@@ -11,6 +11,10 @@
 //   k_layer         one layer's restore (or save) in one launch: scan + entries + unpack (or pack)
 //   k_layer_lds     the same with the LDS-staged transpose
 //   k_copy          plain contiguous copy with the same access shape (measurement ceiling)
+//   k_stream        read-only or write-only stream with the same access shape (per-CU and chip limits)
+//   k_scatter       the copy with one side permuted at a given granularity (measurement floor)
+//   k_sgl_table, k_sqe_direct, k_ring_init, k_iocb_fill, k_issue_io, k_complete, k_cq_check, k_layer_ring
+//                   direct-to-block mode: mapping table, per-block entries, rings, the entry-driven I/O kernel
 //
 // Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
 // the scan), then walks work items with a persistent grid-stride loop, so the grid can be any
@@ -1042,6 +1046,65 @@ __global__ __launch_bounds__(WG) void k_copy(unsigned char *__restrict__ dst,
         const uint64_t o = o0 + k * (kWave * 16ull);
         if (o < bytes) st16<NT>(dst + o, ld16<NT>(src + o));
       }
+    }
+  }
+}
+
+// One direction only, same access shape: READ xors every 16-byte unit into four words per wavefront, added to
+// one of TUTTI_STREAM_SLOTS slots at the end, FILL writes unit i as {lo(i), hi(i), ~lo(i), tag}.  What a CU, or the chip, can read or
+// write when it does nothing else.
+constexpr uint32_t kFillTag = 0x54555454u;
+
+template <int WRITE, int U, int WG>
+__global__ __launch_bounds__(WG) void k_stream(unsigned char *__restrict__ buf, uint64_t bytes, uint32_t *__restrict__ xor4) {
+  constexpr uint64_t kSlice = kWave * 16ull * U;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * (blockDim.x / kWave);
+  const uint64_t n_items = (bytes + kSlice - 1) / kSlice;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (uint64_t it = static_cast<uint64_t>(blockIdx.x) * (blockDim.x / kWave) + threadIdx.x / kWave; it < n_items;
+       it += n_waves) {
+    const uint64_t o0 = it * kSlice + lane * 16ull;
+    const bool whole = (it + 1) * kSlice <= bytes;
+    if (WRITE) {
+#pragma unroll
+      for (int k = 0; k < U; ++k) {
+        const uint64_t o = o0 + k * (kWave * 16ull);
+        const uint64_t unit = o >> 4;
+        const u32x4 v = {static_cast<uint32_t>(unit), static_cast<uint32_t>(unit >> 32), ~static_cast<uint32_t>(unit),
+                         kFillTag};
+        if (whole || o < bytes) st16<3>(buf + o, v);
+      }
+    } else if (whole) {
+      u32x4 v[U];
+#pragma unroll
+      for (int k = 0; k < U; ++k) v[k] = ld16<3>(buf + o0 + k * (kWave * 16ull));
+#pragma unroll
+      for (int k = 0; k < U; ++k) acc ^= v[k];
+    } else {
+      for (int k = 0; k < U; ++k) {
+        const uint64_t o = o0 + k * (kWave * 16ull);
+        if (o < bytes) acc ^= ld16<3>(buf + o);
+      }
+    }
+  }
+  if (!WRITE) {
+#pragma unroll
+    for (uint32_t d = kWave / 2; d >= 1; d >>= 1) {
+      acc.x ^= __shfl_xor(acc.x, d, kWave);
+      acc.y ^= __shfl_xor(acc.y, d, kWave);
+      acc.z ^= __shfl_xor(acc.z, d, kWave);
+      acc.w ^= __shfl_xor(acc.w, d, kWave);
+    }
+    if (lane == 0) {
+      // one slot per wavefront (modulo the slot count): atomics on one address from every wavefront of the chip
+      // would take longer than the reads themselves
+      const uint32_t w = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+      uint32_t *slot = xor4 + 4u * (w % TUTTI_STREAM_SLOTS);
+      atomicXor(&slot[0], acc.x);
+      atomicXor(&slot[1], acc.y);
+      atomicXor(&slot[2], acc.z);
+      atomicXor(&slot[3], acc.w);
     }
   }
 }

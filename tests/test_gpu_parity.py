@@ -679,6 +679,34 @@ def test_copy_baseline(H):
         assert torch.equal(dst[:n], src) and not dst[n:].any()
 
 
+def test_stream_baseline(H):
+    """Read-only and write-only streams: the fill pattern and the xor of all 16-byte units, against numpy."""
+    say("stream baseline")
+    g = torch.Generator(device=H.DEV)
+    g.manual_seed(5)
+    for n in (16, 4096, (1 << 20) + 48, 9 * 8192 + 32):
+        for budget in (0, 3):
+            buf = torch.randint(0, 256, (n + 64,), dtype=torch.uint8, device=H.DEV, generator=g)
+            acc = torch.zeros(4 * B.STREAM_SLOTS, dtype=torch.int32, device=H.DEV)
+            B.tutti_stream_baseline(buf, n, False, acc, budget)
+            B.tutti_stream_baseline(buf, n, False, acc, budget)          # accumulates: twice the same gives zero
+            torch.cuda.synchronize()
+            assert not acc.any()
+            B.tutti_stream_baseline(buf, n, False, acc, budget)
+            torch.cuda.synchronize()
+            words = buf.cpu().numpy()[:n].view(np.uint32).reshape(-1, 4)
+            slots = acc.cpu().numpy().view(np.uint32).reshape(-1, 4)
+            assert np.array_equal(np.bitwise_xor.reduce(slots, axis=0), np.bitwise_xor.reduce(words, axis=0))
+            tail = buf[n:].clone()
+            B.tutti_stream_baseline(buf, n, True, None, budget)
+            torch.cuda.synchronize()
+            got = buf.cpu().numpy()[:n].view(np.uint32).reshape(-1, 4)
+            unit = np.arange(n // 16, dtype=np.uint64)
+            want = np.stack([unit.astype(np.uint32), (unit >> np.uint64(32)).astype(np.uint32),
+                             ~unit.astype(np.uint32), np.full(unit.size, 0x54555454, np.uint32)], axis=1)
+            assert np.array_equal(got, want) and torch.equal(buf[n:], tail)
+
+
 def test_scatter_baseline(H):
     say("scatter baseline")
     rng = np.random.default_rng(2)
