@@ -82,6 +82,43 @@ int check_planes(const tutti_pool *pool) {
   return TUTTI_OK;
 }
 
+SqeArgs sqe_args(const uint32_t *d_file_id, tutti_sqe *d_sqe, uint32_t *d_status, uint64_t stage_addr,
+                 uint32_t sqe_cap, uint32_t chunk_bytes, uint32_t layer, uint32_t opcode, uint32_t sgl_id) {
+  SqeArgs q;
+  q.file_id = d_file_id;
+  q.sqe = d_sqe;
+  q.status = d_status;
+  q.stage_addr = stage_addr;
+  q.sqe_cap = sqe_cap;
+  q.chunk_bytes = chunk_bytes;
+  q.layer = layer;
+  q.opcode = opcode;
+  q.sgl_id = sgl_id;
+  return q;
+}
+
+DirectArgs direct_args(const uint32_t *d_block_table, uint64_t sgl_table_addr, uint32_t table_len,
+                       uint32_t num_blocks, uint32_t block_bytes) {
+  DirectArgs d;
+  d.table = d_block_table;
+  d.sgl_table_addr = sgl_table_addr;
+  d.table_len = table_len;
+  d.num_blocks = num_blocks;
+  d.block_bytes = block_bytes;
+  return d;
+}
+
+LayoutArgs layout_args(const uint32_t *d_n_blocks, tutti_extent *d_extents, uint64_t *d_totals, uint32_t block_bytes,
+                       const tutti_objcfg *cfg, uint32_t n_req) {
+  LayoutArgs a;
+  a.n_blocks = d_n_blocks;
+  a.extents = d_extents;
+  a.totals = d_totals;
+  a.geom = ScanGeom{block_bytes, cfg->align, cfg->chunk_bytes};
+  a.n_req = n_req;
+  return a;
+}
+
 struct Launch {
   uint32_t grid;
   uint32_t wg_threads;   // kWgThreads, or kBudgetWgThreads under a CU budget
@@ -379,12 +416,7 @@ int tutti_obj_layout(const tutti_pool *pool, const tutti_objcfg *cfg, const uint
   if (rc) return rc;
   if (n_req > TUTTI_MAX_REQ) return TUTTI_ERANGE;
   if (!d_totals || (n_req > 0 && (!d_n_blocks || !d_extents))) return TUTTI_EINVAL;
-  LayoutArgs a;
-  a.n_blocks = d_n_blocks;
-  a.extents = d_extents;
-  a.totals = d_totals;
-  a.geom = ScanGeom{bb, cfg->align, cfg->chunk_bytes};
-  a.n_req = n_req;
+  const LayoutArgs a = layout_args(d_n_blocks, d_extents, d_totals, bb, cfg, n_req);
   hipLaunchKernelGGL(k_layout, dim3(1), dim3(kWave), req_lds_bytes(n_req), static_cast<hipStream_t>(stream), a);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
@@ -419,16 +451,8 @@ int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti
   if (n_req == 0) return TUTTI_OK;
   const int cus = cu_count();
   if (cus < 0) return cus;
-  SqeArgs q;
-  q.file_id = d_file_id;
-  q.sqe = d_sqe;
-  q.status = d_status;
-  q.stage_addr = stage_addr;
-  q.sqe_cap = sqe_cap;
-  q.chunk_bytes = cfg->chunk_bytes;
-  q.layer = layer;
-  q.opcode = opcode;
-  q.sgl_id = sgl_id;
+  const SqeArgs q = sqe_args(d_file_id, d_sqe, d_status, stage_addr, sqe_cap, cfg->chunk_bytes, layer,
+                             opcode, sgl_id);
   // one lane per 16-byte quarter of an entry; at most a few workgroups per CU
   uint64_t need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
   if (need == 0) need = 1;
@@ -479,23 +503,10 @@ int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t 
   const uint64_t sqe_max = cu_budget ? 1 : 16;
   const uint32_t sqe_wgs = static_cast<uint32_t>(sqe_need < sqe_max ? sqe_need : sqe_max);
 
-  SqeArgs q;
-  q.file_id = d_file_id;
-  q.sqe = d_sqe;
-  q.status = d_status;
-  q.stage_addr = stage_addr;
-  q.sqe_cap = sqe_cap;
-  q.chunk_bytes = cfg->chunk_bytes;
-  q.layer = layer;
-  q.opcode = (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE;
-  q.sgl_id = sgl_id;
+  const SqeArgs q = sqe_args(d_file_id, d_sqe, d_status, stage_addr, sqe_cap, cfg->chunk_bytes, layer,
+                             (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE, sgl_id);
 
-  LayoutArgs a;
-  a.n_blocks = d_n_blocks;
-  a.extents = d_extents;
-  a.totals = d_totals;
-  a.geom = ScanGeom{bb, cfg->align, cfg->chunk_bytes};
-  a.n_req = n_req;
+  const LayoutArgs a = layout_args(d_n_blocks, d_extents, d_totals, bb, cfg, n_req);
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
@@ -581,22 +592,9 @@ int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, cons
   if (n_req == 0) return TUTTI_OK;
   const int cus = cu_count();
   if (cus < 0) return cus;
-  SqeArgs q;
-  q.file_id = d_file_id;
-  q.sqe = d_sqe;
-  q.status = d_status;
-  q.stage_addr = 0;
-  q.sqe_cap = sqe_cap;
-  q.chunk_bytes = bb;
-  q.layer = layer;
-  q.opcode = opcode;
-  q.sgl_id = sgl_id;
-  DirectArgs d;
-  d.table = d_block_table;
-  d.sgl_table_addr = sgl_table_addr;
-  d.table_len = table_len;
-  d.num_blocks = pool->num_blocks;
-  d.block_bytes = bb;
+  const SqeArgs q = sqe_args(d_file_id, d_sqe, d_status, 0, sqe_cap, bb, layer,
+                             opcode, sgl_id);
+  const DirectArgs d = direct_args(d_block_table, sgl_table_addr, table_len, pool->num_blocks, bb);
   uint64_t need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
   if (need == 0) need = 1;
   const uint64_t lim = static_cast<uint64_t>(cus) * 8;
@@ -646,22 +644,9 @@ int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t
   const int cus = cu_count();
   if (cus < 0) return cus;
   RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
-  SqeArgs q;
-  q.file_id = d_file_id;
-  q.sqe = nullptr;
-  q.status = d_status;
-  q.stage_addr = 0;
-  q.sqe_cap = 0;
-  q.chunk_bytes = bb;
-  q.layer = layer;
-  q.opcode = opcode;
-  q.sgl_id = sgl_id;
-  DirectArgs d;
-  d.table = d_block_table;
-  d.sgl_table_addr = sgl_table_addr;
-  d.table_len = table_len;
-  d.num_blocks = pool->num_blocks;
-  d.block_bytes = bb;
+  const SqeArgs q = sqe_args(d_file_id, nullptr, d_status, 0, 0, bb, layer,
+                             opcode, sgl_id);
+  const DirectArgs d = direct_args(d_block_table, sgl_table_addr, table_len, pool->num_blocks, bb);
   uint64_t need = (4ull * n_slots * TUTTI_IOCB_SLOTS + kWgThreads - 1) / kWgThreads;
   if (need == 0) need = 1;  // no IOCBs given: one workgroup still reports the dropped contexts
   const uint64_t lim = static_cast<uint64_t>(cus) * 8;
@@ -767,30 +752,12 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
   const uint64_t fill_max = cu_budget ? 1 : 16;
   const uint32_t fill_wgs = static_cast<uint32_t>(fill_need < fill_max ? fill_need : fill_max);
 
-  SqeArgs q;
-  q.file_id = d_file_id;
-  q.sqe = nullptr;
-  q.status = d_status;
-  q.stage_addr = 0;
-  q.sqe_cap = 0;
-  q.chunk_bytes = bb;
-  q.layer = layer;
-  q.opcode = (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE;
-  q.sgl_id = sgl_id;
-  DirectArgs d;
-  d.table = d_block_table;
-  d.sgl_table_addr = sgl_table_addr;
-  d.table_len = table_len;
-  d.num_blocks = pool->num_blocks;
-  d.block_bytes = bb;
+  const SqeArgs q = sqe_args(d_file_id, nullptr, d_status, 0, 0, bb, layer,
+                             (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE, sgl_id);
+  const DirectArgs d = direct_args(d_block_table, sgl_table_addr, table_len, pool->num_blocks, bb);
   RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
   FileArgs f{store->file_stride, store->first_file_id, store->n_files};
-  LayoutArgs a;
-  a.n_blocks = d_n_blocks;
-  a.extents = d_extents;
-  a.totals = d_totals;
-  a.geom = ScanGeom{bb, cfg->align, cfg->chunk_bytes};
-  a.n_req = n_req;
+  const LayoutArgs a = layout_args(d_n_blocks, d_extents, d_totals, bb, cfg, n_req);
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   const uint32_t copy_wgs = L.grid;
