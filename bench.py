@@ -544,6 +544,13 @@ def scatter_orders(torch, B, stages, nbytes, dev, gran=32768, span=4 << 30, n_bu
         orders[f"stride_{S}_pieces"] = (np.arange(n) * S) % slots + (np.arange(n) * S) // slots
     for M in (8, 32, 256):
         orders[f"dealt_mod_{M}"] = dealt(M)
+    # whole aligned regions taken at random, their pieces visited in random order: the placement keeps every
+    # neighbour, the order keeps none
+    for region in (1 << 20, 4 << 20, 32 << 20):
+        per = region // gran
+        starts = rng.permutation(slots // per)[: n // per]
+        orders[f"random_order_inside_{region >> 20}MiB_regions"] = rng.permutation(
+            (starts[:, None] * per + np.arange(per)[None, :]).reshape(-1))
     bufs = [torch.empty(span, dtype=torch.uint8, device=dev) for _ in range(n_buf)]
     scratch = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(4)]
     res = {}
