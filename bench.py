@@ -233,6 +233,7 @@ def main():
         out["copy_ceiling"] = copy_ceiling(torch, B, stages, payload_layer, dev)
         out["copy_ceiling"]["restore_vs_copy"] = round(out["restore"]["traffic_GBps"] /
                                                        out["copy_ceiling"]["traffic_GBps"], 4)
+        out["chip_stream_ceilings"] = per_cu_limits(torch, B, dev, budgets=(0,))["0"]
         out["scatter_floor"] = scatter_floor(torch, B, w, stages, payload_layer, dev)
         out["scatter_floor"]["restore_vs_floor"] = round(out["scatter_floor"]["scattered_writes"]["us"] /
                                                          out["restore"]["us_per_layer"], 4)
