@@ -327,6 +327,80 @@ def test_layer_calls_can_be_captured_in_a_graph(orc, H):
         assert torch.isfinite(junk).all() and int(st.item()) == 0
 
 
+def test_ring_layer_calls_can_be_captured_in_a_graph(orc, H):
+    """init_queue, store_layer for every layer, then retrieve_layer into a second pool, captured once and replayed:
+    every replay must leave the rings, the file store and the second pool as the eager run did."""
+    say("graph capture: rings")
+    rng = np.random.default_rng(57)
+    nb = [600, 0, 500]                                   # 2200 contexts: two IOCBs per layer
+    N, L = 1200, 3
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=4096, L=L,
+                    name="graph_rings")
+    o_ext, _ = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    file_stride = int(2 * L * int(o_ext["obj_bytes"].max()))
+    store = torch.zeros(c.n_req * file_stride, dtype=torch.uint8, device=H.DEV)
+    fs = B.make_filestore(store, file_stride, 1000, c.n_req)
+    k2, v2 = torch.zeros_like(c.k_dev), torch.zeros_like(c.v_dev)
+    depth = 4 * L
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=H.DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=H.DEV)
+    ring = B.make_ring(sq, cq, depth)
+    ext = torch.zeros(32 * c.n_req, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    st = H.new_status()
+    addr = 0x7f00_0000_3000
+
+    def train():
+        B.tutti_ring_init(ring)
+        for l in range(L):
+            B.tutti_store_layer(ring, 2 * l, 2, c.gpu_pool(), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size,
+                                c.d_file_id, l, addr, 3, fs, ext, tot, 0, st)
+        for l in range(L):
+            B.tutti_retrieve_layer(ring, 2 * L + 2 * l, 2, c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req,
+                                   c.d_table, c.table.size, c.d_file_id, l, addr, 3, fs, ext, tot, 0, st)
+
+    outs = [store, k2, v2, sq, cq, ext, tot]
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in outs]
+
+    train()
+    eager = snapshot()
+    # the eager result is the oracle's: same calls on host copies
+    o_store = np.zeros(store.numel(), np.uint8)
+    ok2, ov2 = np.zeros_like(c.k_host), np.zeros_like(c.v_host)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    orc.ring_init(o_sq, o_cq)
+    for l in range(L):
+        orc.store_layer(o_sq, o_cq, 2 * l, 2, c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks, c.table, c.file_id, l, addr, 3,
+                        o_store, file_stride, 1000, c.n_req)
+    for l in range(L):
+        orc.retrieve_layer(o_sq, o_cq, 2 * L + 2 * l, 2, c.orc_pool(orc, ok2, ov2), c.orc_cfg(orc), c.n_blocks, c.table,
+                           c.file_id, l, addr, 3, o_store, file_stride, 1000, c.n_req)
+    assert np.array_equal(store.cpu().numpy(), o_store) and np.array_equal(k2.cpu().numpy(), ok2)
+    assert np.array_equal(v2.cpu().numpy(), ov2) and sq.cpu().numpy().tobytes() == o_sq.tobytes()
+    assert cq.cpu().numpy().tobytes() == o_cq.tobytes() and int(o_cq[0]) == 4 * L
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            train()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in outs:
+            t.zero_()
+        junk = torch.randn(512, 512, device=H.DEV) @ torch.randn(512, 512, device=H.DEV)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(eager, got):
+            assert torch.equal(a, b), f"graph replay {rep} differs from the eager result"
+        assert torch.isfinite(junk).all() and int(st.item()) == 0
+
+
 # ------------------------------------------------------------------ seeded random shapes
 
 import os as _os
