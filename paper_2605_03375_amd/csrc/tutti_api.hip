@@ -128,7 +128,7 @@ struct Launch {
   uint32_t tile_lds;     // bytes of LDS for the tile
 };
 
-constexpr uint32_t kHndTileCap = 32768;      // largest tile staged in LDS
+constexpr uint32_t kHndTileCap = 16384;      // largest tile staged in LDS: 8 workgroups per CU keep their tiles resident
 constexpr uint32_t kDynLdsCap = 65536;       // dynamic LDS a launch may ask for without opting in to more
 uint32_t log2u(uint32_t x) {
   uint32_t n = 0;
