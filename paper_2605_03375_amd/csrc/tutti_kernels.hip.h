@@ -827,77 +827,130 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
 // wavefront, which walk the rows of one head, fall on different banks.
 // PT = 16-byte units per thread per tile (tile bytes = PT * 16 * workgroup size).
 // ------------------------------------------------------------------------------------------
+// Shifts and masks of the tile geometry.
+struct TileGeom {
+  uint32_t rs, gs, hr;               // log2 bytes of a row, of one token across all heads, of one head's run in the tile
+  uint32_t g_mask, hr_mask, r_mask;
+};
+
+// The tile of an item on both sides: global loads of its PT 16-byte units per thread (object order for an
+// unpack, pool order for a pack), and where they go afterwards.
+template <int DIR, int PT, int WG>
+struct TileMove {
+  static __device__ __forceinline__ unsigned char *obj_tile(const MoveArgs &a, const TileGeom &g, const Item &d) {
+    const uint32_t t0 = d.s << a.tile_shift;
+    return d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes + (static_cast<uint64_t>(t0) << g.gs);
+  }
+  static __device__ __forceinline__ unsigned char *blk(const MoveArgs &a, const Item &d, uint32_t id) {
+    return (d.kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
+  }
+  // byte offset inside the block of pool-order position p of the tile that starts at token t0
+  static __device__ __forceinline__ uint32_t pool_off(const MoveArgs &a, const TileGeom &g, uint32_t t0, uint32_t p) {
+    const uint32_t i = p >> g.hr, t = (p & g.hr_mask) >> g.rs, w = p & g.r_mask;
+    return (((i << a.token_shift) + t0 + t) << g.rs) + w;
+  }
+  // LDS offset of object-order position o, and of pool-order position p
+  static __device__ __forceinline__ uint32_t lds_obj(const MoveArgs &a, const TileGeom &g, uint32_t o) {
+    return (o >> g.gs) * a.lds_pitch + (o & g.g_mask);
+  }
+  static __device__ __forceinline__ uint32_t lds_pool(const MoveArgs &a, const TileGeom &g, uint32_t p) {
+    const uint32_t i = p >> g.hr, t = (p & g.hr_mask) >> g.rs, w = p & g.r_mask;
+    return t * a.lds_pitch + (i << g.rs) + w;
+  }
+  static __device__ __forceinline__ void load(const MoveArgs &a, const TileGeom &g, const Item &d, uint32_t id,
+                                              uint32_t tid, u32x4 (&v)[PT]) {
+    const uint32_t t0 = d.s << a.tile_shift;
+    const unsigned char *src = DIR == kUnpack ? obj_tile(a, g, d) : blk(a, d, id);
+#pragma unroll
+    for (int k = 0; k < PT; ++k) {
+      const uint32_t q = (k * WG + tid) * 16u;
+      v[k] = ld16<1>(src + (DIR == kUnpack ? q : pool_off(a, g, t0, q)));
+    }
+  }
+  static __device__ __forceinline__ void to_lds(const MoveArgs &a, const TileGeom &g, uint32_t tid, unsigned char *tile,
+                                                const u32x4 (&v)[PT]) {
+#pragma unroll
+    for (int k = 0; k < PT; ++k) {
+      const uint32_t q = (k * WG + tid) * 16u;
+      *reinterpret_cast<u32x4 *>(tile + (DIR == kUnpack ? lds_obj(a, g, q) : lds_pool(a, g, q))) = v[k];
+    }
+  }
+  static __device__ __forceinline__ void from_lds_and_store(const MoveArgs &a, const TileGeom &g, const Item &d,
+                                                            uint32_t id, uint32_t tid, const unsigned char *tile) {
+    const uint32_t t0 = d.s << a.tile_shift;
+    unsigned char *dst = DIR == kUnpack ? blk(a, d, id) : obj_tile(a, g, d);
+    u32x4 w[PT];
+#pragma unroll
+    for (int k = 0; k < PT; ++k) {
+      const uint32_t q = (k * WG + tid) * 16u;
+      w[k] = *reinterpret_cast<const u32x4 *>(tile + (DIR == kUnpack ? lds_pool(a, g, q) : lds_obj(a, g, q)));
+    }
+#pragma unroll
+    for (int k = 0; k < PT; ++k) {
+      const uint32_t q = (k * WG + tid) * 16u;
+      st16<2>(dst + (DIR == kUnpack ? pool_off(a, g, t0, q) : q), w[k]);
+    }
+  }
+};
+
+// One tile per workgroup and iteration, software-pipelined by one item: the global loads of the next tile are
+// issued right after the barrier that publishes the current tile in LDS, so they are in flight while the
+// current tile is read back in the other order and stored.
 template <int DIR, int PT, int WG>
 __device__ __forceinline__ void move_items_hnd_lds(const MoveArgs a, const ReqLds l, uint32_t n_req,
                                                    uint32_t copy_wgs, unsigned char *tile) {
+  typedef TileMove<DIR, PT, WG> TM;
   const uint32_t tid = threadIdx.x;
   const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
   const uint32_t n_items = 2u * total_blocks * a.slices_per_block;
-  const uint32_t rs = a.row_shift;
-  const uint32_t gs = a.row_shift + a.head_shift;  // log2 bytes of one token across all heads
-  const uint32_t hr = a.tile_shift + a.row_shift;  // log2 bytes of one head's run inside the tile
-  const uint32_t g_mask = (1u << gs) - 1u, hr_mask = (1u << hr) - 1u, r_mask = (1u << rs) - 1u;
+  TileGeom g;
+  g.rs = a.row_shift;
+  g.gs = a.row_shift + a.head_shift;
+  g.hr = a.tile_shift + a.row_shift;
+  g.g_mask = (1u << g.gs) - 1u;
+  g.hr_mask = (1u << g.hr) - 1u;
+  g.r_mask = (1u << g.rs) - 1u;
 
-  for (uint32_t it = blockIdx.x; it < n_items; it += copy_wgs) {
-    const Item d = decode_item(a, l, n_req, it, tid);  // workgroup-uniform; thread 0 reports
-    const uint32_t id = load_block_id(a, d);
-    if (d.obj_ptr != nullptr && id < a.num_blocks) {
-      const uint32_t t0 = d.s << a.tile_shift;
-      unsigned char *blk = (d.kind ? a.v_base : a.k_base) + static_cast<uint64_t>(id) * a.block_stride;
-      unsigned char *obj_tile = d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes + (static_cast<uint64_t>(t0) << gs);
-      u32x4 v[PT];
-      if (DIR == kUnpack) {
-#pragma unroll
-        for (int k = 0; k < PT; ++k) v[k] = ld16<1>(obj_tile + (k * WG + tid) * 16u);
-#pragma unroll
-        for (int k = 0; k < PT; ++k) {
-          const uint32_t o = (k * WG + tid) * 16u;
-          *reinterpret_cast<u32x4 *>(tile + (o >> gs) * a.lds_pitch + (o & g_mask)) = v[k];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < PT; ++k) {
-          const uint32_t p = (k * WG + tid) * 16u;  // position in pool order inside the tile
-          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
-          v[k] = *reinterpret_cast<const u32x4 *>(tile + t * a.lds_pitch + (i << rs) + w);
-        }
-#pragma unroll
-        for (int k = 0; k < PT; ++k) {
-          const uint32_t p = (k * WG + tid) * 16u;
-          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
-          st16<2>(blk + ((((i << a.token_shift) + t0 + t)) << rs) + w, v[k]);
-        }
-      } else {
-#pragma unroll
-        for (int k = 0; k < PT; ++k) {
-          const uint32_t p = (k * WG + tid) * 16u;
-          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
-          v[k] = ld16<1>(blk + ((((i << a.token_shift) + t0 + t)) << rs) + w);
-        }
-#pragma unroll
-        for (int k = 0; k < PT; ++k) {
-          const uint32_t p = (k * WG + tid) * 16u;
-          const uint32_t i = p >> hr, t = (p & hr_mask) >> rs, w = p & r_mask;
-          *reinterpret_cast<u32x4 *>(tile + t * a.lds_pitch + (i << rs) + w) = v[k];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < PT; ++k) {
-          const uint32_t o = (k * WG + tid) * 16u;
-          v[k] = *reinterpret_cast<const u32x4 *>(tile + (o >> gs) * a.lds_pitch + (o & g_mask));
-        }
-#pragma unroll
-        for (int k = 0; k < PT; ++k) st16<2>(obj_tile + (k * WG + tid) * 16u, v[k]);
-      }
-      __syncthreads();  // the tile is free again
-    } else if (d.obj_ptr != nullptr && tid == 0 && d.s == 0 && a.status) {
+  uint32_t it = blockIdx.x;
+  if (it >= n_items) return;
+  Item cur = decode_item(a, l, n_req, it, tid);  // workgroup-uniform; thread 0 reports
+  uint32_t id = load_block_id(a, cur);
+  bool ok = cur.obj_ptr != nullptr && id < a.num_blocks;
+  u32x4 v[PT];
+  if (ok) TM::load(a, g, cur, id, tid, v);
+  for (;;) {
+    const uint32_t nit = it + copy_wgs;
+    const bool more = nit < n_items;
+    Item nxt = cur;
+    uint32_t nid = a.num_blocks;
+    bool nok = false;
+    if (more) {
+      nxt = decode_item(a, l, n_req, nit, tid);
+      nid = load_block_id(a, nxt);
+      nok = nxt.obj_ptr != nullptr && nid < a.num_blocks;
+    }
+    if (ok) TM::to_lds(a, g, tid, tile, v);
+    __syncthreads();
+    u32x4 v2[PT];
+    if (nok) TM::load(a, g, nxt, nid, tid, v2);
+    if (ok) {
+      TM::from_lds_and_store(a, g, cur, id, tid, tile);
+    } else if (cur.obj_ptr != nullptr && tid == 0 && cur.s == 0 && a.status) {
       atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
     }
-    if (DIR == kPack && d.obj_ptr != nullptr && d.j + 1 == d.n && d.s + 1 == a.slices_per_block) {
-      const uint64_t used = static_cast<uint64_t>(d.n) * a.block_bytes;
+    __syncthreads();  // the tile is free again
+    if (DIR == kPack && cur.obj_ptr != nullptr && cur.j + 1 == cur.n && cur.s + 1 == a.slices_per_block) {
+      const uint64_t used = static_cast<uint64_t>(cur.n) * a.block_bytes;
       const u32x4 zero = {0u, 0u, 0u, 0u};
-      for (uint64_t o = used + tid * 16ull; o < d.obj_bytes; o += WG * 16ull) st16<0>(d.obj_ptr + o, zero);
+      for (uint64_t o = used + tid * 16ull; o < cur.obj_bytes; o += WG * 16ull) st16<0>(cur.obj_ptr + o, zero);
     }
+    if (!more) break;
+    cur = nxt;
+    id = nid;
+    ok = nok;
+    it = nit;
+#pragma unroll
+    for (int k = 0; k < PT; ++k) v[k] = v2[k];
   }
 }
 
