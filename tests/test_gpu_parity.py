@@ -435,6 +435,12 @@ def test_random_shapes(orc, H, seed):
     H.check_everything(orc, c, cu_budget=budget)
     if bb % A == 0:
         H.check_direct_mode(orc, c, layer=c.L - 1)
+        # the one-call ring path on the same shape (two layers' worth of file, if that stays small)
+        c.L = 2
+        n_slots = (2 * int(nb.sum()) + B.IOCB_SLOTS - 1) // B.IOCB_SLOTS
+        if 2 * c.L * int(nb.max()) * bb * R <= (512 << 20):
+            H.check_ring_layer(orc, c, layer=1, write=bool(seed & 1), depth=n_slots + 1,
+                               first_slot=seed % (n_slots + 1), n_slots=n_slots, cu_budget=budget)
 
 
 # ------------------------------------------------------------------ rings: fill IOCBs, execute them, completions
