@@ -630,7 +630,7 @@ def sqe_rate(torch, B, W, dev, reps=50):
         us = a.elapsed_time(b) * 1e3 / reps
         res[label] = {"entries_per_layer": n_sqe, "us_per_launch": round(us, 2),
                       "sqes_per_s": round(n_sqe / (us * 1e-6), 0),
-                      "regime": "launch-latency bound" if us < 20 else "HBM-write bound"}
+                      "regime": "launch-latency bound" if us < 20 else "kernel bound"}
     return res
 
 
@@ -704,7 +704,8 @@ def big_entry_rate(torch, B, dev, n_req=2048, blocks_per_req=512, reps=20):
     us = a.elapsed_time(b) * 1e3 / reps
     return {"requests": n_req, "entries": n_sqe, "us_per_launch": round(us, 2),
             "sqes_per_s": round(n_sqe / (us * 1e-6), 0), "entry_write_GBps": round(64 * n_sqe / (us * 1e-6) / 1e9, 1),
-            "regime": "HBM-write bound (64 B written per entry, 4 B of table read)"}
+            "regime": "per-entry dependent chain (owner walk in LDS, table word, file id) hidden by occupancy and "
+                      "one-entry pipelining; compare entry_write_GBps with chip_stream_ceilings.write"}
 
 
 def per_cu_limits(torch, B, dev, nbytes=256 << 20, budgets=(8, 32, 128, 0), reps=3, n_buf=4):

@@ -290,59 +290,108 @@ struct DirectArgs {
   uint32_t block_bytes;
 };
 
-// Quarter `part` (16 bytes) of direct-mode entry i.  The block id comes from the table (one 4-byte load
-// per lane; the four lanes of an entry read the same word).  *bad is set for an id out of range.
-__device__ __forceinline__ u32x4 direct_entry_quarter(const SqeArgs &a, const DirectArgs &d, const ReqLds &l,
-                                                      uint32_t n_req, uint32_t i, uint32_t part, bool *bad) {
-  const uint32_t r = find_owner(l.table_off, n_req, i >> 1);
+// Direct-mode entry i in two steps, so that the loads of the next entry can be in flight while the current one
+// is assembled.  Step one: where the entry sits in its request, and the two values that come from global
+// memory (the block id; the file id for the lane that writes the first quarter).
+struct DirectLoc {
+  uint32_t r, kind, j;
+  uint32_t id;   // block id, or num_blocks when the table has no such position
+  uint32_t fid;  // file id of the request (quarter 0 only)
+};
+
+__device__ __forceinline__ DirectLoc direct_locate(const SqeArgs &a, const DirectArgs &d, const ReqLds &l, uint32_t r,
+                                                   uint32_t i, uint32_t part) {
+  DirectLoc c;
   const uint32_t toff = l.table_off[r];
   const uint32_t n = l.table_off[r + 1] - toff;
   const uint32_t v = i - 2u * toff;
-  const uint32_t kind = v >= n ? 1u : 0u;
-  const uint32_t j = v - kind * n;
-  const uint32_t tab_idx = toff + j;
-  uint32_t id = d.num_blocks;
-  if (tab_idx < d.table_len) id = d.table[tab_idx];
-  const bool ok = id < d.num_blocks;
+  c.r = r;
+  c.kind = v >= n ? 1u : 0u;
+  c.j = v - c.kind * n;
+  const uint32_t tab_idx = toff + c.j;
+  c.id = d.num_blocks;
+  if (tab_idx < d.table_len) c.id = d.table[tab_idx];  // the four lanes of an entry read the same word
+  c.fid = part == 0 ? a.file_id[r] : 0u;
+  return c;
+}
+
+// Step two: quarter `part` (16 bytes) of the entry.  *bad is set for an id out of range.
+__device__ __forceinline__ u32x4 direct_entry_quarter(const SqeArgs &a, const DirectArgs &d, const ReqLds &l,
+                                                      const DirectLoc &c, uint32_t i, uint32_t part, bool *bad) {
+  const bool ok = c.id < d.num_blocks;
   *bad = !ok;
   u32x4 w = {0u, 0u, 0u, 0u};
   if (part == 0) {
-    const uint64_t file_off = (2ull * a.layer + kind) * l.obj_bytes[r] + static_cast<uint64_t>(j) * d.block_bytes;
-    w.x = (a.opcode & 0xffu) | (kind << 8) | (a.layer << 16);
-    w.y = a.file_id[r];
+    const uint64_t file_off = (2ull * a.layer + c.kind) * l.obj_bytes[c.r] + static_cast<uint64_t>(c.j) * d.block_bytes;
+    w.x = (a.opcode & 0xffu) | (c.kind << 8) | (a.layer << 16);
+    w.y = c.fid;
     w.z = static_cast<uint32_t>(file_off);
     w.w = static_cast<uint32_t>(file_off >> 32);
   } else if (part == 1) {
-    const uint64_t addr = ok ? d.sgl_table_addr + 16ull * (static_cast<uint64_t>(kind) * d.num_blocks + id) : 0ull;
+    const uint64_t addr = ok ? d.sgl_table_addr + 16ull * (static_cast<uint64_t>(c.kind) * d.num_blocks + c.id) : 0ull;
     w.x = static_cast<uint32_t>(addr);
     w.y = static_cast<uint32_t>(addr >> 32);
     w.z = ok ? d.block_bytes : 0u;
     w.w = a.sgl_id;
   } else if (part == 2) {
     w.x = i;
-    w.y = r;
+    w.y = c.r;
     w.z = i / TUTTI_IOCB_SLOTS;
     w.w = i % TUTTI_IOCB_SLOTS;
   }
   return w;
 }
 
-// Four lanes per entry, as in emit_sqes: a wavefront's store covers 16 whole entries.
+// The request that owns block-table position `key`, found from the owner of an earlier (smaller) position:
+// the offsets are non-decreasing, so walking forward gives what find_owner gives.
+__device__ __forceinline__ uint32_t advance_owner(const uint32_t *table_off, uint32_t n_req, uint32_t r, uint32_t key) {
+  while (r + 1 < n_req && table_off[r + 1] <= key) ++r;
+  return r;
+}
+
+// Four lanes per entry, as in emit_sqes: a wavefront's store covers 16 whole entries.  The `n_wgs` workgroups
+// starting at `first_wg` each take one contiguous run of entries (a whole number of 4 KiB workgroup stores), so a
+// thread's consecutive entries are 64 apart and their owner is found by walking on from the previous one: one
+// binary search per thread instead of one per entry.  The loop is pipelined by one entry: the table and file-id
+// loads of the next entry are issued before the current one is assembled and stored.  `dst(i)` gives the address
+// of entry i.
+template <typename Dst>
+__device__ __forceinline__ void emit_direct_entries(const SqeArgs a, const DirectArgs d, const ReqLds l, uint32_t n_req,
+                                                    uint64_t n_write, uint32_t first_wg, uint32_t n_wgs, Dst dst) {
+  const uint64_t n_quarters = 4ull * n_write;
+  const uint64_t per_pass = blockDim.x;  // quarters one workgroup writes per pass: 4 KiB for 256 threads
+  const uint64_t passes = (n_quarters + per_pass * n_wgs - 1) / (per_pass * n_wgs);
+  const uint64_t begin = static_cast<uint64_t>(blockIdx.x - first_wg) * passes * per_pass;
+  uint64_t end = begin + passes * per_pass;
+  if (end > n_quarters) end = n_quarters;
+  uint64_t q = begin + threadIdx.x;
+  if (q >= end) return;
+  uint32_t i = static_cast<uint32_t>(q >> 2);
+  const uint32_t part = static_cast<uint32_t>(q & 3);  // per_pass is a multiple of 4: the same quarter every pass
+  DirectLoc cur = direct_locate(a, d, l, find_owner(l.table_off, n_req, i >> 1), i, part);
+  for (;;) {
+    const uint64_t qn = q + per_pass;
+    const bool more = qn < end;
+    const uint32_t in = static_cast<uint32_t>(qn >> 2);
+    DirectLoc nxt = cur;
+    if (more) nxt = direct_locate(a, d, l, advance_owner(l.table_off, n_req, cur.r, in >> 1), in, part);
+    bool bad = false;
+    const u32x4 w = direct_entry_quarter(a, d, l, cur, i, part, &bad);
+    if (bad && part == 0 && a.status) atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
+    reinterpret_cast<u32x4 *>(dst(i))[part] = w;
+    if (!more) break;
+    q = qn;
+    i = in;
+    cur = nxt;
+  }
+}
+
 __device__ __forceinline__ void emit_direct_sqes(const SqeArgs a, const DirectArgs d, const ReqLds l, uint32_t n_req) {
   const uint64_t n_sqe = 2ull * l.table_off[n_req];
   const uint64_t n_write = n_sqe < a.sqe_cap ? n_sqe : a.sqe_cap;
   if (n_sqe > a.sqe_cap && blockIdx.x == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
-  const uint64_t n_quarters = 4ull * n_write;
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-  u32x4 *out = reinterpret_cast<u32x4 *>(a.sqe);
-  for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; q < n_quarters; q += stride) {
-    const uint32_t i = static_cast<uint32_t>(q >> 2);
-    const uint32_t part = static_cast<uint32_t>(q & 3);
-    bool bad = false;
-    const u32x4 w = direct_entry_quarter(a, d, l, n_req, i, part, &bad);
-    if (bad && part == 0 && a.status) atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
-    out[q] = w;
-  }
+  tutti_sqe *out = a.sqe;
+  emit_direct_entries(a, d, l, n_req, n_write, 0, gridDim.x, [out](uint32_t i) { return out + i; });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -392,16 +441,10 @@ __device__ __forceinline__ void emit_iocbs(const RingArgs g, const SqeArgs a, co
     h->layer = a.layer;
     h->opcode = a.opcode;
   }
-  const uint64_t n_quarters = 4ull * n_fill;
-  for (uint64_t q = tid; q < n_quarters; q += stride) {
-    const uint32_t i = static_cast<uint32_t>(q >> 2);
-    const uint32_t part = static_cast<uint32_t>(q & 3);
-    bool bad = false;
-    const u32x4 w = direct_entry_quarter(a, d, l, n_req, i, part, &bad);
-    if (bad && part == 0 && a.status) atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
-    tutti_iocb *io = &g.sq[(g.first_slot + i / TUTTI_IOCB_SLOTS) % g.depth];
-    reinterpret_cast<u32x4 *>(&io->ioctx[i % TUTTI_IOCB_SLOTS])[part] = w;
-  }
+  const RingArgs ring = g;
+  emit_direct_entries(a, d, l, n_req, n_fill, first_wg, n_wgs, [ring](uint32_t i) {
+    return &ring.sq[(ring.first_slot + i / TUTTI_IOCB_SLOTS) % ring.depth].ioctx[i % TUTTI_IOCB_SLOTS];
+  });
 }
 
 __global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, const SqeArgs a, const DirectArgs d,
