@@ -682,6 +682,18 @@ def test_max_requests(orc, H):
     c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=n, table=rng.permutation(N)[: int(n.sum())], chunk=4096,
                     L=4, name="max_req")
     H.check_everything(orc, c)
+    # the direct-mode entry writers walk from owner to owner: 2048 requests, a quarter of them empty, and a
+    # second shape where long runs of empty requests sit between the non-empty ones
+    H.check_direct_mode(orc, c, layer=3)
+    n_slots = (2 * int(n.sum()) + B.IOCB_SLOTS - 1) // B.IOCB_SLOTS
+    H.check_ring_layer(orc, c, layer=2, write=False, depth=n_slots + 2, first_slot=1, n_slots=n_slots)
+    sparse = np.zeros(B.MAX_REQ, np.uint32)
+    sparse[[0, 700, 701, 2047]] = [300, 1, 900, 40]
+    c = H.LayerCase(T=1, h=1, d=8, e=2, N=1300, n_blocks=sparse, table=rng.permutation(1300)[:1241], align=16, chunk=16,
+                    L=2, name="max_req_sparse")      # 16-byte blocks keep the 2048 files of the ring check small
+    H.check_direct_mode(orc, c, layer=1)
+    H.check_ring_layer(orc, c, layer=1, write=True, depth=3, first_slot=2, n_slots=2)
+    H.check_ring_layer(orc, c, layer=0, write=False, depth=3, first_slot=0, n_slots=2, cu_budget=3)
     c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=n[:65], table=rng.permutation(N)[: int(n[:65].sum())],
                     chunk=4096, L=4, layout=1, name="req65")
     H.check_everything(orc, c)
