@@ -209,7 +209,8 @@ def main():
                     "payload_GBps": round(payload_layer / (restore_us * 1e-6) / 1e9, 1),
                     "traffic_GBps": round(2 * payload_layer / (restore_us * 1e-6) / 1e9, 1),
                     "pct_hbm_peak": round(100 * 2 * payload_layer / (restore_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
-                    "median_train_ms": round(median(rest_ms), 4), "min_train_ms": round(min(rest_ms), 4)},
+                    "median_train_ms": round(median(rest_ms), 4), "min_train_ms": round(min(rest_ms), 4),
+                    "p95_train_ms": round(float(np.percentile(rest_ms, 95)), 4)},
         "save": {"us_per_layer": round(save_us, 2),
                  "payload_GBps": round(payload_layer / (save_us * 1e-6) / 1e9, 1),
                  "traffic_GBps": round(2 * payload_layer / (save_us * 1e-6) / 1e9, 1),
@@ -230,6 +231,22 @@ def main():
             torch.cuda.synchronize()
             ts.append(a.elapsed_time(b) * 1e3 / L)
         out["save_unfused_3_launches"] = {"us_per_layer": round(median(ts), 2)}
+        # the copy kernels on their own (extents already on the device): tutti_obj_unpack / tutti_obj_pack
+        alone = {}
+        for label, fn in (("unpack_alone", B.tutti_obj_unpack), ("pack_alone", B.tutti_obj_pack)):
+            ts = []
+            for rep in range(4):
+                a, b = ev(), ev()
+                a.record(stream)
+                for l in range(L):
+                    fn(pools[l], cfg, ext_r[l], 1, d_tab, n_tab, stages[l], payload_layer, 0, status, stream)
+                b.record(stream)
+                torch.cuda.synchronize()
+                if rep:
+                    ts.append(a.elapsed_time(b) * 1e3 / L)
+            alone[label] = {"us_per_layer": round(median(ts), 2),
+                            "pct_hbm_peak": round(100 * 2 * payload_layer / (median(ts) * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
+        out["copy_kernels_alone"] = alone
         out["copy_ceiling"] = copy_ceiling(torch, B, stages, payload_layer, dev)
         out["copy_ceiling"]["restore_vs_copy"] = round(out["restore"]["traffic_GBps"] /
                                                        out["copy_ceiling"]["traffic_GBps"], 4)
@@ -596,8 +613,20 @@ def copy_ceiling(torch, B, stages, nbytes, dev, reps=5):
         torch.cuda.synchronize()
         times.append(a.elapsed_time(b) * 1e3 / len(stages))
     us = median(times)
+    # the runtime's own device-to-device copy of the same buffers, for reference (torch's copy_ of a
+    # contiguous same-device tensor is a hipMemcpyAsync)
+    rt = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i, s in enumerate(stages):
+            dsts[i % 4].copy_(s, non_blocking=True)
+        b.record()
+        torch.cuda.synchronize()
+        rt.append(a.elapsed_time(b) * 1e3 / len(stages))
     return {"bytes": nbytes, "us_per_copy": round(us, 2), "traffic_GBps": round(2 * nbytes / (us * 1e-6) / 1e9, 1),
-            "pct_hbm_peak": round(100 * 2 * nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
+            "pct_hbm_peak": round(100 * 2 * nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+            "runtime_d2d_copy_us": round(median(rt), 2)}
 
 
 def sqe_rate(torch, B, W, dev, reps=50):
