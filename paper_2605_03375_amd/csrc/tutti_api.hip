@@ -270,19 +270,43 @@ hipError_t launch_move_lds(const Launch &L, uint32_t lds, hipStream_t s, const M
   return hipGetLastError();
 }
 
+// Who does what in a fused launch (see k_layer).  L.grid is what plan_launch gave the copy; `entry_quarters` is
+// the number of 16-byte quarters of entries to write.  All copy workgroups start at workgroup 0; as many
+// workgroups as there are single passes of entries (one quarter per lane) also write entries, and the grid only
+// grows beyond the copy's when the entries need more workgroups than the copy does, never beyond what the chip
+// holds at once (a CU-budgeted launch never grows: its workgroups take several passes instead).
+Roles make_roles(const Launch &L, uint64_t entry_quarters, uint32_t *grid) {
+  uint64_t need = (entry_quarters + L.wg_threads - 1) / L.wg_threads;
+  if (need < 1) need = 1;
+  uint64_t limit = L.grid;
+  if (L.wg_threads == kWgThreads) {
+    uint32_t per_cu = g_wgs_per_cu.load(std::memory_order_relaxed);
+    if (per_cu == 0) per_cu = kDefaultWgsPerCu;
+    const int cus = cu_count();
+    const uint64_t cap = cus > 0 ? static_cast<uint64_t>(cus) * per_cu : L.grid;
+    if (cap > limit) limit = cap;
+  }
+  Roles w;
+  w.sqe_wgs = static_cast<uint32_t>(need < limit ? need : limit);
+  w.copy_first = 0;
+  w.copy_wgs = L.grid;
+  *grid = w.sqe_wgs > L.grid ? w.sqe_wgs : L.grid;
+  return w;
+}
+
 template <int DIR>
-hipError_t launch_layer_lds(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
+hipError_t launch_layer_lds(const Launch &L, uint64_t entry_quarters, uint32_t lds, hipStream_t s, const MoveArgs &m,
                             const SqeArgs &q, const LayoutArgs &a) {
-  const uint32_t copy_wgs = L.grid;
-  const dim3 grid(L.wg_threads == kWgThreads ? L.grid + sqe_wgs : L.grid);
+  uint32_t n_wgs = 0;
+  const Roles w = make_roles(L, entry_quarters, &n_wgs);
+  const dim3 grid(n_wgs);
 #define TUTTI_LDS_CASE(PT)                                                                                        \
   case PT:                                                                                                        \
     if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_layer_lds<DIR, PT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,       \
-                         sqe_wgs);                                                                                \
+      hipLaunchKernelGGL((k_layer_lds<DIR, PT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, w);         \
     else                                                                                                          \
-      hipLaunchKernelGGL((k_layer_lds<DIR, PT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q, a,     \
-                         copy_wgs, sqe_wgs);                                                                      \
+      hipLaunchKernelGGL((k_layer_lds<DIR, PT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q, a, \
+                         w);                                                                                      \
     break;
   switch (L.unroll) {
     TUTTI_LDS_CASE(1)
@@ -331,19 +355,18 @@ hipError_t launch_move(const Launch &L, uint32_t lds, hipStream_t s, const MoveA
 }
 
 template <int DIR, bool HND>
-hipError_t launch_layer(const Launch &L, uint32_t sqe_wgs, uint32_t lds, hipStream_t s, const MoveArgs &m,
+hipError_t launch_layer(const Launch &L, uint64_t entry_quarters, uint32_t lds, hipStream_t s, const MoveArgs &m,
                           const SqeArgs &q, const LayoutArgs &a) {
-  const uint32_t copy_wgs = L.grid;
-  // whole GPU: entry writers are extra workgroups; CU budget: the last copy workgroup writes them
-  const dim3 grid(L.wg_threads == kWgThreads ? L.grid + sqe_wgs : L.grid);
+  uint32_t n_wgs = 0;
+  const Roles w = make_roles(L, entry_quarters, &n_wgs);
+  const dim3 grid(n_wgs);
 #define TUTTI_RESTORE_NT(U, NT)                                                                                   \
   case NT:                                                                                                        \
     if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, copy_wgs,  \
-                         sqe_wgs);                                                                                \
+      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, w);      \
     else                                                                                                          \
-      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q,   \
-                         a, copy_wgs, sqe_wgs);                                                                   \
+      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q, \
+                         a, w);                                                                                   \
     break;
 #define TUTTI_RESTORE_CASE(U)    \
   case U:                        \
@@ -497,11 +520,7 @@ int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t 
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;
   L.grid = G.grid;
-  // extra workgroups behind the copy ones write the entries (one lane per 16-byte quarter)
-  uint64_t sqe_need = (4ull * sqe_cap + L.wg_threads - 1) / L.wg_threads;
-  if (sqe_need < 1) sqe_need = 1;
-  const uint64_t sqe_max = cu_budget ? 1 : 16;
-  const uint32_t sqe_wgs = static_cast<uint32_t>(sqe_need < sqe_max ? sqe_need : sqe_max);
+  const uint64_t entry_quarters = 4ull * sqe_cap;  // one lane per 16-byte quarter of an entry
 
   const SqeArgs q = sqe_args(d_file_id, d_sqe, d_status, stage_addr, sqe_cap, cfg->chunk_bytes, layer,
                              (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE, sgl_id);
@@ -511,11 +530,11 @@ int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (L.hnd_lds) {
-    e = launch_layer_lds<DIR>(L, sqe_wgs, align16(req_lds_bytes(n_req)) + L.tile_lds, s, m, q, a);
+    e = launch_layer_lds<DIR>(L, entry_quarters, align16(req_lds_bytes(n_req)) + L.tile_lds, s, m, q, a);
   } else {
     const uint32_t lds = req_lds_bytes(n_req);
-    e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_layer<DIR, true>(L, sqe_wgs, lds, s, m, q, a)
-                                                 : launch_layer<DIR, false>(L, sqe_wgs, lds, s, m, q, a);
+    e = (pool->pool_layout == TUTTI_LAYOUT_HND) ? launch_layer<DIR, true>(L, entry_quarters, lds, s, m, q, a)
+                                                 : launch_layer<DIR, false>(L, entry_quarters, lds, s, m, q, a);
   }
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
@@ -747,10 +766,9 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;
   L.grid = G.grid;
-  uint64_t fill_need = (4ull * n_slots * TUTTI_IOCB_SLOTS + L.wg_threads - 1) / L.wg_threads;
-  if (fill_need < 1) fill_need = 1;
-  const uint64_t fill_max = cu_budget ? 1 : 16;
-  const uint32_t fill_wgs = static_cast<uint32_t>(fill_need < fill_max ? fill_need : fill_max);
+  // contexts to record: no more than the IOCBs hold, no more than two per table position
+  uint64_t n_ctx = static_cast<uint64_t>(n_slots) * TUTTI_IOCB_SLOTS;
+  if (n_ctx > 2ull * table_len) n_ctx = 2ull * table_len;
 
   const SqeArgs q = sqe_args(d_file_id, nullptr, d_status, 0, 0, bb, layer,
                              (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE, sgl_id);
@@ -760,16 +778,17 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
   const LayoutArgs a = layout_args(d_n_blocks, d_extents, d_totals, bb, cfg, n_req);
 
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const uint32_t copy_wgs = L.grid;
+  uint32_t n_wgs = 0;
+  const Roles w = make_roles(L, 4 * n_ctx, &n_wgs);
   const uint32_t lds = req_lds_bytes(n_req);
 #define TUTTI_RING_CASE(U)                                                                                        \
   case U:                                                                                                         \
     if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_layer_ring<DIR, U, kWgThreads>), dim3(L.grid + fill_wgs), dim3(kWgThreads), lds, s, m, q, \
-                         d, g, f, a, copy_wgs, fill_wgs);                                                         \
+      hipLaunchKernelGGL((k_layer_ring<DIR, U, kWgThreads>), dim3(n_wgs), dim3(kWgThreads), lds, s, m, q, d, g, f, \
+                         a, w);                                                                                   \
     else                                                                                                          \
-      hipLaunchKernelGGL((k_layer_ring<DIR, U, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), lds, s, m, \
-                         q, d, g, f, a, copy_wgs, fill_wgs);                                                      \
+      hipLaunchKernelGGL((k_layer_ring<DIR, U, kBudgetWgThreads>), dim3(n_wgs), dim3(kBudgetWgThreads), lds, s, m, \
+                         q, d, g, f, a, w);                                                                       \
     break;
   switch (L.unroll) {
     TUTTI_RING_CASE(1)

@@ -32,6 +32,12 @@ constexpr uint32_t kWave = 64;
 constexpr uint32_t kWgThreads = 256;         // whole-GPU launches: 8 such workgroups per CU
 constexpr uint32_t kBudgetWgThreads = 1024;  // CU-budgeted launches: one 16-wave workgroup per budgeted CU
 
+// Wavefronts per SIMD the register allocator must leave room for: the whole-GPU grids are sized for eight
+// 256-thread workgroups per CU being resident at once (a kernel that needs more than 64 VGPRs would hold only
+// seven, and the persistent workgroups beyond that would run after the others: a tail).  Asked for where it
+// costs no spills: 256-thread kernels with at most four 16-byte units in flight per lane.
+constexpr int min_waves_per_simd(int wg_threads, int units) { return (wg_threads == 256 && units <= 4) ? 8 : 4; }
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // A wave-uniform 32-bit value moved to a scalar register.
@@ -87,13 +93,19 @@ __device__ __forceinline__ uint64_t shfl_u64(uint64_t v, uint32_t src) {
   return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
-__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v, uint32_t lane) {
-#pragma unroll
-  for (uint32_t d = 1; d < kWave; d <<= 1) {
-    uint64_t t = shfl_up_u64(v, d);
-    if (lane >= d) v += t;
+// Inclusive prefix sums of three values at once over the first `active` lanes of the wavefront (the other lanes
+// hold zeros and their results are not used).  One loop for the three sums keeps their cross-lane moves
+// independent and back to back, and only ceil(log2(active)) steps are taken: a single request needs none.
+__device__ __forceinline__ void wave_inclusive_scan3(uint64_t &a, uint64_t &b, uint64_t &c, uint32_t lane,
+                                                     uint32_t active) {
+  for (uint32_t d = 1; d < active; d <<= 1) {
+    const uint64_t ta = shfl_up_u64(a, d), tb = shfl_up_u64(b, d), tc = shfl_up_u64(c, d);
+    if (lane >= d) {
+      a += ta;
+      b += tb;
+      c += tc;
+    }
   }
-  return v;
 }
 
 struct ScanGeom {
@@ -107,17 +119,18 @@ struct ScanGeom {
 // carried between passes.  Results go to LDS and, when ext_out != nullptr, to global memory.
 __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32_t *__restrict__ n_blocks, uint32_t n_req,
                                                   uint32_t lane, ReqLds l, tutti_extent *__restrict__ ext_out,
-                                                  uint64_t *__restrict__ totals_out) {
+                                                  uint64_t *__restrict__ totals_out, bool with_chunks = true) {
   uint64_t carry_stage = 0, carry_sqe = 0, carry_tab = 0;
   for (uint32_t base = 0; base < n_req; base += kWave) {
     const uint32_t r = base + lane;
     const uint32_t n = (r < n_req) ? n_blocks[r] : 0u;
     const uint64_t raw = static_cast<uint64_t>(n) * g.block_bytes;
     const uint64_t obj = (raw + (g.align - 1)) & ~static_cast<uint64_t>(g.align - 1);
-    const uint64_t chunks = (obj + g.chunk_bytes - 1) / g.chunk_bytes;
-    const uint64_t inc_stage = wave_inclusive_scan(2 * obj, lane);
-    const uint64_t inc_sqe = wave_inclusive_scan(2 * chunks, lane);
-    const uint64_t inc_tab = wave_inclusive_scan(n, lane);
+    // a workgroup that only moves blocks never reads the entry bases: it skips the 64-bit division
+    const uint64_t chunks = with_chunks ? (obj + g.chunk_bytes - 1) / g.chunk_bytes : 0;
+    const uint32_t active = n_req - base < kWave ? n_req - base : kWave;  // requests of this pass
+    uint64_t inc_stage = 2 * obj, inc_sqe = 2 * chunks, inc_tab = n;
+    wave_inclusive_scan3(inc_stage, inc_sqe, inc_tab, lane, active);
     if (r < n_req) {
       const uint64_t stage_off = carry_stage + inc_stage - 2 * obj;
       const uint32_t sqe_base = static_cast<uint32_t>(carry_sqe + inc_sqe - 2 * chunks);
@@ -137,9 +150,9 @@ __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32
         ext_out[r] = e;
       }
     }
-    carry_stage += shfl_u64(inc_stage, kWave - 1);
-    carry_sqe += shfl_u64(inc_sqe, kWave - 1);
-    carry_tab += shfl_u64(inc_tab, kWave - 1);
+    carry_stage += shfl_u64(inc_stage, active - 1);  // the pass total sits in its last active lane
+    carry_sqe += shfl_u64(inc_sqe, active - 1);
+    carry_tab += shfl_u64(inc_tab, active - 1);
   }
   if (lane == 0) {
     l.table_off[n_req] = static_cast<uint32_t>(carry_tab);
@@ -202,48 +215,81 @@ struct SqeArgs {
   uint32_t sgl_id;
 };
 
-// Written by the `n_wgs` workgroups starting at workgroup `first_wg`.
+// Quarter `part` (16 bytes) of entry i, which belongs to request r whose file id is fid.
+__device__ __forceinline__ u32x4 sqe_quarter(const SqeArgs &a, const ReqLds &l, uint32_t r, uint32_t i, uint32_t part,
+                                             uint32_t fid) {
+  const uint32_t base = l.sqe_base[r];
+  const uint32_t n_chunks = (l.sqe_base[r + 1] - base) >> 1;
+  const uint32_t v = i - base;
+  const uint32_t kind = v >= n_chunks ? 1u : 0u;
+  const uint32_t c = v - kind * n_chunks;
+  const uint64_t obj = l.obj_bytes[r];
+  const uint64_t in_obj = static_cast<uint64_t>(c) * a.chunk_bytes;
+  u32x4 w = {0u, 0u, 0u, 0u};
+  if (part == 0) {
+    const uint64_t file_off = (2ull * a.layer + kind) * obj + in_obj;
+    w.x = (a.opcode & 0xffu) | (kind << 8) | (a.layer << 16);
+    w.y = fid;
+    w.z = static_cast<uint32_t>(file_off);
+    w.w = static_cast<uint32_t>(file_off >> 32);
+  } else if (part == 1) {
+    const uint64_t addr = a.stage_addr + l.stage_off[r] + kind * obj + in_obj;
+    const uint64_t left = obj - in_obj;
+    w.x = static_cast<uint32_t>(addr);
+    w.y = static_cast<uint32_t>(addr >> 32);
+    w.z = left < a.chunk_bytes ? static_cast<uint32_t>(left) : a.chunk_bytes;
+    w.w = a.sgl_id;
+  } else if (part == 2) {
+    w.x = i;
+    w.y = r;
+    w.z = i / TUTTI_IOCB_SLOTS;
+    w.w = i % TUTTI_IOCB_SLOTS;
+  }
+  return w;
+}
+
+// The entries of a layer are written by the `n_wgs` workgroups starting at workgroup `first_wg`, one lane per
+// quarter.  A workgroup that also moves blocks splits the job: sqe_head, right after the scan, finds the owner
+// of the lane's first quarter and requests its file id (the only value that comes from global memory);
+// emit_sqes, after the copy loop, assembles and stores, so the load's latency is spent under the copy.
+struct SqeHead {
+  uint64_t q;    // the lane's first quarter
+  uint32_t r;    // its request
+  uint32_t fid;  // file id of that request (quarter 0 only)
+  bool live;     // the lane has a first quarter
+};
+
+__device__ __forceinline__ SqeHead sqe_head(const SqeArgs a, const ReqLds l, uint32_t n_req, uint32_t first_wg) {
+  const uint32_t n_sqe = l.sqe_base[n_req];
+  const uint32_t n_write = n_sqe < a.sqe_cap ? n_sqe : a.sqe_cap;
+  SqeHead h;
+  h.q = static_cast<uint64_t>(blockIdx.x - first_wg) * blockDim.x + threadIdx.x;
+  h.live = h.q < 4ull * n_write;
+  h.r = 0;
+  h.fid = 0;
+  if (h.live) {
+    h.r = find_owner(l.sqe_base, n_req, static_cast<uint32_t>(h.q >> 2));
+    if ((h.q & 3) == 0) h.fid = a.file_id[h.r];
+  }
+  return h;
+}
+
 __device__ __forceinline__ void emit_sqes(const SqeArgs a, const ReqLds l, uint32_t n_req, uint32_t first_wg,
-                                          uint32_t n_wgs) {
+                                          uint32_t n_wgs, const SqeHead h) {
   const uint32_t n_sqe = l.sqe_base[n_req];
   const uint32_t n_write = n_sqe < a.sqe_cap ? n_sqe : a.sqe_cap;
   const uint32_t wg = blockIdx.x - first_wg;
   if (n_sqe > a.sqe_cap && wg == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
+  if (!h.live) return;
   const uint64_t n_quarters = 4ull * n_write;
   const uint64_t stride = static_cast<uint64_t>(n_wgs) * blockDim.x;
   u32x4 *out = reinterpret_cast<u32x4 *>(a.sqe);
-  for (uint64_t q = static_cast<uint64_t>(wg) * blockDim.x + threadIdx.x; q < n_quarters; q += stride) {
+  const uint32_t part = static_cast<uint32_t>(h.q & 3);  // the stride is a multiple of 4: the same quarter every pass
+  out[h.q] = sqe_quarter(a, l, h.r, static_cast<uint32_t>(h.q >> 2), part, h.fid);
+  for (uint64_t q = h.q + stride; q < n_quarters; q += stride) {
     const uint32_t i = static_cast<uint32_t>(q >> 2);
-    const uint32_t part = static_cast<uint32_t>(q & 3);
     const uint32_t r = find_owner(l.sqe_base, n_req, i);
-    const uint32_t base = l.sqe_base[r];
-    const uint32_t n_chunks = (l.sqe_base[r + 1] - base) >> 1;
-    const uint32_t v = i - base;
-    const uint32_t kind = v >= n_chunks ? 1u : 0u;
-    const uint32_t c = v - kind * n_chunks;
-    const uint64_t obj = l.obj_bytes[r];
-    const uint64_t in_obj = static_cast<uint64_t>(c) * a.chunk_bytes;
-    u32x4 w = {0u, 0u, 0u, 0u};
-    if (part == 0) {
-      const uint64_t file_off = (2ull * a.layer + kind) * obj + in_obj;
-      w.x = (a.opcode & 0xffu) | (kind << 8) | (a.layer << 16);
-      w.y = a.file_id[r];
-      w.z = static_cast<uint32_t>(file_off);
-      w.w = static_cast<uint32_t>(file_off >> 32);
-    } else if (part == 1) {
-      const uint64_t addr = a.stage_addr + l.stage_off[r] + kind * obj + in_obj;
-      const uint64_t left = obj - in_obj;
-      w.x = static_cast<uint32_t>(addr);
-      w.y = static_cast<uint32_t>(addr >> 32);
-      w.z = left < a.chunk_bytes ? static_cast<uint32_t>(left) : a.chunk_bytes;
-      w.w = a.sgl_id;
-    } else if (part == 2) {
-      w.x = i;
-      w.y = r;
-      w.z = i / TUTTI_IOCB_SLOTS;
-      w.w = i % TUTTI_IOCB_SLOTS;
-    }
-    out[q] = w;
+    out[q] = sqe_quarter(a, l, r, i, part, part == 0 ? a.file_id[r] : 0u);
   }
 }
 
@@ -353,25 +399,45 @@ __device__ __forceinline__ uint32_t advance_owner(const uint32_t *table_off, uin
 // starting at `first_wg` each take one contiguous run of entries (a whole number of 4 KiB workgroup stores), so a
 // thread's consecutive entries are 64 apart and their owner is found by walking on from the previous one: one
 // binary search per thread instead of one per entry.  The loop is pipelined by one entry: the table and file-id
-// loads of the next entry are issued before the current one is assembled and stored.  `dst(i)` gives the address
-// of entry i.
-template <typename Dst>
-__device__ __forceinline__ void emit_direct_entries(const SqeArgs a, const DirectArgs d, const ReqLds l, uint32_t n_req,
-                                                    uint64_t n_write, uint32_t first_wg, uint32_t n_wgs, Dst dst) {
+// loads of the next entry are issued before the current one is assembled and stored; the first entry's are issued
+// by direct_head, which a workgroup that also moves blocks calls before its copy loop.  `dst(i)` gives the
+// address of entry i.
+struct DirectHead {
+  uint64_t q, end;  // the lane's first quarter and the end of its workgroup's run
+  DirectLoc loc;    // that quarter's entry, located, with its loads requested
+  bool live;
+};
+
+__device__ __forceinline__ DirectHead direct_head(const SqeArgs a, const DirectArgs d, const ReqLds l, uint32_t n_req,
+                                                  uint64_t n_write, uint32_t first_wg, uint32_t n_wgs) {
   const uint64_t n_quarters = 4ull * n_write;
   const uint64_t per_pass = blockDim.x;  // quarters one workgroup writes per pass: 4 KiB for 256 threads
   const uint64_t passes = (n_quarters + per_pass * n_wgs - 1) / (per_pass * n_wgs);
   const uint64_t begin = static_cast<uint64_t>(blockIdx.x - first_wg) * passes * per_pass;
-  uint64_t end = begin + passes * per_pass;
-  if (end > n_quarters) end = n_quarters;
-  uint64_t q = begin + threadIdx.x;
-  if (q >= end) return;
+  DirectHead h;
+  h.end = begin + passes * per_pass;
+  if (h.end > n_quarters) h.end = n_quarters;
+  h.q = begin + threadIdx.x;
+  h.live = h.q < h.end;
+  if (h.live) {
+    const uint32_t i = static_cast<uint32_t>(h.q >> 2);
+    h.loc = direct_locate(a, d, l, find_owner(l.table_off, n_req, i >> 1), i, static_cast<uint32_t>(h.q & 3));
+  }
+  return h;
+}
+
+template <typename Dst>
+__device__ __forceinline__ void emit_direct_entries(const SqeArgs a, const DirectArgs d, const ReqLds l, uint32_t n_req,
+                                                    const DirectHead h, Dst dst) {
+  if (!h.live) return;
+  const uint64_t per_pass = blockDim.x;
+  uint64_t q = h.q;
   uint32_t i = static_cast<uint32_t>(q >> 2);
   const uint32_t part = static_cast<uint32_t>(q & 3);  // per_pass is a multiple of 4: the same quarter every pass
-  DirectLoc cur = direct_locate(a, d, l, find_owner(l.table_off, n_req, i >> 1), i, part);
+  DirectLoc cur = h.loc;
   for (;;) {
     const uint64_t qn = q + per_pass;
-    const bool more = qn < end;
+    const bool more = qn < h.end;
     const uint32_t in = static_cast<uint32_t>(qn >> 2);
     DirectLoc nxt = cur;
     if (more) nxt = direct_locate(a, d, l, advance_owner(l.table_off, n_req, cur.r, in >> 1), in, part);
@@ -391,7 +457,8 @@ __device__ __forceinline__ void emit_direct_sqes(const SqeArgs a, const DirectAr
   const uint64_t n_write = n_sqe < a.sqe_cap ? n_sqe : a.sqe_cap;
   if (n_sqe > a.sqe_cap && blockIdx.x == 0 && threadIdx.x == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
   tutti_sqe *out = a.sqe;
-  emit_direct_entries(a, d, l, n_req, n_write, 0, gridDim.x, [out](uint32_t i) { return out + i; });
+  emit_direct_entries(a, d, l, n_req, direct_head(a, d, l, n_req, n_write, 0, gridDim.x),
+                      [out](uint32_t i) { return out + i; });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -421,12 +488,23 @@ struct RingArgs {
 };
 
 // Contexts of one layer dealt into IOCBs (see emit_direct_sqes for the entry itself), plus the headers, by the
-// `n_wgs` workgroups starting at workgroup `first_wg`.
-__device__ __forceinline__ void emit_iocbs(const RingArgs g, const SqeArgs a, const DirectArgs d, const ReqLds l,
-                                           uint32_t n_req, uint32_t first_wg, uint32_t n_wgs) {
+// `n_wgs` workgroups starting at workgroup `first_wg`: iocb_head before a copy loop, emit_iocbs after it.
+__device__ __forceinline__ uint64_t iocb_fill_count(const RingArgs &g, const ReqLds &l, uint32_t n_req) {
   const uint64_t n_ctx = 2ull * l.table_off[n_req];
   const uint64_t cap = static_cast<uint64_t>(g.n_slots) * TUTTI_IOCB_SLOTS;
-  const uint64_t n_fill = n_ctx < cap ? n_ctx : cap;
+  return n_ctx < cap ? n_ctx : cap;
+}
+
+__device__ __forceinline__ DirectHead iocb_head(const RingArgs g, const SqeArgs a, const DirectArgs d, const ReqLds l,
+                                                uint32_t n_req, uint32_t first_wg, uint32_t n_wgs) {
+  return direct_head(a, d, l, n_req, iocb_fill_count(g, l, n_req), first_wg, n_wgs);
+}
+
+__device__ __forceinline__ void emit_iocbs(const RingArgs g, const SqeArgs a, const DirectArgs d, const ReqLds l,
+                                           uint32_t n_req, uint32_t first_wg, uint32_t n_wgs, const DirectHead h) {
+  const uint64_t n_ctx = 2ull * l.table_off[n_req];
+  const uint64_t cap = static_cast<uint64_t>(g.n_slots) * TUTTI_IOCB_SLOTS;
+  const uint64_t n_fill = iocb_fill_count(g, l, n_req);
   const uint64_t tid = static_cast<uint64_t>(blockIdx.x - first_wg) * blockDim.x + threadIdx.x;
   if (n_ctx > cap && tid == 0 && a.status) atomicOr(a.status, TUTTI_ST_SQE_CAP);
   const uint64_t stride = static_cast<uint64_t>(n_wgs) * blockDim.x;
@@ -434,15 +512,15 @@ __device__ __forceinline__ void emit_iocbs(const RingArgs g, const SqeArgs a, co
     const uint64_t lo = b * TUTTI_IOCB_SLOTS;
     uint64_t cnt = n_fill > lo ? n_fill - lo : 0;
     if (cnt > TUTTI_IOCB_SLOTS) cnt = TUTTI_IOCB_SLOTS;
-    tutti_iocb_hdr *h = &g.sq[(g.first_slot + b) % g.depth].hdr;
-    h->num_ioctx = static_cast<uint32_t>(cnt);
-    h->state = TUTTI_IOCB_FILLED;
-    h->done = 0;
-    h->layer = a.layer;
-    h->opcode = a.opcode;
+    tutti_iocb_hdr *hd = &g.sq[(g.first_slot + b) % g.depth].hdr;
+    hd->num_ioctx = static_cast<uint32_t>(cnt);
+    hd->state = TUTTI_IOCB_FILLED;
+    hd->done = 0;
+    hd->layer = a.layer;
+    hd->opcode = a.opcode;
   }
   const RingArgs ring = g;
-  emit_direct_entries(a, d, l, n_req, n_fill, first_wg, n_wgs, [ring](uint32_t i) {
+  emit_direct_entries(a, d, l, n_req, h, [ring](uint32_t i) {
     return &ring.sq[(ring.first_slot + i / TUTTI_IOCB_SLOTS) % ring.depth].ioctx[i % TUTTI_IOCB_SLOTS];
   });
 }
@@ -452,7 +530,7 @@ __global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, cons
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
   lds_from_extents(ext, n_req, l);
-  emit_iocbs(g, a, d, l, n_req, 0, gridDim.x);
+  emit_iocbs(g, a, d, l, n_req, 0, gridDim.x, iocb_head(g, a, d, l, n_req, 0, gridDim.x));
 }
 
 struct IoArgs {
@@ -473,7 +551,7 @@ struct IoArgs {
 // atomics on the IOCB header serialises on one address (measured: 1.5 ms per 4096-context layer instead
 // of 55 us), and a kernel boundary already is the "all contexts done" event.
 template <int U, int WG>
-__global__ __launch_bounds__(WG) void k_issue_io(const RingArgs g, const IoArgs a) {
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_issue_io(const RingArgs g, const IoArgs a) {
   constexpr uint32_t kSlice = kWave * 16u * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave_in_wg = rfl(threadIdx.x / kWave);
@@ -638,8 +716,8 @@ struct MoveArgs {
 constexpr uint64_t kNoFile = ~0ull;
 
 // The workgroup index used for item numbering (see MoveArgs::xcd_contiguous).
-__device__ __forceinline__ uint32_t item_wg(const MoveArgs &a, uint32_t copy_wgs) {
-  const uint32_t b = blockIdx.x;
+__device__ __forceinline__ uint32_t item_wg(const MoveArgs &a, uint32_t wg, uint32_t copy_wgs) {
+  const uint32_t b = wg;  // index among the copy workgroups
   if (!a.xcd_contiguous || copy_wgs < 16u) return b;
   const uint32_t per = copy_wgs / 8u;            // workgroups per XCD (the remainder keeps its own index)
   if (b >= per * 8u) return b;
@@ -788,10 +866,10 @@ struct Preload {
 };
 
 template <int U, int NT>
-__device__ __forceinline__ Preload<U> preload_first(const MoveArgs &a, uint32_t copy_wgs) {
+__device__ __forceinline__ Preload<U> preload_first(const MoveArgs &a, uint32_t wg, uint32_t copy_wgs) {
   constexpr uint32_t kSlice = kWave * 16u * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t it = item_wg(a, copy_wgs) * (blockDim.x / kWave) + rfl(threadIdx.x / kWave);
+  const uint32_t it = item_wg(a, wg, copy_wgs) * (blockDim.x / kWave) + rfl(threadIdx.x / kWave);
   Preload<U> p;
   p.valid = a.dense != 0 && it < a.items_bound && (static_cast<uint64_t>(it) + 1) * kSlice <= a.stage_cap;
   if (p.valid) {
@@ -821,12 +899,13 @@ __device__ __forceinline__ void store_preloaded(const MoveArgs &a, const Item &d
   }
 }
 
-// The copy loop of the first `copy_wgs` workgroups of the grid (the rest, if any, have other work).
+// The copy loop of the `copy_wgs` copy workgroups of the grid; `wg` is this workgroup's index among them (the
+// grid may hold other workgroups with other work).
 // Software-pipelined by one item: the next item is decoded and its block id requested before the
 // current item's loads and stores are issued.
 template <int DIR, bool HND, int U, int NT>
-__device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t copy_wgs,
-                                           const Preload<U> &pre) {
+__device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t wg,
+                                           uint32_t copy_wgs, const Preload<U> &pre) {
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const uint32_t n_waves = copy_wgs * (blockDim.x / kWave);
@@ -834,7 +913,7 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
   const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
   const uint32_t n_items = 2u * total_blocks * a.slices_per_block;  // the host checked this fits 32 bits
 
-  uint32_t it = item_wg(a, copy_wgs) * (blockDim.x / kWave) + wave_in_wg;
+  uint32_t it = item_wg(a, wg, copy_wgs) * (blockDim.x / kWave) + wave_in_wg;
   if (it >= n_items) return;
   Item cur = decode_item(a, l, n_req, it, lane);
   uint32_t id = load_block_id(a, cur);
@@ -936,11 +1015,11 @@ struct TileMove {
   }
 };
 
-// One tile per workgroup and iteration, software-pipelined by one item: the global loads of the next tile are
-// issued right after the barrier that publishes the current tile in LDS, so they are in flight while the
-// current tile is read back in the other order and stored.
+// One tile per workgroup and iteration.  Not pipelined across tiles: holding the next tile's loads in
+// registers cost the eighth resident workgroup per CU (more than 64 VGPRs) and bought 0.3 us; the eight
+// workgroups of a CU cover each other's latency instead.
 template <int DIR, int PT, int WG>
-__device__ __forceinline__ void move_items_hnd_lds(const MoveArgs a, const ReqLds l, uint32_t n_req,
+__device__ __forceinline__ void move_items_hnd_lds(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t wg,
                                                    uint32_t copy_wgs, unsigned char *tile) {
   typedef TileMove<DIR, PT, WG> TM;
   const uint32_t tid = threadIdx.x;
@@ -954,46 +1033,24 @@ __device__ __forceinline__ void move_items_hnd_lds(const MoveArgs a, const ReqLd
   g.hr_mask = (1u << g.hr) - 1u;
   g.r_mask = (1u << g.rs) - 1u;
 
-  uint32_t it = blockIdx.x;
-  if (it >= n_items) return;
-  Item cur = decode_item(a, l, n_req, it, tid);  // workgroup-uniform; thread 0 reports
-  uint32_t id = load_block_id(a, cur);
-  bool ok = cur.obj_ptr != nullptr && id < a.num_blocks;
-  u32x4 v[PT];
-  if (ok) TM::load(a, g, cur, id, tid, v);
-  for (;;) {
-    const uint32_t nit = it + copy_wgs;
-    const bool more = nit < n_items;
-    Item nxt = cur;
-    uint32_t nid = a.num_blocks;
-    bool nok = false;
-    if (more) {
-      nxt = decode_item(a, l, n_req, nit, tid);
-      nid = load_block_id(a, nxt);
-      nok = nxt.obj_ptr != nullptr && nid < a.num_blocks;
-    }
-    if (ok) TM::to_lds(a, g, tid, tile, v);
-    __syncthreads();
-    u32x4 v2[PT];
-    if (nok) TM::load(a, g, nxt, nid, tid, v2);
-    if (ok) {
-      TM::from_lds_and_store(a, g, cur, id, tid, tile);
-    } else if (cur.obj_ptr != nullptr && tid == 0 && cur.s == 0 && a.status) {
+  for (uint32_t it = wg; it < n_items; it += copy_wgs) {
+    const Item d = decode_item(a, l, n_req, it, tid);  // workgroup-uniform; thread 0 reports
+    const uint32_t id = load_block_id(a, d);
+    if (d.obj_ptr != nullptr && id < a.num_blocks) {
+      u32x4 v[PT];
+      TM::load(a, g, d, id, tid, v);
+      TM::to_lds(a, g, tid, tile, v);
+      __syncthreads();
+      TM::from_lds_and_store(a, g, d, id, tid, tile);
+      __syncthreads();  // the tile is free again
+    } else if (d.obj_ptr != nullptr && tid == 0 && d.s == 0 && a.status) {
       atomicOr(a.status, TUTTI_ST_BAD_BLOCK);
     }
-    __syncthreads();  // the tile is free again
-    if (DIR == kPack && cur.obj_ptr != nullptr && cur.j + 1 == cur.n && cur.s + 1 == a.slices_per_block) {
-      const uint64_t used = static_cast<uint64_t>(cur.n) * a.block_bytes;
+    if (DIR == kPack && d.obj_ptr != nullptr && d.j + 1 == d.n && d.s + 1 == a.slices_per_block) {
+      const uint64_t used = static_cast<uint64_t>(d.n) * a.block_bytes;
       const u32x4 zero = {0u, 0u, 0u, 0u};
-      for (uint64_t o = used + tid * 16ull; o < cur.obj_bytes; o += WG * 16ull) st16<0>(cur.obj_ptr + o, zero);
+      for (uint64_t o = used + tid * 16ull; o < d.obj_bytes; o += WG * 16ull) st16<0>(d.obj_ptr + o, zero);
     }
-    if (!more) break;
-    cur = nxt;
-    id = nid;
-    ok = nok;
-    it = nit;
-#pragma unroll
-    for (int k = 0; k < PT; ++k) v[k] = v2[k];
   }
 }
 
@@ -1018,58 +1075,71 @@ __global__ __launch_bounds__(kWgThreads) void k_sqe(const SqeArgs a, const tutti
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
   lds_from_extents(ext, n_req, l);
-  emit_sqes(a, l, n_req, 0, gridDim.x);
+  emit_sqes(a, l, n_req, 0, gridDim.x, sqe_head(a, l, n_req, 0));
 }
 
 template <int DIR, bool HND, int U, int NT, int WG>
-__global__ __launch_bounds__(WG) void k_move(const MoveArgs a, const tutti_extent *__restrict__ ext,
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_move(const MoveArgs a, const tutti_extent *__restrict__ ext,
                                                       uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
   Preload<U> pre;
   pre.valid = false;
-  if (DIR == kUnpack) pre = preload_first<U, NT>(a, gridDim.x);
+  if (DIR == kUnpack) pre = preload_first<U, NT>(a, blockIdx.x, gridDim.x);
   lds_from_extents(ext, n_req, l);
-  move_items<DIR, HND, U, NT>(a, l, n_req, gridDim.x, pre);
+  move_items<DIR, HND, U, NT>(a, l, n_req, blockIdx.x, gridDim.x, pre);
 }
 
 template <int DIR, int PT, int WG>
-__global__ __launch_bounds__(WG) void k_move_lds(const MoveArgs a, const tutti_extent *__restrict__ ext,
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, PT)) void k_move_lds(const MoveArgs a, const tutti_extent *__restrict__ ext,
                                                   uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
   lds_from_extents(ext, n_req, l);
-  move_items_hnd_lds<DIR, PT, WG>(a, l, n_req, gridDim.x, smem + align16(req_lds_bytes(n_req)));
+  move_items_hnd_lds<DIR, PT, WG>(a, l, n_req, blockIdx.x, gridDim.x, smem + align16(req_lds_bytes(n_req)));
 }
 
 // One layer's restore (DIR = kUnpack) or save (DIR = kPack) in one launch: every workgroup redoes the
-// (tiny) scan into its own LDS with its first wavefront.  The first `copy_wgs` workgroups move the
-// blocks; the last `sqe_wgs` workgroups of the grid write the entries, and the very last one also
-// publishes extents and totals.  A whole-GPU launch adds the entry writers behind the copy workgroups
-// so no bookkeeping sits in front of the copy; a CU-budgeted launch has no workgroup to spare and
-// its last workgroup does both jobs.
+// (tiny) scan into its own LDS with its first wavefront.  The workgroups [copy_first, copy_first + copy_wgs)
+// move the blocks; the first `sqe_wgs` workgroups of the grid also (or only) write the entries, one quarter per
+// lane, and workgroup 0 publishes extents and totals.  The copy workgroups are persistent and split the items
+// evenly, so the kernel ends when its slowest workgroup does: a workgroup with extra work in front of or behind
+// its share, or one that has to wait for a free slot because the grid is larger than what the chip holds at
+// once, adds that work's latency to the whole kernel (measured: 2.4 us of 53 with the entry writers as extra
+// workgroups behind a full grid).  So the entries ride along: an entry-writing workgroup finds its quarter's
+// request and asks for the file id right after the scan, runs its share of the copy, and only then assembles
+// and stores the entry; with enough entries every workgroup of the grid takes one pass of them.
+struct Roles {
+  uint32_t sqe_wgs;     // workgroups [0, sqe_wgs) write entries
+  uint32_t copy_first;  // workgroups [copy_first, copy_first + copy_wgs) move blocks (the grid may be larger when
+  uint32_t copy_wgs;    // there are more passes of entries than copy workgroups)
+};
+
 template <int DIR, bool HND, int U, int NT, int WG>
-__global__ __launch_bounds__(WG) void k_layer(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
-                                               uint32_t copy_wgs, uint32_t sqe_wgs) {
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer(const MoveArgs m, const SqeArgs q, const LayoutArgs a, const Roles w) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
+  const uint32_t wg = blockIdx.x - w.copy_first;  // wraps for the workgroups in front of the copy ones
+  const bool copies = wg < w.copy_wgs;
   Preload<U> pre;
   pre.valid = false;
-  if (DIR == kUnpack && blockIdx.x < copy_wgs) pre = preload_first<U, NT>(m, copy_wgs);  // in flight during the scan
+  if (DIR == kUnpack && copies) pre = preload_first<U, NT>(m, wg, w.copy_wgs);  // in flight during the scan
   if (threadIdx.x < kWave) {
-    const bool publish = blockIdx.x + 1 == gridDim.x;
+    const bool publish = blockIdx.x == 0;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
-                      publish ? a.totals : nullptr);
+                      publish ? a.totals : nullptr, blockIdx.x < w.sqe_wgs);
   }
   __syncthreads();
-  const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
-  if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
-  if (blockIdx.x < copy_wgs) move_items<DIR, HND, U, NT>(m, l, a.n_req, copy_wgs, pre);
+  SqeHead head;
+  head.live = false;
+  if (blockIdx.x < w.sqe_wgs) head = sqe_head(q, l, a.n_req, 0);
+  if (copies) move_items<DIR, HND, U, NT>(m, l, a.n_req, wg, w.copy_wgs, pre);
+  if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
 // retrieve_layer / store_layer through the rings in one launch (direct-to-block mode): scan, then the start
-// of every request's file in the store goes where the staging offsets were, then the last `fill_wgs`
-// workgroups record the layer's contexts in the IOCBs while the first `copy_wgs` move the very same blocks,
+// of every request's file in the store goes where the staging offsets were, then the first `sqe_wgs`
+// workgroups record the layer's contexts in the IOCBs while the copy workgroups move the very same blocks,
 // each item deriving its file offset and block from the extents and the table exactly as its context does.
 // Blocks go to the file as they sit in the pool (a descriptor names raw bytes), so there is no head-major case.
 struct FileArgs {
@@ -1079,15 +1149,15 @@ struct FileArgs {
 };
 
 template <int DIR, int U, int WG>
-__global__ __launch_bounds__(WG) void k_layer_ring(const MoveArgs m, const SqeArgs q, const DirectArgs d,
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(const MoveArgs m, const SqeArgs q, const DirectArgs d,
                                                     const RingArgs g, const FileArgs f, const LayoutArgs a,
-                                                    uint32_t copy_wgs, uint32_t fill_wgs) {
+                                                    const Roles w) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
   if (threadIdx.x < kWave) {
-    const bool publish = blockIdx.x + 1 == gridDim.x;
+    const bool publish = blockIdx.x == 0;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
-                      publish ? a.totals : nullptr);
+                      publish ? a.totals : nullptr, publish);  // chunk counts only matter for the published extents
   }
   __syncthreads();
   for (uint32_t r = threadIdx.x; r < a.n_req; r += blockDim.x) {
@@ -1096,33 +1166,38 @@ __global__ __launch_bounds__(WG) void k_layer_ring(const MoveArgs m, const SqeAr
     l.stage_off[r] = (fid >= f.first_file_id && rel < f.n_files) ? static_cast<uint64_t>(rel) * f.file_stride : kNoFile;
   }
   __syncthreads();
-  const uint32_t first_fill_wg = gridDim.x - fill_wgs;
-  if (blockIdx.x >= first_fill_wg) emit_iocbs(g, q, d, l, a.n_req, first_fill_wg, fill_wgs);
+  DirectHead head;
+  head.live = false;
+  if (blockIdx.x < w.sqe_wgs) head = iocb_head(g, q, d, l, a.n_req, 0, w.sqe_wgs);
   Preload<U> pre;
   pre.valid = false;
-  if (blockIdx.x < copy_wgs) move_items<DIR, false, U, 3>(m, l, a.n_req, copy_wgs, pre);
+  if (blockIdx.x - w.copy_first < w.copy_wgs)
+    move_items<DIR, false, U, 3>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs, pre);
+  if (blockIdx.x < w.sqe_wgs) emit_iocbs(g, q, d, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
 template <int DIR, int PT, int WG>
-__global__ __launch_bounds__(WG) void k_layer_lds(const MoveArgs m, const SqeArgs q, const LayoutArgs a,
-                                                   uint32_t copy_wgs, uint32_t sqe_wgs) {
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, PT)) void k_layer_lds(const MoveArgs m, const SqeArgs q, const LayoutArgs a, const Roles w) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
   if (threadIdx.x < kWave) {
-    const bool publish = blockIdx.x + 1 == gridDim.x;
+    const bool publish = blockIdx.x == 0;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
-                      publish ? a.totals : nullptr);
+                      publish ? a.totals : nullptr, blockIdx.x < w.sqe_wgs);
   }
   __syncthreads();
-  const uint32_t first_sqe_wg = gridDim.x - sqe_wgs;
-  if (blockIdx.x >= first_sqe_wg) emit_sqes(q, l, a.n_req, first_sqe_wg, sqe_wgs);
-  if (blockIdx.x < copy_wgs)
-    move_items_hnd_lds<DIR, PT, WG>(m, l, a.n_req, copy_wgs, smem + align16(req_lds_bytes(a.n_req)));
+  SqeHead head;
+  head.live = false;
+  if (blockIdx.x < w.sqe_wgs) head = sqe_head(q, l, a.n_req, 0);
+  if (blockIdx.x - w.copy_first < w.copy_wgs)
+    move_items_hnd_lds<DIR, PT, WG>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs,
+                                    smem + align16(req_lds_bytes(a.n_req)));
+  if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
 // Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.
 template <int U, int NT, int WG>
-__global__ __launch_bounds__(WG) void k_copy(unsigned char *__restrict__ dst,
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_copy(unsigned char *__restrict__ dst,
                                                       const unsigned char *__restrict__ src, uint64_t bytes) {
   constexpr uint64_t kSlice = kWave * 16ull * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -1152,7 +1227,7 @@ __global__ __launch_bounds__(WG) void k_copy(unsigned char *__restrict__ dst,
 constexpr uint32_t kFillTag = 0x54555454u;
 
 template <int WRITE, int U, int WG>
-__global__ __launch_bounds__(WG) void k_stream(unsigned char *__restrict__ buf, uint64_t bytes, uint32_t *__restrict__ xor4) {
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_stream(unsigned char *__restrict__ buf, uint64_t bytes, uint32_t *__restrict__ xor4) {
   constexpr uint64_t kSlice = kWave * 16ull * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint64_t n_waves = static_cast<uint64_t>(gridDim.x) * (blockDim.x / kWave);
@@ -1207,7 +1282,7 @@ __global__ __launch_bounds__(WG) void k_stream(unsigned char *__restrict__ buf, 
 
 // The copy with one side permuted at `gran` bytes: the memory system's own cost of the scatter.
 template <int U, int WG>
-__global__ __launch_bounds__(WG) void k_scatter(unsigned char *__restrict__ scattered, uint64_t span_bytes,
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_scatter(unsigned char *__restrict__ scattered, uint64_t span_bytes,
                                                  unsigned char *__restrict__ contig, uint64_t bytes,
                                                  const uint32_t *__restrict__ perm, uint32_t gran, uint32_t to_scattered) {
   constexpr uint32_t kSlice = kWave * 16u * U;  // gran is a multiple of 4096 and of kSlice (host-checked)
