@@ -108,6 +108,15 @@ __device__ __forceinline__ void wave_inclusive_scan3(uint64_t &a, uint64_t &b, u
   }
 }
 
+// The file store of the direct-to-block mode: file f at base + (f - first_file_id)*file_stride.
+struct FileArgs {
+  uint64_t file_stride;
+  uint32_t first_file_id;
+  uint32_t n_files;
+};
+
+constexpr uint64_t kNoFile = ~0ull;
+
 struct ScanGeom {
   uint32_t block_bytes;
   uint32_t align;       // power of two
@@ -119,11 +128,16 @@ struct ScanGeom {
 // carried between passes.  Results go to LDS and, when ext_out != nullptr, to global memory.
 __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32_t *__restrict__ n_blocks, uint32_t n_req,
                                                   uint32_t lane, ReqLds l, tutti_extent *__restrict__ ext_out,
-                                                  uint64_t *__restrict__ totals_out, bool with_chunks = true) {
+                                                  uint64_t *__restrict__ totals_out, bool with_chunks = true,
+                                                  const uint32_t *__restrict__ file_id = nullptr,
+                                                  const FileArgs files = FileArgs{0, 0, 0}) {
   uint64_t carry_stage = 0, carry_sqe = 0, carry_tab = 0;
   for (uint32_t base = 0; base < n_req; base += kWave) {
     const uint32_t r = base + lane;
     const uint32_t n = (r < n_req) ? n_blocks[r] : 0u;
+    // direct-to-block mode: the per-request slot that holds the staging offset holds the start of the request's
+    // file in the store instead (kNoFile if the store has no such file); the published extents are unaffected
+    const uint32_t fid = (file_id && r < n_req) ? file_id[r] : 0u;
     const uint64_t raw = static_cast<uint64_t>(n) * g.block_bytes;
     const uint64_t obj = (raw + (g.align - 1)) & ~static_cast<uint64_t>(g.align - 1);
     // a workgroup that only moves blocks never reads the entry bases: it skips the 64-bit division
@@ -135,7 +149,9 @@ __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32
       const uint64_t stage_off = carry_stage + inc_stage - 2 * obj;
       const uint32_t sqe_base = static_cast<uint32_t>(carry_sqe + inc_sqe - 2 * chunks);
       const uint32_t table_off = static_cast<uint32_t>(carry_tab + inc_tab - n);
-      l.stage_off[r] = stage_off;
+      const uint32_t rel = fid - files.first_file_id;
+      const bool has_file = fid >= files.first_file_id && rel < files.n_files;
+      l.stage_off[r] = !file_id ? stage_off : has_file ? static_cast<uint64_t>(rel) * files.file_stride : kNoFile;
       l.obj_bytes[r] = obj;
       l.table_off[r] = table_off;
       l.sqe_base[r] = sqe_base;
@@ -713,7 +729,6 @@ struct MoveArgs {
   uint64_t ctx_cap;
 };
 
-constexpr uint64_t kNoFile = ~0ull;
 
 // The workgroup index used for item numbering (see MoveArgs::xcd_contiguous).
 __device__ __forceinline__ uint32_t item_wg(const MoveArgs &a, uint32_t wg, uint32_t copy_wgs) {
@@ -1137,17 +1152,11 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer(const M
   if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
-// retrieve_layer / store_layer through the rings in one launch (direct-to-block mode): scan, then the start
-// of every request's file in the store goes where the staging offsets were, then the first `sqe_wgs`
+// retrieve_layer / store_layer through the rings in one launch (direct-to-block mode): the scan puts the start
+// of every request's file in the store where the staging offsets would be, then the first `sqe_wgs`
 // workgroups record the layer's contexts in the IOCBs while the copy workgroups move the very same blocks,
 // each item deriving its file offset and block from the extents and the table exactly as its context does.
 // Blocks go to the file as they sit in the pool (a descriptor names raw bytes), so there is no head-major case.
-struct FileArgs {
-  uint64_t file_stride;
-  uint32_t first_file_id;
-  uint32_t n_files;
-};
-
 template <int DIR, int U, int WG>
 __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(const MoveArgs m, const SqeArgs q, const DirectArgs d,
                                                     const RingArgs g, const FileArgs f, const LayoutArgs a,
@@ -1156,14 +1165,9 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(co
   const ReqLds l = carve_lds(smem, a.n_req);
   if (threadIdx.x < kWave) {
     const bool publish = blockIdx.x == 0;
+    // chunk counts only matter for the published extents; the LDS copy gets file starts instead of staging offsets
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
-                      publish ? a.totals : nullptr, publish);  // chunk counts only matter for the published extents
-  }
-  __syncthreads();
-  for (uint32_t r = threadIdx.x; r < a.n_req; r += blockDim.x) {
-    const uint32_t fid = q.file_id[r];
-    const uint32_t rel = fid - f.first_file_id;
-    l.stage_off[r] = (fid >= f.first_file_id && rel < f.n_files) ? static_cast<uint64_t>(rel) * f.file_stride : kNoFile;
+                      publish ? a.totals : nullptr, publish, q.file_id, f);
   }
   __syncthreads();
   DirectHead head;
