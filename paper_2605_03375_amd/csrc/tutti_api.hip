@@ -520,7 +520,11 @@ int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t 
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;
   L.grid = G.grid;
-  const uint64_t entry_quarters = 4ull * sqe_cap;  // one lane per 16-byte quarter of an entry
+  // one lane per 16-byte quarter of an entry; no more entries than the capacity, nor than the table can give
+  // (every request has at most obj/chunk + 1 chunks per object, and obj < blocks*block_bytes + align <= ... + chunk)
+  uint64_t max_entries = 2ull * ((static_cast<uint64_t>(table_len) * bb) / cfg->chunk_bytes + 2ull * n_req);
+  if (max_entries > sqe_cap) max_entries = sqe_cap;
+  const uint64_t entry_quarters = 4ull * max_entries;
 
   const SqeArgs q = sqe_args(d_file_id, d_sqe, d_status, stage_addr, sqe_cap, cfg->chunk_bytes, layer,
                              (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE, sgl_id);
