@@ -3,18 +3,18 @@
 // Kernels
 //   k_layout        one wavefront: extents of all requests by a wave-level prefix scan
 //   k_sqe           submission entries from extents, four lanes per 64-byte entry
-//   k_sgl_table     the pool's mapping table: one 16-byte descriptor per block
-//   k_sqe_direct    one entry per (hit block, K|V), naming the block's descriptor: no staging copy
-//   k_ring_init / k_iocb_fill / k_issue_io / k_cq_check   SQ/CQ rings: fill IOCBs, execute them, report
 //   k_move          pack / unpack between paged blocks and objects, extents given
-//   k_move_lds      the same for head-major pools with short rows: token-tile transposed in LDS
+//   k_move_lds      the same for head-major pools with short rows: token tile transposed in LDS
 //   k_layer         one layer's restore (or save) in one launch: scan + entries + unpack (or pack)
 //   k_layer_lds     the same with the LDS-staged transpose
+//   k_sgl_table     direct-to-block mode: the pool's mapping table, one 16-byte descriptor per block
+//   k_sqe_direct    one entry per (hit block, K|V), naming the block's descriptor: no staging copy
+//   k_ring_init, k_iocb_fill, k_issue_io, k_complete, k_cq_check
+//                   SQ/CQ rings: IOCBs filled by the GPU, the entry-driven I/O kernel, completions
+//   k_layer_ring    one layer through the rings in one launch: scan + IOCB fill + the blocks' I/O
 //   k_copy          plain contiguous copy with the same access shape (measurement ceiling)
 //   k_stream        read-only or write-only stream with the same access shape (per-CU and chip limits)
-//   k_scatter       the copy with one side permuted at a given granularity (measurement floor)
-//   k_sgl_table, k_sqe_direct, k_ring_init, k_iocb_fill, k_issue_io, k_complete, k_cq_check, k_layer_ring
-//                   direct-to-block mode: mapping table, per-block entries, rings, the entry-driven I/O kernel
+//   k_scatter       the copy with one side permuted at a given granularity (what the pattern itself costs)
 //
 // Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
 // the scan), then walks work items with a persistent grid-stride loop, so the grid can be any
