@@ -324,6 +324,13 @@ int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_conti
 const char *tutti_strerror(int code);
 int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */
 int tutti_cu_count(void);           /* compute units of the current device, or a negative TUTTI_E* */
+/* How many 256-thread workgroups of a data-moving kernel one compute unit holds at once, as the runtime's
+ * occupancy calculator sees it (default instantiation, single-request launch).  The whole-GPU grids are sized for
+ * 8; fewer would leave part of a persistent grid waiting behind the rest.  which: 0 / 1 fused restore / save,
+ * 2 / 3 unpack / pack alone, 4 / 5 retrieve / store through the rings, 6 / 7 fused restore / save of a head-major
+ * pool, 8 / 9 the same through LDS (with a full tile), 10 the entry-driven I/O kernel.  Returns the count or a
+ * negative TUTTI_E*. */
+int tutti_resident_wgs_per_cu(uint32_t which);
 uint32_t tutti_version(void);       /* 0x00MMmmpp */
 /* sizeof / offsetof table of the records above (52 values: extent size + 6 offsets, sqe size + 11,
  * pool size + 9, objcfg size + 3, sgl size + 3, iocb_hdr size + 6, iocb size + offset of its contexts,

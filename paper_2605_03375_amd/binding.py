@@ -39,7 +39,7 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_layer_save",
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
            "tutti_issue_io", "tutti_wait_cqe", "tutti_retrieve_layer", "tutti_store_layer",
-           "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_version",
+           "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_resident_wgs_per_cu", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]
 
 
@@ -139,6 +139,8 @@ def lib():
         L.tutti_set_tuning.argtypes = [u32, u32]
         L.tutti_set_nontemporal.argtypes = [u32]
         L.tutti_set_hnd_mode.argtypes = [u32]
+        L.tutti_resident_wgs_per_cu.argtypes = [u32]
+        L.tutti_resident_wgs_per_cu.restype = C.c_int
         L.tutti_set_xcd_mapping.argtypes = [u32]
         L.tutti_set_xcd_mapping.restype = C.c_int
         for name in ("tutti_ring_init", "tutti_iocb_fill_direct", "tutti_issue_io", "tutti_wait_cqe",
@@ -316,6 +318,13 @@ def tutti_strerror(code):
 
 def tutti_last_hip_error():
     return lib().tutti_last_hip_error()
+
+
+def tutti_resident_wgs_per_cu(which):
+    n = lib().tutti_resident_wgs_per_cu(int(which))
+    if n < 0:
+        raise TuttiError("tutti_resident_wgs_per_cu", n)
+    return n
 
 
 def tutti_cu_count():

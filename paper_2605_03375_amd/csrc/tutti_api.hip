@@ -956,6 +956,30 @@ const char *tutti_strerror(int code) {
 
 int tutti_last_hip_error(void) { return t_last_hip; }
 
+int tutti_resident_wgs_per_cu(uint32_t which) {
+  // the default (unroll 4, non-temporal, 256-thread) instantiation of each data-moving kernel, with the dynamic LDS
+  // of a single-request launch (and a full 16 KiB tile + padding for the LDS-staged kernels)
+  const uint32_t lds = req_lds_bytes(1);
+  const uint32_t lds_tile = align16(lds) + kHndTileCap + kHndTileCap / 8;
+  int n = 0;
+  hipError_t e;
+  switch (which) {
+    case 0: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer<kUnpack, false, 4, 3, kWgThreads>, kWgThreads, lds); break;
+    case 1: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer<kPack, false, 4, 3, kWgThreads>, kWgThreads, lds); break;
+    case 2: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_move<kUnpack, false, 4, 3, kWgThreads>, kWgThreads, lds); break;
+    case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_move<kPack, false, 4, 3, kWgThreads>, kWgThreads, lds); break;
+    case 4: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer_ring<kUnpack, 4, kWgThreads>, kWgThreads, lds); break;
+    case 5: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer_ring<kPack, 4, kWgThreads>, kWgThreads, lds); break;
+    case 6: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer<kUnpack, true, 4, 3, kWgThreads>, kWgThreads, lds); break;
+    case 7: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer<kPack, true, 4, 3, kWgThreads>, kWgThreads, lds); break;
+    case 8: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer_lds<kUnpack, 4, kWgThreads>, kWgThreads, lds_tile); break;
+    case 9: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_layer_lds<kPack, 4, kWgThreads>, kWgThreads, lds_tile); break;
+    case 10: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_issue_io<4, kWgThreads>, kWgThreads, 0); break;
+    default: return TUTTI_EINVAL;
+  }
+  return e == hipSuccess ? n : hip_fail(e);
+}
+
 int tutti_cu_count(void) { return cu_count(); }
 
 uint32_t tutti_version(void) { return 0x00000100u; }

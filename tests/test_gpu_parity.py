@@ -759,6 +759,18 @@ def test_cu_budget_out_of_range(H):
     assert B.tutti_cu_count() >= 64
 
 
+def test_default_kernels_keep_eight_workgroups_per_cu_resident(H):
+    """The whole-GPU grids are sized for 8 resident 256-thread workgroups per compute unit; a kernel variant that
+    grew past 64 VGPRs would leave part of its persistent grid waiting behind the rest (a tail of several percent)."""
+    say("occupancy of the default kernels")
+    names = ["layer_restore", "layer_save", "unpack", "pack", "retrieve_layer", "store_layer", "layer_restore HND",
+             "layer_save HND", "layer_restore LDS", "layer_save LDS", "issue_io"]
+    got = {n: B.tutti_resident_wgs_per_cu(i) for i, n in enumerate(names)}
+    assert all(v >= 8 for v in got.values()), got
+    with pytest.raises(B.TuttiError):
+        B.tutti_resident_wgs_per_cu(len(names))
+
+
 def test_copy_baseline(H):
     say("copy baseline")
     g = torch.Generator(device=H.DEV)
