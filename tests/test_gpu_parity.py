@@ -406,7 +406,7 @@ def test_ring_layer_calls_can_be_captured_in_a_graph(orc, H):
 import os as _os
 
 
-@pytest.mark.parametrize("seed", range(int(_os.environ.get("TUTTI_FUZZ_SEEDS", "12"))))
+@pytest.mark.parametrize("seed", range(int(_os.environ.get("TUTTI_FUZZ_SEEDS", "48"))))
 def test_random_shapes(orc, H, seed):
     """Seeded random geometry, request mix, layout, stride, alignment, chunking and launch shape."""
     rng = np.random.default_rng(9000 + seed)
