@@ -607,6 +607,26 @@ int orc_store_layer(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot,
                     layer, sgl_table_addr, sgl_id, store, extents, totals, status);
 }
 
+int orc_table_validate(uint32_t num_blocks, const uint32_t *block_table, uint32_t table_len, uint32_t *status) {
+  if (num_blocks == 0 || !status || (table_len > 0 && !block_table)) return ORC_EINVAL;
+  uint8_t *seen = (uint8_t *)calloc(num_blocks, 1);
+  if (!seen) return ORC_EINVAL;
+  uint32_t st = 0;
+  for (uint32_t i = 0; i < table_len; ++i) {
+    const uint32_t id = block_table[i];
+    if (id >= num_blocks) {
+      st |= ORC_ST_BAD_BLOCK;
+    } else if (seen[id]) {
+      st |= ORC_ST_DUP_BLOCK;
+    } else {
+      seen[id] = 1;
+    }
+  }
+  free(seen);
+  *status |= st;
+  return ORC_OK;
+}
+
 /* ------------------------------------------------------------------ threaded timing helpers */
 
 typedef struct {

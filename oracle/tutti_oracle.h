@@ -53,6 +53,7 @@ extern "C" {
 #define ORC_ST_BAD_BLOCK 1u  /* a block-table entry >= num_blocks: that block was skipped */
 #define ORC_ST_STAGE_CAP 2u  /* a request's objects end beyond stage_cap: the request was skipped */
 #define ORC_ST_SQE_CAP 4u    /* more entries than sqe_cap: the excess was not written */
+#define ORC_ST_DUP_BLOCK 8u  /* orc_table_validate only: a block id appears more than once in the table */
 
 /* One layer's paged pool: a K plane and a V plane of num_blocks blocks each. */
 typedef struct {
@@ -241,6 +242,11 @@ int orc_store_layer(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot,
                     const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, uint64_t sgl_table_addr,
                     uint32_t sgl_id, const orc_filestore *store, orc_extent *extents, uint64_t *totals,
                     uint32_t *status);
+
+/* The preconditions an unpack places on its table, checked: every id below num_blocks (else ORC_ST_BAD_BLOCK) and
+ * no id twice (else ORC_ST_DUP_BLOCK: two writers to one block, whose result would depend on their order).  Out-of-
+ * range ids are not counted as duplicates of each other.  *status receives the bits (ORed in). */
+int orc_table_validate(uint32_t num_blocks, const uint32_t *block_table, uint32_t table_len, uint32_t *status);
 
 /* Descriptor count for a pool of pool_bytes described at gran bytes per descriptor
  * (the arithmetic of sec. 3.1, "P2P Memory Mapping Table"). */

@@ -17,7 +17,7 @@ _LIB = None
 
 LAYOUT_NHD, LAYOUT_HND = 0, 1
 OP_READ, OP_WRITE = 1, 2
-ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP = 1, 2, 4
+ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP, ST_DUP_BLOCK = 1, 2, 4, 8
 IOCB_SLOTS = 2048
 
 EXTENT_DTYPE = np.dtype([("stage_off", "<u8"), ("obj_bytes", "<u8"), ("n_blocks", "<u4"), ("n_chunks", "<u4"),
@@ -294,6 +294,17 @@ def store_layer(sq, cq, first_slot, n_slots, pool, cfg, n_blocks, block_table, f
     """Pool blocks -> file store through the rings.  Returns (extents, totals, status); store, sq, cq change in place."""
     return _ring_layer("orc_store_layer", sq, cq, first_slot, n_slots, pool, cfg, n_blocks, block_table, file_id,
                        layer, sgl_table_addr, sgl_id, store, file_stride, first_file_id, n_files)
+
+
+def table_validate(num_blocks, block_table):
+    """Status bits for a table: ST_BAD_BLOCK for ids out of range, ST_DUP_BLOCK for an id that appears twice."""
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    status = C.c_uint32(0)
+    rc = lib().orc_table_validate(C.c_uint32(num_blocks), _ptr(block_table), C.c_uint32(block_table.size),
+                                  C.byref(status))
+    if rc:
+        raise OracleError("orc_table_validate", rc)
+    return status.value
 
 
 def layer_save(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap, stage_cap=None):

@@ -810,7 +810,27 @@ def check_ring_layer(orc, seed=41):
     assert np.array_equal(k2[good, :bb], k0r[good, :bb]) and not k2[~good].any()
 
 
+def check_table_validate(orc, seed=43):
+    """Duplicates and out-of-range ids, against numpy.unique on independently built tables."""
+    rng = np.random.default_rng(seed)
+    assert orc.table_validate(10, []) == 0 and orc.table_validate(1, [0]) == 0
+    assert orc.table_validate(1, [0, 0]) == orc.ST_DUP_BLOCK and orc.table_validate(1, [1]) == orc.ST_BAD_BLOCK
+    assert orc.table_validate(4, [7, 7]) == orc.ST_BAD_BLOCK            # out of range twice is not a duplicate
+    assert orc.table_validate(4, [3, 9, 3]) == (orc.ST_BAD_BLOCK | orc.ST_DUP_BLOCK)
+    for _ in range(200):
+        N = int(rng.integers(1, 300))
+        n = int(rng.integers(0, 400))
+        t = rng.integers(0, N + int(rng.integers(0, 3)), size=n).astype(np.uint32)
+        ok = t[t < N]
+        want = (orc.ST_BAD_BLOCK if (t >= N).any() else 0) | (orc.ST_DUP_BLOCK if np.unique(ok).size != ok.size else 0)
+        assert orc.table_validate(N, t) == want, (N, t)
+        assert orc.table_validate(N, rng.permutation(N)[: min(n, N)]) == 0    # a permutation prefix is always clean
+    # first and last entry equal, ids at the ends of the range
+    assert orc.table_validate(65536, np.r_[np.arange(65535, 0, -1), 65535].astype(np.uint32)) == orc.ST_DUP_BLOCK
+    assert orc.table_validate(65536, np.arange(65536, dtype=np.uint32)) == 0
+
+
 ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
               check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io,
-              check_ring_layer]
+              check_ring_layer, check_table_validate]

@@ -96,6 +96,11 @@ MUTANTS = {
     "ring_layer_half_table": ("const uint32_t n_desc = 2u * pool->num_blocks;", "const uint32_t n_desc = 1u * pool->num_blocks;"),
     "ring_layer_skips_issue": ("if (!rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,",
                                "if (rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,"),
+    "validate_first_seen_counts": ("    } else if (seen[id]) {\n      st |= ORC_ST_DUP_BLOCK;\n    } else {\n      seen[id] = 1;",
+                                   "    } else if (seen[id]++) {\n      st |= ORC_ST_DUP_BLOCK;\n    } else {\n      seen[id] = 0;"),
+    "validate_bound_off_by_one": ("    if (id >= num_blocks) {\n      st |= ORC_ST_BAD_BLOCK;", "    if (id > num_blocks) {\n      st |= ORC_ST_BAD_BLOCK;"),
+    "validate_bad_ids_as_duplicates": ("    if (id >= num_blocks) {\n      st |= ORC_ST_BAD_BLOCK;\n    } else if (seen[id]) {",
+                                       "    if (id >= num_blocks) {\n      st |= ORC_ST_BAD_BLOCK | ORC_ST_DUP_BLOCK;\n    } else if (seen[id]) {"),
     "restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
                              "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);"),
 }
