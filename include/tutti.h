@@ -49,6 +49,7 @@ extern "C" {
 #define TUTTI_ST_BAD_BLOCK 1u /* a block-table entry >= num_blocks, or beyond table_len: block skipped */
 #define TUTTI_ST_STAGE_CAP 2u /* a request's objects end beyond stage_cap: request skipped */
 #define TUTTI_ST_SQE_CAP 4u   /* more entries than sqe_cap: the excess was not written */
+#define TUTTI_ST_DUP_BLOCK 8u /* tutti_table_validate only: a block id appears more than once in the table */
 
 /* One layer's paged pool (sec. 2.1 "Paged KV Memory Management"): a K plane and a V plane, each
  * num_blocks blocks of T*h*d*e bytes, block b at base + b*block_stride.  Planes stay owned by the
@@ -292,6 +293,16 @@ int tutti_store_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_sl
 /* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);
+
+/* ---- debugging aid: the preconditions that an unpack (tutti_obj_unpack, tutti_layer_restore, a READ through the
+ * rings) places on its flattened block table, checked on the device: every id < num_blocks (else
+ * TUTTI_ST_BAD_BLOCK; the data calls skip such blocks anyway) and no id twice (else TUTTI_ST_DUP_BLOCK: two
+ * writers to one block, which the data calls neither detect nor order; out-of-range ids do not count as duplicates
+ * of each other).  The bits are ORed into *d_status.  Needs no workspace and costs O(table_len^2) comparisons:
+ * microseconds for the tables of one layer, tens of milliseconds for a million entries.  Not meant for the
+ * per-layer path. */
+int tutti_table_validate(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
+                         void *stream);
 
 /* ---- measurement aid: a plain contiguous device-to-device copy of `bytes` (multiple of 16, both
  * pointers 16-byte aligned) with the same load/store width and launch shape as unpack: the

@@ -20,7 +20,7 @@ OP_READ, OP_WRITE = 1, 2
 STREAM_SLOTS = 4096
 IOCB_SLOTS = 2048
 MAX_REQ = 2048
-ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP = 1, 2, 4
+ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP, ST_DUP_BLOCK = 1, 2, 4, 8
 
 # Declarations of the C records for decoding results on the host.
 EXTENT_DTYPE = np.dtype({"names": ["stage_off", "obj_bytes", "n_blocks", "n_chunks", "sqe_base", "table_off"],
@@ -39,7 +39,7 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_layer_save",
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
            "tutti_issue_io", "tutti_wait_cqe", "tutti_retrieve_layer", "tutti_store_layer",
-           "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_resident_wgs_per_cu", "tutti_version",
+           "tutti_table_validate", "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_resident_wgs_per_cu", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]
 
 
@@ -119,6 +119,7 @@ def lib():
         L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
         L.tutti_layer_save.restype = C.c_int
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
+        L.tutti_table_validate.argtypes = [u32, vp, u32, vp, vp]
         L.tutti_stream_baseline.argtypes = [vp, u64, u32, vp, u32, vp]
         L.tutti_scatter_baseline.argtypes = [vp, u64, vp, u64, vp, u32, u32, u32, vp]
         L.tutti_scatter_baseline.restype = C.c_int
@@ -293,6 +294,11 @@ def tutti_layer_save(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_f
                                          table_len, _p(d_file_id), layer, _p(d_stage), stage_cap, stage_addr, sgl_id,
                                          _p(d_extents), _p(d_totals), _p(d_sqe), sqe_cap, cu_budget, _p(d_status),
                                          _stream(stream)))
+
+
+def tutti_table_validate(num_blocks, d_block_table, table_len, d_status, stream=None):
+    return _check("tutti_table_validate", lib().tutti_table_validate(num_blocks, _p(d_block_table), table_len,
+                                                                     _p(d_status), _stream(stream)))
 
 
 def tutti_stream_baseline(d_buf, nbytes, write, d_xor=None, cu_budget=0, stream=None):

@@ -842,6 +842,21 @@ int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+int tutti_table_validate(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
+                         void *stream) {
+  if (num_blocks == 0 || !d_status || (table_len > 0 && !d_block_table)) return TUTTI_EINVAL;
+  if (table_len == 0) return TUTTI_OK;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  const uint64_t tiles = (static_cast<uint64_t>(table_len) + kWgThreads - 1) / kWgThreads;
+  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
+  const uint32_t grid = static_cast<uint32_t>(tiles < lim ? tiles : lim);
+  hipLaunchKernelGGL(k_table_validate, dim3(grid), dim3(kWgThreads), 0, static_cast<hipStream_t>(stream), d_block_table,
+                     table_len, num_blocks, d_status);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
 int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream) {
   if (!d_dst || !d_src || !aligned16(d_dst) || !aligned16(d_src) || bytes % 16 != 0) return TUTTI_EINVAL;
   if (bytes == 0) return TUTTI_OK;

@@ -15,6 +15,7 @@
 //   k_copy          plain contiguous copy with the same access shape (measurement ceiling)
 //   k_stream        read-only or write-only stream with the same access shape (per-CU and chip limits)
 //   k_scatter       the copy with one side permuted at a given granularity (what the pattern itself costs)
+//   k_table_validate  debugging aid: ids in range and no id twice, by all-pairs comparison (no workspace)
 //
 // Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
 // the scan), then walks work items with a persistent grid-stride loop, so the grid can be any
@@ -1197,6 +1198,43 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, PT)) void k_layer_lds(co
     move_items_hnd_lds<DIR, PT, WG>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs,
                                     smem + align16(req_lds_bytes(a.n_req)));
   if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
+}
+
+// The preconditions of an unpack on its table, checked without any workspace: every id below num_blocks, no id
+// twice.  All pairs: workgroup b takes the 256 table positions [256b, 256b + 256) as rows (one per thread), walks
+// the column tiles from its own onwards through LDS and compares each row with the later positions of the tile,
+// four ids per LDS read.  O(table_len^2) comparisons: a debugging aid (a 40,000-entry table takes microseconds, a
+// million entries tens of milliseconds), not part of the per-layer path.
+__global__ __launch_bounds__(kWgThreads) void k_table_validate(const uint32_t *__restrict__ table, uint32_t n,
+                                                                uint32_t num_blocks, uint32_t *__restrict__ status) {
+  __shared__ __align__(16) uint32_t tile[kWgThreads];
+  const uint32_t n_tiles = (n + kWgThreads - 1) / kWgThreads;
+  uint32_t found = 0;
+  for (uint32_t b = blockIdx.x; b < n_tiles; b += gridDim.x) {
+    const uint32_t i = b * kWgThreads + threadIdx.x;
+    const uint32_t id = i < n ? table[i] : 0xffffffffu;
+    const bool valid = id < num_blocks;
+    if (i < n && !valid) found |= TUTTI_ST_BAD_BLOCK;
+    for (uint32_t c = b; c < n_tiles; ++c) {
+      const uint32_t j0 = c * kWgThreads;
+      const uint32_t j = j0 + threadIdx.x;
+      __syncthreads();  // the previous tile has been read by everyone
+      tile[threadIdx.x] = j < n ? table[j] : 0xffffffffu;  // an id no valid row can equal
+      __syncthreads();
+      if (valid) {
+        // positions after i only: in the row's own tile start behind it (rounded down to a group of four,
+        // with the row's own and earlier positions masked out), in later tiles take everything
+        const uint32_t first = c == b ? (threadIdx.x + 1) : 0;
+        for (uint32_t k = first & ~3u; k < kWgThreads; k += 4) {
+          const u32x4 t = *reinterpret_cast<const u32x4 *>(&tile[k]);
+          const bool e0 = t.x == id && k + 0 >= first, e1 = t.y == id && k + 1 >= first;
+          const bool e2 = t.z == id && k + 2 >= first, e3 = t.w == id && k + 3 >= first;
+          if (e0 || e1 || e2 || e3) found |= TUTTI_ST_DUP_BLOCK;
+        }
+      }
+    }
+  }
+  if (found && status) atomicOr(status, found);
 }
 
 // Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.

@@ -176,6 +176,9 @@ def test_null_and_misaligned_pointers_are_einval():
         _expect(B.ERANGE, one_call, ring, 0, 1, p, cfg, FAKE, B.MAX_REQ + 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, FAKE)
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 4, FAKE)
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 0, 0)
+    _expect(B.EINVAL, B.tutti_table_validate, 0, FAKE, 4, FAKE)
+    _expect(B.EINVAL, B.tutti_table_validate, 8, 0, 4, FAKE)
+    _expect(B.EINVAL, B.tutti_table_validate, 8, FAKE, 4, 0)
     _expect(B.EINVAL, B.tutti_copy_baseline, FAKE, FAKE, 24)
     _expect(B.EINVAL, B.tutti_copy_baseline, 0, FAKE, 32)
     # head-major pools need rows of whole 16-byte units

@@ -759,6 +759,52 @@ def test_cu_budget_out_of_range(H):
     assert B.tutti_cu_count() >= 64
 
 
+def test_table_validate(orc, H):
+    """Ids in range and no id twice: the device's all-pairs check against the oracle's bitmap."""
+    say("table validation")
+    rng = np.random.default_rng(61)
+
+    def both(num_blocks, table):
+        table = np.ascontiguousarray(table, np.uint32)
+        st = H.new_status()
+        B.tutti_table_validate(num_blocks, H.to_dev(table) if table.size else None, table.size, st)
+        torch.cuda.synchronize()
+        want = orc.table_validate(num_blocks, table)
+        assert int(st.item()) == want, (num_blocks, table.size, int(st.item()), want)
+        return want
+
+    assert both(16, []) == 0 and both(1, [0]) == 0 and both(1, [0, 0]) == B.ST_DUP_BLOCK
+    assert both(4, [7, 7]) == B.ST_BAD_BLOCK and both(4, [3, 9, 3]) == (B.ST_BAD_BLOCK | B.ST_DUP_BLOCK)
+    for n in (1, 3, 4, 5, 255, 256, 257, 1000, 2049):
+        N = 3 * n + 7
+        clean = rng.permutation(N)[:n]
+        assert both(N, clean) == 0
+        for _ in range(6):                       # one planted duplicate at random positions, near and far
+            t = clean.copy()
+            i, j = sorted(rng.choice(n, size=2, replace=False)) if n > 1 else (0, 0)
+            if i != j:
+                t[j] = t[i]
+                assert both(N, t) == B.ST_DUP_BLOCK, (n, i, j)
+        if n > 2:
+            t = clean.copy()
+            t[0], t[-1] = N, N + 5                 # out of range at both ends: reported, not duplicates
+            assert both(N, t) == B.ST_BAD_BLOCK
+            if n > 3:
+                t[n - 2] = t[1]
+                assert both(N, t) == (B.ST_BAD_BLOCK | B.ST_DUP_BLOCK)
+    for _ in range(20):                          # random tables with many repeats
+        N = int(rng.integers(1, 3000))
+        both(N, rng.integers(0, N + 2, size=int(rng.integers(0, 4000))))
+    # config 3's table (40,719 distinct blocks of 65,536), then its first and last entries made equal
+    w = W.batch64_zipf()
+    assert both(w.shape.num_blocks, w.block_table) == 0
+    t = w.block_table.copy()
+    t[-1] = t[0]
+    assert both(w.shape.num_blocks, t) == B.ST_DUP_BLOCK
+    with pytest.raises(B.TuttiError):
+        B.tutti_table_validate(0, H.to_dev(t), t.size, H.new_status())
+
+
 def test_default_kernels_keep_eight_workgroups_per_cu_resident(H):
     """The whole-GPU grids are sized for 8 resident 256-thread workgroups per compute unit; a kernel variant that
     grew past 64 VGPRs would leave part of its persistent grid waiting behind the rest (a tail of several percent)."""
