@@ -173,31 +173,62 @@ static void move_block(const orc_pool *pool, uint8_t *blk, uint8_t *obj, int to_
 }
 
 /*
- * Shared body of pack and unpack over the flattened block range [g_lo, g_hi), where block j of
- * request r has flattened index table_off_r + j.  The single-threaded oracle passes the whole range.
+ * Shared body of pack and unpack.  A request's table range is [table_off, table_off + n_blocks); the mt timing
+ * helpers pass a sub-range [g_lo, g_hi) of table positions, the single-threaded oracle passes everything.
+ *
+ * The paper defines the objects (sec. 3.1) but not what a library does with extents that a caller wrote by hand,
+ * so the rules for those are this repository's reading; each one skips and reports instead of touching memory
+ * outside the buffers the caller named:
+ *   - requests are taken in order while the running sum of n_blocks stays within table_len; the request that
+ *     pushes it beyond, and every later one, is skipped (ORC_ST_BAD_EXTENT);
+ *   - a request whose stage_off or obj_bytes is not a multiple of 16 is skipped (ORC_ST_BAD_EXTENT);
+ *   - a request whose two objects do not fit in stage_cap is skipped (ORC_ST_STAGE_CAP);
+ *   - a block that would end beyond its object is skipped (ORC_ST_BAD_EXTENT);
+ *   - a block whose table position is >= table_len, or whose id is >= num_blocks, is skipped (ORC_ST_BAD_BLOCK).
+ * Extents that orc_obj_layout made, with the table they describe, trip none of the first four.
  */
 static void move_range(const orc_pool *pool, const orc_extent *extents, uint32_t n_req, const uint32_t *block_table,
-                       uint8_t *stage, uint64_t stage_cap, int to_object, uint64_t g_lo, uint64_t g_hi,
-                       uint32_t *status) {
+                       uint32_t table_len, uint8_t *stage, uint64_t stage_cap, int to_object, uint64_t g_lo,
+                       uint64_t g_hi, uint32_t *status) {
   const uint64_t bb = orc_block_bytes(pool);
   uint32_t st = 0;
+  uint64_t used = 0; /* table entries claimed by the requests so far */
   for (uint32_t r = 0; r < n_req; ++r) {
     const orc_extent *x = &extents[r];
-    if (x->stage_off + 2 * x->obj_bytes > stage_cap) continue; /* does not fit: skip the request */
+    used += x->n_blocks;
+    if (used > table_len) { /* more blocks than the table holds: this request and all later ones */
+      st |= ORC_ST_BAD_EXTENT;
+      continue;
+    }
+    if (x->stage_off % 16 != 0 || x->obj_bytes % 16 != 0) {
+      st |= ORC_ST_BAD_EXTENT;
+      continue;
+    }
+    if (x->stage_off > stage_cap || x->obj_bytes > (stage_cap - x->stage_off) / 2) { /* K + V do not fit */
+      st |= ORC_ST_STAGE_CAP;
+      continue;
+    }
+    const uint64_t filled = (uint64_t)x->n_blocks * bb; /* bytes of the object that blocks occupy */
+    if (filled > x->obj_bytes) st |= ORC_ST_BAD_EXTENT;  /* the blocks beyond the object are skipped below */
     for (uint32_t kind = 0; kind < 2; ++kind) {
       uint8_t *plane = (uint8_t *)(kind == 0 ? pool->k_base : pool->v_base);
       uint8_t *obj = stage + x->stage_off + kind * x->obj_bytes; /* V object follows K object */
       for (uint32_t j = 0; j < x->n_blocks; ++j) {
         uint64_t g = (uint64_t)x->table_off + j;
         if (g < g_lo || g >= g_hi) continue;
-        uint32_t id = block_table[g];
-        if (id >= pool->num_blocks) {
+        if (((uint64_t)j + 1) * bb > x->obj_bytes) continue; /* would end beyond the object */
+        if (g >= table_len) {
           st |= ORC_ST_BAD_BLOCK;
         } else {
-          move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + (uint64_t)j * bb, to_object);
+          uint32_t id = block_table[g];
+          if (id >= pool->num_blocks) {
+            st |= ORC_ST_BAD_BLOCK;
+          } else {
+            move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + (uint64_t)j * bb, to_object);
+          }
         }
         if (to_object && j + 1 == x->n_blocks) /* pad the tail of the object with zeros */
-          memset(obj + (uint64_t)x->n_blocks * bb, 0, x->obj_bytes - (uint64_t)x->n_blocks * bb);
+          memset(obj + filled, 0, x->obj_bytes - filled);
       }
     }
   }
@@ -205,51 +236,32 @@ static void move_range(const orc_pool *pool, const orc_extent *extents, uint32_t
 }
 
 static int check_move_args(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                           const uint32_t *block_table, const void *stage) {
+                           const uint32_t *block_table, uint32_t table_len, const void *stage) {
   int rc = check_geometry(pool, cfg);
   if (rc) return rc;
   if (!pool->k_base || !pool->v_base) return ORC_EINVAL;
   if (n_req > 0 && (!extents || !stage)) return ORC_EINVAL;
-  uint64_t n_tab = 0;
-  for (uint32_t r = 0; r < n_req; ++r) n_tab += extents[r].n_blocks;
-  if (n_tab > 0 && !block_table) return ORC_EINVAL;
+  if (table_len > 0 && !block_table) return ORC_EINVAL;
   return ORC_OK;
-}
-
-/* ORC_ST_STAGE_CAP if any request's objects end beyond stage_cap. */
-static uint32_t cap_status(const orc_extent *extents, uint32_t n_req, uint64_t stage_cap) {
-  for (uint32_t r = 0; r < n_req; ++r)
-    if (extents[r].stage_off + 2 * extents[r].obj_bytes > stage_cap) return ORC_ST_STAGE_CAP;
-  return 0;
-}
-
-static uint64_t total_blocks(const orc_extent *extents, uint32_t n_req) {
-  uint64_t hi = 0;
-  for (uint32_t r = 0; r < n_req; ++r) {
-    uint64_t end = (uint64_t)extents[r].table_off + extents[r].n_blocks;
-    if (end > hi) hi = end;
-  }
-  return hi;
 }
 
 /* Save direction: every hit block of every request into its object (sec. 3.1; store_layer of sec. 3.4). */
 int orc_obj_pack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                 const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t *status) {
-  int rc = check_move_args(pool, cfg, extents, n_req, block_table, stage);
+                 const uint32_t *block_table, uint32_t table_len, void *stage, uint64_t stage_cap, uint32_t *status) {
+  int rc = check_move_args(pool, cfg, extents, n_req, block_table, table_len, stage);
   if (rc) return rc;
-  if (status) *status |= cap_status(extents, n_req, stage_cap);
-  move_range(pool, extents, n_req, block_table, (uint8_t *)stage, stage_cap, 1, 0, total_blocks(extents, n_req), status);
+  move_range(pool, extents, n_req, block_table, table_len, (uint8_t *)stage, stage_cap, 1, 0, UINT64_MAX, status);
   return ORC_OK;
 }
 
 /* Restore direction: every object back into the request's blocks (retrieve_layer of sec. 3.4). */
 int orc_obj_unpack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                   const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t *status) {
-  int rc = check_move_args(pool, cfg, extents, n_req, block_table, stage);
+                   const uint32_t *block_table, uint32_t table_len, const void *stage, uint64_t stage_cap,
+                   uint32_t *status) {
+  int rc = check_move_args(pool, cfg, extents, n_req, block_table, table_len, stage);
   if (rc) return rc;
-  if (status) *status |= cap_status(extents, n_req, stage_cap);
-  move_range(pool, extents, n_req, block_table, (uint8_t *)(uintptr_t)stage, stage_cap, 0, 0,
-             total_blocks(extents, n_req), status);
+  move_range(pool, extents, n_req, block_table, table_len, (uint8_t *)(uintptr_t)stage, stage_cap, 0, 0, UINT64_MAX,
+             status);
   return ORC_OK;
 }
 
@@ -529,7 +541,8 @@ int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, ui
 
 /* One layer's restore as the library's single call does it: extents, READ entries, unpack. */
 int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
-                      const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, const void *stage,
+                      const uint32_t *block_table, uint32_t table_len, const uint32_t *file_id, uint32_t layer,
+                      const void *stage,
                       uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents,
                       uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status) {
   int rc = check_geometry(pool, cfg);
@@ -542,12 +555,12 @@ int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_
   if (rc) return rc;
   rc = orc_sqe_build(pool, cfg, extents, n_req, file_id, layer, ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);
   if (rc) return rc;
-  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);
+  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, table_len, stage, stage_cap, status);
 }
 
 /* One layer's save as the library's single call does it: extents, WRITE entries, pack (store_layer of sec. 3.4). */
 int orc_layer_save(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
-                   const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, void *stage,
+                   const uint32_t *block_table, uint32_t table_len, const uint32_t *file_id, uint32_t layer, void *stage,
                    uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents, uint64_t *totals,
                    orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status) {
   int rc = check_geometry(pool, cfg);
@@ -560,7 +573,7 @@ int orc_layer_save(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *
   if (rc) return rc;
   rc = orc_sqe_build(pool, cfg, extents, n_req, file_id, layer, ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);
   if (rc) return rc;
-  return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);
+  return orc_obj_pack(pool, cfg, extents, n_req, block_table, table_len, stage, stage_cap, status);
 }
 
 /* retrieve_layer(layer) / store_layer(layer) of sec. 3.4 through the rings, in direct-to-block mode, written as
@@ -634,6 +647,7 @@ typedef struct {
   const orc_extent *extents;
   uint32_t n_req;
   const uint32_t *block_table;
+  uint32_t table_len;
   uint8_t *stage;
   uint64_t stage_cap;
   int to_object;
@@ -642,18 +656,18 @@ typedef struct {
 
 static void *mt_run(void *p) {
   mt_job *j = (mt_job *)p;
-  move_range(j->pool, j->extents, j->n_req, j->block_table, j->stage, j->stage_cap, j->to_object, j->g_lo, j->g_hi,
-             NULL);
+  move_range(j->pool, j->extents, j->n_req, j->block_table, j->table_len, j->stage, j->stage_cap, j->to_object, j->g_lo,
+             j->g_hi, NULL);
   return NULL;
 }
 
 static int move_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                   const uint32_t *block_table, uint8_t *stage, uint64_t stage_cap, int to_object,
+                   const uint32_t *block_table, uint32_t table_len, uint8_t *stage, uint64_t stage_cap, int to_object,
                    uint32_t n_threads) {
-  int rc = check_move_args(pool, cfg, extents, n_req, block_table, stage);
+  int rc = check_move_args(pool, cfg, extents, n_req, block_table, table_len, stage);
   if (rc) return rc;
   if (n_threads == 0 || n_threads > 1024) return ORC_ERANGE;
-  uint64_t n = total_blocks(extents, n_req);
+  uint64_t n = table_len; /* table positions, split evenly over the threads */
   pthread_t tid[1024];
   mt_job job[1024];
   uint32_t started = 0;
@@ -662,6 +676,7 @@ static int move_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent
     job[t].extents = extents;
     job[t].n_req = n_req;
     job[t].block_table = block_table;
+    job[t].table_len = table_len;
     job[t].stage = stage;
     job[t].stage_cap = stage_cap;
     job[t].to_object = to_object;
@@ -675,11 +690,14 @@ static int move_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent
 }
 
 int orc_obj_pack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                    const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t n_threads) {
-  return move_mt(pool, cfg, extents, n_req, block_table, (uint8_t *)stage, stage_cap, 1, n_threads);
+                    const uint32_t *block_table, uint32_t table_len, void *stage, uint64_t stage_cap,
+                    uint32_t n_threads) {
+  return move_mt(pool, cfg, extents, n_req, block_table, table_len, (uint8_t *)stage, stage_cap, 1, n_threads);
 }
 
 int orc_obj_unpack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                      const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t n_threads) {
-  return move_mt(pool, cfg, extents, n_req, block_table, (uint8_t *)(uintptr_t)stage, stage_cap, 0, n_threads);
+                      const uint32_t *block_table, uint32_t table_len, const void *stage, uint64_t stage_cap,
+                      uint32_t n_threads) {
+  return move_mt(pool, cfg, extents, n_req, block_table, table_len, (uint8_t *)(uintptr_t)stage, stage_cap, 0,
+                 n_threads);
 }

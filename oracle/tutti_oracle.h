@@ -54,6 +54,7 @@ extern "C" {
 #define ORC_ST_STAGE_CAP 2u  /* a request's objects end beyond stage_cap: the request was skipped */
 #define ORC_ST_SQE_CAP 4u    /* more entries than sqe_cap: the excess was not written */
 #define ORC_ST_DUP_BLOCK 8u  /* orc_table_validate only: a block id appears more than once in the table */
+#define ORC_ST_BAD_EXTENT 16u /* pack / unpack: an extent that cannot be honoured (see orc_obj_pack) */
 
 /* One layer's paged pool: a K plane and a V plane of num_blocks blocks each. */
 typedef struct {
@@ -114,16 +115,24 @@ uint32_t orc_block_bytes(const orc_pool *pool);
 int orc_obj_layout(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
                    orc_extent *extents, uint64_t *totals);
 
-/* Paged blocks -> objects.  stage receives, per request, the K object then the V object,
- * each zero-padded to obj_bytes.  Requests whose objects do not fit in stage_cap are skipped,
- * and so is any block whose table entry is >= num_blocks (its object bytes stay as they were);
- * both are reported in *status (may be NULL). */
+/* Paged blocks -> objects.  stage receives, per request, the K object (at stage_off) then the V object
+ * (obj_bytes later), each zero-padded from n_blocks*block_bytes to obj_bytes; block j of request r is the
+ * one table entry table_off_r + j names.  The extents are honoured field by field, whoever wrote them
+ * (gaps between requests, any order in the staging buffer, a table range that does not start at 0).
+ * What cannot be honoured is skipped and reported in *status (may be NULL), in this order per request:
+ *   running sum of n_blocks over the requests so far > table_len   request and all later ones skipped, BAD_EXTENT
+ *   stage_off or obj_bytes not a multiple of 16                    request skipped, BAD_EXTENT
+ *   stage_off + 2*obj_bytes > stage_cap                            request skipped, STAGE_CAP
+ *   (j+1)*block_bytes > obj_bytes                                  block skipped, BAD_EXTENT
+ *   table_off + j >= table_len, or the id there >= num_blocks      block skipped, BAD_BLOCK
+ * A skipped block leaves its object bytes as they were. */
 int orc_obj_pack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                 const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t *status);
+                 const uint32_t *block_table, uint32_t table_len, void *stage, uint64_t stage_cap, uint32_t *status);
 
-/* Objects -> paged blocks; padding is not read; blocks not named in the table are not touched. */
+/* Objects -> paged blocks, same rules; padding is not read; blocks not named in the table are not touched. */
 int orc_obj_unpack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                   const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t *status);
+                   const uint32_t *block_table, uint32_t table_len, const void *stage, uint64_t stage_cap,
+                   uint32_t *status);
 
 /* One entry per chunk of every K and V object of one layer.  Entries with index >= sqe_cap are not written. */
 int orc_sqe_build(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
@@ -132,14 +141,14 @@ int orc_sqe_build(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent 
 
 /* layout, then READ entries, then unpack, for one layer. */
 int orc_layer_restore(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
-                      const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, const void *stage,
-                      uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents,
+                      const uint32_t *block_table, uint32_t table_len, const uint32_t *file_id, uint32_t layer,
+                      const void *stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents,
                       uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
 
 /* layout, then WRITE entries, then pack, for one layer (the save direction of the fused call). */
 int orc_layer_save(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
-                   const uint32_t *block_table, const uint32_t *file_id, uint32_t layer, void *stage,
-                   uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents, uint64_t *totals,
+                   const uint32_t *block_table, uint32_t table_len, const uint32_t *file_id, uint32_t layer,
+                   void *stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id, orc_extent *extents, uint64_t *totals,
                    orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);
 
 /* ---- direct-to-block mode: the paper's own data path, no staging copy (sec. 3.1, "P2P Memory
@@ -256,9 +265,11 @@ uint64_t orc_desc_count(uint64_t pool_bytes, uint64_t gran);
  * orc_obj_pack / orc_obj_unpack, with the flattened block range split evenly over n_threads
  * POSIX threads.  Parity never uses these. */
 int orc_obj_pack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                    const uint32_t *block_table, void *stage, uint64_t stage_cap, uint32_t n_threads);
+                    const uint32_t *block_table, uint32_t table_len, void *stage, uint64_t stage_cap,
+                    uint32_t n_threads);
 int orc_obj_unpack_mt(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
-                      const uint32_t *block_table, const void *stage, uint64_t stage_cap, uint32_t n_threads);
+                      const uint32_t *block_table, uint32_t table_len, const void *stage, uint64_t stage_cap,
+                      uint32_t n_threads);
 
 #ifdef __cplusplus
 }

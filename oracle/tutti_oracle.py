@@ -17,7 +17,7 @@ _LIB = None
 
 LAYOUT_NHD, LAYOUT_HND = 0, 1
 OP_READ, OP_WRITE = 1, 2
-ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP, ST_DUP_BLOCK = 1, 2, 4, 8
+ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP, ST_DUP_BLOCK, ST_BAD_EXTENT = 1, 2, 4, 8, 16
 IOCB_SLOTS = 2048
 
 EXTENT_DTYPE = np.dtype([("stage_off", "<u8"), ("obj_bytes", "<u8"), ("n_blocks", "<u4"), ("n_chunks", "<u4"),
@@ -131,33 +131,42 @@ def obj_layout(pool, cfg, n_blocks):
     return ext, totals
 
 
-def obj_pack(pool, cfg, extents, block_table, stage, stage_cap=None, n_threads=0):
-    """Pack into `stage` (uint8 host array, modified in place).  Returns the status word."""
+def obj_pack(pool, cfg, extents, block_table, stage, stage_cap=None, n_threads=0, table_len=None):
+    """Pack into `stage` (uint8 host array, modified in place).  Returns the status word.
+    table_len: how many entries of block_table may be read (default: all of them)."""
     block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    extents = np.ascontiguousarray(extents)
     cap = stage.nbytes if stage_cap is None else stage_cap
+    tl = block_table.size if table_len is None else table_len
+    assert tl <= block_table.size
     status = C.c_uint32(0)
     if n_threads:
         rc = lib().orc_obj_pack_mt(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
-                                   _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.c_uint32(n_threads))
+                                   _ptr(block_table), C.c_uint32(tl), _ptr(stage), C.c_uint64(cap),
+                                   C.c_uint32(n_threads))
     else:
         rc = lib().orc_obj_pack(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
-                                _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.byref(status))
+                                _ptr(block_table), C.c_uint32(tl), _ptr(stage), C.c_uint64(cap), C.byref(status))
     if rc:
         raise OracleError("orc_obj_pack", rc)
     return status.value
 
 
-def obj_unpack(pool, cfg, extents, block_table, stage, stage_cap=None, n_threads=0):
+def obj_unpack(pool, cfg, extents, block_table, stage, stage_cap=None, n_threads=0, table_len=None):
     """Unpack `stage` into the planes the pool points at.  Returns the status word."""
     block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    extents = np.ascontiguousarray(extents)
     cap = stage.nbytes if stage_cap is None else stage_cap
+    tl = block_table.size if table_len is None else table_len
+    assert tl <= block_table.size
     status = C.c_uint32(0)
     if n_threads:
         rc = lib().orc_obj_unpack_mt(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
-                                     _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.c_uint32(n_threads))
+                                     _ptr(block_table), C.c_uint32(tl), _ptr(stage), C.c_uint64(cap),
+                                     C.c_uint32(n_threads))
     else:
         rc = lib().orc_obj_unpack(C.byref(pool), C.byref(cfg), _ptr(extents), C.c_uint32(extents.size),
-                                  _ptr(block_table), _ptr(stage), C.c_uint64(cap), C.byref(status))
+                                  _ptr(block_table), C.c_uint32(tl), _ptr(stage), C.c_uint64(cap), C.byref(status))
     if rc:
         raise OracleError("orc_obj_unpack", rc)
     return status.value
@@ -179,7 +188,7 @@ def sqe_build(pool, cfg, extents, file_id, layer, opcode, stage_addr, sgl_id, sq
 
 
 def layer_restore(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap,
-                  stage_cap=None):
+                  stage_cap=None, table_len=None):
     """Returns (extents, totals, sqe, status); the planes the pool points at are modified in place."""
     n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)
     block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
@@ -189,8 +198,11 @@ def layer_restore(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage
     sqe = np.zeros(sqe_cap, SQE_DTYPE)
     cap = stage.nbytes if stage_cap is None else stage_cap
     status = C.c_uint32(0)
+    tl = block_table.size if table_len is None else table_len
+    assert tl <= block_table.size
     rc = lib().orc_layer_restore(C.byref(pool), C.byref(cfg), _ptr(n_blocks), C.c_uint32(n_blocks.size),
-                                 _ptr(block_table), _ptr(file_id), C.c_uint32(layer), _ptr(stage), C.c_uint64(cap),
+                                 _ptr(block_table), C.c_uint32(tl), _ptr(file_id), C.c_uint32(layer), _ptr(stage),
+                                 C.c_uint64(cap),
                                  C.c_uint64(stage_addr), C.c_uint32(sgl_id), _ptr(ext), _ptr(totals), _ptr(sqe),
                                  C.c_uint32(sqe_cap), C.byref(status))
     if rc:
@@ -307,7 +319,8 @@ def table_validate(num_blocks, block_table):
     return status.value
 
 
-def layer_save(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap, stage_cap=None):
+def layer_save(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap, stage_cap=None,
+               table_len=None):
     """Returns (extents, totals, sqe, status); `stage` is written in place."""
     n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)
     block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
@@ -317,8 +330,11 @@ def layer_save(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_ad
     sqe = np.zeros(sqe_cap, SQE_DTYPE)
     cap = stage.nbytes if stage_cap is None else stage_cap
     status = C.c_uint32(0)
+    tl = block_table.size if table_len is None else table_len
+    assert tl <= block_table.size
     rc = lib().orc_layer_save(C.byref(pool), C.byref(cfg), _ptr(n_blocks), C.c_uint32(n_blocks.size),
-                              _ptr(block_table), _ptr(file_id), C.c_uint32(layer), _ptr(stage), C.c_uint64(cap),
+                              _ptr(block_table), C.c_uint32(tl), _ptr(file_id), C.c_uint32(layer), _ptr(stage),
+                              C.c_uint64(cap),
                               C.c_uint64(stage_addr), C.c_uint32(sgl_id), _ptr(ext), _ptr(totals), _ptr(sqe),
                               C.c_uint32(sqe_cap), C.byref(status))
     if rc:

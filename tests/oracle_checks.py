@@ -810,6 +810,134 @@ def check_ring_layer(orc, seed=41):
     assert np.array_equal(k2[good, :bb], k0r[good, :bb]) and not k2[~good].any()
 
 
+def _expect_pack(stage, planes, stride, bb, ext, table, live_blocks):
+    """Independent formulation of a pack for hand-made extents: numpy gathers, one per live (request, kind, block)."""
+    k, v = planes
+    for r, kind, j in live_blocks:
+        so, ob, toff = int(ext["stage_off"][r]), int(ext["obj_bytes"][r]), int(ext["table_off"][r])
+        b = int(table[toff + j])
+        src = (k, v)[kind]
+        stage[so + kind * ob + j * bb: so + kind * ob + (j + 1) * bb] = src[b * stride: b * stride + bb]
+
+
+def check_caller_extents(orc, seed=47):
+    """Extents written by hand are honoured field by field (a gap between requests, a sub-range of the
+    requests, any order in the staging buffer), and what cannot be honoured is skipped and reported.
+    Expected bytes come from numpy slices written here, never from orc_obj_layout."""
+    rng = np.random.default_rng(seed)
+    T, h, d, e, N = 4, 2, 8, 2, 32
+    bb = T * h * d * e                    # 128
+    A = 128
+    stride = bb + 16
+    k, v = _planes(rng, N, stride)
+    p = _pool(orc, T, h, d, e, N, k, v, stride=stride)
+    cfg = orc.make_cfg(A, A, 1)
+    n = [3, 2, 4]
+    table = rng.permutation(N)[:9].astype(np.uint32)
+
+    def ext_of(rows):
+        x = np.zeros(len(rows), orc.EXTENT_DTYPE)
+        for i, (so, ob, nb, toff) in enumerate(rows):
+            x[i] = (so, ob, nb, 1, 0, toff)
+        return x
+
+    def all_blocks(x):
+        return [(r, kind, j) for r in range(x.size) for kind in (0, 1) for j in range(int(x["n_blocks"][r]))]
+
+    def run_pack(x, tab=table, cap=None, table_len=None, size=8192, fill=0x6D):
+        stage = np.full(size, fill, np.uint8)
+        st = orc.obj_pack(p, cfg, x, tab, stage, stage_cap=cap, table_len=table_len)
+        return stage, st
+
+    # (a) a gap between the requests, and objects larger than their blocks (padding is zeroed up to obj_bytes)
+    x = ext_of([(0, 3 * bb, 3, 0), (2048, 2 * bb + 256, 2, 3), (4096 + 512, 4 * bb, 4, 5)])
+    got, st = run_pack(x)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, x, table, all_blocks(x))
+    for kind in (0, 1):
+        o = 2048 + kind * (2 * bb + 256)
+        want[o + 2 * bb: o + 2 * bb + 256] = 0
+    assert st == 0 and np.array_equal(got, want), "gap between requests / padding of a hand-made object"
+    # (b) requests 1.. of that layout passed alone, with the whole table: the table range starts at 3
+    got, st = run_pack(x[1:])
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, x[1:], table, all_blocks(x[1:]))
+    for kind in (0, 1):
+        o = 2048 + kind * (2 * bb + 256)
+        want[o + 2 * bb: o + 2 * bb + 256] = 0
+    assert st == 0 and np.array_equal(got, want), "sub-range of the requests"
+    # (c) the last request first in the staging buffer
+    y = ext_of([(6 * bb + 8 * bb, 3 * bb, 3, 0), (8 * bb, 2 * bb, 2, 3), (0, 4 * bb, 4, 5)])
+    got, st = run_pack(y)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, y, table, all_blocks(y))
+    assert st == 0 and np.array_equal(got, want), "requests in reverse order in the staging buffer"
+    # ... and the same three shapes restore what they packed, into another pool, touching nothing else
+    for z in (x, x[1:], y):
+        stage = rng.integers(0, 256, 8192, dtype=np.uint8)
+        k2, v2 = _planes(rng, N, stride)
+        kb, vb = k2.copy(), v2.copy()
+        p2 = _pool(orc, T, h, d, e, N, k2, v2, stride=stride)
+        assert orc.obj_unpack(p2, cfg, z, table, stage) == 0
+        for r, kind, j in all_blocks(z):
+            so, ob, toff = int(z["stage_off"][r]), int(z["obj_bytes"][r]), int(z["table_off"][r])
+            b = int(table[toff + j])
+            dst = (kb, vb)[kind]
+            dst[b * stride: b * stride + bb] = stage[so + kind * ob + j * bb: so + kind * ob + (j + 1) * bb]
+        assert np.array_equal(k2, kb) and np.array_equal(v2, vb), "unpack of hand-made extents"
+
+    # ---- what cannot be honoured
+    base = ext_of([(0, 3 * bb, 3, 0), (6 * bb, 2 * bb, 2, 3), (10 * bb, 4 * bb, 4, 5)])
+    # the table holds 8 entries but the requests claim 9: the request that crosses the limit is skipped whole
+    got, st = run_pack(base, table_len=8)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, base, table, all_blocks(base[:2]))
+    assert st == orc.ST_BAD_EXTENT and np.array_equal(got, want), "running sum of n_blocks beyond table_len"
+    # ... and so is every request after it, even one that would fit on its own
+    z = ext_of([(0, 3 * bb, 3, 0), (6 * bb, 7 * bb, 7, 0), (20 * bb, bb, 1, 8)])
+    got, st = run_pack(z)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, z, table, all_blocks(z[:1]))
+    assert st == orc.ST_BAD_EXTENT and np.array_equal(got, want), "requests after the one that overran the table"
+    # an exact fit is fine
+    z = ext_of([(0, 9 * bb, 9, 0)])
+    got, st = run_pack(z)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, z, table, all_blocks(z))
+    assert st == 0 and np.array_equal(got, want)
+    # offsets and sizes must be multiples of 16
+    for rows in ([(8, 3 * bb, 3, 0)], [(0, 3 * bb + 8, 3, 0)]):
+        got, st = run_pack(ext_of(rows))
+        assert st == orc.ST_BAD_EXTENT and np.all(got == 0x6D), "misaligned extent must be skipped"
+    got, st = run_pack(ext_of([(16, 3 * bb + 16, 3, 0)]))
+    assert st == 0 and np.array_equal(got[16:16 + bb], k[int(table[0]) * stride: int(table[0]) * stride + bb])
+    assert np.array_equal(got[16 + 3 * bb + 16: 16 + 4 * bb + 16], v[int(table[0]) * stride: int(table[0]) * stride + bb])
+    # sizes that would wrap around 64 bits do not fit any capacity
+    for rows in ([(0, 1 << 63, 3, 0)], [((1 << 64) - 16, 3 * bb, 3, 0)], [(4096, (1 << 63) - 2048, 3, 0)]):
+        got, st = run_pack(ext_of(rows))
+        assert st == orc.ST_STAGE_CAP and np.all(got == 0x6D), "overflowing extent must not fit"
+    # an object too small for its blocks: the blocks that still fit are moved, no padding, V right behind K
+    z = ext_of([(256, 2 * bb, 3, 0), (256 + 4 * bb + 1024, bb + 64, 2, 3)])
+    got, st = run_pack(z)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, z, table, [(0, 0, 0), (0, 0, 1), (0, 1, 0), (0, 1, 1), (1, 0, 0), (1, 1, 0)])
+    assert st == orc.ST_BAD_EXTENT and np.array_equal(got, want), "blocks beyond their object"
+    # a table range that runs off the end of the table: the positions beyond it are skipped
+    z = ext_of([(0, 3 * bb, 3, 7)])
+    longer = np.r_[table, np.uint32(1), np.uint32(2)]
+    got, st = run_pack(z, tab=longer, table_len=9)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, z, table, [(0, 0, 0), (0, 0, 1), (0, 1, 0), (0, 1, 1)])
+    assert st == orc.ST_BAD_BLOCK and np.array_equal(got, want), "table position beyond table_len"
+    # capacity: the request whose V object ends one byte beyond it is skipped, the others are not
+    got, st = run_pack(base, cap=18 * bb - 1)
+    want = np.full(8192, 0x6D, np.uint8)
+    _expect_pack(want, (k, v), stride, bb, base, table, all_blocks(base[:2]))
+    assert st == orc.ST_STAGE_CAP and np.array_equal(got, want)
+    got, st = run_pack(base, cap=18 * bb)
+    assert st == 0
+
+
 def check_table_validate(orc, seed=43):
     """Duplicates and out-of-range ids, against numpy.unique on independently built tables."""
     rng = np.random.default_rng(seed)
@@ -833,4 +961,4 @@ def check_table_validate(orc, seed=43):
 ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
               check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io,
-              check_ring_layer, check_table_validate]
+              check_ring_layer, check_table_validate, check_caller_extents]

@@ -101,7 +101,7 @@ static void one_case(void) {
   uint8_t *stage = xmalloc(tot[0]);
   memset(stage, 0xA5, tot[0]);
   uint32_t st = 0;
-  CHECK(orc_obj_pack(&pool, &cfg, ext, n_req, table, stage, tot[0], &st) == ORC_OK);
+  CHECK(orc_obj_pack(&pool, &cfg, ext, n_req, table, total, stage, tot[0], &st) == ORC_OK);
   CHECK((st != 0) == (plant_bad != 0));
   uint8_t *k2 = xmalloc(N * stride), *v2 = xmalloc(N * stride);
   memset(k2, 0, N * stride);
@@ -110,7 +110,7 @@ static void one_case(void) {
   pool2.k_base = k2;
   pool2.v_base = v2;
   st = 0;
-  CHECK(orc_obj_unpack(&pool2, &cfg, ext, n_req, table, stage, tot[0], &st) == ORC_OK);
+  CHECK(orc_obj_unpack(&pool2, &cfg, ext, n_req, table, total, stage, tot[0], &st) == ORC_OK);
   uint8_t *named = xmalloc(N);
   memset(named, 0, N);
   for (uint32_t i = 0; i < total; ++i)
@@ -128,9 +128,83 @@ static void one_case(void) {
     uint8_t *shorter = xmalloc(tot[0] - 1);
     memset(shorter, 0x5A, tot[0] - 1);
     st = 0;
-    CHECK(orc_obj_pack(&pool, &cfg, ext, n_req, table, shorter, tot[0] - 1, &st) == ORC_OK);
+    CHECK(orc_obj_pack(&pool, &cfg, ext, n_req, table, total, shorter, tot[0] - 1, &st) == ORC_OK);
     CHECK(st & ORC_ST_STAGE_CAP);
     free(shorter);
+  }
+
+  /* extents written by hand: a gap in front of every request, the requests in reverse order in the staging
+   * buffer, and requests 1.. passed alone with the whole table; each packs into an exact-size buffer and
+   * restores the named blocks of the requests it covers, nothing else */
+  for (int variant = 0; variant < 3 && n_req > 0; ++variant) {
+    const uint64_t gap = 16 * rnd_in(1, 8);
+    orc_extent *hx = xmalloc(sizeof(orc_extent) * n_req);
+    memcpy(hx, ext, sizeof(orc_extent) * n_req);
+    uint64_t end = 0;
+    if (variant == 0 || variant == 2) {
+      for (uint32_t r = 0; r < n_req; ++r) {
+        hx[r].stage_off = end + gap;
+        end = hx[r].stage_off + 2 * hx[r].obj_bytes;
+      }
+    } else {
+      for (uint32_t r = n_req; r-- > 0;) {
+        hx[r].stage_off = end;
+        end += 2 * hx[r].obj_bytes;
+      }
+    }
+    const uint32_t first = variant == 2 ? 1 : 0;
+    uint8_t *hs = xmalloc(end);
+    memset(hs, 0x3C, end);
+    st = 0;
+    CHECK(orc_obj_pack(&pool, &cfg, hx + first, n_req - first, table, total, hs, end, &st) == ORC_OK);
+    CHECK((st & ~ORC_ST_BAD_BLOCK) == 0);
+    if (variant != 1)
+      for (uint32_t r = 0; r < n_req; ++r) /* the gaps stay as they were */
+        for (uint64_t i = hx[r].stage_off - gap; i < hx[r].stage_off; ++i) CHECK(hs[i] == 0x3C);
+    uint8_t *k4 = xmalloc(N * stride), *v4 = xmalloc(N * stride);
+    memset(k4, 0, N * stride);
+    memset(v4, 0, N * stride);
+    orc_pool pool4 = pool;
+    pool4.k_base = k4;
+    pool4.v_base = v4;
+    st = 0;
+    CHECK(orc_obj_unpack(&pool4, &cfg, hx + first, n_req - first, table, total, hs, end, &st) == ORC_OK);
+    uint8_t *covered_blk = xmalloc(N);
+    memset(covered_blk, 0, N);
+    for (uint32_t r = first; r < n_req; ++r)
+      for (uint32_t j = 0; j < hx[r].n_blocks; ++j)
+        if (table[hx[r].table_off + j] < N) covered_blk[table[hx[r].table_off + j]] = 1;
+    for (uint32_t b = 0; b < N; ++b) {
+      if (covered_blk[b]) {
+        CHECK(memcmp(k4 + b * stride, k + b * stride, bb) == 0 && memcmp(v4 + b * stride, v + b * stride, bb) == 0);
+      } else {
+        for (uint32_t i = 0; i < bb; ++i) CHECK(k4[b * stride + i] == 0 && v4[b * stride + i] == 0);
+      }
+    }
+    free(k4);
+    free(v4);
+    /* a table one entry short: the request that crosses the limit and all later ones are skipped, in bounds */
+    if (total > 0 && variant == 0) {
+      uint32_t *shorter_tab = xmalloc(sizeof(uint32_t) * (total - 1));
+      memcpy(shorter_tab, table, sizeof(uint32_t) * (total - 1));
+      st = 0;
+      CHECK(orc_obj_pack(&pool, &cfg, hx, n_req, shorter_tab, total - 1, hs, end, &st) == ORC_OK);
+      CHECK(st & ORC_ST_BAD_EXTENT);
+      free(shorter_tab);
+    }
+    /* an object one alignment unit too small for its blocks: the last block is skipped, in bounds */
+    if (variant == 0 && nb[0] > 0 && ext[0].obj_bytes >= A && ext[0].obj_bytes - A < (uint64_t)nb[0] * bb) {
+      orc_extent small = ext[0];
+      small.obj_bytes -= A;
+      uint8_t *ss = xmalloc(2 * small.obj_bytes);
+      st = 0;
+      CHECK(orc_obj_pack(&pool, &cfg, &small, 1, table, total, ss, 2 * small.obj_bytes, &st) == ORC_OK);
+      CHECK(st & ORC_ST_BAD_EXTENT);
+      free(ss);
+    }
+    free(covered_blk);
+    free(hs);
+    free(hx);
   }
 
   /* entries: exact-size array, and an array one entry short */
@@ -161,7 +235,7 @@ static void one_case(void) {
     uint8_t *stage2 = xmalloc(tot[0]);
     memset(stage2, 0xA5, tot[0]);
     st = 0;
-    CHECK(orc_layer_save(&pool, &cfg, nb, n_req, table, fid, layer, stage2, tot[0], 4096 * 7, 9, ext2, tot2, sqe2,
+    CHECK(orc_layer_save(&pool, &cfg, nb, n_req, table, total, fid, layer, stage2, tot[0], 4096 * 7, 9, ext2, tot2, sqe2,
                          (uint32_t)tot[1], &st) == ORC_OK);
     CHECK(memcmp(stage2, stage, tot[0]) == 0 && memcmp(ext2, ext, sizeof(orc_extent) * n_req) == 0);
     for (uint64_t i = 0; i < tot[1]; ++i) CHECK(sqe2[i].opcode == ORC_OP_WRITE && sqe2[i].addr == sqe[i].addr);
@@ -171,7 +245,7 @@ static void one_case(void) {
     orc_pool pool3 = pool;
     pool3.k_base = k3;
     pool3.v_base = v3;
-    CHECK(orc_layer_restore(&pool3, &cfg, nb, n_req, table, fid, layer, stage, tot[0], 4096 * 7, 9, ext2, tot2, sqe2,
+    CHECK(orc_layer_restore(&pool3, &cfg, nb, n_req, table, total, fid, layer, stage, tot[0], 4096 * 7, 9, ext2, tot2, sqe2,
                             (uint32_t)tot[1], &st) == ORC_OK);
     CHECK(memcmp(k3, k2, N * stride) == 0 && memcmp(v3, v2, N * stride) == 0);
     CHECK(memcmp(sqe2, sqe, sizeof(orc_sqe) * tot[1]) == 0);

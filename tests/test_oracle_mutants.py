@@ -24,11 +24,11 @@ MUTANTS = {
     "hnd_transposed_wrong": ("((i * T + t) * d) * e;", "((i * h + t) * d) * e;"),
     "stride_ignored": ("plane + (uint64_t)id * pool->block_stride", "plane + (uint64_t)id * bb"),
     "object_uses_stride": ("obj + (uint64_t)j * bb, to_object", "obj + (uint64_t)j * pool->block_stride, to_object"),
-    "padding_not_zeroed": ("memset(obj + (uint64_t)x->n_blocks * bb, 0,", "if (0) memset(obj + (uint64_t)x->n_blocks * bb, 0,"),
+    "padding_not_zeroed": ("memset(obj + filled, 0,", "if (0) memset(obj + filled, 0,"),
     "table_offset_dropped": ("uint32_t id = block_table[g];", "uint32_t id = block_table[j];"),
     "block_bound_off_by_one": ("if (id >= pool->num_blocks) {", "if (id > pool->num_blocks) {"),
-    "unpack_direction": ("(uint8_t *)(uintptr_t)stage, stage_cap, 0, 0,\n             total_blocks",
-                         "(uint8_t *)(uintptr_t)stage, stage_cap, 1, 0,\n             total_blocks"),
+    "unpack_direction": ("(uint8_t *)(uintptr_t)stage, stage_cap, 0, 0, UINT64_MAX,",
+                         "(uint8_t *)(uintptr_t)stage, stage_cap, 1, 0, UINT64_MAX,"),
     "file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)", 0),
     "direct_file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)", 1),
     "direct_file_id_of_first": ("make_direct_entry(pool, x, r, kind, j, id, file_id[r],",
@@ -50,8 +50,21 @@ MUTANTS = {
                             "(uint64_t)x->sqe_base + 2ull * c + kind;"),
     "file_id_of_first": ("s.file_id = file_id[r];", "s.file_id = file_id[0];", 0),
     "rsvd_dirty": ("memset(&s, 0, sizeof s);", "memset(&s, 0xff, sizeof s);", 0),
-    "cap_check_inclusive": ("if (x->stage_off + 2 * x->obj_bytes > stage_cap) continue;",
-                            "if (x->stage_off + 2 * x->obj_bytes >= stage_cap) continue;"),
+    "cap_check_inclusive": ("x->obj_bytes > (stage_cap - x->stage_off) / 2) {", "x->obj_bytes >= (stage_cap - x->stage_off) / 2) {"),
+    "cap_check_overflows": ("if (x->stage_off > stage_cap || x->obj_bytes > (stage_cap - x->stage_off) / 2) {",
+                            "if (x->stage_off + 2 * x->obj_bytes > stage_cap) {"),
+    "table_sum_inclusive": ("if (used > table_len) {", "if (used >= table_len) {"),
+    "table_sum_unchecked": ("if (used > table_len) {", "if (0) {"),
+    "table_sum_skips_only_one": ("    used += x->n_blocks;\n    if (used > table_len) {",
+                                 "    if (used + x->n_blocks > table_len) {\n      st |= ORC_ST_BAD_EXTENT;\n      continue;\n    }\n    used += x->n_blocks;\n    if (0) {"),
+    "extent_alignment_unchecked": ("if (x->stage_off % 16 != 0 || x->obj_bytes % 16 != 0) {", "if (0) {"),
+    "block_beyond_object_moved": ("if (((uint64_t)j + 1) * bb > x->obj_bytes) continue;", ""),
+    "block_beyond_object_off_by_one": ("if (((uint64_t)j + 1) * bb > x->obj_bytes) continue;",
+                                       "if (((uint64_t)j + 2) * bb > x->obj_bytes) continue;"),
+    "table_position_unchecked": ("if (g >= table_len) {", "if (0) {"),
+    "v_object_after_blocks": ("uint8_t *obj = stage + x->stage_off + kind * x->obj_bytes;",
+                              "uint8_t *obj = stage + x->stage_off + kind * filled;"),
+    "table_off_ignored": ("uint64_t g = (uint64_t)x->table_off + j;", "uint64_t g = used - x->n_blocks + j;"),
     "sgl_v_plane_uses_k_address": ("table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;",
                                    "table[i].addr = k_addr + (uint64_t)b * pool->block_stride;"),
     "sgl_ignores_stride": ("table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;",
@@ -87,8 +100,8 @@ MUTANTS = {
     "io_file_bound": ("s->file_off + s->len > store->file_stride) {", "s->file_off > store->file_stride) {"),
     "save_builds_read": ("ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);",
                          "ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);"),
-    "save_unpacks": ("  return orc_obj_pack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* retrieve_layer",
-                     "  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, stage, stage_cap, status);\n}\n\n/* retrieve_layer"),
+    "save_unpacks": ("  return orc_obj_pack(pool, cfg, extents, n_req, block_table, table_len, stage, stage_cap, status);\n}\n\n/* retrieve_layer",
+                     "  return orc_obj_unpack(pool, cfg, extents, n_req, block_table, table_len, stage, stage_cap, status);\n}\n\n/* retrieve_layer"),
     "ring_layer_planes_swapped": ("(uint64_t)(uintptr_t)pool->k_base, (uint64_t)(uintptr_t)pool->v_base, sgl_id, table,",
                                   "(uint64_t)(uintptr_t)pool->v_base, (uint64_t)(uintptr_t)pool->k_base, sgl_id, table,"),
     "retrieve_layer_writes": ("return ring_layer(ORC_OP_READ, sq,", "return ring_layer(ORC_OP_WRITE, sq,"),
