@@ -50,6 +50,7 @@ extern "C" {
 #define TUTTI_ST_STAGE_CAP 2u /* a request's objects end beyond stage_cap: request skipped */
 #define TUTTI_ST_SQE_CAP 4u   /* more entries than sqe_cap: the excess was not written */
 #define TUTTI_ST_DUP_BLOCK 8u /* tutti_table_validate only: a block id appears more than once in the table */
+#define TUTTI_ST_BAD_EXTENT 16u /* an extent that cannot be honoured: see tutti_obj_pack and tutti_sqe_build */
 
 /* One layer's paged pool (sec. 2.1 "Paged KV Memory Management"): a K plane and a V plane, each
  * num_blocks blocks of T*h*d*e bytes, block b at base + b*block_stride.  Planes stay owned by the
@@ -103,8 +104,8 @@ typedef struct tutti_sqe {
   uint8_t rsvd[16];    /* zero */
 } tutti_sqe;
 
-/* ---- a1: extents.  Sec. 3.1 ("one key object and one value object for each layer"), sec. 3.2
- * (offset and length of an I/O context).  For request r with n_r = d_n_blocks[r] hit blocks:
+/* ---- a1: extents.  Sec. 3.1 "Scalable GPU File Pool" (a K object and a V object per layer in a request's GPU
+ * file), sec. 3.2 (offset and length of an I/O context).  For request r with n_r = d_n_blocks[r] hit blocks:
  * obj_bytes = align_up(n_r*block_bytes, align), n_chunks = ceil(obj_bytes/chunk_bytes); stage_off,
  * sqe_base and table_off are the exclusive prefix sums over r of 2*obj_bytes, 2*n_chunks and n_r.
  * Writes d_extents[0..n_req) and d_totals[0] = staging bytes of a layer, d_totals[1] = entries of a
@@ -112,10 +113,21 @@ typedef struct tutti_sqe {
 int tutti_obj_layout(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
                      tutti_extent *d_extents, uint64_t *d_totals, void *stream);
 
-/* ---- a2: pack (save; store_layer of sec. 3.4).  For every request r, kind in {K, V} and j < n_r,
- * object bytes [j*block_bytes, (j+1)*block_bytes) <- pool block d_block_table[table_off_r + j], in
- * token-major order ((t*h + i)*d + k)*e whatever the pool layout; the tail up to obj_bytes <- 0.
- * The K object of r starts at d_stage + stage_off_r, its V object obj_bytes later.
+/* ---- a2: pack (save; store_layer of sec. 3.4 "Layer-wise Overlapping"; the objects of sec. 3.1).  For every
+ * request r, kind in {K, V} and j < n_blocks_r, object bytes [j*block_bytes, (j+1)*block_bytes) <- pool block
+ * d_block_table[table_off_r + j], in token-major order ((t*h + i)*d + k)*e whatever the pool layout; the tail
+ * from n_blocks_r*block_bytes up to obj_bytes_r <- 0.  The K object of r starts at d_stage + stage_off_r, its V
+ * object obj_bytes_r later.
+ * Extents: the fields stage_off, obj_bytes, n_blocks and table_off of every record are honoured as they stand,
+ * whoever wrote them (n_chunks and sqe_base are not used): tutti_obj_layout's output, a sub-range of it, records
+ * with gaps between the requests or in any order in the staging buffer.  What cannot be honoured is skipped and
+ * reported in *d_status, never dereferenced; per request, in this order:
+ *   running sum of n_blocks over the requests so far > table_len   request and all later ones skipped, BAD_EXTENT
+ *   stage_off or obj_bytes not a multiple of 16                    request skipped, BAD_EXTENT
+ *   stage_off + 2*obj_bytes > stage_cap (no wrap-around)           request skipped, STAGE_CAP
+ *   (j+1)*block_bytes > obj_bytes                                  block skipped, BAD_EXTENT
+ *   table_off + j >= table_len, or the id there >= num_blocks      block skipped, BAD_BLOCK
+ * Objects of different requests must not overlap (two writers race).
  * table_len = number of entries in d_block_table (entries beyond it are never read).
  * d_stage: 16-byte aligned, stage_cap bytes.  cu_budget: 0 = whole GPU, else the launch is limited
  * to about that many compute units' worth of workgroups (see tutti_layer_restore). */
@@ -123,9 +135,10 @@ int tutti_obj_pack(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_
                    const uint32_t *d_block_table, uint32_t table_len, void *d_stage, uint64_t stage_cap,
                    uint32_t cu_budget, uint32_t *d_status, void *stream);
 
-/* ---- a3: unpack (restore).  The inverse copy: pool block <- object bytes.  Padding is not read;
- * pool blocks not named in the table are not touched.  A block id must not appear twice in one
- * call (two writers of one block race). */
+/* ---- a3: unpack (restore; retrieve_layer of sec. 3.4, the objects of sec. 3.1).  The inverse copy: pool block <-
+ * object bytes, with the same extents contract and the same skip rules as tutti_obj_pack.  Padding is not read;
+ * pool blocks not named in the table are not touched.  A block id must not appear twice in one call (two writers
+ * of one block race). */
 int tutti_obj_unpack(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
                      const uint32_t *d_block_table, uint32_t table_len, const void *d_stage, uint64_t stage_cap,
                      uint32_t cu_budget, uint32_t *d_status, void *stream);
@@ -134,14 +147,20 @@ int tutti_obj_unpack(const tutti_pool *pool, const tutti_objcfg *cfg, const tutt
  * transfer, 2048 per IOCB).  One entry per chunk of every K and V object of `layer`, in the order
  * request ascending, K then V, chunk ascending; entry index = sqe_base_r + kind*n_chunks_r + chunk.
  * stage_addr is the address the entries should name for byte 0 of the staging buffer (multiple of
- * align); it is only arithmetic, never dereferenced.  Entries with index >= sqe_cap are dropped. */
+ * align); it is only arithmetic, never dereferenced.  Entries with index >= sqe_cap are dropped.
+ * Extents: the entry builders (this call, tutti_sqe_build_direct, tutti_iocb_fill_direct) number entries by
+ * sqe_base and table_off, so they take extents exactly as tutti_obj_layout writes them for these n_req requests:
+ * sqe_base and table_off running from 0 without gaps, obj_bytes and n_chunks as defined under a1 (stage_off is
+ * free: it is only added to stage_addr).  This is checked on the device; for any other extents the call writes
+ * nothing at all and reports TUTTI_ST_BAD_EXTENT. */
 int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_extent *d_extents, uint32_t n_req,
                     const uint32_t *d_file_id, uint32_t layer, uint32_t opcode, uint64_t stage_addr, uint32_t sgl_id,
                     tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t *d_status, void *stream);
 
 /* ---- a5 + a6: one layer's restore in ONE launch (retrieve_layer of sec. 3.4; "the CPU only loads
  * I/O kernels once per layer", sec. 1): extents from d_n_blocks, READ entries for `layer`, then the
- * unpack of every hit block, as tutti_obj_layout + tutti_sqe_build(READ) + tutti_obj_unpack would.
+ * unpack of every hit block, as tutti_obj_layout + tutti_sqe_build(READ) + tutti_obj_unpack would (so requests
+ * whose blocks run beyond table_len are skipped and reported as tutti_obj_unpack does).
  * Also writes d_extents[0..n_req) and d_totals[0..2).  d_stage must be device-accessible.
  * cu_budget stands in for the SM count of the paper's issue_io(IOCB_ids, SMs) (sec. 3.2): 0 = whole
  * GPU; B > 0 limits the grid to B compute units' worth of persistent workgroups so a concurrent
@@ -162,7 +181,7 @@ int tutti_layer_save(const tutti_pool *pool, const tutti_objcfg *cfg, const uint
                      void *stream);
 
 /* ---- direct-to-block mode: the paper's own data path, with no staging copy (sec. 3.1 "P2P Memory
- * Mapping Table", sec. 3.2 "an IOCTX records the SGL address, GPU file offset, and length").
+ * Mapping Table"; the three fields of an I/O context: sec. 3.2 "Zero-Copy Ring Buffers").
  *
  * 16-byte SGL descriptor of one pool block: address 8, length 4, identifier 4 (sec. 3.1). */
 typedef struct tutti_sgl {

@@ -268,6 +268,29 @@ int orc_obj_unpack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent
 /* ------------------------------------------------------------------ submission entries */
 
 /*
+ * The entry builders number entries by sqe_base (or by twice table_off in the direct-to-block mode), so the
+ * extents they take are the ones orc_obj_layout writes for exactly these requests: sizes that follow from
+ * n_blocks, offsets running from 0 without gaps and fitting 32 bits.  The paper is silent on other extents;
+ * reading taken: an entry builder handed anything else writes nothing and reports ORC_ST_BAD_EXTENT.
+ * stage_off is free (it is only added to the staging address).
+ */
+static int extents_are_dense(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req) {
+  const uint64_t bb = orc_block_bytes(pool);
+  uint64_t n_sqe = 0, n_tab = 0;
+  for (uint32_t r = 0; r < n_req; ++r) {
+    const orc_extent *x = &extents[r];
+    uint64_t obj = align_up((uint64_t)x->n_blocks * bb, cfg->align);
+    uint64_t chunks = (obj + cfg->chunk_bytes - 1) / cfg->chunk_bytes;
+    if (x->obj_bytes != obj || x->n_chunks != chunks) return 0;
+    if (x->sqe_base != n_sqe || x->table_off != n_tab) return 0;
+    n_sqe += 2 * chunks;
+    n_tab += x->n_blocks;
+    if (n_sqe > 0xffffffffull || n_tab > 0xffffffffull) return 0;
+  }
+  return 1;
+}
+
+/*
  * Entries of one layer in the order: request ascending; K object then V object; chunk ascending.
  * Each carries the I/O-context fields (address, GPU-file offset, length: sec. 3.2), the SGL
  * identifier (sec. 3.1) and its place in the 2048-slot IOCBs (sec. 3.2).  A request's GPU file
@@ -284,6 +307,10 @@ int orc_sqe_build(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent 
   if (opcode != ORC_OP_READ && opcode != ORC_OP_WRITE) return ORC_EINVAL;
   if (layer >= cfg->num_layers) return ORC_EINVAL;
   if (stage_addr % cfg->align != 0) return ORC_EINVAL;
+  if (!extents_are_dense(pool, cfg, extents, n_req)) {
+    if (status) *status |= ORC_ST_BAD_EXTENT;
+    return ORC_OK;
+  }
   const uint64_t C = cfg->chunk_bytes;
   uint32_t st = 0;
 
@@ -393,6 +420,10 @@ int orc_sqe_build_direct(const orc_pool *pool, const orc_objcfg *cfg, const orc_
   if (opcode != ORC_OP_READ && opcode != ORC_OP_WRITE) return ORC_EINVAL;
   if (layer >= cfg->num_layers) return ORC_EINVAL;
   if (sgl_table_addr % 16 != 0) return ORC_EINVAL;
+  if (!extents_are_dense(pool, cfg, extents, n_req)) {
+    if (status) *status |= ORC_ST_BAD_EXTENT;
+    return ORC_OK;
+  }
   uint64_t n_tab = 0;
   for (uint32_t r = 0; r < n_req; ++r) n_tab += extents[r].n_blocks;
   if (n_tab > 0 && !block_table) return ORC_EINVAL;
@@ -451,6 +482,10 @@ int orc_iocb_fill_direct(orc_iocb *sq, uint32_t depth, uint32_t first_slot, uint
   if (opcode != ORC_OP_READ && opcode != ORC_OP_WRITE) return ORC_EINVAL;
   if (layer >= cfg->num_layers || sgl_table_addr % 16 != 0) return ORC_EINVAL;
   if (n_req > 0 && (!extents || !file_id)) return ORC_EINVAL;
+  if (!extents_are_dense(pool, cfg, extents, n_req)) {
+    if (status) *status |= ORC_ST_BAD_EXTENT;
+    return ORC_OK;
+  }
   uint64_t n = 0;
   for (uint32_t r = 0; r < n_req; ++r) n += 2ull * extents[r].n_blocks;
   if (n > 0 && !block_table) return ORC_EINVAL;

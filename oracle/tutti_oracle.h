@@ -134,7 +134,10 @@ int orc_obj_unpack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent
                    const uint32_t *block_table, uint32_t table_len, const void *stage, uint64_t stage_cap,
                    uint32_t *status);
 
-/* One entry per chunk of every K and V object of one layer.  Entries with index >= sqe_cap are not written. */
+/* One entry per chunk of every K and V object of one layer.  Entries with index >= sqe_cap are not written.
+ * The entry builders (this one, orc_sqe_build_direct, orc_iocb_fill_direct) take extents exactly as orc_obj_layout
+ * writes them for these n_req requests (sqe_base and table_off running from 0 without gaps, obj_bytes and n_chunks
+ * following from n_blocks; stage_off is free); handed anything else they write nothing and set ORC_ST_BAD_EXTENT. */
 int orc_sqe_build(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req,
                   const uint32_t *file_id, uint32_t layer, uint32_t opcode, uint64_t stage_addr, uint32_t sgl_id,
                   orc_sqe *sqe, uint32_t sqe_cap, uint32_t *status);

@@ -20,7 +20,7 @@ OP_READ, OP_WRITE = 1, 2
 STREAM_SLOTS = 4096
 IOCB_SLOTS = 2048
 MAX_REQ = 2048
-ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP, ST_DUP_BLOCK = 1, 2, 4, 8
+ST_BAD_BLOCK, ST_STAGE_CAP, ST_SQE_CAP, ST_DUP_BLOCK, ST_BAD_EXTENT = 1, 2, 4, 8, 16
 
 # Declarations of the C records for decoding results on the host.
 EXTENT_DTYPE = np.dtype({"names": ["stage_off", "obj_bytes", "n_blocks", "n_chunks", "sqe_base", "table_off"],

@@ -404,7 +404,7 @@ int move_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti_exte
   if (table_len > 0 && !d_block_table) return TUTTI_EINVAL;
   if (!d_stage && (stage_cap > 0 || table_len > 0)) return TUTTI_EINVAL;
   if (!aligned16(d_stage)) return TUTTI_EINVAL;
-  if (n_req == 0 || table_len == 0) return TUTTI_OK;  // nothing to move
+  if (n_req == 0) return TUTTI_OK;  // nothing to move (with an empty table the kernel still reports the requests it skips)
   Launch L;
   // the workgroup size and unroll decide the item size, so settle them before sizing the grid
   rc = plan_launch(cu_budget, 0, &L);
@@ -482,7 +482,7 @@ int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti
   const uint64_t cap = static_cast<uint64_t>(cus) * 4;
   const uint32_t grid = static_cast<uint32_t>(need < cap ? need : cap);
   hipLaunchKernelGGL(k_sqe, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req), static_cast<hipStream_t>(stream), q,
-                     d_extents, n_req);
+                     ScanGeom{bb, cfg->align, cfg->chunk_bytes}, d_extents, n_req);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
@@ -623,7 +623,7 @@ int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, cons
   const uint64_t lim = static_cast<uint64_t>(cus) * 8;
   const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
   hipLaunchKernelGGL(k_sqe_direct, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req),
-                     static_cast<hipStream_t>(stream), q, d, d_extents, n_req);
+                     static_cast<hipStream_t>(stream), q, d, ScanGeom{bb, cfg->align, cfg->chunk_bytes}, d_extents, n_req);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
@@ -675,7 +675,7 @@ int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t
   const uint64_t lim = static_cast<uint64_t>(cus) * 8;
   const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
   hipLaunchKernelGGL(k_iocb_fill, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req), static_cast<hipStream_t>(stream),
-                     g, q, d, d_extents, n_req);
+                     g, q, d, ScanGeom{bb, cfg->align, cfg->chunk_bytes}, d_extents, n_req);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
@@ -766,6 +766,7 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
   m.layer = layer;
   m.file_stride = store->file_stride;
   m.ctx_cap = static_cast<uint64_t>(n_slots) * TUTTI_IOCB_SLOTS;
+  if (m.ctx_cap * m.slices_per_block > 0xffffffffull) return TUTTI_ERANGE;  // work items are numbered in 32 bits
   Launch G;
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;

@@ -63,20 +63,25 @@ __device__ __forceinline__ void st16(unsigned char *p, u32x4 v) {
 // Per-request offsets in LDS.  Laid out in the dynamic LDS block as
 //   u64 stage_off[R] | u64 obj_bytes[R] | u32 table_off[R+1] | u32 sqe_base[R+1]
 // with the totals in the two sentinel slots.  24*R + 8 bytes.
+// blk_off[r] is the number of blocks of the requests before r that the call moves: the copy loops number their
+// work items by it.  When the library computed the extents itself it is the table offset (same array); a copy
+// kernel that was handed extents keeps it in the sqe_base array, which it has no other use for.
 // ------------------------------------------------------------------------------------------
 struct ReqLds {
   uint64_t *stage_off;
   uint64_t *obj_bytes;
   uint32_t *table_off;
   uint32_t *sqe_base;
+  uint32_t *blk_off;
 };
 
-__device__ __forceinline__ ReqLds carve_lds(unsigned char *smem, uint32_t n_req) {
+__device__ __forceinline__ ReqLds carve_lds(unsigned char *smem, uint32_t n_req, bool caller_extents = false) {
   ReqLds l;
   l.stage_off = reinterpret_cast<uint64_t *>(smem);
   l.obj_bytes = l.stage_off + n_req;
   l.table_off = reinterpret_cast<uint32_t *>(l.obj_bytes + n_req);
   l.sqe_base = l.table_off + n_req + 1;
+  l.blk_off = caller_extents ? l.sqe_base : l.table_off;
   return l;
 }
 
@@ -127,12 +132,19 @@ struct ScanGeom {
 // Extents of all requests, computed by ONE wavefront (the caller passes lane = its lane id and
 // makes sure only one wave of the workgroup runs this).  64 requests per pass, running totals
 // carried between passes.  Results go to LDS and, when ext_out != nullptr, to global memory.
+// In the staged mode (file_id == nullptr) the requests are taken in order while the running sum of
+// their blocks stays within table_len: the request that pushes it beyond, and every later one, gets no
+// work items (its LDS table offset is the cut, so it owns no blocks) and TUTTI_ST_BAD_EXTENT is reported
+// by the workgroup that publishes.  The published extents are the plain sums either way.
 __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32_t *__restrict__ n_blocks, uint32_t n_req,
                                                   uint32_t lane, ReqLds l, tutti_extent *__restrict__ ext_out,
-                                                  uint64_t *__restrict__ totals_out, bool with_chunks = true,
+                                                  uint64_t *__restrict__ totals_out, uint32_t table_len,
+                                                  uint32_t *__restrict__ status, bool with_chunks = true,
                                                   const uint32_t *__restrict__ file_id = nullptr,
                                                   const FileArgs files = FileArgs{0, 0, 0}) {
   uint64_t carry_stage = 0, carry_sqe = 0, carry_tab = 0;
+  bool cut_found = false;   // wave-uniform: some request so far ran beyond the table
+  uint32_t cut_total = 0;   // blocks of the requests in front of the first such request
   for (uint32_t base = 0; base < n_req; base += kWave) {
     const uint32_t r = base + lane;
     const uint32_t n = (r < n_req) ? n_blocks[r] : 0u;
@@ -146,6 +158,13 @@ __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32
     const uint32_t active = n_req - base < kWave ? n_req - base : kWave;  // requests of this pass
     uint64_t inc_stage = 2 * obj, inc_sqe = 2 * chunks, inc_tab = n;
     wave_inclusive_scan3(inc_stage, inc_sqe, inc_tab, lane, active);
+    const bool beyond = !file_id && r < n_req && carry_tab + inc_tab > table_len;
+    const uint64_t beyond_mask = __ballot(beyond);
+    if (!cut_found && beyond_mask != 0) {
+      const uint32_t first = static_cast<uint32_t>(__ffsll(static_cast<long long>(beyond_mask))) - 1u;
+      cut_total = static_cast<uint32_t>(carry_tab + shfl_u64(inc_tab - n, first));
+      cut_found = true;
+    }
     if (r < n_req) {
       const uint64_t stage_off = carry_stage + inc_stage - 2 * obj;
       const uint32_t sqe_base = static_cast<uint32_t>(carry_sqe + inc_sqe - 2 * chunks);
@@ -154,7 +173,7 @@ __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32
       const bool has_file = fid >= files.first_file_id && rel < files.n_files;
       l.stage_off[r] = !file_id ? stage_off : has_file ? static_cast<uint64_t>(rel) * files.file_stride : kNoFile;
       l.obj_bytes[r] = obj;
-      l.table_off[r] = table_off;
+      l.table_off[r] = beyond ? cut_total : table_off;
       l.sqe_base[r] = sqe_base;
       if (ext_out) {
         tutti_extent e;
@@ -172,31 +191,127 @@ __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32
     carry_tab += shfl_u64(inc_tab, active - 1);
   }
   if (lane == 0) {
-    l.table_off[n_req] = static_cast<uint32_t>(carry_tab);
+    l.table_off[n_req] = cut_found ? cut_total : static_cast<uint32_t>(carry_tab);
     l.sqe_base[n_req] = static_cast<uint32_t>(carry_sqe);
     if (totals_out) {
       totals_out[0] = carry_stage;
       totals_out[1] = carry_sqe;
     }
+    if (cut_found && totals_out && status) atomicOr(status, TUTTI_ST_BAD_EXTENT);
   }
 }
 
-// Per-request offsets from extents the caller already has (workgroup-wide, then a barrier).
-__device__ __forceinline__ void lds_from_extents(const tutti_extent *__restrict__ ext, uint32_t n_req, ReqLds l) {
+// Per-request offsets for the entry builders, from extents the caller already has (workgroup-wide, with
+// barriers).  The entry builders number entries by sqe_base (or by twice table_off in the direct-to-block mode)
+// and take a request's chunk and block counts from the differences of consecutive offsets, which is right for
+// extents as tutti_obj_layout writes them for exactly these requests: offsets running from 0 without gaps, sizes
+// that follow from n_blocks.  That is checked here, every request against its successor; the result is the same
+// in every workgroup.  Returns false (after reporting TUTTI_ST_BAD_EXTENT once) if the extents are anything else:
+// the caller then writes nothing.
+__device__ __forceinline__ bool lds_from_extents(const tutti_extent *__restrict__ ext, uint32_t n_req, ReqLds l,
+                                                 const ScanGeom g, uint32_t *__restrict__ status) {
+  bool bad = false;
   for (uint32_t r = threadIdx.x; r < n_req; r += blockDim.x) {
     const tutti_extent e = ext[r];
     l.stage_off[r] = e.stage_off;
     l.obj_bytes[r] = e.obj_bytes;
     l.table_off[r] = e.table_off;
     l.sqe_base[r] = e.sqe_base;
-    if (r + 1 == n_req) {
-      l.table_off[n_req] = e.table_off + e.n_blocks;
-      l.sqe_base[n_req] = e.sqe_base + 2u * e.n_chunks;
+    const uint64_t raw = static_cast<uint64_t>(e.n_blocks) * g.block_bytes;
+    const uint64_t obj = (raw + (g.align - 1)) & ~static_cast<uint64_t>(g.align - 1);
+    bad = bad || e.obj_bytes != obj || e.n_chunks != (obj + g.chunk_bytes - 1) / g.chunk_bytes;
+    // 64-bit sums: offsets that would wrap around 32 bits are not dense either
+    const uint64_t next_sqe = static_cast<uint64_t>(e.sqe_base) + 2ull * e.n_chunks;
+    const uint64_t next_tab = static_cast<uint64_t>(e.table_off) + e.n_blocks;
+    bad = bad || next_sqe > 0xffffffffull || next_tab > 0xffffffffull;
+    if (r == 0) bad = bad || e.sqe_base != 0 || e.table_off != 0;
+    if (r + 1 < n_req) {
+      const tutti_extent f = ext[r + 1];
+      bad = bad || f.sqe_base != next_sqe || f.table_off != next_tab;
+    } else {
+      l.table_off[n_req] = static_cast<uint32_t>(next_tab);
+      l.sqe_base[n_req] = static_cast<uint32_t>(next_sqe);
     }
   }
   if (n_req == 0 && threadIdx.x == 0) {
     l.table_off[0] = 0;
     l.sqe_base[0] = 0;
+  }
+  const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;  // also publishes the LDS writes above
+  if (any_bad && blockIdx.x == 0 && threadIdx.x == 0 && status) atomicOr(status, TUTTI_ST_BAD_EXTENT);
+  return !any_bad;
+}
+
+__device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t a, uint32_t lane, uint32_t active) {
+  for (uint32_t d = 1; d < active; d <<= 1) {
+    const uint64_t t = shfl_up_u64(a, d);
+    if (lane >= d) a += t;
+  }
+  return a;
+}
+
+// Per-request offsets for the copy kernels, from extents the caller hands in: every field is honoured as it
+// stands (a gap between requests, any order in the staging buffer, a table range that does not start at 0), and
+// what cannot be honoured is taken out here, once, so that the copy loop never sees it:
+//   - requests are taken in order while the running sum of n_blocks stays within table_len; the request that
+//     pushes it beyond and every later one get no work items (TUTTI_ST_BAD_EXTENT);
+//   - a request whose stage_off or obj_bytes is not a multiple of 16 (TUTTI_ST_BAD_EXTENT), or whose two objects
+//     do not fit in stage_cap (TUTTI_ST_STAGE_CAP), keeps its work items but gets a zero-sized object, so the
+//     copy loop skips every block of it;
+//   - blocks that would end beyond their object are skipped by the copy loop (TUTTI_ST_BAD_EXTENT).
+// All threads stage the raw fields, then the first wavefront scans n_blocks (64 requests per pass) into
+// blk_off[], the numbering of the work items.  Workgroup 0 reports.
+__device__ __forceinline__ void lds_from_caller_extents(const tutti_extent *__restrict__ ext, uint32_t n_req, ReqLds l,
+                                                        uint32_t table_len, uint32_t block_bytes, uint64_t stage_cap,
+                                                        uint32_t *__restrict__ status) {
+  for (uint32_t r = threadIdx.x; r < n_req; r += blockDim.x) {
+    const tutti_extent e = ext[r];
+    l.stage_off[r] = e.stage_off;
+    l.obj_bytes[r] = e.obj_bytes;
+    l.table_off[r] = e.table_off;
+    l.blk_off[r] = e.n_blocks;  // replaced by its exclusive prefix sum below
+  }
+  __syncthreads();
+  if (threadIdx.x < kWave) {
+    const uint32_t lane = threadIdx.x;
+    uint64_t carry = 0;
+    bool cut_found = false;
+    uint32_t cut_total = 0, flags = 0;
+    for (uint32_t base = 0; base < n_req; base += kWave) {
+      const uint32_t r = base + lane;
+      const uint32_t active = n_req - base < kWave ? n_req - base : kWave;
+      const uint32_t n = r < n_req ? l.blk_off[r] : 0u;
+      const uint64_t incl = carry + wave_inclusive_scan(n, lane, active);
+      const bool beyond = r < n_req && incl > table_len;
+      const uint64_t beyond_mask = __ballot(beyond);
+      if (!cut_found && beyond_mask != 0) {
+        const uint32_t first = static_cast<uint32_t>(__ffsll(static_cast<long long>(beyond_mask))) - 1u;
+        cut_total = static_cast<uint32_t>(shfl_u64(incl - n, first));
+        cut_found = true;
+      }
+      if (r < n_req) {
+        const uint64_t so = l.stage_off[r], ob = l.obj_bytes[r];
+        bool dead = true;
+        if (beyond)
+          flags |= TUTTI_ST_BAD_EXTENT;
+        else if (((so | ob) & 15u) != 0)
+          flags |= TUTTI_ST_BAD_EXTENT;
+        else if (so > stage_cap || ob > (stage_cap - so) / 2)
+          flags |= TUTTI_ST_STAGE_CAP;
+        else {
+          dead = false;
+          if (static_cast<uint64_t>(n) * block_bytes > ob) flags |= TUTTI_ST_BAD_EXTENT;
+        }
+        if (dead) {
+          l.stage_off[r] = 0;
+          l.obj_bytes[r] = 0;
+        }
+        l.blk_off[r] = beyond ? cut_total : static_cast<uint32_t>(incl - n);
+      }
+      carry = shfl_u64(incl, active - 1);
+    }
+    if (lane == 0) l.blk_off[n_req] = cut_found ? cut_total : static_cast<uint32_t>(carry);
+    if (flags != 0 && blockIdx.x == 0 && status) atomicOr(status, flags);
   }
   __syncthreads();
 }
@@ -543,10 +658,11 @@ __device__ __forceinline__ void emit_iocbs(const RingArgs g, const SqeArgs a, co
 }
 
 __global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, const SqeArgs a, const DirectArgs d,
-                                                           const tutti_extent *__restrict__ ext, uint32_t n_req) {
+                                                           const ScanGeom geom, const tutti_extent *__restrict__ ext,
+                                                           uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
-  lds_from_extents(ext, n_req, l);
+  if (!lds_from_extents(ext, n_req, l, geom, a.status)) return;
   emit_iocbs(g, a, d, l, n_req, 0, gridDim.x, iocb_head(g, a, d, l, n_req, 0, gridDim.x));
 }
 
@@ -674,11 +790,11 @@ __global__ void k_cq_check(const tutti_iocb *sq, uint32_t slot, uint32_t *flag) 
   }
 }
 
-__global__ __launch_bounds__(kWgThreads) void k_sqe_direct(const SqeArgs a, const DirectArgs d,
+__global__ __launch_bounds__(kWgThreads) void k_sqe_direct(const SqeArgs a, const DirectArgs d, const ScanGeom geom,
                                                             const tutti_extent *__restrict__ ext, uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
-  lds_from_extents(ext, n_req, l);
+  if (!lds_from_extents(ext, n_req, l, geom, a.status)) return;
   emit_direct_sqes(a, d, l, n_req);
 }
 
@@ -766,20 +882,24 @@ struct Item {
   uint32_t kind;
 };
 
+// SEP: the extents came from the caller (lds_from_caller_extents): items are numbered by blk_off, the table is
+// indexed by the request's own table_off, and requests that cannot be honoured already have a zero-sized object.
+template <bool SEP>
 __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, uint32_t n_req, uint32_t it,
                                             uint32_t lane) {
   Item d;
   const uint32_t S = a.slices_per_block;
   const uint32_t u = it / S;  // (block, kind) unit in staging order
   d.s = it - u * S;
-  const uint32_t r = find_owner(l.table_off, n_req, u >> 1);
-  const uint32_t toff = l.table_off[r];
-  d.n = l.table_off[r + 1] - toff;
+  const uint32_t *off = SEP ? l.blk_off : l.table_off;
+  const uint32_t r = find_owner(off, n_req, u >> 1);
+  const uint32_t toff = off[r];
+  d.n = off[r + 1] - toff;
   const uint32_t v = u - 2u * toff;
   d.kind = v >= d.n ? 1u : 0u;
   d.j = v - d.kind * d.n;
   d.obj_bytes = l.obj_bytes[r];
-  d.tab_idx = toff + d.j;
+  d.tab_idx = (SEP ? l.table_off[r] : toff) + d.j;
   const uint64_t stage_off = l.stage_off[r];
   if (a.direct) {
     // same arithmetic as the context's file offset (direct_entry_quarter), then the I/O kernel's checks
@@ -797,12 +917,12 @@ __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, 
   }
   d.obj_ptr = a.stage + stage_off + d.kind * d.obj_bytes;
   d.obj_blk = d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes;
-  const uint64_t end = stage_off + 2 * d.obj_bytes;
-  if (end > a.stage_cap || end < stage_off) {  // the request's objects do not fit: skip it, report once
+  if (!SEP && (stage_off > a.stage_cap || d.obj_bytes > (a.stage_cap - stage_off) / 2)) {
+    // the request's objects do not fit: skip it, report once
     if (lane == 0 && d.j == 0 && d.s == 0 && d.kind == 0 && a.status) atomicOr(a.status, TUTTI_ST_STAGE_CAP);
     d.obj_ptr = nullptr;
   } else if ((static_cast<uint64_t>(d.j) + 1) * a.block_bytes > d.obj_bytes) {
-    d.obj_ptr = nullptr;  // inconsistent extents: stay inside the object
+    d.obj_ptr = nullptr;  // the block would end beyond its object (caller-made extents only)
   }
   return d;
 }
@@ -919,19 +1039,30 @@ __device__ __forceinline__ void store_preloaded(const MoveArgs &a, const Item &d
 // grid may hold other workgroups with other work).
 // Software-pipelined by one item: the next item is decoded and its block id requested before the
 // current item's loads and stores are issued.
-template <int DIR, bool HND, int U, int NT>
+// Number of work items of a copy.  Staged mode: the scan (or the loader of caller-made extents) has already cut
+// the requests at table_len blocks.  Direct-to-block mode: one unit per recorded context.  The host checked that
+// the bound (2 * table_len, or the contexts the IOCBs hold) times the slices per block fits 32 bits.
+template <bool SEP>
+__device__ __forceinline__ uint32_t count_items(const MoveArgs &a, const ReqLds &l, uint32_t n_req) {
+  if (a.direct) {
+    const uint64_t units = 2ull * l.table_off[n_req];
+    return static_cast<uint32_t>(units < a.ctx_cap ? units : a.ctx_cap) * a.slices_per_block;
+  }
+  return 2u * (SEP ? l.blk_off[n_req] : l.table_off[n_req]) * a.slices_per_block;
+}
+
+template <int DIR, bool HND, int U, int NT, bool SEP>
 __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t wg,
                                            uint32_t copy_wgs, const Preload<U> &pre) {
+  constexpr uint32_t kSlice = kWave * 16u * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const uint32_t n_waves = copy_wgs * (blockDim.x / kWave);
-  // never more blocks than the table holds, whatever the extents claim
-  const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
-  const uint32_t n_items = 2u * total_blocks * a.slices_per_block;  // the host checked this fits 32 bits
+  const uint32_t n_items = count_items<SEP>(a, l, n_req);
 
   uint32_t it = item_wg(a, wg, copy_wgs) * (blockDim.x / kWave) + wave_in_wg;
   if (it >= n_items) return;
-  Item cur = decode_item(a, l, n_req, it, lane);
+  Item cur = decode_item<SEP>(a, l, n_req, it, lane);
   uint32_t id = load_block_id(a, cur);
   bool first = true;
   for (;;) {
@@ -940,10 +1071,15 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
     Item nxt = cur;
     uint32_t nid = a.num_blocks;
     if (more) {
-      nxt = decode_item(a, l, n_req, nit, lane);
+      nxt = decode_item<SEP>(a, l, n_req, nit, lane);
       nid = load_block_id(a, nxt);
     }
-    if (DIR == kUnpack && first && pre.valid)
+    // the preloaded bytes are those of staging item `it`; extents the library computed put the item's slice
+    // exactly there, extents from the caller may not: then the slice is loaded from where they say
+    const bool preloaded = DIR == kUnpack && first && pre.valid &&
+                           (!SEP || cur.obj_blk + static_cast<uint64_t>(cur.s) * kSlice ==
+                                        a.stage + static_cast<uint64_t>(it) * kSlice);
+    if (preloaded)
       store_preloaded<HND, U, NT>(a, cur, id, lane, pre);
     else
       move_one<DIR, HND, U, NT>(a, cur, id, lane);
@@ -1034,13 +1170,12 @@ struct TileMove {
 // One tile per workgroup and iteration.  Not pipelined across tiles: holding the next tile's loads in
 // registers cost the eighth resident workgroup per CU (more than 64 VGPRs) and bought 0.3 us; the eight
 // workgroups of a CU cover each other's latency instead.
-template <int DIR, int PT, int WG>
+template <int DIR, int PT, int WG, bool SEP>
 __device__ __forceinline__ void move_items_hnd_lds(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t wg,
                                                    uint32_t copy_wgs, unsigned char *tile) {
   typedef TileMove<DIR, PT, WG> TM;
   const uint32_t tid = threadIdx.x;
-  const uint32_t total_blocks = l.table_off[n_req] < a.table_len ? l.table_off[n_req] : a.table_len;
-  const uint32_t n_items = 2u * total_blocks * a.slices_per_block;
+  const uint32_t n_items = count_items<SEP>(a, l, n_req);
   TileGeom g;
   g.rs = a.row_shift;
   g.gs = a.row_shift + a.head_shift;
@@ -1050,7 +1185,7 @@ __device__ __forceinline__ void move_items_hnd_lds(const MoveArgs a, const ReqLd
   g.r_mask = (1u << g.rs) - 1u;
 
   for (uint32_t it = wg; it < n_items; it += copy_wgs) {
-    const Item d = decode_item(a, l, n_req, it, tid);  // workgroup-uniform; thread 0 reports
+    const Item d = decode_item<SEP>(a, l, n_req, it, tid);  // workgroup-uniform; thread 0 reports
     const uint32_t id = load_block_id(a, d);
     if (d.obj_ptr != nullptr && id < a.num_blocks) {
       u32x4 v[PT];
@@ -1083,14 +1218,14 @@ struct LayoutArgs {
 __global__ __launch_bounds__(kWave) void k_layout(const LayoutArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
-  wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, a.extents, a.totals);
+  wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, a.extents, a.totals, 0xffffffffu, nullptr);
 }
 
-__global__ __launch_bounds__(kWgThreads) void k_sqe(const SqeArgs a, const tutti_extent *__restrict__ ext,
-                                                     uint32_t n_req) {
+__global__ __launch_bounds__(kWgThreads) void k_sqe(const SqeArgs a, const ScanGeom g,
+                                                     const tutti_extent *__restrict__ ext, uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
-  lds_from_extents(ext, n_req, l);
+  if (!lds_from_extents(ext, n_req, l, g, a.status)) return;
   emit_sqes(a, l, n_req, 0, gridDim.x, sqe_head(a, l, n_req, 0));
 }
 
@@ -1098,21 +1233,21 @@ template <int DIR, bool HND, int U, int NT, int WG>
 __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_move(const MoveArgs a, const tutti_extent *__restrict__ ext,
                                                       uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const ReqLds l = carve_lds(smem, n_req);
+  const ReqLds l = carve_lds(smem, n_req, true);
   Preload<U> pre;
   pre.valid = false;
   if (DIR == kUnpack) pre = preload_first<U, NT>(a, blockIdx.x, gridDim.x);
-  lds_from_extents(ext, n_req, l);
-  move_items<DIR, HND, U, NT>(a, l, n_req, blockIdx.x, gridDim.x, pre);
+  lds_from_caller_extents(ext, n_req, l, a.table_len, a.block_bytes, a.stage_cap, a.status);
+  move_items<DIR, HND, U, NT, true>(a, l, n_req, blockIdx.x, gridDim.x, pre);
 }
 
 template <int DIR, int PT, int WG>
 __global__ __launch_bounds__(WG, min_waves_per_simd(WG, PT)) void k_move_lds(const MoveArgs a, const tutti_extent *__restrict__ ext,
                                                   uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const ReqLds l = carve_lds(smem, n_req);
-  lds_from_extents(ext, n_req, l);
-  move_items_hnd_lds<DIR, PT, WG>(a, l, n_req, blockIdx.x, gridDim.x, smem + align16(req_lds_bytes(n_req)));
+  const ReqLds l = carve_lds(smem, n_req, true);
+  lds_from_caller_extents(ext, n_req, l, a.table_len, a.block_bytes, a.stage_cap, a.status);
+  move_items_hnd_lds<DIR, PT, WG, true>(a, l, n_req, blockIdx.x, gridDim.x, smem + align16(req_lds_bytes(n_req)));
 }
 
 // One layer's restore (DIR = kUnpack) or save (DIR = kPack) in one launch: every workgroup redoes the
@@ -1143,13 +1278,13 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer(const M
   if (threadIdx.x < kWave) {
     const bool publish = blockIdx.x == 0;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
-                      publish ? a.totals : nullptr, blockIdx.x < w.sqe_wgs);
+                      publish ? a.totals : nullptr, m.table_len, m.status, blockIdx.x < w.sqe_wgs);
   }
   __syncthreads();
   SqeHead head;
   head.live = false;
   if (blockIdx.x < w.sqe_wgs) head = sqe_head(q, l, a.n_req, 0);
-  if (copies) move_items<DIR, HND, U, NT>(m, l, a.n_req, wg, w.copy_wgs, pre);
+  if (copies) move_items<DIR, HND, U, NT, false>(m, l, a.n_req, wg, w.copy_wgs, pre);
   if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
@@ -1168,7 +1303,7 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(co
     const bool publish = blockIdx.x == 0;
     // chunk counts only matter for the published extents; the LDS copy gets file starts instead of staging offsets
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
-                      publish ? a.totals : nullptr, publish, q.file_id, f);
+                      publish ? a.totals : nullptr, 0xffffffffu, nullptr, publish, q.file_id, f);
   }
   __syncthreads();
   DirectHead head;
@@ -1177,7 +1312,7 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(co
   Preload<U> pre;
   pre.valid = false;
   if (blockIdx.x - w.copy_first < w.copy_wgs)
-    move_items<DIR, false, U, 3>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs, pre);
+    move_items<DIR, false, U, 3, false>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs, pre);
   if (blockIdx.x < w.sqe_wgs) emit_iocbs(g, q, d, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
@@ -1188,14 +1323,14 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, PT)) void k_layer_lds(co
   if (threadIdx.x < kWave) {
     const bool publish = blockIdx.x == 0;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
-                      publish ? a.totals : nullptr, blockIdx.x < w.sqe_wgs);
+                      publish ? a.totals : nullptr, m.table_len, m.status, blockIdx.x < w.sqe_wgs);
   }
   __syncthreads();
   SqeHead head;
   head.live = false;
   if (blockIdx.x < w.sqe_wgs) head = sqe_head(q, l, a.n_req, 0);
   if (blockIdx.x - w.copy_first < w.copy_wgs)
-    move_items_hnd_lds<DIR, PT, WG>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs,
+    move_items_hnd_lds<DIR, PT, WG, false>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs,
                                     smem + align16(req_lds_bytes(a.n_req)));
   if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
 }

@@ -938,6 +938,53 @@ def check_caller_extents(orc, seed=47):
     assert st == 0
 
 
+def check_entry_builders_want_layout_extents(orc, seed=53):
+    """The entry builders take extents as obj_layout writes them; anything else: nothing written, BAD_EXTENT."""
+    rng = np.random.default_rng(seed)
+    T, h, d, e, N, A = 4, 2, 8, 2, 32, 128
+    bb = T * h * d * e
+    k, v = _planes(rng, N, bb)
+    p = _pool(orc, T, h, d, e, N, k, v)
+    cfg = orc.make_cfg(A, 2 * A, 2)
+    n = np.array([3, 2, 4], np.uint32)
+    table = rng.permutation(N)[:9].astype(np.uint32)
+    fid = np.array([7, 8, 9], np.uint32)
+    ext, tot = orc.obj_layout(p, cfg, n)
+    good, st = orc.sqe_build(p, cfg, ext, fid, 1, orc.OP_READ, 4096, 5)
+    assert st == 0 and good.size == int(tot[1]) and np.all(good["len"] > 0)
+    gd, st = orc.sqe_build_direct(p, cfg, ext, table, fid, 1, orc.OP_WRITE, 1 << 20, 5)
+    assert st == 0 and np.all(gd["len"] == bb)
+
+    def variants():
+        for field, delta in (("sqe_base", 2), ("table_off", 1), ("obj_bytes", A), ("n_chunks", 1), ("n_blocks", 1)):
+            for r in range(3):
+                x = ext.copy()
+                x[field][r] += delta
+                yield f"{field}[{r}]", x, fid
+        yield "requests 1.. alone", ext[1:].copy(), fid[1:]
+        # one request whose entry count no longer fits 32 bits (2 * 2^31 chunks), everything else consistent
+        big, _ = orc.obj_layout(p, cfg, [0xFFFFFFFF])
+        assert int(big["n_chunks"][0]) == 1 << 31
+        yield "entry count beyond 32 bits", big, fid[:1]
+
+    for name, x, f in variants():
+        sqe, st = orc.sqe_build(p, cfg, x, f, 1, orc.OP_READ, 4096, 5, sqe_cap=int(tot[1]))
+        assert st == orc.ST_BAD_EXTENT and not sqe.view(np.uint8).any(), f"sqe_build with {name}"
+        sqe, st = orc.sqe_build_direct(p, cfg, x, table, f, 1, orc.OP_WRITE, 1 << 20, 5, sqe_cap=18)
+        assert st == orc.ST_BAD_EXTENT and not sqe.view(np.uint8).any(), f"sqe_build_direct with {name}"
+        sq, cq = orc.ring_alloc(2)
+        orc.ring_init(sq, cq)
+        before = sq.copy()
+        st = orc.iocb_fill_direct(sq, 0, 1, p, cfg, x, table, f, 1, orc.OP_WRITE, 1 << 20, 5)
+        assert st == orc.ST_BAD_EXTENT and sq.tobytes() == before.tobytes(), f"iocb_fill_direct with {name}"
+    # the staging offset is free: it only moves the addresses
+    x = ext.copy()
+    x["stage_off"] += 1 << 20
+    sqe, st = orc.sqe_build(p, cfg, x, fid, 1, orc.OP_READ, 4096, 5)
+    assert st == 0 and np.array_equal(sqe["addr"], good["addr"] + (1 << 20))
+    assert np.array_equal(sqe["file_off"], good["file_off"])
+
+
 def check_table_validate(orc, seed=43):
     """Duplicates and out-of-range ids, against numpy.unique on independently built tables."""
     rng = np.random.default_rng(seed)
@@ -961,4 +1008,5 @@ def check_table_validate(orc, seed=43):
 ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
               check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io,
-              check_ring_layer, check_table_validate, check_caller_extents]
+              check_ring_layer, check_table_validate, check_caller_extents,
+              check_entry_builders_want_layout_extents]

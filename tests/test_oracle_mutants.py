@@ -64,6 +64,12 @@ MUTANTS = {
     "table_position_unchecked": ("if (g >= table_len) {", "if (0) {"),
     "v_object_after_blocks": ("uint8_t *obj = stage + x->stage_off + kind * x->obj_bytes;",
                               "uint8_t *obj = stage + x->stage_off + kind * filled;"),
+    "dense_check_skipped_sqe": ("if (!extents_are_dense(pool, cfg, extents, n_req)) {", "if (0) {", 0),
+    "dense_check_skipped_direct": ("if (!extents_are_dense(pool, cfg, extents, n_req)) {", "if (0) {", 1),
+    "dense_check_skipped_fill": ("if (!extents_are_dense(pool, cfg, extents, n_req)) {", "if (0) {", 2),
+    "dense_ignores_sizes": ("if (x->obj_bytes != obj || x->n_chunks != chunks) return 0;", ""),
+    "dense_ignores_offsets": ("if (x->sqe_base != n_sqe || x->table_off != n_tab) return 0;", ""),
+    "dense_ignores_wrap": ("if (n_sqe > 0xffffffffull || n_tab > 0xffffffffull) return 0;", ""),
     "table_off_ignored": ("uint64_t g = (uint64_t)x->table_off + j;", "uint64_t g = used - x->n_blocks + j;"),
     "sgl_v_plane_uses_k_address": ("table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;",
                                    "table[i].addr = k_addr + (uint64_t)b * pool->block_stride;"),
