@@ -146,6 +146,46 @@ def check_unpack(orc, c, ext, o_ext, o_tot, cu_budget=0, seed=99, stage_cap=None
     return stage
 
 
+def check_moves_with_extents(orc, c, x, stage_bytes, table_len=None, stage_cap=None, cu_budget=0, seed=77, label=""):
+    """tutti_obj_pack and tutti_obj_unpack with extents written by the test (numpy records, B.EXTENT_DTYPE),
+    whole buffers and the status word against the oracle given the very same records."""
+    x = np.ascontiguousarray(x, dtype=B.EXTENT_DTYPE)
+    o_x = np.zeros(x.size, orc.EXTENT_DTYPE)
+    for f in B.EXTENT_DTYPE.names:
+        o_x[f] = x[f]
+    n_req = int(x.size)
+    d_x = torch.from_numpy(x.view(np.uint8).copy()).to(DEV) if n_req else torch.zeros(32, dtype=torch.uint8, device=DEV)
+    tl = c.table.size if table_len is None else table_len
+    cap = stage_bytes if stage_cap is None else stage_cap
+    nbytes = max(stage_bytes, 16)
+    # pack
+    stage = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=DEV)
+    st = new_status()
+    B.tutti_obj_pack(c.gpu_pool(), c.gpu_cfg(), d_x, n_req, c.d_table, tl, stage, cap, cu_budget, st)
+    torch.cuda.synchronize()
+    o_stage = np.full(nbytes, 0xA5, np.uint8)
+    o_st = orc.obj_pack(c.orc_pool(orc), c.orc_cfg(orc), o_x, c.table, o_stage, stage_cap=cap, table_len=tl)
+    got = stage.cpu().numpy()
+    assert np.array_equal(got, o_stage), f"{c.name} {label}: packed bytes differ at {first_diff(got, o_stage)}"
+    assert int(st.item()) == o_st, f"{c.name} {label}: pack status {int(st.item())} vs oracle {o_st}"
+    # unpack
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    stage = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=DEV, generator=g)
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    st = new_status()
+    B.tutti_obj_unpack(c.gpu_pool(k2, v2), c.gpu_cfg(), d_x, n_req, c.d_table, tl, stage, cap, cu_budget, st)
+    torch.cuda.synchronize()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    o_st = orc.obj_unpack(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), o_x, c.table, stage.cpu().numpy(), stage_cap=cap,
+                          table_len=tl)
+    gk, gv = k2.cpu().numpy(), v2.cpu().numpy()
+    assert np.array_equal(gk, ok), f"{c.name} {label}: K plane differs at byte {first_diff(gk, ok)}"
+    assert np.array_equal(gv, ov), f"{c.name} {label}: V plane differs at byte {first_diff(gv, ov)}"
+    assert int(st.item()) == o_st, f"{c.name} {label}: unpack status {int(st.item())} vs oracle {o_st}"
+    return o_st
+
+
 def check_sqe(orc, c, ext, o_ext, o_tot, layer=0, stage_addr=0x7F1200000000, sgl_id=42, sqe_cap=None):
     n = int(o_tot[1])
     cap = n if sqe_cap is None else sqe_cap
@@ -165,7 +205,8 @@ def check_sqe(orc, c, ext, o_ext, o_tot, layer=0, stage_addr=0x7F1200000000, sgl
 
 
 def check_layer_restore(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000, sgl_id=7, seed=5, sqe_cap=None,
-                        stage_cap=None):
+                        stage_cap=None, table_len=None):
+    tl = c.table.size if table_len is None else table_len
     o_ext0, o_tot0 = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
     nbytes = max(int(o_tot0[0]), 16)
     n_sqe = int(o_tot0[1])
@@ -179,13 +220,13 @@ def check_layer_restore(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000,
     tot = torch.zeros(2, dtype=torch.int64, device=DEV)
     sqe = torch.full((max(cap, 1) * 64,), 0x3C, dtype=torch.uint8, device=DEV)
     st = new_status()
-    B.tutti_layer_restore(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id,
+    B.tutti_layer_restore(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, tl, c.d_file_id,
                           layer, stage, scap, stage_addr, sgl_id, ext, tot, sqe, cap, cu_budget, st)
     torch.cuda.synchronize()
     ok, ov = c.k_host.copy(), c.v_host.copy()
     o_ext, o_tot, o_sqe, o_st = orc.layer_restore(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks, c.table,
                                                   c.file_id, layer, stage.cpu().numpy(), stage_addr, sgl_id, cap,
-                                                  stage_cap=scap)
+                                                  stage_cap=scap, table_len=tl)
     assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes()
     assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot)
     n_written = min(n_sqe, cap)
@@ -198,7 +239,9 @@ def check_layer_restore(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000,
     assert int(st.item()) == o_st
 
 
-def check_layer_save(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000, sgl_id=8, sqe_cap=None, stage_cap=None):
+def check_layer_save(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000, sgl_id=8, sqe_cap=None, stage_cap=None,
+                     table_len=None):
+    tl = c.table.size if table_len is None else table_len
     o_ext0, o_tot0 = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
     nbytes = max(int(o_tot0[0]), 16)
     n_sqe = int(o_tot0[1])
@@ -209,12 +252,12 @@ def check_layer_save(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000, sg
     tot = torch.zeros(2, dtype=torch.int64, device=DEV)
     sqe = torch.full((max(cap, 1) * 64,), 0x3C, dtype=torch.uint8, device=DEV)
     st = new_status()
-    B.tutti_layer_save(c.gpu_pool(), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id, layer,
+    B.tutti_layer_save(c.gpu_pool(), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, tl, c.d_file_id, layer,
                        stage, scap, stage_addr, sgl_id, ext, tot, sqe, cap, cu_budget, st)
     torch.cuda.synchronize()
     o_stage = np.full(nbytes, 0x5A, np.uint8)
     o_ext, o_tot, o_sqe, o_st = orc.layer_save(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks, c.table, c.file_id, layer,
-                                               o_stage, stage_addr, sgl_id, cap, stage_cap=scap)
+                                               o_stage, stage_addr, sgl_id, cap, stage_cap=scap, table_len=tl)
     assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes()
     assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot)
     w = min(n_sqe, cap)

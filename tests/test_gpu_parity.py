@@ -726,27 +726,166 @@ def test_small_capacities_are_clamped_and_reported(orc, H):
 
 
 def test_short_table_is_never_overrun(orc, H):
-    """table_len smaller than the extents claim: the missing blocks are skipped and reported."""
+    """table_len smaller than the extents claim: the request that runs beyond it is skipped and reported, by the
+    separate calls and by the fused ones alike."""
     say("edge: short table")
     rng = np.random.default_rng(10)
-    c = H.LayerCase(T=16, h=2, d=64, e=2, N=64, n_blocks=[6, 6], table=rng.permutation(64)[:12], name="short")
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=64, n_blocks=[6, 6, 0, 1], table=rng.permutation(64)[:13], name="short")
     ext, tot, o_ext, o_tot = H.check_layout(orc, c)
-    stage = torch.full((int(o_tot[0]),), 0xA5, dtype=torch.uint8, device=H.DEV)
-    st = H.new_status()
-    B.tutti_obj_pack(c.gpu_pool(), c.gpu_cfg(), ext, 2, c.d_table, 8, stage, int(o_tot[0]), 0, st)
-    torch.cuda.synchronize()
-    # the oracle sees the same situation as a table whose tail ids are out of range
-    t2 = c.table.copy()
-    t2[8:] = 0xFFFFFFFF
-    o_stage = np.full(int(o_tot[0]), 0xA5, np.uint8)
-    orc.obj_pack(c.orc_pool(orc), c.orc_cfg(orc), o_ext, t2, o_stage)
-    got = stage.cpu().numpy()
-    bb = c.bb
-    # blocks 0..7 of the flattened table are packed; blocks 8..11 (request 1, j = 2..5) are not
-    assert np.array_equal(got[: 6 * bb], o_stage[: 6 * bb])
-    k1 = int(o_ext["stage_off"][1])
-    assert np.array_equal(got[k1: k1 + 2 * bb], o_stage[k1: k1 + 2 * bb])
-    assert np.all(got[k1 + 2 * bb: k1 + 6 * bb] == 0xA5)
+    for tl in (12, 8, 6, 5, 0):
+        assert H.check_moves_with_extents(orc, c, H.ext_np(ext, c.n_req), int(o_tot[0]), table_len=tl,
+                                          label=f"table_len {tl}") == B.ST_BAD_EXTENT
+        H.check_layer_restore(orc, c, table_len=tl)
+        H.check_layer_save(orc, c, table_len=tl)
+
+
+CALLER_EXTENT_SHAPES = [
+    # T, h, d, e, N, n_blocks, align, layout
+    (16, 8, 128, 2, 256, [40, 0, 7, 25, 1], 4096, 0),   # 32 KiB blocks: whole slices, the unpack preloads its first item
+    (16, 8, 128, 2, 256, [40, 0, 7, 25, 1], 4096, 1),   # the same, head-major (16 bytes per lane between the orders)
+    (16, 5, 40, 2, 128, [7, 0, 33, 1, 2], 4096, 0),     # 6400-byte blocks: ragged slices, padded objects
+    (16, 32, 32, 1, 128, [9, 3, 0, 11], 4096, 1),       # head-major with 32-byte rows: token tiles through LDS
+    (3, 1, 8, 2, 64, [1, 2, 3, 4, 5], 64, 0),           # 48-byte blocks
+]
+
+
+@pytest.mark.parametrize("budget", [0, 3])
+@pytest.mark.parametrize("shape", CALLER_EXTENT_SHAPES, ids=[f"bb{t*h*d*e}_l{lay}" for t, h, d, e, _, _, _, lay in
+                                                             CALLER_EXTENT_SHAPES])
+def test_extents_written_by_the_caller(orc, H, shape, budget):
+    """Pack and unpack honour hand-made extents field by field: a gap between requests, a sub-range of the
+    requests, reversed order in the staging buffer, objects larger than their blocks; and they skip and report
+    what cannot be honoured exactly as the oracle does."""
+    T, h, d, e, N, n_blocks, A, layout = shape
+    say("caller extents", shape, budget)
+    rng = np.random.default_rng(77 + T * h + layout)
+    total = sum(n_blocks)
+    table = rng.permutation(N)[:total]
+    c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=n_blocks, table=table, align=A, chunk=A, layout=layout,
+                    seed=3 + T, name=f"caller_extents{shape}")
+    o_ext, o_tot = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    base = np.zeros(len(n_blocks), B.EXTENT_DTYPE)
+    for f in B.EXTENT_DTYPE.names:
+        base[f] = o_ext[f]
+    total_bytes = int(o_tot[0])
+    R = len(n_blocks)
+
+    def run(x, size, label, **kw):
+        return H.check_moves_with_extents(orc, c, x, size, cu_budget=budget, label=label, **kw)
+
+    assert run(base, total_bytes, "layout's own") == 0
+    # a 2 MiB gap in front of every request
+    gap = 2 << 20
+    x = base.copy()
+    x["stage_off"] += gap * (1 + np.arange(R, dtype=np.uint64))
+    assert run(x, total_bytes + gap * R, "2 MiB gaps") == 0
+    # requests 1.. passed alone with the whole table; then the last two alone
+    assert run(base[1:], total_bytes, "requests 1..") == 0
+    assert run(base[-2:], total_bytes, "last two requests") == 0
+    # the requests in reverse order in the staging buffer
+    x = base.copy()
+    end = 0
+    for r in range(R - 1, -1, -1):
+        x["stage_off"][r] = end
+        end += 2 * int(x["obj_bytes"][r])
+    assert run(x, total_bytes, "reverse order") == 0
+    # objects one alignment unit larger than layout makes them: more padding, V further away
+    x = base.copy()
+    x["obj_bytes"] += A
+    x["stage_off"] = np.concatenate([[0], np.cumsum(2 * x["obj_bytes"].astype(np.uint64))[:-1]])
+    assert run(x, total_bytes + 2 * A * R, "larger objects") == 0
+    # requests in another order than their table ranges
+    x = base[::-1].copy()
+    assert run(x, total_bytes, "records reversed") == 0
+    # ---- what cannot be honoured
+    assert run(base, total_bytes, "table one short", table_len=total - 1) == B.ST_BAD_EXTENT
+    assert run(base, total_bytes, "empty table", table_len=0) == B.ST_BAD_EXTENT
+    x = base.copy()
+    x["stage_off"][0] += 8
+    st = run(x, total_bytes + 16, "misaligned offset")
+    assert st & B.ST_BAD_EXTENT
+    x = base.copy()
+    x["obj_bytes"][0] = 1 << 63
+    assert run(x, total_bytes, "object size wraps") & B.ST_STAGE_CAP
+    x = base.copy()
+    x["stage_off"][R - 1] = (1 << 64) - 4096
+    assert run(x, total_bytes, "offset wraps") & B.ST_STAGE_CAP
+    big = int(np.argmax(n_blocks))
+    x = base.copy()
+    x["obj_bytes"][big] -= A          # too small for its last block (and the V object moves up)
+    assert run(x, total_bytes, "object too small") & B.ST_BAD_EXTENT
+    x = base.copy()
+    x["table_off"][R - 1] = total - 1  # runs off the end of the table
+    if n_blocks[R - 1] > 1:
+        assert run(x, total_bytes, "table range beyond the table") & B.ST_BAD_BLOCK
+    x = base.copy()
+    x["n_blocks"][0] += 1              # claims one block more than the table holds in all
+    assert run(x, total_bytes + c.bb, "one block too many") & B.ST_BAD_EXTENT
+    assert run(base, total_bytes, "capacity one byte short", stage_cap=total_bytes - 1) == B.ST_STAGE_CAP
+
+
+def test_entry_builders_want_layout_extents(orc, H):
+    """tutti_sqe_build, tutti_sqe_build_direct and tutti_iocb_fill_direct write nothing and report BAD_EXTENT when
+    the extents are not the ones tutti_obj_layout writes for these requests; stage_off alone is free."""
+    say("entry builders: extents contract")
+    rng = np.random.default_rng(5)
+    n = [3, 2, 4, 0, 70]
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=128, n_blocks=n, table=rng.permutation(128)[: sum(n)], chunk=8192, L=3,
+                    name="dense_extents")
+    ext, tot, o_ext, o_tot = H.check_layout(orc, c)
+    base = H.ext_np(ext, c.n_req).copy()
+    n_sqe, n_ctx = int(o_tot[1]), 2 * sum(n)
+    variants = []
+    for field, delta in (("sqe_base", 2), ("table_off", 1), ("obj_bytes", 4096), ("n_chunks", 1), ("n_blocks", 1)):
+        for r in (0, 2, 4):
+            x = base.copy()
+            x[field][r] += delta
+            variants.append((f"{field}[{r}]", x, c.file_id))
+    variants.append(("requests 1.. alone", base[1:].copy(), c.file_id[1:]))
+    x = base.copy()
+    x["stage_off"] += 1 << 21
+    variants.append(("stage_off moved (allowed)", x, c.file_id))
+    for label, x, fid in variants:
+        o_x = np.zeros(x.size, orc.EXTENT_DTYPE)
+        for f in B.EXTENT_DTYPE.names:
+            o_x[f] = x[f]
+        d_x = torch.from_numpy(x.view(np.uint8).copy()).to(H.DEV)
+        d_fid = H.to_dev(fid)
+        sqe = torch.full((n_sqe * 64,), 0x3C, dtype=torch.uint8, device=H.DEV)
+        st = H.new_status()
+        B.tutti_sqe_build(c.gpu_pool(), c.gpu_cfg(), d_x, x.size, d_fid, 1, B.OP_READ, 1 << 30, 9, sqe, n_sqe, st)
+        dsqe = torch.full((n_ctx * 64,), 0x3C, dtype=torch.uint8, device=H.DEV)
+        st2 = H.new_status()
+        B.tutti_sqe_build_direct(c.gpu_pool(), c.gpu_cfg(), d_x, x.size, c.d_table, c.table.size, d_fid, 1, B.OP_WRITE,
+                                 1 << 20, 9, dsqe, n_ctx, st2)
+        sq_b, cq_b = B.ring_bytes(2)
+        d_sq = torch.zeros(sq_b, dtype=torch.uint8, device=H.DEV)
+        d_cq = torch.zeros(cq_b, dtype=torch.uint8, device=H.DEV)
+        ring = B.make_ring(d_sq, d_cq, 2)
+        B.tutti_ring_init(ring)
+        st3 = H.new_status()
+        B.tutti_iocb_fill_direct(ring, 1, 1, c.gpu_pool(), c.gpu_cfg(), d_x, x.size, c.d_table, c.table.size, d_fid, 1,
+                                 B.OP_WRITE, 1 << 20, 9, st3)
+        torch.cuda.synchronize()
+        o_sqe, o_st = orc.sqe_build(c.orc_pool(orc), c.orc_cfg(orc), o_x, fid, 1, orc.OP_READ, 1 << 30, 9, sqe_cap=n_sqe)
+        o_d, o_st2 = orc.sqe_build_direct(c.orc_pool(orc), c.orc_cfg(orc), o_x, c.table, fid, 1, orc.OP_WRITE, 1 << 20,
+                                          9, sqe_cap=n_ctx)
+        o_sq, o_cq = orc.ring_alloc(2)
+        orc.ring_init(o_sq, o_cq)
+        o_st3 = orc.iocb_fill_direct(o_sq, 1, 1, c.orc_pool(orc), c.orc_cfg(orc), o_x, c.table, fid, 1, orc.OP_WRITE,
+                                     1 << 20, 9)
+        assert (int(st.item()), int(st2.item()), int(st3.item())) == (o_st, o_st2, o_st3), label
+        got, gotd = sqe.cpu().numpy(), dsqe.cpu().numpy()
+        if o_st:
+            assert o_st == B.ST_BAD_EXTENT and np.all(got == 0x3C) and np.all(gotd == 0x3C), label
+        else:
+            assert got.tobytes() == o_sqe.tobytes() and gotd.tobytes() == o_d.tobytes(), label
+        # IOCB headers and the contexts that were filled (the rest of an IOCB is never written by either side)
+        g_sq = d_sq.cpu().numpy().view(B.IOCB_DTYPE)
+        for b in range(2):
+            assert g_sq["hdr"][b].tobytes()[:24] == o_sq["hdr"][b].tobytes()[:24], label
+            k = int(o_sq["hdr"]["num_ioctx"][b])
+            assert g_sq["ioctx"][b][:k].tobytes() == o_sq["ioctx"][b][:k].tobytes(), label
 
 
 def test_cu_budget_out_of_range(H):
