@@ -276,16 +276,16 @@ int orc_obj_unpack(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent
  */
 static int extents_are_dense(const orc_pool *pool, const orc_objcfg *cfg, const orc_extent *extents, uint32_t n_req) {
   const uint64_t bb = orc_block_bytes(pool);
-  uint64_t n_sqe = 0, n_tab = 0;
+  uint64_t want_sqe = 0, want_tab = 0; /* what orc_obj_layout would have written */
   for (uint32_t r = 0; r < n_req; ++r) {
     const orc_extent *x = &extents[r];
     uint64_t obj = align_up((uint64_t)x->n_blocks * bb, cfg->align);
     uint64_t chunks = (obj + cfg->chunk_bytes - 1) / cfg->chunk_bytes;
     if (x->obj_bytes != obj || x->n_chunks != chunks) return 0;
-    if (x->sqe_base != n_sqe || x->table_off != n_tab) return 0;
-    n_sqe += 2 * chunks;
-    n_tab += x->n_blocks;
-    if (n_sqe > 0xffffffffull || n_tab > 0xffffffffull) return 0;
+    if (x->sqe_base != want_sqe || x->table_off != want_tab) return 0;
+    want_sqe += chunks + chunks;
+    want_tab += x->n_blocks;
+    if (want_sqe > 0xffffffffull || want_tab > 0xffffffffull) return 0;
   }
   return 1;
 }
@@ -527,12 +527,20 @@ int orc_iocb_fill_direct(orc_iocb *sq, uint32_t depth, uint32_t first_slot, uint
 /*
  * issue_io (sec. 3.2): every context becomes one transfer between the block its SGL descriptor describes and
  * the GPU file at its offset; when an IOCB's contexts are done its index goes to the CQ.
+ * The paper does not say what happens to a context that cannot be executed (the application may have filled
+ * it by hand).  Reading taken: such a context is skipped and ORC_ST_BAD_BLOCK reported, and the IOCB still
+ * completes.  A context cannot be executed when: its opcode is neither READ nor WRITE; its SGL address is not
+ * that of a descriptor of the table (below it, not a multiple of 16 from it, index >= n_desc); its length is
+ * not a multiple of 16, exceeds max_len or the descriptor's length; the block address or the file offset is
+ * not a multiple of 16; the file id is outside the store; or [file_off, file_off + len) is not inside the file.
+ * Length 0 is a no-op, not an error.
  */
 int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
                  const orc_sgl *sgl_table, uint32_t n_desc, uint64_t sgl_table_addr, const orc_filestore *store,
-                 uint32_t *status) {
+                 uint32_t max_len, uint32_t *status) {
   if (!sq || !cq || depth == 0 || n_slots > depth || first_slot >= depth) return ORC_EINVAL;
   if (!store || !store->base || (n_desc > 0 && !sgl_table)) return ORC_EINVAL;
+  if (max_len == 0 || max_len % 16 != 0 || sgl_table_addr % 16 != 0) return ORC_EINVAL;
   orc_cq_hdr *c = (orc_cq_hdr *)cq;
   uint32_t *entry = (uint32_t *)(c + 1);
   uint32_t st = 0;
@@ -542,6 +550,10 @@ int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, ui
     for (uint32_t k = 0; k < io->hdr.num_ioctx && k < ORC_IOCB_SLOTS; ++k) {
       const orc_sqe *s = &io->ioctx[k];
       if (s->len == 0) continue; /* a no-op context */
+      if (s->opcode != ORC_OP_READ && s->opcode != ORC_OP_WRITE) {
+        st |= ORC_ST_BAD_BLOCK;
+        continue;
+      }
       if (s->addr < sgl_table_addr || (s->addr - sgl_table_addr) % 16 != 0) {
         st |= ORC_ST_BAD_BLOCK;
         continue;
@@ -551,8 +563,12 @@ int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, ui
         st |= ORC_ST_BAD_BLOCK;
         continue;
       }
+      if (s->len > max_len || s->len % 16 != 0 || s->file_off % 16 != 0 || sgl_table[di].addr % 16 != 0) {
+        st |= ORC_ST_BAD_BLOCK;
+        continue;
+      }
       if (s->file_id < store->first_file_id || s->file_id - store->first_file_id >= store->n_files ||
-          s->file_off + s->len > store->file_stride) {
+          s->file_off > store->file_stride || s->len > store->file_stride - s->file_off) {
         st |= ORC_ST_BAD_BLOCK;
         continue;
       }
@@ -632,7 +648,9 @@ static int ring_layer(uint32_t opcode, orc_iocb *sq, void *cq, uint32_t depth, u
   if (!rc)
     rc = orc_iocb_fill_direct(sq, depth, first_slot, n_slots, pool, cfg, extents, n_req, block_table, file_id, layer,
                               opcode, sgl_table_addr, sgl_id, status);
-  if (!rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc, sgl_table_addr, store, status);
+  if (!rc)
+    rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc, sgl_table_addr, store, orc_block_bytes(pool),
+                      status);
   free(table);
   return rc;
 }

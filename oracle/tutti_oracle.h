@@ -233,11 +233,13 @@ int orc_iocb_fill_direct(orc_iocb *sq, uint32_t depth, uint32_t first_slot, uint
  * descriptor the context names (index (addr - sgl_table_addr)/16 into sgl_table, n_desc entries), then move
  * len bytes between that block and the request's GPU file at file_off (READ: file -> block, WRITE: block ->
  * file).  The descriptor's address is used as a host pointer here.  Each IOCB is then marked DONE and its
- * index appended to the CQ.  Contexts naming a descriptor or file outside the given ranges, or longer than
- * the descriptor, are skipped (ORC_ST_BAD_BLOCK). */
+ * index appended to the CQ.  A context that cannot be executed is skipped (ORC_ST_BAD_BLOCK): opcode neither
+ * READ nor WRITE; address not that of a descriptor of the table; length not a multiple of 16 or beyond max_len
+ * or the descriptor's length; block address or file offset not a multiple of 16; file id outside the store;
+ * [file_off, file_off + len) not inside the file.  Length 0 is a no-op.  max_len: multiple of 16, > 0. */
 int orc_issue_io(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot, uint32_t n_slots,
                  const orc_sgl *sgl_table, uint32_t n_desc, uint64_t sgl_table_addr, const orc_filestore *store,
-                 uint32_t *status);
+                 uint32_t max_len, uint32_t *status);
 
 /* retrieve_layer(layer) / store_layer(layer) (sec. 3.4) through the rings in direct-to-block mode: extents of
  * the requests, the layer's contexts into n_slots IOCBs from first_slot, their execution against the file

@@ -264,13 +264,17 @@ def iocb_fill_direct(sq, first_slot, n_slots, pool, cfg, extents, block_table, f
     return status.value
 
 
-def issue_io(sq, cq, first_slot, n_slots, sgl_table, sgl_table_addr, store, file_stride, first_file_id, n_files):
-    """`store`: uint8 host array of n_files * file_stride bytes.  Returns the status word."""
+def issue_io(sq, cq, first_slot, n_slots, sgl_table, sgl_table_addr, store, file_stride, first_file_id, n_files,
+             max_len=None):
+    """`store`: uint8 host array of n_files * file_stride bytes.  max_len: longest context allowed (default: the
+    longest descriptor of the table).  Returns the status word."""
     fs = OrcFileStore(store.ctypes.data, file_stride, first_file_id, n_files)
     status = C.c_uint32(0)
+    if max_len is None:
+        max_len = int(sgl_table["len"].max()) if sgl_table.size else 16
     rc = lib().orc_issue_io(_ptr(sq), _ptr(cq), C.c_uint32(sq.size), C.c_uint32(first_slot), C.c_uint32(n_slots),
                             _ptr(sgl_table), C.c_uint32(sgl_table.size), C.c_uint64(sgl_table_addr), C.byref(fs),
-                            C.byref(status))
+                            C.c_uint32(max_len), C.byref(status))
     if rc:
         raise OracleError("orc_issue_io", rc)
     return status.value

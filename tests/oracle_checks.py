@@ -723,6 +723,81 @@ def check_issue_io(orc, seed=37):
     assert orc.issue_io(sq, cq, 2, 2, sgl, base, store, file_stride, 70, 4) == 0 and int(cq[0]) == 2  # FREE slots: no-op
 
 
+def check_issue_io_hand_filled(orc, seed=59):
+    """The paper's own flow (sec. 3.2 "Async I/O Processing"): the application fills the contexts and num_ioctx
+    itself.  Contexts written here with numpy, one per rule; expected bytes are numpy slices."""
+    rng = np.random.default_rng(seed)
+    N, bb = 12, 256
+    k = rng.integers(0, 256, N * bb, dtype=np.uint8)
+    k0 = k.copy()
+    sgl = np.zeros(N, orc.SGL_DTYPE)
+    sgl["addr"] = k.ctypes.data + bb * np.arange(N, dtype=np.uint64)
+    sgl["len"] = bb
+    sgl["len"][5] = 128                       # a short descriptor
+    sgl["addr"][6] += 8                       # a misaligned block address
+    sgl["len"][9] = 512                       # a descriptor longer than max_len below
+    sgl["id"] = 3
+    base = 0x4000_0000
+    file_stride, n_files, first_file = 4096, 2, 40
+    store = rng.integers(0, 256, n_files * file_stride, dtype=np.uint8)
+    store0 = store.copy()
+
+    def ctx(op, blk, fid, off, ln, addr=None):
+        c = np.zeros((), orc.SQE_DTYPE)
+        c["opcode"], c["file_id"], c["file_off"], c["len"] = op, fid, off, ln
+        c["addr"] = base + 16 * blk if addr is None else addr
+        return c
+
+    good = [ctx(orc.OP_READ, 0, 40, 0, 256), ctx(orc.OP_READ, 1, 41, 4096 - 256, 256), ctx(orc.OP_WRITE, 2, 40, 512, 128),
+            ctx(orc.OP_READ, 3, 41, 16, 16), ctx(orc.OP_READ, 5, 40, 1024, 128), ctx(orc.OP_READ, 4, 40, 2048, 0)]
+    bad = [ctx(0, 7, 40, 0, 256), ctx(3, 7, 40, 0, 256),                  # opcode
+           ctx(orc.OP_READ, 7, 40, 0, 256, addr=base - 16),              # below the table
+           ctx(orc.OP_READ, 7, 40, 0, 256, addr=base + 16 * 7 + 8),      # between two descriptors
+           ctx(orc.OP_READ, N, 40, 0, 256),                              # beyond the table
+           ctx(orc.OP_READ, 5, 40, 0, 144),                              # longer than its descriptor
+           ctx(orc.OP_READ, 9, 40, 0, 272),                              # within its descriptor, beyond max_len
+           ctx(orc.OP_READ, 7, 40, 0, 24),                               # length not a multiple of 16
+           ctx(orc.OP_READ, 7, 40, 8, 256),                              # file offset not a multiple of 16
+           ctx(orc.OP_READ, 6, 40, 0, 256),                              # block address not a multiple of 16
+           ctx(orc.OP_READ, 7, 39, 0, 256), ctx(orc.OP_READ, 7, 42, 0, 256),   # file outside the store
+           ctx(orc.OP_READ, 7, 40, 4096 - 240, 256),                     # runs off the end of the file
+           ctx(orc.OP_READ, 7, 40, (1 << 64) - 16, 256)]                 # offset + length wraps around
+    depth = 3
+    sq, cq = orc.ring_alloc(depth)
+    orc.ring_init(sq, cq)
+    # application side: IOCB 2 takes the good contexts and IOCB 0 the bad ones (wrap-around), num_ioctx updated
+    for slot, items in ((2, good), (0, bad)):
+        for i, c in enumerate(items):
+            sq["ioctx"][slot][i] = c
+        sq["hdr"]["num_ioctx"][slot] = len(items)
+        sq["hdr"]["state"][slot] = orc.IOCB_FILLED
+    sq["ioctx"][2][len(good)] = ctx(orc.OP_READ, 8, 40, 0, 256)   # beyond num_ioctx: must not run
+    st = orc.issue_io(sq, cq, 2, 2, sgl[:N], base, store, file_stride, first_file, n_files, max_len=256)
+    assert st == orc.ST_BAD_BLOCK
+    want_k, want_store = k0.copy(), store0.copy()
+    want_k[0:256] = store0[0:256]
+    want_k[256:512] = store0[file_stride + 4096 - 256: file_stride + 4096]
+    want_store[512:640] = k0[2 * bb: 2 * bb + 128]
+    want_k[3 * bb: 3 * bb + 16] = store0[file_stride + 16: file_stride + 32]
+    want_k[5 * bb: 5 * bb + 128] = store0[1024:1152]
+    assert np.array_equal(k, want_k) and np.array_equal(store, want_store)
+    assert int(cq[0]) == 2 and list(cq[16:18]) == [2, 0]
+    assert list(sq["hdr"]["state"]) == [orc.IOCB_DONE, orc.IOCB_FREE, orc.IOCB_DONE]
+    assert int(sq["hdr"]["done"][0]) == len(bad) and int(sq["hdr"]["done"][2]) == len(good)
+    # each bad context alone trips the status word; each good one alone does not
+    for items, want in ((bad, orc.ST_BAD_BLOCK), (good, 0)):
+        for c in items:
+            orc.ring_init(sq, cq)
+            sq["ioctx"][1][0] = c
+            sq["hdr"]["num_ioctx"][1] = 1
+            sq["hdr"]["state"][1] = orc.IOCB_FILLED
+            kb, sb = k.copy(), store.copy()
+            st = orc.issue_io(sq, cq, 1, 1, sgl[:N], base, store, file_stride, first_file, n_files, max_len=256)
+            assert st == want, c
+            if want:
+                assert np.array_equal(k, kb) and np.array_equal(store, sb), c
+
+
 def check_ring_layer(orc, seed=41):
     """store_layer / retrieve_layer through the rings: the file regions hold what obj_pack stages for the same
     requests (either mode reads what the other wrote), a retrieve into a wiped pool brings the named blocks
@@ -1007,6 +1082,6 @@ def check_table_validate(orc, seed=43):
 
 ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout_scan, check_pack_bruteforce,
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
-              check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io,
+              check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io, check_issue_io_hand_filled,
               check_ring_layer, check_table_validate, check_caller_extents,
               check_entry_builders_want_layout_extents]

@@ -290,7 +290,7 @@ static void one_case(void) {
     /* three steps on A, one call on B */
     CHECK(orc_iocb_fill_direct(sq_a, depth, first, n_slots, &pool, &cfg, ext, n_req, table, fid, layer, ORC_OP_WRITE, base,
                                3, &st_a) == ORC_OK);
-    CHECK(orc_issue_io(sq_a, cq_a, depth, first, n_slots, sgl, 2 * N, base, &fa, &st_a) == ORC_OK);
+    CHECK(orc_issue_io(sq_a, cq_a, depth, first, n_slots, sgl, 2 * N, base, &fa, bb, &st_a) == ORC_OK);
     orc_extent *ext_b = xmalloc(sizeof(orc_extent) * n_req);
     uint64_t tot_b[2];
     CHECK(orc_store_layer(sq_b, cq_b, depth, first, n_slots, &pool, &cfg, nb, n_req, table, fid, layer, base, 3, &fb, ext_b,

@@ -68,8 +68,8 @@ MUTANTS = {
     "dense_check_skipped_direct": ("if (!extents_are_dense(pool, cfg, extents, n_req)) {", "if (0) {", 1),
     "dense_check_skipped_fill": ("if (!extents_are_dense(pool, cfg, extents, n_req)) {", "if (0) {", 2),
     "dense_ignores_sizes": ("if (x->obj_bytes != obj || x->n_chunks != chunks) return 0;", ""),
-    "dense_ignores_offsets": ("if (x->sqe_base != n_sqe || x->table_off != n_tab) return 0;", ""),
-    "dense_ignores_wrap": ("if (n_sqe > 0xffffffffull || n_tab > 0xffffffffull) return 0;", ""),
+    "dense_ignores_offsets": ("if (x->sqe_base != want_sqe || x->table_off != want_tab) return 0;", ""),
+    "dense_ignores_wrap": ("if (want_sqe > 0xffffffffull || want_tab > 0xffffffffull) return 0;", ""),
     "table_off_ignored": ("uint64_t g = (uint64_t)x->table_off + j;", "uint64_t g = used - x->n_blocks + j;"),
     "sgl_v_plane_uses_k_address": ("table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;",
                                    "table[i].addr = k_addr + (uint64_t)b * pool->block_stride;"),
@@ -103,7 +103,21 @@ MUTANTS = {
     "io_descriptor_index": ("uint64_t di = (s->addr - sgl_table_addr) / 16;", "uint64_t di = (s->addr - sgl_table_addr) / 32;"),
     "io_cq_index": ("entry[c->tail % depth] = io->hdr.iocb_idx;", "entry[c->tail % depth] = b;"),
     "io_not_marked_done": ("io->hdr.state = ORC_IOCB_DONE;", "io->hdr.state = ORC_IOCB_FILLED;"),
-    "io_file_bound": ("s->file_off + s->len > store->file_stride) {", "s->file_off > store->file_stride) {"),
+    "io_file_bound": ("s->file_off > store->file_stride || s->len > store->file_stride - s->file_off) {",
+                      "s->file_off > store->file_stride) {"),
+    "io_file_bound_wraps": ("s->file_off > store->file_stride || s->len > store->file_stride - s->file_off) {",
+                            "s->file_off + s->len > store->file_stride) {"),
+    "io_opcode_unchecked": ("if (s->opcode != ORC_OP_READ && s->opcode != ORC_OP_WRITE) {", "if (0) {"),
+    "io_max_len_unchecked": ("if (s->len > max_len || s->len % 16 != 0", "if (s->len % 16 != 0"),
+    "io_len_alignment_unchecked": ("s->len % 16 != 0 || s->file_off % 16 != 0 ||", "s->file_off % 16 != 0 ||"),
+    "io_offset_alignment_unchecked": ("s->len % 16 != 0 || s->file_off % 16 != 0 ||", "s->len % 16 != 0 ||"),
+    "io_block_alignment_unchecked": (" || sgl_table[di].addr % 16 != 0) {", ") {"),
+    "io_descriptor_length_unchecked": ("if (di >= n_desc || s->len > sgl_table[di].len) {", "if (di >= n_desc) {"),
+    "io_address_between_descriptors": ("if (s->addr < sgl_table_addr || (s->addr - sgl_table_addr) % 16 != 0) {",
+                                       "if (s->addr < sgl_table_addr) {"),
+    "io_runs_beyond_num_ioctx": ("k < io->hdr.num_ioctx && k < ORC_IOCB_SLOTS; ++k) {", "k < ORC_IOCB_SLOTS; ++k) {"),
+    "io_zero_length_is_error": ("if (s->len == 0) continue; /* a no-op context */",
+                                "if (s->len == 0) { st |= ORC_ST_BAD_BLOCK; continue; }"),
     "save_builds_read": ("ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);",
                          "ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);"),
     "save_unpacks": ("  return orc_obj_pack(pool, cfg, extents, n_req, block_table, table_len, stage, stage_cap, status);\n}\n\n/* retrieve_layer",
@@ -113,8 +127,8 @@ MUTANTS = {
     "retrieve_layer_writes": ("return ring_layer(ORC_OP_READ, sq,", "return ring_layer(ORC_OP_WRITE, sq,"),
     "store_layer_reads": ("return ring_layer(ORC_OP_WRITE, sq,", "return ring_layer(ORC_OP_READ, sq,"),
     "ring_layer_half_table": ("const uint32_t n_desc = 2u * pool->num_blocks;", "const uint32_t n_desc = 1u * pool->num_blocks;"),
-    "ring_layer_skips_issue": ("if (!rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,",
-                               "if (rc) rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,"),
+    "ring_layer_skips_issue": ("  if (!rc)\n    rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,",
+                               "  if (rc)\n    rc = orc_issue_io(sq, cq, depth, first_slot, n_slots, table, n_desc,"),
     "validate_first_seen_counts": ("    } else if (seen[id]) {\n      st |= ORC_ST_DUP_BLOCK;\n    } else {\n      seen[id] = 1;",
                                    "    } else if (seen[id]++) {\n      st |= ORC_ST_DUP_BLOCK;\n    } else {\n      seen[id] = 0;"),
     "validate_bound_off_by_one": ("    if (id >= num_blocks) {\n      st |= ORC_ST_BAD_BLOCK;", "    if (id > num_blocks) {\n      st |= ORC_ST_BAD_BLOCK;"),
