@@ -36,6 +36,7 @@ extern "C" {
 #define TUTTI_EINVAL (-1) /* null pointer, zero dimension, bad alignment / layout / opcode / layer */
 #define TUTTI_ERANGE (-2) /* n_req > TUTTI_MAX_REQ, cu_budget > number of CUs */
 #define TUTTI_EHIP (-3)   /* a HIP call failed; see tutti_last_hip_error() */
+#define TUTTI_EAGAIN (-4) /* host-side ring calls: not enough free IOCBs now / no budget fits the slack window */
 
 #define TUTTI_LAYOUT_NHD 0u /* block stored [T][h][d]: the paper's [Block, h, d] (sec. 2.1) */
 #define TUTTI_LAYOUT_HND 1u /* block stored [h][T][d]: head-major engines; objects stay token-major */
@@ -281,9 +282,14 @@ int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t
  * I/O kernel then marks every executed IOCB DONE (done = num_ioctx) and appends its index to the CQ, in slot
  * order: the kernel boundary is the "all contexts finished" event (counting finished contexts with atomics on
  * the IOCB header was measured 28x slower).  max_len bounds the length of any context (the pool's block size).
- * Contexts naming a descriptor or file out of range, longer than their descriptor or max_len, or not 16-byte
- * aligned are skipped (TUTTI_ST_BAD_BLOCK).  cu_budget as in tutti_layer_restore.  Two tutti_issue_io calls on
- * the same ring must be ordered by the stream (they share the CQ tail). */
+ * The IOCBs may have been filled by the GPU (tutti_iocb_fill_direct) or by the application itself, as in the
+ * paper's flow (sec. 3.2 "Async I/O Processing", step 2): an SQ in pinned host memory, contexts, num_ioctx,
+ * layer, opcode and state = TUTTI_IOCB_FILLED written by the CPU; so a context may hold anything.  One that
+ * cannot be executed is skipped (TUTTI_ST_BAD_BLOCK) and its IOCB still completes: opcode neither READ nor
+ * WRITE; address not that of a descriptor of the table; length not a multiple of 16, or beyond max_len or the
+ * descriptor's length; block address or file offset not a multiple of 16; file id outside the store;
+ * [file_off, file_off + len) not inside the file.  Length 0 is a no-op.  cu_budget as in tutti_layer_restore.
+ * Two tutti_issue_io calls on the same ring must be ordered by the stream (they share the CQ tail). */
 int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_sgl *d_sgl_table,
                    uint32_t n_desc, uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len,
                    uint32_t cu_budget, uint32_t *d_status, void *stream);
@@ -312,6 +318,62 @@ int tutti_store_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_sl
 /* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);
+
+/* ---- the application's side of the rings: get_iocb and the reaping of completions (sec. 3.2 "Async I/O
+ * Processing", steps 2 and 4).  Host code only: no HIP call, no device access, O(1) per IOCB.  The state lives in
+ * host memory the caller owns (one per ring, used from one thread at a time).  IOCBs are handed out in ring order,
+ * so a run of n is always the n consecutive slots (modulo depth) that the fill / issue calls take as
+ * (first_slot, n_slots); a slot is handed out again only after its completion has been reaped AND every older
+ * slot has been given back (completions may arrive in any order, e.g. deferred writes behind later reads). */
+typedef struct tutti_sq_state {
+  uint32_t depth;
+  uint32_t head;    /* the next slot to hand out */
+  uint32_t held;    /* slots handed out and not yet given back: the `held` slots in front of head */
+  uint32_t cq_seen; /* completions consumed from the CQ so far (modulo 2^32, as the CQ tail) */
+  uint8_t *done;    /* depth flags (caller's memory): completed, waiting for an older slot to be given back */
+} tutti_sq_state;
+
+/* flags: depth bytes of host memory that stay valid as long as the state is used. */
+int tutti_sq_state_init(tutti_sq_state *s, uint32_t depth, uint8_t *flags);
+/* get_iocb(n): *first_slot <- the first of n consecutive free slots.  TUTTI_EAGAIN if fewer than n are free
+ * (nothing changes), TUTTI_EINVAL for n = 0 or n > depth. */
+int tutti_get_iocb(tutti_sq_state *s, uint32_t n, uint32_t *first_slot);
+uint32_t tutti_sq_free_count(const tutti_sq_state *s);
+/* Consumes the completions the CQ has gained since the last call.  cq_host: a host-readable view of the ring's
+ * CQ (the CQ itself when it lives in pinned host memory: no synchronisation is needed, the tail is read with
+ * acquire order; otherwise a host copy taken after synchronising).  sq_host: the SQ when it lives in
+ * host-accessible memory, else NULL; each reaped IOCB's state becomes TUTTI_IOCB_FREE there.  *n_new (may be
+ * NULL) <- completions consumed.  TUTTI_EINVAL, with nothing consumed, if the queue names a slot that is not
+ * held, names one twice, or holds more completions than slots are held. */
+int tutti_reap_cqe(tutti_sq_state *s, const void *cq_host, tutti_iocb *sq_host, uint32_t *n_new);
+/* 1 if the IOCB last handed out in `slot` has completed (as far as the reaping has seen), else 0. */
+int tutti_iocb_completed(const tutti_sq_state *s, uint32_t slot);
+/* wait_cqe() from the host: reaps until `slot` has completed or max_polls further polls have not shown it.
+ * Returns 1 (completed), 0 (not yet) or a negative TUTTI_E*.  A bounded wait: it never spins for ever. */
+int tutti_wait_cqe_host(tutti_sq_state *s, const void *cq_host, tutti_iocb *sq_host, uint32_t slot,
+                        uint32_t max_polls);
+
+/* ---- slack table (sec. 3.3 "Offline Profiling of SM Slack Windows": besides the slack windows of the model,
+ * the execution time of the read / write kernels under different IOCB counts and compute-unit budgets is
+ * profiled offline, and the runtime picks a launch size by table lookup).  A row is one profiled launch; the
+ * table is whatever the profiling run measured (bench.py writes one), in any order.  Pure lookups, no
+ * interpolation: a launch is taken to cost what the next larger profiled launch at the same budget cost. */
+typedef struct tutti_io_profile {
+  uint32_t cu_budget; /* compute units given to the I/O kernel; 0 = whole GPU */
+  uint32_t n_iocbs;   /* IOCBs (2048 contexts each) in the launch */
+  float read_us;      /* measured duration of a retrieve of that size; <= 0 = not measured */
+  float write_us;     /* the same for a store */
+} tutti_io_profile;
+
+/* How many IOCBs may be launched into a slack window of slack_us microseconds that leaves cu_budget compute
+ * units free: the largest profiled count at that budget whose duration fits; *n_iocbs <- 0 if none does. */
+int tutti_iocbs_for_slack(const tutti_io_profile *rows, uint32_t n_rows, uint32_t cu_budget, uint32_t opcode,
+                          double slack_us, uint32_t *n_iocbs);
+/* The smallest budget in [1, max_budget] at which n_iocbs IOCBs fit a window of slack_us microseconds.
+ * TUTTI_EAGAIN (*cu_budget <- 0) if none does: the caller then defers a write, or launches a read on the whole
+ * GPU at once because retrieval has become the bottleneck (sec. 3.3 "Decoupled Scheduling for Read and Write"). */
+int tutti_budget_for_slack(const tutti_io_profile *rows, uint32_t n_rows, uint32_t n_iocbs, uint32_t opcode,
+                           double slack_us, uint32_t max_budget, uint32_t *cu_budget);
 
 /* ---- debugging aid: the preconditions that an unpack (tutti_obj_unpack, tutti_layer_restore, a READ through the
  * rings) places on its flattened block table, checked on the device: every id < num_blocks (else

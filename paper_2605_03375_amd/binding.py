@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtutti.so")
 _LIB = None
 
-OK, EINVAL, ERANGE, EHIP = 0, -1, -2, -3
+OK, EINVAL, ERANGE, EHIP, EAGAIN = 0, -1, -2, -3, -4
 LAYOUT_NHD, LAYOUT_HND = 0, 1
 OP_READ, OP_WRITE = 1, 2
 STREAM_SLOTS = 4096
@@ -40,7 +40,9 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
            "tutti_issue_io", "tutti_wait_cqe", "tutti_retrieve_layer", "tutti_store_layer",
            "tutti_table_validate", "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_resident_wgs_per_cu", "tutti_version",
-           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]
+           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping",
+           "tutti_sq_state_init", "tutti_get_iocb", "tutti_sq_free_count", "tutti_reap_cqe", "tutti_iocb_completed",
+           "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack"]
 
 
 class tutti_pool(C.Structure):
@@ -60,6 +62,15 @@ class tutti_ring(C.Structure):
 class tutti_filestore(C.Structure):
     _fields_ = [("base", C.c_void_p), ("file_stride", C.c_uint64), ("first_file_id", C.c_uint32),
                 ("n_files", C.c_uint32)]
+
+
+class tutti_sq_state(C.Structure):
+    _fields_ = [("depth", C.c_uint32), ("head", C.c_uint32), ("held", C.c_uint32), ("cq_seen", C.c_uint32),
+                ("done", C.c_void_p)]
+
+
+class tutti_io_profile(C.Structure):
+    _fields_ = [("cu_budget", C.c_uint32), ("n_iocbs", C.c_uint32), ("read_us", C.c_float), ("write_us", C.c_float)]
 
 
 IOCB_FREE, IOCB_FILLED, IOCB_DONE = 0, 1, 2
@@ -144,6 +155,19 @@ def lib():
         L.tutti_resident_wgs_per_cu.restype = C.c_int
         L.tutti_set_xcd_mapping.argtypes = [u32]
         L.tutti_set_xcd_mapping.restype = C.c_int
+        ps, pio = C.POINTER(tutti_sq_state), C.POINTER(tutti_io_profile)
+        L.tutti_sq_state_init.argtypes = [ps, u32, vp]
+        L.tutti_get_iocb.argtypes = [ps, u32, C.POINTER(u32)]
+        L.tutti_sq_free_count.argtypes = [ps]
+        L.tutti_sq_free_count.restype = u32
+        L.tutti_reap_cqe.argtypes = [ps, vp, vp, C.POINTER(u32)]
+        L.tutti_iocb_completed.argtypes = [ps, u32]
+        L.tutti_wait_cqe_host.argtypes = [ps, vp, vp, u32, u32]
+        L.tutti_iocbs_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, C.POINTER(u32)]
+        L.tutti_budget_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, u32, C.POINTER(u32)]
+        for name in ("tutti_sq_state_init", "tutti_get_iocb", "tutti_reap_cqe", "tutti_iocb_completed",
+                     "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack"):
+            getattr(L, name).restype = C.c_int
         for name in ("tutti_ring_init", "tutti_iocb_fill_direct", "tutti_issue_io", "tutti_wait_cqe",
                      "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
                      "tutti_layer_restore", "tutti_copy_baseline", "tutti_last_hip_error", "tutti_cu_count",
@@ -366,3 +390,73 @@ def tutti_set_hnd_mode(mode=0):
 
 def tutti_set_xcd_mapping(contiguous=0):
     return _check("tutti_set_xcd_mapping", lib().tutti_set_xcd_mapping(1 if contiguous else 0))
+
+
+# ---- the application's side of the rings (host code only: none of these needs a GPU)
+
+def make_sq_state(depth):
+    """Host bookkeeping of one ring's SQ (tutti_sq_state_init).  The flag bytes live in a numpy array kept alive
+    by the returned structure."""
+    st = tutti_sq_state()
+    flags = np.zeros(max(depth, 1), np.uint8)
+    st._keep = flags
+    _check("tutti_sq_state_init", lib().tutti_sq_state_init(C.byref(st), depth, _p(flags)))
+    return st
+
+
+def tutti_get_iocb(state, n):
+    """First of n consecutive free slots; raises TuttiError(EAGAIN) when fewer than n are free."""
+    first = C.c_uint32(0)
+    _check("tutti_get_iocb", lib().tutti_get_iocb(C.byref(state), n, C.byref(first)))
+    return first.value
+
+
+def tutti_sq_free_count(state):
+    return lib().tutti_sq_free_count(C.byref(state))
+
+
+def tutti_reap_cqe(state, cq_host, sq_host=None):
+    """Consumes new completions from a host-readable CQ; returns how many."""
+    n = C.c_uint32(0)
+    _check("tutti_reap_cqe", lib().tutti_reap_cqe(C.byref(state), _p(cq_host), _p(sq_host), C.byref(n)))
+    return n.value
+
+
+def tutti_iocb_completed(state, slot):
+    rc = lib().tutti_iocb_completed(C.byref(state), slot)
+    if rc < 0:
+        raise TuttiError("tutti_iocb_completed", rc)
+    return bool(rc)
+
+
+def tutti_wait_cqe_host(state, cq_host, sq_host, slot, max_polls):
+    rc = lib().tutti_wait_cqe_host(C.byref(state), _p(cq_host), _p(sq_host), slot, max_polls)
+    if rc < 0:
+        raise TuttiError("tutti_wait_cqe_host", rc)
+    return bool(rc)
+
+
+def make_io_profile(rows):
+    """rows: iterable of (cu_budget, n_iocbs, read_us, write_us) -> ctypes array of tutti_io_profile."""
+    rows = list(rows)
+    arr = (tutti_io_profile * max(len(rows), 1))()
+    for i, (b, n, r, w) in enumerate(rows):
+        arr[i] = tutti_io_profile(int(b), int(n), float(r), float(w))
+    return arr, len(rows)
+
+
+def tutti_iocbs_for_slack(profile, n_rows, cu_budget, opcode, slack_us):
+    out = C.c_uint32(0)
+    _check("tutti_iocbs_for_slack", lib().tutti_iocbs_for_slack(profile, n_rows, cu_budget, opcode, slack_us,
+                                                               C.byref(out)))
+    return out.value
+
+
+def tutti_budget_for_slack(profile, n_rows, n_iocbs, opcode, slack_us, max_budget):
+    """Smallest budget that fits, or None when none does (EAGAIN)."""
+    out = C.c_uint32(0)
+    rc = lib().tutti_budget_for_slack(profile, n_rows, n_iocbs, opcode, slack_us, max_budget, C.byref(out))
+    if rc == EAGAIN:
+        return None
+    _check("tutti_budget_for_slack", rc)
+    return out.value

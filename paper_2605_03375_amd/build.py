@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtutti.so")
-SOURCES = [os.path.join(CSRC, "tutti_api.hip")]
+SOURCES = [os.path.join(CSRC, "tutti_api.hip"), os.path.join(CSRC, "tutti_host.cpp")]
 DEPS = SOURCES + [os.path.join(CSRC, "tutti_kernels.hip.h"), os.path.join(ROOT, "include", "tutti.h")]
 
 HIPCC_FLAGS = [

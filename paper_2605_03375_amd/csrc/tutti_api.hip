@@ -965,6 +965,8 @@ const char *tutti_strerror(int code) {
       return "out of range (too many requests, CU budget above the CU count, or table too long)";
     case TUTTI_EHIP:
       return "a HIP call failed (see tutti_last_hip_error)";
+    case TUTTI_EAGAIN:
+      return "not now (too few free IOCBs, or no compute-unit budget fits the slack window)";
     default:
       return "unknown tutti error code";
   }

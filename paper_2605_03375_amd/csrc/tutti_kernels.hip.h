@@ -709,8 +709,8 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_issue_io(cons
     const uint64_t addr = (static_cast<uint64_t>(rfl(q1.y)) << 32) | rfl(q1.x);
     const uint32_t len = rfl(q1.z);
     if (len == 0) continue;  // a no-op context
-    bool ok = addr >= a.sgl_table_addr && ((addr - a.sgl_table_addr) & 15u) == 0 && len <= a.max_len &&
-              (len & 15u) == 0 && (file_off & 15u) == 0;
+    bool ok = (opcode == TUTTI_OP_READ || opcode == TUTTI_OP_WRITE) && addr >= a.sgl_table_addr &&
+              ((addr - a.sgl_table_addr) & 15u) == 0 && len <= a.max_len && (len & 15u) == 0 && (file_off & 15u) == 0;
     const uint64_t di = ok ? (addr - a.sgl_table_addr) >> 4 : 0;
     ok = ok && di < a.n_desc;
     uint64_t blk_addr = 0;

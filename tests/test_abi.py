@@ -77,7 +77,7 @@ int main(void) { (void)p_restore; return 0; }
 
 
 def test_strerror():
-    for code in (B.OK, B.EINVAL, B.ERANGE, B.EHIP, -99):
+    for code in (B.OK, B.EINVAL, B.ERANGE, B.EHIP, B.EAGAIN, -99):
         assert isinstance(B.tutti_strerror(code), str) and B.tutti_strerror(code)
 
 
@@ -202,11 +202,11 @@ def test_tuning_arguments():
 
 
 def test_empty_calls_do_not_need_a_gpu():
-    """n_req = 0 (or an empty table) is a no-op for pack / unpack / entries: nothing is enqueued."""
+    """n_req = 0 is a no-op for pack / unpack / entries: nothing is enqueued."""
     p = B.make_pool(FAKE, FAKE, **GOOD)
     cfg = B.make_cfg()
     assert B.tutti_obj_pack(p, cfg, 0, 0, 0, 0, FAKE, 0, stream=0) == B.OK
-    assert B.tutti_obj_unpack(p, cfg, FAKE, 1, 0, 0, FAKE, 0, stream=0) == B.OK
+    assert B.tutti_obj_unpack(p, cfg, 0, 0, 0, 0, FAKE, 0, stream=0) == B.OK
     assert B.tutti_sqe_build(p, cfg, 0, 0, 0, 0, B.OP_READ, 0, 0, 0, 0, stream=0) == B.OK
     assert B.tutti_copy_baseline(FAKE, FAKE, 0, stream=0) == B.OK
 

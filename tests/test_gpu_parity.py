@@ -651,6 +651,112 @@ def test_rings_deferred_writes_flushed_in_pieces(orc, H):
     assert np.all(o_sq["hdr"]["state"] == orc.IOCB_DONE) and o_st == 0
 
 
+def test_iocbs_filled_by_the_cpu(orc, H):
+    """The paper's own flow (sec. 3.2 "Async I/O Processing"): SQ and CQ in pinned host memory, slots from
+    get_iocb, contexts and num_ioctx written by the CPU with numpy, issue_io executes them, the CPU reaps the
+    CQ without synchronising the stream.  The contexts include one that trips each validity rule; pool, file
+    store, status and queues are compared with the oracle given the same contexts."""
+    say("rings: IOCBs filled by the CPU")
+    rng = np.random.default_rng(61)
+    N, bb, depth = 64, 8192, 3
+    c = H.LayerCase(T=16, h=2, d=128, e=2, N=N, n_blocks=[1], table=[0], name="cpu_filled")
+    assert c.bb == bb
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    nd = 2 * N
+    sgl = torch.zeros(nd * 16, dtype=torch.uint8, device=H.DEV)
+    B.tutti_sgl_table_build(c.gpu_pool(k2, v2), k2.data_ptr(), v2.data_ptr(), 5, sgl, nd)
+    torch.cuda.synchronize()
+    o_sgl, _ = orc.sgl_table_build(c.orc_pool(orc, ok, ov), ok.ctypes.data, ov.ctypes.data, 5)
+    # two descriptors patched the same way on both sides: a short one and one whose block address is misaligned
+    g_sgl = sgl.cpu().numpy().view(B.SGL_DTYPE).copy()
+    for t in (g_sgl, o_sgl):
+        t["len"][7] = 4096
+        t["addr"][9] += 8
+    sgl.copy_(torch.from_numpy(g_sgl.view(np.uint8)))
+    base = sgl.data_ptr()
+    file_stride, n_files, first_file = 1 << 20, 2, 300
+    g = torch.Generator(device=H.DEV)
+    g.manual_seed(8)
+    store = torch.randint(0, 256, (n_files * file_stride,), dtype=torch.uint8, device=H.DEV, generator=g)
+    o_store = store.cpu().numpy().copy()
+    fs = B.make_filestore(store, file_stride, first_file, n_files)
+
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq_pin = torch.zeros(sq_bytes, dtype=torch.uint8).pin_memory()
+    cq_pin = torch.zeros(cq_bytes, dtype=torch.uint8).pin_memory()
+    ring = B.make_ring(sq_pin, cq_pin, depth)
+    B.tutti_ring_init(ring)
+    torch.cuda.synchronize()
+    sq_np = sq_pin.numpy().view(B.IOCB_DTYPE)      # the CPU's mapping of the rings
+    cq_np = cq_pin.numpy().view(np.uint32)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    orc.ring_init(o_sq, o_cq)
+    state = B.make_sq_state(depth)
+    side = torch.cuda.Stream()
+    st = H.new_status()
+    o_st = 0
+
+    def ctx(op, desc, fid, off, ln, addr=None):
+        return dict(opcode=op, file_id=fid, file_off=off, len=ln, addr=base + 16 * desc if addr is None else addr)
+
+    def submit(first, items_per_slot, layer, opcode):
+        """The application's part: contexts, num_ioctx, layer, opcode, state, on both sides' rings."""
+        for b, items in enumerate(items_per_slot):
+            slot = (first + b) % depth
+            for ring_np in (sq_np, o_sq):
+                for i, it in enumerate(items):
+                    e = ring_np["ioctx"][slot][i]
+                    for f in ("opcode", "kind", "layer", "file_id", "file_off", "addr", "len", "sgl_id", "user_data",
+                              "iocb_idx", "ioctx_slot"):
+                        e[f] = 0
+                    for f, val in it.items():
+                        e[f] = val
+                ring_np["hdr"]["num_ioctx"][slot] = len(items)
+                ring_np["hdr"]["layer"][slot] = layer
+                ring_np["hdr"]["opcode"][slot] = opcode
+                ring_np["hdr"]["done"][slot] = 0
+                ring_np["hdr"]["state"][slot] = B.IOCB_FILLED
+
+    blocks = rng.permutation(np.r_[0:7, 10:N])       # descriptors 7 and 9 are the patched ones
+    reads = [ctx(B.OP_READ, int(blocks[i]) + (N if i % 2 else 0), first_file + i % 2, 8192 * i, 8192) for i in range(40)]
+    reads += [ctx(B.OP_READ, 7, first_file, 8192 * 50, 4096), ctx(B.OP_READ, int(blocks[41]), first_file, 8192 * 60, 0)]
+    bad = [ctx(0, 8, first_file, 0, 8192), ctx(3, 8, first_file, 0, 8192), ctx(B.OP_READ, 8, first_file, 0, 8192, addr=base - 16),
+           ctx(B.OP_READ, 8, first_file, 0, 8192, addr=base + 16 * 8 + 8), ctx(B.OP_READ, nd, first_file, 0, 8192),
+           ctx(B.OP_READ, 7, first_file, 0, 4112), ctx(B.OP_READ, 8, first_file, 0, 8208), ctx(B.OP_READ, 8, first_file, 0, 8184),
+           ctx(B.OP_READ, 8, first_file, 8, 8192), ctx(B.OP_READ, 9, first_file, 0, 8192),
+           ctx(B.OP_READ, 8, first_file - 1, 0, 8192), ctx(B.OP_READ, 8, first_file + 2, 0, 8192),
+           ctx(B.OP_READ, 8, first_file, file_stride - 8176, 8192), ctx(B.OP_READ, 8, first_file, (1 << 64) - 16, 8192)]
+    first = B.tutti_get_iocb(state, 2)
+    assert first == 0
+    submit(first, [reads, bad], layer=0, opcode=B.OP_READ)
+    with torch.cuda.stream(side):
+        B.tutti_issue_io(ring, first, 2, sgl, nd, base, fs, bb, 0, st, stream=side)
+    # the CPU polls the CQ in pinned memory; no synchronisation before the completions are seen
+    assert B.tutti_wait_cqe_host(state, cq_np, sq_np, (first + 1) % depth, 50_000_000), "completion never arrived"
+    assert B.tutti_iocb_completed(state, first) and B.tutti_sq_free_count(state) == depth
+    assert list(sq_np["hdr"]["state"][:2]) == [B.IOCB_FREE, B.IOCB_FREE]          # reaped: free again
+    o_st |= orc.issue_io(o_sq, o_cq, first, 2, o_sgl, base, o_store, file_stride, first_file, n_files, max_len=bb)
+    torch.cuda.synchronize()
+    assert int(st.item()) == o_st == B.ST_BAD_BLOCK
+    assert np.array_equal(k2.cpu().numpy(), ok) and np.array_equal(v2.cpu().numpy(), ov), "pool differs after the reads"
+    assert np.array_equal(sq_np["hdr"]["done"], o_sq["hdr"]["done"]) and cq_np.tobytes() == o_cq.tobytes()
+    # second round wraps around the ring: slot 2 then slot 0, writes this time, under a CU budget
+    first = B.tutti_get_iocb(state, 2)
+    assert first == 2
+    writes = [ctx(B.OP_WRITE, int(blocks[i]) + (0 if i % 2 else N), first_file + 1, 8192 * (100 - i), 8192) for i in range(30)]
+    submit(first, [writes[:11], writes[11:]], layer=1, opcode=B.OP_WRITE)
+    with torch.cuda.stream(side):
+        B.tutti_issue_io(ring, first, 2, sgl, nd, base, fs, bb, 4, st, stream=side)
+    assert B.tutti_wait_cqe_host(state, cq_np, sq_np, 0, 50_000_000)
+    o_st |= orc.issue_io(o_sq, o_cq, first, 2, o_sgl, base, o_store, file_stride, first_file, n_files, max_len=bb)
+    torch.cuda.synchronize()
+    assert np.array_equal(store.cpu().numpy(), o_store), "file store differs after the writes"
+    assert cq_np.tobytes() == o_cq.tobytes() and int(cq_np[0]) == 4      # slot 2, then slot 0: the ring wrapped
+    assert np.array_equal(k2.cpu().numpy(), ok) and np.array_equal(v2.cpu().numpy(), ov)
+    assert int(st.item()) == o_st and B.tutti_sq_free_count(state) == depth
+
+
 def test_ring_layer_cfg2(orc, H):
     """Config 2's layer through the rings in one call: 4096 contexts = two full IOCBs."""
     w = W.llama8b_32k(num_blocks=8192)
