@@ -319,6 +319,17 @@ int tutti_store_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_sl
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);
 
+/* ---- I/O domain (sec. 3.2 "SM Partitioning For Accurate I/O": the I/O kernels get compute units of their own,
+ * isolated in hardware from the compute kernels).  *stream <- a new stream whose kernels the hardware dispatches
+ * only to the first n_cus compute units of the device (a compute-unit mask on the stream's queue); pass it as
+ * `stream` to any call above with cu_budget = 0, and the call occupies those units and no others, whatever its
+ * grid.  Unlike cu_budget, which only bounds how many workgroups exist, the mask binds placement.  Other streams
+ * are not kept off those units.  TUTTI_ERANGE if n_cus is 0 or above the CU count, TUTTI_EHIP if the runtime
+ * refuses the mask (tutti_last_hip_error() tells why).  The stream has default priority and belongs to the caller
+ * until tutti_io_domain_destroy. */
+int tutti_io_domain_create(uint32_t n_cus, void **stream);
+int tutti_io_domain_destroy(void *stream);
+
 /* ---- the application's side of the rings: get_iocb and the reaping of completions (sec. 3.2 "Async I/O
  * Processing", steps 2 and 4).  Host code only: no HIP call, no device access, O(1) per IOCB.  The state lives in
  * host memory the caller owns (one per ring, used from one thread at a time).  IOCBs are handed out in ring order,

@@ -42,7 +42,8 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_table_validate", "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_resident_wgs_per_cu", "tutti_version",
            "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping",
            "tutti_sq_state_init", "tutti_get_iocb", "tutti_sq_free_count", "tutti_reap_cqe", "tutti_iocb_completed",
-           "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack"]
+           "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack", "tutti_io_domain_create",
+           "tutti_io_domain_destroy"]
 
 
 class tutti_pool(C.Structure):
@@ -155,6 +156,10 @@ def lib():
         L.tutti_resident_wgs_per_cu.restype = C.c_int
         L.tutti_set_xcd_mapping.argtypes = [u32]
         L.tutti_set_xcd_mapping.restype = C.c_int
+        L.tutti_io_domain_create.argtypes = [u32, C.POINTER(vp)]
+        L.tutti_io_domain_create.restype = C.c_int
+        L.tutti_io_domain_destroy.argtypes = [vp]
+        L.tutti_io_domain_destroy.restype = C.c_int
         ps, pio = C.POINTER(tutti_sq_state), C.POINTER(tutti_io_profile)
         L.tutti_sq_state_init.argtypes = [ps, u32, vp]
         L.tutti_get_iocb.argtypes = [ps, u32, C.POINTER(u32)]
@@ -460,3 +465,14 @@ def tutti_budget_for_slack(profile, n_rows, n_iocbs, opcode, slack_us, max_budge
         return None
     _check("tutti_budget_for_slack", rc)
     return out.value
+
+
+def tutti_io_domain_create(n_cus):
+    """A stream confined to the first n_cus compute units, as an integer handle (hipStream_t)."""
+    s = C.c_void_p(0)
+    _check("tutti_io_domain_create", lib().tutti_io_domain_create(n_cus, C.byref(s)))
+    return s.value
+
+
+def tutti_io_domain_destroy(stream):
+    return _check("tutti_io_domain_destroy", lib().tutti_io_domain_destroy(C.c_void_p(int(stream))))

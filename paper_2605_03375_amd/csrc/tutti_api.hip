@@ -955,6 +955,31 @@ int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_conti
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+int tutti_io_domain_create(uint32_t n_cus, void **stream) {
+  if (!stream) return TUTTI_EINVAL;
+  *stream = nullptr;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  if (n_cus == 0 || n_cus > static_cast<uint32_t>(cus)) return TUTTI_ERANGE;
+  // one bit per compute unit, the first n_cus of them: the only kind of mask every runtime tried so far accepts
+  constexpr uint32_t kWords = 32;  // room for 1024 compute units
+  uint32_t mask[kWords] = {0};
+  if (static_cast<uint32_t>(cus) > 32u * kWords) return TUTTI_ERANGE;
+  for (uint32_t i = 0; i < n_cus; ++i) mask[i / 32] |= 1u << (i % 32);
+  const uint32_t words = (static_cast<uint32_t>(cus) + 31u) / 32u;
+  hipStream_t s = nullptr;
+  const hipError_t e = hipExtStreamCreateWithCUMask(&s, words, mask);
+  if (e != hipSuccess) return hip_fail(e);
+  *stream = s;
+  return TUTTI_OK;
+}
+
+int tutti_io_domain_destroy(void *stream) {
+  if (!stream) return TUTTI_EINVAL;
+  const hipError_t e = hipStreamDestroy(static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
 const char *tutti_strerror(int code) {
   switch (code) {
     case TUTTI_OK:

@@ -994,6 +994,60 @@ def test_entry_builders_want_layout_extents(orc, H):
             assert g_sq["ioctx"][b][:k].tobytes() == o_sq["ioctx"][b][:k].tobytes(), label
 
 
+def test_io_domain_stream_confines_the_calls(orc, H):
+    """A stream from tutti_io_domain_create (compute-unit mask: the hardware-isolated I/O domain of sec. 3.2) passed
+    as `stream`: results stay bit-exact, and a whole-GPU-sized launch on it is held to the domain's units (timed
+    against the same launch on an ordinary stream)."""
+    say("I/O domain: CU-masked stream")
+    try:
+        handle = B.tutti_io_domain_create(16)
+    except B.TuttiError as e:
+        pytest.skip(f"the runtime refuses a compute-unit mask on this machine: {e}")
+    try:
+        dom = torch.cuda.ExternalStream(handle)
+        rng = np.random.default_rng(12)
+        n = [300, 0, 41, 700]
+        c = H.LayerCase(T=16, h=8, d=128, e=2, N=2048, n_blocks=n, table=rng.permutation(2048)[: sum(n)], chunk=32768,
+                        L=4, name="io_domain")
+        torch.cuda.synchronize()
+        with torch.cuda.stream(dom):
+            H.check_layer_restore(orc, c, layer=2)
+            H.check_layer_save(orc, c, layer=1)
+            H.check_ring_layer(orc, c, layer=3, write=False, depth=3, first_slot=2, n_slots=2)
+            H.check_ring_layer(orc, c, layer=0, write=True, depth=3, first_slot=1, n_slots=2)
+        # the same restore, 64 MiB of payload, on the domain and on an ordinary stream
+        ext = torch.zeros(c.n_req * 32, dtype=torch.uint8, device=H.DEV)
+        tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+        sqe = torch.zeros(64 * 4096, dtype=torch.uint8, device=H.DEV)
+        stage = torch.zeros(2 * sum(n) * c.bb, dtype=torch.uint8, device=H.DEV)
+        k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+        pool = c.gpu_pool(k2, v2)
+
+        def timed(stream):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for rep in range(3):
+                if rep == 1:
+                    a.record(stream)
+                B.tutti_layer_restore(pool, c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, c.table.size, c.d_file_id, 0,
+                                      stage, stage.numel(), 0, 1, ext, tot, sqe, 4096, 0, None, stream)
+            b.record(stream)
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / 2 * 1e3
+        plain = torch.cuda.Stream()
+        t_plain, t_dom = timed(plain), timed(dom)
+        say(f"I/O domain of 16 CUs: restore {t_dom:.1f} us, whole GPU {t_plain:.1f} us")
+        assert t_dom > 2.0 * t_plain, "the masked stream did not confine the launch"
+    finally:
+        torch.cuda.synchronize()
+        B.tutti_io_domain_destroy(handle)
+    with pytest.raises(B.TuttiError) as ei:
+        B.tutti_io_domain_create(0)
+    assert ei.value.code == B.ERANGE
+    with pytest.raises(B.TuttiError) as ei:
+        B.tutti_io_domain_create(B.tutti_cu_count() + 1)
+    assert ei.value.code == B.ERANGE
+
+
 def test_cu_budget_out_of_range(H):
     c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[2], table=[1, 2], name="budget")
     ext, tot = H.gpu_layout(c)
