@@ -747,14 +747,16 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_issue_io(cons
   }
 }
 
-// Completion of the IOCBs an I/O kernel has just executed (stream order puts this after all its stores):
-// FILLED -> DONE, done = num_ioctx, index appended to the CQ in slot order.  One wavefront; the CQ tail is
-// only ever advanced here, so no read-modify-write atomics are needed within a stream.  The state and the tail are published
-// with system-scope release stores, so a ring (or just its CQ) placed in pinned host memory can be polled by
-// the CPU while the stream runs on: whoever sees the new tail also sees the entries before it.
-__global__ __launch_bounds__(kWave) void k_complete(const RingArgs g) {
-  if (blockIdx.x != 0) return;
-  const uint32_t lane = threadIdx.x;
+// Completion of the IOCBs an I/O kernel has executed: FILLED -> DONE, done = num_ioctx, index appended to the CQ
+// in slot order.  Run by ONE wavefront (lane = its lane id) once every store of the I/O is visible to it: the
+// k_complete kernel enqueued behind the I/O kernel (stream order).  Doing it inside the I/O kernel instead, by
+// whichever workgroup finishes last (each workgroup releasing its stores at agent scope and counting itself in
+// on a two-level tree of counters), was built and measured: 153 us per layer against 50 + 4: an agent-scope
+// release writes back the XCD's whole L2, and 2048 workgroups each pay for one.  The CQ tail is only ever
+// advanced here, so no read-modify-write atomics are needed within a stream.  The state and the tail are
+// published with system-scope release stores, so a ring (or just its CQ) placed in pinned host memory can be
+// polled by the CPU while the stream runs on: whoever sees the new tail also sees the entries before it.
+__device__ __forceinline__ void complete_iocbs(const RingArgs g, uint32_t lane) {
   uint32_t *cq_entry = reinterpret_cast<uint32_t *>(g.cq + 1);
   uint32_t tail = g.cq->tail;  // every lane reads the same word
   // one lane per IOCB, 64 per pass (the host checked n_slots <= depth, so the slots are distinct): the header
@@ -779,8 +781,16 @@ __global__ __launch_bounds__(kWave) void k_complete(const RingArgs g) {
     }
     tail += static_cast<uint32_t>(__popcll(mask));
   }
-  __syncthreads();  // the other lanes' queue entries happen before lane 0's release of the tail
+  // every lane releases its own queue entries before lane 0 publishes the tail (the wavefront runs in step, so
+  // lane 0's store is issued after the other lanes' fences)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");  // system scope
+  __builtin_amdgcn_wave_barrier();
   if (lane == 0) __hip_atomic_store(&g.cq->tail, tail, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__global__ __launch_bounds__(kWave) void k_complete(const RingArgs g) {
+  if (blockIdx.x != 0) return;
+  complete_iocbs(g, threadIdx.x);
 }
 
 __global__ void k_cq_check(const tutti_iocb *sq, uint32_t slot, uint32_t *flag) {
@@ -998,6 +1008,7 @@ __device__ __forceinline__ void move_one(const MoveArgs &a, const Item &d, uint3
 template <int U>
 struct Preload {
   u32x4 buf[U];
+  const unsigned char *src;  // where the slice was read from (wave-uniform)
   bool valid;
 };
 
@@ -1008,8 +1019,9 @@ __device__ __forceinline__ Preload<U> preload_first(const MoveArgs &a, uint32_t 
   const uint32_t it = item_wg(a, wg, copy_wgs) * (blockDim.x / kWave) + rfl(threadIdx.x / kWave);
   Preload<U> p;
   p.valid = a.dense != 0 && it < a.items_bound && (static_cast<uint64_t>(it) + 1) * kSlice <= a.stage_cap;
+  p.src = a.stage + static_cast<uint64_t>(it) * kSlice;
   if (p.valid) {
-    const unsigned char *src = a.stage + static_cast<uint64_t>(it) * kSlice + lane * 16u;
+    const unsigned char *src = p.src + lane * 16u;
 #pragma unroll
     for (int k = 0; k < U; ++k) p.buf[k] = ld16<NT>(src + k * (kWave * 16u));
   }
@@ -1074,11 +1086,11 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
       nxt = decode_item<SEP>(a, l, n_req, nit, lane);
       nid = load_block_id(a, nxt);
     }
-    // the preloaded bytes are those of staging item `it`; extents the library computed put the item's slice
-    // exactly there, extents from the caller may not: then the slice is loaded from where they say
+    // the preloaded bytes were read where the item's slice sits when the extents are the library's own; extents
+    // from the caller (and the files of the direct-to-block mode) may put it elsewhere: then the slice is loaded
+    // from where they say
     const bool preloaded = DIR == kUnpack && first && pre.valid &&
-                           (!SEP || cur.obj_blk + static_cast<uint64_t>(cur.s) * kSlice ==
-                                        a.stage + static_cast<uint64_t>(it) * kSlice);
+                           ((!SEP && !a.direct) || cur.obj_blk + static_cast<uint64_t>(cur.s) * kSlice == pre.src);
     if (preloaded)
       store_preloaded<HND, U, NT>(a, cur, id, lane, pre);
     else
@@ -1288,17 +1300,56 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer(const M
   if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
+// First item of a wavefront in a retrieve of ONE request: its file bytes sit at
+//   file start + 2*layer*obj_bytes + item*slice        (obj_bytes = n_blocks*block_bytes: blocks are whole
+// alignment units in this mode), which takes two words from memory, the block count and the file id, and no scan.
+// Every wavefront fetches them itself through the scalar path and has its loads in flight while the workgroup's
+// first wavefront scans and the barrier is crossed; move_items checks the address against the decoded one.
+template <int U>
+__device__ __forceinline__ Preload<U> preload_first_direct(const MoveArgs &m, const uint32_t *n_blocks,
+                                                           const uint32_t *file_id, const FileArgs f, uint32_t wg,
+                                                           uint32_t copy_wgs) {
+  constexpr uint32_t kSlice = kWave * 16u * U;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t it = item_wg(m, wg, copy_wgs) * (blockDim.x / kWave) + rfl(threadIdx.x / kWave);
+  Preload<U> p;
+  p.valid = false;
+  if (m.block_bytes % kSlice != 0) return p;
+  const uint32_t n = rfl(n_blocks[0]), fid = rfl(file_id[0]);
+  const uint32_t rel = fid - f.first_file_id;
+  const uint64_t obj = static_cast<uint64_t>(n) * m.block_bytes;
+  const uint64_t units = 2ull * (n < m.table_len ? n : m.table_len);
+  const uint64_t lo = 2ull * m.layer * obj;  // file offset of the layer's K object
+  // inside the table, inside the recorded contexts, inside the file (K and V objects of the layer: 2*obj bytes)
+  if (fid < f.first_file_id || rel >= f.n_files || it >= units * m.slices_per_block ||
+      it / m.slices_per_block >= m.ctx_cap || obj == 0 || lo / obj != 2ull * m.layer || lo + 2 * obj < lo ||
+      lo + 2 * obj > f.file_stride)
+    return p;
+  p.valid = true;
+  p.src = m.stage + static_cast<uint64_t>(rel) * f.file_stride + lo + static_cast<uint64_t>(it) * kSlice;
+  const unsigned char *src = p.src + lane * 16u;
+#pragma unroll
+  for (int k = 0; k < U; ++k) p.buf[k] = ld16<3>(src + k * (kWave * 16u));
+  return p;
+}
+
 // retrieve_layer / store_layer through the rings in one launch (direct-to-block mode): the scan puts the start
 // of every request's file in the store where the staging offsets would be, then the first `sqe_wgs`
 // workgroups record the layer's contexts in the IOCBs while the copy workgroups move the very same blocks,
 // each item deriving its file offset and block from the extents and the table exactly as its context does.
 // Blocks go to the file as they sit in the pool (a descriptor names raw bytes), so there is no head-major case.
+// The host enqueues k_complete behind this kernel.
 template <int DIR, int U, int WG>
 __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(const MoveArgs m, const SqeArgs q, const DirectArgs d,
                                                     const RingArgs g, const FileArgs f, const LayoutArgs a,
                                                     const Roles w) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
+  const bool copies = blockIdx.x - w.copy_first < w.copy_wgs;
+  Preload<U> pre;
+  pre.valid = false;
+  if (DIR == kUnpack && copies && a.n_req == 1)
+    pre = preload_first_direct<U>(m, a.n_blocks, q.file_id, f, blockIdx.x - w.copy_first, w.copy_wgs);
   if (threadIdx.x < kWave) {
     const bool publish = blockIdx.x == 0;
     // chunk counts only matter for the published extents; the LDS copy gets file starts instead of staging offsets
@@ -1309,10 +1360,7 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(co
   DirectHead head;
   head.live = false;
   if (blockIdx.x < w.sqe_wgs) head = iocb_head(g, q, d, l, a.n_req, 0, w.sqe_wgs);
-  Preload<U> pre;
-  pre.valid = false;
-  if (blockIdx.x - w.copy_first < w.copy_wgs)
-    move_items<DIR, false, U, 3, false>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs, pre);
+  if (copies) move_items<DIR, false, U, 3, false>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs, pre);
   if (blockIdx.x < w.sqe_wgs) emit_iocbs(g, q, d, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
