@@ -83,12 +83,15 @@ def main():
     from paper_2605_03375_amd import binding as B
     from paper_2605_03375_amd import workloads as W
 
-    B.lib()  # no fallback: raises if libtutti.so is not built
+    B.product_lib()  # no fallback: raises if libtutti.so is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    B.tutti_set_tuning(args.wgs_per_cu, args.unroll)
-    B.tutti_set_nontemporal(0 if args.plain_loads else 3)
+    tuned = bool(args.wgs_per_cu or args.unroll or args.plain_loads)
+    if tuned:   # an experiment: the same kernels in another launch shape, from the measurement library
+        B.use_bench_library(True)
+        B.tutti_set_tuning(args.wgs_per_cu, args.unroll)
+        B.tutti_set_nontemporal(0 if args.plain_loads else 3)
 
     w = W.llama8b_32k()
     s = w.shape

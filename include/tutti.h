@@ -11,9 +11,11 @@
  *   - Pointers named d_* are DEVICE pointers owned by the caller; tutti_pool / tutti_objcfg
  *     pointers are HOST pointers read during the call.  `stream` is a hipStream_t passed as
  *     void* (NULL = the null stream).
- *   - The library allocates no device memory and keeps no per-call state (the pool is fixed
- *     for the engine's lifetime and nothing on the I/O path may allocate: sec. 3.1 "P2P
- *     Memory Mapping Table", sec. 3.2 "Zero-Copy Ring Buffers").
+ *   - The library allocates no device memory and keeps no state between calls: what a call does
+ *     depends on its arguments alone (the pool is fixed for the engine's lifetime and nothing on
+ *     the I/O path may allocate: sec. 3.1 "P2P Memory Mapping Table", sec. 3.2 "Zero-Copy Ring
+ *     Buffers").  Launch-tuning knobs and baseline kernels for measurements live in a separate
+ *     library (tutti_bench.h), not here.
  *   - A call validates its host arguments in O(1), enqueues a constant number of kernels on
  *     `stream` and returns; it never synchronises and never copies to the host.  Results are
  *     valid once the caller has synchronised the stream.
@@ -396,33 +398,6 @@ int tutti_budget_for_slack(const tutti_io_profile *rows, uint32_t n_rows, uint32
 int tutti_table_validate(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
                          void *stream);
 
-/* ---- measurement aid: a plain contiguous device-to-device copy of `bytes` (multiple of 16, both
- * pointers 16-byte aligned) with the same load/store width and launch shape as unpack: the
- * achievable ceiling the pack/unpack rates are compared with. */
-int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream);
-
-/* ---- measurement aid: one direction only, with the copy's access and launch shape.  write = 0: read `bytes`
- * from d_buf and xor every 16-byte unit, as four 32-bit words, into d_xor: TUTTI_STREAM_SLOTS slots of four
- * words, which the caller zeroes first; each wavefront adds its part to one slot with atomics, so the xor over
- * all slots is the xor of the buffer's units, and calls on one d_xor accumulate.  write != 0: fill d_buf,
- * 16-byte unit i becoming the words { low 32 bits of i, high 32 bits of i, ~low, 0x54555454 }; d_xor is not
- * used.  bytes a multiple of 16, d_buf 16-byte aligned.  What one compute unit (under a CU budget) or the chip
- * reads or writes when it does nothing else: the limits the budgeted copy is compared with. */
-#define TUTTI_STREAM_SLOTS 4096u
-int tutti_stream_baseline(void *d_buf, uint64_t bytes, uint32_t write, uint32_t *d_xor, uint32_t cu_budget,
-                          void *stream);
-
-/* ---- measurement aid: the same copy with one side scattered at `gran`-byte granularity and nothing else
- * (no extents, no requests, no K/V planes): piece i of the contiguous side, i < bytes/gran, pairs with the
- * piece at d_scattered + d_perm[i]*gran.  scatter_writes != 0: contiguous -> scattered (the shape of an
- * unpack); 0: scattered -> contiguous (a pack).  What the memory system itself gives for that access
- * pattern: the floor pack / unpack are compared with.  gran a multiple of 4096; bytes a multiple of gran;
- * every d_perm[i]*gran + gran must lie inside the scattered buffer (span_bytes is checked on the device,
- * offending pieces are skipped). */
-int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_contig, uint64_t bytes,
-                           const uint32_t *d_perm, uint32_t gran, uint32_t scatter_writes, uint32_t cu_budget,
-                           void *stream);
-
 /* ---- housekeeping */
 const char *tutti_strerror(int code);
 int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */
@@ -439,20 +414,6 @@ uint32_t tutti_version(void);       /* 0x00MMmmpp */
  * pool size + 9, objcfg size + 3, sgl size + 3, iocb_hdr size + 6, iocb size + offset of its contexts,
  * cq_hdr size, filestore size + 4); returns the count or TUTTI_EINVAL if cap is too small. */
 int tutti_abi_describe(uint32_t *out, uint32_t cap);
-/* Launch tuning, for experiments: wgs_per_cu persistent workgroups per budgeted CU (0 = default),
- * unroll = 16-byte accesses in flight per lane (0 = default; 1, 2, 4 or 8). */
-int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll);
-/* Head-major pools: 0 = the library chooses (token tiles transposed in LDS when a (token, head) row is
- * shorter than 128 bytes and T, h and the row size are powers of two; else 16 bytes per lane straight
- * between the two orders), 1 = always the direct copy, 2 = through LDS whenever the shape allows. */
-int tutti_set_hnd_mode(uint32_t mode);
-/* Experiment switch: how pack / unpack work items are dealt to workgroups.  0 (default): workgroup b starts
- * at item 4b, so the workgroups the dispatcher deals round-robin to the 8 XCDs take neighbouring 16 KiB;
- * 1: each XCD takes one contiguous eighth of the items. */
-int tutti_set_xcd_mapping(uint32_t contiguous);
-/* Experiment switch for the copy loops: bit 0 = non-temporal 16-byte loads, bit 1 = non-temporal
- * 16-byte stores (default 3 = both). */
-int tutti_set_nontemporal(uint32_t mask);
 
 #ifdef __cplusplus
 }

@@ -4,6 +4,12 @@ Every function has the name and argument order of its C entry point; device poin
 given as torch tensors (their data_ptr() is taken) or as integers.  `stream=None` means
 torch's current stream.  A non-zero return code raises TuttiError.  There is no fallback:
 if the HIP library has not been built, `lib()` raises.
+
+Two libraries are built from the same sources: libtutti.so, the product, and libtutti_bench.so, which
+exports the same entry points plus the measurement aids of include/tutti_bench.h (baseline kernels, tuning
+knobs, every launch shape).  The wrappers of the measurement aids always call the latter;
+`use_bench_library(True)` also routes the ordinary entry points through it, so that an experiment can run the
+product's kernels in another launch shape.  Nothing but bench.py and the tests of those aids does that.
 """
 import ctypes as C
 import os
@@ -12,7 +18,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtutti.so")
+BENCH_LIB_PATH = os.path.join(_HERE, "libtutti_bench.so")
 _LIB = None
+_BENCH_LIB = None
+_USE_BENCH = False
 
 OK, EINVAL, ERANGE, EHIP, EAGAIN = 0, -1, -2, -3, -4
 LAYOUT_NHD, LAYOUT_HND = 0, 1
@@ -36,14 +45,17 @@ SGL_DTYPE = np.dtype({"names": ["addr", "len", "id"], "formats": ["<u8", "<u4", 
                       "itemsize": 16})
 
 EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
-           "tutti_layer_save",
-           "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
-           "tutti_issue_io", "tutti_wait_cqe", "tutti_retrieve_layer", "tutti_store_layer",
-           "tutti_table_validate", "tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count", "tutti_resident_wgs_per_cu", "tutti_version",
-           "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping",
+           "tutti_layer_save", "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init",
+           "tutti_iocb_fill_direct", "tutti_issue_io", "tutti_wait_cqe", "tutti_retrieve_layer", "tutti_store_layer",
+           "tutti_table_validate", "tutti_strerror", "tutti_last_hip_error", "tutti_cu_count",
+           "tutti_resident_wgs_per_cu", "tutti_version", "tutti_abi_describe",
            "tutti_sq_state_init", "tutti_get_iocb", "tutti_sq_free_count", "tutti_reap_cqe", "tutti_iocb_completed",
            "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack", "tutti_io_domain_create",
            "tutti_io_domain_destroy"]
+BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
+                 "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
+SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
+                  "wg_piece_nt_loads": 5, "wg_piece_nt_stores": 6}
 
 
 class tutti_pool(C.Structure):
@@ -108,78 +120,96 @@ class TuttiError(RuntimeError):
         super().__init__(f"{fn}: {msg} (code {code}" + (f", hipError {hip})" if hip else ")"))
 
 
-def lib():
-    """The loaded HIP library.  Raises if it has not been built: there is no other path."""
-    global _LIB
-    if _LIB is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_03375_amd.build` "
-                               "(or __graft_entry__.build()); libtutti has no CPU fallback")
-        # PyTorch ships its own HIP runtime (same soname as the system one).  Import it first so
-        # that libtutti binds to the runtime that owns the process's device context and streams;
-        # two HIP runtimes in one process do not share a device.
-        import torch  # noqa: F401
-        L = C.CDLL(LIB_PATH)
-        vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
-        pp, pc = C.POINTER(tutti_pool), C.POINTER(tutti_objcfg)
-        L.tutti_obj_layout.argtypes = [pp, pc, vp, u32, vp, vp, vp]
-        L.tutti_obj_pack.argtypes = [pp, pc, vp, u32, vp, u32, vp, u64, u32, vp, vp]
-        L.tutti_obj_unpack.argtypes = [pp, pc, vp, u32, vp, u32, vp, u64, u32, vp, vp]
-        L.tutti_sqe_build.argtypes = [pp, pc, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
-        L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
-                                          vp, vp]
-        L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
-        L.tutti_layer_save.restype = C.c_int
+def _declare(L, bench):
+    vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
+    pp, pc = C.POINTER(tutti_pool), C.POINTER(tutti_objcfg)
+    L.tutti_obj_layout.argtypes = [pp, pc, vp, u32, vp, vp, vp]
+    L.tutti_obj_pack.argtypes = [pp, pc, vp, u32, vp, u32, vp, u64, u32, vp, vp]
+    L.tutti_obj_unpack.argtypes = [pp, pc, vp, u32, vp, u32, vp, u64, u32, vp, vp]
+    L.tutti_sqe_build.argtypes = [pp, pc, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
+    L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
+                                      vp, vp]
+    L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
+    L.tutti_table_validate.argtypes = [u32, vp, u32, vp, vp]
+    pr, pf = C.POINTER(tutti_ring), C.POINTER(tutti_filestore)
+    L.tutti_ring_init.argtypes = [pr, vp]
+    L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
+    L.tutti_issue_io.argtypes = [pr, u32, u32, vp, u32, u64, pf, u32, u32, vp, vp]
+    L.tutti_wait_cqe.argtypes = [pr, u32, vp, vp]
+    L.tutti_retrieve_layer.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u64, u32, pf, vp, vp, u32,
+                                       vp, vp]
+    L.tutti_store_layer.argtypes = L.tutti_retrieve_layer.argtypes
+    L.tutti_sgl_table_build.argtypes = [pp, u64, u64, u32, vp, u32, vp, vp]
+    L.tutti_sqe_build_direct.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
+    L.tutti_strerror.argtypes = [C.c_int]
+    L.tutti_strerror.restype = C.c_char_p
+    L.tutti_version.restype = u32
+    L.tutti_abi_describe.argtypes = [vp, u32]
+    L.tutti_resident_wgs_per_cu.argtypes = [u32]
+    L.tutti_io_domain_create.argtypes = [u32, C.POINTER(vp)]
+    L.tutti_io_domain_destroy.argtypes = [vp]
+    ps, pio = C.POINTER(tutti_sq_state), C.POINTER(tutti_io_profile)
+    L.tutti_sq_state_init.argtypes = [ps, u32, vp]
+    L.tutti_get_iocb.argtypes = [ps, u32, C.POINTER(u32)]
+    L.tutti_sq_free_count.argtypes = [ps]
+    L.tutti_sq_free_count.restype = u32
+    L.tutti_reap_cqe.argtypes = [ps, vp, vp, C.POINTER(u32)]
+    L.tutti_iocb_completed.argtypes = [ps, u32]
+    L.tutti_wait_cqe_host.argtypes = [ps, vp, vp, u32, u32]
+    L.tutti_iocbs_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, C.POINTER(u32)]
+    L.tutti_budget_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, u32, C.POINTER(u32)]
+    for name in EXPORTS:
+        if name not in ("tutti_strerror", "tutti_version", "tutti_sq_free_count"):
+            getattr(L, name).restype = C.c_int
+    if bench:
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
-        L.tutti_table_validate.argtypes = [u32, vp, u32, vp, vp]
         L.tutti_stream_baseline.argtypes = [vp, u64, u32, vp, u32, vp]
-        L.tutti_scatter_baseline.argtypes = [vp, u64, vp, u64, vp, u32, u32, u32, vp]
-        L.tutti_scatter_baseline.restype = C.c_int
-        pr, pf = C.POINTER(tutti_ring), C.POINTER(tutti_filestore)
-        L.tutti_ring_init.argtypes = [pr, vp]
-        L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
-        L.tutti_issue_io.argtypes = [pr, u32, u32, vp, u32, u64, pf, u32, u32, vp, vp]
-        L.tutti_wait_cqe.argtypes = [pr, u32, vp, vp]
-        L.tutti_retrieve_layer.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u64, u32, pf, vp, vp, u32,
-                                           vp, vp]
-        L.tutti_store_layer.argtypes = L.tutti_retrieve_layer.argtypes
-        L.tutti_sgl_table_build.argtypes = [pp, u64, u64, u32, vp, u32, vp, vp]
-        L.tutti_sqe_build_direct.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
-        L.tutti_strerror.argtypes = [C.c_int]
-        L.tutti_strerror.restype = C.c_char_p
-        L.tutti_version.restype = u32
-        L.tutti_abi_describe.argtypes = [vp, u32]
+        L.tutti_scatter_baseline.argtypes = [vp, u64, vp, u64, vp, u32, u32, u32, u32, vp]
         L.tutti_set_tuning.argtypes = [u32, u32]
         L.tutti_set_nontemporal.argtypes = [u32]
         L.tutti_set_hnd_mode.argtypes = [u32]
-        L.tutti_resident_wgs_per_cu.argtypes = [u32]
-        L.tutti_resident_wgs_per_cu.restype = C.c_int
         L.tutti_set_xcd_mapping.argtypes = [u32]
-        L.tutti_set_xcd_mapping.restype = C.c_int
-        L.tutti_io_domain_create.argtypes = [u32, C.POINTER(vp)]
-        L.tutti_io_domain_create.restype = C.c_int
-        L.tutti_io_domain_destroy.argtypes = [vp]
-        L.tutti_io_domain_destroy.restype = C.c_int
-        ps, pio = C.POINTER(tutti_sq_state), C.POINTER(tutti_io_profile)
-        L.tutti_sq_state_init.argtypes = [ps, u32, vp]
-        L.tutti_get_iocb.argtypes = [ps, u32, C.POINTER(u32)]
-        L.tutti_sq_free_count.argtypes = [ps]
-        L.tutti_sq_free_count.restype = u32
-        L.tutti_reap_cqe.argtypes = [ps, vp, vp, C.POINTER(u32)]
-        L.tutti_iocb_completed.argtypes = [ps, u32]
-        L.tutti_wait_cqe_host.argtypes = [ps, vp, vp, u32, u32]
-        L.tutti_iocbs_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, C.POINTER(u32)]
-        L.tutti_budget_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, u32, C.POINTER(u32)]
-        for name in ("tutti_sq_state_init", "tutti_get_iocb", "tutti_reap_cqe", "tutti_iocb_completed",
-                     "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack"):
+        for name in BENCH_EXPORTS:
             getattr(L, name).restype = C.c_int
-        for name in ("tutti_ring_init", "tutti_iocb_fill_direct", "tutti_issue_io", "tutti_wait_cqe",
-                     "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build",
-                     "tutti_layer_restore", "tutti_copy_baseline", "tutti_last_hip_error", "tutti_cu_count",
-                     "tutti_abi_describe", "tutti_set_tuning", "tutti_set_nontemporal", "tutti_set_hnd_mode"):
-            getattr(L, name).restype = C.c_int
-        _LIB = L
+    return L
+
+
+def _load(path, bench):
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2605_03375_amd.build` "
+                           "(or __graft_entry__.build()); libtutti has no CPU fallback")
+    # PyTorch ships its own HIP runtime (same soname as the system one).  Import it first so
+    # that libtutti binds to the runtime that owns the process's device context and streams;
+    # two HIP runtimes in one process do not share a device.
+    import torch  # noqa: F401
+    return _declare(C.CDLL(path), bench)
+
+
+def product_lib():
+    """libtutti.so.  Raises if it has not been built: there is no other path."""
+    global _LIB
+    if _LIB is None:
+        _LIB = _load(LIB_PATH, False)
     return _LIB
+
+
+def bench_lib():
+    """libtutti_bench.so: the same entry points plus the measurement aids."""
+    global _BENCH_LIB
+    if _BENCH_LIB is None:
+        _BENCH_LIB = _load(BENCH_LIB_PATH, True)
+    return _BENCH_LIB
+
+
+def use_bench_library(on=True):
+    """Route the ordinary entry points through libtutti_bench.so (experiments with the tuning knobs) or back."""
+    global _USE_BENCH
+    _USE_BENCH = bool(on)
+
+
+def lib():
+    """The library the ordinary wrappers call: the product, unless use_bench_library(True) was called."""
+    return bench_lib() if _USE_BENCH else product_lib()
 
 
 def _p(x):
@@ -331,20 +361,21 @@ def tutti_table_validate(num_blocks, d_block_table, table_len, d_status, stream=
 
 
 def tutti_stream_baseline(d_buf, nbytes, write, d_xor=None, cu_budget=0, stream=None):
-    return _check("tutti_stream_baseline", lib().tutti_stream_baseline(_p(d_buf), nbytes, 1 if write else 0, _p(d_xor),
+    return _check("tutti_stream_baseline", bench_lib().tutti_stream_baseline(_p(d_buf), nbytes, 1 if write else 0, _p(d_xor),
                                                                        cu_budget, _stream(stream)))
 
 
 def tutti_copy_baseline(d_dst, d_src, nbytes, cu_budget=0, stream=None):
-    return _check("tutti_copy_baseline", lib().tutti_copy_baseline(_p(d_dst), _p(d_src), nbytes, cu_budget,
+    return _check("tutti_copy_baseline", bench_lib().tutti_copy_baseline(_p(d_dst), _p(d_src), nbytes, cu_budget,
                                                                    _stream(stream)))
 
 
-def tutti_scatter_baseline(d_scattered, span_bytes, d_contig, nbytes, d_perm, gran, scatter_writes, cu_budget=0,
-                           stream=None):
+def tutti_scatter_baseline(d_scattered, span_bytes, d_contig, nbytes, d_perm, gran, scatter_writes, shape=0,
+                           cu_budget=0, stream=None):
+    shape = SCATTER_SHAPES.get(shape, shape)
     return _check("tutti_scatter_baseline",
-                  lib().tutti_scatter_baseline(_p(d_scattered), span_bytes, _p(d_contig), nbytes, _p(d_perm), gran,
-                                               1 if scatter_writes else 0, cu_budget, _stream(stream)))
+                  bench_lib().tutti_scatter_baseline(_p(d_scattered), span_bytes, _p(d_contig), nbytes, _p(d_perm), gran,
+                                                     1 if scatter_writes else 0, shape, cu_budget, _stream(stream)))
 
 
 def tutti_strerror(code):
@@ -382,19 +413,19 @@ def tutti_abi_describe():
 
 
 def tutti_set_tuning(wgs_per_cu=0, unroll=0):
-    return _check("tutti_set_tuning", lib().tutti_set_tuning(wgs_per_cu, unroll))
+    return _check("tutti_set_tuning", bench_lib().tutti_set_tuning(wgs_per_cu, unroll))
 
 
 def tutti_set_nontemporal(mask=3):
-    return _check("tutti_set_nontemporal", lib().tutti_set_nontemporal(int(mask)))
+    return _check("tutti_set_nontemporal", bench_lib().tutti_set_nontemporal(int(mask)))
 
 
 def tutti_set_hnd_mode(mode=0):
-    return _check("tutti_set_hnd_mode", lib().tutti_set_hnd_mode(int(mode)))
+    return _check("tutti_set_hnd_mode", bench_lib().tutti_set_hnd_mode(int(mode)))
 
 
 def tutti_set_xcd_mapping(contiguous=0):
-    return _check("tutti_set_xcd_mapping", lib().tutti_set_xcd_mapping(1 if contiguous else 0))
+    return _check("tutti_set_xcd_mapping", bench_lib().tutti_set_xcd_mapping(1 if contiguous else 0))
 
 
 # ---- the application's side of the rings (host code only: none of these needs a GPU)

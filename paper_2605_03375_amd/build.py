@@ -9,8 +9,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtutti.so")
+BENCH_LIB = os.path.join(HERE, "libtutti_bench.so")  # the same sources with the measurement aids compiled in
 SOURCES = [os.path.join(CSRC, "tutti_api.hip"), os.path.join(CSRC, "tutti_host.cpp")]
-DEPS = SOURCES + [os.path.join(CSRC, "tutti_kernels.hip.h"), os.path.join(ROOT, "include", "tutti.h")]
+DEPS = SOURCES + [os.path.join(CSRC, "tutti_kernels.hip.h"), os.path.join(ROOT, "include", "tutti.h"),
+                  os.path.join(ROOT, "include", "tutti_bench.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
@@ -19,17 +21,28 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_lib(force: bool = True, verbose: bool = False) -> str:
-    if not force and os.path.exists(LIB):
-        if os.path.getmtime(LIB) >= max(os.path.getmtime(p) for p in DEPS):
-            return LIB
+def _build(out: str, defines, force: bool, verbose: bool) -> str:
+    if not force and os.path.exists(out):
+        if os.path.getmtime(out) >= max(os.path.getmtime(p) for p in DEPS):
+            return out
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, f"-I{os.path.join(ROOT, 'include')}", f"-I{CSRC}", *SOURCES, "-o", LIB]
+    cmd = [hipcc, *HIPCC_FLAGS, *defines, f"-I{os.path.join(ROOT, 'include')}", f"-I{CSRC}", *SOURCES, "-o", out]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True, cwd=ROOT)
-    return LIB
+    return out
+
+
+def build_lib(force: bool = True, verbose: bool = False) -> str:
+    """The product library: paper_2605_03375_amd/libtutti.so."""
+    return _build(LIB, [], force, verbose)
+
+
+def build_bench_lib(force: bool = True, verbose: bool = False) -> str:
+    """The measurement library: the same entry points plus baselines, tuning knobs and all launch shapes."""
+    return _build(BENCH_LIB, ["-DTUTTI_BENCH_BUILD"], force, verbose)
 
 
 if __name__ == "__main__":
     print(build_lib(force=True, verbose=True))
+    print(build_bench_lib(force=True, verbose=True))

@@ -2,12 +2,21 @@
 //
 // Each entry point checks its host arguments in O(1), fills a small argument struct and
 // enqueues a constant number of kernels on the caller's stream.  No allocation, no
-// synchronisation, no device-to-host copy.
+// synchronisation, no device-to-host copy, and no state that one call leaves for another (the
+// only thing remembered is the device's compute-unit count).
+//
+// The same file builds the measurement library libtutti_bench.so when TUTTI_BENCH_BUILD is defined:
+// the same entry points, plus the launch-tuning knobs (per host thread), the baseline kernels and
+// every launch shape the knobs can select, all declared in include/tutti_bench.h.  The product
+// library holds the two launch shapes it uses and no knob.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
 
 #include "tutti.h"
+#ifdef TUTTI_BENCH_BUILD
+#include "tutti_bench.h"
+#endif
 #include "tutti_kernels.hip.h"
 
 namespace {
@@ -16,16 +25,26 @@ using namespace tutti;
 
 thread_local int t_last_hip = 0;
 
-std::atomic<uint32_t> g_wgs_per_cu{0};
-std::atomic<uint32_t> g_unroll{0};
-std::atomic<uint32_t> g_nontemporal{3};  // bit 0: loads, bit 1: stores
-std::atomic<uint32_t> g_xcd_contiguous{0};  // experiment: item numbering per XCD (see MoveArgs::xcd_contiguous)
-std::atomic<uint32_t> g_hnd_mode{0};     // head-major pools: 0 = choose, 1 = direct, 2 = through LDS when possible
-
 constexpr uint32_t kDefaultWgsPerCu = 8;     // whole-GPU launches: 8 x 256 threads = 32 wavefronts per CU
 constexpr uint32_t kDefaultUnroll = 4;       // 4 x 16 B in flight per lane: 4 KiB slices
 constexpr uint32_t kBudgetUnroll = 8;        // CU-budgeted launches keep more bytes in flight per wavefront
 constexpr int kMaxDevices = 64;
+
+// What an experiment may change about a launch; 0 = the library's own choice.
+struct Tuning {
+  uint32_t wgs_per_cu = 0;
+  uint32_t unroll = 0;
+  uint32_t nontemporal = 3;     // bit 0: loads, bit 1: stores
+  uint32_t xcd_contiguous = 0;  // item numbering per XCD (see MoveArgs::xcd_contiguous)
+  uint32_t hnd_mode = 0;        // head-major pools: 0 = choose, 1 = direct, 2 = through LDS when possible
+};
+
+#ifdef TUTTI_BENCH_BUILD
+thread_local Tuning t_tuning;  // set by tutti_set_*: only the calls of the same host thread see it
+inline Tuning tuning() { return t_tuning; }
+#else
+inline Tuning tuning() { return Tuning{}; }
+#endif
 
 std::atomic<int> g_cu_count[kMaxDevices];
 
@@ -144,8 +163,9 @@ int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
   const int cus = cu_count();
   if (cus < 0) return cus;
   if (cu_budget > static_cast<uint32_t>(cus)) return TUTTI_ERANGE;
-  uint32_t u = g_unroll.load(std::memory_order_relaxed);
-  out->nontemporal = g_nontemporal.load(std::memory_order_relaxed) & 3u;
+  const Tuning t = tuning();
+  uint32_t u = t.unroll;
+  out->nontemporal = t.nontemporal & 3u;
   if (cu_budget) {
     out->hnd_lds = false;
     out->tile_lds = 0;
@@ -157,7 +177,7 @@ int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
     out->grid = static_cast<uint32_t>(need < cu_budget ? need : cu_budget);
     return TUTTI_OK;
   }
-  uint32_t per_cu = g_wgs_per_cu.load(std::memory_order_relaxed);
+  uint32_t per_cu = t.wgs_per_cu;
   if (per_cu == 0) per_cu = kDefaultWgsPerCu;
   const uint64_t cap = static_cast<uint64_t>(cus) * per_cu;
   const uint64_t waves = kWgThreads / kWave;
@@ -197,7 +217,7 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
 
   L->hnd_lds = false;
   L->tile_lds = 0;
-  const uint32_t mode = g_hnd_mode.load(std::memory_order_relaxed);
+  const uint32_t mode = tuning().hnd_mode;
   if (pool->pool_layout == TUTTI_LAYOUT_HND && mode != 1) {
     // through LDS: T, h and the row size powers of two, one token of all heads within the tile cap,
     // the tile a whole number (1, 2, 4 or 8) of 16-byte units per thread, and LDS to hold it
@@ -233,7 +253,7 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
   // the kernels number work items in 32 bits
   if (2ull * table_len * m->slices_per_block > 0xffffffffull) return TUTTI_ERANGE;
   m->items_bound = 2u * table_len * m->slices_per_block;
-  m->xcd_contiguous = g_xcd_contiguous.load(std::memory_order_relaxed);
+  m->xcd_contiguous = tuning().xcd_contiguous;
   // dense staging: no padding anywhere and no ragged slice, so the staging offset of an item is item * slice
   const uint32_t slice_bytes = kWave * 16u * L->unroll;
   m->dense = (!L->hnd_lds && block_bytes % align == 0 && block_bytes % slice_bytes == 0) ? 1u : 0u;
@@ -280,7 +300,7 @@ Roles make_roles(const Launch &L, uint64_t entry_quarters, uint32_t *grid) {
   if (need < 1) need = 1;
   uint64_t limit = L.grid;
   if (L.wg_threads == kWgThreads) {
-    uint32_t per_cu = g_wgs_per_cu.load(std::memory_order_relaxed);
+    uint32_t per_cu = tuning().wgs_per_cu;
     if (per_cu == 0) per_cu = kDefaultWgsPerCu;
     const int cus = cu_count();
     const uint64_t cap = cus > 0 ? static_cast<uint64_t>(cus) * per_cu : L.grid;
@@ -320,74 +340,56 @@ hipError_t launch_layer_lds(const Launch &L, uint64_t entry_quarters, uint32_t l
   return hipGetLastError();
 }
 
+// The launch shape as template arguments: U = 16-byte accesses in flight per lane, NT = non-temporal mask,
+// WG = workgroup size.  The product library holds the two shapes plan_launch chooses by itself (whole GPU and
+// under a CU budget); the measurement build adds every shape the tuning knobs can ask for.
+template <int U_, int NT_, int WG_>
+struct Shape {
+  static constexpr int U = U_, NT = NT_, WG = WG_;
+};
+
+template <typename F>
+hipError_t with_shape(const Launch &L, F &&f) {
+#define TUTTI_SHAPE(U, NT, WG) \
+  if (L.unroll == U && L.nontemporal == NT && L.wg_threads == WG) return f(Shape<U, NT, WG>{});
+  TUTTI_SHAPE(4, 3, kWgThreads)
+  TUTTI_SHAPE(8, 3, kBudgetWgThreads)
+#ifdef TUTTI_BENCH_BUILD
+#define TUTTI_SHAPES_NT(U, WG) TUTTI_SHAPE(U, 0, WG) TUTTI_SHAPE(U, 1, WG) TUTTI_SHAPE(U, 2, WG) TUTTI_SHAPE(U, 3, WG)
+  TUTTI_SHAPES_NT(1, kWgThreads)
+  TUTTI_SHAPES_NT(2, kWgThreads)
+  TUTTI_SHAPES_NT(4, kWgThreads)
+  TUTTI_SHAPES_NT(8, kWgThreads)
+  TUTTI_SHAPES_NT(1, kBudgetWgThreads)
+  TUTTI_SHAPES_NT(2, kBudgetWgThreads)
+  TUTTI_SHAPES_NT(4, kBudgetWgThreads)
+  TUTTI_SHAPES_NT(8, kBudgetWgThreads)
+#undef TUTTI_SHAPES_NT
+#endif
+#undef TUTTI_SHAPE
+  return hipErrorInvalidValue;
+}
+
 template <int DIR, bool HND>
 hipError_t launch_move(const Launch &L, uint32_t lds, hipStream_t s, const MoveArgs &m, const tutti_extent *ext,
                        uint32_t n_req) {
-#define TUTTI_MOVE_NT(U, NT)                                                                                      \
-  case NT:                                                                                                        \
-    if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_move<DIR, HND, U, NT, kWgThreads>), dim3(L.grid), dim3(kWgThreads), lds, s, m, ext,   \
-                         n_req);                                                                                  \
-    else                                                                                                          \
-      hipLaunchKernelGGL((k_move<DIR, HND, U, NT, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), lds,  \
-                         s, m, ext, n_req);                                                                       \
-    break;
-#define TUTTI_MOVE_CASE(U)       \
-  case U:                        \
-    switch (L.nontemporal) {     \
-      TUTTI_MOVE_NT(U, 0)        \
-      TUTTI_MOVE_NT(U, 1)        \
-      TUTTI_MOVE_NT(U, 2)        \
-      TUTTI_MOVE_NT(U, 3)        \
-    }                            \
-    break;
-  switch (L.unroll) {
-    TUTTI_MOVE_CASE(1)
-    TUTTI_MOVE_CASE(2)
-    TUTTI_MOVE_CASE(4)
-    TUTTI_MOVE_CASE(8)
-    default:
-      return hipErrorInvalidValue;
-  }
-#undef TUTTI_MOVE_NT
-#undef TUTTI_MOVE_CASE
-  return hipGetLastError();
+  return with_shape(L, [&](auto sh) {
+    using S = decltype(sh);
+    hipLaunchKernelGGL((k_move<DIR, HND, S::U, S::NT, S::WG>), dim3(L.grid), dim3(S::WG), lds, s, m, ext, n_req);
+    return hipGetLastError();
+  });
 }
 
 template <int DIR, bool HND>
 hipError_t launch_layer(const Launch &L, uint64_t entry_quarters, uint32_t lds, hipStream_t s, const MoveArgs &m,
-                          const SqeArgs &q, const LayoutArgs &a) {
+                        const SqeArgs &q, const LayoutArgs &a) {
   uint32_t n_wgs = 0;
   const Roles w = make_roles(L, entry_quarters, &n_wgs);
-  const dim3 grid(n_wgs);
-#define TUTTI_RESTORE_NT(U, NT)                                                                                   \
-  case NT:                                                                                                        \
-    if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kWgThreads>), grid, dim3(kWgThreads), lds, s, m, q, a, w);      \
-    else                                                                                                          \
-      hipLaunchKernelGGL((k_layer<DIR, HND, U, NT, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), lds, s, m, q, \
-                         a, w);                                                                                   \
-    break;
-#define TUTTI_RESTORE_CASE(U)    \
-  case U:                        \
-    switch (L.nontemporal) {     \
-      TUTTI_RESTORE_NT(U, 0)     \
-      TUTTI_RESTORE_NT(U, 1)     \
-      TUTTI_RESTORE_NT(U, 2)     \
-      TUTTI_RESTORE_NT(U, 3)     \
-    }                            \
-    break;
-  switch (L.unroll) {
-    TUTTI_RESTORE_CASE(1)
-    TUTTI_RESTORE_CASE(2)
-    TUTTI_RESTORE_CASE(4)
-    TUTTI_RESTORE_CASE(8)
-    default:
-      return hipErrorInvalidValue;
-  }
-#undef TUTTI_RESTORE_NT
-#undef TUTTI_RESTORE_CASE
-  return hipGetLastError();
+  return with_shape(L, [&](auto sh) {
+    using S = decltype(sh);
+    hipLaunchKernelGGL((k_layer<DIR, HND, S::U, S::NT, S::WG>), dim3(n_wgs), dim3(S::WG), lds, s, m, q, a, w);
+    return hipGetLastError();
+  });
 }
 
 template <int DIR>
@@ -786,25 +788,13 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
   uint32_t n_wgs = 0;
   const Roles w = make_roles(L, 4 * n_ctx, &n_wgs);
   const uint32_t lds = req_lds_bytes(n_req);
-#define TUTTI_RING_CASE(U)                                                                                        \
-  case U:                                                                                                         \
-    if (L.wg_threads == kWgThreads)                                                                               \
-      hipLaunchKernelGGL((k_layer_ring<DIR, U, kWgThreads>), dim3(n_wgs), dim3(kWgThreads), lds, s, m, q, d, g, f, \
-                         a, w);                                                                                   \
-    else                                                                                                          \
-      hipLaunchKernelGGL((k_layer_ring<DIR, U, kBudgetWgThreads>), dim3(n_wgs), dim3(kBudgetWgThreads), lds, s, m, \
-                         q, d, g, f, a, w);                                                                       \
-    break;
-  switch (L.unroll) {
-    TUTTI_RING_CASE(1)
-    TUTTI_RING_CASE(2)
-    TUTTI_RING_CASE(4)
-    TUTTI_RING_CASE(8)
-    default:
-      return TUTTI_EINVAL;
-  }
-#undef TUTTI_RING_CASE
-  hipError_t e = hipGetLastError();
+  Launch R = L;
+  R.nontemporal = 3;  // the ring kernels have one cache policy
+  hipError_t e = with_shape(R, [&](auto sh) {
+    using S = decltype(sh);
+    hipLaunchKernelGGL((k_layer_ring<DIR, S::U, S::WG>), dim3(n_wgs), dim3(S::WG), lds, s, m, q, d, g, f, a, w);
+    return hipGetLastError();
+  });
   if (e != hipSuccess) return hip_fail(e);
   hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, s, g);
   e = hipGetLastError();
@@ -858,6 +848,9 @@ int tutti_table_validate(uint32_t num_blocks, const uint32_t *d_block_table, uin
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+#ifdef TUTTI_BENCH_BUILD
+// ---- measurement aids (include/tutti_bench.h): ceilings, floors and the tuning knobs
+
 int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t cu_budget, void *stream) {
   if (!d_dst || !d_src || !aligned16(d_dst) || !aligned16(d_src) || bytes % 16 != 0) return TUTTI_EINVAL;
   if (bytes == 0) return TUTTI_OK;
@@ -870,34 +863,11 @@ int tutti_copy_baseline(void *d_dst, const void *d_src, uint64_t bytes, uint32_t
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char *dst = static_cast<unsigned char *>(d_dst);
   const unsigned char *src = static_cast<const unsigned char *>(d_src);
-#define TUTTI_COPY_NT(U, NT)                                                                                    \
-  case NT:                                                                                                      \
-    if (L.wg_threads == kWgThreads)                                                                             \
-      hipLaunchKernelGGL((k_copy<U, NT, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, dst, src, bytes);   \
-    else                                                                                                        \
-      hipLaunchKernelGGL((k_copy<U, NT, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, dst,    \
-                         src, bytes);                                                                           \
-    break;
-#define TUTTI_COPY_CASE(U)       \
-  case U:                        \
-    switch (L.nontemporal) {     \
-      TUTTI_COPY_NT(U, 0)        \
-      TUTTI_COPY_NT(U, 1)        \
-      TUTTI_COPY_NT(U, 2)        \
-      TUTTI_COPY_NT(U, 3)        \
-    }                            \
-    break;
-  switch (L.unroll) {
-    TUTTI_COPY_CASE(1)
-    TUTTI_COPY_CASE(2)
-    TUTTI_COPY_CASE(4)
-    TUTTI_COPY_CASE(8)
-    default:
-      return TUTTI_EINVAL;
-  }
-#undef TUTTI_COPY_NT
-#undef TUTTI_COPY_CASE
-  hipError_t e = hipGetLastError();
+  const hipError_t e = with_shape(L, [&](auto sh) {
+    using S = decltype(sh);
+    hipLaunchKernelGGL((k_copy<S::U, S::NT, S::WG>), dim3(L.grid), dim3(S::WG), 0, s, dst, src, bytes);
+    return hipGetLastError();
+  });
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
@@ -934,26 +904,95 @@ int tutti_stream_baseline(void *d_buf, uint64_t bytes, uint32_t write, uint32_t 
 }
 
 int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_contig, uint64_t bytes,
-                           const uint32_t *d_perm, uint32_t gran, uint32_t scatter_writes, uint32_t cu_budget,
-                           void *stream) {
+                           const uint32_t *d_perm, uint32_t gran, uint32_t scatter_writes, uint32_t shape,
+                           uint32_t cu_budget, void *stream) {
   if (!d_scattered || !d_contig || !d_perm || !aligned16(d_scattered) || !aligned16(d_contig)) return TUTTI_EINVAL;
   if (gran == 0 || gran % 4096 != 0 || bytes % gran != 0) return TUTTI_EINVAL;
+  if (shape > TUTTI_SCATTER_SHAPE_MAX) return TUTTI_EINVAL;
   if (bytes == 0) return TUTTI_OK;
-  Launch L;
-  int rc = plan_launch(cu_budget, bytes / 4096, &L);
-  if (rc) return rc;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char *sc = static_cast<unsigned char *>(d_scattered);
   unsigned char *ct = static_cast<unsigned char *>(d_contig);
-  if (L.wg_threads == kWgThreads)
-    hipLaunchKernelGGL((k_scatter<4, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes,
-                       d_perm, gran, scatter_writes);
-  else
-    hipLaunchKernelGGL((k_scatter<4, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, sc, span_bytes, ct,
-                       bytes, d_perm, gran, scatter_writes);
+  const uint32_t to = scatter_writes ? 1u : 0u;
+  if (shape == TUTTI_SCATTER_WAVE_SLICE) {  // the product's shape: a wavefront per 4 KiB, 256-thread workgroups
+    Launch L;
+    int rc = plan_launch(cu_budget, bytes / 4096, &L);
+    if (rc) return rc;
+    if (L.wg_threads == kWgThreads)
+      hipLaunchKernelGGL((k_scatter<4, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes,
+                         d_perm, gran, to);
+    else
+      hipLaunchKernelGGL((k_scatter<4, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, sc, span_bytes,
+                         ct, bytes, d_perm, gran, to);
+  } else {
+    if (cu_budget != 0) return TUTTI_EINVAL;  // the other shapes are whole-GPU launches
+    const uint64_t pieces = bytes / gran;
+    const uint64_t cap = static_cast<uint64_t>(cus) * 8;
+    switch (shape) {
+      case TUTTI_SCATTER_WAVE_SLICE_1024: {
+        const uint64_t need = (bytes / 4096 + 15) / 16;
+        const uint64_t lim = static_cast<uint64_t>(cus) * 2;
+        hipLaunchKernelGGL((k_scatter<4, kBudgetWgThreads>), dim3(static_cast<uint32_t>(need < lim ? need : lim)),
+                           dim3(kBudgetWgThreads), 0, s, sc, span_bytes, ct, bytes, d_perm, gran, to);
+        break;
+      }
+      case TUTTI_SCATTER_WAVE_PIECE: {
+        const uint64_t need = (pieces + 3) / 4;
+        hipLaunchKernelGGL((k_scatter_piece<false, 3>), dim3(static_cast<uint32_t>(need < cap ? need : cap)),
+                           dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes, d_perm, gran, to);
+        break;
+      }
+      case TUTTI_SCATTER_WG_PIECE:
+        hipLaunchKernelGGL((k_scatter_piece<true, 3>), dim3(static_cast<uint32_t>(pieces < cap ? pieces : cap)),
+                           dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes, d_perm, gran, to);
+        break;
+      case TUTTI_SCATTER_WG_PIECE_PLAIN:
+        hipLaunchKernelGGL((k_scatter_piece<true, 0>), dim3(static_cast<uint32_t>(pieces < cap ? pieces : cap)),
+                           dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes, d_perm, gran, to);
+        break;
+      case TUTTI_SCATTER_WG_PIECE_NT_LOADS:
+        hipLaunchKernelGGL((k_scatter_piece<true, 1>), dim3(static_cast<uint32_t>(pieces < cap ? pieces : cap)),
+                           dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes, d_perm, gran, to);
+        break;
+      case TUTTI_SCATTER_WG_PIECE_NT_STORES:
+        hipLaunchKernelGGL((k_scatter_piece<true, 2>), dim3(static_cast<uint32_t>(pieces < cap ? pieces : cap)),
+                           dim3(kWgThreads), 0, s, sc, span_bytes, ct, bytes, d_perm, gran, to);
+        break;
+      default:
+        return TUTTI_EINVAL;
+    }
+  }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
+
+int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll) {
+  if (unroll != 0 && unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return TUTTI_EINVAL;
+  if (wgs_per_cu > 1024) return TUTTI_ERANGE;
+  t_tuning.wgs_per_cu = wgs_per_cu;
+  t_tuning.unroll = unroll;
+  return TUTTI_OK;
+}
+
+int tutti_set_hnd_mode(uint32_t mode) {
+  if (mode > 2u) return TUTTI_EINVAL;
+  t_tuning.hnd_mode = mode;
+  return TUTTI_OK;
+}
+
+int tutti_set_xcd_mapping(uint32_t contiguous) {
+  t_tuning.xcd_contiguous = contiguous ? 1u : 0u;
+  return TUTTI_OK;
+}
+
+int tutti_set_nontemporal(uint32_t mask) {
+  if (mask > 3u) return TUTTI_EINVAL;
+  t_tuning.nontemporal = mask;
+  return TUTTI_OK;
+}
+#endif  // TUTTI_BENCH_BUILD
 
 int tutti_io_domain_create(uint32_t n_cus, void **stream) {
   if (!stream) return TUTTI_EINVAL;
@@ -1083,35 +1122,6 @@ int tutti_abi_describe(uint32_t *out, uint32_t cap) {
   out[i++] = offsetof(tutti_filestore, first_file_id);
   out[i++] = offsetof(tutti_filestore, n_files);
   return static_cast<int>(i);
-}
-
-int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll) {
-  if (unroll != 0 && unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return TUTTI_EINVAL;
-  if (wgs_per_cu > 1024) return TUTTI_ERANGE;
-  g_wgs_per_cu.store(wgs_per_cu, std::memory_order_relaxed);
-  g_unroll.store(unroll, std::memory_order_relaxed);
-  return TUTTI_OK;
-}
-
-// Head-major pools: 0 = library chooses (through LDS when a row is shorter than 128 bytes and the
-// shape allows it), 1 = always the direct 16-byte permuted copy, 2 = through LDS whenever the shape allows.
-int tutti_set_hnd_mode(uint32_t mode) {
-  if (mode > 2u) return TUTTI_EINVAL;
-  g_hnd_mode.store(mode, std::memory_order_relaxed);
-  return TUTTI_OK;
-}
-
-// Experiment switch: 1 = every XCD takes one contiguous eighth of the items instead of every eighth 16 KiB.
-int tutti_set_xcd_mapping(uint32_t contiguous) {
-  g_xcd_contiguous.store(contiguous ? 1u : 0u, std::memory_order_relaxed);
-  return TUTTI_OK;
-}
-
-// Experiment switch: bit 0 = non-temporal loads, bit 1 = non-temporal stores in the copy loops.
-int tutti_set_nontemporal(uint32_t mask) {
-  if (mask > 3u) return TUTTI_EINVAL;
-  g_nontemporal.store(mask, std::memory_order_relaxed);
-  return TUTTI_OK;
 }
 
 }  // extern "C"

@@ -12,9 +12,8 @@
 //   k_ring_init, k_iocb_fill, k_issue_io, k_complete, k_cq_check
 //                   SQ/CQ rings: IOCBs filled by the GPU, the entry-driven I/O kernel, completions
 //   k_layer_ring    one layer through the rings in one launch: scan + IOCB fill + the blocks' I/O
-//   k_copy          plain contiguous copy with the same access shape (measurement ceiling)
-//   k_stream        read-only or write-only stream with the same access shape (per-CU and chip limits)
-//   k_scatter       the copy with one side permuted at a given granularity (what the pattern itself costs)
+//   k_copy, k_stream, k_scatter, k_scatter_piece   (measurement build only) plain copy, one-direction streams and
+//                   copies with one side permuted at a given granularity: ceilings and floors for the above
 //   k_table_validate  debugging aid: ids in range and no id twice, by all-pairs comparison (no workspace)
 //
 // Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
@@ -1420,6 +1419,9 @@ __global__ __launch_bounds__(kWgThreads) void k_table_validate(const uint32_t *_
   if (found && status) atomicOr(status, found);
 }
 
+#ifdef TUTTI_BENCH_BUILD
+// ---- measurement kernels (libtutti_bench.so only)
+
 // Plain contiguous copy with the access shape of move_items: the ceiling pack / unpack can reach.
 template <int U, int NT, int WG>
 __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_copy(unsigned char *__restrict__ dst,
@@ -1532,5 +1534,39 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_scatter(unsig
     for (int u = 0; u < U; ++u) st16<3>(dst + u * (kWave * 16u), buf[u]);
   }
 }
+
+// The same scattered copy with the work dealt differently: a whole piece per wavefront (PER_WG = false) or per
+// workgroup (true), walked in 4 KiB steps, with any of the four cache policies.  Whether another way of dealing
+// out the same bytes would suit the memory system better than the product's wavefront-per-4-KiB.
+template <bool PER_WG, int NT>
+__global__ __launch_bounds__(kWgThreads, 8) void k_scatter_piece(unsigned char *__restrict__ scattered, uint64_t span_bytes,
+                                                                  unsigned char *__restrict__ contig, uint64_t bytes,
+                                                                  const uint32_t *__restrict__ perm, uint32_t gran,
+                                                                  uint32_t to_scattered) {
+  constexpr uint32_t kStep = kWave * 16u * 4u;  // 4 KiB per wavefront and step; gran is a multiple of it
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave_in_wg = rfl(threadIdx.x / kWave);
+  const uint32_t waves = blockDim.x / kWave;
+  const uint64_t n_pieces = bytes / gran;
+  const uint64_t first = PER_WG ? blockIdx.x : static_cast<uint64_t>(blockIdx.x) * waves + wave_in_wg;
+  const uint64_t stride = PER_WG ? gridDim.x : static_cast<uint64_t>(gridDim.x) * waves;
+  for (uint64_t piece = first; piece < n_pieces; piece += stride) {
+    const uint64_t so = static_cast<uint64_t>(rfl(perm[piece])) * gran;
+    if (so + gran > span_bytes) continue;
+    for (uint32_t off = PER_WG ? wave_in_wg * kStep : 0u; off < gran; off += PER_WG ? waves * kStep : kStep) {
+      unsigned char *sp = scattered + so + off + lane * 16u;
+      unsigned char *cp = contig + piece * gran + off + lane * 16u;
+      const unsigned char *src = to_scattered ? cp : sp;
+      unsigned char *dst = to_scattered ? sp : cp;
+      u32x4 buf[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) buf[u] = ld16<NT>(src + u * (kWave * 16u));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) st16<NT>(dst + u * (kWave * 16u), buf[u]);
+    }
+  }
+}
+
+#endif  // TUTTI_BENCH_BUILD
 
 }  // namespace tutti

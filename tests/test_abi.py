@@ -11,13 +11,28 @@ from paper_2605_03375_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)          # comments mention calls of other headers
+    return sorted(set(re.findall(r"\b(tutti_[a-z_0-9]+)\s*\(", header)))
+
+
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "tutti.h")).read()
-    declared = sorted(set(re.findall(r"\b(tutti_[a-z_0-9]+)\s*\(", header)))
-    assert set(declared) == set(B.EXPORTS)
-    L = B.lib()
+    """libtutti.so exports exactly what include/tutti.h declares; libtutti_bench.so (the same sources with the
+    measurement aids compiled in) exports that plus what include/tutti_bench.h declares."""
+    import subprocess
+    declared = _declared("tutti.h")
+    bench_declared = _declared("tutti_bench.h")
+    assert set(declared) == set(B.EXPORTS) and set(bench_declared) == set(B.BENCH_EXPORTS)
+    for path, names in ((B.LIB_PATH, declared), (B.BENCH_LIB_PATH, declared + bench_declared)):
+        out = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+        exported = sorted(line.split()[-1] for line in out.splitlines() if " T tutti_" in line)
+        assert exported == sorted(names), path
+    L, LB = B.product_lib(), B.bench_lib()
     for name in declared:
-        assert getattr(L, name) is not None
+        assert getattr(L, name) is not None and getattr(LB, name) is not None
+    for name in bench_declared:
+        assert getattr(LB, name) is not None and not hasattr(L, name)
     for name in ("tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_build", "tutti_layer_restore",
                  "tutti_layer_save", "tutti_sgl_table_build", "tutti_sqe_build_direct", "tutti_ring_init", "tutti_iocb_fill_direct",
                  "tutti_issue_io", "tutti_wait_cqe"):

@@ -20,15 +20,18 @@ def H():
     return gpu_harness
 
 
-@pytest.fixture(autouse=True)
-def _default_tuning():
-    B.tutti_set_tuning(0, 0)
-    B.tutti_set_nontemporal(3)
-    B.tutti_set_hnd_mode(0)
+@pytest.fixture
+def knobs():
+    """For tests of the measurement library: the ordinary entry points go through libtutti_bench.so (the same
+    sources plus tuning knobs and every launch shape) while the test runs; everything is put back afterwards.
+    All other tests run the product library, which has no knobs."""
+    B.use_bench_library(True)
     yield
     B.tutti_set_tuning(0, 0)
     B.tutti_set_nontemporal(3)
     B.tutti_set_hnd_mode(0)
+    B.tutti_set_xcd_mapping(0)
+    B.use_bench_library(False)
 
 
 def say(*a):
@@ -75,7 +78,7 @@ def test_ragged_shapes(orc, H, shape, layout):
 
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8])
 @pytest.mark.parametrize("nt", [0, 1, 2, 3])
-def test_launch_tuning_does_not_change_results(orc, H, unroll, nt):
+def test_launch_tuning_does_not_change_results(orc, H, knobs, unroll, nt):
     say("tuning", unroll, nt)
     B.tutti_set_tuning(3, unroll)
     B.tutti_set_nontemporal(nt)
@@ -103,10 +106,12 @@ HND_SHAPES = [
 
 @pytest.mark.parametrize("mode", [0, 1, 2], ids=["auto", "direct", "lds"])
 @pytest.mark.parametrize("shape", HND_SHAPES, ids=[f"T{t}h{h}d{d}e{e}" for t, h, d, e, *_ in HND_SHAPES])
-def test_head_major_paths(orc, H, shape, mode):
+def test_head_major_paths(orc, H, request, shape, mode):
     T, h, d, e, N, n_blocks, C = shape
     say("hnd", shape, "mode", mode)
-    B.tutti_set_hnd_mode(mode)
+    if mode:      # forcing a path is a knob of the measurement library; "auto" is the product choosing by shape
+        request.getfixturevalue("knobs")
+        B.tutti_set_hnd_mode(mode)
     rng = np.random.default_rng(500 + T + h)
     c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=n_blocks, table=rng.permutation(N)[: sum(n_blocks)], chunk=C, L=2,
                     layout=1, seed=h, name=f"hnd{shape}m{mode}")
@@ -117,7 +122,6 @@ def test_head_major_paths(orc, H, shape, mode):
 def test_head_major_lds_edge_cases(orc, H):
     """Bad ids, a small staging buffer and the 2048-request limit through the LDS-staged path."""
     say("hnd lds edges")
-    B.tutti_set_hnd_mode(2)
     table = np.array([3, 999, 5, 16, 7, 1], np.uint32)
     c = H.LayerCase(T=16, h=32, d=32, e=2, N=16, n_blocks=[4, 2], table=table, layout=1, name="hnd_bad_ids")
     ext, tot, o_ext, o_tot = H.check_layout(orc, c)
@@ -407,7 +411,7 @@ import os as _os
 
 
 @pytest.mark.parametrize("seed", range(int(_os.environ.get("TUTTI_FUZZ_SEEDS", "48"))))
-def test_random_shapes(orc, H, seed):
+def test_random_shapes(orc, H, request, seed):
     """Seeded random geometry, request mix, layout, stride, alignment, chunking and launch shape."""
     rng = np.random.default_rng(9000 + seed)
     e = int(rng.choice([1, 2, 4]))
@@ -426,10 +430,14 @@ def test_random_shapes(orc, H, seed):
     unroll = int(rng.choice([1, 2, 4, 8]))
     wgs = int(rng.choice([1, 2, 8]))
     budget = int(rng.choice([0, 0, 1, 5]))
+    hnd_mode = int(rng.integers(0, 3))
+    tuned = bool(seed % 3)        # two seeds in three also vary the launch shape, through the measurement library
     say("random", dict(seed=seed, T=T, h=h, d=d, e=e, bb=bb, A=A, C=C, pad=pad, layout=layout, R=R, blocks=int(nb.sum()),
-                       N=N, unroll=unroll, wgs=wgs, budget=budget))
-    B.tutti_set_tuning(wgs, unroll)
-    B.tutti_set_hnd_mode(int(rng.integers(0, 3)))
+                       N=N, budget=budget, **(dict(unroll=unroll, wgs=wgs, hnd_mode=hnd_mode) if tuned else {})))
+    if tuned:
+        request.getfixturevalue("knobs")
+        B.tutti_set_tuning(wgs, unroll)
+        B.tutti_set_hnd_mode(hnd_mode)
     c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=nb, table=rng.permutation(N)[: int(nb.sum())], align=A, chunk=C,
                     L=int(rng.integers(1, 90)), layout=layout, pad=pad, seed=seed, name=f"random{seed}")
     H.check_everything(orc, c, cu_budget=budget)
@@ -485,7 +493,7 @@ def test_rings_cfg2_layer(orc, H):
         assert H.check_rings(orc, c, layer=31, opcode=op, depth=4, first_slot=3, n_slots=2) == 2
 
 
-def test_ring_layer_small(orc, H):
+def test_ring_layer_small(orc, H, request):
     """retrieve_layer / store_layer in one call against the oracle's layout + fill + issue sequence."""
     say("ring layer: small")
     rng = np.random.default_rng(43)
@@ -524,13 +532,13 @@ def test_ring_layer_small(orc, H):
             H.check_ring_layer(orc, c, layer=1, write=write, depth=3, first_slot=2, n_slots=1, cu_budget=4)
     c = H.LayerCase(T=3, h=2, d=256, e=2, N=40, n_blocks=[11, 5], table=rng.permutation(40)[:16], align=1024,
                     chunk=3072, L=2, name="ringlayer_3K")
-    try:
-        for u in (1, 2, 8):
-            B.tutti_set_tuning(0, u)
-            for write in (False, True):
-                H.check_ring_layer(orc, c, layer=1, write=write, depth=2, first_slot=0, n_slots=1)
-    finally:
-        B.tutti_set_tuning(0, 0)
+    for write in (False, True):
+        H.check_ring_layer(orc, c, layer=1, write=write, depth=2, first_slot=0, n_slots=1)
+    request.getfixturevalue("knobs")
+    for u in (1, 2, 8):
+        B.tutti_set_tuning(0, u)
+        for write in (False, True):
+            H.check_ring_layer(orc, c, layer=1, write=write, depth=2, first_slot=0, n_slots=1)
 
 
 def test_ring_cq_in_pinned_host_memory_polled_by_cpu(orc, H):
@@ -1167,9 +1175,10 @@ def test_scatter_baseline(H):
     g.manual_seed(3)
     contig = torch.randint(0, 256, (n * gran,), dtype=torch.uint8, device=H.DEV, generator=g)
     scat = torch.zeros(n_slots * gran, dtype=torch.uint8, device=H.DEV)
-    for budget in (0, 2):
+    for shape, budget in [("wave_slice", 0), ("wave_slice", 2)] + [(s, 0) for s in B.SCATTER_SHAPES if s != "wave_slice"]:
+        say("  shape", shape, "budget", budget)
         scat.zero_()
-        B.tutti_scatter_baseline(scat, scat.numel(), contig, contig.numel(), d_perm, gran, 1, budget)
+        B.tutti_scatter_baseline(scat, scat.numel(), contig, contig.numel(), d_perm, gran, 1, shape, budget)
         torch.cuda.synchronize()
         want = np.zeros((n_slots, gran), np.uint8)
         src = contig.cpu().numpy().reshape(n, gran)
@@ -1178,7 +1187,7 @@ def test_scatter_baseline(H):
                 want[p] = src[i]
         assert np.array_equal(scat.cpu().numpy().reshape(n_slots, gran), want)
         back = torch.full_like(contig, 7)
-        B.tutti_scatter_baseline(scat, scat.numel(), back, back.numel(), d_perm, gran, 0, budget)
+        B.tutti_scatter_baseline(scat, scat.numel(), back, back.numel(), d_perm, gran, 0, shape, budget)
         torch.cuda.synchronize()
         exp = src.copy()
         exp[5] = 7
