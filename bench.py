@@ -3,18 +3,20 @@
 
 A step is one pass of the whole path over the Llama-3-8B-shaped 32K-token workload (config 2):
 for every layer, save (tutti_layer_save: extents + WRITE entries + pack in one launch), then for every
-layer, restore (tutti_layer_restore: extents + READ entries + unpack in one launch).  The separate calls
-(tutti_obj_layout, tutti_obj_pack, tutti_sqe_build) are timed in an extra leg.  Every layer
+layer, restore (tutti_layer_restore: extents + READ entries + unpack in one launch).  Every layer
 has its own K/V planes and its own staging buffer, so each launch touches memory no earlier launch
 left in the 256 MB Infinity Cache.  Inputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
-  value            payload GB/s of the whole step (bytes packed + bytes restored, 1 GB = 1e9 B)
+  value            payload GB/s of the per-layer RESTORE of config 2 (the metric's quantity; 1 GB = 1e9 B)
   roofline         the dominant kernel (k_layer<unpack>: the fused restore) against the 8 TB/s HBM peak,
                    timed with events on the launch stream inside the timed region
-  cpu_baseline     the CPU oracle, as it stands, on one layer of the same workload
-Extra legs (same JSON line): restore / pack alone, a plain-copy ceiling, entries built per second,
-and with --corun the CU-budget sweep beside a bf16 4096^3 GEMM (config 5).
+  cpu_baseline     the CPU oracle, as it stands, on a bounded sample of configs 1-4 (1 thread and every core
+                   of the affinity mask)
+Further legs of the same line (all on by default; --quick leaves them out): the save, the copy kernels alone,
+copy ceilings and the scattered-copy floor, entries built per second, configs 3 and 4 at their real pool sizes,
+config 5 (CU budgets and a CU-masked I/O domain beside two GEMMs) with the slack table it yields, the ring
+path, and a sweep of the prefix length from 1K to 128K tokens (eager launches and a HIP-graph replay).
 """
 import argparse
 import json
@@ -58,20 +60,23 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=0, help="layers resident (0 = all 32 if memory allows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="config 2's step only: none of the further legs")
     ap.add_argument("--no-extra", action="store_true", help="skip the copy-ceiling / entry-rate legs")
-    ap.add_argument("--corun", action="store_true", help="also run the CU-budget sweep beside a GEMM (config 5)")
+    ap.add_argument("--no-corun", action="store_true", help="skip config 5 (CU budgets beside a GEMM) and the slack table")
+    ap.add_argument("--no-rings", action="store_true", help="skip the ring path (IOCBs, issue_io, retrieve/store_layer)")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip configs 3 and 4")
+    ap.add_argument("--no-length-sweep", action="store_true", help="skip the 1K..128K-token prefix-length sweep")
     ap.add_argument("--scatter-sweep", action="store_true",
-                    help="also sweep the granularity of tutti_scatter_baseline (4 KiB .. 4 MiB, random and sorted)")
-    ap.add_argument("--rings", action="store_true",
-                    help="also time the entry-driven path: fill IOCBs on the GPU, then tutti_issue_io (no staging copy)")
+                    help="also sweep the granularity, the order and the launch shape of tutti_scatter_baseline")
     ap.add_argument("--pinned-stage", action="store_true",
                     help="also time the restore with the staging buffer in pinned host memory (host-link bound)")
-    ap.add_argument("--other-configs", action="store_true",
-                    help="also time the per-layer restore of configs 3 and 4 (frees config 2's pool first)")
+    ap.add_argument("--write-lut", default="", help="also write the slack table (JSON) to this path")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--plain-loads", action="store_true", help="disable non-temporal loads/stores")
     args = ap.parse_args()
+    if args.quick:
+        args.no_extra = args.no_corun = args.no_rings = args.no_other_configs = args.no_length_sweep = True
     if args.gpus != 1:
         print("bench.py measures one GPU: this path has no collective and no cross-GPU step; "
               "run it with --gpus 1 (each GPU of a larger job would run exactly this on its own shard)",
@@ -149,11 +154,11 @@ def main():
             B.tutti_sqe_build(pools[l], cfg, ext_w[l], 1, d_fid, l, B.OP_WRITE, stages[l].data_ptr(), sgl_id,
                               wsqe[l], n_sqe_layer, status, stream)
 
-    def restore_layers(budget=0):
+    def restore_layers(budget=0, on=None):
         for l in range(L):
             B.tutti_layer_restore(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload_layer,
                                   stages[l].data_ptr(), sgl_id, ext_r[l], tot_r[l], rsqe[l], n_sqe_layer, budget,
-                                  status, stream)
+                                  status, stream if on is None else on)
 
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731  (events of torch's current stream = launch stream)
 
@@ -185,9 +190,8 @@ def main():
     rest_ms = [b.elapsed_time(c) for _, b, c in marks]
     assert int(status.item()) == 0, f"device status word {int(status.item())}: a block or capacity check tripped"
 
-    step_payload = 2 * L * payload_layer                 # packed + restored
-    value = step_payload / (ms_per_step * 1e-3) / 1e9
     restore_us = float(np.mean(rest_ms)) * 1e3 / L       # average restore launch, launch gaps included
+    value = payload_layer / (restore_us * 1e-6) / 1e9    # the metric: payload GB/s of the per-layer restore
     save_us = float(np.mean(save_ms)) * 1e3 / L
     # algorithmic bytes of one restore launch: payload read + payload written, the block table,
     # the request counts and file ids, the entries and extents it writes
@@ -195,7 +199,8 @@ def main():
     achieved = restore_alg_bytes / (restore_us * 1e-6) / 1e9
 
     out = {
-        "metric": "per-layer KV save+restore payload GB/s, Llama-3-8B shape, 32K-token prefix (one launch per layer each way)",
+        "metric": "per-layer KV restore payload GB/s (and % of HBM peak in roofline.frac), Llama-3-8B shape, 32K-token "
+                  "prefix, one launch per layer; the step also saves every layer (see save); SQEs built/sec in sqe",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
@@ -204,9 +209,13 @@ def main():
                    "layers_resident": L, "layers_model": s.num_layers, "payload_bytes_per_layer": payload_layer,
                    "step": "per layer: layer_save (extents + WRITE entries + pack); then per layer: layer_restore "
                            "(extents + READ entries + unpack); one launch each",
+                   "library": "libtutti_bench.so (tuned launch shape: an experiment)" if tuned else "libtutti.so",
                    "wgs_per_cu": args.wgs_per_cu, "unroll": args.unroll, "nontemporal": not args.plain_loads},
         "roofline": {"bound": "hbm", "kernel": "k_layer<unpack> (tutti_layer_restore)", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": read_traffic_note(),
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs recorded in "
+                                       "profiles/k_restore_llama8b_32k_pmc.txt, not measured in this run",
+                     "north_star_bar": 0.70, "bar_met": bool(achieved / HBM_PEAK_GBPS >= 0.70),
                      "algorithmic_bytes_per_launch": restore_alg_bytes, "avg_launch_us": round(restore_us, 2)},
         "restore": {"us_per_layer": round(restore_us, 2),
                     "payload_GBps": round(payload_layer / (restore_us * 1e-6) / 1e9, 1),
@@ -263,30 +272,49 @@ def main():
         out["sqe"]["direct_to_block"] = direct_rate(torch, B, W, dev)
         out["sqe"]["direct_to_block_2M_entries"] = big_entry_rate(torch, B, dev)
         log(f"[bench] copy ceiling {out['copy_ceiling']}; entries {out['sqe']}")
-    if args.corun:
+    cpu2 = None
+    if not args.no_cpu_baseline:   # needs layer 0 as saved and restored: before the legs below overwrite the pool
+        cpu2 = cpu_baseline(torch, W, w, planes[0], pristine, stages[0], geom, payload_layer)
+    if not args.no_corun:
         out["per_cu_limits"] = per_cu_limits(torch, B, dev)
-        out["corun"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev)
-        # a GEMM with many more tiles than CUs, for contrast with the 4096^3 one (256 tiles on 256 CUs)
-        out["corun_gemm8192"] = corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=12, reps=2,
-                                            gemm_n=8192, budgets=(8, 32, 0))
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(torch, W, w, planes[0], pristine, stages[0], geom, payload_layer)
+        out["corun"] = {
+            "note": "config 5: the restore of config 2 on one stream beside a bf16 GEMM looping on another, each "
+                    "timed while the other outlasts it; budget = cu_budget argument, domain = a CU-masked stream "
+                    "from tutti_io_domain_create with cu_budget 0",
+            "gemm_4096x4096x4096 (256 tiles of 256x256: one per CU)":
+                corun_sweep(torch, B, restore_layers, L, payload_layer, dev),
+            "gemm_4096x5120x4096 (320 tiles: not a multiple of the CU count)":
+                corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_n=(4096, 5120, 4096)),
+            "gemm_8192x8192x8192 (1024 tiles)":
+                corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=12, reps=2,
+                            gemm_n=(8192, 8192, 8192), budgets=(8, 32, 0), domains=(32,)),
+        }
+        out["slack_lut"] = slack_lut(torch, B, w, pools, planes, cfg, d_tab, d_fid, dev)
+        if args.write_lut:
+            with open(args.write_lut, "w") as f:
+                json.dump(out["slack_lut"], f, indent=1)
+    if not args.no_rings:
+        out["rings_direct_to_block"] = ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid,
+                                                payload_layer, dev)
+    if not args.no_length_sweep:
+        out["length_sweep"] = length_sweep(torch, B, W, pools, cfg, dev)
     if args.scatter_sweep:
         out["scatter_sweep"] = scatter_sweep(torch, B, stages, payload_layer, dev)
         out["scatter_orders_32KiB"] = scatter_orders(torch, B, stages, payload_layer, dev)
-    if args.rings:
-        out["rings_direct_to_block"] = ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid,
-                                                payload_layer, dev)
+        out["scatter_shapes_32KiB"] = scatter_shapes(torch, B, w, stages, payload_layer, dev)
     if args.pinned_stage:
         out["pinned_host_stage"] = pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload_layer,
                                               n_sqe_layer, dev)
-    if args.other_configs:
+    if not args.no_other_configs:
         del pools, planes, stages, restore_layers, save_layers, save_layers_unfused
         torch.cuda.empty_cache()
         out["other_configs"] = {
             "config3_batch64_zipf": restore_leg(torch, B, W.batch64_zipf(), dev, max_layers=8),
             "config4_llama70b_128k": restore_leg(torch, B, W.llama70b_128k(), dev, max_layers=80),
         }
+    if cpu2 is not None:
+        out["cpu_baseline"] = cpu2
+        out["cpu_baseline"]["other_configs"] = cpu_baseline_others(W)
     print(json.dumps(out), flush=True)
 
 
@@ -772,18 +800,21 @@ def per_cu_limits(torch, B, dev, nbytes=256 << 20, budgets=(8, 32, 128, 0), reps
     return res
 
 
-def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, reps=3, gemm_n=4096,
-                budgets=(8, 16, 32, 64, 0)):
-    """Config 5: restore under a CU budget on one stream while a bf16 4096^3 GEMM loops on another.
+def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, reps=3, gemm_n=(4096, 4096, 4096),
+                budgets=(8, 16, 32, 64, 0), domains=(8, 16, 32, 64)):
+    """Config 5: restore under a CU budget (or on a CU-masked stream) while a bf16 GEMM loops on another stream.
 
-    Each figure is taken under FULL overlap: to time the GEMM, a restore loop long enough to outlast it
-    is queued first on the other stream (and the other way round), and the events are checked afterwards
-    to confirm the background work was still running when the measured loop ended.
+    gemm_n = (M, N, K).  Each figure is taken under FULL overlap: to time the GEMM, a restore loop long enough
+    to outlast it is queued first on the other stream (and the other way round), and the events are checked
+    afterwards to confirm the background work was still running when the measured loop ended.
+    Rows "budget B": cu_budget = B on an ordinary stream (B workgroups of 1024 threads: bounds occupancy, not
+    placement).  Rows "domain B": cu_budget = 0 on a stream from tutti_io_domain_create(B) (the hardware
+    dispatches the launch to the first B compute units only).
     """
-    a = torch.randn(gemm_n, gemm_n, dtype=torch.bfloat16, device=dev)
-    b = torch.randn(gemm_n, gemm_n, dtype=torch.bfloat16, device=dev)
+    M, N, K = gemm_n
+    a = torch.randn(M, K, dtype=torch.bfloat16, device=dev)
+    b = torch.randn(K, N, dtype=torch.bfloat16, device=dev)
     side = torch.cuda.Stream()
-    main = torch.cuda.current_stream()
     E = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
 
     def gemm_loop(n):
@@ -795,55 +826,258 @@ def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, 
             e1.record(side)
         return e0, e1
 
-    def restore_loop(budget, trains):
+    def restore_loop(stream, budget, trains):
         e0, e1 = E(), E()
-        e0.record(main)
-        for _ in range(trains):
-            restore_layers(budget)
-        e1.record(main)
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for _ in range(trains):
+                restore_layers(budget, stream)
+            e1.record(stream)
         return e0, e1
 
     gemm_loop(10)
     torch.cuda.synchronize()
     out = {}
-    for budget in budgets:
+    rows_spec = [(f"budget {x}", x, None) for x in budgets] + [(f"domain {x}", 0, x) for x in domains]
+    for label, budget, domain in rows_spec:
+        handle = None
+        if domain is None:
+            main = torch.cuda.Stream()
+        else:
+            try:
+                handle = B.tutti_io_domain_create(domain)
+            except B.TuttiError as e:
+                out[label] = {"skipped": f"the runtime refuses the compute-unit mask: {e}"}
+                continue
+            main = torch.cuda.ExternalStream(handle)
         rows = []
         for _ in range(reps):
             g0, g1 = gemm_loop(gemm_iters)
             torch.cuda.synchronize()
             gemm_solo = g0.elapsed_time(g1) / gemm_iters                      # ms per GEMM
-            r0, r1 = restore_loop(budget, 1)
+            r0, r1 = restore_loop(main, budget, 1)
             torch.cuda.synchronize()
-            train_solo = r0.elapsed_time(r1)                                  # ms per 32-layer train
-            # (a) GEMM timed while restores run in the background for ~4x as long
-            bg_trains = max(2, int(4 * gemm_solo * gemm_iters / train_solo) + 1)
-            side.wait_stream(main)
-            r0, r1 = restore_loop(budget, bg_trains)
-            g0, g1 = gemm_loop(gemm_iters)
-            torch.cuda.synchronize()
-            gemm_co = g0.elapsed_time(g1) / gemm_iters
-            ok_a = g1.elapsed_time(r1) > 0                                    # restores ended after the GEMMs
-            # (b) restore timed while GEMMs run in the background for ~4x as long
+            train_solo = r0.elapsed_time(r1)                                  # ms per layer train
+            # (a) GEMM timed while restores run in the background for ~4x as long (12x on a second try, should the
+            # background have ended first)
+            for factor in (4, 12):
+                bg_trains = max(2, int(factor * gemm_solo * gemm_iters / train_solo) + 1)
+                r0, r1 = restore_loop(main, budget, bg_trains)
+                g0, g1 = gemm_loop(gemm_iters)
+                torch.cuda.synchronize()
+                gemm_co = g0.elapsed_time(g1) / gemm_iters
+                ok_a = g1.elapsed_time(r1) > 0                                # restores ended after the GEMMs
+                if ok_a:
+                    break
+            # (b) restore timed while GEMMs run in the background for ~4x (12x) as long
             trains = max(1, int(gemm_solo * gemm_iters / train_solo))
-            bg_gemms = int(4 * trains * train_solo / gemm_solo) + 1
-            main.wait_stream(side)
-            g0, g1 = gemm_loop(bg_gemms)
-            r0, r1 = restore_loop(budget, trains)
-            torch.cuda.synchronize()
-            train_co = r0.elapsed_time(r1) / trains
-            ok_b = r1.elapsed_time(g1) > 0
-            rows.append((gemm_solo, gemm_co, train_solo / L, train_co / L, ok_a and ok_b))
+            for factor in (4, 12):
+                bg_gemms = int(factor * trains * train_solo / gemm_solo) + 1
+                g0, g1 = gemm_loop(bg_gemms)
+                r0, r1 = restore_loop(main, budget, trains)
+                torch.cuda.synchronize()
+                train_co = r0.elapsed_time(r1) / trains
+                ok_b = r1.elapsed_time(g1) > 0
+                if ok_b:
+                    break
+            rows.append((gemm_solo, gemm_co, train_solo / L, train_co / L, ok_a, ok_b))
         gs, gc, rs, rc = (median([r[i] for r in rows]) for i in range(4))
-        out[str(budget)] = {"gemm_ms_solo": round(gs, 4), "gemm_ms_corun": round(gc, 4),
-                            "gemm_slowdown": round(gc / gs, 3),
-                            "restore_us_per_layer_solo": round(rs * 1e3, 1),
-                            "restore_us_per_layer_corun": round(rc * 1e3, 1),
-                            "restore_payload_GBps_solo": round(payload_layer / (rs * 1e-3) / 1e9, 1),
-                            "restore_payload_GBps_corun": round(payload_layer / (rc * 1e-3) / 1e9, 1),
-                            "restore_slowdown": round(rc / rs, 3),
-                            "full_overlap": all(r[4] for r in rows)}
-        log(f"[bench] corun gemm {gemm_n}^3 budget {budget}: {out[str(budget)]}")
+        out[label] = {"gemm_ms_solo": round(gs, 4), "gemm_ms_corun": round(gc, 4),
+                      "gemm_slowdown": round(gc / gs, 3),
+                      "restore_us_per_layer_solo": round(rs * 1e3, 1),
+                      "restore_us_per_layer_corun": round(rc * 1e3, 1),
+                      "restore_payload_GBps_solo": round(payload_layer / (rs * 1e-3) / 1e9, 1),
+                      "restore_payload_GBps_corun": round(payload_layer / (rc * 1e-3) / 1e9, 1),
+                      "restore_slowdown": round(rc / rs, 3),
+                      # a figure taken while the other side had already finished is not a co-run figure
+                      "gemm_figure_under_overlap": all(r[4] for r in rows),
+                      "restore_figure_under_overlap": all(r[5] for r in rows)}
+        log(f"[bench] corun gemm {M}x{N}x{K} {label}: {out[label]}")
+        if handle is not None:
+            torch.cuda.synchronize()
+            B.tutti_io_domain_destroy(handle)
     return out
+
+
+def slack_lut(torch, B, w, pools, planes, cfg, d_tab, d_fid, dev, budgets=(8, 16, 32, 64, 0), iocbs=(1, 2, 4), reps=3):
+    """The offline profile of the I/O kernels that the slack-aware scheduler looks launch sizes up in (sec. 3.3):
+    duration of tutti_retrieve_layer / tutti_store_layer for 1, 2 and 4 IOCBs (2048 contexts = 1024 blocks of K
+    and V each) under every CU budget, config 2's pool and block shape, alone on the GPU.  The rows are what
+    tutti_iocbs_for_slack / tutti_budget_for_slack take (tutti_io_profile)."""
+    s = w.shape
+    L = min(len(pools), 8)
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    rng = np.random.default_rng(w.seed + 9)
+    max_blocks = max(iocbs) * B.IOCB_SLOTS // 2
+    table = rng.permutation(s.num_blocks)[:max_blocks].astype(np.uint32)
+    d_table = torch.from_numpy(table.view(np.int32)).to(dev)
+    file_stride = 2 * L * max_blocks * bb
+    store = torch.empty(file_stride, dtype=torch.uint8, device=dev)
+    fs = B.make_filestore(store, file_stride, int(w.file_id[0]), 1)
+    depth = max(iocbs) * L
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.empty(sq_bytes, dtype=torch.uint8, device=dev)
+    cq = torch.empty(cq_bytes, dtype=torch.uint8, device=dev)
+    ring = B.make_ring(sq, cq, depth)
+    ext = torch.zeros(32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    cfg_l = B.make_cfg(cfg.align, cfg.chunk_bytes, L)
+    rows = []
+    for n_io in iocbs:
+        n_blk = n_io * B.IOCB_SLOTS // 2
+        d_n = torch.tensor([n_blk], dtype=torch.int32, device=dev)
+        for budget in budgets:
+            us = {}
+            for label, fn in (("write", B.tutti_store_layer), ("read", B.tutti_retrieve_layer)):
+                ts = []
+                for rep in range(reps + 1):
+                    B.tutti_ring_init(ring)
+                    torch.cuda.synchronize()
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    for l in range(L):
+                        fn(ring, l * n_io, n_io, pools[l], cfg_l, d_n, 1, d_table, n_blk, d_fid, l, 0, 1, fs, ext, tot,
+                           budget, status)
+                    b.record()
+                    torch.cuda.synchronize()
+                    if rep:
+                        ts.append(a.elapsed_time(b) * 1e3 / L)
+                us[label] = median(ts)
+            rows.append({"cu_budget": budget, "n_iocbs": n_io, "read_us": round(us["read"], 2),
+                         "write_us": round(us["write"], 2)})
+    assert int(status.item()) == 0
+    # what the lookups answer for a few slack windows (the runtime's question before each layer)
+    prof, n = B.make_io_profile([(r["cu_budget"], r["n_iocbs"], r["read_us"], r["write_us"]) for r in rows])
+    examples = []
+    for slack_us, budget in ((100.0, 64), (300.0, 32), (300.0, 8), (1000.0, 16)):
+        examples.append({"slack_us": slack_us, "cu_budget": budget,
+                         "read_iocbs_that_fit": B.tutti_iocbs_for_slack(prof, n, budget, B.OP_READ, slack_us),
+                         "smallest_budget_for_2_read_iocbs": B.tutti_budget_for_slack(prof, n, 2, B.OP_READ, slack_us, 64)})
+    res = {"made_by": "python bench.py --write-lut <this file>   (on one MI355X; the same table is in the bench line as slack_lut)",
+           "workload": "config 2 pool and block shape (32 KiB blocks; one IOCB = 1024 blocks of K and of V = 64 MiB)",
+           "what": "tutti_retrieve_layer (read_us) / tutti_store_layer (write_us), completion kernel included, "
+                   "microseconds per call, alone on the GPU; cu_budget 0 = whole GPU",
+           "rows": rows, "lookups": examples}
+    log(f"[bench] slack table: {res}")
+    return res
+
+
+def length_sweep(torch, B, W, pools, cfg, dev, lengths=(1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072), reps=5):
+    """Config 2's shape at prefix lengths from 1K to 128K tokens (the range of the paper's raw-bandwidth ablation,
+    sec. 4): per-layer restore and save over all resident layers, as eager launches and as one HIP-graph replay
+    of the whole layer train (which removes the host's launch cost but not the kernels' own start-up)."""
+    L = len(pools)
+    n_stage = 8
+    out = {}
+    for T in lengths:
+        w = W.llama8b_32k(tokens=T)
+        s = w.shape
+        bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+        n_tab = int(w.block_table.size)
+        payload = 2 * n_tab * bb
+        n_sqe = 2 * ((n_tab * bb + w.chunk_bytes - 1) // w.chunk_bytes)
+        stages = [torch.empty(payload, dtype=torch.uint8, device=dev) for _ in range(n_stage)]
+        d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
+        d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
+        d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
+        ext = torch.zeros(32, dtype=torch.uint8, device=dev)
+        tot = torch.zeros(2, dtype=torch.int64, device=dev)
+        sqe = torch.zeros(n_sqe * 64, dtype=torch.uint8, device=dev)
+        status = torch.zeros(1, dtype=torch.int32, device=dev)
+
+        def train(fn):
+            for l in range(L):
+                st = stages[l % n_stage]
+                fn(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, st, payload, st.data_ptr(), 1, ext, tot, sqe, n_sqe, 0,
+                   status)
+
+        row = {"blocks": n_tab, "payload_bytes_per_layer": payload}
+        for label, fn in (("restore", B.tutti_layer_restore), ("save", B.tutti_layer_save)):
+            train(fn)
+            torch.cuda.synchronize()
+            eager = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                train(fn)
+                b.record()
+                torch.cuda.synchronize()
+                eager.append(a.elapsed_time(b) * 1e3 / L)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    train(fn)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            replay = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                graph.replay()
+                b.record()
+                torch.cuda.synchronize()
+                replay.append(a.elapsed_time(b) * 1e3 / L)
+            del graph
+            us_e, us_g = median(eager), median(replay)
+            best = min(us_e, us_g)
+            pct = 100 * 2 * payload / (best * 1e-6) / 1e9 / HBM_PEAK_GBPS
+            # against the time the bytes alone would take at the rate of the largest size
+            row[label] = {"us_per_layer_eager": round(us_e, 2), "us_per_layer_graph": round(us_g, 2),
+                          "payload_GBps": round(payload / (best * 1e-6) / 1e9, 1), "pct_hbm_peak": round(pct, 2)}
+        assert int(status.item()) == 0
+        out[str(T)] = row
+        log(f"[bench] prefix {T} tokens: {row}")
+        del stages
+    # regime of each point: how much of the time is the bytes moving at the rate the longest prefix reaches
+    for label in ("restore", "save"):
+        top = max(out[str(T)][label]["payload_GBps"] for T in lengths)
+        for T in lengths:
+            r = out[str(T)][label]
+            share = r["payload_GBps"] / top
+            r["regime"] = ("bandwidth bound" if share >= 0.9 else
+                           "transition (launch start-up and tail still visible)" if share >= 0.5 else
+                           "launch-latency bound")
+    out["context"] = ("the paper's retrieve bandwidth over the same lengths is bound by its SSDs (at most 25.9 GB/s on "
+                      "its 4-SSD H100 box, sec. 4); quoted as context only")
+    return out
+
+
+def scatter_shapes(torch, B, w, stages, nbytes, dev, n_buf=6, reps=5):
+    """Config 2's own table (4096 pieces of 32 KiB inside the 4 GiB of a layer's K and V planes) moved by every
+    shape of tutti_scatter_baseline: would dealing the same bytes to the wavefronts differently, or another
+    cache policy, suit the memory system better than the product's wavefront-per-4-KiB with nt accesses?"""
+    s = w.shape
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    span = 2 * s.num_blocks * bb
+    perm = np.concatenate([w.block_table, w.block_table + s.num_blocks]).astype(np.uint32)
+    d_perm = torch.from_numpy(perm.view(np.int32)).to(dev)
+    bufs = [torch.empty(span, dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    scratch = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(4)]
+    res = {}
+    for shape in B.SCATTER_SHAPES:
+        row = {}
+        for label, wr in (("scattered_writes_us", 1), ("scattered_reads_us", 0)):
+            def run():
+                for i in range(len(stages)):
+                    B.tutti_scatter_baseline(bufs[i % n_buf], span, scratch[i % 4], nbytes, d_perm, bb, wr, shape)
+            run()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                run()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) * 1e3 / len(stages))
+            row[label] = round(median(ts), 2)
+        res[shape] = row
+        log(f"[bench] scatter shape {shape}: {row}")
+    return res
 
 
 def cpu_baseline(torch, W, w, plane0, pristine, stage0, geom, payload_layer, budget_s=8.0):
@@ -860,7 +1094,7 @@ def cpu_baseline(torch, W, w, plane0, pristine, stage0, geom, payload_layer, bud
     cfg = orc.make_cfg(w.align, w.chunk_bytes, w.shape.num_layers)
     ext, tot = orc.obj_layout(pool, cfg, w.n_blocks)
     stage = np.zeros(int(tot[0]), np.uint8)
-    cores = min(len(os.sched_getaffinity(0)), 16)
+    cores = len(os.sched_getaffinity(0))     # every core the process may run on; the count goes into the line
 
     def one_pass(nt):
         t = time.perf_counter()
@@ -895,12 +1129,52 @@ def cpu_baseline(torch, W, w, plane0, pristine, stage0, geom, payload_layer, bud
     log(f"[bench] oracle: 1 thread {res['1thread'][0]:.2f} GB/s, {cores} threads {res['allcores'][0]:.2f} GB/s; "
         f"GPU staging buffer of layer 0 equals the oracle's: {parity}")
     assert parity, "GPU-packed layer 0 differs from the CPU oracle"
-    return {"value": round(res["allcores"][0], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "value_1thread": round(res["1thread"][0], 3),
+    return {"value": round(res["allcores"][0], 3), "unit": "GB/s (bytes packed + bytes restored per second)", "cores": cores,
+            "kind": "oracle", "value_1thread": round(res["1thread"][0], 3),
             "sqes_per_s_1thread": round(oracle_sqes, 0),
             "sample": f"layer 0 of config 2 (2048 blocks, {payload_layer >> 20} MiB packed + {payload_layer >> 20} MiB "
                       f"restored per pass), median of {res['allcores'][1]} passes with {cores} threads "
                       f"({res['1thread'][1]} passes single-threaded)"}
+
+
+def cpu_baseline_others(W, budget_s=3.0):
+    """The oracle on one layer of configs 1, 3 and 4 (config 2 is the headline sample): pack + restore, one thread
+    and every core of the affinity mask.  Pool contents are a constant fill (the oracle's time does not depend on
+    the values); tables, extents and shapes are the workloads' own."""
+    from oracle import tutti_oracle as orc
+    cores = len(os.sched_getaffinity(0))
+    out = {}
+    for name, w in (("config1_tiny", W.tiny()), ("config3_batch64_zipf", W.batch64_zipf()),
+                    ("config4_llama70b_128k", W.llama70b_128k())):
+        s = w.shape
+        bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+        k = np.full(s.num_blocks * bb, 0x5A, np.uint8)
+        v = np.full(s.num_blocks * bb, 0xA5, np.uint8)
+        pool = orc.make_pool(k, v, num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
+                             head_dim=s.head_dim, elt_bytes=s.elt_bytes)
+        cfg = orc.make_cfg(w.align, w.chunk_bytes, s.num_layers)
+        ext, tot = orc.obj_layout(pool, cfg, w.n_blocks)
+        stage = np.zeros(int(tot[0]), np.uint8)
+        payload = 2 * int(w.block_table.size) * bb
+        row = {"payload_bytes_per_layer": payload}
+        for label, nt in (("1thread", 0), ("allcores", cores)):
+            def one_pass():
+                t = time.perf_counter()
+                orc.obj_pack(pool, cfg, ext, w.block_table, stage, n_threads=nt)
+                orc.obj_unpack(pool, cfg, ext, w.block_table, stage, n_threads=nt)
+                return time.perf_counter() - t
+            one_pass()
+            times, t0 = [], time.perf_counter()
+            while len(times) < 2 or (time.perf_counter() - t0 < budget_s and len(times) < 500):
+                times.append(one_pass())
+            row[f"GBps_{label}"] = round(2 * payload / median(times) / 1e9, 3)
+            row[f"passes_{label}"] = len(times)
+        out[name] = row
+        log(f"[bench] oracle on {name}: {row}")
+        del k, v, stage
+    out["cores"] = cores
+    out["sample"] = "one layer of each config, pack + restore per pass, median over the passes that fit about 3 s"
+    return out
 
 
 if __name__ == "__main__":

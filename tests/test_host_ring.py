@@ -198,3 +198,35 @@ def test_budget_for_slack():
     assert B.tutti_budget_for_slack(prof, n, 5, B.OP_READ, 1e9, 256) is None   # larger than anything profiled
     with pytest.raises(B.TuttiError):
         B.tutti_budget_for_slack(prof, n, 0, B.OP_READ, 1.0, 256)
+
+
+def test_committed_slack_table_answers_lookups():
+    """The table a profiling run wrote (profiles/slack_lut_*.json: bench.py --write-lut) loads into the C lookups,
+    and what they answer agrees with reading the rows by eye: durations grow with the IOCB count and shrink with
+    the budget, so the answers are monotone in the window."""
+    import glob
+    import json
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    paths = glob.glob(os.path.join(root, "profiles", "slack_lut_*.json"))
+    assert paths, "no slack table committed under profiles/"
+    for path in paths:
+        lut = json.load(open(path))
+        rows = [(r["cu_budget"], r["n_iocbs"], r["read_us"], r["write_us"]) for r in lut["rows"]]
+        prof, n = B.make_io_profile(rows)
+        budgets = sorted({r[0] for r in rows if r[0]})
+        for b in budgets:
+            mine = sorted((r[1], r[2]) for r in rows if r[0] == b)
+            for n_io, us in mine:
+                assert B.tutti_iocbs_for_slack(prof, n, b, B.OP_READ, us) >= n_io
+                fit = [m for m, t in mine if t <= us * 0.999]
+                assert B.tutti_iocbs_for_slack(prof, n, b, B.OP_READ, us * 0.999) == (max(fit) if fit else 0)
+        prev = None
+        for slack in (50.0, 100.0, 200.0, 400.0, 800.0, 1600.0):
+            got = B.tutti_budget_for_slack(prof, n, 2, B.OP_READ, slack, max(budgets))
+            if prev is not None and got is not None:
+                assert got <= prev          # a longer window never needs a larger budget
+            if got is not None:
+                prev = got
+                us = [r[2] for r in rows if r[0] == got and r[1] == 2][0]
+                assert us <= slack
