@@ -398,6 +398,15 @@ int tutti_budget_for_slack(const tutti_io_profile *rows, uint32_t n_rows, uint32
 int tutti_table_validate(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
                          void *stream);
 
+/* The same check in time linear in table_len, for the tables of whole batches: one bit per pool block in device
+ * memory that the caller lends for the call: d_work, 16-byte aligned, work_bytes >=
+ * tutti_table_validate_work_bytes(num_blocks) (= num_blocks / 8, rounded up to 256; TUTTI_ERANGE if smaller).  Its
+ * contents need not be initialised and are garbage afterwards; the call clears what it uses with a kernel on
+ * `stream`, so the pair of launches can be captured in a graph.  Same status bits as tutti_table_validate. */
+uint64_t tutti_table_validate_work_bytes(uint32_t num_blocks);
+int tutti_table_validate_ws(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
+                            void *d_work, uint64_t work_bytes, void *stream);
+
 /* ---- housekeeping */
 const char *tutti_strerror(int code);
 int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */

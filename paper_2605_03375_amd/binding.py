@@ -51,7 +51,7 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_resident_wgs_per_cu", "tutti_version", "tutti_abi_describe",
            "tutti_sq_state_init", "tutti_get_iocb", "tutti_sq_free_count", "tutti_reap_cqe", "tutti_iocb_completed",
            "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack", "tutti_io_domain_create",
-           "tutti_io_domain_destroy"]
+           "tutti_io_domain_destroy", "tutti_table_validate_work_bytes", "tutti_table_validate_ws"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
                  "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
 SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
@@ -131,6 +131,9 @@ def _declare(L, bench):
                                       vp, vp]
     L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
     L.tutti_table_validate.argtypes = [u32, vp, u32, vp, vp]
+    L.tutti_table_validate_ws.argtypes = [u32, vp, u32, vp, vp, u64, vp]
+    L.tutti_table_validate_work_bytes.argtypes = [u32]
+    L.tutti_table_validate_work_bytes.restype = u64
     pr, pf = C.POINTER(tutti_ring), C.POINTER(tutti_filestore)
     L.tutti_ring_init.argtypes = [pr, vp]
     L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
@@ -159,7 +162,7 @@ def _declare(L, bench):
     L.tutti_iocbs_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, C.POINTER(u32)]
     L.tutti_budget_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, u32, C.POINTER(u32)]
     for name in EXPORTS:
-        if name not in ("tutti_strerror", "tutti_version", "tutti_sq_free_count"):
+        if name not in ("tutti_strerror", "tutti_version", "tutti_sq_free_count", "tutti_table_validate_work_bytes"):
             getattr(L, name).restype = C.c_int
     if bench:
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
@@ -358,6 +361,16 @@ def tutti_layer_save(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_f
 def tutti_table_validate(num_blocks, d_block_table, table_len, d_status, stream=None):
     return _check("tutti_table_validate", lib().tutti_table_validate(num_blocks, _p(d_block_table), table_len,
                                                                      _p(d_status), _stream(stream)))
+
+
+def tutti_table_validate_work_bytes(num_blocks):
+    return int(lib().tutti_table_validate_work_bytes(num_blocks))
+
+
+def tutti_table_validate_ws(num_blocks, d_block_table, table_len, d_status, d_work, work_bytes, stream=None):
+    return _check("tutti_table_validate_ws", lib().tutti_table_validate_ws(num_blocks, _p(d_block_table), table_len,
+                                                                           _p(d_status), _p(d_work), work_bytes,
+                                                                           _stream(stream)))
 
 
 def tutti_stream_baseline(d_buf, nbytes, write, d_xor=None, cu_budget=0, stream=None):

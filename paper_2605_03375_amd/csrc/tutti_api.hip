@@ -848,6 +848,43 @@ int tutti_table_validate(uint32_t num_blocks, const uint32_t *d_block_table, uin
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
+extern "C++" {
+namespace {
+// The linear-time table check on `bits` (device memory for at least ceil(num_blocks / 32) words).
+int validate_with_bitmap(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
+                         uint32_t *bits, hipStream_t s) {
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  const uint32_t n_words = (num_blocks + 31u) / 32u;
+  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
+  uint64_t need = (static_cast<uint64_t>(n_words) + kWgThreads - 1) / kWgThreads;
+  hipLaunchKernelGGL(k_bitmap_clear, dim3(static_cast<uint32_t>(need < lim ? need : lim)), dim3(kWgThreads), 0, s, bits,
+                     n_words);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  need = (static_cast<uint64_t>(table_len) + kWgThreads - 1) / kWgThreads;
+  hipLaunchKernelGGL(k_table_validate_bitmap, dim3(static_cast<uint32_t>(need < lim ? need : lim)), dim3(kWgThreads), 0, s,
+                     d_block_table, table_len, num_blocks, bits, d_status);
+  e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+}  // namespace
+}  // extern "C++"
+
+uint64_t tutti_table_validate_work_bytes(uint32_t num_blocks) {
+  return ((static_cast<uint64_t>(num_blocks) + 31u) / 32u * 4u + 255u) & ~255ull;
+}
+
+int tutti_table_validate_ws(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
+                            void *d_work, uint64_t work_bytes, void *stream) {
+  if (num_blocks == 0 || !d_status || (table_len > 0 && !d_block_table)) return TUTTI_EINVAL;
+  if (!d_work || !aligned16(d_work)) return TUTTI_EINVAL;
+  if (work_bytes < tutti_table_validate_work_bytes(num_blocks)) return TUTTI_ERANGE;
+  if (table_len == 0) return TUTTI_OK;
+  return validate_with_bitmap(num_blocks, d_block_table, table_len, d_status, static_cast<uint32_t *>(d_work),
+                              static_cast<hipStream_t>(stream));
+}
+
 #ifdef TUTTI_BENCH_BUILD
 // ---- measurement aids (include/tutti_bench.h): ceilings, floors and the tuning knobs
 

@@ -15,6 +15,7 @@
 //   k_copy, k_stream, k_scatter, k_scatter_piece   (measurement build only) plain copy, one-direction streams and
 //                   copies with one side permuted at a given granularity: ceilings and floors for the above
 //   k_table_validate  debugging aid: ids in range and no id twice, by all-pairs comparison (no workspace)
+//   k_bitmap_clear, k_table_validate_bitmap   the same check in linear time with one bit per pool block
 //
 // Every workgroup first puts the per-request offsets into LDS (from the extents, or by redoing
 // the scan), then walks work items with a persistent grid-stride loop, so the grid can be any
@@ -1417,6 +1418,35 @@ __global__ __launch_bounds__(kWgThreads) void k_table_validate(const uint32_t *_
     }
   }
   if (found && status) atomicOr(status, found);
+}
+
+// The same two preconditions in time linear in the table, with one bit per pool block in memory that the caller
+// lends (or that the library keeps): a thread sets the bit of its id with an atomic OR and has found a duplicate
+// when the bit was already set.  The bits a call uses are cleared by a kernel in front of it (a fill kernel, not
+// a memset node, so that the pair can be captured in a graph).
+__global__ __launch_bounds__(kWgThreads) void k_bitmap_clear(uint32_t *__restrict__ bits, uint32_t n_words) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += gridDim.x * blockDim.x) bits[i] = 0u;
+}
+
+__global__ __launch_bounds__(kWgThreads) void k_table_validate_bitmap(const uint32_t *__restrict__ table, uint32_t n,
+                                                                       uint32_t num_blocks, uint32_t *__restrict__ bits,
+                                                                       uint32_t *__restrict__ status) {
+  uint32_t found = 0;
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const uint32_t id = table[i];
+    if (id >= num_blocks) {
+      found |= TUTTI_ST_BAD_BLOCK;
+    } else {
+      const uint32_t bit = 1u << (id & 31u);
+      if (atomicOr(&bits[id >> 5], bit) & bit) found |= TUTTI_ST_DUP_BLOCK;
+    }
+  }
+  // one atomic per wavefront that found something
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  uint32_t any = found;
+#pragma unroll
+  for (uint32_t d = kWave / 2; d >= 1; d >>= 1) any |= __shfl_xor(any, d, kWave);
+  if (lane == 0 && any && status) atomicOr(status, any);
 }
 
 #ifdef TUTTI_BENCH_BUILD

@@ -194,6 +194,10 @@ def test_null_and_misaligned_pointers_are_einval():
     _expect(B.EINVAL, B.tutti_table_validate, 0, FAKE, 4, FAKE)
     _expect(B.EINVAL, B.tutti_table_validate, 8, 0, 4, FAKE)
     _expect(B.EINVAL, B.tutti_table_validate, 8, FAKE, 4, 0)
+    _expect(B.EINVAL, B.tutti_table_validate_ws, 8, FAKE, 4, FAKE, 0, 256)
+    _expect(B.EINVAL, B.tutti_table_validate_ws, 8, FAKE, 4, 0, FAKE, 256)
+    _expect(B.ERANGE, B.tutti_table_validate_ws, 4096, FAKE, 4, FAKE, FAKE, 256)
+    assert B.tutti_table_validate_work_bytes(1) == 256 and B.tutti_table_validate_work_bytes(65536) == 8192
     _expect(B.EINVAL, B.tutti_copy_baseline, FAKE, FAKE, 24)
     _expect(B.EINVAL, B.tutti_copy_baseline, 0, FAKE, 32)
     # head-major pools need rows of whole 16-byte units

@@ -1067,17 +1067,25 @@ def test_cu_budget_out_of_range(H):
 
 
 def test_table_validate(orc, H):
-    """Ids in range and no id twice: the device's all-pairs check against the oracle's bitmap."""
+    """Ids in range and no id twice: the device's all-pairs check, and its linear-time check with a lent bitmap
+    (handed over full of garbage), against the oracle."""
     say("table validation")
     rng = np.random.default_rng(61)
 
     def both(num_blocks, table):
         table = np.ascontiguousarray(table, np.uint32)
-        st = H.new_status()
-        B.tutti_table_validate(num_blocks, H.to_dev(table) if table.size else None, table.size, st)
+        st, st_ws = H.new_status(), H.new_status()
+        d_table = H.to_dev(table) if table.size else None
+        B.tutti_table_validate(num_blocks, d_table, table.size, st)
+        nbytes = B.tutti_table_validate_work_bytes(num_blocks)
+        assert nbytes % 256 == 0 and nbytes * 8 >= num_blocks
+        work = torch.full((nbytes + 256,), 0xFF, dtype=torch.uint8, device=H.DEV)
+        B.tutti_table_validate_ws(num_blocks, d_table, table.size, st_ws, work, nbytes)
         torch.cuda.synchronize()
         want = orc.table_validate(num_blocks, table)
         assert int(st.item()) == want, (num_blocks, table.size, int(st.item()), want)
+        assert int(st_ws.item()) == want, ("bitmap", num_blocks, table.size, int(st_ws.item()), want)
+        assert bool((work[nbytes:] == 0xFF).all()), "the check wrote beyond the bytes it was lent"
         return want
 
     assert both(16, []) == 0 and both(1, [0]) == 0 and both(1, [0, 0]) == B.ST_DUP_BLOCK
@@ -1110,6 +1118,20 @@ def test_table_validate(orc, H):
     assert both(w.shape.num_blocks, t) == B.ST_DUP_BLOCK
     with pytest.raises(B.TuttiError):
         B.tutti_table_validate(0, H.to_dev(t), t.size, H.new_status())
+    # a million entries over four million blocks: linear time, about a millisecond
+    N = 1 << 22
+    big = rng.permutation(N)[: 1 << 20].astype(np.uint32)
+    work = torch.empty(B.tutti_table_validate_work_bytes(N), dtype=torch.uint8, device=H.DEV)
+    for plant, want in ((False, 0), (True, B.ST_DUP_BLOCK)):
+        if plant:
+            big[777_777] = big[3]
+        st = H.new_status()
+        B.tutti_table_validate_ws(N, H.to_dev(big), big.size, st, work, work.numel())
+        torch.cuda.synchronize()
+        assert int(st.item()) == want == orc.table_validate(N, big)
+    with pytest.raises(B.TuttiError) as ei:      # a bitmap one byte short
+        B.tutti_table_validate_ws(N, H.to_dev(big), big.size, H.new_status(), work, work.numel() - 1)
+    assert ei.value.code == B.ERANGE
 
 
 def test_default_kernels_keep_eight_workgroups_per_cu_resident(H):
