@@ -407,6 +407,16 @@ uint64_t tutti_table_validate_work_bytes(uint32_t num_blocks);
 int tutti_table_validate_ws(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_status,
                             void *d_work, uint64_t work_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or lend any: code under HIP-graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  tutti_table_validate_ws with the bitmap in an array the library itself keeps
+ * on every GPU it runs on (TUTTI_STATIC_VALIDATE_MAX_BLOCKS bits = 512 KiB, held until the process ends); the call
+ * allocates nothing.  num_blocks above TUTTI_STATIC_VALIDATE_MAX_BLOCKS is TUTTI_ERANGE (nothing is enqueued).
+ * Every call on a GPU uses that GPU's one array and clears the bits it needs first: calls that overlap on one GPU
+ * (two streams, two threads) race and must be ordered by the caller.  Same status bits as tutti_table_validate. */
+#define TUTTI_STATIC_VALIDATE_MAX_BLOCKS (1u << 22)
+int tutti_table_validate_static(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len,
+                                uint32_t *d_status, void *stream);
+
 /* ---- housekeeping */
 const char *tutti_strerror(int code);
 int tutti_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */

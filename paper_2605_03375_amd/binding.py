@@ -51,7 +51,8 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_resident_wgs_per_cu", "tutti_version", "tutti_abi_describe",
            "tutti_sq_state_init", "tutti_get_iocb", "tutti_sq_free_count", "tutti_reap_cqe", "tutti_iocb_completed",
            "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack", "tutti_io_domain_create",
-           "tutti_io_domain_destroy", "tutti_table_validate_work_bytes", "tutti_table_validate_ws"]
+           "tutti_io_domain_destroy", "tutti_table_validate_work_bytes", "tutti_table_validate_ws",
+           "tutti_table_validate_static"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
                  "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
 SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
@@ -132,6 +133,7 @@ def _declare(L, bench):
     L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
     L.tutti_table_validate.argtypes = [u32, vp, u32, vp, vp]
     L.tutti_table_validate_ws.argtypes = [u32, vp, u32, vp, vp, u64, vp]
+    L.tutti_table_validate_static.argtypes = [u32, vp, u32, vp, vp]
     L.tutti_table_validate_work_bytes.argtypes = [u32]
     L.tutti_table_validate_work_bytes.restype = u64
     pr, pf = C.POINTER(tutti_ring), C.POINTER(tutti_filestore)
@@ -371,6 +373,15 @@ def tutti_table_validate_ws(num_blocks, d_block_table, table_len, d_status, d_wo
     return _check("tutti_table_validate_ws", lib().tutti_table_validate_ws(num_blocks, _p(d_block_table), table_len,
                                                                            _p(d_status), _p(d_work), work_bytes,
                                                                            _stream(stream)))
+
+
+STATIC_VALIDATE_MAX_BLOCKS = 1 << 22
+
+
+def tutti_table_validate_static(num_blocks, d_block_table, table_len, d_status, stream=None):
+    return _check("tutti_table_validate_static", lib().tutti_table_validate_static(num_blocks, _p(d_block_table),
+                                                                                   table_len, _p(d_status),
+                                                                                   _stream(stream)))
 
 
 def tutti_stream_baseline(d_buf, nbytes, write, d_xor=None, cu_budget=0, stream=None):

@@ -19,6 +19,10 @@
 #endif
 #include "tutti_kernels.hip.h"
 
+// Bitmap of tutti_table_validate_static: one bit per pool block, kept by the library on every GPU it runs on.
+// In host code this name is only a stand-in; the array's device address is looked up per device (scratch_bits()).
+static __device__ __align__(256) uint32_t scratch[TUTTI_STATIC_VALIDATE_MAX_BLOCKS / 32u];
+
 namespace {
 
 using namespace tutti;
@@ -885,6 +889,43 @@ int tutti_table_validate_ws(uint32_t num_blocks, const uint32_t *d_block_table, 
                               static_cast<hipStream_t>(stream));
 }
 
+extern "C++" {
+namespace {
+std::atomic<uint32_t *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device: looked up once per device, with that device current (every
+// GPU holds its own copy of the array at its own address).
+int scratch_bits(uint32_t **out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return TUTTI_ERANGE;
+  uint32_t *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void *addr = nullptr;
+    e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!addr) return TUTTI_EHIP;
+    p = static_cast<uint32_t *>(addr);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return TUTTI_OK;
+}
+}  // namespace
+}  // extern "C++"
+
+int tutti_table_validate_static(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len,
+                                uint32_t *d_status, void *stream) {
+  if (num_blocks == 0 || !d_status || (table_len > 0 && !d_block_table)) return TUTTI_EINVAL;
+  if (num_blocks > TUTTI_STATIC_VALIDATE_MAX_BLOCKS) return TUTTI_ERANGE;  // the static bitmap has no bit for them
+  if (table_len == 0) return TUTTI_OK;
+  uint32_t *bits = nullptr;
+  const int rc = scratch_bits(&bits);
+  if (rc) return rc;
+  return validate_with_bitmap(num_blocks, d_block_table, table_len, d_status, bits, static_cast<hipStream_t>(stream));
+}
+
 #ifdef TUTTI_BENCH_BUILD
 // ---- measurement aids (include/tutti_bench.h): ceilings, floors and the tuning knobs
 
@@ -1063,7 +1104,8 @@ const char *tutti_strerror(int code) {
     case TUTTI_EINVAL:
       return "invalid argument (null pointer, zero dimension, bad alignment, layout, opcode or layer)";
     case TUTTI_ERANGE:
-      return "out of range (too many requests, CU budget above the CU count, or table too long)";
+      return "out of range (too many requests, CU budget above the CU count, table too long, workspace too small, or "
+             "more pool blocks than the static bitmap of tutti_table_validate_static covers)";
     case TUTTI_EHIP:
       return "a HIP call failed (see tutti_last_hip_error)";
     case TUTTI_EAGAIN:
