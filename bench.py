@@ -302,6 +302,7 @@ def main():
         out["scatter_sweep"] = scatter_sweep(torch, B, stages, payload_layer, dev)
         out["scatter_orders_32KiB"] = scatter_orders(torch, B, stages, payload_layer, dev)
         out["scatter_shapes_32KiB"] = scatter_shapes(torch, B, w, stages, payload_layer, dev)
+        out["visit_order"] = visit_order(torch, B, W, dev)
     if args.pinned_stage:
         out["pinned_host_stage"] = pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload_layer,
                                               n_sqe_layer, dev)
@@ -1044,6 +1045,46 @@ def length_sweep(torch, B, W, pools, cfg, dev, lengths=(1024, 2048, 4096, 8192, 
     out["context"] = ("the paper's retrieve bandwidth over the same lengths is bound by its SSDs (at most 25.9 GB/s on "
                       "its 4-SSD H100 box, sec. 4); quoted as context only")
     return out
+
+
+def visit_order(torch, B, W, dev, reps=5):
+    """Would it pay to visit the blocks of a restore in the order of their pool addresses instead of token order?
+    (A one-off argsort of the block table, reused by every layer, would make that free per layer.)  The tables of
+    configs 2, 3 and 4 as scattered writes of 32 KiB pieces (K plane then V plane of one layer), in table order
+    and sorted by address, with the kernel that has the product's access shape and nothing else in it."""
+    res = {}
+    for name, w in (("config2", W.llama8b_32k()), ("config3", W.batch64_zipf()), ("config4", W.llama70b_128k())):
+        s = w.shape
+        bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+        span = 2 * s.num_blocks * bb
+        perm = np.concatenate([w.block_table, w.block_table + s.num_blocks]).astype(np.uint32)
+        nbytes = int(perm.size) * bb
+        bufs = [torch.empty(span, dtype=torch.uint8, device=dev) for _ in range(3)]
+        src = [torch.empty(nbytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+        row = {"pieces": int(perm.size), "pool_blocks": s.num_blocks,
+               "fill": round(w.block_table.size / s.num_blocks, 3)}
+        for order, p in (("table_order", perm), ("address_order", np.sort(perm))):
+            d_perm = torch.from_numpy(p.view(np.int32)).to(dev)
+
+            def run():
+                for i in range(6):
+                    B.tutti_scatter_baseline(bufs[i % 3], span, src[i % 2], nbytes, d_perm, bb, 1)
+            run()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                run()
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) * 1e3 / 6)
+            row[f"{order}_us"] = round(median(ts), 2)
+        row["gain_pct"] = round(100 * (1 - row["address_order_us"] / row["table_order_us"]), 2)
+        res[name] = row
+        log(f"[bench] visit order {name}: {row}")
+        del bufs, src
+    return res
 
 
 def scatter_shapes(torch, B, w, stages, nbytes, dev, n_buf=6, reps=5):
