@@ -1134,6 +1134,47 @@ def test_table_validate(orc, H):
     assert ei.value.code == B.ERANGE
 
 
+def test_table_validate_with_bitmap_can_be_captured_in_a_graph(orc, H):
+    """The linear-time check clears its bitmap with a kernel (no memset node), so both of its forms can be captured
+    in a HIP graph; every replay must report what the eager call reports, with eager work between the replays and
+    the table changed in place (same address) from clean to one with a duplicate and back."""
+    say("table validation under graph capture")
+    rng = np.random.default_rng(88)
+    N = 50_000
+    clean = rng.permutation(N)[:20_000].astype(np.uint32)
+    dup = clean.copy()
+    dup[19_999] = dup[0]
+    d_table = H.to_dev(clean)
+    st_ws, st_static = H.new_status(), H.new_status()
+    work = torch.empty(B.tutti_table_validate_work_bytes(N), dtype=torch.uint8, device=H.DEV)
+
+    def both():
+        B.tutti_table_validate_ws(N, d_table, clean.size, st_ws, work, work.numel())
+        B.tutti_table_validate_static(N, d_table, clean.size, st_static)
+
+    both()                                     # eager first (also looks the static array up, outside the capture)
+    torch.cuda.synchronize()
+    assert int(st_ws.item()) == int(st_static.item()) == 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            both()
+    torch.cuda.synchronize()
+    for rep, table in enumerate((dup, clean, dup, clean)):
+        d_table.copy_(H.to_dev(table))
+        st_ws.zero_()
+        st_static.zero_()
+        junk = torch.randn(256, 256, device=H.DEV) @ torch.randn(256, 256, device=H.DEV)   # eager work in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = orc.table_validate(N, table)
+        assert int(st_ws.item()) == int(st_static.item()) == want, (rep, int(st_ws.item()), int(st_static.item()), want)
+        assert torch.isfinite(junk).all()
+
+
 def test_default_kernels_keep_eight_workgroups_per_cu_resident(H):
     """The whole-GPU grids are sized for 8 resident 256-thread workgroups per compute unit; a kernel variant that
     grew past 64 VGPRs would leave part of its persistent grid waiting behind the rest (a tail of several percent)."""
