@@ -693,6 +693,96 @@ int orc_table_validate(uint32_t num_blocks, const uint32_t *block_table, uint32_
   return ORC_OK;
 }
 
+/* ------------------------------------------------------------------ visiting order */
+
+/*
+ * The order in which a restore may visit the blocks of a table so that it walks the pool by ascending address:
+ * visit[k] = the table position of the k-th smallest block id.  The paper keeps token order (sec. 3.1: an object
+ * holds a request's blocks as they come); the visiting order is this repository's addition and changes no result,
+ * only the order of the writes.  A table that a restore may not use anyway (an id out of range, or an id twice:
+ * orc_table_validate) gets the identity order, and the status bits say why.
+ */
+int orc_table_order(uint32_t num_blocks, const uint32_t *block_table, uint32_t table_len, uint32_t *visit,
+                    uint32_t *status) {
+  if (num_blocks == 0 || (table_len > 0 && (!block_table || !visit))) return ORC_EINVAL;
+  uint32_t st = 0;
+  int rc = orc_table_validate(num_blocks, block_table, table_len, &st);
+  if (rc) return rc;
+  if (status) *status |= st;
+  for (uint32_t k = 0; k < table_len; ++k) visit[k] = k;
+  if (st) return ORC_OK;
+  /* insertion sort of the positions by block id: plain, quadratic, obviously an ascending order */
+  for (uint32_t k = 1; k < table_len; ++k) {
+    uint32_t pos = visit[k];
+    uint32_t m = k;
+    while (m > 0 && block_table[visit[m - 1]] > block_table[pos]) {
+      visit[m] = visit[m - 1];
+      --m;
+    }
+    visit[m] = pos;
+  }
+  return ORC_OK;
+}
+
+/*
+ * One layer's restore with the blocks visited in the order `visit` gives (table positions, table_len of them):
+ * extents and READ entries as orc_layer_restore, then for every listed position, in list order, the K block and
+ * the V block it names.  A position that lies beyond the blocks the requests claim (or beyond table_len) is
+ * passed over; a position listed twice is restored twice; one not listed is not restored.  With a permutation of
+ * the positions the result is orc_layer_restore's.
+ */
+int orc_layer_restore_ordered(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                              const uint32_t *block_table, uint32_t table_len, const uint32_t *file_id, uint32_t layer,
+                              const void *stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id,
+                              orc_extent *extents, uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap,
+                              const uint32_t *visit, uint32_t *status) {
+  int rc = check_geometry(pool, cfg);
+  if (rc) return rc;
+  if (layer >= cfg->num_layers || stage_addr % cfg->align != 0) return ORC_EINVAL;
+  if (n_req > 0 && (!file_id || !stage)) return ORC_EINVAL;
+  if (!pool->k_base || !pool->v_base) return ORC_EINVAL;
+  if (sqe_cap > 0 && !sqe) return ORC_EINVAL;
+  if (table_len > 0 && (!visit || !block_table)) return ORC_EINVAL;
+  rc = orc_obj_layout(pool, cfg, n_blocks, n_req, extents, totals);
+  if (rc) return rc;
+  rc = orc_sqe_build(pool, cfg, extents, n_req, file_id, layer, ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);
+  if (rc) return rc;
+  const uint64_t bb = orc_block_bytes(pool);
+  uint32_t st = 0;
+  /* the requests that take part: in order, while their blocks fit the table (as in orc_obj_unpack) */
+  uint64_t live_blocks = 0;
+  uint32_t live_req = 0;
+  while (live_req < n_req && live_blocks + extents[live_req].n_blocks <= table_len) {
+    live_blocks += extents[live_req].n_blocks;
+    ++live_req;
+  }
+  if (live_req < n_req) st |= ORC_ST_BAD_EXTENT;
+  for (uint32_t r = 0; r < live_req; ++r)
+    if (extents[r].stage_off > stage_cap || extents[r].obj_bytes > (stage_cap - extents[r].stage_off) / 2)
+      st |= ORC_ST_STAGE_CAP;
+  for (uint32_t kind = 0; kind < 2; ++kind) {
+    uint8_t *plane = (uint8_t *)(kind == 0 ? pool->k_base : pool->v_base);
+    for (uint32_t k = 0; k < table_len; ++k) {
+      const uint64_t pos = visit[k];
+      if (pos >= live_blocks) continue; /* not a block of a request that takes part */
+      uint32_t r = 0;
+      while (pos >= (uint64_t)extents[r].table_off + extents[r].n_blocks) ++r; /* the request that owns it */
+      const orc_extent *x = &extents[r];
+      if (x->stage_off > stage_cap || x->obj_bytes > (stage_cap - x->stage_off) / 2) continue;
+      const uint64_t j = pos - x->table_off;
+      const uint32_t id = block_table[pos];
+      if (id >= pool->num_blocks) {
+        st |= ORC_ST_BAD_BLOCK;
+        continue;
+      }
+      uint8_t *obj = (uint8_t *)(uintptr_t)stage + x->stage_off + kind * x->obj_bytes;
+      move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + j * bb, 0);
+    }
+  }
+  if (status && st) *status |= st;
+  return ORC_OK;
+}
+
 /* ------------------------------------------------------------------ threaded timing helpers */
 
 typedef struct {

@@ -262,6 +262,20 @@ int orc_store_layer(orc_iocb *sq, void *cq, uint32_t depth, uint32_t first_slot,
  * range ids are not counted as duplicates of each other.  *status receives the bits (ORed in). */
 int orc_table_validate(uint32_t num_blocks, const uint32_t *block_table, uint32_t table_len, uint32_t *status);
 
+/* visit[k] = table position of the k-th smallest block id (an ascending walk through the pool); the identity, with
+ * the bits of orc_table_validate in *status, for a table with an id out of range or an id twice. */
+int orc_table_order(uint32_t num_blocks, const uint32_t *block_table, uint32_t table_len, uint32_t *visit,
+                    uint32_t *status);
+
+/* orc_layer_restore with the blocks visited in the listed order of table positions (table_len entries).  A
+ * position beyond the blocks of the requests that take part is passed over, one listed twice is restored twice,
+ * one not listed is not restored; a permutation gives exactly orc_layer_restore's result. */
+int orc_layer_restore_ordered(const orc_pool *pool, const orc_objcfg *cfg, const uint32_t *n_blocks, uint32_t n_req,
+                              const uint32_t *block_table, uint32_t table_len, const uint32_t *file_id, uint32_t layer,
+                              const void *stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id,
+                              orc_extent *extents, uint64_t *totals, orc_sqe *sqe, uint32_t sqe_cap,
+                              const uint32_t *visit, uint32_t *status);
+
 /* Descriptor count for a pool of pool_bytes described at gran bytes per descriptor
  * (the arithmetic of sec. 3.1, "P2P Memory Mapping Table"). */
 uint64_t orc_desc_count(uint64_t pool_bytes, uint64_t gran);

@@ -344,3 +344,40 @@ def layer_save(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_ad
     if rc:
         raise OracleError("orc_layer_save", rc)
     return ext, totals, sqe, status.value
+
+
+def table_order(num_blocks, block_table):
+    """Returns (visit, status): table positions in ascending order of block id; identity + status bits for a table
+    that table_validate objects to."""
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    visit = np.zeros(block_table.size, np.uint32)
+    status = C.c_uint32(0)
+    rc = lib().orc_table_order(C.c_uint32(num_blocks), _ptr(block_table), C.c_uint32(block_table.size), _ptr(visit),
+                               C.byref(status))
+    if rc:
+        raise OracleError("orc_table_order", rc)
+    return visit, status.value
+
+
+def layer_restore_ordered(pool, cfg, n_blocks, block_table, file_id, layer, stage, stage_addr, sgl_id, sqe_cap, visit,
+                          stage_cap=None, table_len=None):
+    """layer_restore with the blocks visited in the order `visit` lists (table positions)."""
+    n_blocks = np.ascontiguousarray(n_blocks, dtype=np.uint32)
+    block_table = np.ascontiguousarray(block_table, dtype=np.uint32)
+    file_id = np.ascontiguousarray(file_id, dtype=np.uint32)
+    visit = np.ascontiguousarray(visit, dtype=np.uint32)
+    ext = np.zeros(n_blocks.size, EXTENT_DTYPE)
+    totals = np.zeros(2, np.uint64)
+    sqe = np.zeros(sqe_cap, SQE_DTYPE)
+    cap = stage.nbytes if stage_cap is None else stage_cap
+    tl = block_table.size if table_len is None else table_len
+    assert tl <= block_table.size and tl <= visit.size
+    status = C.c_uint32(0)
+    rc = lib().orc_layer_restore_ordered(C.byref(pool), C.byref(cfg), _ptr(n_blocks), C.c_uint32(n_blocks.size),
+                                         _ptr(block_table), C.c_uint32(tl), _ptr(file_id), C.c_uint32(layer),
+                                         _ptr(stage), C.c_uint64(cap), C.c_uint64(stage_addr), C.c_uint32(sgl_id),
+                                         _ptr(ext), _ptr(totals), _ptr(sqe), C.c_uint32(sqe_cap), _ptr(visit),
+                                         C.byref(status))
+    if rc:
+        raise OracleError("orc_layer_restore_ordered", rc)
+    return ext, totals, sqe, status.value

@@ -1060,6 +1060,77 @@ def check_entry_builders_want_layout_extents(orc, seed=53):
     assert np.array_equal(sqe["file_off"], good["file_off"])
 
 
+def check_visit_order(orc, seed=67):
+    """table_order against numpy.argsort; the ordered restore against the plain one for permutations, and against
+    numpy slices for lists that are not permutations."""
+    rng = np.random.default_rng(seed)
+    for _ in range(40):
+        N = int(rng.integers(1, 400))
+        n = int(rng.integers(0, N + 1))
+        t = rng.permutation(N)[:n].astype(np.uint32)
+        visit, st = orc.table_order(N, t)
+        assert st == 0 and np.array_equal(visit, np.argsort(t, kind="stable").astype(np.uint32))
+        assert np.all(np.diff(t[visit].astype(np.int64)) > 0) if n > 1 else True
+    t = np.array([5, 2, 9, 2, 7], np.uint32)
+    visit, st = orc.table_order(10, t)
+    assert st == orc.ST_DUP_BLOCK and np.array_equal(visit, np.arange(5))
+    visit, st = orc.table_order(8, np.array([5, 2, 9, 7], np.uint32))
+    assert st == orc.ST_BAD_BLOCK and np.array_equal(visit, np.arange(4))
+    assert orc.table_order(4, [])[0].size == 0
+    # restore: any permutation gives the plain restore's result, entries and extents included
+    T, h, d, e, N, A = 4, 2, 8, 2, 64, 128
+    bb = T * h * d * e
+    for layout in (0, 1):
+        n = np.array([5, 0, 9, 3], np.uint32)
+        table = rng.permutation(N)[: int(n.sum())].astype(np.uint32)
+        fid = np.array([3, 4, 5, 6], np.uint32)
+        cfg = orc.make_cfg(A, 2 * A, 3)
+        k0, v0 = _planes(rng, N, bb)
+        p0 = _pool(orc, T, h, d, e, N, k0, v0, layout=layout)
+        ext, tot = orc.obj_layout(p0, cfg, n)
+        stage = rng.integers(0, 256, int(tot[0]), dtype=np.uint8)
+        ka, va = k0.copy(), v0.copy()
+        ea, ta, sa, st_a = orc.layer_restore(_pool(orc, T, h, d, e, N, ka, va, layout=layout), cfg, n, table, fid, 2,
+                                             stage, 4096, 7, int(tot[1]))
+        for visit in (orc.table_order(N, table)[0], rng.permutation(table.size), np.arange(table.size)[::-1]):
+            kb, vb = k0.copy(), v0.copy()
+            eb, tb, sb, st_b = orc.layer_restore_ordered(_pool(orc, T, h, d, e, N, kb, vb, layout=layout), cfg, n, table,
+                                                         fid, 2, stage, 4096, 7, int(tot[1]), visit)
+            assert st_a == st_b == 0 and np.array_equal(ka, kb) and np.array_equal(va, vb)
+            assert ea.tobytes() == eb.tobytes() and sa.tobytes() == sb.tobytes() and np.array_equal(ta, tb)
+    # a list that is not a permutation: listed positions are restored, the others are not (NHD: a block is one slice)
+    n = np.array([4, 3], np.uint32)
+    table = np.array([10, 3, 7, 20, 1, 30, 12], np.uint32)
+    cfg = orc.make_cfg(A, A, 1)
+    k0, v0 = _planes(rng, N, bb)
+    p0 = _pool(orc, T, h, d, e, N, k0, v0)
+    ext, tot = orc.obj_layout(p0, cfg, n)
+    stage = rng.integers(0, 256, int(tot[0]), dtype=np.uint8)
+    visit = np.array([5, 5, 0, 99, 6, 7, 2], np.uint32)       # 1, 3, 4 missing; 5 twice; 99 and 7 out of range
+    kb, vb = k0.copy(), v0.copy()
+    _, _, _, st = orc.layer_restore_ordered(_pool(orc, T, h, d, e, N, kb, vb), cfg, n, table, [1, 2], 0, stage, 0, 0,
+                                            int(tot[1]), visit)
+    want_k, want_v = k0.copy(), v0.copy()
+    for pos in (5, 0, 6, 2):
+        r = 0 if pos < 4 else 1
+        j = pos - int(ext["table_off"][r])
+        so, ob = int(ext["stage_off"][r]), int(ext["obj_bytes"][r])
+        b = int(table[pos])
+        want_k[b * bb:(b + 1) * bb] = stage[so + j * bb: so + (j + 1) * bb]
+        want_v[b * bb:(b + 1) * bb] = stage[so + ob + j * bb: so + ob + (j + 1) * bb]
+    assert st == 0 and np.array_equal(kb, want_k) and np.array_equal(vb, want_v)
+    # the table one entry short: the second request does not take part, whatever the list says
+    kb, vb = k0.copy(), v0.copy()
+    _, _, _, st = orc.layer_restore_ordered(_pool(orc, T, h, d, e, N, kb, vb), cfg, n, table, [1, 2], 0, stage, 0, 0,
+                                            int(tot[1]), np.arange(7, dtype=np.uint32), table_len=6)
+    want_k, want_v = k0.copy(), v0.copy()
+    for pos in range(4):
+        b = int(table[pos])
+        want_k[b * bb:(b + 1) * bb] = stage[pos * bb:(pos + 1) * bb]
+        want_v[b * bb:(b + 1) * bb] = stage[int(ext["obj_bytes"][0]) + pos * bb: int(ext["obj_bytes"][0]) + (pos + 1) * bb]
+    assert st == orc.ST_BAD_EXTENT and np.array_equal(kb, want_k) and np.array_equal(vb, want_v)
+
+
 def check_table_validate(orc, seed=43):
     """Duplicates and out-of-range ids, against numpy.unique on independently built tables."""
     rng = np.random.default_rng(seed)
@@ -1084,4 +1155,4 @@ ALL_CHECKS = [check_paper_counts, check_closed_forms_8b, check_abi, check_layout
               check_pack_vs_numpy, check_address_tags, check_roundtrip_and_untouched, check_skips_and_status,
               check_sqe_fields, check_layer_restore, check_threaded, check_sgl_table, check_direct_entries, check_ring_fill, check_issue_io, check_issue_io_hand_filled,
               check_ring_layer, check_table_validate, check_caller_extents,
-              check_entry_builders_want_layout_extents]
+              check_entry_builders_want_layout_extents, check_visit_order]

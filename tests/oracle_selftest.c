@@ -249,6 +249,27 @@ static void one_case(void) {
                             (uint32_t)tot[1], &st) == ORC_OK);
     CHECK(memcmp(k3, k2, N * stride) == 0 && memcmp(v3, v2, N * stride) == 0);
     CHECK(memcmp(sqe2, sqe, sizeof(orc_sqe) * tot[1]) == 0);
+    /* the ordered restore with the order orc_table_order gives (the identity when the table has a bad id) equals
+     * the plain one */
+    {
+      uint32_t *visit = xmalloc(sizeof(uint32_t) * total);
+      uint32_t st_o = 0;
+      CHECK(orc_table_order(N, table, total, visit, &st_o) == ORC_OK);
+      CHECK((st_o != 0) == (plant_bad != 0));
+      uint8_t *k5 = xmalloc(N * stride), *v5 = xmalloc(N * stride);
+      memset(k5, 0, N * stride);
+      memset(v5, 0, N * stride);
+      orc_pool pool5 = pool;
+      pool5.k_base = k5;
+      pool5.v_base = v5;
+      uint32_t st5 = 0;
+      CHECK(orc_layer_restore_ordered(&pool5, &cfg, nb, n_req, table, total, fid, layer, stage, tot[0], 4096 * 7, 9, ext2,
+                                      tot2, sqe2, (uint32_t)tot[1], visit, &st5) == ORC_OK);
+      CHECK(memcmp(k5, k3, N * stride) == 0 && memcmp(v5, v3, N * stride) == 0);
+      free(k5);
+      free(v5);
+      free(visit);
+    }
     free(k3);
     free(v3);
     free(stage2);

@@ -70,6 +70,17 @@ MUTANTS = {
     "dense_ignores_sizes": ("if (x->obj_bytes != obj || x->n_chunks != chunks) return 0;", ""),
     "dense_ignores_offsets": ("if (x->sqe_base != want_sqe || x->table_off != want_tab) return 0;", ""),
     "dense_ignores_wrap": ("if (want_sqe > 0xffffffffull || want_tab > 0xffffffffull) return 0;", ""),
+    "order_descending": ("while (m > 0 && block_table[visit[m - 1]] > block_table[pos]) {",
+                         "while (m > 0 && block_table[visit[m - 1]] < block_table[pos]) {"),
+    "order_by_position": ("while (m > 0 && block_table[visit[m - 1]] > block_table[pos]) {",
+                          "while (m > 0 && visit[m - 1] > block_table[pos]) {"),
+    "order_sorts_invalid_tables": ("  if (st) return ORC_OK;\n  /* insertion sort", "  /* insertion sort"),
+    "ordered_uses_list_index": ("      const uint64_t pos = visit[k];", "      const uint64_t pos = k;"),
+    "ordered_ignores_dead_requests": ("      if (pos >= live_blocks) continue;", "      if (pos >= table_len) continue;"),
+    "ordered_object_offset_by_list": ("move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + j * bb, 0);",
+                                      "move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + (uint64_t)k * bb, 0);"),
+    "ordered_packs": ("move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + j * bb, 0);",
+                      "move_block(pool, plane + (uint64_t)id * pool->block_stride, obj + j * bb, 1);"),
     "table_off_ignored": ("uint64_t g = (uint64_t)x->table_off + j;", "uint64_t g = used - x->n_blocks + j;"),
     "sgl_v_plane_uses_k_address": ("table[i].addr = (kind == 0 ? k_addr : v_addr) + (uint64_t)b * pool->block_stride;",
                                    "table[i].addr = k_addr + (uint64_t)b * pool->block_stride;"),
