@@ -160,8 +160,8 @@ int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti
                     const uint32_t *d_file_id, uint32_t layer, uint32_t opcode, uint64_t stage_addr, uint32_t sgl_id,
                     tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t *d_status, void *stream);
 
-/* ---- a5 + a6: one layer's restore in ONE launch (retrieve_layer of sec. 3.4; "the CPU only loads
- * I/O kernels once per layer", sec. 1): extents from d_n_blocks, READ entries for `layer`, then the
+/* ---- a5 + a6: one layer's restore in ONE launch (retrieve_layer of sec. 3.4; sec. 1 has the CPU launch I/O
+ * kernels once per layer and no more): extents from d_n_blocks, READ entries for `layer`, then the
  * unpack of every hit block, as tutti_obj_layout + tutti_sqe_build(READ) + tutti_obj_unpack would (so requests
  * whose blocks run beyond table_len are skipped and reported as tutti_obj_unpack does).
  * Also writes d_extents[0..n_req) and d_totals[0..2).  d_stage must be device-accessible.
@@ -173,6 +173,35 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
                         uint32_t layer, const void *d_stage, uint64_t stage_cap, uint64_t stage_addr,
                         uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe,
                         uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status, void *stream);
+
+/* The same restore with the blocks visited in an order the caller names (sec. 3.4 fixes what a layer's restore
+ * moves, not the order in which its blocks are written; on a pool whose hit blocks are dense in memory, visiting
+ * them by ascending address keeps neighbouring wavefronts on neighbouring DRAM pages).  d_visit: table_len table
+ * positions, device memory, as tutti_table_order writes them; the launch visits position d_visit[0], d_visit[1],
+ * ... for the K plane, then the same for V.  A position that is not a block of a request that takes part
+ * (>= the blocks of the requests within table_len) is passed over; a position listed twice is restored twice (same
+ * bytes); a position not listed is not restored.  Everything else (entries, extents, totals, status bits, skip
+ * rules) as tutti_layer_restore, whose results a permutation of 0..table_len-1 reproduces bit for bit.  d_visit ==
+ * NULL is tutti_layer_restore itself.  A head-major pool that goes through LDS tiles keeps staging order (d_visit
+ * is not read). */
+int tutti_layer_restore_ordered(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks,
+                                uint32_t n_req, const uint32_t *d_block_table, uint32_t table_len,
+                                const uint32_t *d_file_id, uint32_t layer, const void *d_stage, uint64_t stage_cap,
+                                uint64_t stage_addr, uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals,
+                                tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget, const uint32_t *d_visit,
+                                uint32_t *d_status, void *stream);
+
+/* The visiting order of a block table by ascending block id (= ascending address in both planes), computed on the
+ * device in time linear in table_len + num_blocks: d_visit[k] <- the table position that holds the k-th smallest
+ * id.  A table with an id >= num_blocks or an id twice has no such order that a restore may use: the identity
+ * (d_visit[k] = k) is written and TUTTI_ST_BAD_BLOCK / TUTTI_ST_DUP_BLOCK are ORed into *d_status (may be NULL),
+ * as tutti_table_validate reports them.  d_work: device memory lent for the call, 16-byte aligned, work_bytes >=
+ * tutti_table_order_work_bytes(num_blocks) (about num_blocks / 4 bytes; TUTTI_ERANGE if smaller), contents
+ * garbage before and after; cleared by a kernel on `stream`, so the launches can be captured in a graph.  One
+ * table serves every layer of a request batch: compute the order once, restore all layers with it. */
+uint64_t tutti_table_order_work_bytes(uint32_t num_blocks);
+int tutti_table_order(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_visit,
+                      void *d_work, uint64_t work_bytes, uint32_t *d_status, void *stream);
 
 /* ---- one layer's save in ONE launch (store_layer of sec. 3.4): extents from d_n_blocks, WRITE entries for
  * `layer`, then the pack of every hit block with zero padding, as tutti_obj_layout + tutti_sqe_build(WRITE) +

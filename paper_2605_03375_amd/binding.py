@@ -52,7 +52,8 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_sq_state_init", "tutti_get_iocb", "tutti_sq_free_count", "tutti_reap_cqe", "tutti_iocb_completed",
            "tutti_wait_cqe_host", "tutti_iocbs_for_slack", "tutti_budget_for_slack", "tutti_io_domain_create",
            "tutti_io_domain_destroy", "tutti_table_validate_work_bytes", "tutti_table_validate_ws",
-           "tutti_table_validate_static"]
+           "tutti_table_validate_static", "tutti_layer_restore_ordered", "tutti_table_order",
+           "tutti_table_order_work_bytes"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
                  "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
 SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
@@ -131,6 +132,11 @@ def _declare(L, bench):
     L.tutti_layer_restore.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32, u32,
                                       vp, vp]
     L.tutti_layer_save.argtypes = L.tutti_layer_restore.argtypes
+    L.tutti_layer_restore_ordered.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, vp, u64, u64, u32, vp, vp, vp, u32,
+                                              u32, vp, vp, vp]
+    L.tutti_table_order.argtypes = [u32, vp, u32, vp, vp, u64, vp, vp]
+    L.tutti_table_order_work_bytes.argtypes = [u32]
+    L.tutti_table_order_work_bytes.restype = u64
     L.tutti_table_validate.argtypes = [u32, vp, u32, vp, vp]
     L.tutti_table_validate_ws.argtypes = [u32, vp, u32, vp, vp, u64, vp]
     L.tutti_table_validate_static.argtypes = [u32, vp, u32, vp, vp]
@@ -292,6 +298,26 @@ def tutti_layer_restore(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, 
                                             table_len, _p(d_file_id), layer, _p(d_stage), stage_cap, stage_addr,
                                             sgl_id, _p(d_extents), _p(d_totals), _p(d_sqe), sqe_cap, cu_budget,
                                             _p(d_status), _stream(stream)))
+
+
+def tutti_layer_restore_ordered(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage,
+                                stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, d_visit,
+                                cu_budget=0, d_status=None, stream=None):
+    return _check("tutti_layer_restore_ordered",
+                  lib().tutti_layer_restore_ordered(C.byref(pool), C.byref(cfg), _p(d_n_blocks), n_req,
+                                                    _p(d_block_table), table_len, _p(d_file_id), layer, _p(d_stage),
+                                                    stage_cap, stage_addr, sgl_id, _p(d_extents), _p(d_totals),
+                                                    _p(d_sqe), sqe_cap, cu_budget, _p(d_visit), _p(d_status),
+                                                    _stream(stream)))
+
+
+def tutti_table_order_work_bytes(num_blocks):
+    return int(lib().tutti_table_order_work_bytes(num_blocks))
+
+
+def tutti_table_order(num_blocks, d_block_table, table_len, d_visit, d_work, work_bytes, d_status=None, stream=None):
+    return _check("tutti_table_order", lib().tutti_table_order(num_blocks, _p(d_block_table), table_len, _p(d_visit),
+                                                               _p(d_work), work_bytes, _p(d_status), _stream(stream)))
 
 
 def tutti_sgl_table_build(pool, k_addr, v_addr, sgl_id, d_table, cap, d_status=None, stream=None):

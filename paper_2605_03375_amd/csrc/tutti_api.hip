@@ -218,6 +218,7 @@ int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t 
   m->layer = 0;
   m->file_stride = 0;
   m->ctx_cap = 0;
+  m->visit = nullptr;
 
   L->hnd_lds = false;
   L->tile_lds = 0;
@@ -391,6 +392,13 @@ hipError_t launch_layer(const Launch &L, uint64_t entry_quarters, uint32_t lds, 
   const Roles w = make_roles(L, entry_quarters, &n_wgs);
   return with_shape(L, [&](auto sh) {
     using S = decltype(sh);
+    if constexpr (DIR == kUnpack) {
+      if (m.visit) {  // the caller's visiting order
+        hipLaunchKernelGGL((k_layer<DIR, HND, S::U, S::NT, S::WG, true>), dim3(n_wgs), dim3(S::WG), lds, s, m, q, a,
+                           w);
+        return hipGetLastError();
+      }
+    }
     hipLaunchKernelGGL((k_layer<DIR, HND, S::U, S::NT, S::WG>), dim3(n_wgs), dim3(S::WG), lds, s, m, q, a, w);
     return hipGetLastError();
   });
@@ -501,7 +509,7 @@ int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t 
                 const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
                 const void *d_stage, uint64_t stage_cap, uint64_t stage_addr, uint32_t sgl_id,
                 tutti_extent *d_extents, uint64_t *d_totals, tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget,
-                uint32_t *d_status, void *stream) {
+                uint32_t *d_status, void *stream, const uint32_t *d_visit = nullptr) {
   uint32_t bb = 0;
   int rc = check_geometry(pool, cfg, &bb);
   if (rc) return rc;
@@ -522,6 +530,7 @@ int layer_entry(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t 
   MoveArgs m;
   rc = fill_move_args(pool, bb, d_block_table, table_len, d_stage, stage_cap, d_status, n_req, cfg->align, &L, &m);
   if (rc) return rc;
+  if (!L.hnd_lds) m.visit = d_visit;  // the tiles of the through-LDS path keep staging order
   Launch G;
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;
@@ -559,6 +568,17 @@ int tutti_layer_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const u
   return layer_entry<kUnpack>(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage,
                               stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, cu_budget, d_status,
                               stream);
+}
+
+int tutti_layer_restore_ordered(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks,
+                                uint32_t n_req, const uint32_t *d_block_table, uint32_t table_len,
+                                const uint32_t *d_file_id, uint32_t layer, const void *d_stage, uint64_t stage_cap,
+                                uint64_t stage_addr, uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals,
+                                tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget, const uint32_t *d_visit,
+                                uint32_t *d_status, void *stream) {
+  return layer_entry<kUnpack>(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage,
+                              stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, cu_budget, d_status,
+                              stream, d_visit);
 }
 
 int tutti_layer_save(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
@@ -924,6 +944,46 @@ int tutti_table_validate_static(uint32_t num_blocks, const uint32_t *d_block_tab
   const int rc = scratch_bits(&bits);
   if (rc) return rc;
   return validate_with_bitmap(num_blocks, d_block_table, table_len, d_status, bits, static_cast<hipStream_t>(stream));
+}
+
+// ---- visiting order by ascending block id
+// work memory: 64 words whose first holds what the check found, then the bitmap, then its prefix sums
+uint64_t tutti_table_order_work_bytes(uint32_t num_blocks) {
+  return 256u + 2u * tutti_table_validate_work_bytes(num_blocks);
+}
+
+int tutti_table_order(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len, uint32_t *d_visit,
+                      void *d_work, uint64_t work_bytes, uint32_t *d_status, void *stream) {
+  if (num_blocks == 0 || (table_len > 0 && (!d_block_table || !d_visit))) return TUTTI_EINVAL;
+  if (!d_work || !aligned16(d_work)) return TUTTI_EINVAL;
+  if (work_bytes < tutti_table_order_work_bytes(num_blocks)) return TUTTI_ERANGE;
+  if (table_len == 0) return TUTTI_OK;
+  const int cus = cu_count();
+  if (cus < 0) return cus;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint32_t n_words = (num_blocks + 31u) / 32u;
+  uint32_t *flags = static_cast<uint32_t *>(d_work);
+  uint32_t *bits = flags + 64;
+  uint32_t *prefix = bits + tutti_table_validate_work_bytes(num_blocks) / 4u;
+  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
+  uint64_t need = (64ull + n_words + kWgThreads - 1) / kWgThreads;
+  hipLaunchKernelGGL(k_bitmap_clear, dim3(static_cast<uint32_t>(need < lim ? need : lim)), dim3(kWgThreads), 0, s, flags,
+                     64u + n_words);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  need = (static_cast<uint64_t>(table_len) + kWgThreads - 1) / kWgThreads;
+  const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
+  hipLaunchKernelGGL(k_table_validate_bitmap, dim3(grid), dim3(kWgThreads), 0, s, d_block_table, table_len, num_blocks,
+                     bits, flags);
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  hipLaunchKernelGGL(k_bitmap_prefix, dim3(1), dim3(kPrefixThreads), 0, s, bits, n_words, prefix);
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  hipLaunchKernelGGL(k_table_rank, dim3(grid), dim3(kWgThreads), 0, s, d_block_table, table_len, bits, prefix, flags,
+                     d_visit, d_status);
+  e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
 #ifdef TUTTI_BENCH_BUILD

@@ -892,6 +892,9 @@ struct MoveArgs {
   uint32_t layer;
   uint64_t file_stride;
   uint64_t ctx_cap;
+  // ordered restore: table positions in the order in which their blocks are to be visited (table_len entries);
+  // unit u of the launch is (plane u / table_len, position visit[u % table_len]) instead of staging order
+  const uint32_t *visit;
 };
 
 
@@ -932,7 +935,9 @@ struct Item {
 
 // SEP: the extents came from the caller (lds_from_caller_extents): items are numbered by blk_off, the table is
 // indexed by the request's own table_off, and requests that cannot be honoured already have a zero-sized object.
-template <bool SEP>
+// ORD: the units are visited in the order a.visit lists (all K blocks, then all V blocks, each in that order);
+// a listed position that is not a block of a request that takes part is passed over.
+template <bool SEP, bool ORD = false>
 __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, uint32_t n_req, uint32_t it,
                                             uint32_t lane) {
   Item d;
@@ -940,12 +945,29 @@ __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, 
   const uint32_t u = it / S;  // (block, kind) unit in staging order
   d.s = it - u * S;
   const uint32_t *off = SEP ? l.blk_off : l.table_off;
-  const uint32_t r = find_owner(off, n_req, u >> 1);
-  const uint32_t toff = off[r];
-  d.n = off[r + 1] - toff;
-  const uint32_t v = u - 2u * toff;
-  d.kind = v >= d.n ? 1u : 0u;
-  d.j = v - d.kind * d.n;
+  uint32_t r, toff;
+  if (ORD) {
+    d.kind = u >= a.table_len ? 1u : 0u;
+    const uint32_t pos = rfl(a.visit[u - d.kind * a.table_len]);  // wave-uniform index: one word for the wavefront
+    if (pos >= l.table_off[n_req]) {  // beyond the blocks of the requests that take part
+      d.obj_ptr = nullptr;
+      d.obj_blk = nullptr;
+      d.obj_bytes = 0;
+      d.tab_idx = d.n = d.j = 0;
+      return d;
+    }
+    r = find_owner(l.table_off, n_req, pos);
+    toff = l.table_off[r];
+    d.n = l.table_off[r + 1] - toff;
+    d.j = pos - toff;
+  } else {
+    r = find_owner(off, n_req, u >> 1);
+    toff = off[r];
+    d.n = off[r + 1] - toff;
+    const uint32_t v = u - 2u * toff;
+    d.kind = v >= d.n ? 1u : 0u;
+    d.j = v - d.kind * d.n;
+  }
   d.obj_bytes = l.obj_bytes[r];
   d.tab_idx = (SEP ? l.table_off[r] : toff) + d.j;
   const uint64_t stage_off = l.stage_off[r];
@@ -967,7 +989,8 @@ __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, 
   d.obj_blk = d.obj_ptr + static_cast<uint64_t>(d.j) * a.block_bytes;
   if (!SEP && (stage_off > a.stage_cap || d.obj_bytes > (a.stage_cap - stage_off) / 2)) {
     // the request's objects do not fit: skip it, report once
-    if (lane == 0 && d.j == 0 && d.s == 0 && d.kind == 0 && a.status) atomicOr(a.status, TUTTI_ST_STAGE_CAP);
+    // (an ordered launch reports from its first workgroup instead: its list need not name the request's first block)
+    if (!ORD && lane == 0 && d.j == 0 && d.s == 0 && d.kind == 0 && a.status) atomicOr(a.status, TUTTI_ST_STAGE_CAP);
     d.obj_ptr = nullptr;
   } else if ((static_cast<uint64_t>(d.j) + 1) * a.block_bytes > d.obj_bytes) {
     d.obj_ptr = nullptr;  // the block would end beyond its object (caller-made extents only)
@@ -1092,8 +1115,9 @@ __device__ __forceinline__ void store_preloaded(const MoveArgs &a, const Item &d
 // Number of work items of a copy.  Staged mode: the scan (or the loader of caller-made extents) has already cut
 // the requests at table_len blocks.  Direct-to-block mode: one unit per recorded context.  The host checked that
 // the bound (2 * table_len, or the contexts the IOCBs hold) times the slices per block fits 32 bits.
-template <bool SEP>
+template <bool SEP, bool ORD = false>
 __device__ __forceinline__ uint32_t count_items(const MoveArgs &a, const ReqLds &l, uint32_t n_req) {
+  if (ORD) return 2u * a.table_len * a.slices_per_block;  // every listed position, for K and for V
   if (a.direct) {
     const uint64_t units = 2ull * l.table_off[n_req];
     return static_cast<uint32_t>(units < a.ctx_cap ? units : a.ctx_cap) * a.slices_per_block;
@@ -1101,18 +1125,18 @@ __device__ __forceinline__ uint32_t count_items(const MoveArgs &a, const ReqLds 
   return 2u * (SEP ? l.blk_off[n_req] : l.table_off[n_req]) * a.slices_per_block;
 }
 
-template <int DIR, bool HND, int U, int NT, bool SEP>
+template <int DIR, bool HND, int U, int NT, bool SEP, bool ORD = false>
 __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uint32_t n_req, uint32_t wg,
                                            uint32_t copy_wgs, const Preload<U> &pre) {
   constexpr uint32_t kSlice = kWave * 16u * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave_in_wg = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const uint32_t n_waves = copy_wgs * (blockDim.x / kWave);
-  const uint32_t n_items = count_items<SEP>(a, l, n_req);
+  const uint32_t n_items = count_items<SEP, ORD>(a, l, n_req);
 
   uint32_t it = item_wg(a, wg, copy_wgs) * (blockDim.x / kWave) + wave_in_wg;
   if (it >= n_items) return;
-  Item cur = decode_item<SEP>(a, l, n_req, it, lane);
+  Item cur = decode_item<SEP, ORD>(a, l, n_req, it, lane);
   uint32_t id = load_block_id(a, cur);
   bool first = true;
   for (;;) {
@@ -1121,14 +1145,15 @@ __device__ __forceinline__ void move_items(const MoveArgs a, const ReqLds l, uin
     Item nxt = cur;
     uint32_t nid = a.num_blocks;
     if (more) {
-      nxt = decode_item<SEP>(a, l, n_req, nit, lane);
+      nxt = decode_item<SEP, ORD>(a, l, n_req, nit, lane);
       nid = load_block_id(a, nxt);
     }
     // the preloaded bytes were read where the item's slice sits when the extents are the library's own; extents
     // from the caller (and the files of the direct-to-block mode) may put it elsewhere: then the slice is loaded
     // from where they say
     const bool preloaded = DIR == kUnpack && first && pre.valid &&
-                           ((!SEP && !a.direct) || cur.obj_blk + static_cast<uint64_t>(cur.s) * kSlice == pre.src);
+                           ((!SEP && !ORD && !a.direct) ||
+                            cur.obj_blk + static_cast<uint64_t>(cur.s) * kSlice == pre.src);
     if (preloaded)
       store_preloaded<HND, U, NT>(a, cur, id, lane, pre);
     else
@@ -1316,7 +1341,9 @@ struct Roles {
   uint32_t copy_wgs;    // there are more passes of entries than copy workgroups)
 };
 
-template <int DIR, bool HND, int U, int NT, int WG>
+// ORD (restore only): the blocks are visited in the order m.visit lists instead of staging order; the first slices
+// cannot be preloaded then (where they sit depends on the list).
+template <int DIR, bool HND, int U, int NT, int WG, bool ORD = false>
 __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer(const MoveArgs m, const SqeArgs q, const LayoutArgs a, const Roles w) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, a.n_req);
@@ -1324,7 +1351,7 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer(const M
   const bool copies = wg < w.copy_wgs;
   Preload<U> pre;
   pre.valid = false;
-  if (DIR == kUnpack && copies) pre = preload_first<U, NT>(m, wg, w.copy_wgs);  // in flight during the scan
+  if (DIR == kUnpack && !ORD && copies) pre = preload_first<U, NT>(m, wg, w.copy_wgs);  // in flight during the scan
   if (threadIdx.x < kWave) {
     const bool publish = blockIdx.x == 0;
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
@@ -1334,7 +1361,14 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer(const M
   SqeHead head;
   head.live = false;
   if (blockIdx.x < w.sqe_wgs) head = sqe_head(q, l, a.n_req, 0);
-  if (copies) move_items<DIR, HND, U, NT, false>(m, l, a.n_req, wg, w.copy_wgs, pre);
+  if (ORD && wg == 0 && m.status) {
+    // requests whose objects do not fit the staging buffer are skipped by every item: report them here, once
+    for (uint32_t r = threadIdx.x; r < a.n_req; r += WG)
+      if (l.table_off[r + 1] > l.table_off[r] &&
+          (l.stage_off[r] > m.stage_cap || l.obj_bytes[r] > (m.stage_cap - l.stage_off[r]) / 2))
+        atomicOr(m.status, TUTTI_ST_STAGE_CAP);
+  }
+  if (copies) move_items<DIR, HND, U, NT, false, ORD>(m, l, a.n_req, wg, w.copy_wgs, pre);
   if (blockIdx.x < w.sqe_wgs) emit_sqes(q, l, a.n_req, 0, w.sqe_wgs, head);
 }
 
@@ -1485,6 +1519,54 @@ __global__ __launch_bounds__(kWgThreads) void k_table_validate_bitmap(const uint
 #pragma unroll
   for (uint32_t d = kWave / 2; d >= 1; d >>= 1) any |= __shfl_xor(any, d, kWave);
   if (lane == 0 && any && status) atomicOr(status, any);
+}
+
+// The visiting order of a table by ascending block id, from the bitmap of its ids: the rank of an id is the number
+// of set bits below it.  k_bitmap_prefix (ONE workgroup) turns the per-word bit counts into exclusive prefix sums;
+// k_table_rank then places every table position at its id's rank.  If the check that set the bits found an id out
+// of range or twice (flags != 0) the ranks are not a permutation and the identity order is written instead.
+constexpr uint32_t kPrefixThreads = 1024;
+
+__global__ __launch_bounds__(kPrefixThreads) void k_bitmap_prefix(const uint32_t *__restrict__ bits, uint32_t n_words,
+                                                                   uint32_t *__restrict__ prefix) {
+  __shared__ uint32_t part[kPrefixThreads];
+  const uint32_t t = threadIdx.x;
+  const uint32_t per = (n_words + kPrefixThreads - 1) / kPrefixThreads;  // consecutive words per thread
+  const uint32_t lo = t * per < n_words ? t * per : n_words;
+  const uint32_t hi = lo + per < n_words ? lo + per : n_words;
+  uint32_t sum = 0;
+  for (uint32_t i = lo; i < hi; ++i) sum += static_cast<uint32_t>(__popc(bits[i]));
+  part[t] = sum;
+  __syncthreads();
+  for (uint32_t d = 1; d < kPrefixThreads; d <<= 1) {  // inclusive scan of the per-thread sums
+    const uint32_t v = t >= d ? part[t - d] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  uint32_t run = part[t] - sum;  // bits in front of this thread's words
+  for (uint32_t i = lo; i < hi; ++i) {
+    prefix[i] = run;
+    run += static_cast<uint32_t>(__popc(bits[i]));
+  }
+}
+
+__global__ __launch_bounds__(kWgThreads) void k_table_rank(const uint32_t *__restrict__ table, uint32_t n,
+                                                            const uint32_t *__restrict__ bits,
+                                                            const uint32_t *__restrict__ prefix,
+                                                            const uint32_t *__restrict__ flags, uint32_t *__restrict__ visit,
+                                                            uint32_t *__restrict__ status) {
+  const uint32_t found = flags[0];  // what the check in front of this kernel found
+  if (found && status && blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, found);
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    if (found) {
+      visit[i] = i;
+    } else {
+      const uint32_t id = table[i];
+      const uint32_t below = bits[id >> 5] & ((1u << (id & 31u)) - 1u);
+      visit[prefix[id >> 5] + static_cast<uint32_t>(__popc(below))] = i;
+    }
+  }
 }
 
 #ifdef TUTTI_BENCH_BUILD

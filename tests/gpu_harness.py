@@ -205,7 +205,8 @@ def check_sqe(orc, c, ext, o_ext, o_tot, layer=0, stage_addr=0x7F1200000000, sgl
 
 
 def check_layer_restore(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000, sgl_id=7, seed=5, sqe_cap=None,
-                        stage_cap=None, table_len=None):
+                        stage_cap=None, table_len=None, visit=None):
+    """visit: table positions in visiting order (numpy): both sides run their ordered restore on the same list."""
     tl = c.table.size if table_len is None else table_len
     o_ext0, o_tot0 = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
     nbytes = max(int(o_tot0[0]), 16)
@@ -220,13 +221,26 @@ def check_layer_restore(orc, c, layer=0, cu_budget=0, stage_addr=0x7F1200000000,
     tot = torch.zeros(2, dtype=torch.int64, device=DEV)
     sqe = torch.full((max(cap, 1) * 64,), 0x3C, dtype=torch.uint8, device=DEV)
     st = new_status()
-    B.tutti_layer_restore(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, tl, c.d_file_id,
-                          layer, stage, scap, stage_addr, sgl_id, ext, tot, sqe, cap, cu_budget, st)
-    torch.cuda.synchronize()
     ok, ov = c.k_host.copy(), c.v_host.copy()
-    o_ext, o_tot, o_sqe, o_st = orc.layer_restore(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks, c.table,
-                                                  c.file_id, layer, stage.cpu().numpy(), stage_addr, sgl_id, cap,
-                                                  stage_cap=scap, table_len=tl)
+    if visit is None:
+        B.tutti_layer_restore(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, tl, c.d_file_id,
+                              layer, stage, scap, stage_addr, sgl_id, ext, tot, sqe, cap, cu_budget, st)
+        torch.cuda.synchronize()
+        o_ext, o_tot, o_sqe, o_st = orc.layer_restore(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks, c.table,
+                                                      c.file_id, layer, stage.cpu().numpy(), stage_addr, sgl_id, cap,
+                                                      stage_cap=scap, table_len=tl)
+    else:
+        visit = np.ascontiguousarray(visit, np.uint32)
+        assert visit.size >= tl
+        d_visit = to_dev(visit) if visit.size else torch.zeros(1, dtype=torch.int32, device=DEV)
+        B.tutti_layer_restore_ordered(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, tl,
+                                      c.d_file_id, layer, stage, scap, stage_addr, sgl_id, ext, tot, sqe, cap, d_visit,
+                                      cu_budget, st)
+        torch.cuda.synchronize()
+        o_ext, o_tot, o_sqe, o_st = orc.layer_restore_ordered(c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks,
+                                                              c.table, c.file_id, layer, stage.cpu().numpy(),
+                                                              stage_addr, sgl_id, cap, visit, stage_cap=scap,
+                                                              table_len=tl)
     assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes()
     assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot)
     n_written = min(n_sqe, cap)

@@ -1098,6 +1098,25 @@ def check_visit_order(orc, seed=67):
                                                          fid, 2, stage, 4096, 7, int(tot[1]), visit)
             assert st_a == st_b == 0 and np.array_equal(ka, kb) and np.array_equal(va, vb)
             assert ea.tobytes() == eb.tobytes() and sa.tobytes() == sb.tobytes() and np.array_equal(ta, tb)
+    # a padded pool (the block stride is not the block size) with ids out of range, the first of them num_blocks
+    # itself (the planes hold one spare block here): again what the plain restore gives, spare block untouched
+    stride = bb + 48
+    n = np.array([3, 4], np.uint32)
+    table = np.array([9, N, 2, 63, 0, 0xFFFFFFFF, 17], np.uint32)
+    cfg = orc.make_cfg(A, 2 * A, 2)
+    k0, v0 = _planes(rng, N + 1, stride)
+    ext, tot = orc.obj_layout(_pool(orc, T, h, d, e, N, k0, v0, stride=stride), cfg, n)
+    stage = rng.integers(0, 256, int(tot[0]), dtype=np.uint8)
+    ka, va = k0.copy(), v0.copy()
+    ea, ta, sa, st_a = orc.layer_restore(_pool(orc, T, h, d, e, N, ka, va, stride=stride), cfg, n, table, [8, 9], 1,
+                                         stage, 0, 0, int(tot[1]))
+    kb, vb = k0.copy(), v0.copy()
+    eb, tb, sb, st_b = orc.layer_restore_ordered(_pool(orc, T, h, d, e, N, kb, vb, stride=stride), cfg, n, table, [8, 9],
+                                                 1, stage, 0, 0, int(tot[1]), np.array([6, 1, 0, 5, 4, 3, 2], np.uint32))
+    assert st_a == st_b == orc.ST_BAD_BLOCK and np.array_equal(ka, kb) and np.array_equal(va, vb)
+    assert np.array_equal(kb[N * stride:], k0[N * stride:]) and np.array_equal(vb[N * stride:], v0[N * stride:])
+    assert not np.array_equal(kb, k0) and not np.array_equal(kb, vb)
+    assert sa.tobytes() == sb.tobytes() and np.all(sb["opcode"] == orc.OP_READ)
     # a list that is not a permutation: listed positions are restored, the others are not (NHD: a block is one slice)
     n = np.array([4, 3], np.uint32)
     table = np.array([10, 3, 7, 20, 1, 30, 12], np.uint32)

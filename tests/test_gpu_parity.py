@@ -1134,6 +1134,181 @@ def test_table_validate(orc, H):
     assert ei.value.code == B.ERANGE
 
 
+def test_table_order(orc, H):
+    """The visiting order by ascending block id, device against oracle, element by element: clean tables of many
+    sizes (pool sizes that are not multiples of 32, ids in the first and last bitmap words), tables the check objects
+    to (identity order plus the status bits), work memory handed over full of garbage."""
+    say("table order")
+    rng = np.random.default_rng(71)
+
+    def both(num_blocks, table):
+        table = np.ascontiguousarray(table, np.uint32)
+        nbytes = B.tutti_table_order_work_bytes(num_blocks)
+        assert nbytes % 256 == 0
+        work = torch.full((nbytes + 256,), 0xA5, dtype=torch.uint8, device=H.DEV)
+        d_visit = torch.full((table.size + 8,), -7, dtype=torch.int32, device=H.DEV)
+        st = H.new_status()
+        B.tutti_table_order(num_blocks, H.to_dev(table) if table.size else None, table.size, d_visit, work, nbytes, st)
+        torch.cuda.synchronize()
+        want, want_st = orc.table_order(num_blocks, table)
+        got = d_visit.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got[: table.size], want), (num_blocks, table.size)
+        assert np.all(d_visit.cpu().numpy()[table.size:] == -7), "wrote beyond table_len"
+        assert int(st.item()) == want_st
+        assert bool((work[nbytes:] == 0xA5).all()), "wrote beyond the bytes it was lent"
+        return want_st
+
+    assert both(16, []) == 0 and both(1, [0]) == 0 and both(33, [32, 0, 31]) == 0
+    assert both(1, [0, 0]) == B.ST_DUP_BLOCK and both(4, [1, 7]) == B.ST_BAD_BLOCK
+    assert both(40, [3, 99, 3, 1]) == (B.ST_BAD_BLOCK | B.ST_DUP_BLOCK)
+    for n in (2, 63, 64, 65, 1000, 4097, 70_001):
+        for N in (n, n + 1, 3 * n + 7, 32 * ((3 * n + 31) // 32)):
+            assert both(N, rng.permutation(N)[:n]) == 0
+        t = rng.permutation(2 * n)[:n]
+        t[n - 1] = t[0]
+        assert both(2 * n, t) == B.ST_DUP_BLOCK
+        t[n // 2] = 2 * n
+        assert both(2 * n, t) == (B.ST_BAD_BLOCK | B.ST_DUP_BLOCK)
+    for w in (W.llama8b_32k(), W.batch64_zipf(), W.llama70b_128k()):     # the tables of configs 2, 3, 4
+        assert both(w.shape.num_blocks, w.block_table) == 0
+    N = (1 << 22) + 5                                                    # a million entries over four million blocks
+    assert both(N, rng.permutation(N)[: 1 << 20]) == 0
+    tab = H.to_dev(np.arange(8, dtype=np.uint32))
+    vis = torch.zeros(8, dtype=torch.int32, device=H.DEV)
+    work = torch.zeros(B.tutti_table_order_work_bytes(64), dtype=torch.uint8, device=H.DEV)
+    with pytest.raises(B.TuttiError) as ei:
+        B.tutti_table_order(64, tab, 8, vis, work, work.numel() - 1)
+    assert ei.value.code == B.ERANGE
+    for bad in (dict(num_blocks=0), dict(d_visit=None), dict(d_block_table=None), dict(d_work=None)):
+        kw = dict(num_blocks=64, d_block_table=tab, table_len=8, d_visit=vis, d_work=work, work_bytes=work.numel())
+        kw.update(bad)
+        with pytest.raises(B.TuttiError) as ei:
+            B.tutti_table_order(**kw)
+        assert ei.value.code == B.EINVAL
+
+
+ORDERED_SHAPES = [
+    # T, h, d, e, N, n_blocks, layout, pad
+    (16, 8, 128, 2, 300, [40, 0, 7, 25, 1], 0, 0),     # 32 KiB blocks: eight whole slices each
+    (16, 8, 128, 2, 300, [40, 0, 7, 25, 1], 1, 0),     # head-major, rows of 256 bytes: moved row by row, in order
+    (16, 5, 40, 2, 200, [7, 0, 33, 1, 2], 0, 48),      # 6400-byte blocks: a ragged last slice, padded objects, stride
+    (16, 2, 16, 2, 128, [9, 30, 2], 1, 0),             # head-major through LDS tiles: the order is not used
+]
+
+
+@pytest.mark.parametrize("shape", ORDERED_SHAPES, ids=lambda s: f"T{s[0]}h{s[1]}d{s[2]}L{s[6]}")
+def test_layer_restore_in_a_given_order(orc, H, shape):
+    """tutti_layer_restore_ordered against the oracle's ordered restore on the same list: the order the device
+    computes for the table, a reversed and a shuffled list, lists with positions out of range, twice and missing,
+    a table shorter than the requests claim, capacities too small, ids out of range, CU budgets."""
+    T, h, d, e, N, nb, layout, pad = shape
+    say(f"ordered restore T={T} h={h} d={d} layout={layout}")
+    rng = np.random.default_rng(sum(shape[:5]))
+    n = int(np.sum(nb))
+    c = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=nb, table=rng.permutation(N)[:n], chunk=8192, L=3,
+                    layout=layout, pad=pad, name="ordered")
+    through_lds = layout == 1 and d * e < 128
+    # the device's own order for this table, checked against the oracle's, then used by both
+    work = torch.zeros(B.tutti_table_order_work_bytes(N), dtype=torch.uint8, device=H.DEV)
+    d_visit = torch.zeros(n, dtype=torch.int32, device=H.DEV)
+    B.tutti_table_order(N, c.d_table, n, d_visit, work, work.numel())
+    torch.cuda.synchronize()
+    by_id = d_visit.cpu().numpy().view(np.uint32).copy()
+    assert np.array_equal(by_id, orc.table_order(N, c.table)[0])
+    perms = [by_id, by_id[::-1].copy(), rng.permutation(n).astype(np.uint32), np.arange(n, dtype=np.uint32)]
+    for k, visit in enumerate(perms):
+        for budget in (0, 3):
+            H.check_layer_restore(orc, c, layer=k % 3, cu_budget=budget, visit=visit, seed=20 + k)
+    if through_lds:
+        return            # lists that are not permutations mean something only where the list is read
+    # lists that are not permutations: out of range, twice, missing
+    odd = by_id.copy()
+    odd[0] = n
+    odd[1] = 0xFFFFFFFF
+    odd[2] = odd[3]
+    odd[n - 1] = odd[n - 2]
+    H.check_layer_restore(orc, c, visit=odd, seed=31)
+    H.check_layer_restore(orc, c, visit=np.zeros(n, np.uint32), seed=32)
+    # a table shorter than the requests claim: the list still has table_len entries, some now beyond the live blocks
+    for tl in (n - 1, int(nb[0]), int(nb[0]) - 1, 0):
+        H.check_layer_restore(orc, c, table_len=tl, visit=rng.permutation(n).astype(np.uint32), seed=33)
+    # staging and entry capacities too small, with the first block of the request that does not fit not listed
+    o_ext, _ = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    last = c.n_req - 1
+    cap = int(o_ext["stage_off"][last]) + 16
+    H.check_layer_restore(orc, c, stage_cap=cap, sqe_cap=3, visit=by_id, seed=34)
+    skip_first = by_id.copy()
+    skip_first[skip_first == int(o_ext["table_off"][last])] = 0
+    H.check_layer_restore(orc, c, stage_cap=cap, visit=skip_first, seed=35)
+    # ids out of range in the table
+    bad = c.table.copy()
+    bad[[1, n // 2]] = [N, 0xFFFFFFFF]
+    cb = H.LayerCase(T=T, h=h, d=d, e=e, N=N, n_blocks=nb, table=bad, chunk=8192, L=3, layout=layout, pad=pad,
+                     name="ordered_bad_ids")
+    H.check_layer_restore(orc, cb, visit=by_id, seed=36)
+    # no list: the plain restore
+    st = H.new_status()
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    k3, v3 = c.k_dev.clone(), c.v_dev.clone()
+    tot0 = int(orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)[1][0])
+    stage = torch.randint(0, 256, (tot0,), dtype=torch.uint8, device=H.DEV)
+    ext = torch.zeros(c.n_req * 32, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    B.tutti_layer_restore_ordered(c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, n, c.d_file_id,
+                                  0, stage, tot0, 0, 1, ext, tot, None, 0, None, 0, st)
+    B.tutti_layer_restore(c.gpu_pool(k3, v3), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, n, c.d_file_id, 0, stage,
+                          tot0, 0, 1, ext, tot, None, 0, 0, st)
+    torch.cuda.synchronize()
+    assert torch.equal(k2, k3) and torch.equal(v2, v3) and int(st.item()) == 0
+
+
+def test_ordered_restore_of_a_whole_layer_matches_the_plain_one(orc, H):
+    """Config 3 (64 requests, fragmented pool) at full size, in bench.py's launch shape: with the device's own order
+    the ordered restore writes exactly what the plain restore writes (planes, entries, extents, status)."""
+    say("ordered restore, config 3 full size")
+    w = W.batch64_zipf()
+    c = H.LayerCase.from_workload(w, fill="tags")
+    n = c.table.size
+    work = torch.zeros(B.tutti_table_order_work_bytes(c.N), dtype=torch.uint8, device=H.DEV)
+    d_visit = torch.zeros(n, dtype=torch.int32, device=H.DEV)
+    st = H.new_status()
+    B.tutti_table_order(c.N, c.d_table, n, d_visit, work, work.numel(), st)
+    o_ext, o_tot = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    stage = H.as_u8(W.device_values(5, int(o_tot[0]) // 2, "bf16", H.DEV))
+    n_sqe = int(o_tot[1])
+    outs = []
+    for ordered in (False, True):
+        k2, v2 = torch.zeros_like(c.k_dev), torch.zeros_like(c.v_dev)
+        ext = torch.zeros(c.n_req * 32, dtype=torch.uint8, device=H.DEV)
+        tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+        sqe = torch.zeros(n_sqe * 64, dtype=torch.uint8, device=H.DEV)
+        args = (c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table, n, c.d_file_id, 7, stage,
+                stage.numel(), 0x7F0000000000, 3, ext, tot, sqe, n_sqe)
+        if ordered:
+            B.tutti_layer_restore_ordered(*args, d_visit, 0, st)
+        else:
+            B.tutti_layer_restore(*args, 0, st)
+        torch.cuda.synchronize()
+        outs.append((k2, v2, ext, tot, sqe))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    assert int(st.item()) == 0
+    # and the plain one against the oracle on sampled blocks: the object bytes of block j of request r sit in block
+    # table[table_off + j] of both planes
+    stage_h = stage.cpu().numpy()
+    k_h, v_h = outs[1][0].cpu().numpy(), outs[1][1].cpu().numpy()
+    rng = np.random.default_rng(3)
+    for r in rng.choice(c.n_req, size=12, replace=False):
+        x = o_ext[r]
+        if x["n_blocks"] == 0:
+            continue
+        for j in {0, int(x["n_blocks"]) - 1, int(rng.integers(0, x["n_blocks"]))}:
+            bid = int(c.table[int(x["table_off"]) + j])
+            for kind, plane in ((0, k_h), (1, v_h)):
+                src = int(x["stage_off"]) + kind * int(x["obj_bytes"]) + j * c.bb
+                assert np.array_equal(plane[bid * c.stride: bid * c.stride + c.bb], stage_h[src: src + c.bb])
+
+
 def test_table_validate_with_bitmap_can_be_captured_in_a_graph(orc, H):
     """The linear-time check clears its bitmap with a kernel (no memset node), so both of its forms can be captured
     in a HIP graph; every replay must report what the eager call reports, with eager work between the replays and

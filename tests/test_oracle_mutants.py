@@ -17,16 +17,20 @@ MUTANTS = {
     "align_down": ("return (x + a - 1) / a * a;", "return x / a * a;"),
     "chunks_floor": ("uint64_t chunks = (obj + C - 1) / C;", "uint64_t chunks = obj / C;"),
     "table_off_is_request": ("extents[r].table_off = (uint32_t)n_tab;", "extents[r].table_off = r;"),
-    "k_v_planes_swapped": ("kind == 0 ? pool->k_base : pool->v_base", "kind == 1 ? pool->k_base : pool->v_base"),
+    "k_v_planes_swapped": ("kind == 0 ? pool->k_base : pool->v_base", "kind == 1 ? pool->k_base : pool->v_base", 0),
+    "ordered_k_v_planes_swapped": ("kind == 0 ? pool->k_base : pool->v_base",
+                                   "kind == 1 ? pool->k_base : pool->v_base", 1),
     "v_object_at_k": ("uint8_t *obj = stage + x->stage_off + kind * x->obj_bytes;",
                       "uint8_t *obj = stage + x->stage_off;"),
     "hnd_ignored": ("? in_obj : ((i * T + t) * d) * e;", "? in_obj : ((t * h + i) * d) * e;"),
     "hnd_transposed_wrong": ("((i * T + t) * d) * e;", "((i * h + t) * d) * e;"),
-    "stride_ignored": ("plane + (uint64_t)id * pool->block_stride", "plane + (uint64_t)id * bb"),
+    "stride_ignored": ("plane + (uint64_t)id * pool->block_stride", "plane + (uint64_t)id * bb", 0),
+    "ordered_stride_ignored": ("plane + (uint64_t)id * pool->block_stride", "plane + (uint64_t)id * bb", 1),
     "object_uses_stride": ("obj + (uint64_t)j * bb, to_object", "obj + (uint64_t)j * pool->block_stride, to_object"),
     "padding_not_zeroed": ("memset(obj + filled, 0,", "if (0) memset(obj + filled, 0,"),
     "table_offset_dropped": ("uint32_t id = block_table[g];", "uint32_t id = block_table[j];"),
-    "block_bound_off_by_one": ("if (id >= pool->num_blocks) {", "if (id > pool->num_blocks) {"),
+    "block_bound_off_by_one": ("if (id >= pool->num_blocks) {", "if (id > pool->num_blocks) {", 0),
+    "ordered_block_bound_off_by_one": ("if (id >= pool->num_blocks) {", "if (id > pool->num_blocks) {", 1),
     "unpack_direction": ("(uint8_t *)(uintptr_t)stage, stage_cap, 0, 0, UINT64_MAX,",
                          "(uint8_t *)(uintptr_t)stage, stage_cap, 1, 0, UINT64_MAX,"),
     "file_off_layer_kind": ("s.file_off = (2ull * layer + kind)", "s.file_off = (2ull * kind + layer)", 0),
@@ -146,7 +150,9 @@ MUTANTS = {
     "validate_bad_ids_as_duplicates": ("    if (id >= num_blocks) {\n      st |= ORC_ST_BAD_BLOCK;\n    } else if (seen[id]) {",
                                        "    if (id >= num_blocks) {\n      st |= ORC_ST_BAD_BLOCK | ORC_ST_DUP_BLOCK;\n    } else if (seen[id]) {"),
     "restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
-                             "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);"),
+                             "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);", 0),
+    "ordered_restore_builds_write": ("ORC_OP_READ, stage_addr, sgl_id, sqe, sqe_cap, status);",
+                                     "ORC_OP_WRITE, stage_addr, sgl_id, sqe, sqe_cap, status);", 1),
 }
 
 
