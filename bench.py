@@ -306,6 +306,9 @@ def main():
     if args.pinned_stage:
         out["pinned_host_stage"] = pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload_layer,
                                               n_sqe_layer, dev)
+    if not args.no_extra:
+        out["restore_address_order"] = ordered_restore(torch, B, s.num_blocks, pools, cfg, d_n, d_tab, n_tab, d_fid,
+                                                       stages, payload_layer, n_sqe_layer, dev)
     if not args.no_other_configs:
         del pools, planes, stages, restore_layers, save_layers, save_layers_unfused
         torch.cuda.empty_cache()
@@ -317,6 +320,54 @@ def main():
         out["cpu_baseline"] = cpu2
         out["cpu_baseline"]["other_configs"] = cpu_baseline_others(W)
     print(json.dumps(out), flush=True)
+
+
+def ordered_restore(torch, B, num_blocks, pools, cfg, d_n, d_tab, n_tab, d_fid, stages, payload, n_sqe, dev, reps=5):
+    """Config 2's restore again, once in table order (tutti_layer_restore) and once with the blocks visited by
+    ascending pool address (tutti_table_order once, then tutti_layer_restore_ordered per layer), back to back on
+    the same buffers."""
+    L = len(pools)
+    ext = torch.zeros(32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    sqe = torch.zeros(max(n_sqe, 1) * 64, dtype=torch.uint8, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    d_visit = torch.zeros(n_tab, dtype=torch.int32, device=dev)
+    work = torch.empty(B.tutti_table_order_work_bytes(num_blocks), dtype=torch.uint8, device=dev)
+
+    def order():
+        B.tutti_table_order(num_blocks, d_tab, n_tab, d_visit, work, work.numel(), status)
+
+    def train(ordered):
+        for l in range(L):
+            if ordered:
+                B.tutti_layer_restore_ordered(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload,
+                                              stages[l].data_ptr(), 1, ext, tot, sqe, n_sqe, d_visit, 0, status)
+            else:
+                B.tutti_layer_restore(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload,
+                                      stages[l].data_ptr(), 1, ext, tot, sqe, n_sqe, 0, status)
+
+    def timed(fn, per):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / per)
+        return median(ts)
+
+    order_us = timed(order, 1)
+    plain = timed(lambda: train(False), L)
+    ordered = timed(lambda: train(True), L)
+    plain2 = timed(lambda: train(False), L)
+    assert int(status.item()) == 0
+    res = {"table_order_us_per_layer": round(min(plain, plain2), 2), "address_order_us_per_layer": round(ordered, 2),
+           "gain_pct": round(100 * (1 - ordered / min(plain, plain2)), 2), "table_order_call_us_once": round(order_us, 2)}
+    log(f"[bench] restore, blocks visited by address: {res}")
+    return res
 
 
 def restore_leg(torch, B, w, dev, max_layers, reps=5):
@@ -347,29 +398,48 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
     sqe = torch.zeros(n_sqe * 64, dtype=torch.uint8, device=dev)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
 
-    def train():
+    # the table's address order, computed once on the device and used by every layer of the ordered variant
+    d_visit = torch.zeros(max(n_tab, 1), dtype=torch.int32, device=dev)
+    work = torch.empty(B.tutti_table_order_work_bytes(s.num_blocks), dtype=torch.uint8, device=dev)
+
+    def order():
+        B.tutti_table_order(s.num_blocks, d_tab, n_tab, d_visit, work, work.numel(), status)
+
+    def train(ordered=False):
         for l in range(L):
             st = stages[l % len(stages)]
-            B.tutti_layer_restore(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, st, payload,
-                                  st.data_ptr(), 1, ext, tot, sqe, n_sqe, 0, status)
+            if ordered:
+                B.tutti_layer_restore_ordered(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, st, payload,
+                                              st.data_ptr(), 1, ext, tot, sqe, n_sqe, d_visit, 0, status)
+            else:
+                B.tutti_layer_restore(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, st, payload,
+                                      st.data_ptr(), 1, ext, tot, sqe, n_sqe, 0, status)
 
-    train()
-    torch.cuda.synchronize()
-    times = []
-    for _ in range(reps):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        train()
-        b.record()
+    def timed(fn, per):
+        fn()
         torch.cuda.synchronize()
-        times.append(a.elapsed_time(b) * 1e3 / L)
-    us = median(times)
+        times = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b) * 1e3 / per)
+        return median(times)
+
+    us = timed(train, L)
+    order_us = timed(order, 1)
+    us_ordered = timed(lambda: train(True), L)
     assert int(status.item()) == 0 and int(tot[1].item()) == n_sqe
     res = {"layers_resident": L, "layers_model": s.num_layers, "pool_blocks": s.num_blocks, "requests": w.n_req,
            "blocks_per_layer": n_tab, "payload_bytes_per_layer": payload, "entries_per_layer": n_sqe,
            "us_per_layer": round(us, 2), "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
            "traffic_GBps": round(2 * payload / (us * 1e-6) / 1e9, 1),
-           "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}
+           "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+           "address_order": {"us_per_layer": round(us_ordered, 2), "gain_pct": round(100 * (1 - us_ordered / us), 2),
+                             "table_order_us_once": round(order_us, 2),
+                             "pct_hbm_peak": round(100 * 2 * payload / (us_ordered * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}}
     log(f"[bench] {w.name}: {res}")
     return res
 
