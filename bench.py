@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--no-length-sweep", action="store_true", help="skip the 1K..128K-token prefix-length sweep")
     ap.add_argument("--scatter-sweep", action="store_true",
                     help="also sweep the granularity, the order and the launch shape of tutti_scatter_baseline")
+    ap.add_argument("--hnd-sweep", action="store_true",
+                    help="also time head-major pools of four row sizes, moved 16 bytes per lane and through LDS tiles")
     ap.add_argument("--pinned-stage", action="store_true",
                     help="also time the restore with the staging buffer in pinned host memory (host-link bound)")
     ap.add_argument("--write-lut", default="", help="also write the slack table (JSON) to this path")
@@ -303,6 +305,8 @@ def main():
         out["scatter_orders_32KiB"] = scatter_orders(torch, B, stages, payload_layer, dev)
         out["scatter_shapes_32KiB"] = scatter_shapes(torch, B, w, stages, payload_layer, dev)
         out["visit_order"] = visit_order(torch, B, W, dev)
+    if args.hnd_sweep:
+        out["head_major_rows"] = hnd_rows(torch, B, w, stages, dev)
     if args.pinned_stage:
         out["pinned_host_stage"] = pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload_layer,
                                               n_sqe_layer, dev)
@@ -524,6 +528,62 @@ def ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid, payload,
     done = int(cq[:4].view(torch.int32)[0].item())
     assert int(status.item()) == 0 and done == depth, (int(status.item()), done, depth)
     log(f"[bench] rings: {res}")
+    return res
+
+
+def hnd_rows(torch, B, w, stages, dev, layers=8, reps=5):
+    """Head-major pools ([h][T][d] blocks) of config 2's block size (32 KiB, 16 tokens) with (token, head) rows of
+    256, 128, 64 and 32 bytes: tutti_obj_unpack / tutti_obj_pack alone, once moved 16 bytes per lane straight
+    between the two orders and once through token tiles in LDS (the choice forced with the measurement library's
+    switch; the product library takes LDS for rows shorter than 128 bytes).  Random table of 2048 blocks."""
+    s = w.shape
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    n_tab = int(w.block_table.size)
+    payload = 2 * n_tab * bb
+    L = min(layers, len(stages))
+    plane_bytes = s.num_blocks * bb
+    planes = [(torch.empty(plane_bytes, dtype=torch.uint8, device=dev),
+               torch.empty(plane_bytes, dtype=torch.uint8, device=dev)) for _ in range(L)]
+    d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
+    d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
+    ext = torch.zeros(32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(2, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
+    res = {}
+    B.use_bench_library(True)
+    try:
+        for heads, dim in ((8, 128), (16, 64), (32, 32), (64, 16)):
+            row = dim * s.elt_bytes
+            geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=heads, head_dim=dim,
+                        elt_bytes=s.elt_bytes, pool_layout=1)
+            pools = [B.make_pool(k, v, **geom) for k, v in planes]
+            B.tutti_obj_layout(pools[0], cfg, d_n, 1, ext, tot)
+            r = {}
+            for mode, label in ((1, "direct"), (2, "lds")):
+                B.tutti_set_hnd_mode(mode)
+                for fn, name in ((B.tutti_obj_unpack, "unpack"), (B.tutti_obj_pack, "pack")):
+                    def train():
+                        for l in range(L):
+                            fn(pools[l], cfg, ext, 1, d_tab, n_tab, stages[l], payload, 0, status)
+                    train()
+                    torch.cuda.synchronize()
+                    ts = []
+                    for _ in range(reps):
+                        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        a.record()
+                        train()
+                        b.record()
+                        torch.cuda.synchronize()
+                        ts.append(a.elapsed_time(b) * 1e3 / L)
+                    r[f"{label}_{name}_us"] = round(median(ts), 2)
+            r["product_choice"] = "lds" if row < 128 else "direct"
+            res[f"row_{row}B ({heads} heads x {dim})"] = r
+            log(f"[bench] head-major rows of {row} B: {r}")
+    finally:
+        B.tutti_set_hnd_mode(0)
+        B.use_bench_library(False)
+    assert int(status.item()) == 0
     return res
 
 
@@ -951,7 +1011,18 @@ def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, 
                 ok_b = r1.elapsed_time(g1) > 0
                 if ok_b:
                     break
-            rows.append((gemm_solo, gemm_co, train_solo / L, train_co / L, ok_a, ok_b))
+            # (c) both loops, sized to last equally long alone, started together: time until both have ended, against
+            # the sum of their solo times (a figure that needs no overlap check: 1.0 = no better than taking turns)
+            e0, e1 = E(), E()
+            e0.record(main)
+            side.wait_event(e0)
+            restore_loop(main, budget, trains)
+            gemm_loop(gemm_iters)
+            main.wait_stream(side)
+            e1.record(main)
+            torch.cuda.synchronize()
+            pair = e0.elapsed_time(e1) / (gemm_solo * gemm_iters + trains * train_solo)
+            rows.append((gemm_solo, gemm_co, train_solo / L, train_co / L, ok_a, ok_b, pair))
         gs, gc, rs, rc = (median([r[i] for r in rows]) for i in range(4))
         out[label] = {"gemm_ms_solo": round(gs, 4), "gemm_ms_corun": round(gc, 4),
                       "gemm_slowdown": round(gc / gs, 3),
@@ -960,6 +1031,7 @@ def corun_sweep(torch, B, restore_layers, L, payload_layer, dev, gemm_iters=60, 
                       "restore_payload_GBps_solo": round(payload_layer / (rs * 1e-3) / 1e9, 1),
                       "restore_payload_GBps_corun": round(payload_layer / (rc * 1e-3) / 1e9, 1),
                       "restore_slowdown": round(rc / rs, 3),
+                      "both_together_vs_taking_turns": round(median([r[6] for r in rows]), 3),
                       # a figure taken while the other side had already finished is not a co-run figure
                       "gemm_figure_under_overlap": all(r[4] for r in rows),
                       "restore_figure_under_overlap": all(r[5] for r in rows)}

@@ -230,6 +230,27 @@ def test_empty_calls_do_not_need_a_gpu():
     assert B.tutti_copy_baseline(FAKE, FAKE, 0, stream=0) == B.OK
 
 
+def test_table_order_arguments_are_checked_before_any_gpu_call():
+    """The visiting-order call: sizes and pointers are checked on the host; an empty table enqueues nothing."""
+    need = B.tutti_table_order_work_bytes(65536)
+    assert need % 256 == 0 and need >= 2 * 65536 // 8 and need == 256 + 2 * B.tutti_table_validate_work_bytes(65536)
+    assert B.tutti_table_order_work_bytes(1) == 256 + 2 * 256
+    assert B.tutti_table_order(65536, 0, 0, 0, FAKE, need, stream=0) == B.OK
+    for kw, code in ((dict(num_blocks=0), B.EINVAL), (dict(d_block_table=0), B.EINVAL), (dict(d_visit=0), B.EINVAL),
+                     (dict(d_work=0), B.EINVAL), (dict(d_work=FAKE + 4), B.EINVAL), (dict(work_bytes=need - 1), B.ERANGE)):
+        args = dict(num_blocks=65536, d_block_table=FAKE, table_len=8, d_visit=FAKE, d_work=FAKE, work_bytes=need)
+        args.update(kw)
+        with pytest.raises(B.TuttiError) as ei:
+            B.tutti_table_order(**args, stream=0)
+        assert ei.value.code == code, kw
+    # the ordered restore checks what the plain one checks, before anything is enqueued
+    p = B.make_pool(FAKE, FAKE, **GOOD)
+    with pytest.raises(B.TuttiError) as ei:
+        B.tutti_layer_restore_ordered(p, B.make_cfg(4096, 1 << 20, 4), FAKE, 1, FAKE, 8, FAKE, 9, FAKE, 1 << 20, 0, 0,
+                                      FAKE, FAKE, FAKE, 4, FAKE, stream=0)      # layer 9 of 4
+    assert ei.value.code == B.EINVAL
+
+
 def test_workloads_are_seeded_and_shaped():
     from paper_2605_03375_amd import workloads as W
     a, b = W.batch64_zipf(), W.batch64_zipf()
