@@ -933,6 +933,10 @@ struct Item {
   uint32_t kind;
 };
 
+// Wave-uniform words (block ids, visiting order) are fetched through the scalar (constant) path: one s_load per
+// wavefront, counted apart from the vector loads and stores in flight, so waiting for it does not wait for them.
+typedef const __attribute__((address_space(4))) uint32_t *const_u32_ptr;
+
 // SEP: the extents came from the caller (lds_from_caller_extents): items are numbered by blk_off, the table is
 // indexed by the request's own table_off, and requests that cannot be honoured already have a zero-sized object.
 // ORD: the units are visited in the order a.visit lists (all K blocks, then all V blocks, each in that order);
@@ -948,7 +952,11 @@ __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, 
   uint32_t r, toff;
   if (ORD) {
     d.kind = u >= a.table_len ? 1u : 0u;
-    const uint32_t pos = rfl(a.visit[u - d.kind * a.table_len]);  // wave-uniform index: one word for the wavefront
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+    const_u32_ptr vis = (const_u32_ptr)a.visit;
+#pragma clang diagnostic pop
+    const uint32_t pos = vis[rfl(u - d.kind * a.table_len)];  // wave-uniform index: one scalar load
     if (pos >= l.table_off[n_req]) {  // beyond the blocks of the requests that take part
       d.obj_ptr = nullptr;
       d.obj_blk = nullptr;
@@ -1000,8 +1008,6 @@ __device__ __forceinline__ Item decode_item(const MoveArgs &a, const ReqLds &l, 
 
 // Block id of an item through the scalar (constant) path: the index is wave-uniform, so this is
 // one s_load that overlaps the vector loads and stores of the item before it.
-typedef const __attribute__((address_space(4))) uint32_t *const_u32_ptr;
-
 __device__ __forceinline__ uint32_t load_block_id(const MoveArgs &a, const Item &d) {
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Wold-style-cast"
