@@ -432,15 +432,24 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
             times.append(a.elapsed_time(b) * 1e3 / per)
         return median(times)
 
+    def save_train():
+        for l in range(L):
+            st = stages[l % len(stages)]
+            B.tutti_layer_save(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, st, payload, st.data_ptr(), 1, ext,
+                               tot, sqe, n_sqe, 0, status)
+
     us = timed(train, L)
     order_us = timed(order, 1)
     us_ordered = timed(lambda: train(True), L)
+    us_save = timed(save_train, L)
     assert int(status.item()) == 0 and int(tot[1].item()) == n_sqe
     res = {"layers_resident": L, "layers_model": s.num_layers, "pool_blocks": s.num_blocks, "requests": w.n_req,
            "blocks_per_layer": n_tab, "payload_bytes_per_layer": payload, "entries_per_layer": n_sqe,
            "us_per_layer": round(us, 2), "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
            "traffic_GBps": round(2 * payload / (us * 1e-6) / 1e9, 1),
            "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+           "save": {"us_per_layer": round(us_save, 2),
+                    "pct_hbm_peak": round(100 * 2 * payload / (us_save * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)},
            "address_order": {"us_per_layer": round(us_ordered, 2), "gain_pct": round(100 * (1 - us_ordered / us), 2),
                              "table_order_us_once": round(order_us, 2),
                              "pct_hbm_peak": round(100 * 2 * payload / (us_ordered * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)}}
