@@ -527,9 +527,57 @@ def ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid, payload,
             b.record()
             torch.cuda.synchronize()
             fused.append(a.elapsed_time(b) * 1e3 / L)
+        # the same one-call train (ring initialisation included) as one HIP-graph replay: launch gaps at their smallest
+        def one_call_train():
+            B.tutti_ring_init(ring)
+            for l in range(L):
+                one_call(ring, l * n_slots, n_slots, pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l,
+                         sgls[l].data_ptr(), 1, fs, ext, tot, 0, status)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                one_call_train()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        replay = []
+        for _ in range(reps):
+            a, b = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+            a.record()
+            graph.replay()
+            b.record()
+            torch.cuda.synchronize()
+            replay.append(a.elapsed_time(b) * 1e3 / L)
+        del graph
+        # the two halves: data launches on this stream, every completion on a second stream behind an event, so that
+        # the next layer's data kernel does not wait for the completion kernel of the layer before it
+        issue = B.tutti_store_layer_issue if op == B.OP_WRITE else B.tutti_retrieve_layer_issue
+        comp = torch.cuda.Stream()
+        main = torch.cuda.current_stream()
+        halves = []
+        for _ in range(reps):
+            B.tutti_ring_init(ring)
+            torch.cuda.synchronize()
+            a, b = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+            a.record()
+            for l in range(L):
+                issue(ring, l * n_slots, n_slots, pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l,
+                      sgls[l].data_ptr(), 1, fs, ext, tot, 0, status)
+                ev = torch.cuda.Event()
+                ev.record(main)
+                comp.wait_event(ev)
+                B.tutti_complete_io(ring, l * n_slots, n_slots, comp)
+            main.wait_stream(comp)             # the train has ended when its last completion has
+            b.record()
+            torch.cuda.synchronize()
+            halves.append(a.elapsed_time(b) * 1e3 / L)
         us, us_io, us_one = median(both), median(only_io), median(fused)
-        res[label] = {"us_per_layer_fill_plus_io": round(us, 2), "us_per_layer_issue_io": round(us_io, 2),
+        res[label] = {"us_per_layer_completions_on_second_stream": round(median(halves), 2),
+"us_per_layer_fill_plus_io": round(us, 2), "us_per_layer_issue_io": round(us_io, 2),
                       "us_per_layer_one_call": round(us_one, 2),
+                      "us_per_layer_one_call_graph_replay": round(median(replay), 2),
                       "pct_hbm_peak_one_call": round(100 * 2 * payload / (us_one * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
                       "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
                       "traffic_GBps_issue_io": round(2 * payload / (us_io * 1e-6) / 1e9, 1),

@@ -346,6 +346,30 @@ int tutti_store_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_sl
                       uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
                       uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream);
 
+/* The two halves of tutti_retrieve_layer / tutti_store_layer, for callers that pipeline layers: the _issue calls
+ * enqueue the data-moving launch only and leave the IOCBs FILLED; tutti_complete_io enqueues the completion kernel
+ * alone: every FILLED IOCB of the n_slots slots from first_slot becomes DONE (done = num_ioctx) and its index is
+ * appended to the CQ, in slot order (sec. 3.2 "Async I/O Processing", step 4).  tutti_complete_io must be ordered
+ * after the launch that executed those IOCBs (same stream, or an event), and completions of one ring after each
+ * other (they share the CQ tail); it does not check that the IOCBs were executed.  On one stream, _issue followed by
+ * tutti_complete_io IS the one-call form.  With the completions on a second stream, each behind an event recorded
+ * after its layer's _issue call, the next layer's data kernel does not wait for the completion kernel of the
+ * layer before it (different IOCB slots, different blocks, different file ranges: nothing is shared but the CQ
+ * tail, which only the completions touch), which takes the completion's launch boundary off the layer train. */
+int tutti_retrieve_layer_issue(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                               const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                               const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                               uint32_t layer, uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store,
+                               tutti_extent *d_extents, uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status,
+                               void *stream);
+int tutti_store_layer_issue(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                            const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                            const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                            uint32_t layer, uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store,
+                            tutti_extent *d_extents, uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status,
+                            void *stream);
+int tutti_complete_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, void *stream);
+
 /* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);

@@ -764,7 +764,7 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
                      const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
                      const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
                      uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
-                     uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+                     uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream, bool complete = true) {
   int rc = check_ring(ring, first_slot, n_slots);
   if (rc) return rc;
   uint32_t bb = 0;
@@ -820,12 +820,45 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
     return hipGetLastError();
   });
   if (e != hipSuccess) return hip_fail(e);
+  if (!complete) return TUTTI_OK;
   hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, s, g);
   e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 }  // namespace
 }  // extern "C++"
+
+int tutti_retrieve_layer_issue(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                               const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                               const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                               uint32_t layer, uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store,
+                               tutti_extent *d_extents, uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status,
+                               void *stream) {
+  return ring_layer_entry<kUnpack>(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len,
+                                   d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget,
+                                   d_status, stream, false);
+}
+
+int tutti_store_layer_issue(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
+                            const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
+                            const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id,
+                            uint32_t layer, uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store,
+                            tutti_extent *d_extents, uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status,
+                            void *stream) {
+  return ring_layer_entry<kPack>(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len,
+                                 d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget,
+                                 d_status, stream, false);
+}
+
+int tutti_complete_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, void *stream) {
+  const int rc = check_ring(ring, first_slot, n_slots);
+  if (rc) return rc;
+  if (n_slots == 0) return TUTTI_OK;
+  RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
+  hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, static_cast<hipStream_t>(stream), g);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
 
 int tutti_retrieve_layer(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_pool *pool,
                          const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,

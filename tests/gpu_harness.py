@@ -388,7 +388,7 @@ def check_rings(orc, c, layer, opcode, depth, first_slot, n_slots, cu_budget=0, 
 
 
 def check_ring_layer(orc, c, layer, write, depth, first_slot, n_slots, cu_budget=0, first_file_id=1000, n_files=None,
-                     stride_cut=0, seed=5, prefill=False):
+                     stride_cut=0, seed=5, prefill=False, side_completion=False):
     """retrieve_layer / store_layer through the rings in one call, device against oracle: same inputs, every
     output compared (extents, totals, status, planes, file store, IOCBs, completion queue, wait_cqe flags).
     prefill: the ring already holds completions of an earlier call (the CQ tail is not 0)."""
@@ -414,6 +414,17 @@ def check_ring_layer(orc, c, layer, write, depth, first_slot, n_slots, cu_budget
     ext = torch.zeros(max(1, c.n_req) * 32, dtype=torch.uint8, device=DEV)
     tot = torch.zeros(2, dtype=torch.int64, device=DEV)
     fn = B.tutti_store_layer if write else B.tutti_retrieve_layer
+    if side_completion:
+        # the two halves: the data launch on the current stream, the completion on a second stream behind an event
+        issue = B.tutti_store_layer_issue if write else B.tutti_retrieve_layer_issue
+        side = torch.cuda.Stream()
+
+        def fn(ring, fslot, ns, *rest):
+            issue(ring, fslot, ns, *rest)
+            ev = torch.cuda.Event()
+            ev.record()
+            side.wait_event(ev)
+            B.tutti_complete_io(ring, fslot, ns, side)
     o_fn = orc.store_layer if write else orc.retrieve_layer
     calls = [(0, min(1, depth), (layer + 1) % c.L)] if prefill else []
     calls.append((first_slot, n_slots, layer))

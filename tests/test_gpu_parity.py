@@ -782,6 +782,71 @@ def test_ring_layer_cfg2(orc, H):
         assert H.check_ring_layer(orc, c, layer=31, write=write, depth=4, first_slot=3, n_slots=2) == 0
 
 
+def test_ring_layer_calls_in_two_halves_with_completions_on_a_second_stream(orc, H):
+    """tutti_retrieve_layer_issue / tutti_store_layer_issue + tutti_complete_io behind an event on another stream give
+    what the one-call forms give (IOCBs, CQ order, blocks, files, status), also across two calls on one ring and
+    under a budget; and a train of layers whose completions all run on the second stream ends with every IOCB DONE
+    and the CQ in slot order."""
+    say("rings: issue and completion as separate calls")
+    rng = np.random.default_rng(77)
+    nb = [700, 0, 1500, 3]
+    N = 2500
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=4096, L=3,
+                    name="ring_halves")
+    n_slots = (2 * sum(nb) + B.IOCB_SLOTS - 1) // B.IOCB_SLOTS
+    for write in (False, True):
+        assert H.check_ring_layer(orc, c, layer=1, write=write, depth=n_slots + 2, first_slot=n_slots, n_slots=n_slots,
+                                  side_completion=True) == 0
+        H.check_ring_layer(orc, c, layer=2, write=write, depth=n_slots + 1, first_slot=1, n_slots=n_slots,
+                           cu_budget=3, prefill=True, side_completion=True)
+        assert H.check_ring_layer(orc, c, layer=0, write=write, depth=4, first_slot=0, n_slots=1,
+                                  side_completion=True) == B.ST_SQE_CAP                      # too few IOCBs
+    # a train: 6 layers of config 2's shape (smaller pool), completions on the side stream, nothing waited for in between
+    w = W.llama8b_32k(num_blocks=4096, tokens=8192, num_layers=6)
+    s = w.shape
+    c = H.LayerCase.from_workload(w)
+    bb = c.bb
+    n_tab = c.table.size
+    n_slots = (2 * n_tab + B.IOCB_SLOTS - 1) // B.IOCB_SLOTS
+    depth = 6 * n_slots
+    file_stride = 2 * 6 * n_tab * bb
+    g = torch.Generator(device=H.DEV)
+    g.manual_seed(12)
+    store = torch.randint(0, 256, (file_stride,), dtype=torch.uint8, device=H.DEV, generator=g)
+    fs = B.make_filestore(store, file_stride, int(c.file_id[0]), 1)
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=H.DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=H.DEV)
+    ring = B.make_ring(sq, cq, depth)
+    B.tutti_ring_init(ring)
+    planes = [(torch.zeros_like(c.k_dev), torch.zeros_like(c.v_dev)) for _ in range(6)]
+    ext = torch.zeros(32, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    st = H.new_status()
+    side = torch.cuda.Stream()
+    for l in range(6):
+        B.tutti_retrieve_layer_issue(ring, l * n_slots, n_slots, c.gpu_pool(*planes[l]), c.gpu_cfg(), c.d_n_blocks, 1,
+                                     c.d_table, n_tab, c.d_file_id, l, 0x1000, 5, fs, ext, tot, 0, st)
+        ev = torch.cuda.Event()
+        ev.record()
+        side.wait_event(ev)
+        B.tutti_complete_io(ring, l * n_slots, n_slots, side)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    q = cq.cpu().numpy().view(np.uint32)
+    assert int(q[0]) == depth and list(q[16:16 + depth]) == list(range(depth))
+    hdr = sq.cpu().numpy().view(B.IOCB_DTYPE)["hdr"]
+    assert np.all(hdr["state"] == B.IOCB_DONE) and np.all(hdr["done"] == hdr["num_ioctx"])
+    file_h = store.cpu().numpy()
+    for l in (0, 3, 5):                       # the blocks of three layers against the file, byte for byte
+        k_h, v_h = planes[l][0].cpu().numpy(), planes[l][1].cpu().numpy()
+        for kind, plane in ((0, k_h), (1, v_h)):
+            lo = (2 * l + kind) * n_tab * bb
+            for j in (0, 1, n_tab // 2, n_tab - 1):
+                bid = int(c.table[j])
+                assert np.array_equal(plane[bid * c.stride: bid * c.stride + bb], file_h[lo + j * bb: lo + (j + 1) * bb])
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_no_requests_and_empty_requests(orc, H):
