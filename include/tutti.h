@@ -373,6 +373,10 @@ int tutti_complete_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_sl
 /* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);
+/* The same check for the n_slots IOCBs from first_slot on (wrapping at depth) in one launch: d_flags[i] <- 1 if IOCB
+ * (first_slot + i) % depth is DONE, else 0.  d_flags: n_slots words of device memory. */
+int tutti_wait_cqe_range(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t *d_flags,
+                         void *stream);
 
 /* ---- I/O domain (sec. 3.2 "SM Partitioning For Accurate I/O": the I/O kernels get compute units of their own,
  * isolated in hardware from the compute kernels).  *stream <- a new stream whose kernels the hardware dispatches

@@ -54,7 +54,7 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_io_domain_destroy", "tutti_table_validate_work_bytes", "tutti_table_validate_ws",
            "tutti_table_validate_static", "tutti_layer_restore_ordered", "tutti_table_order",
            "tutti_table_order_work_bytes", "tutti_retrieve_layer_issue", "tutti_store_layer_issue",
-           "tutti_complete_io"]
+           "tutti_complete_io", "tutti_wait_cqe_range"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
                  "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
 SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
@@ -148,6 +148,7 @@ def _declare(L, bench):
     L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
     L.tutti_issue_io.argtypes = [pr, u32, u32, vp, u32, u64, pf, u32, u32, vp, vp]
     L.tutti_wait_cqe.argtypes = [pr, u32, vp, vp]
+    L.tutti_wait_cqe_range.argtypes = [pr, u32, u32, vp, vp]
     L.tutti_retrieve_layer.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u64, u32, pf, vp, vp, u32,
                                        vp, vp]
     L.tutti_store_layer.argtypes = L.tutti_retrieve_layer.argtypes
@@ -398,6 +399,11 @@ def tutti_store_layer(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d
 
 def tutti_wait_cqe(ring, slot, d_flag, stream=None):
     return _check("tutti_wait_cqe", lib().tutti_wait_cqe(C.byref(ring), slot, _p(d_flag), _stream(stream)))
+
+
+def tutti_wait_cqe_range(ring, first_slot, n_slots, d_flags, stream=None):
+    return _check("tutti_wait_cqe_range", lib().tutti_wait_cqe_range(C.byref(ring), first_slot, n_slots, _p(d_flags),
+                                                                     _stream(stream)))
 
 
 def tutti_layer_save(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage, stage_cap,

@@ -885,7 +885,21 @@ int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void
   int rc = check_ring(ring, slot, 0);
   if (rc) return rc;
   if (!d_flag) return TUTTI_EINVAL;
-  hipLaunchKernelGGL(k_cq_check, dim3(1), dim3(kWave), 0, static_cast<hipStream_t>(stream), ring->d_sq, slot, d_flag);
+  hipLaunchKernelGGL(k_cq_check, dim3(1), dim3(kWave), 0, static_cast<hipStream_t>(stream), ring->d_sq, ring->depth, slot,
+                     1u, d_flag);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_wait_cqe_range(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t *d_flags,
+                         void *stream) {
+  int rc = check_ring(ring, first_slot, n_slots);
+  if (rc) return rc;
+  if (n_slots > 0 && !d_flags) return TUTTI_EINVAL;
+  if (n_slots == 0) return TUTTI_OK;
+  const uint32_t grid = (n_slots + kWgThreads - 1) / kWgThreads;
+  hipLaunchKernelGGL(k_cq_check, dim3(grid < 64u ? grid : 64u), dim3(kWgThreads), 0, static_cast<hipStream_t>(stream),
+                     ring->d_sq, ring->depth, first_slot, n_slots, d_flags);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }

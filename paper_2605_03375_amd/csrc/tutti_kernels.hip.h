@@ -831,10 +831,13 @@ __global__ __launch_bounds__(kWave) void k_complete(const RingArgs g) {
   complete_iocbs(g, threadIdx.x);
 }
 
-__global__ void k_cq_check(const tutti_iocb *sq, uint32_t slot, uint32_t *flag) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    const uint32_t st = __hip_atomic_load(&sq[slot].hdr.state, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-    *flag = st == TUTTI_IOCB_DONE ? 1u : 0u;
+// wait_cqe for n slots from `slot` on (wrapping at depth): flag[i] <- 1 if IOCB (slot + i) % depth is DONE, else 0.
+__global__ __launch_bounds__(kWgThreads) void k_cq_check(const tutti_iocb *sq, uint32_t depth, uint32_t slot, uint32_t n,
+                                                          uint32_t *flag) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const uint32_t st =
+        __hip_atomic_load(&sq[(slot + i) % depth].hdr.state, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    flag[i] = st == TUTTI_IOCB_DONE ? 1u : 0u;
   }
 }
 

@@ -451,6 +451,12 @@ def check_ring_layer(orc, c, layer, write, depth, first_slot, n_slots, cu_budget
     assert cq.cpu().numpy().tobytes() == o_cq.tobytes(), f"{c.name}: completion queue differs"
     done = o_sq["hdr"]["state"] == orc.IOCB_DONE
     assert flags.cpu().tolist() == [1 if x else 0 for x in done]
+    # the same answers from one launch over the whole ring, starting in the middle and wrapping around
+    start = depth // 2
+    many = torch.full((depth + 1,), 9, dtype=torch.int32, device=DEV)
+    B.tutti_wait_cqe_range(ring, start, depth, many)
+    torch.cuda.synchronize()
+    assert many.cpu().tolist() == [1 if done[(start + i) % depth] else 0 for i in range(depth)] + [9]
     if write:
         assert np.array_equal(gk, c.k_host) and np.array_equal(gv, c.v_host)
     return o_st
