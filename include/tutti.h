@@ -14,8 +14,9 @@
  *   - The library allocates no device memory and keeps no state between calls: what a call does
  *     depends on its arguments alone (the pool is fixed for the engine's lifetime and nothing on
  *     the I/O path may allocate: sec. 3.1 "P2P Memory Mapping Table", sec. 3.2 "Zero-Copy Ring
- *     Buffers").  Launch-tuning knobs and baseline kernels for measurements live in a separate
- *     library (tutti_bench.h), not here.
+ *     Buffers").  The one exception is stated where it is declared: tutti_table_validate_static
+ *     works in a fixed array inside the library.  Launch-tuning knobs and baseline kernels for
+ *     measurements live in a separate library (tutti_bench.h), not here.
  *   - A call validates its host arguments in O(1), enqueues a constant number of kernels on
  *     `stream` and returns; it never synchronises and never copies to the host.  Results are
  *     valid once the caller has synchronised the stream.
@@ -52,7 +53,7 @@ extern "C" {
 #define TUTTI_ST_BAD_BLOCK 1u /* a block-table entry >= num_blocks, or beyond table_len: block skipped */
 #define TUTTI_ST_STAGE_CAP 2u /* a request's objects end beyond stage_cap: request skipped */
 #define TUTTI_ST_SQE_CAP 4u   /* more entries than sqe_cap: the excess was not written */
-#define TUTTI_ST_DUP_BLOCK 8u /* tutti_table_validate only: a block id appears more than once in the table */
+#define TUTTI_ST_DUP_BLOCK 8u /* tutti_table_validate* and tutti_table_order only: a block id appears twice in the table */
 #define TUTTI_ST_BAD_EXTENT 16u /* an extent that cannot be honoured: see tutti_obj_pack and tutti_sqe_build */
 
 /* One layer's paged pool (sec. 2.1 "Paged KV Memory Management"): a K plane and a V plane, each
