@@ -105,6 +105,26 @@ int check_planes(const tutti_pool *pool) {
   return TUTTI_OK;
 }
 
+// Workgroup shape of the entry builders.  Every workgroup first stages and checks all n_req extents, so with
+// thousands of requests that preamble is what a launch of many small workgroups spends its instructions on (and
+// its LDS: 24 bytes per request and workgroup limit a CU to three 256-thread workgroups at 2048 requests); the
+// large shape has a quarter of the workgroups do it, with four times the wavefronts each.
+struct EntryLaunch {
+  uint32_t wg_threads;
+  uint32_t grid;
+};
+
+EntryLaunch entry_launch(uint32_t n_req, uint64_t quarters, int cus, uint32_t small_wgs_per_cu) {
+  EntryLaunch L;
+  L.wg_threads = n_req > 512 ? kBudgetWgThreads : kWgThreads;
+  uint64_t need = (quarters + L.wg_threads - 1) / L.wg_threads;
+  if (need == 0) need = 1;
+  const uint64_t per_cu = L.wg_threads == kWgThreads ? small_wgs_per_cu : 2;
+  const uint64_t lim = static_cast<uint64_t>(cus) * per_cu;
+  L.grid = static_cast<uint32_t>(need < lim ? need : lim);
+  return L;
+}
+
 SqeArgs sqe_args(const uint32_t *d_file_id, tutti_sqe *d_sqe, uint32_t *d_status, uint64_t stage_addr,
                  uint32_t sqe_cap, uint32_t chunk_bytes, uint32_t layer, uint32_t opcode, uint32_t sgl_id) {
   SqeArgs q;
@@ -491,12 +511,14 @@ int tutti_sqe_build(const tutti_pool *pool, const tutti_objcfg *cfg, const tutti
   const SqeArgs q = sqe_args(d_file_id, d_sqe, d_status, stage_addr, sqe_cap, cfg->chunk_bytes, layer,
                              opcode, sgl_id);
   // one lane per 16-byte quarter of an entry; at most a few workgroups per CU
-  uint64_t need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
-  if (need == 0) need = 1;
-  const uint64_t cap = static_cast<uint64_t>(cus) * 4;
-  const uint32_t grid = static_cast<uint32_t>(need < cap ? need : cap);
-  hipLaunchKernelGGL(k_sqe, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req), static_cast<hipStream_t>(stream), q,
-                     ScanGeom{bb, cfg->align, cfg->chunk_bytes}, d_extents, n_req);
+  const EntryLaunch E = entry_launch(n_req, 4ull * sqe_cap, cus, 4);
+  const ScanGeom geom{bb, cfg->align, cfg->chunk_bytes};
+  if (E.wg_threads == kWgThreads)
+    hipLaunchKernelGGL(k_sqe<kWgThreads>, dim3(E.grid), dim3(kWgThreads), req_lds_bytes(n_req),
+                       static_cast<hipStream_t>(stream), q, geom, d_extents, n_req);
+  else
+    hipLaunchKernelGGL(k_sqe<kBudgetWgThreads>, dim3(E.grid), dim3(kBudgetWgThreads), req_lds_bytes(n_req),
+                       static_cast<hipStream_t>(stream), q, geom, d_extents, n_req);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
@@ -644,12 +666,14 @@ int tutti_sqe_build_direct(const tutti_pool *pool, const tutti_objcfg *cfg, cons
   const SqeArgs q = sqe_args(d_file_id, d_sqe, d_status, 0, sqe_cap, bb, layer,
                              opcode, sgl_id);
   const DirectArgs d = direct_args(d_block_table, sgl_table_addr, table_len, pool->num_blocks, bb);
-  uint64_t need = (4ull * sqe_cap + kWgThreads - 1) / kWgThreads;
-  if (need == 0) need = 1;
-  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
-  const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
-  hipLaunchKernelGGL(k_sqe_direct, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req),
-                     static_cast<hipStream_t>(stream), q, d, ScanGeom{bb, cfg->align, cfg->chunk_bytes}, d_extents, n_req);
+  const EntryLaunch E = entry_launch(n_req, 4ull * sqe_cap, cus, 8);
+  const ScanGeom geom{bb, cfg->align, cfg->chunk_bytes};
+  if (E.wg_threads == kWgThreads)
+    hipLaunchKernelGGL(k_sqe_direct<kWgThreads>, dim3(E.grid), dim3(kWgThreads), req_lds_bytes(n_req),
+                       static_cast<hipStream_t>(stream), q, d, geom, d_extents, n_req);
+  else
+    hipLaunchKernelGGL(k_sqe_direct<kBudgetWgThreads>, dim3(E.grid), dim3(kBudgetWgThreads), req_lds_bytes(n_req),
+                       static_cast<hipStream_t>(stream), q, d, geom, d_extents, n_req);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
@@ -696,12 +720,15 @@ int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t
   const SqeArgs q = sqe_args(d_file_id, nullptr, d_status, 0, 0, bb, layer,
                              opcode, sgl_id);
   const DirectArgs d = direct_args(d_block_table, sgl_table_addr, table_len, pool->num_blocks, bb);
-  uint64_t need = (4ull * n_slots * TUTTI_IOCB_SLOTS + kWgThreads - 1) / kWgThreads;
-  if (need == 0) need = 1;  // no IOCBs given: one workgroup still reports the dropped contexts
-  const uint64_t lim = static_cast<uint64_t>(cus) * 8;
-  const uint32_t grid = static_cast<uint32_t>(need < lim ? need : lim);
-  hipLaunchKernelGGL(k_iocb_fill, dim3(grid), dim3(kWgThreads), req_lds_bytes(n_req), static_cast<hipStream_t>(stream),
-                     g, q, d, ScanGeom{bb, cfg->align, cfg->chunk_bytes}, d_extents, n_req);
+  // (no IOCBs given: one workgroup still reports the dropped contexts)
+  const EntryLaunch E = entry_launch(n_req, 4ull * n_slots * TUTTI_IOCB_SLOTS, cus, 8);
+  const ScanGeom geom{bb, cfg->align, cfg->chunk_bytes};
+  if (E.wg_threads == kWgThreads)
+    hipLaunchKernelGGL(k_iocb_fill<kWgThreads>, dim3(E.grid), dim3(kWgThreads), req_lds_bytes(n_req),
+                       static_cast<hipStream_t>(stream), g, q, d, geom, d_extents, n_req);
+  else
+    hipLaunchKernelGGL(k_iocb_fill<kBudgetWgThreads>, dim3(E.grid), dim3(kBudgetWgThreads), req_lds_bytes(n_req),
+                       static_cast<hipStream_t>(stream), g, q, d, geom, d_extents, n_req);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }

@@ -208,36 +208,69 @@ __device__ __forceinline__ void wave_scan_extents(const ScanGeom g, const uint32
 // that follow from n_blocks.  That is checked here, every request against its successor; the result is the same
 // in every workgroup.  Returns false (after reporting TUTTI_ST_BAD_EXTENT once) if the extents are anything else:
 // the caller then writes nothing.
+template <int WG>
 __device__ __forceinline__ bool lds_from_extents(const tutti_extent *__restrict__ ext, uint32_t n_req, ReqLds l,
                                                  const ScanGeom g, uint32_t *__restrict__ status) {
+  // Called by workgroups of WG threads: thread t holds requests t, t + WG, ... (at most kPer of them).  The loop is
+  // fully unrolled so that a thread's loads are all in flight together; a request's successor sits in the next
+  // lane, and for the last lane of a wavefront in LDS once the barrier has been crossed.  Every workgroup of an
+  // entry builder runs this over all requests, so its instruction count matters when there are thousands of
+  // both: the host then launches few, large workgroups (entry_wg_threads).
+  constexpr uint32_t kPer = TUTTI_MAX_REQ / WG;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
   bool bad = false;
-  for (uint32_t r = threadIdx.x; r < n_req; r += blockDim.x) {
-    const tutti_extent e = ext[r];
-    l.stage_off[r] = e.stage_off;
-    l.obj_bytes[r] = e.obj_bytes;
-    l.table_off[r] = e.table_off;
-    l.sqe_base[r] = e.sqe_base;
-    const uint64_t raw = static_cast<uint64_t>(e.n_blocks) * g.block_bytes;
-    const uint64_t obj = (raw + (g.align - 1)) & ~static_cast<uint64_t>(g.align - 1);
-    bad = bad || e.obj_bytes != obj || e.n_chunks != (obj + g.chunk_bytes - 1) / g.chunk_bytes;
-    // 64-bit sums: offsets that would wrap around 32 bits are not dense either
-    const uint64_t next_sqe = static_cast<uint64_t>(e.sqe_base) + 2ull * e.n_chunks;
-    const uint64_t next_tab = static_cast<uint64_t>(e.table_off) + e.n_blocks;
-    bad = bad || next_sqe > 0xffffffffull || next_tab > 0xffffffffull;
-    if (r == 0) bad = bad || e.sqe_base != 0 || e.table_off != 0;
-    if (r + 1 < n_req) {
-      const tutti_extent f = ext[r + 1];
-      bad = bad || f.sqe_base != next_sqe || f.table_off != next_tab;
-    } else {
-      l.table_off[n_req] = static_cast<uint32_t>(next_tab);
-      l.sqe_base[n_req] = static_cast<uint32_t>(next_sqe);
+  uint32_t nx_sqe[kPer], nx_tab[kPer];
+#pragma unroll
+  for (uint32_t k = 0; k < kPer; ++k) {
+    const uint32_t r = k * WG + threadIdx.x;
+    tutti_extent e;
+    e.stage_off = e.obj_bytes = 0;
+    e.n_blocks = e.n_chunks = e.sqe_base = e.table_off = 0;
+    if (r < n_req) e = ext[r];
+    uint64_t next_sqe = 0, next_tab = 0;
+    if (r < n_req) {
+      l.stage_off[r] = e.stage_off;
+      l.obj_bytes[r] = e.obj_bytes;
+      l.table_off[r] = e.table_off;
+      l.sqe_base[r] = e.sqe_base;
+      const uint64_t raw = static_cast<uint64_t>(e.n_blocks) * g.block_bytes;
+      const uint64_t obj = (raw + (g.align - 1)) & ~static_cast<uint64_t>(g.align - 1);
+      // n_chunks == ceil(obj / chunk_bytes), without the 64-bit division: c*chunk >= obj > (c-1)*chunk
+      const uint32_t c = e.n_chunks;
+      const bool chunks_ok = obj == 0 ? c == 0
+                                      : (c >= 1 && static_cast<uint64_t>(c) * g.chunk_bytes >= obj &&
+                                         static_cast<uint64_t>(c - 1) * g.chunk_bytes < obj);
+      bad = bad || e.obj_bytes != obj || !chunks_ok;
+      // 64-bit sums: offsets that would wrap around 32 bits are not dense either
+      next_sqe = static_cast<uint64_t>(e.sqe_base) + 2ull * e.n_chunks;
+      next_tab = static_cast<uint64_t>(e.table_off) + e.n_blocks;
+      bad = bad || next_sqe > 0xffffffffull || next_tab > 0xffffffffull;
+      if (r == 0) bad = bad || e.sqe_base != 0 || e.table_off != 0;
+      if (r + 1 == n_req) {
+        l.table_off[n_req] = static_cast<uint32_t>(next_tab);
+        l.sqe_base[n_req] = static_cast<uint32_t>(next_sqe);
+      }
     }
+    nx_sqe[k] = static_cast<uint32_t>(next_sqe);
+    nx_tab[k] = static_cast<uint32_t>(next_tab);
+    // the successor's offsets, from the next lane (every lane takes part in the exchange)
+    const uint32_t f_sqe = static_cast<uint32_t>(__shfl_down(static_cast<int>(e.sqe_base), 1, kWave));
+    const uint32_t f_tab = static_cast<uint32_t>(__shfl_down(static_cast<int>(e.table_off), 1, kWave));
+    if (r + 1 < n_req && lane != kWave - 1) bad = bad || f_sqe != nx_sqe[k] || f_tab != nx_tab[k];
   }
   if (n_req == 0 && threadIdx.x == 0) {
     l.table_off[0] = 0;
     l.sqe_base[0] = 0;
   }
-  const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;  // also publishes the LDS writes above
+  __syncthreads();  // publishes the LDS writes above
+  if (lane == kWave - 1) {
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+      const uint32_t r = k * WG + threadIdx.x;
+      if (r + 1 < n_req) bad = bad || l.sqe_base[r + 1] != nx_sqe[k] || l.table_off[r + 1] != nx_tab[k];
+    }
+  }
+  const bool any_bad = __syncthreads_or(bad ? 1 : 0) != 0;
   if (any_bad && blockIdx.x == 0 && threadIdx.x == 0 && status) atomicOr(status, TUTTI_ST_BAD_EXTENT);
   return !any_bad;
 }
@@ -657,12 +690,13 @@ __device__ __forceinline__ void emit_iocbs(const RingArgs g, const SqeArgs a, co
   });
 }
 
-__global__ __launch_bounds__(kWgThreads) void k_iocb_fill(const RingArgs g, const SqeArgs a, const DirectArgs d,
+template <int WG>
+__global__ __launch_bounds__(WG) void k_iocb_fill(const RingArgs g, const SqeArgs a, const DirectArgs d,
                                                            const ScanGeom geom, const tutti_extent *__restrict__ ext,
                                                            uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
-  if (!lds_from_extents(ext, n_req, l, geom, a.status)) return;
+  if (!lds_from_extents<WG>(ext, n_req, l, geom, a.status)) return;
   emit_iocbs(g, a, d, l, n_req, 0, gridDim.x, iocb_head(g, a, d, l, n_req, 0, gridDim.x));
 }
 
@@ -841,11 +875,12 @@ __global__ __launch_bounds__(kWgThreads) void k_cq_check(const tutti_iocb *sq, u
   }
 }
 
-__global__ __launch_bounds__(kWgThreads) void k_sqe_direct(const SqeArgs a, const DirectArgs d, const ScanGeom geom,
+template <int WG>
+__global__ __launch_bounds__(WG) void k_sqe_direct(const SqeArgs a, const DirectArgs d, const ScanGeom geom,
                                                             const tutti_extent *__restrict__ ext, uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
-  if (!lds_from_extents(ext, n_req, l, geom, a.status)) return;
+  if (!lds_from_extents<WG>(ext, n_req, l, geom, a.status)) return;
   emit_direct_sqes(a, d, l, n_req);
 }
 
@@ -1305,11 +1340,12 @@ __global__ __launch_bounds__(kWave) void k_layout(const LayoutArgs a) {
   wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, a.extents, a.totals, 0xffffffffu, nullptr);
 }
 
-__global__ __launch_bounds__(kWgThreads) void k_sqe(const SqeArgs a, const ScanGeom g,
+template <int WG>
+__global__ __launch_bounds__(WG) void k_sqe(const SqeArgs a, const ScanGeom g,
                                                      const tutti_extent *__restrict__ ext, uint32_t n_req) {
   extern __shared__ __align__(16) unsigned char smem[];
   const ReqLds l = carve_lds(smem, n_req);
-  if (!lds_from_extents(ext, n_req, l, g, a.status)) return;
+  if (!lds_from_extents<WG>(ext, n_req, l, g, a.status)) return;
   emit_sqes(a, l, n_req, 0, gridDim.x, sqe_head(a, l, n_req, 0));
 }
 
