@@ -231,6 +231,26 @@ def main():
                  "pct_hbm_peak": round(100 * 2 * payload_layer / (save_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
                  "launches_per_layer": 1},
     }
+    if not args.no_extra:
+        # the same restore train with an event between every two launches (adds a gap of a microsecond or two to
+        # each): the layers differ only in where the driver placed their planes, and so does their time
+        per = np.zeros((3, L))
+        for rep in range(3):
+            evs = [ev() for _ in range(L + 1)]
+            for l in range(L):
+                evs[l].record(stream)
+                B.tutti_layer_restore(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload_layer,
+                                      stages[l].data_ptr(), sgl_id, ext_r[l], tot_r[l], rsqe[l], n_sqe_layer, 0,
+                                      status, stream)
+            evs[L].record(stream)
+            torch.cuda.synchronize()
+            per[rep] = [evs[l].elapsed_time(evs[l + 1]) * 1e3 for l in range(L)]
+        by_layer = np.median(per, axis=0)[1:]            # the first launch of a train also pays for the idle queue
+        out["restore"]["by_layer_with_event_gaps_us"] = {
+            "min": round(float(by_layer.min()), 1), "median": round(float(np.median(by_layer)), 1),
+            "max": round(float(by_layer.max()), 1),
+            "layers_under_49us": int((by_layer < 49.0).sum()), "layers": int(by_layer.size),
+            "sorted": [round(float(x), 1) for x in np.sort(by_layer)]}
     log(f"[bench] step {ms_per_step:.3f} ms, restore {restore_us:.1f} us/layer "
         f"({out['restore']['traffic_GBps']} GB/s traffic, {out['restore']['pct_hbm_peak']} % of peak), "
         f"save {save_us:.1f} us/layer")
