@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--pinned-stage", action="store_true",
                     help="also time the restore with the staging buffer in pinned host memory (host-link bound)")
     ap.add_argument("--write-lut", default="", help="also write the slack table (JSON) to this path")
+    ap.add_argument("--no-placement", action="store_true",
+                    help="take the pool's planes as the allocator hands them out instead of putting every layer's K "
+                         "and V plane in different HBM regions")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--plain-loads", action="store_true", help="disable non-temporal loads/stores")
@@ -120,15 +123,19 @@ def main():
                 head_dim=s.head_dim, elt_bytes=s.elt_bytes)
     cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
     t0 = time.time()
-    planes = []
+    # where the planes sit: every layer's K plane and V plane in different regions of the HBM (set-up, untimed)
+    planes, planes_same, placement_info = placed_planes(torch, L, plane_bytes, dev, reserve_bytes=(L * payload_layer) + (12 << 30),
+                                                        place=not args.no_placement)
+    log(f"[bench] placement ({time.time() - t0:.1f} s): {placement_info}")
+    td = {"fp16": torch.float16, "bf16": torch.bfloat16}[s.dtype]
     for l in range(L):
-        k = W.device_values(W.seed_for(2, l), plane_bytes // 2, s.dtype, dev).view(torch.uint8)
-        v = W.device_values(W.seed_for(2, l) + 500, plane_bytes // 2, s.dtype, dev).view(torch.uint8)
-        planes.append((k, v))
+        W.device_values(W.seed_for(2, l), plane_bytes // 2, s.dtype, dev, out=planes[l][0].view(td))
+        W.device_values(W.seed_for(2, l) + 500, plane_bytes // 2, s.dtype, dev, out=planes[l][1].view(td))
         if l % 8 == 7 or l == L - 1:
             torch.cuda.synchronize()
             log(f"[bench] filled {l + 1}/{L} layers ({time.time() - t0:.1f} s)")
     pools = [B.make_pool(k, v, **geom) for k, v in planes]
+    pools_same = [B.make_pool(k, v, **geom) for k, v in planes_same]
     stages = [torch.zeros(payload_layer, dtype=torch.uint8, device=dev) for _ in range(L)]
     d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
     d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
@@ -231,6 +238,33 @@ def main():
                  "pct_hbm_peak": round(100 * 2 * payload_layer / (save_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
                  "launches_per_layer": 1},
     }
+    out["config"]["placement"] = placement_info
+    if pools_same:
+        # the same planes paired within one region (what an allocator that knows nothing of the regions mostly gives)
+        def same_train():
+            for l, p in enumerate(pools_same):
+                B.tutti_layer_restore(p, cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload_layer,
+                                      stages[l].data_ptr(), sgl_id, ext_r[l], tot_r[l], rsqe[l], n_sqe_layer, 0,
+                                      status, stream)
+        same_train()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(5):
+            a, b = ev(), ev()
+            a.record(stream)
+            same_train()
+            b.record(stream)
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / len(pools_same))
+        us_same = median(ts)
+        out["restore_K_and_V_in_one_region"] = {
+            "layers": len(pools_same), "us_per_layer": round(us_same, 2),
+            "pct_hbm_peak": round(100 * 2 * payload_layer / (us_same * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+            "note": "the same planes, paired so that a layer's K and V plane lie in one HBM region (contents differ "
+                    "from the seeded pool after this leg: it runs after the timed region and the CPU-baseline copy)"}
+        # put the seeded contents back where this leg overwrote them: restore every layer once more from its stage
+        restore_layers()
+        torch.cuda.synchronize()
     if not args.no_extra:
         # the same restore train with an event between every two launches (adds a gap of a microsecond or two to
         # each): the layers differ only in where the driver placed their planes, and so does their time
@@ -297,6 +331,22 @@ def main():
     cpu2 = None
     if not args.no_cpu_baseline:   # needs layer 0 as saved and restored: before the legs below overwrite the pool
         cpu2 = cpu_baseline(torch, W, w, planes[0], pristine, stages[0], geom, payload_layer)
+    if not args.no_extra and placement_info.get("placed"):
+        # the plain copy again, from a layer's K plane to its V plane (different HBM regions): does the ceiling move?
+        def across():
+            for l in range(L):
+                B.tutti_copy_baseline(planes[l][1][:payload_layer], planes[l][0][:payload_layer], payload_layer)
+        across()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(5):
+            a, b = ev(), ev()
+            a.record(stream)
+            across()
+            b.record(stream)
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / L)
+        out["copy_ceiling"]["us_per_copy_between_two_regions"] = round(median(ts), 2)
     if not args.no_corun:
         out["per_cu_limits"] = per_cu_limits(torch, B, dev)
         out["corun"] = {
@@ -326,7 +376,7 @@ def main():
         out["scatter_shapes_32KiB"] = scatter_shapes(torch, B, w, stages, payload_layer, dev)
         out["visit_order"] = visit_order(torch, B, W, dev)
     if args.hnd_sweep:
-        out["head_major_rows"] = hnd_rows(torch, B, w, stages, dev)
+        out["head_major_rows"] = hnd_rows(torch, B, w, planes, stages, dev)
     if args.pinned_stage:
         out["pinned_host_stage"] = pinned_leg(torch, B, pools, cfg, d_n, d_tab, n_tab, d_fid, payload_layer,
                                               n_sqe_layer, dev)
@@ -334,16 +384,50 @@ def main():
         out["restore_address_order"] = ordered_restore(torch, B, s.num_blocks, pools, cfg, d_n, d_tab, n_tab, d_fid,
                                                        stages, payload_layer, n_sqe_layer, dev)
     if not args.no_other_configs:
-        del pools, planes, stages, restore_layers, save_layers, save_layers_unfused
+        del pools, planes, pools_same, planes_same, stages, restore_layers, save_layers, save_layers_unfused
         torch.cuda.empty_cache()
         out["other_configs"] = {
-            "config3_batch64_zipf": restore_leg(torch, B, W.batch64_zipf(), dev, max_layers=8),
-            "config4_llama70b_128k": restore_leg(torch, B, W.llama70b_128k(), dev, max_layers=80),
+            "config3_batch64_zipf": restore_leg(torch, B, W.batch64_zipf(), dev, max_layers=8,
+                                                place=not args.no_placement),
+            "config4_llama70b_128k": restore_leg(torch, B, W.llama70b_128k(), dev, max_layers=80,
+                                                 place=not args.no_placement),
         }
     if cpu2 is not None:
         out["cpu_baseline"] = cpu2
         out["cpu_baseline"]["other_configs"] = cpu_baseline_others(W)
     print(json.dumps(out), flush=True)
+
+
+def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True):
+    """K and V planes for n_layers layers.  place: candidates covering about 200 GiB are allocated, told apart by
+    HBM region with paper_2605_03375_amd.placement (a timing probe with the real restore call), every layer gets a K
+    plane and a V plane from different regions, and the candidates not needed are freed.  Also returns the same
+    planes paired within a region (what an allocator that knows nothing of the regions usually produces: the layout
+    to compare against) and a description.  Contents are left as allocated."""
+    from paper_2605_03375_amd import placement
+    free, _ = torch.cuda.mem_get_info()
+    fit = int((free - reserve_bytes) // plane_bytes)
+    if not place or fit < 2 * n_layers + 2:
+        n = min(n_layers, fit // 2)
+        cands = [torch.empty(plane_bytes, dtype=torch.uint8, device=dev) for _ in range(2 * n)]
+        planes = [(cands[2 * l], cands[2 * l + 1]) for l in range(n)]
+        return planes, [], {"placed": False, "why": "switched off" if not place else "no room for spare candidates"}
+    n_cand = min(fit, max(3 * n_layers, int((200 << 30) // plane_bytes)))
+    cands = [torch.empty(plane_bytes, dtype=torch.uint8, device=dev) for _ in range(n_cand)]
+    classes, report = placement.classify_planes(cands, dev)
+    info = {"candidates": n_cand, "candidate_GiB": round(n_cand * plane_bytes / 2 ** 30, 1),
+            "regions_in_allocation_order": "".join("ABC?"[c] for c in classes), "rounds": report["rounds"]}
+    pairs = placement.choose_pairs(classes, n_layers, strict=False)
+    info["placed"] = True
+    used = sorted(i for p in pairs for i in p)
+    same = placement.same_region_pairs([classes[i] for i in used], n_layers)
+    planes = [(cands[i], cands[j]) for i, j in pairs]
+    planes_same = [(cands[used[i]], cands[used[j]]) for i, j in same]
+    info["layers_with_K_and_V_in_different_regions"] = sum(1 for i, j in pairs if classes[i] != classes[j] and
+                                                            classes[i] >= 0 and classes[j] >= 0)
+    del cands
+    torch.cuda.empty_cache()
+    return planes, planes_same, info
 
 
 def ordered_restore(torch, B, num_blocks, pools, cfg, d_n, d_tab, n_tab, d_fid, stages, payload, n_sqe, dev, reps=5):
@@ -394,7 +478,7 @@ def ordered_restore(torch, B, num_blocks, pools, cfg, d_n, d_tab, n_tab, d_fid, 
     return res
 
 
-def restore_leg(torch, B, w, dev, max_layers, reps=5):
+def restore_leg(torch, B, w, dev, max_layers, reps=5, place=True):
     """Per-layer tutti_layer_restore of another workload at its real pool size: as many layers resident
     as fit (each with its own planes and staging buffer, so launches stay cold), contents left as
     allocated (timing only; parity for these shapes is in the tests)."""
@@ -410,9 +494,11 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
     geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
                 head_dim=s.head_dim, elt_bytes=s.elt_bytes)
     cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
-    planes = [(torch.empty(plane_bytes, dtype=torch.uint8, device=dev),
-               torch.empty(plane_bytes, dtype=torch.uint8, device=dev)) for _ in range(L)]
+    planes, planes_same, placement_info = placed_planes(torch, L, plane_bytes, dev,
+                                                        reserve_bytes=n_stage * payload + (10 << 30), place=place)
+    L = len(planes)
     pools = [B.make_pool(k, v, **geom) for k, v in planes]
+    pools_same = [B.make_pool(k, v, **geom) for k, v in planes_same]
     stages = [torch.empty(payload, dtype=torch.uint8, device=dev) for _ in range(min(L, n_stage))]
     d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
     d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
@@ -458,7 +544,14 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
             B.tutti_layer_save(pools[l], cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, st, payload, st.data_ptr(), 1, ext,
                                tot, sqe, n_sqe, 0, status)
 
+    def same_train():
+        for l, p in enumerate(pools_same):
+            st = stages[l % len(stages)]
+            B.tutti_layer_restore(p, cfg, d_n, w.n_req, d_tab, n_tab, d_fid, l, st, payload, st.data_ptr(), 1, ext,
+                                  tot, sqe, n_sqe, 0, status)
+
     us = timed(train, L)
+    us_same = timed(same_train, len(pools_same)) if pools_same else None
     order_us = timed(order, 1)
     us_ordered = timed(lambda: train(True), L)
     us_save = timed(save_train, L)
@@ -468,6 +561,10 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5):
            "us_per_layer": round(us, 2), "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
            "traffic_GBps": round(2 * payload / (us * 1e-6) / 1e9, 1),
            "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+           "placement": {k: v for k, v in placement_info.items() if k != "rounds"},
+           "restore_K_and_V_in_one_region": None if us_same is None else {
+               "layers": len(pools_same), "us_per_layer": round(us_same, 2),
+               "pct_hbm_peak": round(100 * 2 * payload / (us_same * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)},
            "save": {"us_per_layer": round(us_save, 2),
                     "pct_hbm_peak": round(100 * 2 * payload / (us_save * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2)},
            "address_order": {"us_per_layer": round(us_ordered, 2), "gain_pct": round(100 * (1 - us_ordered / us), 2),
@@ -608,7 +705,7 @@ def ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid, payload,
     return res
 
 
-def hnd_rows(torch, B, w, stages, dev, layers=8, reps=5):
+def hnd_rows(torch, B, w, planes, stages, dev, layers=8, reps=5):
     """Head-major pools ([h][T][d] blocks) of config 2's block size (32 KiB, 16 tokens) with (token, head) rows of
     256, 128, 64 and 32 bytes: tutti_obj_unpack / tutti_obj_pack alone, once moved 16 bytes per lane straight
     between the two orders and once through token tiles in LDS (the choice forced with the measurement library's
@@ -617,10 +714,8 @@ def hnd_rows(torch, B, w, stages, dev, layers=8, reps=5):
     bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
     n_tab = int(w.block_table.size)
     payload = 2 * n_tab * bb
-    L = min(layers, len(stages))
-    plane_bytes = s.num_blocks * bb
-    planes = [(torch.empty(plane_bytes, dtype=torch.uint8, device=dev),
-               torch.empty(plane_bytes, dtype=torch.uint8, device=dev)) for _ in range(L)]
+    L = min(layers, len(stages), len(planes))
+    planes = planes[:L]                 # the bench's own planes (their contents are not needed any more)
     d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
     d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
     ext = torch.zeros(32, dtype=torch.uint8, device=dev)

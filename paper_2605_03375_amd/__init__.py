@@ -4,4 +4,4 @@
 synthetic inputs.  Importing the package loads nothing; `binding.lib()` raises if the HIP
 library has not been built.
 """
-__all__ = ["binding", "workloads", "build"]
+__all__ = ["binding", "workloads", "build", "placement"]

@@ -176,13 +176,16 @@ def host_address_tags(n_bytes: int, base_word: int = 0) -> np.ndarray:
     return (np.arange(n_bytes // 4, dtype=np.uint64) + base_word).astype(np.uint32).view(np.uint8)
 
 
-def device_values(seed: int, n_elts: int, dtype: str, device="cuda"):
-    """Seeded uniform[-1,1) fp16 / bf16 values drawn on the device (a torch tensor)."""
+def device_values(seed: int, n_elts: int, dtype: str, device="cuda", out=None):
+    """Seeded uniform[-1,1) fp16 / bf16 values drawn on the device (a torch tensor).  `out`: a tensor of n_elts
+    elements of that dtype to fill in place (a buffer whose place in memory was chosen beforehand)."""
     import torch
     g = torch.Generator(device=device)
     g.manual_seed(seed)
     td = {"fp16": torch.float16, "bf16": torch.bfloat16}[dtype]
-    out = torch.empty(n_elts, dtype=td, device=device)
+    if out is None:
+        out = torch.empty(n_elts, dtype=td, device=device)
+    assert out.dtype == td and out.numel() == n_elts
     step = 1 << 28
     for lo in range(0, n_elts, step):
         out[lo:lo + step].uniform_(-1.0, 1.0, generator=g)
