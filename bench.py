@@ -413,8 +413,15 @@ def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True):
         planes = [(cands[2 * l], cands[2 * l + 1]) for l in range(n)]
         return planes, [], {"placed": False, "why": "switched off" if not place else "no room for spare candidates"}
     n_cand = min(fit, max(3 * n_layers, int((200 << 30) // plane_bytes)))
-    cands = [torch.empty(plane_bytes, dtype=torch.uint8, device=dev) for _ in range(n_cand)]
-    classes, report = placement.classify_planes(cands, dev)
+    cands = []
+    try:
+        cands = [torch.empty(plane_bytes, dtype=torch.uint8, device=dev) for _ in range(n_cand)]
+        classes, report = placement.classify_planes(cands, dev)
+    except (RuntimeError, ValueError) as e:       # out of memory, or a probe that reported a status: go on unplaced
+        del cands
+        torch.cuda.empty_cache()
+        log(f"[bench] placement failed ({type(e).__name__}: {str(e)[:200]}); taking the planes as allocated")
+        return placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=False)
     info = {"candidates": n_cand, "candidate_GiB": round(n_cand * plane_bytes / 2 ** 30, 1),
             "regions_in_allocation_order": "".join("ABC?"[c] for c in classes), "rounds": report["rounds"]}
     pairs = placement.choose_pairs(classes, n_layers, strict=False)
