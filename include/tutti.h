@@ -58,7 +58,11 @@ extern "C" {
 
 /* One layer's paged pool (sec. 2.1 "Paged KV Memory Management"): a K plane and a V plane, each
  * num_blocks blocks of T*h*d*e bytes, block b at base + b*block_stride.  Planes stay owned by the
- * caller.  Requirements: bases and block_stride multiples of 16; T*h*d*e a multiple of 16. */
+ * caller.  Requirements: bases and block_stride multiples of 16; T*h*d*e a multiple of 16.
+ * The two planes may lie anywhere.  Measured on the MI355X: its 288 GB of HBM behave as three regions of 96 GB, and
+ * a restore (32 KiB blocks scattered over the K plane, then over the V plane) runs at the speed of a contiguous
+ * copy when the two planes lie in different regions, 15 % slower when they share one; the Python package's
+ * `placement` module finds such pairs of buffers by timing when a pool is created. */
 typedef struct tutti_pool {
   void *k_base;
   void *v_base;
