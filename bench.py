@@ -209,7 +209,9 @@ def main():
 
     out = {
         "metric": "per-layer KV restore payload GB/s (and % of HBM peak in roofline.frac), Llama-3-8B shape, 32K-token "
-                  "prefix, one launch per layer; the step also saves every layer (see save); SQEs built/sec in sqe",
+                  "prefix, one launch per layer, the pool's planes placed across the HBM regions (config.placement; the same "
+                  "planes without that in restore_K_and_V_in_one_region); the step also saves every layer (see save); "
+                  "SQEs built/sec in sqe",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
