@@ -19,7 +19,8 @@
  *     measurements live in a separate library (tutti_bench.h), not here.
  *   - A call validates its host arguments in O(1), enqueues a constant number of kernels on
  *     `stream` and returns; it never synchronises and never copies to the host.  Results are
- *     valid once the caller has synchronised the stream.
+ *     valid once the caller has synchronised the stream.  (The set-up calls tutti_place_* are
+ *     the exception, stated where they are declared: they time launches and block.)
  *   - Return value: 0 (TUTTI_OK) or a negative TUTTI_E* code; on error nothing was enqueued.
  *   - What only the device can know is reported through the optional status word d_status
  *     (TUTTI_ST_* bits, ORed in atomically, never cleared by the library) and never causes an
@@ -61,8 +62,8 @@ extern "C" {
  * caller.  Requirements: bases and block_stride multiples of 16; T*h*d*e a multiple of 16.
  * The two planes may lie anywhere.  Measured on the MI355X: its 288 GB of HBM behave as three regions of 96 GB, and
  * a restore (32 KiB blocks scattered over the K plane, then over the V plane) runs at the speed of a contiguous
- * copy when the two planes lie in different regions, 15 % slower when they share one; the Python package's
- * `placement` module finds such pairs of buffers by timing when a pool is created. */
+ * copy when the two planes lie in different regions, 15 % slower when they share one; tutti_place_classify and
+ * tutti_place_pairs below find such pairs of buffers by timing when a pool is created. */
 typedef struct tutti_pool {
   void *k_base;
   void *v_base;
@@ -478,6 +479,53 @@ int tutti_table_validate_ws(uint32_t num_blocks, const uint32_t *d_block_table, 
 #define TUTTI_STATIC_VALIDATE_MAX_BLOCKS (1u << 22)
 int tutti_table_validate_static(uint32_t num_blocks, const uint32_t *d_block_table, uint32_t table_len,
                                 uint32_t *d_status, void *stream);
+
+/* ---- set-up: where a pool's planes sit in HBM.  The pool is allocated and registered once and stays fixed for
+ * the engine's life (sec. 3.1 "Scalable GPU File Pool", "P2P Memory Mapping Table"), so its place in memory is
+ * chosen once, before any layer is restored (sec. 3.4 "Layer-wise Overlapping").  Measured on the MI355X: its 288 GB
+ * of HBM behave as three regions of 96 GB; a restore runs at the speed of a contiguous copy when a layer's K plane
+ * and V plane lie in different regions and about 15 % slower when they share one.  Nothing in an address tells the
+ * region, so the calls below tell it by timing: the library's own restore (tutti_layer_restore, 2048 blocks of
+ * 32 KiB picked by a fixed pseudo-random table) on the pool (plane a, plane b) is slow exactly when a and b share a
+ * region.  Unlike the data calls these BLOCK: they synchronise `stream`, time with events and return host values;
+ * they allocate no device memory (the caller lends d_work) and OVERWRITE blocks of the planes they are given with the
+ * bytes of d_work, so they run before the pool is filled.
+ *
+ * planes: a HOST array of n device pointers, each the start of a buffer of plane_bytes bytes (16-byte aligned,
+ * plane_bytes >= TUTTI_PLACE_MIN_PLANE_BYTES, else TUTTI_ERANGE).  d_work: device memory, 256-byte aligned,
+ * work_bytes >= tutti_place_work_bytes() (else TUTTI_ERANGE); contents need not be initialised. */
+#define TUTTI_PLACE_MIN_PLANE_BYTES (128ull << 20)
+#define TUTTI_PLACE_MAX_REGIONS 8u
+uint64_t tutti_place_work_bytes(void);
+/* us[i] (HOST array of n floats) <- microseconds of the probe restore on the pool (ref, cands[i]): the median of
+ * `reps` (1..16) timed passes after one warm-up pass; each figure includes the gap between two launches, the same
+ * for all.  TUTTI_EINVAL if the device reported a status (it cannot with valid planes). */
+int tutti_place_pair_times(const void *ref, const void *const *cands, uint32_t n, uint64_t plane_bytes, void *d_work,
+                           uint64_t work_bytes, uint32_t reps, float *us, void *stream);
+/* One round of the classification, for the caller's records. */
+typedef struct tutti_place_round {
+  uint32_t reference;   /* index of the round's reference plane */
+  uint32_t members;     /* planes put into the reference's class */
+  float same_region_us; /* the pool (reference, reference): one region by construction, the slow case */
+  float fastest_us;     /* the fastest pool (reference, x) of the round */
+} tutti_place_round;
+/* classes[i] (HOST array of n) <- region class 0, 1, ... of planes[i], or -1 if max_regions rounds did not reach
+ * it.  Round c takes the first unclassified plane r as reference and times (r, r) and (r, x) for every
+ * unclassified x; x joins class c if its time is nearer the slow case (r, r) than the round's fastest pair.  A
+ * round in which nothing beats the slow case by min_gap_us puts everything left into class c (a part with one
+ * region ends there, with every plane in class 0).  max_regions in 1..TUTTI_PLACE_MAX_REGIONS.  rounds (HOST,
+ * max_regions records, may be NULL) and *n_rounds (may be NULL) <- what each round measured. */
+int tutti_place_classify(const void *const *planes, uint32_t n, uint64_t plane_bytes, void *d_work,
+                         uint64_t work_bytes, uint32_t max_regions, double min_gap_us, int32_t *classes,
+                         tutti_place_round *rounds, uint32_t *n_rounds, void *stream);
+/* Host code only.  pairs[2p], pairs[2p+1] (p < n_pairs) <- indices (K plane, V plane) with different classes >= 0,
+ * every plane used at most once; taken greedily from the two classes with the most planes left, lowest indices
+ * first, which forms as many such pairs as any pairing can.  *n_mixed (may be NULL) <- how many pairs were formed
+ * that way.  If fewer than n_pairs: TUTTI_EAGAIN when strict != 0 (pairs untouched beyond *n_mixed); otherwise
+ * the rest is filled with pairs of the planes left over (same class or class -1), lowest indices first, and
+ * TUTTI_ERANGE if even that does not give n_pairs. */
+int tutti_place_pairs(const int32_t *classes, uint32_t n, uint32_t n_pairs, uint32_t strict, uint32_t *pairs,
+                      uint32_t *n_mixed);
 
 /* ---- housekeeping */
 const char *tutti_strerror(int code);

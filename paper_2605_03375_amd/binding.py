@@ -54,7 +54,8 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_io_domain_destroy", "tutti_table_validate_work_bytes", "tutti_table_validate_ws",
            "tutti_table_validate_static", "tutti_layer_restore_ordered", "tutti_table_order",
            "tutti_table_order_work_bytes", "tutti_retrieve_layer_issue", "tutti_store_layer_issue",
-           "tutti_complete_io", "tutti_wait_cqe_range"]
+           "tutti_complete_io", "tutti_wait_cqe_range", "tutti_place_work_bytes", "tutti_place_pair_times",
+           "tutti_place_classify", "tutti_place_pairs"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
                  "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
 SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
@@ -83,6 +84,15 @@ class tutti_filestore(C.Structure):
 class tutti_sq_state(C.Structure):
     _fields_ = [("depth", C.c_uint32), ("head", C.c_uint32), ("held", C.c_uint32), ("cq_seen", C.c_uint32),
                 ("done", C.c_void_p)]
+
+
+class tutti_place_round(C.Structure):
+    _fields_ = [("reference", C.c_uint32), ("members", C.c_uint32), ("same_region_us", C.c_float),
+                ("fastest_us", C.c_float)]
+
+
+PLACE_MIN_PLANE_BYTES = 128 << 20
+PLACE_MAX_REGIONS = 8
 
 
 class tutti_io_profile(C.Structure):
@@ -174,8 +184,15 @@ def _declare(L, bench):
     L.tutti_wait_cqe_host.argtypes = [ps, vp, vp, u32, u32]
     L.tutti_iocbs_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, C.POINTER(u32)]
     L.tutti_budget_for_slack.argtypes = [pio, u32, u32, u32, C.c_double, u32, C.POINTER(u32)]
+    L.tutti_place_work_bytes.argtypes = []
+    L.tutti_place_work_bytes.restype = u64
+    L.tutti_place_pair_times.argtypes = [vp, C.POINTER(vp), u32, u64, vp, u64, u32, C.POINTER(C.c_float), vp]
+    L.tutti_place_classify.argtypes = [C.POINTER(vp), u32, u64, vp, u64, u32, C.c_double, C.POINTER(C.c_int32),
+                                       C.POINTER(tutti_place_round), C.POINTER(u32), vp]
+    L.tutti_place_pairs.argtypes = [C.POINTER(C.c_int32), u32, u32, u32, C.POINTER(u32), C.POINTER(u32)]
     for name in EXPORTS:
-        if name not in ("tutti_strerror", "tutti_version", "tutti_sq_free_count", "tutti_table_validate_work_bytes"):
+        if name not in ("tutti_strerror", "tutti_version", "tutti_sq_free_count", "tutti_table_validate_work_bytes",
+                        "tutti_table_order_work_bytes", "tutti_place_work_bytes"):
             getattr(L, name).restype = C.c_int
     if bench:
         L.tutti_copy_baseline.argtypes = [vp, vp, u64, u32, vp]
@@ -586,3 +603,44 @@ def tutti_io_domain_create(n_cus):
 
 def tutti_io_domain_destroy(stream):
     return _check("tutti_io_domain_destroy", lib().tutti_io_domain_destroy(C.c_void_p(int(stream))))
+
+
+def tutti_place_work_bytes():
+    return lib().tutti_place_work_bytes()
+
+
+def _plane_array(planes):
+    return (C.c_void_p * len(planes))(*[_p(x) for x in planes])
+
+
+def tutti_place_pair_times(ref, cands, plane_bytes, d_work, work_bytes, reps=3, stream=None):
+    """Microseconds of the probe restore on the pool (ref, c) for every c in cands (a list of floats).  Blocks."""
+    us = (C.c_float * len(cands))()
+    _check("tutti_place_pair_times",
+           lib().tutti_place_pair_times(_p(ref), _plane_array(cands), len(cands), plane_bytes, _p(d_work), work_bytes,
+                                        reps, us, _stream(stream)))
+    return list(us)
+
+
+def tutti_place_classify(planes, plane_bytes, d_work, work_bytes, max_regions=3, min_gap_us=3.0, stream=None):
+    """(classes, rounds): the region class of every plane and the tutti_place_round records.  Blocks."""
+    n = len(planes)
+    classes = (C.c_int32 * n)()
+    rounds = (tutti_place_round * PLACE_MAX_REGIONS)()
+    n_rounds = C.c_uint32(0)
+    _check("tutti_place_classify",
+           lib().tutti_place_classify(_plane_array(planes), n, plane_bytes, _p(d_work), work_bytes, max_regions,
+                                      min_gap_us, classes, rounds, C.byref(n_rounds), _stream(stream)))
+    return list(classes), [rounds[i] for i in range(n_rounds.value)]
+
+
+def tutti_place_pairs(classes, n_pairs, strict=True):
+    """(pairs, n_mixed): n_pairs (K plane, V plane) index pairs, the first n_mixed from different classes.  Host
+    code only.  Raises TuttiError(EAGAIN) when strict and the classes do not allow n_pairs mixed pairs,
+    TuttiError(ERANGE) when the planes do not make n_pairs pairs at all."""
+    n = len(classes)
+    cls = (C.c_int32 * n)(*classes)
+    pairs = (C.c_uint32 * (2 * n_pairs))()
+    n_mixed = C.c_uint32(0)
+    _check("tutti_place_pairs", lib().tutti_place_pairs(cls, n, n_pairs, 1 if strict else 0, pairs, C.byref(n_mixed)))
+    return [(pairs[2 * i], pairs[2 * i + 1]) for i in range(n_pairs)], n_mixed.value

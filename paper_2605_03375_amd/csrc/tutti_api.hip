@@ -3,7 +3,8 @@
 // Each entry point checks its host arguments in O(1), fills a small argument struct and
 // enqueues a constant number of kernels on the caller's stream.  No allocation, no
 // synchronisation, no device-to-host copy, and no state that one call leaves for another (the
-// only thing remembered is the device's compute-unit count).
+// only thing remembered is the device's compute-unit count).  The set-up calls tutti_place_* are
+// the exception: they time the restore on candidate planes and return host values.
 //
 // The same file builds the measurement library libtutti_bench.so when TUTTI_BENCH_BUILD is defined:
 // the same entry points, plus the launch-tuning knobs (per host thread), the baseline kernels and
@@ -11,7 +12,10 @@
 // library holds the two launch shapes it uses and no knob.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
+#include <unordered_map>
+#include <vector>
 
 #include "tutti.h"
 #ifdef TUTTI_BENCH_BUILD
@@ -1058,6 +1062,219 @@ int tutti_table_order(uint32_t num_blocks, const uint32_t *d_block_table, uint32
                      d_visit, d_status);
   e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+// ---- set-up: where a pool's planes sit in HBM (timing probe).  These calls block and return host values.
+
+extern "C++" {
+namespace {
+
+// The probe: a restore of 2048 blocks of 32 KiB (128 MiB of payload), the shape the effect was measured with.
+constexpr uint32_t kProbeBlocks = 2048, kProbeTokens = 16, kProbeHeads = 8, kProbeDim = 128, kProbeElt = 2;
+constexpr uint32_t kProbeBlockBytes = kProbeTokens * kProbeHeads * kProbeDim * kProbeElt;
+constexpr uint64_t kProbePayload = 2ull * kProbeBlocks * kProbeBlockBytes;
+constexpr uint32_t kProbeChunk = 2u << 20;
+constexpr uint32_t kProbeEntries = 2u * (kProbeBlocks * kProbeBlockBytes / kProbeChunk);
+// d_work: a header (block count, file id, status, totals, one extent), the block table, the entries, the staging area
+constexpr uint64_t kProbeOffStatus = 8, kProbeOffTotals = 16, kProbeOffExtent = 64, kProbeOffTable = 256;
+constexpr uint64_t kProbeOffSqe = kProbeOffTable + 4ull * kProbeBlocks;
+constexpr uint64_t kProbeOffStage = 65536;
+static_assert(kProbeOffSqe + 64ull * kProbeEntries <= kProbeOffStage, "the probe's small buffers overlap its staging area");
+static_assert(kProbePayload == TUTTI_PLACE_MIN_PLANE_BYTES, "a plane must hold the probe's blocks twice over");
+
+uint64_t splitmix64(uint64_t *x) {
+  uint64_t z = (*x += 0x9e3779b97f4a7c15ull);
+  z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+  z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+  return z ^ (z >> 31);
+}
+
+struct Events {
+  std::vector<hipEvent_t> ev;
+  ~Events() {
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+  }
+  hipError_t make(size_t n) {
+    ev.reserve(n);
+    for (size_t i = 0; i < n; ++i) {
+      hipEvent_t e;
+      const hipError_t rc = hipEventCreate(&e);
+      if (rc != hipSuccess) return rc;
+      ev.push_back(e);
+    }
+    return hipSuccess;
+  }
+};
+
+struct Probe {
+  char *work = nullptr;
+  uint64_t plane_bytes = 0;
+  hipStream_t stream = nullptr;
+  tutti_objcfg cfg{4096u, kProbeChunk, 1u};
+
+  // Checks the arguments the two calls share and writes the header and the table: 2048 distinct block ids drawn
+  // from the whole plane (the first 2048 places of a Fisher-Yates shuffle, kept sparse).
+  int init(uint64_t plane_bytes_, void *d_work, uint64_t work_bytes, void *stream_) {
+    if (!d_work || reinterpret_cast<uintptr_t>(d_work) % 256 != 0) return TUTTI_EINVAL;
+    if (plane_bytes_ < TUTTI_PLACE_MIN_PLANE_BYTES || work_bytes < tutti_place_work_bytes()) return TUTTI_ERANGE;
+    if (plane_bytes_ / kProbeBlockBytes > 0xffffffffull) return TUTTI_ERANGE;
+    work = static_cast<char *>(d_work);
+    plane_bytes = plane_bytes_;
+    stream = static_cast<hipStream_t>(stream_);
+    const uint32_t num_blocks = static_cast<uint32_t>(plane_bytes / kProbeBlockBytes);
+    std::vector<uint32_t> head((kProbeOffTable + 4ull * kProbeBlocks) / 4, 0u);
+    head[0] = kProbeBlocks;  // the one request's block count
+    head[1] = 1u;            // its file id
+    std::unordered_map<uint32_t, uint32_t> moved;  // places of the shuffle that no longer hold their own index
+    uint64_t seed = 0x7475747469ull;
+    for (uint32_t j = 0; j < kProbeBlocks; ++j) {
+      const uint32_t k = j + static_cast<uint32_t>(splitmix64(&seed) % (num_blocks - j));
+      const auto at_k = moved.find(k);
+      const auto at_j = moved.find(j);
+      const uint32_t vk = at_k == moved.end() ? k : at_k->second;
+      const uint32_t vj = at_j == moved.end() ? j : at_j->second;
+      moved[k] = vj;
+      head[kProbeOffTable / 4 + j] = vk;
+    }
+    hipError_t e = hipMemcpyAsync(work, head.data(), head.size() * 4, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamSynchronize(stream);  // `head` goes out of scope
+    return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+  }
+
+  int restore(const void *k_plane, const void *v_plane) const {
+    tutti_pool pool{};
+    pool.k_base = const_cast<void *>(k_plane);
+    pool.v_base = const_cast<void *>(v_plane);
+    pool.block_stride = kProbeBlockBytes;
+    pool.num_blocks = static_cast<uint32_t>(plane_bytes / kProbeBlockBytes);
+    pool.block_tokens = kProbeTokens;
+    pool.num_kv_heads = kProbeHeads;
+    pool.head_dim = kProbeDim;
+    pool.elt_bytes = kProbeElt;
+    pool.pool_layout = TUTTI_LAYOUT_NHD;
+    return tutti_layer_restore(&pool, &cfg, reinterpret_cast<const uint32_t *>(work), 1u,
+                               reinterpret_cast<const uint32_t *>(work + kProbeOffTable), kProbeBlocks,
+                               reinterpret_cast<const uint32_t *>(work + 4), 0u, work + kProbeOffStage, kProbePayload,
+                               0ull, 1u, reinterpret_cast<tutti_extent *>(work + kProbeOffExtent),
+                               reinterpret_cast<uint64_t *>(work + kProbeOffTotals),
+                               reinterpret_cast<tutti_sqe *>(work + kProbeOffSqe), kProbeEntries, 0u,
+                               reinterpret_cast<uint32_t *>(work + kProbeOffStatus), stream);
+  }
+
+  // us[i] <- median over `reps` passes of the restore on (ref, cands[i]), timed between events on the stream
+  int pair_times(const void *ref, const void *const *cands, uint32_t n, uint32_t reps, float *us) const {
+    Events evs;
+    hipError_t e = evs.make(n + 1u);
+    if (e != hipSuccess) return hip_fail(e);
+    std::vector<float> t(static_cast<size_t>(reps) * n);
+    for (uint32_t rep = 0; rep <= reps; ++rep) {  // the first pass warms up
+      int rc = restore(ref, cands[n - 1]);        // so that the first timed launch does not start an idle queue
+      if (rc) return rc;
+      for (uint32_t i = 0; i < n; ++i) {
+        e = hipEventRecord(evs.ev[i], stream);
+        if (e != hipSuccess) return hip_fail(e);
+        rc = restore(ref, cands[i]);
+        if (rc) return rc;
+      }
+      e = hipEventRecord(evs.ev[n], stream);
+      if (e != hipSuccess) return hip_fail(e);
+      e = hipStreamSynchronize(stream);
+      if (e != hipSuccess) return hip_fail(e);
+      if (rep == 0) continue;
+      for (uint32_t i = 0; i < n; ++i) {
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, evs.ev[i], evs.ev[i + 1]);
+        if (e != hipSuccess) return hip_fail(e);
+        t[static_cast<size_t>(i) * reps + (rep - 1)] = ms * 1e3f;
+      }
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+      float *row = t.data() + static_cast<size_t>(i) * reps;
+      std::sort(row, row + reps);
+      us[i] = (reps & 1u) ? row[reps / 2] : 0.5f * (row[reps / 2 - 1] + row[reps / 2]);
+    }
+    return TUTTI_OK;
+  }
+
+  // the status word the probe's launches ORed into: anything but 0 means the planes were not what the call was told
+  int status_clean() const {
+    uint32_t st = 0;
+    const hipError_t e = hipMemcpy(&st, work + kProbeOffStatus, 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e);
+    return st == 0 ? TUTTI_OK : TUTTI_EINVAL;
+  }
+};
+
+int check_plane_list(const void *const *planes, uint32_t n) {
+  if (n == 0 || !planes) return TUTTI_EINVAL;
+  if (n > 65536u) return TUTTI_ERANGE;
+  for (uint32_t i = 0; i < n; ++i)
+    if (!planes[i] || !aligned16(planes[i])) return TUTTI_EINVAL;
+  return TUTTI_OK;
+}
+
+}  // namespace
+}  // extern "C++"
+
+uint64_t tutti_place_work_bytes(void) { return kProbeOffStage + kProbePayload; }
+
+int tutti_place_pair_times(const void *ref, const void *const *cands, uint32_t n, uint64_t plane_bytes, void *d_work,
+                           uint64_t work_bytes, uint32_t reps, float *us, void *stream) {
+  int rc = check_plane_list(cands, n);
+  if (rc) return rc;
+  if (!ref || !aligned16(ref) || !us || reps == 0 || reps > 16) return TUTTI_EINVAL;
+  Probe p;
+  rc = p.init(plane_bytes, d_work, work_bytes, stream);
+  if (rc) return rc;
+  rc = p.pair_times(ref, cands, n, reps, us);
+  return rc ? rc : p.status_clean();
+}
+
+int tutti_place_classify(const void *const *planes, uint32_t n, uint64_t plane_bytes, void *d_work,
+                         uint64_t work_bytes, uint32_t max_regions, double min_gap_us, int32_t *classes,
+                         tutti_place_round *rounds, uint32_t *n_rounds, void *stream) {
+  if (n_rounds) *n_rounds = 0;
+  int rc = check_plane_list(planes, n);
+  if (rc) return rc;
+  if (!classes || max_regions == 0 || max_regions > TUTTI_PLACE_MAX_REGIONS || !(min_gap_us >= 0.0)) return TUTTI_EINVAL;
+  Probe p;
+  rc = p.init(plane_bytes, d_work, work_bytes, stream);
+  if (rc) return rc;
+  for (uint32_t i = 0; i < n; ++i) classes[i] = -1;
+  std::vector<uint32_t> todo;
+  std::vector<const void *> cands;
+  std::vector<float> us;
+  for (uint32_t c = 0; c < max_regions; ++c) {
+    todo.clear();
+    for (uint32_t i = 0; i < n; ++i)
+      if (classes[i] < 0) todo.push_back(i);
+    if (todo.empty()) break;
+    const uint32_t r = todo[0];
+    cands.assign(1, planes[r]);  // (r, r): both planes in one region by construction
+    for (uint32_t i : todo) cands.push_back(planes[i]);
+    us.assign(cands.size(), 0.f);
+    rc = p.pair_times(planes[r], cands.data(), static_cast<uint32_t>(cands.size()), 3u, us.data());
+    if (rc) return rc;
+    const float slow = us[0];
+    const float fast = *std::min_element(us.begin() + 1, us.end());
+    uint32_t members = 0;
+    if (slow - fast < min_gap_us) {  // nothing left lies in another region
+      for (uint32_t i : todo) classes[i] = static_cast<int32_t>(c);
+      members = static_cast<uint32_t>(todo.size());
+    } else {
+      const float mid = 0.5f * (slow + fast);
+      for (size_t k = 0; k < todo.size(); ++k)
+        if (us[k + 1] > mid || todo[k] == r) {
+          classes[todo[k]] = static_cast<int32_t>(c);
+          ++members;
+        }
+    }
+    if (rounds) rounds[c] = tutti_place_round{r, members, slow, fast};
+    if (n_rounds) *n_rounds = c + 1;
+    if (members == todo.size()) break;
+  }
+  return p.status_clean();
 }
 
 #ifdef TUTTI_BENCH_BUILD

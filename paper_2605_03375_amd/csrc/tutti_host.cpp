@@ -1,6 +1,6 @@
-// Host-only part of libtutti: the application's side of the rings (get_iocb, reaping the completion queue)
-// and the slack-table lookups.  No HIP call in this file: everything here is O(1) or O(rows) bookkeeping on
-// host memory the caller owns, so it runs without a GPU.
+// Host-only part of libtutti: the application's side of the rings (get_iocb, reaping the completion queue),
+// the slack-table lookups and the pairing of classified planes.  No HIP call in this file: everything here is
+// O(1) or O(rows) bookkeeping on host memory the caller owns, so it runs without a GPU.
 #include <stddef.h>
 #include <stdint.h>
 
@@ -135,6 +135,57 @@ int tutti_budget_for_slack(const tutti_io_profile *rows, uint32_t n_rows, uint32
   }
   *cu_budget = found ? best_budget : 0u;
   return found ? TUTTI_OK : TUTTI_EAGAIN;
+}
+
+// ---- pool placement: pairing the classified planes
+
+int tutti_place_pairs(const int32_t *classes, uint32_t n, uint32_t n_pairs, uint32_t strict, uint32_t *pairs,
+                      uint32_t *n_mixed) {
+  if (n_mixed) *n_mixed = 0;
+  if ((n > 0 && !classes) || (n_pairs > 0 && !pairs)) return TUTTI_EINVAL;
+  uint32_t left[TUTTI_PLACE_MAX_REGIONS] = {};  // planes of the class not yet used
+  uint32_t next[TUTTI_PLACE_MAX_REGIONS] = {};  // every plane of the class below this index is used
+  for (uint32_t i = 0; i < n; ++i) {
+    if (classes[i] < -1 || classes[i] >= static_cast<int32_t>(TUTTI_PLACE_MAX_REGIONS)) return TUTTI_EINVAL;
+    if (classes[i] >= 0) ++left[classes[i]];
+  }
+  auto take = [&](uint32_t c) {
+    uint32_t i = next[c];
+    while (classes[i] != static_cast<int32_t>(c)) ++i;  // left[c] > 0: there is one
+    next[c] = i + 1;
+    --left[c];
+    return i;
+  };
+  uint32_t made = 0;
+  while (made < n_pairs) {
+    // the two classes with the most planes left (ties: the lower class first)
+    int a = -1, b = -1;
+    for (uint32_t c = 0; c < TUTTI_PLACE_MAX_REGIONS; ++c) {
+      if (left[c] == 0) continue;
+      if (a < 0 || left[c] > left[a]) {
+        b = a;
+        a = static_cast<int>(c);
+      } else if (b < 0 || left[c] > left[b]) {
+        b = static_cast<int>(c);
+      }
+    }
+    if (b < 0) break;
+    pairs[2 * made] = take(static_cast<uint32_t>(a));
+    pairs[2 * made + 1] = take(static_cast<uint32_t>(b));
+    ++made;
+  }
+  if (n_mixed) *n_mixed = made;
+  if (made == n_pairs) return TUTTI_OK;
+  if (strict) return TUTTI_EAGAIN;
+  // what is left over, lowest indices first: planes of one class, and those no round reached
+  uint32_t spare = 0;
+  for (uint32_t i = 0; i < n; ++i)
+    if (classes[i] < 0 || i >= next[classes[i]]) ++spare;
+  if (spare / 2 < n_pairs - made) return TUTTI_ERANGE;
+  uint32_t slot = 2 * made;
+  for (uint32_t i = 0; i < n && slot < 2 * n_pairs; ++i)
+    if (classes[i] < 0 || i >= next[classes[i]]) pairs[slot++] = i;
+  return TUTTI_OK;
 }
 
 }  // extern "C"

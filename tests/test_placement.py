@@ -31,6 +31,63 @@ def test_choose_pairs_only_pairs_different_regions():
         P.choose_pairs(classes, 5, strict=False)
 
 
+def test_pairing_is_as_good_as_any_on_small_cases():
+    """Brute force over every way to pair up to 7 planes: none forms more pairs from different regions."""
+    import itertools
+
+    def best(classes, idx):
+        if len(idx) < 2:
+            return 0
+        first, rest = idx[0], idx[1:]
+        out = best(classes, rest)                                      # `first` stays single
+        for k, other in enumerate(rest):
+            if classes[first] != classes[other]:
+                out = max(out, 1 + best(classes, rest[:k] + rest[k + 1:]))
+        return out
+
+    for n in range(0, 8):
+        for classes in itertools.product((-1, 0, 1, 2), repeat=n):
+            idx = [i for i, c in enumerate(classes) if c >= 0]
+            most = best(classes, idx)
+            pairs, n_mixed = P.B.tutti_place_pairs(list(classes), most, strict=True)
+            assert n_mixed == most and all(classes[i] != classes[j] and min(classes[i], classes[j]) >= 0
+                                           for i, j in pairs)
+            assert len({i for p in pairs for i in p}) == 2 * most
+
+
+def test_place_arguments_are_checked_before_any_gpu_call():
+    B = P.B
+    L = B.lib()
+    import ctypes as C
+    cls = (C.c_int32 * 2)(0, 9)
+    out = (C.c_uint32 * 2)()
+    assert L.tutti_place_pairs(cls, 2, 1, 1, out, None) == B.EINVAL          # class beyond TUTTI_PLACE_MAX_REGIONS
+    assert L.tutti_place_pairs(None, 2, 1, 1, out, None) == B.EINVAL
+    assert L.tutti_place_pairs((C.c_int32 * 2)(0, 1), 2, 1, 1, None, None) == B.EINVAL
+    assert L.tutti_place_work_bytes() == (128 << 20) + 65536
+    planes = (C.c_void_p * 2)(0x1000, 0x2000)
+    us = (C.c_float * 2)()
+    cl = (C.c_int32 * 2)()
+    big, work = 1 << 30, L.tutti_place_work_bytes()
+    # every one of these returns before the probe touches the device
+    assert L.tutti_place_pair_times(0x1000, planes, 0, big, 0x10000, work, 3, us, None) == B.EINVAL      # no candidates
+    assert L.tutti_place_pair_times(None, planes, 2, big, 0x10000, work, 3, us, None) == B.EINVAL
+    assert L.tutti_place_pair_times(0x1000, planes, 2, big, 0x10000, work, 0, us, None) == B.EINVAL      # reps
+    assert L.tutti_place_pair_times(0x1000, planes, 2, big, 0x10000, work, 17, us, None) == B.EINVAL
+    assert L.tutti_place_pair_times(0x1000, planes, 2, big, 0x10000, work, 3, None, None) == B.EINVAL
+    assert L.tutti_place_pair_times(0x1000, planes, 2, big, None, work, 3, us, None) == B.EINVAL
+    assert L.tutti_place_pair_times(0x1000, planes, 2, big, 0x10010, work, 3, us, None) == B.EINVAL      # work alignment
+    assert L.tutti_place_pair_times(0x1000, planes, 2, big, 0x10000, work - 1, 3, us, None) == B.ERANGE
+    assert L.tutti_place_pair_times(0x1000, planes, 2, (128 << 20) - 16, 0x10000, work, 3, us, None) == B.ERANGE
+    assert L.tutti_place_pair_times(0x1008, planes, 2, big, 0x10000, work, 3, us, None) == B.EINVAL      # plane alignment
+    assert L.tutti_place_classify(planes, 2, big, 0x10000, work, 0, 3.0, cl, None, None, None) == B.EINVAL
+    assert L.tutti_place_classify(planes, 2, big, 0x10000, work, 9, 3.0, cl, None, None, None) == B.EINVAL
+    assert L.tutti_place_classify(planes, 2, big, 0x10000, work, 3, -1.0, cl, None, None, None) == B.EINVAL
+    assert L.tutti_place_classify(planes, 2, big, 0x10000, work, 3, 3.0, None, None, None, None) == B.EINVAL
+    assert L.tutti_place_classify(planes, 2, big, 0x10000, work - 1, 3, 3.0, cl, None, None, None) == B.ERANGE
+    assert L.tutti_place_classify(None, 2, big, 0x10000, work, 3, 3.0, cl, None, None, None) == B.EINVAL
+
+
 def test_same_region_pairs():
     classes = [0, 0, 1, 1, 1, 2, -1, 0, 0]
     pairs = P.same_region_pairs(classes, 10)
@@ -58,8 +115,7 @@ def test_classification_by_timing_agrees_with_direct_pair_timings():
         pytest.skip("all candidates lie in one region on this box")
     mixed = P.choose_pairs(classes, 3)
     same = P.same_region_pairs(classes, 3)
-    probe = P._Probe(torch, 2 << 30, dev)
-    t_mixed = [float(probe.pair_times(cands[i], [cands[j]])[0]) for i, j in mixed]
-    t_same = [float(probe.pair_times(cands[i], [cands[j]])[0]) for i, j in same]
+    t_mixed = [P.pair_times(cands[i], [cands[j]], dev)[0] for i, j in mixed]
+    t_same = [P.pair_times(cands[i], [cands[j]], dev)[0] for i, j in same]
     print("pairs from two regions:", t_mixed, "pairs within a region:", t_same)
     assert max(t_mixed) + 2.0 < min(t_same), (t_mixed, t_same)
