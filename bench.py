@@ -241,6 +241,8 @@ def main():
                  "launches_per_layer": 1},
     }
     out["config"]["placement"] = placement_info
+    out["restore"]["host_us_per_call"] = host_us_per_call(torch, restore_layers, L)
+    out["restore"]["blocks_per_call"] = n_tab
     if pools_same:
         # the same planes paired within one region (what an allocator that knows nothing of the regions mostly gives)
         def same_train():
@@ -439,6 +441,20 @@ def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True):
     return planes, planes_same, info
 
 
+def host_us_per_call(torch, fn, n_calls, reps=7):
+    """Host microseconds one call costs: wall time of the enqueueing loop alone, started on an idle stream and not
+    waiting for the device (through the Python binding, so ctypes marshalling is in it).  The paper's point is that
+    this is constant per layer whatever the number of blocks (sec. 3.2: the CPU launches one I/O kernel per layer)."""
+    ts = []
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        ts.append((time.perf_counter() - t0) * 1e6 / n_calls)
+    torch.cuda.synchronize()
+    return round(median(ts), 2)
+
+
 def ordered_restore(torch, B, num_blocks, pools, cfg, d_n, d_tab, n_tab, d_fid, stages, payload, n_sqe, dev, reps=5):
     """Config 2's restore again, once in table order (tutti_layer_restore) and once with the blocks visited by
     ascending pool address (tutti_table_order once, then tutti_layer_restore_ordered per layer), back to back on
@@ -564,12 +580,14 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5, place=True):
     order_us = timed(order, 1)
     us_ordered = timed(lambda: train(True), L)
     us_save = timed(save_train, L)
+    host_us = host_us_per_call(torch, train, L, reps=3)
     assert int(status.item()) == 0 and int(tot[1].item()) == n_sqe
     res = {"layers_resident": L, "layers_model": s.num_layers, "pool_blocks": s.num_blocks, "requests": w.n_req,
            "blocks_per_layer": n_tab, "payload_bytes_per_layer": payload, "entries_per_layer": n_sqe,
            "us_per_layer": round(us, 2), "payload_GBps": round(payload / (us * 1e-6) / 1e9, 1),
            "traffic_GBps": round(2 * payload / (us * 1e-6) / 1e9, 1),
            "pct_hbm_peak": round(100 * 2 * payload / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+           "host_us_per_call": host_us,
            "placement": {k: v for k, v in placement_info.items() if k != "rounds"},
            "restore_K_and_V_in_one_region": None if us_same is None else {
                "layers": len(pools_same), "us_per_layer": round(us_same, 2),
