@@ -410,7 +410,7 @@ def test_ring_layer_calls_can_be_captured_in_a_graph(orc, H):
 import os as _os
 
 
-@pytest.mark.parametrize("seed", range(int(_os.environ.get("TUTTI_FUZZ_SEEDS", "48"))))
+@pytest.mark.parametrize("seed", range(int(_os.environ.get("TUTTI_FUZZ_SEEDS", "160"))))
 def test_random_shapes(orc, H, request, seed):
     """Seeded random geometry, request mix, layout, stride, alignment, chunking and launch shape."""
     rng = np.random.default_rng(9000 + seed)
