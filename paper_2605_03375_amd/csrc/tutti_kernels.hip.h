@@ -215,7 +215,7 @@ __device__ __forceinline__ bool lds_from_extents(const tutti_extent *__restrict_
   // fully unrolled so that a thread's loads are all in flight together; a request's successor sits in the next
   // lane, and for the last lane of a wavefront in LDS once the barrier has been crossed.  Every workgroup of an
   // entry builder runs this over all requests, so its instruction count matters when there are thousands of
-  // both: the host then launches few, large workgroups (entry_wg_threads).
+  // both: the host then launches few, large workgroups (entry_launch in the host code).
   constexpr uint32_t kPer = TUTTI_MAX_REQ / WG;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   bool bad = false;
