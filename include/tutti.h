@@ -376,6 +376,30 @@ int tutti_store_layer_issue(const tutti_ring *ring, uint32_t first_slot, uint32_
                             void *stream);
 int tutti_complete_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, void *stream);
 
+/* A train of layers on ONE stream without a completion kernel between them (sec. 3.4 "Layer-wise Overlapping": the
+ * layers of a request are retrieved one after the other): as the _issue calls, and the same launch also completes
+ * the IOCBs [done_first_slot, done_first_slot + done_n_slots) that an EARLIER call on the same stream executed
+ * (typically the layer before), exactly as tutti_complete_io would: one more workgroup, in front of the grid, does it
+ * and leaves.  Stream order has made the earlier launch's stores visible before this launch starts, so the
+ * completion is published as early as a completion kernel's would be, and the train pays for no kernel boundary
+ * between a layer's data and the next layer's.  The last layer of a train is completed with tutti_complete_io.
+ * done_n_slots = 0: nothing to complete (the first layer of a train).  The two slot ranges must not overlap
+ * (TUTTI_EINVAL); a later completion of the same ring must still be ordered after this launch (they share the CQ
+ * tail).  Under a cu_budget the launch has cu_budget + 1 workgroups for as long as the completing one lives (a few
+ * microseconds). */
+int tutti_retrieve_layer_chained(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t done_first_slot,
+                                 uint32_t done_n_slots, const tutti_pool *pool, const tutti_objcfg *cfg,
+                                 const uint32_t *d_n_blocks, uint32_t n_req, const uint32_t *d_block_table,
+                                 uint32_t table_len, const uint32_t *d_file_id, uint32_t layer, uint64_t sgl_table_addr,
+                                 uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
+                                 uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream);
+int tutti_store_layer_chained(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t done_first_slot,
+                              uint32_t done_n_slots, const tutti_pool *pool, const tutti_objcfg *cfg,
+                              const uint32_t *d_n_blocks, uint32_t n_req, const uint32_t *d_block_table,
+                              uint32_t table_len, const uint32_t *d_file_id, uint32_t layer, uint64_t sgl_table_addr,
+                              uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
+                              uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream);
+
 /* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);

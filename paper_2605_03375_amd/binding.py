@@ -55,7 +55,8 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_table_validate_static", "tutti_layer_restore_ordered", "tutti_table_order",
            "tutti_table_order_work_bytes", "tutti_retrieve_layer_issue", "tutti_store_layer_issue",
            "tutti_complete_io", "tutti_wait_cqe_range", "tutti_place_work_bytes", "tutti_place_pair_times",
-           "tutti_place_classify", "tutti_place_pairs"]
+           "tutti_place_classify", "tutti_place_pairs", "tutti_retrieve_layer_chained",
+           "tutti_store_layer_chained"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
                  "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
 SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
@@ -165,6 +166,8 @@ def _declare(L, bench):
     L.tutti_retrieve_layer_issue.argtypes = L.tutti_retrieve_layer.argtypes
     L.tutti_store_layer_issue.argtypes = L.tutti_retrieve_layer.argtypes
     L.tutti_complete_io.argtypes = [pr, u32, u32, vp]
+    L.tutti_retrieve_layer_chained.argtypes = [pr, u32, u32, u32, u32] + L.tutti_retrieve_layer.argtypes[3:]
+    L.tutti_store_layer_chained.argtypes = L.tutti_retrieve_layer_chained.argtypes
     L.tutti_sgl_table_build.argtypes = [pp, u64, u64, u32, vp, u32, vp, vp]
     L.tutti_sqe_build_direct.argtypes = [pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, u32, vp, vp]
     L.tutti_strerror.argtypes = [C.c_int]
@@ -396,6 +399,21 @@ def _ring_layer_call(name):
     return call
 
 
+def _ring_layer_chained_call(name):
+    def call(ring, first_slot, n_slots, done_first_slot, done_n_slots, pool, cfg, d_n_blocks, n_req, d_block_table,
+             table_len, d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget=0,
+             d_status=None, stream=None):
+        return _check(name, getattr(lib(), name)(C.byref(ring), first_slot, n_slots, done_first_slot, done_n_slots,
+                                                 C.byref(pool), C.byref(cfg), _p(d_n_blocks), n_req,
+                                                 _p(d_block_table), table_len, _p(d_file_id), layer, sgl_table_addr,
+                                                 sgl_id, C.byref(store), _p(d_extents), _p(d_totals), cu_budget,
+                                                 _p(d_status), _stream(stream)))
+    call.__name__ = name
+    return call
+
+
+tutti_retrieve_layer_chained = _ring_layer_chained_call("tutti_retrieve_layer_chained")
+tutti_store_layer_chained = _ring_layer_chained_call("tutti_store_layer_chained")
 tutti_retrieve_layer_issue = _ring_layer_call("tutti_retrieve_layer_issue")
 tutti_store_layer_issue = _ring_layer_call("tutti_store_layer_issue")
 

@@ -219,6 +219,14 @@ int plan_launch(uint32_t cu_budget, uint64_t n_wave_items, Launch *out) {
   return TUTTI_OK;
 }
 
+// Workgroups of a whole-GPU launch that fills every place (what plan_launch caps its grid at).
+uint32_t whole_gpu_wgs() {
+  const int cus = cu_count();
+  uint32_t per_cu = tuning().wgs_per_cu;
+  if (per_cu == 0) per_cu = kDefaultWgsPerCu;
+  return cus > 0 ? static_cast<uint32_t>(cus) * per_cu : 0u;
+}
+
 // Fills the kernel arguments and settles how a head-major pool is moved (L->hnd_lds, L->unroll,
 // L->tile_lds).  L must already hold the workgroup size and default unroll from plan_launch.
 int fill_move_args(const tutti_pool *pool, uint32_t block_bytes, const uint32_t *d_block_table, uint32_t table_len,
@@ -795,9 +803,18 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
                      const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
                      const uint32_t *d_block_table, uint32_t table_len, const uint32_t *d_file_id, uint32_t layer,
                      uint64_t sgl_table_addr, uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
-                     uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream, bool complete = true) {
+                     uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream, bool complete = true,
+                     uint32_t done_first = 0, uint32_t done_n = 0) {
   int rc = check_ring(ring, first_slot, n_slots);
   if (rc) return rc;
+  if (done_n > 0) {
+    rc = check_ring(ring, done_first, done_n);
+    if (rc) return rc;
+    // the IOCBs to complete are an earlier call's: none of them may be one this call fills
+    const uint32_t ahead = (done_first + ring->depth - first_slot) % ring->depth;   // done_first seen from first_slot
+    const uint32_t behind = (first_slot + ring->depth - done_first) % ring->depth;  // and the other way round
+    if (n_slots > 0 && (ahead < n_slots || behind < done_n)) return TUTTI_EINVAL;
+  }
   uint32_t bb = 0;
   rc = check_geometry(pool, cfg, &bb);
   if (rc) return rc;
@@ -828,6 +845,10 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
   rc = plan_launch(cu_budget, move_wave_items(L, m), &G);
   if (rc) return rc;
   L.grid = G.grid;
+  // a chained launch has one more workgroup in front (it completes the earlier call's IOCBs and leaves); a
+  // whole-GPU grid gives it one of its places, so that every workgroup is still resident from the start
+  const uint32_t lead = done_n > 0 ? 1u : 0u;
+  if (lead && cu_budget == 0 && L.grid > 1 && L.grid == whole_gpu_wgs()) L.grid -= 1;
   // contexts to record: no more than the IOCBs hold, no more than two per table position
   uint64_t n_ctx = static_cast<uint64_t>(n_slots) * TUTTI_IOCB_SLOTS;
   if (n_ctx > 2ull * table_len) n_ctx = 2ull * table_len;
@@ -836,6 +857,7 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
                              (DIR == kUnpack) ? TUTTI_OP_READ : TUTTI_OP_WRITE, sgl_id);
   const DirectArgs d = direct_args(d_block_table, sgl_table_addr, table_len, pool->num_blocks, bb);
   RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
+  RingArgs gd{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, done_first, done_n};
   FileArgs f{store->file_stride, store->first_file_id, store->n_files};
   const LayoutArgs a = layout_args(d_n_blocks, d_extents, d_totals, bb, cfg, n_req);
 
@@ -847,7 +869,8 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
   R.nontemporal = 3;  // the ring kernels have one cache policy
   hipError_t e = with_shape(R, [&](auto sh) {
     using S = decltype(sh);
-    hipLaunchKernelGGL((k_layer_ring<DIR, S::U, S::WG>), dim3(n_wgs), dim3(S::WG), lds, s, m, q, d, g, f, a, w);
+    hipLaunchKernelGGL((k_layer_ring<DIR, S::U, S::WG>), dim3(n_wgs + lead), dim3(S::WG), lds, s, m, q, d, g, gd, f, a,
+                       w);
     return hipGetLastError();
   });
   if (e != hipSuccess) return hip_fail(e);
@@ -879,6 +902,28 @@ int tutti_store_layer_issue(const tutti_ring *ring, uint32_t first_slot, uint32_
   return ring_layer_entry<kPack>(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len,
                                  d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget,
                                  d_status, stream, false);
+}
+
+int tutti_retrieve_layer_chained(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t done_first_slot,
+                                 uint32_t done_n_slots, const tutti_pool *pool, const tutti_objcfg *cfg,
+                                 const uint32_t *d_n_blocks, uint32_t n_req, const uint32_t *d_block_table,
+                                 uint32_t table_len, const uint32_t *d_file_id, uint32_t layer, uint64_t sgl_table_addr,
+                                 uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
+                                 uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  return ring_layer_entry<kUnpack>(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len,
+                                   d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget,
+                                   d_status, stream, false, done_first_slot, done_n_slots);
+}
+
+int tutti_store_layer_chained(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t done_first_slot,
+                              uint32_t done_n_slots, const tutti_pool *pool, const tutti_objcfg *cfg,
+                              const uint32_t *d_n_blocks, uint32_t n_req, const uint32_t *d_block_table,
+                              uint32_t table_len, const uint32_t *d_file_id, uint32_t layer, uint64_t sgl_table_addr,
+                              uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
+                              uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  return ring_layer_entry<kPack>(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len,
+                                 d_file_id, layer, sgl_table_addr, sgl_id, store, d_extents, d_totals, cu_budget,
+                                 d_status, stream, false, done_first_slot, done_n_slots);
 }
 
 int tutti_complete_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, void *stream) {

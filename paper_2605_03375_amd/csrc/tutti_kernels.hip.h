@@ -1455,20 +1455,29 @@ __device__ __forceinline__ Preload<U> preload_first_direct(const MoveArgs &m, co
 // workgroups record the layer's contexts in the IOCBs while the copy workgroups move the very same blocks,
 // each item deriving its file offset and block from the extents and the table exactly as its context does.
 // Blocks go to the file as they sit in the pool (a descriptor names raw bytes), so there is no head-major case.
-// The host enqueues k_complete behind this kernel.
+// The completion of these IOCBs is a kernel boundary away: the host enqueues k_complete behind this kernel, or the
+// next layer's launch carries it along (`done`: the IOCBs an earlier launch on the same stream has executed; when
+// done.n_slots is not 0 the grid has one workgroup more, in front, whose first wavefront completes them and leaves,
+// so a train of layers pays for no kernel boundary between a layer's data and the next layer's).
 template <int DIR, int U, int WG>
 __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(const MoveArgs m, const SqeArgs q, const DirectArgs d,
-                                                    const RingArgs g, const FileArgs f, const LayoutArgs a,
-                                                    const Roles w) {
+                                                    const RingArgs g, const RingArgs done, const FileArgs f,
+                                                    const LayoutArgs a, const Roles w) {
   extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t lead = done.n_slots != 0 ? 1u : 0u;
+  if (lead && blockIdx.x == 0) {  // the whole workgroup takes this branch: no barrier is left waiting
+    if (threadIdx.x < kWave) complete_iocbs(done, threadIdx.x);
+    return;
+  }
+  const uint32_t bx = blockIdx.x - lead;
   const ReqLds l = carve_lds(smem, a.n_req);
-  const bool copies = blockIdx.x - w.copy_first < w.copy_wgs;
+  const bool copies = bx - w.copy_first < w.copy_wgs;
   Preload<U> pre;
   pre.valid = false;
   if (DIR == kUnpack && copies && a.n_req == 1)
-    pre = preload_first_direct<U>(m, a.n_blocks, q.file_id, f, blockIdx.x - w.copy_first, w.copy_wgs);
+    pre = preload_first_direct<U>(m, a.n_blocks, q.file_id, f, bx - w.copy_first, w.copy_wgs);
   if (threadIdx.x < kWave) {
-    const bool publish = blockIdx.x == 0;
+    const bool publish = bx == 0;
     // chunk counts only matter for the published extents; the LDS copy gets file starts instead of staging offsets
     wave_scan_extents(a.geom, a.n_blocks, a.n_req, threadIdx.x, l, publish ? a.extents : nullptr,
                       publish ? a.totals : nullptr, 0xffffffffu, nullptr, publish, q.file_id, f);
@@ -1476,9 +1485,9 @@ __global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_layer_ring(co
   __syncthreads();
   DirectHead head;
   head.live = false;
-  if (blockIdx.x < w.sqe_wgs) head = iocb_head(g, q, d, l, a.n_req, 0, w.sqe_wgs);
-  if (copies) move_items<DIR, false, U, 3, false>(m, l, a.n_req, blockIdx.x - w.copy_first, w.copy_wgs, pre);
-  if (blockIdx.x < w.sqe_wgs) emit_iocbs(g, q, d, l, a.n_req, 0, w.sqe_wgs, head);
+  if (bx < w.sqe_wgs) head = iocb_head(g, q, d, l, a.n_req, lead, w.sqe_wgs);
+  if (copies) move_items<DIR, false, U, 3, false>(m, l, a.n_req, bx - w.copy_first, w.copy_wgs, pre);
+  if (bx < w.sqe_wgs) emit_iocbs(g, q, d, l, a.n_req, lead, w.sqe_wgs, head);
 }
 
 template <int DIR, int PT, int WG>

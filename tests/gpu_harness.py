@@ -460,3 +460,69 @@ def check_ring_layer(orc, c, layer, write, depth, first_slot, n_slots, cu_budget
     if write:
         assert np.array_equal(gk, c.k_host) and np.array_equal(gv, c.v_host)
     return o_st
+
+def check_ring_layer_train(orc, c, layers, write, depth, n_slots, first_slot=0, cu_budget=0, first_file_id=1000,
+                           seed=5):
+    """A train of layers through the chained calls (each launch also completes the IOCBs of the call before it, the
+    last layer is completed by tutti_complete_io), against the oracle's sequence of one-call retrieve_layer /
+    store_layer: every output compared once the train is through.  Before the last completion the last call's IOCBs
+    must not read as DONE and every earlier call's must.  Consecutive calls take consecutive slot ranges (modulo
+    depth), so depth >= 2 * n_slots keeps a call's range apart from the one it completes."""
+    assert c.bb % c.align == 0 and depth >= 2 * n_slots and n_slots > 0
+    o_ext0, _ = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    file_stride = max(16, int(2 * c.L * (int(o_ext0["obj_bytes"].max()) if c.n_req else 0)))
+    n_files = max(1, c.n_req)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    store = torch.randint(0, 256, (n_files * file_stride,), dtype=torch.uint8, device=DEV, generator=g)
+    o_store = store.cpu().numpy().copy()
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    table_addr = 0x7f00_0000_1000
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=DEV)
+    ring = B.make_ring(sq, cq, depth)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    B.tutti_ring_init(ring)
+    orc.ring_init(o_sq, o_cq)
+    fs = B.make_filestore(store, file_stride, first_file_id, n_files)
+    ext = torch.zeros(max(1, c.n_req) * 32, dtype=torch.uint8, device=DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=DEV)
+    fn = B.tutti_store_layer_chained if write else B.tutti_retrieve_layer_chained
+    o_fn = orc.store_layer if write else orc.retrieve_layer
+    st = new_status()
+    o_st_all = 0
+    prev = (0, 0)
+    slots = []
+    for i, lay in enumerate(layers):
+        fslot = (first_slot + i * n_slots) % depth
+        fn(ring, fslot, n_slots, prev[0], prev[1], c.gpu_pool(k2, v2), c.gpu_cfg(), c.d_n_blocks, c.n_req, c.d_table,
+           c.table.size, c.d_file_id, lay, table_addr, 5, fs, ext, tot, cu_budget, st)      # no synchronisation
+        o_ext, o_tot, o_st = o_fn(o_sq, o_cq, fslot, n_slots, c.orc_pool(orc, ok, ov), c.orc_cfg(orc), c.n_blocks,
+                                  c.table, c.file_id, lay, table_addr, 5, o_store, file_stride, first_file_id, n_files)
+        o_st_all |= o_st
+        prev = (fslot, n_slots)
+        slots.append(fslot)
+    # the train is through but for its last completion
+    flags = torch.full((depth,), 9, dtype=torch.int32, device=DEV)
+    B.tutti_wait_cqe_range(ring, 0, depth, flags)
+    torch.cuda.synchronize()
+    got = flags.cpu().tolist()
+    last = {(prev[0] + k) % depth for k in range(n_slots)}
+    done = o_sq["hdr"]["state"] == orc.IOCB_DONE
+    assert got == [0 if s in last else (1 if done[s] else 0) for s in range(depth)], f"{c.name}: {got}"
+    tail_before = int(cq[:8].cpu().numpy().view(np.uint32)[0])
+    B.tutti_complete_io(ring, prev[0], prev[1])
+    torch.cuda.synchronize()
+    assert int(st.item()) == o_st_all, f"{c.name}: status {int(st.item())} vs oracle {o_st_all}"
+    assert ext.cpu().numpy()[: 32 * c.n_req].tobytes() == o_ext.tobytes(), f"{c.name}: extents differ"
+    assert np.array_equal(tot.cpu().numpy().view(np.uint64), o_tot), f"{c.name}: totals differ"
+    gk, gv = k2.cpu().numpy(), v2.cpu().numpy()
+    assert np.array_equal(gk, ok), f"{c.name}: K plane differs at byte {first_diff(gk, ok)}"
+    assert np.array_equal(gv, ov), f"{c.name}: V plane differs at byte {first_diff(gv, ov)}"
+    gs = store.cpu().numpy()
+    assert np.array_equal(gs, o_store), f"{c.name}: file store differs at byte {first_diff(gs, o_store)}"
+    assert sq.cpu().numpy().tobytes() == o_sq.tobytes(), f"{c.name}: IOCBs differ"
+    assert cq.cpu().numpy().tobytes() == o_cq.tobytes(), f"{c.name}: completion queue differs"
+    return o_st_all, tail_before

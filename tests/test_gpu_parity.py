@@ -847,6 +847,58 @@ def test_ring_layer_calls_in_two_halves_with_completions_on_a_second_stream(orc,
                 assert np.array_equal(plane[bid * c.stride: bid * c.stride + bb], file_h[lo + j * bb: lo + (j + 1) * bb])
 
 
+def test_ring_layer_trains_with_chained_completions(orc, H):
+    """tutti_retrieve_layer_chained / tutti_store_layer_chained: every launch of a train also completes the IOCBs of
+    the launch before it, one tutti_complete_io ends the train.  IOCBs, CQ order, blocks, files, extents and status
+    must be what the oracle's one-call sequence gives, with slot ranges that wrap around the ring and are reused,
+    under a budget, with too few IOCBs, and at config 2's size; overlapping slot ranges are refused."""
+    say("rings: trains of layers with chained completions")
+    rng = np.random.default_rng(78)
+    nb = [700, 0, 1500, 3]
+    N = 2500
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=N, n_blocks=nb, table=rng.permutation(N)[: sum(nb)], chunk=4096, L=5,
+                    name="ring_chained")
+    n_slots = (2 * sum(nb) + B.IOCB_SLOTS - 1) // B.IOCB_SLOTS          # 3
+    for write in (False, True):
+        st, tail = H.check_ring_layer_train(orc, c, [0, 1, 2, 3, 4], write, depth=5 * n_slots, n_slots=n_slots)
+        assert st == 0 and tail == 4 * n_slots                          # four layers completed by their successors
+        # the ring wraps and every slot is used again; the train starts in the middle of the ring
+        H.check_ring_layer_train(orc, c, [4, 0, 3, 1, 2, 2], write, depth=2 * n_slots + 1, n_slots=n_slots, first_slot=4)
+        H.check_ring_layer_train(orc, c, [1, 2, 3], write, depth=2 * n_slots, n_slots=n_slots, cu_budget=3)
+        H.check_ring_layer_train(orc, c, [2], write, depth=2 * n_slots, n_slots=n_slots)   # a train of one layer
+        st, _ = H.check_ring_layer_train(orc, c, [0, 1, 2], write, depth=4, n_slots=2)     # too few IOCBs per layer
+        assert st == B.ST_SQE_CAP
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=16, n_blocks=[4, 2], table=[3, 999, 5, 16, 7, 1], chunk=4096, L=2,
+                    name="ring_chained_bad")
+    for write in (False, True):
+        st, _ = H.check_ring_layer_train(orc, c, [0, 1], write, depth=2, n_slots=1)
+        assert st == B.ST_BAD_BLOCK
+    w = W.llama8b_32k(num_blocks=8192)
+    c = H.LayerCase.from_workload(w)
+    c.chunk = c.bb
+    for write in (False, True):
+        st, tail = H.check_ring_layer_train(orc, c, [30, 31, 0], write, depth=6, n_slots=2, first_slot=3)
+        assert st == 0 and tail == 4
+    # slot ranges that overlap are refused before anything is enqueued
+    sq_bytes, cq_bytes = B.ring_bytes(8)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=H.DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=H.DEV)
+    ring = B.make_ring(sq, cq, 8)
+    store = torch.zeros(1 << 20, dtype=torch.uint8, device=H.DEV)
+    fs = B.make_filestore(store, 1 << 20, int(c.file_id[0]), 1)
+    ext = torch.zeros(32, dtype=torch.uint8, device=H.DEV)
+    tot = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    for first, n, dfirst, dn in ((0, 2, 1, 2), (2, 2, 1, 2), (7, 2, 0, 1), (0, 2, 7, 2), (3, 1, 3, 1), (0, 8, 4, 1)):
+        for fn in (B.tutti_retrieve_layer_chained, B.tutti_store_layer_chained):
+            with pytest.raises(B.TuttiError) as err:
+                fn(ring, first, n, dfirst, dn, c.gpu_pool(c.k_dev, c.v_dev), c.gpu_cfg(), c.d_n_blocks, 1, c.d_table,
+                   c.table.size, c.d_file_id, 0, 0x1000, 5, fs, ext, tot)
+            assert err.value.code == B.EINVAL
+    with pytest.raises(B.TuttiError):                                   # done range outside the ring
+        B.tutti_retrieve_layer_chained(ring, 0, 1, 8, 1, c.gpu_pool(c.k_dev, c.v_dev), c.gpu_cfg(), c.d_n_blocks, 1,
+                                       c.d_table, c.table.size, c.d_file_id, 0, 0x1000, 5, fs, ext, tot)
+
+
 # ------------------------------------------------------------------ edge cases
 
 def test_no_requests_and_empty_requests(orc, H):
