@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--no-placement", action="store_true",
                     help="take the pool's planes as the allocator hands them out instead of putting every layer's K "
                          "and V plane in different HBM regions")
+    ap.add_argument("--region-matrix", action="store_true",
+                    help="instead of the benchmark: restore and save of config 2's layer for every combination of HBM "
+                         "region of the K plane, the V plane and the staging buffer; prints its own JSON line")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--plain-loads", action="store_true", help="disable non-temporal loads/stores")
@@ -103,6 +106,10 @@ def main():
         B.tutti_set_tuning(args.wgs_per_cu, args.unroll)
         B.tutti_set_nontemporal(0 if args.plain_loads else 3)
 
+    if args.region_matrix:
+        print(json.dumps(region_matrix(torch, B, W.llama8b_32k(), dev)), flush=True)
+        return
+
     w = W.llama8b_32k()
     s = w.shape
     bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
@@ -124,8 +131,9 @@ def main():
     cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
     t0 = time.time()
     # where the planes sit: every layer's K plane and V plane in different regions of the HBM (set-up, untimed)
-    planes, planes_same, placement_info = placed_planes(torch, L, plane_bytes, dev, reserve_bytes=(L * payload_layer) + (12 << 30),
-                                                        place=not args.no_placement)
+    planes, planes_same, placement_info, placed_stages = placed_planes(
+        torch, L, plane_bytes, dev, reserve_bytes=(L * payload_layer) + (12 << 30), place=not args.no_placement,
+        stage_bytes=payload_layer)
     log(f"[bench] placement ({time.time() - t0:.1f} s): {placement_info}")
     td = {"fp16": torch.float16, "bf16": torch.bfloat16}[s.dtype]
     for l in range(L):
@@ -136,7 +144,12 @@ def main():
             log(f"[bench] filled {l + 1}/{L} layers ({time.time() - t0:.1f} s)")
     pools = [B.make_pool(k, v, **geom) for k, v in planes]
     pools_same = [B.make_pool(k, v, **geom) for k, v in planes_same]
-    stages = [torch.zeros(payload_layer, dtype=torch.uint8, device=dev) for _ in range(L)]
+    if placed_stages is not None:
+        stages = placed_stages[:L]
+        for st in stages:
+            st.zero_()
+    else:
+        stages = [torch.zeros(payload_layer, dtype=torch.uint8, device=dev) for _ in range(L)]
     d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
     d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
     d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
@@ -402,12 +415,14 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True):
+def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True, stage_bytes=0):
     """K and V planes for n_layers layers.  place: candidates covering about 200 GiB are allocated, told apart by
     HBM region with paper_2605_03375_amd.placement (a timing probe with the real restore call), every layer gets a K
     plane and a V plane from different regions, and the candidates not needed are freed.  Also returns the same
     planes paired within a region (what an allocator that knows nothing of the regions usually produces: the layout
-    to compare against) and a description.  Contents are left as allocated."""
+    to compare against), a description, and, when stage_bytes is given and spare candidates allow it, one staging
+    buffer per layer cut from a spare candidate of the region that holds neither of the layer's planes (else None:
+    the caller allocates them wherever the allocator puts them).  Contents are left as allocated."""
     from paper_2605_03375_amd import placement
     free, _ = torch.cuda.mem_get_info()
     fit = int((free - reserve_bytes) // plane_bytes)
@@ -415,7 +430,7 @@ def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True):
         n = min(n_layers, fit // 2)
         cands = [torch.empty(plane_bytes, dtype=torch.uint8, device=dev) for _ in range(2 * n)]
         planes = [(cands[2 * l], cands[2 * l + 1]) for l in range(n)]
-        return planes, [], {"placed": False, "why": "switched off" if not place else "no room for spare candidates"}
+        return planes, [], {"placed": False, "why": "switched off" if not place else "no room for spare candidates"}, None
     n_cand = min(fit, max(3 * n_layers, int((200 << 30) // plane_bytes)))
     cands = []
     try:
@@ -436,9 +451,110 @@ def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True):
     planes_same = [(cands[used[i]], cands[used[j]]) for i, j in same]
     info["layers_with_K_and_V_in_different_regions"] = sum(1 for i, j in pairs if classes[i] != classes[j] and
                                                             classes[i] >= 0 and classes[j] >= 0)
+    stages = None
+    if stage_bytes and plane_bytes >= stage_bytes:
+        # spare candidates cut into staging buffers, by region; a layer takes one from the region of neither plane
+        spare = {}
+        taken = set(used)
+        for i, c in enumerate(classes):
+            if i not in taken and c >= 0:
+                spare.setdefault(c, []).append(i)
+        per_cand = plane_bytes // stage_bytes
+        cut = {c: [] for c in spare}                     # views not handed out yet
+        nxt = {c: 0 for c in spare}                      # spare candidates of the class not yet cut
+        def take(c):
+            if not cut[c] and nxt[c] < len(spare[c]):
+                t = cands[spare[c][nxt[c]]]
+                nxt[c] += 1
+                cut[c] = [t[k * stage_bytes:(k + 1) * stage_bytes] for k in range(per_cand)]
+            return cut[c].pop(0) if cut[c] else None
+        stages, third = [], 0
+        for i, j in pairs:
+            want = [c for c in sorted(spare) if c not in (classes[i], classes[j])]
+            st = None
+            for c in want:
+                st = take(c)
+                if st is not None:
+                    third += 1
+                    break
+            if st is None:
+                st = torch.empty(stage_bytes, dtype=torch.uint8, device=dev)
+            stages.append(st)
+        info["staging_buffers_in_a_third_region"] = third
     del cands
     torch.cuda.empty_cache()
-    return planes, planes_same, info
+    return planes, planes_same, info, stages
+
+
+def region_matrix(torch, B, w, dev, layers=16, reps=6):
+    """Config 2's fused restore and save, microseconds per layer, for every combination of the HBM region of the K
+    plane, the V plane and the staging buffer that the candidates of this process allow (about 220 GiB of 2 GiB
+    candidates, classified by tutti_place_classify; `layers` layers rotate so that every launch is cold; staging
+    buffers are 128 MiB pieces of two spare candidates of the wanted region)."""
+    from paper_2605_03375_amd import placement
+    s = w.shape
+    bb = s.block_tokens * s.num_kv_heads * s.head_dim * s.elt_bytes
+    plane = s.num_blocks * bb
+    n_tab = int(w.block_table.size)
+    payload = 2 * n_tab * bb
+    n_sqe = 2 * ((n_tab * bb + w.chunk_bytes - 1) // w.chunk_bytes)
+    free, _ = torch.cuda.mem_get_info()
+    n_cand = int(min(112, (free - (12 << 30)) // plane))
+    cands = [torch.empty(plane, dtype=torch.uint8, device=dev) for _ in range(n_cand)]
+    classes, report = placement.classify_planes(cands, dev)
+    by = {c: [i for i in range(n_cand) if classes[i] == c] for c in range(3)}
+    L = layers
+    geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
+                head_dim=s.head_dim, elt_bytes=s.elt_bytes)
+    cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
+    d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
+    d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
+    d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
+    ext = torch.zeros(L, 32, dtype=torch.uint8, device=dev)
+    tot = torch.zeros(L, 2, dtype=torch.int64, device=dev)
+    sqe = torch.zeros(L, n_sqe * 64, dtype=torch.uint8, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def us_per_layer(pools, stages, fn):
+        def train():
+            for l in range(L):
+                fn(pools[l], cfg, d_n, 1, d_tab, n_tab, d_fid, l, stages[l], payload, stages[l].data_ptr(), 1, ext[l],
+                   tot[l], sqe[l], n_sqe, 0, status)
+        train()
+        train()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            train()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / L)
+        return round(median(ts), 2)
+
+    rows = []
+    for ka, kb in ((0, 1), (1, 0), (0, 2), (1, 2), (0, 0), (1, 1), (2, 2)):
+        # planes from the front of a class, staging pieces from its last two candidates
+        need_a = 2 * L + 2 if ka == kb else L + 2
+        if len(by[ka]) < need_a or len(by[kb]) < L + 2:
+            continue
+        ia = by[ka][:2 * L]
+        ib = by[kb][:2 * L]
+        pools = [B.make_pool(cands[ia[2 * l if ka == kb else l]], cands[ib[2 * l + 1 if ka == kb else l]], **geom)
+                 for l in range(L)]
+        for kc in range(3):
+            if len(by[kc]) < 2:
+                continue
+            stages = [cands[c][k * payload:(k + 1) * payload] for c in by[kc][-2:] for k in range(plane // payload)][:L]
+            rows.append({"K": "ABC"[ka], "V": "ABC"[kb], "staging": "ABC"[kc],
+                         "restore_us": us_per_layer(pools, stages, B.tutti_layer_restore),
+                         "save_us": us_per_layer(pools, stages, B.tutti_layer_save)})
+            log(f"[bench] region matrix: {rows[-1]}")
+    assert int(status.item()) == 0
+    return {"workload": "config 2 layer (2048 blocks of 32 KiB, 128 MiB of payload), fused restore / save, us per layer",
+            "regions_in_allocation_order": "".join("ABC?"[c] for c in classes), "rounds": report["rounds"],
+            "layers_rotating": L, "rows": rows}
 
 
 def host_us_per_call(torch, fn, n_calls, reps=7):
@@ -519,8 +635,8 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5, place=True):
     geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
                 head_dim=s.head_dim, elt_bytes=s.elt_bytes)
     cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
-    planes, planes_same, placement_info = placed_planes(torch, L, plane_bytes, dev,
-                                                        reserve_bytes=n_stage * payload + (10 << 30), place=place)
+    planes, planes_same, placement_info, _ = placed_planes(torch, L, plane_bytes, dev,
+                                                           reserve_bytes=n_stage * payload + (10 << 30), place=place)
     L = len(planes)
     pools = [B.make_pool(k, v, **geom) for k, v in planes]
     pools_same = [B.make_pool(k, v, **geom) for k, v in planes_same]

@@ -537,9 +537,10 @@ typedef struct tutti_place_round {
  * it.  Round c takes the first unclassified plane r as reference and times (r, r) and (r, x) for every
  * unclassified x; x joins class c if its time is nearer the slow case (r, r) than the round's fastest pair.  A
  * round in which nothing beats the slow case by min_gap_us puts everything left into class c (a part with one
- * region ends there, with every plane in class 0).  A plane that straddles two regions would time in between and
- * join the nearer side (every allocation of up to 2 GiB measured so far lay inside one region; larger planes are
- * better cut into several candidates).  max_regions in 1..TUTTI_PLACE_MAX_REGIONS.  rounds (HOST,
+ * region ends there, with every plane in class 0).  A plane that straddles two regions times in between against
+ * everything: as a reference it finds no partner and is set aside (class -1, and the round is not counted, at most
+ * four times); as a candidate it joins the nearer side.  Planes much larger than the 2 GiB of the measurements are
+ * better cut into several candidates.  max_regions in 1..TUTTI_PLACE_MAX_REGIONS.  rounds (HOST,
  * max_regions records, may be NULL) and *n_rounds (may be NULL) <- what each round measured. */
 int tutti_place_classify(const void *const *planes, uint32_t n, uint64_t plane_bytes, void *d_work,
                          uint64_t work_bytes, uint32_t max_regions, double min_gap_us, int32_t *classes,

@@ -1251,6 +1251,8 @@ struct Probe {
   }
 };
 
+constexpr int32_t kSetAside = -2;  // during classification: a reference that turned out to share its region with nothing
+
 int check_plane_list(const void *const *planes, uint32_t n) {
   if (n == 0 || !planes) return TUTTI_EINVAL;
   if (n > 65536u) return TUTTI_ERANGE;
@@ -1290,10 +1292,11 @@ int tutti_place_classify(const void *const *planes, uint32_t n, uint64_t plane_b
   std::vector<uint32_t> todo;
   std::vector<const void *> cands;
   std::vector<float> us;
-  for (uint32_t c = 0; c < max_regions; ++c) {
+  uint32_t c = 0;
+  for (uint32_t attempt = 0; c < max_regions && attempt < max_regions + 4u; ++attempt) {
     todo.clear();
     for (uint32_t i = 0; i < n; ++i)
-      if (classes[i] < 0) todo.push_back(i);
+      if (classes[i] == -1) todo.push_back(i);
     if (todo.empty()) break;
     const uint32_t r = todo[0];
     cands.assign(1, planes[r]);  // (r, r): both planes in one region by construction
@@ -1310,15 +1313,23 @@ int tutti_place_classify(const void *const *planes, uint32_t n, uint64_t plane_b
     } else {
       const float mid = 0.5f * (slow + fast);
       for (size_t k = 0; k < todo.size(); ++k)
-        if (us[k + 1] > mid || todo[k] == r) {
-          classes[todo[k]] = static_cast<int32_t>(c);
-          ++members;
-        }
+        if (us[k + 1] > mid || todo[k] == r) ++members;
+      if (members == 1) {
+        // nothing shares the reference's region although other planes are left: most likely a plane that
+        // straddles two regions (every pair with it times in between).  It is set aside and gets no class.
+        classes[r] = kSetAside;
+        continue;
+      }
+      for (size_t k = 0; k < todo.size(); ++k)
+        if (us[k + 1] > mid || todo[k] == r) classes[todo[k]] = static_cast<int32_t>(c);
     }
     if (rounds) rounds[c] = tutti_place_round{r, members, slow, fast};
-    if (n_rounds) *n_rounds = c + 1;
+    ++c;
+    if (n_rounds) *n_rounds = c;
     if (members == todo.size()) break;
   }
+  for (uint32_t i = 0; i < n; ++i)
+    if (classes[i] == kSetAside) classes[i] = -1;
   return p.status_clean();
 }
 
