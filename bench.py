@@ -415,14 +415,15 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True, stage_bytes=0):
+def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True, stage_bytes=0, stage_rotation=0):
     """K and V planes for n_layers layers.  place: candidates covering about 200 GiB are allocated, told apart by
     HBM region with paper_2605_03375_amd.placement (a timing probe with the real restore call), every layer gets a K
     plane and a V plane from different regions, and the candidates not needed are freed.  Also returns the same
     planes paired within a region (what an allocator that knows nothing of the regions usually produces: the layout
     to compare against), a description, and, when stage_bytes is given and spare candidates allow it, one staging
     buffer per layer cut from a spare candidate of the region that holds neither of the layer's planes (else None:
-    the caller allocates them wherever the allocator puts them).  Contents are left as allocated."""
+    the caller allocates them wherever the allocator puts them); with stage_rotation = n, at most n buffers per region,
+    taken in turn.  Contents are left as allocated."""
     from paper_2605_03375_amd import placement
     free, _ = torch.cuda.mem_get_info()
     fit = int((free - reserve_bytes) // plane_bytes)
@@ -462,13 +463,24 @@ def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True, 
         per_cand = plane_bytes // stage_bytes
         cut = {c: [] for c in spare}                     # views not handed out yet
         nxt = {c: 0 for c in spare}                      # spare candidates of the class not yet cut
+        handed = {c: [] for c in spare}                  # views handed out (they are taken in turn once
+        turn = {c: 0 for c in spare}                     # stage_rotation of them exist)
         def take(c):
+            if stage_rotation and len(handed[c]) >= stage_rotation:
+                turn[c] += 1
+                return handed[c][turn[c] % len(handed[c])]
             if not cut[c] and nxt[c] < len(spare[c]):
                 t = cands[spare[c][nxt[c]]]
                 nxt[c] += 1
                 cut[c] = [t[k * stage_bytes:(k + 1) * stage_bytes] for k in range(per_cand)]
-            return cut[c].pop(0) if cut[c] else None
-        stages, third = [], 0
+            if not cut[c]:
+                if handed[c]:
+                    turn[c] += 1
+                    return handed[c][turn[c] % len(handed[c])]
+                return None
+            handed[c].append(cut[c].pop(0))
+            return handed[c][-1]
+        stages, third, loose = [], 0, []
         for i, j in pairs:
             want = [c for c in sorted(spare) if c not in (classes[i], classes[j])]
             st = None
@@ -478,7 +490,11 @@ def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True, 
                     third += 1
                     break
             if st is None:
-                st = torch.empty(stage_bytes, dtype=torch.uint8, device=dev)
+                if stage_rotation and len(loose) >= stage_rotation:
+                    st = loose[len(stages) % len(loose)]
+                else:
+                    st = torch.empty(stage_bytes, dtype=torch.uint8, device=dev)
+                    loose.append(st)
             stages.append(st)
         info["staging_buffers_in_a_third_region"] = third
     del cands
@@ -635,12 +651,17 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5, place=True):
     geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
                 head_dim=s.head_dim, elt_bytes=s.elt_bytes)
     cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
-    planes, planes_same, placement_info, _ = placed_planes(torch, L, plane_bytes, dev,
-                                                           reserve_bytes=n_stage * payload + (10 << 30), place=place)
+    planes, planes_same, placement_info, layer_stage = placed_planes(
+        torch, L, plane_bytes, dev, reserve_bytes=n_stage * payload + (10 << 30), place=place, stage_bytes=payload,
+        stage_rotation=3)
     L = len(planes)
     pools = [B.make_pool(k, v, **geom) for k, v in planes]
     pools_same = [B.make_pool(k, v, **geom) for k, v in planes_same]
-    stages = [torch.empty(payload, dtype=torch.uint8, device=dev) for _ in range(min(L, n_stage))]
+    if layer_stage is not None:
+        stages = layer_stage[:L]            # per layer: a buffer in the region of neither plane, three per region in turn
+    else:
+        few = [torch.empty(payload, dtype=torch.uint8, device=dev) for _ in range(min(L, n_stage))]
+        stages = [few[l % len(few)] for l in range(L)]
     d_n = torch.from_numpy(w.n_blocks.view(np.int32)).to(dev)
     d_tab = torch.from_numpy(w.block_table.view(np.int32)).to(dev)
     d_fid = torch.from_numpy(w.file_id.view(np.int32)).to(dev)
