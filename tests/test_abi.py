@@ -189,6 +189,15 @@ def test_null_and_misaligned_pointers_are_einval():
         _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0, fs, 0, FAKE)     # extents
         _expect(B.EINVAL, one_call, ring, 0, 1, p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, 0)     # totals
         _expect(B.ERANGE, one_call, ring, 0, 1, p, cfg, FAKE, B.MAX_REQ + 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, FAKE)
+    for chained in (B.tutti_retrieve_layer_chained, B.tutti_store_layer_chained):
+        ok = (p, cfg, FAKE, 1, FAKE, 1, FAKE, 0, 0, 0, fs, FAKE, FAKE)
+        _expect(B.EINVAL, chained, ring, 0, 1, 4, 1, *ok)              # the earlier call's first slot is not in the ring
+        _expect(B.EINVAL, chained, ring, 0, 1, 1, 5, *ok)              # more of its slots than the ring has
+        _expect(B.EINVAL, chained, ring, 0, 2, 1, 1, *ok)              # its slots are among the ones this call fills
+        _expect(B.EINVAL, chained, ring, 3, 2, 0, 1, *ok)              # the same, with this call's slots wrapping
+        _expect(B.EINVAL, chained, ring, 1, 1, 0, 2, *ok)              # this call's slot is among the earlier call's
+        _expect(B.EINVAL, chained, ring, 4, 1, 0, 1, *ok)              # the ordinary checks still come first
+        _expect(B.EINVAL, chained, ring, 0, 1, 2, 1, odd, *ok[1:])     # ... and after
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 4, FAKE)
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 0, 0)
     _expect(B.EINVAL, B.tutti_table_validate, 0, FAKE, 4, FAKE)
