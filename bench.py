@@ -19,6 +19,7 @@ config 5 (CU budgets and a CU-masked I/O domain beside two GEMMs) with the slack
 path, and a sweep of the prefix length from 1K to 128K tokens (eager launches and a HIP-graph replay).
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -409,6 +410,13 @@ def main():
             "config4_llama70b_128k": restore_leg(torch, B, W.llama70b_128k(), dev, max_layers=80,
                                                  place=not args.no_placement),
         }
+        # what one rank of a tensor-parallel group of 8 runs on config 4: one KV head of every block, so 4 KiB blocks
+        # (the paper keeps one instance of the store beside every GPU process: sec. 3.4 "Support for Multi-GPUs")
+        w4 = W.llama70b_128k()
+        w_tp = dataclasses.replace(w4, name="llama70b_128k_tp8_rank",
+                                   shape=dataclasses.replace(w4.shape, num_kv_heads=w4.shape.num_kv_heads // 8))
+        out["other_configs"]["config4_one_rank_of_tp8"] = restore_leg(torch, B, w_tp, dev, max_layers=80,
+                                                                      place=not args.no_placement)
     if cpu2 is not None:
         out["cpu_baseline"] = cpu2
         out["cpu_baseline"]["other_configs"] = cpu_baseline_others(W)
@@ -573,6 +581,36 @@ def region_matrix(torch, B, w, dev, layers=16, reps=6):
             "layers_rotating": L, "rows": rows}
 
 
+def carved_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place, stage_bytes):
+    """placed_planes for planes much smaller than the pieces the driver hands memory out in: 2 GiB buffers are placed
+    (K buffer and V buffer of a group in different regions, the group's staging buffer in the third) and every group
+    of layers cuts its planes and staging buffers out of them."""
+    big = 2 << 30
+    plane_al = (plane_bytes + 4095) // 4096 * 4096
+    stage_al = (stage_bytes + 4095) // 4096 * 4096
+    per = max(1, min(big // plane_al, big // stage_al))
+    groups = (n_layers + per - 1) // per
+    bplanes, bsame, info, bstages = placed_planes(torch, groups, big, dev, reserve_bytes, place=place,
+                                                  stage_bytes=per * stage_al, stage_rotation=3)
+    def cut(buf, k, step, size):
+        return buf[k * step: k * step + size]
+    planes, stages = [], []
+    for l in range(min(n_layers, len(bplanes) * per)):
+        g, k = divmod(l, per)
+        planes.append((cut(bplanes[g][0], k, plane_al, plane_bytes), cut(bplanes[g][1], k, plane_al, plane_bytes)))
+        if bstages is not None:
+            stages.append(cut(bstages[g], k, stage_al, stage_bytes))
+    same = []
+    for g, (a, b) in enumerate(bsame):
+        for k in range(per):
+            same.append((cut(a, k, plane_al, plane_bytes), cut(b, k, plane_al, plane_bytes)))
+    info = dict(info, planes_cut_from_buffers_of_GiB=2, layers_per_buffer_pair=per)
+    for key in ("layers_with_K_and_V_in_different_regions", "staging_buffers_in_a_third_region"):
+        if key in info:                                     # counted in buffer pairs so far
+            info[key] = min(len(planes), info[key] * per)
+    return planes, same[:len(planes)], info, (stages if bstages is not None else None)
+
+
 def host_us_per_call(torch, fn, n_calls, reps=7):
     """Host microseconds one call costs: wall time of the enqueueing loop alone, started on an idle stream and not
     waiting for the device (through the Python binding, so ctypes marshalling is in it).  The paper's point is that
@@ -645,15 +683,20 @@ def restore_leg(torch, B, w, dev, max_layers, reps=5, place=True):
     n_tab = int(w.block_table.size)
     payload = 2 * n_tab * bb
     n_sqe = int(2 * np.sum((w.n_blocks.astype(np.int64) * bb + w.chunk_bytes - 1) // w.chunk_bytes))
+    torch.cuda.empty_cache()            # what an earlier leg's allocator cache still holds
     free, _ = torch.cuda.mem_get_info()
     n_stage = 8  # staging buffers rotate (8 x payload is well beyond the 256 MB Infinity Cache)
     L = max(1, min(max_layers, s.num_layers, int((free - (8 << 30) - n_stage * payload) // (2 * plane_bytes))))
     geom = dict(num_blocks=s.num_blocks, block_tokens=s.block_tokens, num_kv_heads=s.num_kv_heads,
                 head_dim=s.head_dim, elt_bytes=s.elt_bytes)
     cfg = B.make_cfg(w.align, w.chunk_bytes, s.num_layers)
-    planes, planes_same, placement_info, layer_stage = placed_planes(
-        torch, L, plane_bytes, dev, reserve_bytes=n_stage * payload + (10 << 30), place=place, stage_bytes=payload,
-        stage_rotation=3)
+    if plane_bytes < (1 << 30):
+        planes, planes_same, placement_info, layer_stage = carved_planes(
+            torch, L, plane_bytes, dev, reserve_bytes=n_stage * payload + (10 << 30), place=place, stage_bytes=payload)
+    else:
+        planes, planes_same, placement_info, layer_stage = placed_planes(
+            torch, L, plane_bytes, dev, reserve_bytes=n_stage * payload + (10 << 30), place=place,
+            stage_bytes=payload, stage_rotation=3)
     L = len(planes)
     pools = [B.make_pool(k, v, **geom) for k, v in planes]
     pools_same = [B.make_pool(k, v, **geom) for k, v in planes_same]

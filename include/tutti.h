@@ -122,7 +122,7 @@ typedef struct tutti_sqe {
 int tutti_obj_layout(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks, uint32_t n_req,
                      tutti_extent *d_extents, uint64_t *d_totals, void *stream);
 
-/* ---- a2: pack (save; store_layer of sec. 3.4 "Layer-wise Overlapping"; the objects of sec. 3.1).  For every
+/* ---- a2: pack (save; store_layer of sec. 3.4 "Integration with vLLM"; the objects of sec. 3.1).  For every
  * request r, kind in {K, V} and j < n_blocks_r, object bytes [j*block_bytes, (j+1)*block_bytes) <- pool block
  * d_block_table[table_off_r + j], in token-major order ((t*h + i)*d + k)*e whatever the pool layout; the tail
  * from n_blocks_r*block_bytes up to obj_bytes_r <- 0.  The K object of r starts at d_stage + stage_off_r, its V
@@ -331,7 +331,7 @@ int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots
                    uint32_t n_desc, uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len,
                    uint32_t cu_budget, uint32_t *d_status, void *stream);
 
-/* retrieve_layer(layer) / store_layer(layer) (sec. 3.4 "Layer-wise Overlapping") through the rings, in
+/* retrieve_layer(layer) / store_layer(layer) (sec. 3.4 "Integration with vLLM") through the rings, in
  * direct-to-block mode, as ONE data-moving launch plus the completion kernel: the result (extents, totals,
  * IOCBs, CQ, pool blocks or file store, status word) is that of tutti_obj_layout, tutti_iocb_fill_direct with
  * READ (retrieve) or WRITE (store) and tutti_issue_io run one after the other, with a mapping table that
@@ -376,7 +376,7 @@ int tutti_store_layer_issue(const tutti_ring *ring, uint32_t first_slot, uint32_
                             void *stream);
 int tutti_complete_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, void *stream);
 
-/* A train of layers on ONE stream without a completion kernel between them (sec. 3.4 "Layer-wise Overlapping": the
+/* A train of layers on ONE stream without a completion kernel between them (sec. 3.4 "Integration with vLLM": the
  * layers of a request are retrieved one after the other): as the _issue calls, and the same launch also completes
  * the IOCBs [done_first_slot, done_first_slot + done_n_slots) that an EARLIER call on the same stream executed
  * (typically the layer before), exactly as tutti_complete_io would: one more workgroup, in front of the grid, does it
@@ -506,7 +506,7 @@ int tutti_table_validate_static(uint32_t num_blocks, const uint32_t *d_block_tab
 
 /* ---- set-up: where a pool's planes sit in HBM.  The pool is allocated and registered once and stays fixed for
  * the engine's life (sec. 3.1 "Scalable GPU File Pool", "P2P Memory Mapping Table"), so its place in memory is
- * chosen once, before any layer is restored (sec. 3.4 "Layer-wise Overlapping").  Measured on the MI355X: its 288 GB
+ * chosen once, before any layer is restored (sec. 3.4 "Integration with vLLM").  Measured on the MI355X: its 288 GB
  * of HBM behave as three regions of 96 GB; a restore runs at the speed of a contiguous copy when a layer's K plane
  * and V plane lie in different regions and about 15 % slower when they share one.  Nothing in an address tells the
  * region, so the calls below tell it by timing: the library's own restore (tutti_layer_restore, 2048 blocks of
