@@ -1605,6 +1605,19 @@ def test_cfg4_llama70b_128k_layer(orc, H):
     H.check_everything(orc, c)
 
 
+def test_cfg4_layer_of_one_tensor_parallel_rank(orc, H):
+    """Config 4 as one rank of a tensor-parallel group of 8 holds it: one KV head of every block, so 4 KiB blocks
+    (a wavefront's slice is the whole block), the same 8192-entry fragmented table; also under a budget."""
+    import dataclasses
+    w = W.llama70b_128k()
+    w = dataclasses.replace(w, name="llama70b_128k_tp8_rank", shape=dataclasses.replace(w.shape, num_kv_heads=1))
+    say("cfg4 layer, one rank of TP 8", w.shape)
+    c = H.LayerCase.from_workload(w)
+    assert c.bb == 4096
+    H.check_everything(orc, c)
+    H.check_layer_restore(orc, c, layer=79, cu_budget=16)
+
+
 def _full_pool_sampled(orc, H, w, sample_layers, n_stage=4):
     """Every layer of the workload resident, each restored by its own launch as bench.py does it; the layers
     in `sample_layers` hold seeded values and are compared with the oracle plane by plane, and the save of
