@@ -230,3 +230,24 @@ def test_committed_slack_table_answers_lookups():
                 prev = got
                 us = [r[2] for r in rows if r[0] == got and r[1] == 2][0]
                 assert us <= slack * 1.001
+
+
+def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
+    """tests/host_selftest.cpp drives the host-only part of the library (IOCB allocator, slack lookups, pairing of
+    placed planes) with random call sequences on exact-size heap buffers, checked against simple models, under
+    AddressSanitizer and UndefinedBehaviorSanitizer."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "host_selftest"
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-Wall", "-Wextra", "-Werror", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", f"-I{os.path.join(root, 'include')}",
+           os.path.join(root, "tests", "host_selftest.cpp"),
+           os.path.join(root, "paper_2605_03375_amd", "csrc", "tutti_host.cpp"), "-o", str(exe)]
+    build = subprocess.run(cmd, capture_output=True, text=True)
+    if build.returncode != 0 and "asan" in build.stderr.lower() and "cannot find" in build.stderr.lower():
+        pytest.skip("no static sanitizer runtime on this machine")
+    assert build.returncode == 0, build.stderr[-2000:]
+    run = subprocess.run([str(exe), "2000"], capture_output=True, text=True, timeout=600)
+    assert run.returncode == 0, (run.stdout[-500:], run.stderr[-3000:])
+    assert run.stdout.strip() == "ok 2000"
