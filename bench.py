@@ -257,6 +257,15 @@ def main():
     out["config"]["placement"] = placement_info
     out["restore"]["host_us_per_call"] = host_us_per_call(torch, restore_layers, L)
     out["restore"]["blocks_per_call"] = n_tab
+    # the same without the Python binding in between: the loop runs in C (measurement library, same source)
+    c_ns = []
+    for _ in range(7):
+        torch.cuda.synchronize()
+        c_ns.append(B.tutti_host_cost_of_restore(pools[0], cfg, d_n, 1, d_tab, n_tab, d_fid, 0, stages[0], payload_layer,
+                                                 stages[0].data_ptr(), sgl_id, ext_r[0], tot_r[0], rsqe[0], n_sqe_layer,
+                                                 L, 0, status, stream))
+    torch.cuda.synchronize()
+    out["restore"]["host_us_per_call_from_c"] = round(median(c_ns) / 1e3, 2)
     if pools_same:
         # the same planes paired within one region (what an allocator that knows nothing of the regions mostly gives)
         def same_train():

@@ -55,6 +55,16 @@ int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_conti
                            const uint32_t *d_perm, uint32_t gran, uint32_t scatter_writes, uint32_t shape,
                            uint32_t cu_budget, void *stream);
 
+/* What the host pays for one tutti_layer_restore call, without a language binding in between: the call is made
+ * n_calls times in a row from C with these arguments (the launches are only enqueued; the caller synchronises
+ * afterwards) and *host_ns_per_call <- wall time of that loop / n_calls.  Arguments as tutti_layer_restore's. */
+int tutti_host_cost_of_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks,
+                               uint32_t n_req, const uint32_t *d_block_table, uint32_t table_len,
+                               const uint32_t *d_file_id, uint32_t layer, const void *d_stage, uint64_t stage_cap,
+                               uint64_t stage_addr, uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals,
+                               tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status,
+                               void *stream, uint32_t n_calls, double *host_ns_per_call);
+
 /* Launch tuning: wgs_per_cu persistent workgroups per compute unit for whole-GPU launches (0 = default),
  * unroll = 16-byte accesses in flight per lane (0 = default; 1, 2, 4 or 8). */
 int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll);

@@ -58,7 +58,8 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_place_classify", "tutti_place_pairs", "tutti_retrieve_layer_chained",
            "tutti_store_layer_chained"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
-                 "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping"]   # include/tutti_bench.h
+                 "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping",
+                 "tutti_host_cost_of_restore"]   # include/tutti_bench.h
 SCATTER_SHAPES = {"wave_slice": 0, "wave_slice_1024": 1, "wave_piece": 2, "wg_piece": 3, "wg_piece_plain": 4,
                   "wg_piece_nt_loads": 5, "wg_piece_nt_stores": 6}
 
@@ -205,6 +206,7 @@ def _declare(L, bench):
         L.tutti_set_nontemporal.argtypes = [u32]
         L.tutti_set_hnd_mode.argtypes = [u32]
         L.tutti_set_xcd_mapping.argtypes = [u32]
+        L.tutti_host_cost_of_restore.argtypes = L.tutti_layer_restore.argtypes + [u32, C.POINTER(C.c_double)]
         for name in BENCH_EXPORTS:
             getattr(L, name).restype = C.c_int
     return L
@@ -662,3 +664,17 @@ def tutti_place_pairs(classes, n_pairs, strict=True):
     n_mixed = C.c_uint32(0)
     _check("tutti_place_pairs", lib().tutti_place_pairs(cls, n, n_pairs, 1 if strict else 0, pairs, C.byref(n_mixed)))
     return [(pairs[2 * i], pairs[2 * i + 1]) for i in range(n_pairs)], n_mixed.value
+
+
+def tutti_host_cost_of_restore(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer, d_stage,
+                               stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap, n_calls,
+                               cu_budget=0, d_status=None, stream=None):
+    """Host nanoseconds per tutti_layer_restore call when the calls come from C (measurement library only)."""
+    ns = C.c_double(0.0)
+    _check("tutti_host_cost_of_restore",
+           bench_lib().tutti_host_cost_of_restore(C.byref(pool), C.byref(cfg), _p(d_n_blocks), n_req,
+                                                  _p(d_block_table), table_len, _p(d_file_id), layer, _p(d_stage),
+                                                  stage_cap, stage_addr, sgl_id, _p(d_extents), _p(d_totals),
+                                                  _p(d_sqe), sqe_cap, cu_budget, _p(d_status), _stream(stream),
+                                                  n_calls, C.byref(ns)))
+    return ns.value

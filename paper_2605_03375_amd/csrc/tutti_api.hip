@@ -14,6 +14,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <unordered_map>
 #include <vector>
 
@@ -1451,6 +1452,25 @@ int tutti_scatter_baseline(void *d_scattered, uint64_t span_bytes, void *d_conti
   }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+
+int tutti_host_cost_of_restore(const tutti_pool *pool, const tutti_objcfg *cfg, const uint32_t *d_n_blocks,
+                               uint32_t n_req, const uint32_t *d_block_table, uint32_t table_len,
+                               const uint32_t *d_file_id, uint32_t layer, const void *d_stage, uint64_t stage_cap,
+                               uint64_t stage_addr, uint32_t sgl_id, tutti_extent *d_extents, uint64_t *d_totals,
+                               tutti_sqe *d_sqe, uint32_t sqe_cap, uint32_t cu_budget, uint32_t *d_status,
+                               void *stream, uint32_t n_calls, double *host_ns_per_call) {
+  if (n_calls == 0 || !host_ns_per_call) return TUTTI_EINVAL;
+  const auto t0 = std::chrono::steady_clock::now();
+  for (uint32_t i = 0; i < n_calls; ++i) {
+    const int rc = tutti_layer_restore(pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id, layer,
+                                       d_stage, stage_cap, stage_addr, sgl_id, d_extents, d_totals, d_sqe, sqe_cap,
+                                       cu_budget, d_status, stream);
+    if (rc) return rc;
+  }
+  const auto t1 = std::chrono::steady_clock::now();
+  *host_ns_per_call = std::chrono::duration<double, std::nano>(t1 - t0).count() / n_calls;
+  return TUTTI_OK;
 }
 
 int tutti_set_tuning(uint32_t wgs_per_cu, uint32_t unroll) {
