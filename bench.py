@@ -923,11 +923,26 @@ def ring_leg(torch, B, w, pools, planes, cfg, d_n, d_tab, n_tab, d_fid, payload,
             chained.append(a.elapsed_time(b) * 1e3 / L)
         done_now = int(cq[:4].view(torch.int32)[0].item())
         assert done_now == L * n_slots, (done_now, L * n_slots)
+        # the entry-driven issue in the same way: IOCBs already FILLED, every issue completes the one before it
+        io_chained = []
+        for _ in range(reps):
+            train(op, issue=False)
+            torch.cuda.synchronize()
+            a, b = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+            a.record()
+            for l in range(L):
+                B.tutti_issue_io_chained(ring, l * n_slots, n_slots, (l - 1) * n_slots if l else 0, n_slots if l else 0,
+                                         sgls[l], nd, sgls[l].data_ptr(), fs, bb, 0, status)
+            B.tutti_complete_io(ring, (L - 1) * n_slots, n_slots)
+            b.record()
+            torch.cuda.synchronize()
+            io_chained.append(a.elapsed_time(b) * 1e3 / L)
         us, us_io, us_one, us_ch = median(both), median(only_io), median(fused), median(chained)
         res[label] = {"us_per_layer_chained_completions": round(us_ch, 2),
                       "pct_hbm_peak_chained": round(100 * 2 * payload / (us_ch * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
                       "us_per_layer_completions_on_second_stream": round(median(halves), 2),
 "us_per_layer_fill_plus_io": round(us, 2), "us_per_layer_issue_io": round(us_io, 2),
+                      "us_per_layer_issue_io_chained": round(median(io_chained), 2),
                       "us_per_layer_one_call": round(us_one, 2),
                       "us_per_layer_one_call_graph_replay": round(median(replay), 2),
                       "pct_hbm_peak_one_call": round(100 * 2 * payload / (us_one * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),

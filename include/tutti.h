@@ -400,6 +400,15 @@ int tutti_store_layer_chained(const tutti_ring *ring, uint32_t first_slot, uint3
                               uint32_t sgl_id, const tutti_filestore *store, tutti_extent *d_extents,
                               uint64_t *d_totals, uint32_t cu_budget, uint32_t *d_status, void *stream);
 
+/* tutti_issue_io for a train of issues on ONE stream in the same way: the entry-driven I/O kernel alone, and the same
+ * launch completes the IOCBs [done_first_slot, done_first_slot + done_n_slots) that an earlier call on the stream
+ * executed; the last issue of a train is completed with tutti_complete_io.  n_slots = 0 with done_n_slots > 0 only
+ * completes.  Other arguments, errors and status bits as tutti_issue_io; the slot ranges must not overlap. */
+int tutti_issue_io_chained(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t done_first_slot,
+                           uint32_t done_n_slots, const tutti_sgl *d_sgl_table, uint32_t n_desc,
+                           uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len, uint32_t cu_budget,
+                           uint32_t *d_status, void *stream);
+
 /* wait_cqe(): a check, not a blocking wait.  *d_flag <- 1 if IOCB slot `slot` is DONE, else 0; enqueue
  * it on any stream and read the flag after synchronising that stream. */
 int tutti_wait_cqe(const tutti_ring *ring, uint32_t slot, uint32_t *d_flag, void *stream);

@@ -56,7 +56,7 @@ EXPORTS = ["tutti_obj_layout", "tutti_obj_pack", "tutti_obj_unpack", "tutti_sqe_
            "tutti_table_order_work_bytes", "tutti_retrieve_layer_issue", "tutti_store_layer_issue",
            "tutti_complete_io", "tutti_wait_cqe_range", "tutti_place_work_bytes", "tutti_place_pair_times",
            "tutti_place_classify", "tutti_place_pairs", "tutti_retrieve_layer_chained",
-           "tutti_store_layer_chained"]
+           "tutti_store_layer_chained", "tutti_issue_io_chained"]
 BENCH_EXPORTS = ["tutti_copy_baseline", "tutti_stream_baseline", "tutti_scatter_baseline", "tutti_set_tuning",
                  "tutti_set_nontemporal", "tutti_set_hnd_mode", "tutti_set_xcd_mapping",
                  "tutti_host_cost_of_restore"]   # include/tutti_bench.h
@@ -159,6 +159,7 @@ def _declare(L, bench):
     L.tutti_ring_init.argtypes = [pr, vp]
     L.tutti_iocb_fill_direct.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u32, u64, u32, vp, vp]
     L.tutti_issue_io.argtypes = [pr, u32, u32, vp, u32, u64, pf, u32, u32, vp, vp]
+    L.tutti_issue_io_chained.argtypes = [pr, u32, u32, u32, u32, vp, u32, u64, pf, u32, u32, vp, vp]
     L.tutti_wait_cqe.argtypes = [pr, u32, vp, vp]
     L.tutti_wait_cqe_range.argtypes = [pr, u32, u32, vp, vp]
     L.tutti_retrieve_layer.argtypes = [pr, u32, u32, pp, pc, vp, u32, vp, u32, vp, u32, u64, u32, pf, vp, vp, u32,
@@ -378,6 +379,14 @@ def tutti_issue_io(ring, first_slot, n_slots, d_sgl_table, n_desc, sgl_table_add
     return _check("tutti_issue_io",
                   lib().tutti_issue_io(C.byref(ring), first_slot, n_slots, _p(d_sgl_table), n_desc, sgl_table_addr,
                                        C.byref(store), max_len, cu_budget, _p(d_status), _stream(stream)))
+
+
+def tutti_issue_io_chained(ring, first_slot, n_slots, done_first_slot, done_n_slots, d_sgl_table, n_desc,
+                           sgl_table_addr, store, max_len, cu_budget=0, d_status=None, stream=None):
+    return _check("tutti_issue_io_chained",
+                  lib().tutti_issue_io_chained(C.byref(ring), first_slot, n_slots, done_first_slot, done_n_slots,
+                                               _p(d_sgl_table), n_desc, sgl_table_addr, C.byref(store), max_len,
+                                               cu_budget, _p(d_status), _stream(stream)))
 
 
 def tutti_retrieve_layer(ring, first_slot, n_slots, pool, cfg, d_n_blocks, n_req, d_block_table, table_len, d_file_id,

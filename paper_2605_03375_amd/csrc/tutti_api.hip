@@ -698,6 +698,18 @@ int check_ring(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots) {
   if (first_slot >= ring->depth || n_slots > ring->depth) return TUTTI_EINVAL;
   return TUTTI_OK;
 }
+
+// The IOCBs a chained launch completes are an earlier call's: none of them may be one this call fills or executes.
+int check_done_range(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t done_first,
+                     uint32_t done_n) {
+  if (done_n == 0) return TUTTI_OK;
+  const int rc = check_ring(ring, done_first, done_n);
+  if (rc) return rc;
+  const uint32_t ahead = (done_first + ring->depth - first_slot) % ring->depth;   // done_first seen from first_slot
+  const uint32_t behind = (first_slot + ring->depth - done_first) % ring->depth;  // and the other way round
+  if (n_slots > 0 && (ahead < n_slots || behind < done_n)) return TUTTI_EINVAL;
+  return TUTTI_OK;
+}
 }  // namespace
 
 int tutti_ring_init(const tutti_ring *ring, void *stream) {
@@ -746,15 +758,29 @@ int tutti_iocb_fill_direct(const tutti_ring *ring, uint32_t first_slot, uint32_t
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
 }
 
-int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_sgl *d_sgl_table,
+extern "C++" {
+namespace {
+// issue_io: the entry-driven I/O kernel, then the completion kernel (complete), or neither (a chained train: this
+// launch completes the IOCBs [done_first, done_first + done_n) of an earlier one instead).
+int issue_io_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_sgl *d_sgl_table,
                    uint32_t n_desc, uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len,
-                   uint32_t cu_budget, uint32_t *d_status, void *stream) {
+                   uint32_t cu_budget, uint32_t *d_status, void *stream, bool complete, uint32_t done_first,
+                   uint32_t done_n) {
   int rc = check_ring(ring, first_slot, n_slots);
+  if (rc) return rc;
+  rc = check_done_range(ring, first_slot, n_slots, done_first, done_n);
   if (rc) return rc;
   if (!store || !store->base || !aligned16(store->base) || store->file_stride % 16 != 0) return TUTTI_EINVAL;
   if (n_desc > 0 && (!d_sgl_table || !aligned16(d_sgl_table))) return TUTTI_EINVAL;
   if (max_len == 0 || max_len % 16 != 0 || sgl_table_addr % 16 != 0) return TUTTI_EINVAL;
-  if (n_slots == 0) return TUTTI_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  RingArgs gd{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, done_first, done_n};
+  if (n_slots == 0) {
+    if (done_n == 0) return TUTTI_OK;
+    hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, s, gd);  // nothing to execute: only the completion
+    const hipError_t e0 = hipGetLastError();
+    return e0 == hipSuccess ? TUTTI_OK : hip_fail(e0);
+  }
   Launch L;
   rc = plan_launch(cu_budget, 0, &L);
   if (rc) return rc;
@@ -775,24 +801,45 @@ int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots
   if (items > 0xffffffffull) return TUTTI_ERANGE;
   rc = plan_launch(cu_budget, items, &L);
   if (rc) return rc;
+  // a chained launch: one more workgroup in front; a whole-GPU grid gives it one of its places
+  const uint32_t lead = done_n > 0 ? 1u : 0u;
+  if (lead && cu_budget == 0 && L.grid > 1 && L.grid == whole_gpu_wgs()) L.grid -= 1;
   RingArgs g{ring->d_sq, static_cast<tutti_cq_hdr *>(ring->d_cq), ring->depth, first_slot, n_slots};
-  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid(L.grid + lead);
   if (L.wg_threads == kWgThreads) {
     if (unroll == 8)
-      hipLaunchKernelGGL((k_issue_io<8, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, g, a);
+      hipLaunchKernelGGL((k_issue_io<8, kWgThreads>), grid, dim3(kWgThreads), 0, s, g, gd, a);
     else
-      hipLaunchKernelGGL((k_issue_io<4, kWgThreads>), dim3(L.grid), dim3(kWgThreads), 0, s, g, a);
+      hipLaunchKernelGGL((k_issue_io<4, kWgThreads>), grid, dim3(kWgThreads), 0, s, g, gd, a);
   } else {
     if (unroll == 8)
-      hipLaunchKernelGGL((k_issue_io<8, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, g, a);
+      hipLaunchKernelGGL((k_issue_io<8, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), 0, s, g, gd, a);
     else
-      hipLaunchKernelGGL((k_issue_io<4, kBudgetWgThreads>), dim3(L.grid), dim3(kBudgetWgThreads), 0, s, g, a);
+      hipLaunchKernelGGL((k_issue_io<4, kBudgetWgThreads>), grid, dim3(kBudgetWgThreads), 0, s, g, gd, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e);
+  if (!complete) return TUTTI_OK;
   hipLaunchKernelGGL(k_complete, dim3(1), dim3(kWave), 0, s, g);
   e = hipGetLastError();
   return e == hipSuccess ? TUTTI_OK : hip_fail(e);
+}
+}  // namespace
+}  // extern "C++"
+
+int tutti_issue_io(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, const tutti_sgl *d_sgl_table,
+                   uint32_t n_desc, uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len,
+                   uint32_t cu_budget, uint32_t *d_status, void *stream) {
+  return issue_io_entry(ring, first_slot, n_slots, d_sgl_table, n_desc, sgl_table_addr, store, max_len, cu_budget,
+                        d_status, stream, true, 0, 0);
+}
+
+int tutti_issue_io_chained(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slots, uint32_t done_first_slot,
+                           uint32_t done_n_slots, const tutti_sgl *d_sgl_table, uint32_t n_desc,
+                           uint64_t sgl_table_addr, const tutti_filestore *store, uint32_t max_len, uint32_t cu_budget,
+                           uint32_t *d_status, void *stream) {
+  return issue_io_entry(ring, first_slot, n_slots, d_sgl_table, n_desc, sgl_table_addr, store, max_len, cu_budget,
+                        d_status, stream, false, done_first_slot, done_n_slots);
 }
 
 extern "C++" {
@@ -808,14 +855,8 @@ int ring_layer_entry(const tutti_ring *ring, uint32_t first_slot, uint32_t n_slo
                      uint32_t done_first = 0, uint32_t done_n = 0) {
   int rc = check_ring(ring, first_slot, n_slots);
   if (rc) return rc;
-  if (done_n > 0) {
-    rc = check_ring(ring, done_first, done_n);
-    if (rc) return rc;
-    // the IOCBs to complete are an earlier call's: none of them may be one this call fills
-    const uint32_t ahead = (done_first + ring->depth - first_slot) % ring->depth;   // done_first seen from first_slot
-    const uint32_t behind = (first_slot + ring->depth - done_first) % ring->depth;  // and the other way round
-    if (n_slots > 0 && (ahead < n_slots || behind < done_n)) return TUTTI_EINVAL;
-  }
+  rc = check_done_range(ring, first_slot, n_slots, done_first, done_n);
+  if (rc) return rc;
   uint32_t bb = 0;
   rc = check_geometry(pool, cfg, &bb);
   if (rc) return rc;

@@ -780,16 +780,26 @@ __device__ __forceinline__ IoItem io_decode(const RingArgs &g, const IoArgs &a, 
 // k_complete, enqueued right behind it on the same stream: counting finished items with atomics on the IOCB
 // header serialises on one address (measured: 1.5 ms per 4096-context layer instead of 55 us), and a kernel
 // boundary already is the "all contexts done" event.
+__device__ __forceinline__ void complete_iocbs(const RingArgs g, uint32_t lane);  // defined below
+
+// `done`: IOCBs that an earlier launch on the same stream has executed; when done.n_slots is not 0 the grid has one
+// workgroup more, in front, whose first wavefront completes them and leaves (see k_layer_ring).
 template <int U, int WG>
-__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_issue_io(const RingArgs g, const IoArgs a) {
+__global__ __launch_bounds__(WG, min_waves_per_simd(WG, U)) void k_issue_io(const RingArgs g, const RingArgs done,
+                                                                             const IoArgs a) {
   constexpr uint32_t kSlice = kWave * 16u * U;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave_in_wg = rfl(threadIdx.x / kWave);
-  const uint32_t n_waves = gridDim.x * (blockDim.x / kWave);
+  const uint32_t lead = done.n_slots != 0 ? 1u : 0u;
+  if (lead && blockIdx.x == 0) {
+    if (threadIdx.x < kWave) complete_iocbs(done, threadIdx.x);
+    return;
+  }
+  const uint32_t n_waves = (gridDim.x - lead) * (blockDim.x / kWave);
   const uint32_t per_iocb = TUTTI_IOCB_SLOTS * a.slices;
   const uint32_t n_items = g.n_slots * per_iocb;  // the host checked this fits 32 bits
 
-  uint32_t it = blockIdx.x * (blockDim.x / kWave) + wave_in_wg;
+  uint32_t it = (blockIdx.x - lead) * (blockDim.x / kWave) + wave_in_wg;
   if (it >= n_items) return;
   IoItem cur = io_decode<U>(g, a, it, per_iocb, lane);
   for (;;) {

@@ -526,3 +526,62 @@ def check_ring_layer_train(orc, c, layers, write, depth, n_slots, first_slot=0, 
     assert sq.cpu().numpy().tobytes() == o_sq.tobytes(), f"{c.name}: IOCBs differ"
     assert cq.cpu().numpy().tobytes() == o_cq.tobytes(), f"{c.name}: completion queue differs"
     return o_st_all, tail_before
+
+def check_rings_train(orc, c, steps, depth, n_slots, first_slot=0, cu_budget=0, first_file_id=1000, seed=3):
+    """A train of fill + tutti_issue_io_chained calls (steps: (layer, opcode) pairs; each issue completes the IOCBs of
+    the one before it, tutti_complete_io ends the train) against the oracle's fill + issue_io sequence: IOCBs, CQ,
+    planes, file store and status compared once the train is through."""
+    assert c.bb % c.align == 0 and depth >= 2 * n_slots and n_slots > 0
+    o_ext, o_tot = orc.obj_layout(c.orc_pool(orc), c.orc_cfg(orc), c.n_blocks)
+    ext, tot = gpu_layout(c)
+    file_stride = max(16, int(2 * c.L * (int(o_ext["obj_bytes"].max()) if c.n_req else 0)))
+    n_files = max(1, c.n_req)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    store = torch.randint(0, 256, (n_files * file_stride,), dtype=torch.uint8, device=DEV, generator=g)
+    o_store = store.cpu().numpy().copy()
+    k2, v2 = c.k_dev.clone(), c.v_dev.clone()
+    ok, ov = c.k_host.copy(), c.v_host.copy()
+    nd = 2 * c.N
+    sgl = torch.zeros(nd * 16, dtype=torch.uint8, device=DEV)
+    B.tutti_sgl_table_build(c.gpu_pool(k2, v2), k2.data_ptr(), v2.data_ptr(), 5, sgl, nd)
+    o_sgl, _ = orc.sgl_table_build(c.orc_pool(orc, ok, ov), ok.ctypes.data, ov.ctypes.data, 5)
+    table_addr = sgl.data_ptr()
+    sq_bytes, cq_bytes = B.ring_bytes(depth)
+    sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=DEV)
+    cq = torch.zeros(cq_bytes, dtype=torch.uint8, device=DEV)
+    ring = B.make_ring(sq, cq, depth)
+    o_sq, o_cq = orc.ring_alloc(depth)
+    B.tutti_ring_init(ring)
+    orc.ring_init(o_sq, o_cq)
+    fs = B.make_filestore(store, file_stride, first_file_id, n_files)
+    st = new_status()
+    o_st_all = 0
+    prev = (0, 0)
+    for i, (layer, opcode) in enumerate(steps):
+        fslot = (first_slot + i * n_slots) % depth
+        B.tutti_iocb_fill_direct(ring, fslot, n_slots, c.gpu_pool(k2, v2), c.gpu_cfg(), ext, c.n_req, c.d_table,
+                                 c.table.size, c.d_file_id, layer, opcode, table_addr, 5, st)
+        B.tutti_issue_io_chained(ring, fslot, n_slots, prev[0], prev[1], sgl, nd, table_addr, fs, c.bb, cu_budget, st)
+        o_st_all |= orc.iocb_fill_direct(o_sq, fslot, n_slots, c.orc_pool(orc, ok, ov), c.orc_cfg(orc), o_ext, c.table,
+                                         c.file_id, layer, opcode, table_addr, 5)
+        o_st_all |= orc.issue_io(o_sq, o_cq, fslot, n_slots, o_sgl, table_addr, o_store, file_stride, first_file_id,
+                                 n_files)
+        prev = (fslot, n_slots)
+    flags = torch.full((depth,), 9, dtype=torch.int32, device=DEV)
+    B.tutti_wait_cqe_range(ring, 0, depth, flags)
+    torch.cuda.synchronize()
+    last = {(prev[0] + k) % depth for k in range(n_slots)}
+    done = o_sq["hdr"]["state"] == orc.IOCB_DONE
+    assert flags.cpu().tolist() == [0 if s in last else (1 if done[s] else 0) for s in range(depth)]
+    B.tutti_issue_io_chained(ring, 0, 0, prev[0], prev[1], sgl, nd, table_addr, fs, c.bb, cu_budget, st)   # only completes
+    torch.cuda.synchronize()
+    assert int(st.item()) == o_st_all, f"{c.name}: status {int(st.item())} vs oracle {o_st_all}"
+    gk, gv = k2.cpu().numpy(), v2.cpu().numpy()
+    assert np.array_equal(gk, ok), f"{c.name}: K plane differs at byte {first_diff(gk, ok)}"
+    assert np.array_equal(gv, ov), f"{c.name}: V plane differs at byte {first_diff(gv, ov)}"
+    gs = store.cpu().numpy()
+    assert np.array_equal(gs, o_store), f"{c.name}: file store differs at byte {first_diff(gs, o_store)}"
+    assert sq.cpu().numpy().tobytes() == o_sq.tobytes(), f"{c.name}: IOCBs differ"
+    assert cq.cpu().numpy().tobytes() == o_cq.tobytes(), f"{c.name}: completion queue differs"
+    return o_st_all

@@ -198,6 +198,9 @@ def test_null_and_misaligned_pointers_are_einval():
         _expect(B.EINVAL, chained, ring, 1, 1, 0, 2, *ok)              # this call's slot is among the earlier call's
         _expect(B.EINVAL, chained, ring, 4, 1, 0, 1, *ok)              # the ordinary checks still come first
         _expect(B.EINVAL, chained, ring, 0, 1, 2, 1, odd, *ok[1:])     # ... and after
+    _expect(B.EINVAL, B.tutti_issue_io_chained, ring, 0, 2, 1, 1, FAKE, 4, 0, fs, 4096)   # overlapping slot ranges
+    _expect(B.EINVAL, B.tutti_issue_io_chained, ring, 0, 1, 4, 1, FAKE, 4, 0, fs, 4096)   # earlier slots not in the ring
+    _expect(B.EINVAL, B.tutti_issue_io_chained, ring, 0, 1, 2, 1, FAKE, 4, 0, fs, 0)      # the ordinary checks
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 4, FAKE)
     _expect(B.EINVAL, B.tutti_wait_cqe, ring, 0, 0)
     _expect(B.EINVAL, B.tutti_table_validate, 0, FAKE, 4, FAKE)

@@ -879,6 +879,17 @@ def test_ring_layer_trains_with_chained_completions(orc, H):
     for write in (False, True):
         st, tail = H.check_ring_layer_train(orc, c, [30, 31, 0], write, depth=6, n_slots=2, first_slot=3)
         assert st == 0 and tail == 4
+    # the entry-driven issue in the same way: fill + tutti_issue_io_chained per step, reads and writes mixed
+    rng = np.random.default_rng(79)
+    nb = [700, 0, 1500, 3]
+    c = H.LayerCase(T=16, h=2, d=64, e=2, N=2500, n_blocks=nb, table=rng.permutation(2500)[: sum(nb)], chunk=4096, L=5,
+                    name="rings_chained")
+    R, Wr = B.OP_READ, B.OP_WRITE
+    assert H.check_rings_train(orc, c, [(0, Wr), (1, R), (2, R), (3, Wr), (4, R)], depth=15, n_slots=3) == 0
+    assert H.check_rings_train(orc, c, [(4, R), (0, Wr), (3, R), (1, Wr), (2, R), (2, Wr)], depth=7, n_slots=3,
+                               first_slot=4) == 0
+    assert H.check_rings_train(orc, c, [(1, R), (2, Wr), (3, R)], depth=6, n_slots=3, cu_budget=3) == 0
+    assert H.check_rings_train(orc, c, [(0, R), (1, Wr)], depth=4, n_slots=2) == B.ST_SQE_CAP
     # slot ranges that overlap are refused before anything is enqueued
     sq_bytes, cq_bytes = B.ring_bytes(8)
     sq = torch.zeros(sq_bytes, dtype=torch.uint8, device=H.DEV)
@@ -894,6 +905,9 @@ def test_ring_layer_trains_with_chained_completions(orc, H):
                 fn(ring, first, n, dfirst, dn, c.gpu_pool(c.k_dev, c.v_dev), c.gpu_cfg(), c.d_n_blocks, 1, c.d_table,
                    c.table.size, c.d_file_id, 0, 0x1000, 5, fs, ext, tot)
             assert err.value.code == B.EINVAL
+        with pytest.raises(B.TuttiError) as err:
+            B.tutti_issue_io_chained(ring, first, n, dfirst, dn, store, 4, 0, fs, 4096)
+        assert err.value.code == B.EINVAL
     with pytest.raises(B.TuttiError):                                   # done range outside the ring
         B.tutti_retrieve_layer_chained(ring, 0, 1, 8, 1, c.gpu_pool(c.k_dev, c.v_dev), c.gpu_cfg(), c.d_n_blocks, 1,
                                        c.d_table, c.table.size, c.d_file_id, 0, 0x1000, 5, fs, ext, tot)
