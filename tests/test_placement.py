@@ -103,6 +103,9 @@ def test_classification_by_timing_agrees_with_direct_pair_timings():
     one class is slower than a pair from two classes.  Skipped (not failed) if only one region is found."""
     import torch
     dev = "cuda:0"
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()          # earlier tests' blocks are cached by the allocator, not free
     free, _ = torch.cuda.mem_get_info()
     n = int(min(50, (free - (8 << 30)) // (2 << 30)))
     if n < 8:
