@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--region-matrix", action="store_true",
                     help="instead of the benchmark: restore and save of config 2's layer for every combination of HBM "
                          "region of the K plane, the V plane and the staging buffer; prints its own JSON line")
+    ap.add_argument("--region-map", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark: classify candidates of MIB mebibytes (at least 128) covering the free "
+                         "HBM by region, in allocation order; prints its own JSON line")
     ap.add_argument("--wgs-per-cu", type=int, default=0)
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--plain-loads", action="store_true", help="disable non-temporal loads/stores")
@@ -107,6 +110,9 @@ def main():
         B.tutti_set_tuning(args.wgs_per_cu, args.unroll)
         B.tutti_set_nontemporal(0 if args.plain_loads else 3)
 
+    if args.region_map:
+        print(json.dumps(region_map(torch, dev, args.region_map)), flush=True)
+        return
     if args.region_matrix:
         print(json.dumps(region_matrix(torch, B, W.llama8b_32k(), dev)), flush=True)
         return
@@ -517,6 +523,28 @@ def placed_planes(torch, n_layers, plane_bytes, dev, reserve_bytes, place=True, 
     del cands
     torch.cuda.empty_cache()
     return planes, planes_same, info, stages
+
+
+def region_map(torch, dev, mib):
+    """The HBM regions in the order the allocator hands memory out: candidates of `mib` MiB covering the free memory
+    (at most 1,000 of them), classified by tutti_place_classify; the classes as runs in allocation order."""
+    from paper_2605_03375_amd import placement
+    size = max(128, mib) << 20
+    free, _ = torch.cuda.mem_get_info()
+    n = int(min(1000, (free - (10 << 30)) // size))
+    cands = [torch.empty(size, dtype=torch.uint8, device=dev) for _ in range(n)]
+    classes, report = placement.classify_planes(cands, dev, max_regions=4)
+    runs = []
+    for c in classes:
+        ch = "ABCD?"[c]
+        if runs and runs[-1][0] == ch:
+            runs[-1][1] += 1
+        else:
+            runs.append([ch, 1])
+    return {"candidate_MiB": size >> 20, "candidates": n, "GiB": round(n * size / 2 ** 30, 2), "rounds": report["rounds"],
+            "runs_in_allocation_order": [[ch, k, round(k * size / 2 ** 30, 2)] for ch, k in runs],
+            "GiB_per_class": {ch: round(sum(k for c2, k in runs if c2 == ch) * size / 2 ** 30, 2)
+                              for ch in sorted({r[0] for r in runs})}}
 
 
 def region_matrix(torch, B, w, dev, layers=16, reps=6):
